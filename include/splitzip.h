@@ -1,0 +1,159 @@
+/*
+ * splitzip.h -- C ABI of the SplitZip codec for AMD Instinct MI355X (gfx950).
+ *
+ * SplitZip is a lossless codec for BF16 (and FP8 E5M2) KV-cache tensors
+ * (paper section 3, "SplitZip").  Every word is split into a sign+mantissa
+ * part that is stored verbatim and an exponent that is mapped through an
+ * offline-calibrated table of the 16 most frequent exponents to a 4-bit code,
+ * two codes per byte.  Exponents outside the table get a dummy code and are
+ * recorded in a sparse escape stream of (chunk-relative 16-bit position, raw
+ * exponent) records; the decoder applies them as a scatter correction after
+ * the dense unpack / table lookup / recombination.
+ *
+ * All entry points are plain C: pointers and sizes only.  "d_" pointers are
+ * device (HBM) addresses, "h_"/unprefixed pointers are host addresses.  Nothing
+ * in this library allocates device memory, synchronises a stream or the
+ * device, or reads device memory from the host: device work is enqueued on
+ * the caller's stream and results (including sizes) are written by kernels.
+ * Calls return 0 (SPLITZIP_OK) or a negative splitzip_error.
+ *
+ * Compressed stream (little endian; each section starts 16-byte aligned, pad
+ * bytes are zero; A16(x) = x rounded up to 16; C = ceil(N/1024)):
+ *
+ *   header     64 B        u32 magic "SZP1", u16 version 1, u8 dtype, u8 code
+ *                          bits (4), u32 chunk elements (1024), u32 0,
+ *                          u64 N, u64 M (escapes), u64 total bytes,
+ *                          u8 dec[16], u8 zero[8]
+ *   chunk_off  4(C+1) B    u32 exclusive prefix sums of the per-chunk escape
+ *                          counts; chunk_off[C] = M
+ *   sm plane   BF16: N B, byte i = a_i (eq. (1)).  E5M2: ceil(3N/8) B,
+ *              LSB-first bit stream, bit 3i+k = bit k of a_i
+ *   code plane ceil(N/2) B, byte j = code[2j] | code[2j+1] << 4
+ *   esc_pos    2M B        u16 chunk-relative positions, ascending elements
+ *   esc_val    M B         u8 raw exponents, same order
+ *
+ *   total = 64 + A16(4(C+1)) + A16(sm) + A16(ceil(N/2)) + A16(2M) + M
+ *
+ * The payload (planes + 3M) is the paper's B_SZ = N + N/2 + 3M (section 3.2).
+ */
+#ifndef SPLITZIP_H
+#define SPLITZIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SPLITZIP_BF16 = 0,     /* 16-bit words: 1 sign, 8 exponent, 7 mantissa bits */
+  SPLITZIP_FP8_E5M2 = 1  /* 8-bit words: 1 sign, 5 exponent, 2 mantissa bits (paper appendix "SplitZip on FP8") */
+} splitzip_dtype;
+
+typedef enum {
+  SPLITZIP_OK = 0,
+  SPLITZIP_ERR_INVALID_ARG = -1, /* null / misaligned pointer, inconsistent codebook, bad dtype */
+  SPLITZIP_ERR_UNSUPPORTED = -2, /* n_elems >= 2^32 (offsets are 32-bit) */
+  SPLITZIP_ERR_CAPACITY = -3,    /* output / workspace / stream smaller than the fixed part needs */
+  SPLITZIP_ERR_HIP = -4          /* a HIP runtime call (kernel launch) failed */
+} splitzip_error;
+
+/* bits of splitzip_sizes.status, written by kernels */
+enum {
+  SPLITZIP_STATUS_OVERFLOW = 1u,   /* compress: escapes did not fit out_capacity; total_bytes is the size needed */
+  SPLITZIP_STATUS_BAD_STREAM = 2u, /* decompress: header / offsets / positions inconsistent; offending records skipped */
+  SPLITZIP_STATUS_INTERNAL = 4u    /* compress: workspace was not initialised or is shared by overlapping calls */
+};
+
+/* The three calibration tables of section 3.3.  Plain data, host memory,
+ * caller-owned, copyable.  For E5M2 only indices 0..31 of enc/member are used. */
+typedef struct {
+  uint8_t dec[16];     /* 4-bit code -> exponent; code k is the k-th most frequent exponent */
+  uint8_t enc[256];    /* exponent -> 4-bit code; 0 (the dummy code, section 3.4) for non-members */
+  uint8_t member[256]; /* 1 if the exponent is in the codebook (escape detection) */
+  uint32_t dtype;      /* splitzip_dtype the tables were built for */
+} splitzip_codebook;
+
+typedef struct {
+  uint64_t total_bytes; /* size of the whole compressed stream */
+  uint64_t n_escapes;   /* M */
+  uint32_t status;      /* SPLITZIP_STATUS_* bits, 0 = fine */
+  uint32_t reserved;
+} splitzip_sizes;
+
+/* Section 3.3 "Calibration": histogram the exponents of a HOST sample of
+ * n_elems words, take the 16 most frequent (ties to the smaller exponent;
+ * never-seen exponents fill up in ascending order) and build the three
+ * tables.  hist_out (nullable) receives the 256 exponent counts.  Host only;
+ * touches no GPU. */
+int splitzip_calibrate(const void* h_sample, uint64_t n_elems, int dtype, splitzip_codebook* out,
+                       uint64_t* hist_out);
+
+/* Tables for a given list of 16 distinct exponents (code k = dec[k]); used to
+ * restore a saved codebook.  INVALID_ARG on duplicates / out-of-range values. */
+int splitzip_codebook_from_dec(const uint8_t dec[16], int dtype, splitzip_codebook* out);
+
+/* Stream sizes.  fixed = header + chunk_off + both planes (independent of the
+ * data); total adds the escape sections for M escapes; bound = total at M = N.
+ * Return 0 for an invalid dtype or n_elems >= 2^32. */
+size_t splitzip_fixed_bytes(uint64_t n_elems, int dtype);
+size_t splitzip_total_bytes(uint64_t n_elems, uint64_t n_escapes, int dtype);
+size_t splitzip_compress_bound(uint64_t n_elems, int dtype);
+
+/* Device scratch a compress call of up to n_elems needs (scan state of the
+ * escape compaction plus staging for the escape values, about n_elems bytes).
+ * A workspace must be prepared once with splitzip_workspace_init and can then
+ * serve any number of compress calls of up to that size; each call leaves it
+ * ready for the next.  Calls that share a workspace must not overlap in time
+ * (same stream, or otherwise ordered). */
+size_t splitzip_workspace_bytes(uint64_t n_elems, int dtype);
+int splitzip_workspace_init(void* d_workspace, size_t workspace_bytes, void* stream);
+
+/* Section 3.2, encoding path (dense split / table / pack fused with escape
+ * detection, counting and position-ordered compaction, appendix A) on device
+ * buffers, enqueued on `stream` (a hipStream_t; NULL = default stream).
+ *   d_in        N words (16-bit for BF16, 8-bit for E5M2), 16-byte aligned, read only
+ *   d_out       >= out_capacity bytes, 16-byte aligned; receives the stream
+ *   d_sizes     device (or pinned host) splitzip_sizes, written by the kernel
+ * out_capacity below splitzip_fixed_bytes() -> SPLITZIP_ERR_CAPACITY, nothing
+ * enqueued.  If the fixed part fits but the escapes do not, everything that
+ * fits is written, status gets SPLITZIP_STATUS_OVERFLOW and total_bytes is
+ * the size a retry needs.  n_elems == 0 is valid (header and one offset).
+ * The output is a pure function of (input, codebook): independent of
+ * scheduling, capacity slack and earlier calls. */
+int splitzip_compress(const void* d_in, uint64_t n_elems, int dtype, const splitzip_codebook* cb,
+                      void* d_out, size_t out_capacity, void* d_workspace, size_t workspace_bytes,
+                      splitzip_sizes* d_sizes, void* stream);
+
+/* Section 3.2, decoding path: nibble unpack, 16-entry table, recombination by
+ * eq. (2), then the sparse overwrite of the exponent field at every recorded
+ * escape position.
+ *   d_comp      the stream, comp_bytes readable bytes, 16-byte aligned
+ *   d_out       n_elems words, 16-byte aligned
+ *   d_sizes     nullable.  total_bytes / n_escapes are copied from the header;
+ *               status bits are OR-ed into the existing value (sticky), so the
+ *               caller zeroes it once and can watch many calls with one word.
+ * n_elems and the codebook come from the caller, never from a hidden read of
+ * the stream; a stream whose header disagrees, or whose offsets / positions
+ * point outside their sections, sets SPLITZIP_STATUS_BAD_STREAM and the
+ * offending records are skipped (no out-of-bounds access).  comp_bytes below
+ * splitzip_fixed_bytes() -> SPLITZIP_ERR_CAPACITY. */
+int splitzip_decompress(const void* d_comp, size_t comp_bytes, uint64_t n_elems, int dtype,
+                        const splitzip_codebook* cb, void* d_out, splitzip_sizes* d_sizes,
+                        void* stream);
+
+/* Measurement aid: a plain streaming kernel that reads read_bytes from d_src
+ * and writes write_bytes (<= read_bytes) to d_dst with 128-bit accesses, i.e.
+ * the memory traffic of the codec without its arithmetic.  Both sizes are
+ * rounded down to a multiple of 16. */
+int splitzip_traffic_probe(const void* d_src, size_t read_bytes, void* d_dst, size_t write_bytes,
+                           void* stream);
+
+const char* splitzip_strerror(int err);
+int splitzip_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPLITZIP_H */

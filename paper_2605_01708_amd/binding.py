@@ -1,0 +1,199 @@
+"""ctypes binding of include/splitzip.h.  Same names as the C entry points
+(without the ``splitzip_`` prefix); torch tensors supply device pointers and
+the current HIP stream, nothing else."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+BF16 = 0
+FP8_E5M2 = 1
+
+STATUS_OVERFLOW = 1
+STATUS_BAD_STREAM = 2
+STATUS_INTERNAL = 4
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libsplitzip.so")
+
+
+class SplitZipError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(f"{what}: {lib().splitzip_strerror(code).decode()} ({code})")
+
+
+class _CCodebook(C.Structure):
+    _fields_ = [("dec", C.c_uint8 * 16), ("enc", C.c_uint8 * 256), ("member", C.c_uint8 * 256),
+                ("dtype", C.c_uint32)]
+
+
+class _CSizes(C.Structure):
+    _fields_ = [("total_bytes", C.c_uint64), ("n_escapes", C.c_uint64), ("status", C.c_uint32),
+                ("reserved", C.c_uint32)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C library; raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise ImportError(
+                f"{path} is missing: build it with `python -m paper_2605_01708_amd.build` "
+                "(or __graft_entry__.build()); there is no CPU fallback")
+        L = C.CDLL(path)
+        vp, u64, sz, i = C.c_void_p, C.c_uint64, C.c_size_t, C.c_int
+        cbp = C.POINTER(_CCodebook)
+        L.splitzip_version.restype = i
+        L.splitzip_strerror.restype = C.c_char_p
+        L.splitzip_strerror.argtypes = [i]
+        L.splitzip_calibrate.restype = i
+        L.splitzip_calibrate.argtypes = [vp, u64, i, cbp, C.POINTER(C.c_uint64)]
+        L.splitzip_codebook_from_dec.restype = i
+        L.splitzip_codebook_from_dec.argtypes = [C.POINTER(C.c_uint8), i, cbp]
+        for f in (L.splitzip_fixed_bytes, L.splitzip_compress_bound, L.splitzip_workspace_bytes):
+            f.restype = sz
+            f.argtypes = [u64, i]
+        L.splitzip_total_bytes.restype = sz
+        L.splitzip_total_bytes.argtypes = [u64, u64, i]
+        L.splitzip_workspace_init.restype = i
+        L.splitzip_workspace_init.argtypes = [vp, sz, vp]
+        L.splitzip_compress.restype = i
+        L.splitzip_compress.argtypes = [vp, u64, i, cbp, vp, sz, vp, sz, vp, vp]
+        L.splitzip_decompress.restype = i
+        L.splitzip_decompress.argtypes = [vp, sz, u64, i, cbp, vp, vp, vp]
+        L.splitzip_traffic_probe.restype = i
+        L.splitzip_traffic_probe.argtypes = [vp, sz, vp, sz, vp]
+        _lib = L
+    return _lib
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise SplitZipError(rc, what)
+
+
+class Codebook:
+    """Host-side calibration tables (a splitzip_codebook)."""
+
+    def __init__(self, c: _CCodebook):
+        self.c = c
+
+    @property
+    def dtype(self) -> int:
+        return int(self.c.dtype)
+
+    @property
+    def dec(self):
+        return list(self.c.dec)
+
+    @property
+    def enc(self):
+        return list(self.c.enc)
+
+    @property
+    def member(self):
+        return list(self.c.member)
+
+
+def _elem_size(dtype: int) -> int:
+    return 2 if dtype == BF16 else 1
+
+
+def calibrate(sample: torch.Tensor, dtype: int, return_hist: bool = False):
+    """splitzip_calibrate on a HOST tensor of raw words (any 2-byte dtype for BF16, 1-byte for E5M2)."""
+    if sample.device.type != "cpu":
+        raise ValueError("calibration runs on the host: pass a CPU tensor")
+    s = sample.contiguous()
+    if s.element_size() != _elem_size(dtype):
+        raise ValueError("sample element size does not match dtype")
+    cb = _CCodebook()
+    hist = (C.c_uint64 * 256)()
+    _check(lib().splitzip_calibrate(s.data_ptr(), s.numel(), dtype, C.byref(cb), hist), "splitzip_calibrate")
+    return (Codebook(cb), list(hist)) if return_hist else Codebook(cb)
+
+
+def codebook_from_dec(dec, dtype: int) -> Codebook:
+    arr = (C.c_uint8 * 16)(*[int(v) for v in dec])
+    cb = _CCodebook()
+    _check(lib().splitzip_codebook_from_dec(arr, dtype, C.byref(cb)), "splitzip_codebook_from_dec")
+    return Codebook(cb)
+
+
+def fixed_bytes(n: int, dtype: int) -> int:
+    return int(lib().splitzip_fixed_bytes(n, dtype))
+
+
+def total_bytes(n: int, m: int, dtype: int) -> int:
+    return int(lib().splitzip_total_bytes(n, m, dtype))
+
+
+def compress_bound(n: int, dtype: int) -> int:
+    return int(lib().splitzip_compress_bound(n, dtype))
+
+
+def workspace_bytes(n: int, dtype: int) -> int:
+    return int(lib().splitzip_workspace_bytes(n, dtype))
+
+
+def _stream_ptr(stream) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+class Workspace:
+    """Device scratch for compress calls of up to n_elems; initialised once."""
+
+    def __init__(self, n_elems: int, dtype: int, device="cuda", stream=None):
+        self.n_elems = n_elems
+        self.nbytes = workspace_bytes(n_elems, dtype)
+        self.buf = torch.empty(self.nbytes, dtype=torch.uint8, device=device)
+        _check(lib().splitzip_workspace_init(self.buf.data_ptr(), self.nbytes, _stream_ptr(stream)),
+               "splitzip_workspace_init")
+
+
+def new_sizes(device="cuda") -> torch.Tensor:
+    """Zeroed device splitzip_sizes record (24 bytes as 3 x int64)."""
+    return torch.zeros(3, dtype=torch.int64, device=device)
+
+
+def read_sizes(sizes: torch.Tensor):
+    """(total_bytes, n_escapes, status) -- copies the record to the host (synchronises)."""
+    h = sizes.cpu()
+    return int(h[0]), int(h[1]), int(h[2]) & 0xFFFFFFFF
+
+
+def compress(x: torch.Tensor, cb: Codebook, out: torch.Tensor, workspace: Workspace,
+             sizes: torch.Tensor, stream=None, capacity: int | None = None) -> None:
+    """splitzip_compress: x (device words) -> out (device uint8), sizes written on the stream."""
+    n = x.numel()
+    if x.element_size() != _elem_size(cb.dtype) or not x.is_contiguous():
+        raise ValueError("x must be a contiguous tensor of raw words of the codebook's dtype")
+    cap = out.numel() * out.element_size() if capacity is None else capacity
+    _check(lib().splitzip_compress(x.data_ptr(), n, cb.dtype, C.byref(cb.c), out.data_ptr(), cap,
+                                   workspace.buf.data_ptr(), workspace.nbytes, sizes.data_ptr(),
+                                   _stream_ptr(stream)), "splitzip_compress")
+
+
+def decompress(comp: torch.Tensor, comp_bytes: int, n_elems: int, cb: Codebook, out: torch.Tensor,
+               sizes: torch.Tensor | None = None, stream=None) -> None:
+    """splitzip_decompress: comp (device uint8 stream) -> out (device words)."""
+    if out.numel() < n_elems or out.element_size() != _elem_size(cb.dtype) or not out.is_contiguous():
+        raise ValueError("out must be a contiguous tensor of at least n_elems raw words")
+    _check(lib().splitzip_decompress(comp.data_ptr(), comp_bytes, n_elems, cb.dtype, C.byref(cb.c),
+                                     out.data_ptr(), sizes.data_ptr() if sizes is not None else None,
+                                     _stream_ptr(stream)), "splitzip_decompress")
+
+
+def traffic_probe(src: torch.Tensor, read_bytes: int, dst: torch.Tensor, write_bytes: int, stream=None) -> None:
+    _check(lib().splitzip_traffic_probe(src.data_ptr(), read_bytes, dst.data_ptr(), write_bytes,
+                                        _stream_ptr(stream)), "splitzip_traffic_probe")

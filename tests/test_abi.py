@@ -1,0 +1,130 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the
+header declares, and its host-side logic (calibration, size functions,
+argument validation) agrees with the oracle.  No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+import kv_synth
+import oracle
+import paper_2605_01708_amd as sz
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "splitzip.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(splitzip_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert {"splitzip_calibrate", "splitzip_compress", "splitzip_decompress", "splitzip_workspace_init",
+            "splitzip_fixed_bytes", "splitzip_total_bytes", "splitzip_compress_bound",
+            "splitzip_workspace_bytes", "splitzip_codebook_from_dec", "splitzip_strerror",
+            "splitzip_version", "splitzip_traffic_probe"} <= set(names)
+    L = C.CDLL(sz.lib_path())
+    for n in names:
+        assert hasattr(L, n), n
+    assert sz.lib().splitzip_version() == 1
+    assert sz.lib().splitzip_strerror(-3) == b"buffer too small"
+
+
+@pytest.mark.parametrize("dtype,gen", [(sz.BF16, kv_synth.kv_bf16), (sz.FP8_E5M2, kv_synth.kv_e5m2)])
+def test_host_calibrate_matches_oracle(dtype, gen):
+    for seed, tokens in [(1, 64), (2, 7), (3, 1)]:
+        s = gen(tokens, seed)
+        cb, hist = sz.calibrate(s, dtype, return_hist=True)
+        ref = oracle.calibrate(kv_synth.to_numpy_words(s), dtype)
+        assert cb.dec == ref.dec.tolist()
+        assert cb.enc == ref.enc.tolist()
+        assert cb.member == ref.member.tolist()
+        assert hist == ref.hist.tolist()
+        assert cb.dtype == dtype
+
+
+def test_host_calibrate_ties_and_empty():
+    # ties to the smaller exponent, unseen values fill in ascending order (same reading as the oracle)
+    es = np.array([130] * 50 + [120] * 50 + [125] * 70 + [3] * 50, np.uint16)
+    cb = sz.calibrate(torch.from_numpy((es << 7).astype(np.int16)), sz.BF16)
+    assert cb.dec == [125, 3, 120, 130, 0, 1, 2, 4, 5, 6, 7, 8, 9, 10, 11, 12]
+    cb = sz.calibrate(torch.zeros(0, dtype=torch.int16), sz.BF16)
+    assert cb.dec == list(range(16))
+    cb = sz.calibrate(torch.tensor([31 << 2] * 9 + [30 << 2] * 9 + [2 << 2] * 10, dtype=torch.uint8), sz.FP8_E5M2)
+    assert cb.dec == [2, 30, 31, 0, 1, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13]
+
+
+def test_codebook_from_dec_validation():
+    cb = sz.codebook_from_dec(range(100, 116), sz.BF16)
+    assert cb.dec == list(range(100, 116)) and sum(cb.member) == 16 and cb.enc[107] == 7
+    with pytest.raises(sz.SplitZipError):
+        sz.codebook_from_dec([1] * 16, sz.BF16)            # duplicates
+    with pytest.raises(sz.SplitZipError):
+        sz.codebook_from_dec(range(20, 36), sz.FP8_E5M2)   # 5-bit exponents only
+    with pytest.raises(sz.SplitZipError):
+        sz.codebook_from_dec(range(16), 7)                 # dtype
+
+
+def test_size_functions_match_oracle():
+    for dtype in (sz.BF16, sz.FP8_E5M2):
+        for n in [0, 1, 2, 15, 16, 17, 1023, 1024, 1025, 8191, 8192, 8193, 4194304, 33554432]:
+            assert sz.fixed_bytes(n, dtype) == oracle.total_bytes(n, 0, dtype)
+            assert sz.compress_bound(n, dtype) == oracle.total_bytes(n, n, dtype)
+            for m in {0, 1, 7, 8, min(n, 12345)}:
+                if m <= n:
+                    assert sz.total_bytes(n, m, dtype) == oracle.total_bytes(n, m, dtype)
+            assert sz.workspace_bytes(n, dtype) >= n + 64
+    assert sz.fixed_bytes(1 << 32, sz.BF16) == 0 and sz.fixed_bytes(8, 5) == 0
+
+
+def test_argument_validation_without_gpu():
+    """Every rejected call returns before any GPU work is enqueued."""
+    L = sz.lib()
+    cb = sz.codebook_from_dec(range(100, 116), sz.BF16)
+    buf = (C.c_uint8 * 4096)()
+    base = (C.addressof(buf) + 15) & ~15
+    n = 64
+    good = dict(d_in=base, n=n, dtype=sz.BF16, cb=C.byref(cb.c), d_out=base + 1024, cap=1 << 20,
+                ws=base + 2048, wsb=1 << 20, sizes=base + 3072, stream=None)
+
+    def comp(**kw):
+        a = dict(good, **kw)
+        return L.splitzip_compress(a["d_in"], a["n"], a["dtype"], a["cb"], a["d_out"], a["cap"], a["ws"],
+                                   a["wsb"], a["sizes"], a["stream"])
+
+    assert comp(d_in=None) == -1
+    assert comp(d_out=None) == -1
+    assert comp(ws=None) == -1
+    assert comp(sizes=None) == -1
+    assert comp(d_in=base + 2) == -1           # misaligned
+    assert comp(d_out=base + 1024 + 8) == -1
+    assert comp(dtype=9) == -1
+    assert comp(n=1 << 32) == -2
+    assert comp(cap=sz.fixed_bytes(n, sz.BF16) - 1) == -3
+    assert comp(wsb=16) == -3
+    bad = sz.codebook_from_dec(range(100, 116), sz.BF16)
+    bad.c.enc[100] = 3                         # enc/dec no longer inverse
+    assert comp(cb=C.byref(bad.c)) == -1
+    e5 = sz.codebook_from_dec(range(16), sz.FP8_E5M2)
+    assert comp(cb=C.byref(e5.c)) == -1        # codebook built for another dtype
+
+    def decomp(**kw):
+        a = dict(d_comp=base, cb=C.byref(cb.c), bytes=1 << 20, n=n, dtype=sz.BF16, d_out=base + 1024,
+                 sizes=None, stream=None)
+        a.update(kw)
+        return L.splitzip_decompress(a["d_comp"], a["bytes"], a["n"], a["dtype"], a["cb"], a["d_out"],
+                                     a["sizes"], a["stream"])
+
+    assert decomp(d_comp=None) == -1
+    assert decomp(d_out=None) == -1
+    assert decomp(d_comp=base + 4) == -1
+    assert decomp(bytes=sz.fixed_bytes(n, sz.BF16) - 1) == -3
+    assert decomp(n=1 << 32) == -2
+    assert decomp(dtype=2) == -1
+    assert L.splitzip_workspace_init(None, 1024, None) == -1
+    assert L.splitzip_traffic_probe(None, 16, base, 16, None) == -1

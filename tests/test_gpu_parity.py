@@ -1,0 +1,265 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle,
+byte for byte -- the compressed stream and the decompressed tensor -- on the
+same seeded inputs.  All integer / bit work, so the bar is exact equality."""
+import numpy as np
+import pytest
+import torch
+
+import kv_synth
+import oracle
+import paper_2605_01708_amd as sz
+
+pytestmark = pytest.mark.gpu
+
+POISON = 0xA5
+DT = {sz.BF16: oracle.BF16, sz.FP8_E5M2: oracle.E5M2}
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "GPU tests need a GPU (run them on the MI355X box)"
+    print("device:", torch.cuda.get_device_name(0), flush=True)
+
+
+def words_tensor(x_np):
+    """numpy raw words -> device tensor of the same bytes"""
+    if x_np.dtype == np.uint16:
+        return torch.from_numpy(x_np.view(np.int16).copy()).cuda()
+    return torch.from_numpy(x_np.copy()).cuda()
+
+
+def gpu_codebook(cb_or):
+    return sz.codebook_from_dec(cb_or.dec.tolist(), cb_or.dtype)
+
+
+class Gpu:
+    """buffers for a run of calls of up to nmax elements"""
+
+    def __init__(self, nmax, dtype):
+        self.dtype = dtype
+        self.ws = sz.Workspace(nmax, dtype)
+        self.cap = sz.compress_bound(nmax, dtype) + 64
+        self.out = torch.empty(self.cap, dtype=torch.uint8, device="cuda")
+        self.sizes = sz.new_sizes()
+
+    def compress(self, x_dev, cb, capacity=None):
+        self.out.fill_(POISON)
+        self.sizes.fill_(-1)
+        sz.compress(x_dev, cb, self.out, self.ws, self.sizes, capacity=capacity)
+        torch.cuda.synchronize()
+        return sz.read_sizes(self.sizes)
+
+    def decompress(self, comp_dev, comp_bytes, n, cb):
+        es = 2 if self.dtype == sz.BF16 else 1
+        y = torch.full((n + 64,), 0x5A if es == 1 else 0x5A5A, dtype=torch.int16 if es == 2 else torch.uint8,
+                       device="cuda")
+        st = sz.new_sizes()
+        sz.decompress(comp_dev, comp_bytes, n, cb, y, st)
+        torch.cuda.synchronize()
+        yh = y.cpu().numpy()
+        yh = yh.view(np.uint16) if es == 2 else yh
+        guard = 0x5A5A if es == 2 else 0x5A
+        assert (yh[n:] == guard).all(), "decompress wrote past n_elems"
+        return yh[:n], sz.read_sizes(st)
+
+
+def check_parity(g, x_np, cb_or, label=""):
+    print(f"case {label}: n={x_np.size} dtype={g.dtype}", flush=True)
+    cb = gpu_codebook(cb_or)
+    x_dev = words_tensor(x_np)
+    ref_blob, ref_m = oracle.compress(x_np, cb_or)
+    total, m, status = g.compress(x_dev, cb)
+    assert status == 0
+    assert m == ref_m
+    assert total == ref_blob.size
+    got = g.out[:total].cpu().numpy()
+    if not np.array_equal(got, ref_blob):
+        bad = np.flatnonzero(got != ref_blob)
+        raise AssertionError(f"{label}: stream differs at {bad.size} bytes, first {bad[:8]} "
+                             f"got {got[bad[:8]]} want {ref_blob[bad[:8]]}")
+    tail = g.out[total:total + 4096].cpu().numpy()
+    assert (tail == POISON).all(), "compress wrote past total_bytes"
+    # GPU decoder on the GPU stream and on the oracle's stream
+    y, (t2, m2, st2) = g.decompress(g.out, total, x_np.size, cb)
+    assert st2 == 0 and t2 == total and m2 == m
+    assert np.array_equal(y, x_np), f"{label}: GPU round trip differs"
+    ref_dev = torch.from_numpy(ref_blob.copy()).cuda()
+    y2, (_, _, st3) = g.decompress(ref_dev, ref_blob.size, x_np.size, cb)
+    assert st3 == 0 and np.array_equal(y2, x_np)
+    # oracle decoder on the GPU stream
+    assert np.array_equal(oracle.decompress(got, x_np.size, cb_or), x_np)
+    return total, m
+
+
+def synth(dtype, tokens, seed, layer=0, kind="K"):
+    gen = kv_synth.kv_bf16 if dtype == sz.BF16 else kv_synth.kv_e5m2
+    return kv_synth.to_numpy_words(gen(tokens, seed, layer, kind))
+
+
+def calibrated(dtype, seed=1, tokens=1024, layer=0, kind="K"):
+    return oracle.calibrate(synth(dtype, tokens, seed, layer, kind), DT[dtype])
+
+
+DTYPES = [sz.BF16]
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_config0_single_k_tensor(dtype):
+    """[4096, 8, 128] tensor, codebook from a separate seed-1 tensor of the same law"""
+    x = synth(dtype, 4096, 0)
+    cb = calibrated(dtype, seed=1, tokens=4096)
+    g = Gpu(x.size, dtype)
+    total, m = check_parity(g, x, cb, "config0")
+    es = 2 if dtype == sz.BF16 else 1
+    print(f"config0 dtype={dtype}: eps={m / x.size:.5f} ratio={es * x.size / total:.4f}", flush=True)
+    assert m / x.size < 0.01
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_ragged_and_tiny_sizes(dtype):
+    """empty, single element, pack / lane / chunk / tile boundaries, several tiles plus a ragged tail"""
+    cb = calibrated(dtype)
+    base = synth(dtype, 64, 5).copy()                     # 65536 elements
+    rng = np.random.default_rng(2)
+    esc = rng.random(base.size) < 0.01                     # sprinkle zeros / max exponents
+    base[esc] = 0
+    base[::4099] = 0x7F80 if dtype == sz.BF16 else 0x7C
+    g = Gpu(base.size, dtype)
+    sizes = [0, 1, 2, 3, 15, 16, 17, 31, 32, 33, 1023, 1024, 1025, 2047, 2048, 2049, 8191, 8192, 8193,
+             16384, 3 * 8192 + 5, 5 * 8192 - 1, 40000, 65535, 65536]
+    for n in sizes:
+        check_parity(g, base[:n].copy(), cb, f"n={n}")
+
+
+def test_all_bf16_bit_patterns():
+    rng = np.random.default_rng(7)
+    x = rng.permutation(65536).astype(np.uint16)
+    g = Gpu(x.size, sz.BF16)
+    books = [oracle.codebook_from_dec(np.arange(119, 135, dtype=np.uint8), oracle.BF16),
+             oracle.codebook_from_dec(np.arange(200, 216, dtype=np.uint8), oracle.BF16),
+             oracle.codebook_from_dec(np.array([0, 255] + list(range(120, 134)), np.uint8), oracle.BF16)]
+    for i, cb in enumerate(books):
+        check_parity(g, x, cb, f"patterns/cb{i}")
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_all_escape_and_no_escape(dtype):
+    """codebook that covers nothing (M = N, every chunk full) next to one that covers everything"""
+    x = synth(dtype, 41, 3)[: 5 * 8192 + 777].copy()
+    g = Gpu(x.size, dtype)
+    if dtype == sz.BF16:
+        none = oracle.codebook_from_dec(np.arange(230, 246, dtype=np.uint8), oracle.BF16)
+    else:
+        none = oracle.codebook_from_dec(np.array([0, 31, 1, 30, 2, 29, 3, 28, 4, 27, 5, 26, 6, 25, 24, 23], np.uint8),
+                                        oracle.E5M2)
+        x = x[(((x >> 2) & 0x1F) >= 7) & (((x >> 2) & 0x1F) <= 22)][: 3 * 8192 + 77].copy()
+    total, m = check_parity(g, x, none, "all-escape")
+    assert m == x.size
+    cb = calibrated(dtype)
+    e = ((x >> 7) & 0xFF) if dtype == sz.BF16 else ((x >> 2) & 0x1F)
+    covered = x[np.isin(e, cb.dec)].copy()
+    total, m = check_parity(g, covered, cb, "no-escape")
+    assert m == 0
+    # mixed: an all-escape chunk right next to clean ones
+    y = covered[: 4 * 8192].copy()
+    y[1024:2048] = 0
+    y[8191] = 0
+    y[8192] = 0
+    check_parity(g, y, cb, "burst")
+
+
+def test_escape_stress_outliers():
+    """config-2 law at reduced size: 0.5 % outliers x 2^U{6..14}, 0.1 % zeros / subnormals"""
+    x = kv_synth.to_numpy_words(kv_synth.kv_bf16_outliers(512, 0))
+    cb = calibrated(sz.BF16)
+    g = Gpu(x.size, sz.BF16)
+    total, m = check_parity(g, x, cb, "outliers")
+    print(f"outliers eps={m / x.size:.5f}", flush=True)
+    assert m / x.size > 0.003
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_deterministic_and_workspace_reuse(dtype):
+    """same input twice -> identical stream; one workspace serves calls of different sizes in a row"""
+    cb_or = calibrated(dtype)
+    cb = gpu_codebook(cb_or)
+    x = synth(dtype, 300, 11)
+    g = Gpu(x.size, dtype)
+    xd = words_tensor(x)
+    t1 = g.compress(xd, cb)
+    a = g.out[: t1[0]].clone()
+    for n in (x.size, 12345, x.size, 1, x.size):
+        t = g.compress(xd[:n], cb)
+        assert t[2] == 0
+        if n == x.size:
+            assert t == t1 and torch.equal(g.out[: t[0]], a)
+        else:
+            ref, _ = oracle.compress(x[:n], cb_or)
+            assert np.array_equal(g.out[: t[0]].cpu().numpy(), ref)
+
+
+def test_overflow_reports_needed_size():
+    """escapes that do not fit: status OVERFLOW, total_bytes = size needed, nothing written past capacity"""
+    x = synth(sz.BF16, 64, 3)
+    none = oracle.codebook_from_dec(np.arange(230, 246, dtype=np.uint8), oracle.BF16)
+    cb = gpu_codebook(none)
+    g = Gpu(x.size, sz.BF16)
+    xd = words_tensor(x)
+    fixed = sz.fixed_bytes(x.size, sz.BF16)
+    need = sz.total_bytes(x.size, x.size, sz.BF16)
+    for cap in (fixed, fixed + 1000, need - 1):
+        total, m, status = g.compress(xd, cb, capacity=cap)
+        assert status == sz.STATUS_OVERFLOW and total == need and m == x.size
+        assert (g.out[cap:cap + 4096].cpu().numpy() == POISON).all()
+        # the fixed part is still the oracle's
+        ref, _ = oracle.compress(x, none)
+        assert np.array_equal(g.out[64:fixed].cpu().numpy(), ref[64:fixed])
+    total, m, status = g.compress(xd, cb, capacity=need)
+    assert status == 0 and total == need
+
+
+def test_bad_stream_is_flagged_not_followed():
+    x = synth(sz.BF16, 16, 3).copy()
+    x[5] = 0
+    x[9000] = 0x7F80
+    cb_or = calibrated(sz.BF16)
+    cb = gpu_codebook(cb_or)
+    blob, m = oracle.compress(x, cb_or)
+    g = Gpu(x.size, sz.BF16)
+    n = x.size
+
+    def run(mut):
+        b = blob.copy()
+        mut(b)
+        y, (_, _, st) = g.decompress(torch.from_numpy(b).cuda(), b.size, n, cb)
+        return y, st
+
+    def set_(i, v):
+        def f(b):
+            b[i] = v
+        return f
+
+    y, st = run(lambda b: None)
+    assert st == 0 and np.array_equal(y, x)
+    for mut in (set_(0, 0x58), set_(6, 1), set_(16, int(blob[16]) ^ 1), set_(40, int(blob[40]) ^ 1)):
+        y, st = run(mut)                     # header disagrees: flagged
+        assert st & sz.STATUS_BAD_STREAM
+    off_pos = blob.size - m - (2 * m + 15) // 16 * 16
+    y, st = run(set_(off_pos + 1, 0xFF))     # position outside the chunk: skipped and flagged
+    assert st & sz.STATUS_BAD_STREAM
+    c = (n + 1023) // 1024
+    y, st = run(set_(64 + 4 * c + 3, 0x7F))  # M in the offset table far beyond the stream
+    assert st & sz.STATUS_BAD_STREAM
+
+
+def test_full_size_tensors_of_the_benchmark_workload():
+    """config 1 at its real tensor size [32768, 8, 128] (64 MiB), K of layer 0 and V of layer 31, with the
+    per-kind codebooks from a seed-1 1024-token sample; whole stream and round trip compared."""
+    n = 32768 * 1024
+    g = Gpu(n, sz.BF16)
+    for layer, kind in ((0, "K"), (31, "V")):
+        cb_or = calibrated(sz.BF16, seed=1, tokens=1024, layer=0, kind=kind)
+        x_dev = kv_synth.kv_bf16(32768, 0, layer, kind, device="cuda")
+        x = kv_synth.to_numpy_words(x_dev)
+        total, m = check_parity(g, x, cb_or, f"config1 L{layer}{kind}")
+        print(f"config1 L{layer}{kind}: eps={m / n:.5f} ratio={2 * n / total:.4f}", flush=True)
