@@ -139,16 +139,16 @@ def main():
     c_ach = alg_bytes / (c_launch_us * 1e-6) / 1e9
     d_ach = alg_bytes / (d_launch_us * 1e-6) / 1e9
 
-    # plain streaming kernel with the codec's traffic (reads 4, writes 3 parts), same buffers
+    # plain streaming kernel with the codec's traffic (reads 4, writes 3 parts) into the decode outputs
     wbytes = raw_bytes * 3 // 4 // 16 * 16
     for _ in range(2):
         for i, (kind, x) in enumerate(xs):
-            sz.traffic_probe(x, raw_bytes, comps[i], wbytes)
+            sz.traffic_probe(x, raw_bytes, outs[i], wbytes)
     p0, p1 = ev(), ev()
     p0.record()
     for _ in range(3):
         for i, (kind, x) in enumerate(xs):
-            sz.traffic_probe(x, raw_bytes, comps[i], wbytes)
+            sz.traffic_probe(x, raw_bytes, outs[i], wbytes)
     p1.record()
     torch.cuda.synchronize()
     probe_gbps = (raw_bytes + wbytes) * nt * 3 / (p0.elapsed_time(p1) * 1e-3) / 1e9

@@ -1,20 +1,24 @@
 // SplitZip codec for MI355X (gfx950): HIP kernels and the C ABI of include/splitzip.h.
 //
-// One compress call is ONE kernel launch: the dense transform (paper section
+// One compress call is ONE kernel launch.  The dense transform (paper section
 // 3.2 eq. (1), encode table, nibble pack, sign+mantissa plane) is fused with
 // escape detection, per-chunk counting and the position-ordered compaction of
-// the escape stream.  The cross-workgroup offsets of the compaction come from
-// a decoupled look-back scan over per-tile escape counts, so the input is read
-// exactly once and the output does not depend on scheduling.
+// the escape stream (appendix A fuses only the counting).  The input is read
+// exactly once: escapes are staged in LDS while their words are in registers,
+// and the cross-workgroup offsets come from a decoupled look-back scan over
+// per-tile escape counts, so the output does not depend on scheduling.
 // One decompress call is ONE kernel launch as well: nibble unpack, decode
 // table, eq. (2), and the sparse overwrite done by the wave that owns the
-// chunk, after its own dense stores.
+// chunk once its own dense stores have completed.
 //
 // Work decomposition (wavefront = 64 lanes, workgroup = 4 waves):
-//   tile  = 8 chunks = 8192 elements, one per workgroup iteration
-//   chunk = 1024 elements, owned by one wave; lane l owns elements
-//           [16 l, 16 l + 16) of the chunk: two 128-bit loads, one 128-bit
-//           sign+mantissa store and one 64-bit code store per lane and chunk.
+//   chunk = 1024 elements (the escape-position granule), owned by one wave and
+//           processed as two half-chunks of 512 elements; in a half-chunk lane
+//           l owns elements [8 l, 8 l + 8): every global access of a wave is
+//           one fully coalesced run (16, 8 or 4 bytes per lane).
+//   tile  = 4 waves x cpw consecutive chunks each, one tile per workgroup;
+//           cpw (1..16) is chosen per call so that the grid fills the chip.
+// All plane traffic uses non-temporal loads / stores: nothing is re-used.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdlib.h>
@@ -24,14 +28,17 @@
 
 namespace {
 
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 constexpr uint32_t kChunk = 1024;
+constexpr uint32_t kHalf = 512;
 constexpr uint32_t kHeaderBytes = 64;
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
-constexpr int kCPW = 2;                                   // chunks per wave per tile
-constexpr uint32_t kTileChunks = kWaves * kCPW;           // 8
-constexpr uint32_t kTileElems = kTileChunks * kChunk;     // 8192
-constexpr uint32_t kLaneElems = 16;                       // elements per lane per chunk (BF16)
+constexpr uint32_t kMaxCpw = 16;                          // chunks per wave per tile, at most
+constexpr uint32_t kMinTileChunks = kWaves;               // smallest tile (cpw = 1)
+constexpr uint32_t kStageCap = 512;                       // escapes a wave can stage in LDS
 constexpr uint32_t kWsHeaderBytes = 64;                   // ticket, done, flags
 constexpr uint32_t kSpinLimit = 1u << 22;                 // look-back polls before giving up
 
@@ -39,7 +46,7 @@ __host__ __device__ inline uint64_t a16(uint64_t x) { return (x + 15u) & ~(uint6
 __host__ __device__ inline uint64_t a256(uint64_t x) { return (x + 255u) & ~(uint64_t)255u; }
 
 struct Layout {
-  uint64_t n, n_chunks, n_tiles, sm_bytes, code_bytes;
+  uint64_t n, n_chunks, sm_bytes, code_bytes;
   uint64_t off_tab, off_sm, off_code, off_pos;  // the value section starts at off_pos + a16(2M)
 };
 
@@ -47,7 +54,6 @@ __host__ __device__ inline Layout make_layout(uint64_t n, int dtype) {
   Layout L;
   L.n = n;
   L.n_chunks = (n + kChunk - 1) / kChunk;
-  L.n_tiles = (n + kTileElems - 1) / kTileElems;
   L.sm_bytes = dtype == SPLITZIP_BF16 ? n : (3 * n + 7) / 8;
   L.code_bytes = (n + 1) / 2;
   L.off_tab = kHeaderBytes;
@@ -61,56 +67,60 @@ __host__ __device__ inline Layout make_layout(uint64_t n, int dtype) {
 // device helpers
 // ---------------------------------------------------------------------------
 
+template <typename T>
+__device__ inline T ld_stream(const T* p) { return __builtin_nontemporal_load(p); }
+template <typename T>
+__device__ inline void st_stream(T* p, T v) { __builtin_nontemporal_store(v, p); }
+
 // v_perm_b32: result byte i = byte sel[i] of the 8-byte pool {hi:4..7, lo:0..3}; 0x0c gives 0x00.
 __device__ inline uint32_t byte_perm(uint32_t hi, uint32_t lo, uint32_t sel) {
   return __builtin_amdgcn_perm(hi, lo, sel);
 }
 
-__device__ inline uint32_t wave_incl_scan(uint32_t v, int lane) {
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    uint32_t t = __shfl_up(v, d, 64);
-    if (lane >= d) v += t;
-  }
+// inclusive prefix sum over the 64 lanes with DPP moves: Kogge-Stone inside rows of 16 lanes,
+// then the row totals are carried over with the two row-broadcast steps
+__device__ inline uint32_t wave_incl_scan(uint32_t v) {
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x111, 0xf, 0xf, false);  // row_shr:1
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x112, 0xf, 0xf, false);  // row_shr:2
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x114, 0xf, 0xf, false);  // row_shr:4
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x118, 0xf, 0xf, false);  // row_shr:8
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1, 3
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2, 3
   return v;
 }
 
-__device__ inline uint32_t wave_sum(uint32_t v) {
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
-  return v;
-}
+__device__ inline uint32_t wave_last(uint32_t v) { return __builtin_amdgcn_readlane(v, 63); }
+
+// agent-scope relaxed accesses: performed at the device-wide coherence point, no fences
+template <typename T>
+__device__ inline void st_agent(T* p, T v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+template <typename T>
+__device__ inline T ld_agent(const T* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
 // tile state of the decoupled look-back scan: flag in the two top bits, count below
 constexpr uint64_t kFlagAgg = 1ull << 62;   // value = escapes of this tile only
 constexpr uint64_t kFlagInc = 2ull << 62;   // value = escapes of all tiles up to and including this one
 
-__device__ inline void st_state(uint64_t* p, uint64_t v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ inline uint64_t ld_state(const uint64_t* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
 // Run by one whole wave.  Publishes this tile's escape count, sums the counts
 // of all earlier tiles (64 predecessors per poll) and publishes the inclusive
 // total.  Flag and count share one 64-bit word, so relaxed accesses suffice.
-// Every tile a wave waits for was handed out earlier by the ticket counter and
-// publishes its count without waiting for anyone, so the wait always ends; the
-// poll limit only guards against a workspace that was never initialised.
+// Tiles are handed out by a ticket counter: every tile a wave waits for belongs
+// to a workgroup that is already running and that publishes its count without
+// waiting for anyone, so the wait always ends; the poll limit only guards
+// against a workspace that was never initialised.
 __device__ inline uint32_t lookback(uint64_t* state, uint32_t tile, uint32_t agg, int lane,
                                     uint32_t* ws_flags) {
   if (tile == 0) {
-    if (lane == 0) st_state(&state[0], kFlagInc | agg);
+    if (lane == 0) st_agent(&state[0], kFlagInc | (uint64_t)agg);
     return 0;
   }
-  if (lane == 0) st_state(&state[tile], kFlagAgg | agg);
+  if (lane == 0) st_agent(&state[tile], kFlagAgg | (uint64_t)agg);
   uint32_t prefix = 0;
   int64_t base = (int64_t)tile - 1;
   uint32_t spins = 0;
   for (;;) {
     const int64_t idx = base - lane;
-    const uint64_t s = idx >= 0 ? ld_state(&state[idx]) : kFlagInc;  // before tile 0: inclusive 0
+    const uint64_t s = idx >= 0 ? ld_agent(&state[idx]) : kFlagInc;  // before tile 0: inclusive 0
     const uint32_t flag = (uint32_t)(s >> 62);
     const uint64_t inc_mask = __ballot(flag == 2u);
     const uint64_t empty_mask = __ballot(flag == 0u);
@@ -121,14 +131,14 @@ __device__ inline uint32_t lookback(uint64_t* state, uint32_t tile, uint32_t agg
         if (lane == 0) atomicOr(ws_flags, SPLITZIP_STATUS_INTERNAL);
         break;
       }
-      __builtin_amdgcn_s_sleep(2);
+      __builtin_amdgcn_s_sleep(1);
       continue;
     }
-    prefix += wave_sum(lane <= first_inc ? (uint32_t)s : 0u);
+    prefix += wave_last(wave_incl_scan(lane <= first_inc ? (uint32_t)s : 0u));
     if (first_inc < 64) break;
     base -= 64;
   }
-  if (lane == 0) st_state(&state[tile], kFlagInc | (uint64_t)(prefix + agg));
+  if (lane == 0) st_agent(&state[tile], kFlagInc | (uint64_t)(prefix + agg));
   return prefix;
 }
 
@@ -145,20 +155,39 @@ struct CompressArgs {
   uint8_t* val_stage;    // n bytes: escape values until M is known
   splitzip_sizes* sizes;
   uint64_t off_tab, off_sm, off_code, off_pos, sm_bytes, code_bytes;
-  uint32_t n_chunks, n_tiles, dtype, pad;
+  uint32_t n_chunks, n_tiles, cpw, dtype;
   uint8_t dec[16];
   uint16_t lut[256];     // exponent -> code | (non-member ? 0x100 : 0)   (the "marked" table of appendix A)
 };
 
-// Dense transform of one lane's 16 BF16 elements (eight dwords w).
-//   sm   : 16 sign+mantissa bytes, a = ((x >> 8) & 0x80) | (x & 0x7f)        (eq. (1))
-//   code : 16 nibbles, element j in nibble j
-//   F    : 16 nibbles, nibble j = 1 if element j is an escape
-__device__ inline void encode16_bf16(const uint32_t (&w)[8], const uint16_t* lut, uint4& sm,
-                                     uint2& code, uint2& F) {
-  uint32_t t[8], u[8];
+// where a chunk's escape records go: LDS staging (first pass) or their final place (second pass)
+struct LdsSink {
+  uint16_t* pos;
+  uint8_t* val;
+  __device__ inline void put(uint32_t r, uint32_t p, uint32_t e) const {
+    if (r < kStageCap) {
+      pos[r] = (uint16_t)p;
+      val[r] = (uint8_t)e;
+    }
+  }
+};
+struct GlobalSink {
+  const CompressArgs* a;
+  __device__ inline void put(uint32_t r, uint32_t p, uint32_t e) const {
+    if (a->off_pos + 2ull * (r + 1) <= a->capacity) reinterpret_cast<uint16_t*>(a->out + a->off_pos)[r] = (uint16_t)p;
+    st_agent(a->val_stage + r, (uint8_t)e);
+  }
+};
+
+// Dense transform of 8 BF16 elements held in four dwords.
+//   sm   : 8 sign+mantissa bytes, a = ((x >> 8) & 0x80) | (x & 0x7f)        (eq. (1))
+//   code : 8 nibbles, element j in nibble j
+//   F    : 8 nibbles, nibble j = 1 if element j is an escape
+__device__ inline void encode8_bf16(const uint32_t (&w)[4], const uint16_t* lut, u32x2& sm,
+                                    uint32_t& code, uint32_t& F) {
+  uint32_t t[4], u[4];
 #pragma unroll
-  for (int d = 0; d < 8; ++d) {
+  for (int d = 0; d < 4; ++d) {
     // bytes 0 and 2 of t hold a of the low / high half-word
     t[d] = (w[d] & 0x007f007fu) | ((w[d] >> 8) & 0x00800080u);
     const uint32_t e0 = (w[d] >> 7) & 0xffu, e1 = (w[d] >> 23) & 0xffu;
@@ -167,70 +196,110 @@ __device__ inline void encode16_bf16(const uint32_t (&w)[8], const uint16_t* lut
   }
   sm.x = byte_perm(t[1], t[0], 0x06040200u);
   sm.y = byte_perm(t[3], t[2], 0x06040200u);
-  sm.z = byte_perm(t[5], t[4], 0x06040200u);
-  sm.w = byte_perm(t[7], t[6], 0x06040200u);
   // x = [code(u_lo), code(u_hi), flag(u_lo), flag(u_hi)]
   const uint32_t x01 = byte_perm(u[1], u[0], 0x05010400u), x23 = byte_perm(u[3], u[2], 0x05010400u);
-  const uint32_t x45 = byte_perm(u[5], u[4], 0x05010400u), x67 = byte_perm(u[7], u[6], 0x05010400u);
-  code.x = byte_perm(x23, x01, 0x05040100u);
-  code.y = byte_perm(x67, x45, 0x05040100u);
-  F.x = byte_perm(x23, x01, 0x07060302u);
-  F.y = byte_perm(x67, x45, 0x07060302u);
+  code = byte_perm(x23, x01, 0x05040100u);
+  F = byte_perm(x23, x01, 0x07060302u);
 }
 
-template <bool FULL>
-__device__ inline void compress_lane_chunk_bf16(const CompressArgs& a, const uint16_t* lut,
-                                                uint64_t e0, uint2& F) {
-  uint32_t w[8];
-  uint32_t nvalid = kLaneElems;
-  if (!FULL) nvalid = e0 >= a.n ? 0u : (uint32_t)(a.n - e0 < kLaneElems ? a.n - e0 : kLaneElems);
-  if (FULL || nvalid == kLaneElems) {
-    const uint4* p = reinterpret_cast<const uint4*>(a.in + 2 * e0);
-    const uint4 v0 = p[0], v1 = p[1];
-    w[0] = v0.x; w[1] = v0.y; w[2] = v0.z; w[3] = v0.w;
-    w[4] = v1.x; w[5] = v1.y; w[6] = v1.z; w[7] = v1.w;
-  } else {
-    const uint16_t* p = reinterpret_cast<const uint16_t*>(a.in) + e0;
+// escape records of one lane's 8 elements (flag nibbles in m), ranks r, r+1, ...
+// The lane parks its four dwords in its own 16 bytes of LDS so that the escaping element can be
+// picked with a run-time index (registers cannot be indexed that way).
+template <typename Sink>
+__device__ inline void emit_half_bf16(uint32_t* park, const uint32_t (&w)[4], uint32_t m, uint32_t r,
+                                      uint32_t pos0, const Sink& sink) {
+  if (m) {
+    *reinterpret_cast<u32x4*>(park) = u32x4{w[0], w[1], w[2], w[3]};
+    const uint16_t* x = reinterpret_cast<const uint16_t*>(park);
+    do {
+      const uint32_t jj = (uint32_t)(__ffs(m) - 1) >> 2;
+      m &= m - 1;
+      sink.put(r, pos0 + jj, ((uint32_t)x[jj] >> 7) & 0xffu);
+      ++r;
+    } while (m);
+  }
+}
+
+// One chunk by one wave: load, dense transform, (optionally) plane stores, escape
+// ranks inside the chunk, escape records into `sink` starting at rank `base`.
+// Returns the chunk's escape count (wave-uniform).
+template <bool FULL, bool STORE, typename Sink>
+__device__ inline uint32_t compress_chunk_bf16(const CompressArgs& a, const uint16_t* lut, uint32_t* park,
+                                               uint64_t cbase, int lane, uint32_t base, const Sink& sink) {
+  uint32_t w[2][4], F[2];
 #pragma unroll
-    for (int d = 0; d < 8; ++d) {
-      const uint32_t lo = (uint32_t)(2 * d) < nvalid ? p[2 * d] : 0u;
-      const uint32_t hi = (uint32_t)(2 * d + 1) < nvalid ? p[2 * d + 1] : 0u;
-      w[d] = lo | (hi << 16);
+  for (int h = 0; h < 2; ++h) {
+    const uint64_t g0 = cbase + h * kHalf + lane * 8;   // first element of this lane's group
+    uint32_t nvalid = 8;
+    if (!FULL) nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 8 ? a.n - g0 : 8);
+    if (FULL || nvalid == 8) {
+      const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(a.in + 2 * g0));
+      w[h][0] = v.x; w[h][1] = v.y; w[h][2] = v.z; w[h][3] = v.w;
+    } else {
+      const uint16_t* p = reinterpret_cast<const uint16_t*>(a.in) + g0;
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        const uint32_t lo = (uint32_t)(2 * d) < nvalid ? p[2 * d] : 0u;
+        const uint32_t hi = (uint32_t)(2 * d + 1) < nvalid ? p[2 * d + 1] : 0u;
+        w[h][d] = lo | (hi << 16);
+      }
     }
   }
-  uint4 sm;
-  uint2 code;
-  encode16_bf16(w, lut, sm, code, F);
-  if (!FULL && nvalid < kLaneElems) {
-    // elements past N contribute zero nibbles (their sm bytes are already 0)
-    const uint64_t keep = nvalid ? (~0ull >> (64 - 4 * nvalid)) : 0ull;
-    code.x &= (uint32_t)keep; code.y &= (uint32_t)(keep >> 32);
-    F.x &= (uint32_t)keep; F.y &= (uint32_t)(keep >> 32);
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const uint64_t g0 = cbase + h * kHalf + lane * 8;
+    u32x2 sm;
+    uint32_t code;
+    encode8_bf16(w[h], lut, sm, code, F[h]);
+    if (!FULL) {
+      const uint32_t nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 8 ? a.n - g0 : 8);
+      // elements past N contribute zero nibbles (their sm bytes are already 0)
+      const uint32_t keep = nvalid == 8 ? ~0u : ((1u << (4 * nvalid)) - 1u);
+      code &= keep;
+      F[h] &= keep;
+    }
+    if (STORE) {
+      // Sections are padded to 16 bytes and a lane's group never straddles the padded end, so
+      // whole-group stores also write the zero padding.
+      if (FULL || g0 < a16(a.sm_bytes)) st_stream(reinterpret_cast<u32x2*>(a.out + a.off_sm + g0), sm);
+      if (FULL || (g0 >> 1) < a16(a.code_bytes))
+        st_stream(reinterpret_cast<uint32_t*>(a.out + a.off_code + (g0 >> 1)), code);
+    }
   }
-  // Sections are padded to 16 bytes and a lane's group never straddles the
-  // padded end, so whole-vector stores also write the zero padding.
-  if (FULL || e0 < a16(a.sm_bytes)) *reinterpret_cast<uint4*>(a.out + a.off_sm + e0) = sm;
-  if (FULL || (e0 >> 1) < a16(a.code_bytes)) *reinterpret_cast<uint2*>(a.out + a.off_code + (e0 >> 1)) = code;
+  // escapes per lane; both halves scanned at once (16 bits each: a half has at most 512)
+  const uint32_t packed = __popc(F[0]) | (__popc(F[1]) << 16);
+  const uint32_t incl = wave_incl_scan(packed);
+  const uint32_t tot = wave_last(incl);
+  const uint32_t excl = incl - packed;
+  const uint32_t tot0 = tot & 0xffffu, total = tot0 + (tot >> 16);
+  if (total) {
+    // element order inside the chunk: half, lane, element
+    emit_half_bf16(park, w[0], F[0], base + (excl & 0xffffu), lane * 8, sink);
+    emit_half_bf16(park, w[1], F[1], base + tot0 + (excl >> 16), kHalf + lane * 8, sink);
+  }
+  return total;
 }
 
 // Last workgroup to finish: M is known now.  Moves the staged escape values
 // behind the position array, writes pads, header and sizes, and leaves the
-// workspace zeroed for the next call.
+// workspace zeroed for the next call.  The staged values were written with
+// agent-scope stores that had completed before their workgroup signalled, and
+// are read with agent-scope loads.
 __device__ void compress_finalize(const CompressArgs& a, int tid) {
-  const uint32_t M = a.n_tiles ? (uint32_t)ld_state(&a.state[a.n_tiles - 1]) : 0u;
+  const uint32_t M = a.n_tiles ? (uint32_t)ld_agent(&a.state[a.n_tiles - 1]) : 0u;
   const uint64_t off_val = a.off_pos + a16(2ull * M);
   const uint64_t total = off_val + M;
-  const uint64_t nvec = M / 16;
-  const uint4* src = reinterpret_cast<const uint4*>(a.val_stage);
-  uint4* dst = reinterpret_cast<uint4*>(a.out + off_val);
+  const uint64_t nvec = M / 8;
+  const uint64_t* src = reinterpret_cast<const uint64_t*>(a.val_stage);
+  uint64_t* dst = reinterpret_cast<uint64_t*>(a.out + off_val);
   for (uint64_t i = tid; i < nvec; i += kThreads)
-    if (off_val + 16 * (i + 1) <= a.capacity) dst[i] = src[i];
-  for (uint64_t i = nvec * 16 + tid; i < M; i += kThreads)
-    if (off_val + i < a.capacity) a.out[off_val + i] = a.val_stage[i];
+    if (off_val + 8 * (i + 1) <= a.capacity) dst[i] = ld_agent(src + i);
+  for (uint64_t i = nvec * 8 + tid; i < M; i += kThreads)
+    if (off_val + i < a.capacity) a.out[off_val + i] = ld_agent(a.val_stage + i);
   for (uint64_t i = 2ull * M + tid; i < a16(2ull * M); i += kThreads)
     if (a.off_pos + i < a.capacity) a.out[a.off_pos + i] = 0;
   if (a.n_tiles == 0 && tid < 4) reinterpret_cast<uint32_t*>(a.out + a.off_tab)[tid] = 0;  // chunk_off[0] + pad
-  for (uint32_t i = tid; i < a.n_tiles; i += kThreads) st_state(&a.state[i], 0);
+  for (uint32_t i = tid; i < a.n_tiles; i += kThreads) st_agent(&a.state[i], (uint64_t)0);
   if (tid == 0) {
     uint32_t h[16];
 #pragma unroll
@@ -247,133 +316,101 @@ __device__ void compress_finalize(const CompressArgs& a, int tid) {
     uint4* ho = reinterpret_cast<uint4*>(a.out);
 #pragma unroll
     for (int i = 0; i < 4; ++i) ho[i] = make_uint4(h[4 * i], h[4 * i + 1], h[4 * i + 2], h[4 * i + 3]);
-    const uint32_t flags = a.ws_hdr[2];
+    const uint32_t flags = ld_agent(&a.ws_hdr[2]);
     a.sizes->total_bytes = total;
     a.sizes->n_escapes = M;
     a.sizes->status = (total > a.capacity ? SPLITZIP_STATUS_OVERFLOW : 0u) | flags;
     a.sizes->reserved = 0;
-    a.ws_hdr[0] = 0;
-    a.ws_hdr[1] = 0;
-    a.ws_hdr[2] = 0;
+    st_agent(&a.ws_hdr[0], 0u);
+    st_agent(&a.ws_hdr[1], 0u);
+    st_agent(&a.ws_hdr[2], 0u);
   }
 }
 
 __global__ __launch_bounds__(kThreads) void compress_bf16_kernel(const CompressArgs a) {
   __shared__ uint16_t lut[256];
-  __shared__ uint32_t s_cnt[kTileChunks];
-  __shared__ uint32_t s_next, s_prefix, s_last;
+  __shared__ uint16_t stage_pos[kWaves][kStageCap];
+  __shared__ uint8_t stage_val[kWaves][kStageCap];
+  __shared__ uint32_t s_cnt[kWaves * kMaxCpw];
+  __shared__ u32x4 s_park[kThreads];
+  __shared__ uint32_t s_tile, s_prefix, s_last;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  uint32_t* park = reinterpret_cast<uint32_t*>(&s_park[tid]);
 
   lut[tid] = a.lut[tid];
-  if (tid == 0) s_next = atomicAdd(&a.ws_hdr[0], 1u);
+  if (tid < (int)(kWaves * kMaxCpw)) s_cnt[tid] = 0;
+  if (tid == 0) s_tile = a.n_tiles ? __hip_atomic_fetch_add(&a.ws_hdr[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
   __syncthreads();
-  uint32_t tile = s_next;
+  const uint32_t tile = s_tile;
 
-  while (tile < a.n_tiles) {
-    // ticket of the next tile: asked for now, needed at the end of this iteration
-    uint32_t ticket = 0;
-    if (tid == 0) ticket = atomicAdd(&a.ws_hdr[0], 1u);
-
-    const uint64_t tile_e0 = (uint64_t)tile * kTileElems;
-    const uint32_t chunk0 = tile * kTileChunks + wave * kCPW;   // first chunk of this wave
-    const bool full = tile_e0 + kTileElems <= a.n;
-    uint2 F[kCPW];
-    if (full) {
-#pragma unroll
-      for (int k = 0; k < kCPW; ++k)
-        compress_lane_chunk_bf16<true>(a, lut, (uint64_t)(chunk0 + k) * kChunk + lane * kLaneElems, F[k]);
-    } else {
-#pragma unroll
-      for (int k = 0; k < kCPW; ++k)
-        compress_lane_chunk_bf16<false>(a, lut, (uint64_t)(chunk0 + k) * kChunk + lane * kLaneElems, F[k]);
-    }
-
-    // escapes per lane and chunk, both chunks scanned at once (16 bits each: a chunk has <= 1024)
-    uint32_t cnt[kCPW], packed = 0;
-#pragma unroll
-    for (int k = 0; k < kCPW; ++k) {
-      cnt[k] = __popc(F[k].x) + __popc(F[k].y);
-      packed |= cnt[k] << (16 * k);
-    }
-    const uint32_t incl = wave_incl_scan(packed, lane);
-    const uint32_t wave_tot = __shfl(incl, 63, 64);
-    const uint32_t excl = incl - packed;
-    if (lane == 0) {
-#pragma unroll
-      for (int k = 0; k < kCPW; ++k) s_cnt[wave * kCPW + k] = (wave_tot >> (16 * k)) & 0xffffu;
+  if (tile < a.n_tiles) {
+    const uint32_t cpw = a.cpw;
+    const uint32_t tile_chunk0 = tile * kWaves * cpw;
+    const uint32_t wave_chunk0 = tile_chunk0 + wave * cpw;
+    const LdsSink lds{stage_pos[wave], stage_val[wave]};
+    uint32_t wave_count = 0;
+    for (uint32_t c = 0; c < cpw; ++c) {
+      const uint32_t chunk = wave_chunk0 + c;
+      if (chunk >= a.n_chunks) break;
+      const uint64_t cbase = (uint64_t)chunk * kChunk;
+      const uint32_t cnt = cbase + kChunk <= a.n
+                               ? compress_chunk_bf16<true, true>(a, lut, park, cbase, lane, wave_count, lds)
+                               : compress_chunk_bf16<false, true>(a, lut, park, cbase, lane, wave_count, lds);
+      if (lane == 0) s_cnt[wave * cpw + c] = cnt;
+      wave_count += cnt;
     }
     __syncthreads();
 
-    // escapes of the chunks before this wave's first chunk, and of the whole tile
-    uint32_t before = 0, tile_tot = 0;
-#pragma unroll
-    for (int q = 0; q < (int)kTileChunks; ++q) {
-      const uint32_t c = s_cnt[q];
-      if (q < wave * kCPW) before += c;
-      tile_tot += c;
-    }
+    // exclusive offsets of the tile's chunks (lane q <-> chunk q of the tile) and the tile total
+    const uint32_t my = lane < (int)(kWaves * cpw) ? s_cnt[lane] : 0u;
+    const uint32_t incl = wave_incl_scan(my);
+    const uint32_t tile_tot = wave_last(incl);
+    const uint32_t chunk_excl = incl - my;
     if (wave == 0) {
       const uint32_t p = lookback(a.state, tile, tile_tot, lane, &a.ws_hdr[2]);
-      if (lane == 0) {
-        s_prefix = p;
-        s_next = ticket;
-      }
+      if (lane == 0) s_prefix = p;
     }
     __syncthreads();
     const uint32_t tile_prefix = s_prefix;
-    const uint32_t next_tile = s_next;
 
-    // chunk offsets
-    uint32_t* tab = reinterpret_cast<uint32_t*>(a.out + a.off_tab);
-    uint32_t chunk_prefix[kCPW];
-    {
-      uint32_t run = tile_prefix + before;
-#pragma unroll
-      for (int k = 0; k < kCPW; ++k) {
-        chunk_prefix[k] = run;
-        if (lane == 0 && chunk0 + k < a.n_chunks) tab[chunk0 + k] = run;
-        run += (wave_tot >> (16 * k)) & 0xffffu;
+    if (wave == 0) {
+      uint32_t* tab = reinterpret_cast<uint32_t*>(a.out + a.off_tab);
+      if (lane < (int)(kWaves * cpw) && tile_chunk0 + lane < a.n_chunks) tab[tile_chunk0 + lane] = tile_prefix + chunk_excl;
+      if (tile == a.n_tiles - 1 && lane == 0) {
+        // chunk_off[C] = M, then zero padding up to the 16-byte boundary
+        tab[a.n_chunks] = tile_prefix + tile_tot;
+        for (uint64_t i = a.n_chunks + 1; 4 * i < a16(4ull * (a.n_chunks + 1)); ++i) tab[i] = 0;
       }
     }
-    if (tile == a.n_tiles - 1 && tid == 0) {
-      // chunk_off[C] = M, then zero padding up to the 16-byte boundary
-      tab[a.n_chunks] = tile_prefix + tile_tot;
-      for (uint64_t i = a.n_chunks + 1; 4 * i < a16(4ull * (a.n_chunks + 1)); ++i) tab[i] = 0;
-    }
 
-    // escape records, in element order: lanes ascending, elements ascending inside a lane
-    uint16_t* pos_arr = reinterpret_cast<uint16_t*>(a.out + a.off_pos);
-#pragma unroll
-    for (int k = 0; k < kCPW; ++k) {
-      if (cnt[k]) {
-        uint64_t m = (uint64_t)F[k].x | ((uint64_t)F[k].y << 32);
-        uint32_t rank = chunk_prefix[k] + ((excl >> (16 * k)) & 0xffffu);
-        const uint64_t cbase = (uint64_t)(chunk0 + k) * kChunk;
-        while (m) {
-          const uint32_t j = (uint32_t)(__ffsll((unsigned long long)m) - 1) >> 2;
-          m &= m - 1;
-          const uint32_t pos = lane * kLaneElems + j;
-          const uint32_t x = reinterpret_cast<const uint16_t*>(a.in)[cbase + pos];
-          if (a.off_pos + 2ull * (rank + 1) <= a.capacity) pos_arr[rank] = (uint16_t)pos;
-          a.val_stage[rank] = (uint8_t)((x >> 7) & 0xffu);
-          ++rank;
-        }
+    // this wave's escape records go to their final rank
+    const uint32_t wave_base = tile_prefix + __shfl(chunk_excl, wave * cpw, 64);
+    if (wave_count <= kStageCap) {
+      const GlobalSink g{&a};
+      for (uint32_t i = lane; i < wave_count; i += 64) g.put(wave_base + i, stage_pos[wave][i], stage_val[wave][i]);
+    } else {
+      // more escapes than the staging holds: go over this wave's chunks again (their lines are
+      // still in cache) and write the records straight to their place
+      const GlobalSink g{&a};
+      uint32_t r = wave_base;
+      for (uint32_t c = 0; c < cpw; ++c) {
+        const uint32_t chunk = wave_chunk0 + c;
+        if (chunk >= a.n_chunks) break;
+        const uint64_t cbase = (uint64_t)chunk * kChunk;
+        r += cbase + kChunk <= a.n ? compress_chunk_bf16<true, false>(a, lut, park, cbase, lane, r, g)
+                                   : compress_chunk_bf16<false, false>(a, lut, park, cbase, lane, r, g);
       }
     }
-    tile = next_tile;
   }
 
-  // the last workgroup to get here finishes the stream
+  // the last workgroup to get here finishes the stream; every store of escape values has
+  // completed (vmcnt) before its workgroup is counted
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  if (tid == 0) {
-    __threadfence();
-    s_last = atomicAdd(&a.ws_hdr[1], 1u) == gridDim.x - 1 ? 1u : 0u;
-  }
+  if (tid == 0)
+    s_last = __hip_atomic_fetch_add(&a.ws_hdr[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gridDim.x - 1 ? 1u : 0u;
   __syncthreads();
-  if (s_last) {
-    __threadfence();
-    compress_finalize(a, tid);
-  }
+  if (s_last) compress_finalize(a, tid);
 }
 
 // ---------------------------------------------------------------------------
@@ -386,7 +423,7 @@ struct DecompressArgs {
   uint64_t n, comp_bytes;
   splitzip_sizes* sizes;   // nullable
   uint64_t off_tab, off_sm, off_code, off_pos, sm_bytes, code_bytes;
-  uint32_t n_chunks, n_tiles, dtype, pad;
+  uint32_t n_chunks, n_tiles, cpw, dtype;
   uint8_t dec[16];
 };
 
@@ -413,36 +450,44 @@ __device__ void decompress_check_header(const DecompressArgs& a, uint32_t M) {
   }
 }
 
+// dense decode of one chunk by one wave: two half-chunks, 8 elements per lane each
 template <bool FULL>
-__device__ inline void decompress_lane_chunk_bf16(const DecompressArgs& a, const uint32_t* tbl,
-                                                  uint64_t e0) {
-  uint4 sm = make_uint4(0, 0, 0, 0);
-  uint2 cd = make_uint2(0, 0);
-  if (FULL || e0 < a16(a.sm_bytes)) sm = *reinterpret_cast<const uint4*>(a.comp + a.off_sm + e0);
-  if (FULL || (e0 >> 1) < a16(a.code_bytes)) cd = *reinterpret_cast<const uint2*>(a.comp + a.off_code + (e0 >> 1));
-  const uint32_t smw[4] = {sm.x, sm.y, sm.z, sm.w};
-  const uint32_t cw[2] = {cd.x, cd.y};
-  uint32_t o[8];
+__device__ inline void decompress_chunk_bf16(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane) {
+  u32x2 sm[2];
+  uint32_t cd[2];
 #pragma unroll
-  for (int b = 0; b < 8; ++b) {
-    // code byte b -> both exponents already in place (bits 7..14 and 23..30)
-    const uint32_t cb = (cw[b >> 2] >> (8 * (b & 3))) & 0xffu;
-    // [a0, a0, a1, a1], then keep mantissa in the low and sign in the high byte of each half-word (eq. (2))
-    const uint32_t p = byte_perm(0u, smw[b >> 1], (b & 1) ? 0x03030202u : 0x01010000u);
-    o[b] = (p & 0x807f807fu) | tbl[cb];
+  for (int h = 0; h < 2; ++h) {
+    const uint64_t g0 = cbase + h * kHalf + lane * 8;
+    sm[h] = u32x2{0u, 0u};
+    cd[h] = 0;
+    if (FULL || g0 < a16(a.sm_bytes)) sm[h] = ld_stream(reinterpret_cast<const u32x2*>(a.comp + a.off_sm + g0));
+    if (FULL || (g0 >> 1) < a16(a.code_bytes))
+      cd[h] = ld_stream(reinterpret_cast<const uint32_t*>(a.comp + a.off_code + (g0 >> 1)));
   }
-  uint32_t nvalid = kLaneElems;
-  if (!FULL) nvalid = e0 >= a.n ? 0u : (uint32_t)(a.n - e0 < kLaneElems ? a.n - e0 : kLaneElems);
-  if (FULL || nvalid == kLaneElems) {
-    uint4* q = reinterpret_cast<uint4*>(a.out + 2 * e0);
-    q[0] = make_uint4(o[0], o[1], o[2], o[3]);
-    q[1] = make_uint4(o[4], o[5], o[6], o[7]);
-  } else {
-    uint16_t* q = reinterpret_cast<uint16_t*>(a.out) + e0;
 #pragma unroll
-    for (int d = 0; d < 8; ++d) {
-      if ((uint32_t)(2 * d) < nvalid) q[2 * d] = (uint16_t)o[d];
-      if ((uint32_t)(2 * d + 1) < nvalid) q[2 * d + 1] = (uint16_t)(o[d] >> 16);
+  for (int h = 0; h < 2; ++h) {
+    const uint64_t g0 = cbase + h * kHalf + lane * 8;
+    const uint32_t smw[2] = {sm[h].x, sm[h].y};
+    uint32_t o[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      // code byte b -> both exponents already in place (bits 7..14 and 23..30)
+      const uint32_t cb = (cd[h] >> (8 * b)) & 0xffu;
+      // [a0, a0, a1, a1], then keep mantissa in the low and sign in the high byte of each half-word (eq. (2))
+      const uint32_t p = byte_perm(0u, smw[b >> 1], (b & 1) ? 0x03030202u : 0x01010000u);
+      o[b] = (p & 0x807f807fu) | tbl[cb];
+    }
+    uint32_t nvalid = 8;
+    if (!FULL) nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 8 ? a.n - g0 : 8);
+    if (FULL || nvalid == 8) {
+      st_stream(reinterpret_cast<u32x4*>(a.out + 2 * g0), u32x4{o[0], o[1], o[2], o[3]});
+    } else {
+      uint16_t* q = reinterpret_cast<uint16_t*>(a.out) + g0;
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        if ((uint32_t)(2 * d) < nvalid) q[2 * d] = (uint16_t)o[d];
+        if ((uint32_t)(2 * d + 1) < nvalid) q[2 * d + 1] = (uint16_t)(o[d] >> 16);
+      }
     }
   }
 }
@@ -466,51 +511,36 @@ __global__ __launch_bounds__(kThreads) void decompress_bf16_kernel(const Decompr
   const uint8_t* val_arr = a.comp + off_val;
   __syncthreads();
 
-  for (uint32_t tile = blockIdx.x; tile < a.n_tiles; tile += gridDim.x) {
-    const uint64_t tile_e0 = (uint64_t)tile * kTileElems;
-    const uint32_t chunk0 = tile * kTileChunks + wave * kCPW;
-    const bool full = tile_e0 + kTileElems <= a.n;
-    uint32_t lo[kCPW], hi[kCPW];
-#pragma unroll
-    for (int k = 0; k < kCPW; ++k) {
-      lo[k] = hi[k] = 0;
-      if (chunk0 + k < a.n_chunks) {
-        lo[k] = tab[chunk0 + k];
-        hi[k] = tab[chunk0 + k + 1];
-      }
-    }
-    if (full) {
-#pragma unroll
-      for (int k = 0; k < kCPW; ++k)
-        decompress_lane_chunk_bf16<true>(a, tbl, (uint64_t)(chunk0 + k) * kChunk + lane * kLaneElems);
-    } else {
-#pragma unroll
-      for (int k = 0; k < kCPW; ++k)
-        decompress_lane_chunk_bf16<false>(a, tbl, (uint64_t)(chunk0 + k) * kChunk + lane * kLaneElems);
-    }
+  const uint32_t cpw = a.cpw;
+  const uint32_t wave_chunk0 = (blockIdx.x * kWaves + wave) * cpw;
+  for (uint32_t c = 0; c < cpw; ++c) {
+    const uint32_t chunk = wave_chunk0 + c;
+    if (chunk >= a.n_chunks) break;
+    const uint64_t cbase = (uint64_t)chunk * kChunk;
+    const uint32_t lo = tab[chunk], hi = tab[chunk + 1];
+    if (cbase + kChunk <= a.n)
+      decompress_chunk_bf16<true>(a, tbl, cbase, lane);
+    else
+      decompress_chunk_bf16<false>(a, tbl, cbase, lane);
     // sparse overwrite (the exponent field of x at every recorded position), by the wave that
     // wrote the chunk, once its dense stores have completed
-#pragma unroll
-    for (int k = 0; k < kCPW; ++k) {
-      if (hi[k] == lo[k]) continue;
-      const uint64_t cbase = (uint64_t)(chunk0 + k) * kChunk;
-      const uint32_t clen = (uint32_t)(a.n - cbase < kChunk ? a.n - cbase : kChunk);
-      if (hi[k] < lo[k] || hi[k] - lo[k] > clen || hi[k] > M) {
-        if (lane == 0) flag_bad(a);
+    if (hi == lo) continue;
+    const uint32_t clen = (uint32_t)(a.n - cbase < kChunk ? a.n - cbase : kChunk);
+    if (hi < lo || hi - lo > clen || hi > M) {
+      if (lane == 0) flag_bad(a);
+      continue;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    for (uint32_t j = lo + lane; j < hi; j += 64) {
+      const uint32_t pos = pos_arr[j];
+      const uint32_t val = val_arr[j];
+      if (pos >= clen) {
+        flag_bad(a);
         continue;
       }
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      for (uint32_t j = lo[k] + lane; j < hi[k]; j += 64) {
-        const uint32_t pos = pos_arr[j];
-        const uint32_t val = val_arr[j];
-        if (pos >= clen) {
-          flag_bad(a);
-          continue;
-        }
-        const uint32_t sa = a.comp[a.off_sm + cbase + pos];
-        reinterpret_cast<uint16_t*>(a.out)[cbase + pos] =
-            (uint16_t)(((sa & 0x80u) << 8) | (val << 7) | (sa & 0x7fu));
-      }
+      const uint32_t sa = a.comp[a.off_sm + cbase + pos];
+      reinterpret_cast<uint16_t*>(a.out)[cbase + pos] =
+          (uint16_t)(((sa & 0x80u) << 8) | (val << 7) | (sa & 0x7fu));
     }
   }
 }
@@ -524,19 +554,24 @@ __global__ void workspace_init_kernel(uint4* p, uint64_t nvec) {
     p[i] = make_uint4(0, 0, 0, 0);
 }
 
-// reads 64 bytes, writes 48 bytes per thread and step when the sizes are in the codec's 4:3 ratio
-__global__ __launch_bounds__(kThreads) void traffic_probe_kernel(const uint4* src, uint64_t nread,
-                                                                  uint4* dst, uint64_t nwrite) {
-  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
-  const uint64_t groups = (nread + 3) / 4;
-  for (uint64_t g = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; g < groups; g += stride) {
-    uint4 v[4];
+// Per step a workgroup reads four coalesced 4 KB runs and writes three: the codec's 4:3 traffic
+// without its arithmetic.
+__global__ __launch_bounds__(kThreads) void traffic_probe_kernel(const u32x4* src, uint64_t nread,
+                                                                  u32x4* dst, uint64_t nwrite) {
+  const uint64_t steps = (nread + 4 * kThreads - 1) / (4 * kThreads);
+  for (uint64_t s = blockIdx.x; s < steps; s += gridDim.x) {
+    u32x4 v[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) v[i] = 4 * g + i < nread ? src[4 * g + i] : make_uint4(0, 0, 0, 0);
+    for (int i = 0; i < 4; ++i) {
+      const uint64_t idx = (4 * s + i) * kThreads + threadIdx.x;
+      v[i] = idx < nread ? ld_stream(src + idx) : u32x4{0u, 0u, 0u, 0u};
+    }
     v[0].x ^= v[3].x; v[1].y ^= v[3].y; v[2].z ^= v[3].z; v[0].w ^= v[3].w;
 #pragma unroll
-    for (int i = 0; i < 3; ++i)
-      if (3 * g + i < nwrite) dst[3 * g + i] = v[i];
+    for (int i = 0; i < 3; ++i) {
+      const uint64_t idx = (3 * s + i) * kThreads + threadIdx.x;
+      if (idx < nwrite) st_stream(dst + idx, v[i]);
+    }
   }
 }
 
@@ -565,6 +600,20 @@ int cu_count() {
     cached[dev] = n;
   }
   return cached[dev];
+}
+
+// most tiles a call of n elements can have (cpw = 1); sizes the look-back state in the workspace
+uint64_t max_tiles(uint64_t n) {
+  const uint64_t chunks = (n + kChunk - 1) / kChunk;
+  return (chunks + kMinTileChunks - 1) / kMinTileChunks;
+}
+
+// chunks per wave: the largest power of two (up to `most`) that still leaves `want` tiles per CU
+uint32_t pick_cpw(uint64_t n_chunks, uint32_t most, uint32_t want_tiles_per_cu) {
+  const uint64_t want = (uint64_t)cu_count() * want_tiles_per_cu;
+  uint32_t cpw = most;
+  while (cpw > 1 && (n_chunks + (uint64_t)kWaves * cpw - 1) / (kWaves * cpw) < want) cpw >>= 1;
+  return cpw;
 }
 
 // tables must describe one bijection between 16 codes and 16 distinct exponents
@@ -654,8 +703,7 @@ size_t splitzip_compress_bound(uint64_t n_elems, int dtype) { return splitzip_to
 
 size_t splitzip_workspace_bytes(uint64_t n_elems, int dtype) {
   if (!dtype_ok(dtype) || n_elems >> 32) return 0;
-  const Layout L = make_layout(n_elems, dtype);
-  return (size_t)(kWsHeaderBytes + a256(8 * L.n_tiles) + a256(n_elems));
+  return (size_t)(kWsHeaderBytes + a256(8 * max_tiles(n_elems)) + a256(n_elems));
 }
 
 int splitzip_workspace_init(void* d_workspace, size_t workspace_bytes, void* stream) {
@@ -691,20 +739,22 @@ int splitzip_compress(const void* d_in, uint64_t n_elems, int dtype, const split
   uint8_t* ws = static_cast<uint8_t*>(d_workspace);
   a.ws_hdr = reinterpret_cast<uint32_t*>(ws);
   a.state = reinterpret_cast<uint64_t*>(ws + kWsHeaderBytes);
-  a.val_stage = ws + kWsHeaderBytes + a256(8 * L.n_tiles);
+  a.val_stage = ws + kWsHeaderBytes + a256(8 * max_tiles(n_elems));
   a.sizes = d_sizes;
   a.off_tab = L.off_tab; a.off_sm = L.off_sm; a.off_code = L.off_code; a.off_pos = L.off_pos;
   a.sm_bytes = L.sm_bytes; a.code_bytes = L.code_bytes;
-  a.n_chunks = (uint32_t)L.n_chunks; a.n_tiles = (uint32_t)L.n_tiles; a.dtype = (uint32_t)dtype;
+  static const int cpw_env = env_int("SPLITZIP_COMPRESS_CPW", 0);
+  static const int tiles_per_cu = env_int("SPLITZIP_COMPRESS_TILES_PER_CU", 4);
+  a.cpw = cpw_env ? (uint32_t)cpw_env : pick_cpw(L.n_chunks, 8, (uint32_t)tiles_per_cu);
+  if (a.cpw > kMaxCpw) a.cpw = kMaxCpw;
+  a.n_chunks = (uint32_t)L.n_chunks;
+  a.n_tiles = (uint32_t)((L.n_chunks + (uint64_t)kWaves * a.cpw - 1) / (kWaves * a.cpw));
+  a.dtype = (uint32_t)dtype;
   memcpy(a.dec, cb->dec, 16);
   for (unsigned v = 0; v < 256; ++v) a.lut[v] = cb->member[v] ? cb->enc[v] : 0x100u;
 
-  static const int wgs_per_cu = env_int("SPLITZIP_COMPRESS_WGS_PER_CU", 4);
-  uint64_t grid = (uint64_t)cu_count() * wgs_per_cu;
-  if (grid > L.n_tiles) grid = L.n_tiles;
-  if (grid < 1) grid = 1;
-  hipLaunchKernelGGL(compress_bf16_kernel, dim3((unsigned)grid), dim3(kThreads), 0,
-                     static_cast<hipStream_t>(stream), a);
+  const unsigned grid = a.n_tiles ? a.n_tiles : 1u;
+  hipLaunchKernelGGL(compress_bf16_kernel, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
   return hipGetLastError() == hipSuccess ? SPLITZIP_OK : SPLITZIP_ERR_HIP;
 }
 
@@ -728,15 +778,17 @@ int splitzip_decompress(const void* d_comp, size_t comp_bytes, uint64_t n_elems,
   a.sizes = d_sizes;
   a.off_tab = L.off_tab; a.off_sm = L.off_sm; a.off_code = L.off_code; a.off_pos = L.off_pos;
   a.sm_bytes = L.sm_bytes; a.code_bytes = L.code_bytes;
-  a.n_chunks = (uint32_t)L.n_chunks; a.n_tiles = (uint32_t)L.n_tiles; a.dtype = (uint32_t)dtype;
+  static const int cpw_env = env_int("SPLITZIP_DECOMPRESS_CPW", 0);
+  static const int tiles_per_cu = env_int("SPLITZIP_DECOMPRESS_TILES_PER_CU", 8);
+  a.cpw = cpw_env ? (uint32_t)cpw_env : pick_cpw(L.n_chunks, 4, (uint32_t)tiles_per_cu);
+  if (a.cpw > kMaxCpw) a.cpw = kMaxCpw;
+  a.n_chunks = (uint32_t)L.n_chunks;
+  a.n_tiles = (uint32_t)((L.n_chunks + (uint64_t)kWaves * a.cpw - 1) / (kWaves * a.cpw));
+  a.dtype = (uint32_t)dtype;
   memcpy(a.dec, cb->dec, 16);
 
-  static const int wgs_per_cu = env_int("SPLITZIP_DECOMPRESS_WGS_PER_CU", 8);
-  uint64_t grid = (uint64_t)cu_count() * wgs_per_cu;
-  if (grid > L.n_tiles) grid = L.n_tiles;
-  if (grid < 1) grid = 1;
-  hipLaunchKernelGGL(decompress_bf16_kernel, dim3((unsigned)grid), dim3(kThreads), 0,
-                     static_cast<hipStream_t>(stream), a);
+  const unsigned grid = a.n_tiles ? a.n_tiles : 1u;
+  hipLaunchKernelGGL(decompress_bf16_kernel, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
   return hipGetLastError() == hipSuccess ? SPLITZIP_OK : SPLITZIP_ERR_HIP;
 }
 
@@ -747,11 +799,11 @@ int splitzip_traffic_probe(const void* d_src, size_t read_bytes, void* d_dst, si
   if (!nread) return SPLITZIP_OK;
   static const int wgs_per_cu = env_int("SPLITZIP_PROBE_WGS_PER_CU", 8);
   uint64_t grid = (uint64_t)cu_count() * wgs_per_cu;
-  const uint64_t need = (nread / 4 + kThreads - 1) / kThreads;
+  const uint64_t need = (nread + 4 * kThreads - 1) / (4 * kThreads);
   if (grid > need) grid = need;
   if (grid < 1) grid = 1;
   hipLaunchKernelGGL(traffic_probe_kernel, dim3((unsigned)grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
-                     static_cast<const uint4*>(d_src), nread, static_cast<uint4*>(d_dst), nwrite);
+                     static_cast<const u32x4*>(d_src), nread, static_cast<u32x4*>(d_dst), nwrite);
   return hipGetLastError() == hipSuccess ? SPLITZIP_OK : SPLITZIP_ERR_HIP;
 }
 
