@@ -1,23 +1,31 @@
 // SplitZip codec for MI355X (gfx950): HIP kernels and the C ABI of include/splitzip.h.
 //
-// One compress call is ONE kernel launch.  The dense transform (paper section
-// 3.2 eq. (1), encode table, nibble pack, sign+mantissa plane) is fused with
-// escape detection, per-chunk counting and the position-ordered compaction of
-// the escape stream (appendix A fuses only the counting).  The input is read
-// exactly once: escapes are staged in LDS while their words are in registers,
-// and the cross-workgroup offsets come from a decoupled look-back scan over
-// per-tile escape counts, so the output does not depend on scheduling.
+// One compress call is ONE kernel launch (tensors of up to 64 Mi elements or
+// so; larger ones take one launch per segment and a small finishing launch).
+// The dense transform (paper section 3.2 eq. (1), encode table, nibble pack,
+// sign+mantissa plane) is fused with escape detection, per-chunk counting and
+// the position-ordered compaction of the escape stream (appendix A fuses only
+// the counting).  The input is read exactly once: escapes are staged in LDS
+// while their words are in registers.  The launch is a persistent grid that
+// fits the chip; every workgroup owns one contiguous range of chunks, and the
+// one cross-workgroup step is a flat exchange of the per-range escape counts
+// through one word per workgroup: each workgroup publishes its count, reads
+// everybody's, and then knows both its own offset (counts of the ranges before
+// it) and M, so positions, values and the offset table go straight to their
+// final place.  No atomic read-modify-write is used: on this chip every
+// device-wide atomic on one address costs about 12 ns, serialised.
 // One decompress call is ONE kernel launch as well: nibble unpack, decode
 // table, eq. (2), and the sparse overwrite done by the wave that owns the
 // chunk once its own dense stores have completed.
 //
-// Work decomposition (wavefront = 64 lanes, workgroup = 4 waves):
+// Work decomposition (wavefront = 64 lanes):
 //   chunk = 1024 elements (the escape-position granule), owned by one wave and
 //           processed as two half-chunks of 512 elements; in a half-chunk lane
 //           l owns elements [8 l, 8 l + 8): every global access of a wave is
 //           one fully coalesced run (16, 8 or 4 bytes per lane).
-//   tile  = 4 waves x cpw consecutive chunks each, one tile per workgroup;
-//           cpw (1..16) is chosen per call so that the grid fills the chip.
+//   compress: the chunks of a workgroup's range are dealt round-robin to its
+//           waves, so a workgroup reads one moving window.
+//   decompress: one workgroup per tile of 4 waves x cpw chunks.
 // All plane traffic uses non-temporal loads / stores: nothing is re-used.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -34,13 +42,15 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr uint32_t kChunk = 1024;
 constexpr uint32_t kHalf = 512;
 constexpr uint32_t kHeaderBytes = 64;
-constexpr int kThreads = 256;
+constexpr int kThreads = 256;                             // decompress / helper kernels
 constexpr int kWaves = kThreads / 64;
-constexpr uint32_t kMaxCpw = 16;                          // chunks per wave per tile, at most
-constexpr uint32_t kMinTileChunks = kWaves;               // smallest tile (cpw = 1)
+constexpr uint32_t kMaxCpw = 16;                          // decompress: chunks per wave per tile, at most
+constexpr uint32_t kMaxRange = 256;                       // compress: chunks per workgroup per launch, at most
+constexpr uint32_t kMaxWorkgroups = 4096;                 // compress: words of exchange state in the workspace
 constexpr uint32_t kStageCap = 512;                       // escapes a wave can stage in LDS
-constexpr uint32_t kWsHeaderBytes = 64;                   // ticket, done, flags
-constexpr uint32_t kSpinLimit = 1u << 22;                 // look-back polls before giving up
+constexpr uint32_t kWsHeaderBytes = 64;                   // epoch, running escape count, error flags
+constexpr uint32_t kSegFirst = 1u, kSegLast = 2u;         // CompressArgs.flags
+constexpr uint64_t kSpinTicks = 200000000ull;             // 2 s of the 100 MHz wall clock
 
 __host__ __device__ inline uint64_t a16(uint64_t x) { return (x + 15u) & ~(uint64_t)15u; }
 __host__ __device__ inline uint64_t a256(uint64_t x) { return (x + 255u) & ~(uint64_t)255u; }
@@ -97,51 +107,6 @@ __device__ inline void st_agent(T* p, T v) { __hip_atomic_store(p, v, __ATOMIC_R
 template <typename T>
 __device__ inline T ld_agent(const T* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
-// tile state of the decoupled look-back scan: flag in the two top bits, count below
-constexpr uint64_t kFlagAgg = 1ull << 62;   // value = escapes of this tile only
-constexpr uint64_t kFlagInc = 2ull << 62;   // value = escapes of all tiles up to and including this one
-
-// Run by one whole wave.  Publishes this tile's escape count, sums the counts
-// of all earlier tiles (64 predecessors per poll) and publishes the inclusive
-// total.  Flag and count share one 64-bit word, so relaxed accesses suffice.
-// Tiles are handed out by a ticket counter: every tile a wave waits for belongs
-// to a workgroup that is already running and that publishes its count without
-// waiting for anyone, so the wait always ends; the poll limit only guards
-// against a workspace that was never initialised.
-__device__ inline uint32_t lookback(uint64_t* state, uint32_t tile, uint32_t agg, int lane,
-                                    uint32_t* ws_flags) {
-  if (tile == 0) {
-    if (lane == 0) st_agent(&state[0], kFlagInc | (uint64_t)agg);
-    return 0;
-  }
-  if (lane == 0) st_agent(&state[tile], kFlagAgg | (uint64_t)agg);
-  uint32_t prefix = 0;
-  int64_t base = (int64_t)tile - 1;
-  uint32_t spins = 0;
-  for (;;) {
-    const int64_t idx = base - lane;
-    const uint64_t s = idx >= 0 ? ld_agent(&state[idx]) : kFlagInc;  // before tile 0: inclusive 0
-    const uint32_t flag = (uint32_t)(s >> 62);
-    const uint64_t inc_mask = __ballot(flag == 2u);
-    const uint64_t empty_mask = __ballot(flag == 0u);
-    const int first_inc = inc_mask ? (__ffsll((unsigned long long)inc_mask) - 1) : 64;
-    const uint64_t need = first_inc >= 63 ? ~0ull : ((2ull << first_inc) - 1ull);
-    if (empty_mask & need) {
-      if (++spins > kSpinLimit) {
-        if (lane == 0) atomicOr(ws_flags, SPLITZIP_STATUS_INTERNAL);
-        break;
-      }
-      __builtin_amdgcn_s_sleep(1);
-      continue;
-    }
-    prefix += wave_last(wave_incl_scan(lane <= first_inc ? (uint32_t)s : 0u));
-    if (first_inc < 64) break;
-    base -= 64;
-  }
-  if (lane == 0) st_agent(&state[tile], kFlagInc | (uint64_t)(prefix + agg));
-  return prefix;
-}
-
 // ---------------------------------------------------------------------------
 // compress
 // ---------------------------------------------------------------------------
@@ -150,17 +115,21 @@ struct CompressArgs {
   const uint8_t* in;
   uint8_t* out;
   uint64_t n, capacity;
-  uint32_t* ws_hdr;      // [0] ticket, [1] done, [2] flags
-  uint64_t* state;       // n_tiles look-back words
-  uint8_t* val_stage;    // n bytes: escape values until M is known
+  uint32_t* ws_hdr;      // [0] epoch of this launch, [1] escapes of the earlier segments, [2] sticky error flags
+  uint64_t* state;       // one word per workgroup: epoch << 32 | escapes in its range
+  uint8_t* val_stage;    // n bytes: escape values of a call of several launches, until M is known
   splitzip_sizes* sizes;
-  uint64_t off_tab, off_sm, off_code, off_pos, sm_bytes, code_bytes;
-  uint32_t n_chunks, n_tiles, cpw, dtype;
+  uint64_t off_tab, off_sm, off_code, off_pos, sm_bytes, code_bytes, spin_ticks;
+  uint32_t n_chunks;     // of the whole tensor
+  uint32_t seg_chunk0, seg_chunks;   // the chunks this launch covers
+  uint32_t flags;        // kSegFirst | kSegLast
+  uint32_t dtype;
+  uint32_t expect_wgs;   // workgroups whose counts are awaited (= the grid size)
   uint8_t dec[16];
   uint16_t lut[256];     // exponent -> code | (non-member ? 0x100 : 0)   (the "marked" table of appendix A)
 };
 
-// where a chunk's escape records go: LDS staging (first pass) or their final place (second pass)
+// where a chunk's escape records go: LDS staging (first pass) or their final place
 struct LdsSink {
   uint16_t* pos;
   uint8_t* val;
@@ -172,10 +141,12 @@ struct LdsSink {
   }
 };
 struct GlobalSink {
-  const CompressArgs* a;
+  uint16_t* pos;
+  uint8_t* val;
+  uint64_t pos_room, val_room;   // records that fit below the capacity
   __device__ inline void put(uint32_t r, uint32_t p, uint32_t e) const {
-    if (a->off_pos + 2ull * (r + 1) <= a->capacity) reinterpret_cast<uint16_t*>(a->out + a->off_pos)[r] = (uint16_t)p;
-    st_agent(a->val_stage + r, (uint8_t)e);
+    if (r < pos_room) pos[r] = (uint16_t)p;
+    if (r < val_room) val[r] = (uint8_t)e;
   }
 };
 
@@ -280,27 +251,17 @@ __device__ inline uint32_t compress_chunk_bf16(const CompressArgs& a, const uint
   return total;
 }
 
-// Last workgroup to finish: M is known now.  Moves the staged escape values
-// behind the position array, writes pads, header and sizes, and leaves the
-// workspace zeroed for the next call.  The staged values were written with
-// agent-scope stores that had completed before their workgroup signalled, and
-// are read with agent-scope loads.
-__device__ void compress_finalize(const CompressArgs& a, int tid) {
-  const uint32_t M = a.n_tiles ? (uint32_t)ld_agent(&a.state[a.n_tiles - 1]) : 0u;
+// header, sizes record and the zero padding behind the positions: one wave, once M is known
+__device__ void compress_write_trailer(const CompressArgs& a, uint32_t M, uint32_t err_flags, int lane) {
   const uint64_t off_val = a.off_pos + a16(2ull * M);
   const uint64_t total = off_val + M;
-  const uint64_t nvec = M / 8;
-  const uint64_t* src = reinterpret_cast<const uint64_t*>(a.val_stage);
-  uint64_t* dst = reinterpret_cast<uint64_t*>(a.out + off_val);
-  for (uint64_t i = tid; i < nvec; i += kThreads)
-    if (off_val + 8 * (i + 1) <= a.capacity) dst[i] = ld_agent(src + i);
-  for (uint64_t i = nvec * 8 + tid; i < M; i += kThreads)
-    if (off_val + i < a.capacity) a.out[off_val + i] = ld_agent(a.val_stage + i);
-  for (uint64_t i = 2ull * M + tid; i < a16(2ull * M); i += kThreads)
+  for (uint64_t i = 2ull * M + lane; i < a16(2ull * M); i += 64)
     if (a.off_pos + i < a.capacity) a.out[a.off_pos + i] = 0;
-  if (a.n_tiles == 0 && tid < 4) reinterpret_cast<uint32_t*>(a.out + a.off_tab)[tid] = 0;  // chunk_off[0] + pad
-  for (uint32_t i = tid; i < a.n_tiles; i += kThreads) st_agent(&a.state[i], (uint64_t)0);
-  if (tid == 0) {
+  if (lane == 0) {
+    uint32_t* tab = reinterpret_cast<uint32_t*>(a.out + a.off_tab);
+    // chunk_off[C] = M, then zero padding up to the 16-byte boundary
+    tab[a.n_chunks] = M;
+    for (uint64_t i = (uint64_t)a.n_chunks + 1; 4 * i < a16(4ull * ((uint64_t)a.n_chunks + 1)); ++i) tab[i] = 0;
     uint32_t h[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) h[i] = 0;
@@ -316,101 +277,182 @@ __device__ void compress_finalize(const CompressArgs& a, int tid) {
     uint4* ho = reinterpret_cast<uint4*>(a.out);
 #pragma unroll
     for (int i = 0; i < 4; ++i) ho[i] = make_uint4(h[4 * i], h[4 * i + 1], h[4 * i + 2], h[4 * i + 3]);
-    const uint32_t flags = ld_agent(&a.ws_hdr[2]);
     a.sizes->total_bytes = total;
     a.sizes->n_escapes = M;
-    a.sizes->status = (total > a.capacity ? SPLITZIP_STATUS_OVERFLOW : 0u) | flags;
+    a.sizes->status = (total > a.capacity ? SPLITZIP_STATUS_OVERFLOW : 0u) | err_flags;
     a.sizes->reserved = 0;
-    st_agent(&a.ws_hdr[0], 0u);
-    st_agent(&a.ws_hdr[1], 0u);
-    st_agent(&a.ws_hdr[2], 0u);
   }
 }
 
-__global__ __launch_bounds__(kThreads) void compress_bf16_kernel(const CompressArgs a) {
+// One launch covers the chunks [seg_chunk0, seg_chunk0 + seg_chunks) with a grid in which every
+// workgroup is resident at the same time.  Workgroup b owns a contiguous range of at most
+// kMaxRange chunks.  After its dense pass it publishes the escape count of its range in state[b]
+// (tagged with the launch's epoch, so that the words never need clearing) and reads the words of
+// all workgroups: the counts before b give its offset, all of them give M.  The wait ends when
+// the slowest workgroup has published; it is bounded by spin_ticks of the wall clock, after which
+// the launch gives up with SPLITZIP_STATUS_INTERNAL instead of hanging.
+template <int T>
+__global__ __launch_bounds__(T) void compress_bf16_kernel(const CompressArgs a) {
+  constexpr int NW = T / 64;
+  static_assert(T >= (int)kMaxRange && NW <= 16, "the range scan uses one thread per chunk");
   __shared__ uint16_t lut[256];
-  __shared__ uint16_t stage_pos[kWaves][kStageCap];
-  __shared__ uint8_t stage_val[kWaves][kStageCap];
-  __shared__ uint32_t s_cnt[kWaves * kMaxCpw];
-  __shared__ u32x4 s_park[kThreads];
-  __shared__ uint32_t s_tile, s_prefix, s_last;
+  __shared__ uint16_t stage_pos[NW][kStageCap];
+  __shared__ uint8_t stage_val[NW][kStageCap];
+  __shared__ uint32_t s_off[kMaxRange + 1];
+  __shared__ u32x4 s_park[T];
+  __shared__ uint32_t s_red[3][16];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const uint32_t W = a.expect_wgs, b = blockIdx.x;
   uint32_t* park = reinterpret_cast<uint32_t*>(&s_park[tid]);
 
-  lut[tid] = a.lut[tid];
-  if (tid < (int)(kWaves * kMaxCpw)) s_cnt[tid] = 0;
-  if (tid == 0) s_tile = a.n_tiles ? __hip_atomic_fetch_add(&a.ws_hdr[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+  if (tid < 256) lut[tid] = a.lut[tid];
+  const uint32_t epoch = ld_agent(&a.ws_hdr[0]);
+  const uint32_t base = (a.flags & kSegFirst) ? 0u : ld_agent(&a.ws_hdr[1]);
   __syncthreads();
-  const uint32_t tile = s_tile;
 
-  if (tile < a.n_tiles) {
-    const uint32_t cpw = a.cpw;
-    const uint32_t tile_chunk0 = tile * kWaves * cpw;
-    const uint32_t wave_chunk0 = tile_chunk0 + wave * cpw;
-    const LdsSink lds{stage_pos[wave], stage_val[wave]};
-    uint32_t wave_count = 0;
-    for (uint32_t c = 0; c < cpw; ++c) {
-      const uint32_t chunk = wave_chunk0 + c;
-      if (chunk >= a.n_chunks) break;
-      const uint64_t cbase = (uint64_t)chunk * kChunk;
-      const uint32_t cnt = cbase + kChunk <= a.n
-                               ? compress_chunk_bf16<true, true>(a, lut, park, cbase, lane, wave_count, lds)
-                               : compress_chunk_bf16<false, true>(a, lut, park, cbase, lane, wave_count, lds);
-      if (lane == 0) s_cnt[wave * cpw + c] = cnt;
-      wave_count += cnt;
-    }
-    __syncthreads();
+  // this workgroup's range: seg_chunks dealt evenly, the first `rem` workgroups get one more
+  const uint32_t per = a.seg_chunks / gridDim.x, rem = a.seg_chunks % gridDim.x;
+  const uint32_t nb = per + (b < rem ? 1u : 0u);
+  const uint32_t r0 = a.seg_chunk0 + b * per + (b < rem ? b : rem);
 
-    // exclusive offsets of the tile's chunks (lane q <-> chunk q of the tile) and the tile total
-    const uint32_t my = lane < (int)(kWaves * cpw) ? s_cnt[lane] : 0u;
-    const uint32_t incl = wave_incl_scan(my);
-    const uint32_t tile_tot = wave_last(incl);
-    const uint32_t chunk_excl = incl - my;
-    if (wave == 0) {
-      const uint32_t p = lookback(a.state, tile, tile_tot, lane, &a.ws_hdr[2]);
-      if (lane == 0) s_prefix = p;
-    }
-    __syncthreads();
-    const uint32_t tile_prefix = s_prefix;
+  const LdsSink lds{stage_pos[wave], stage_val[wave]};
+  uint32_t wave_count = 0;
+  for (uint32_t k = wave; k < nb; k += NW) {
+    const uint64_t cbase = (uint64_t)(r0 + k) * kChunk;
+    const uint32_t cnt = cbase + kChunk <= a.n
+                             ? compress_chunk_bf16<true, true>(a, lut, park, cbase, lane, wave_count, lds)
+                             : compress_chunk_bf16<false, true>(a, lut, park, cbase, lane, wave_count, lds);
+    if (lane == 0) s_off[k] = cnt;
+    wave_count += cnt;
+  }
+  __syncthreads();
 
-    if (wave == 0) {
-      uint32_t* tab = reinterpret_cast<uint32_t*>(a.out + a.off_tab);
-      if (lane < (int)(kWaves * cpw) && tile_chunk0 + lane < a.n_chunks) tab[tile_chunk0 + lane] = tile_prefix + chunk_excl;
-      if (tile == a.n_tiles - 1 && lane == 0) {
-        // chunk_off[C] = M, then zero padding up to the 16-byte boundary
-        tab[a.n_chunks] = tile_prefix + tile_tot;
-        for (uint64_t i = a.n_chunks + 1; 4 * i < a16(4ull * (a.n_chunks + 1)); ++i) tab[i] = 0;
-      }
-    }
-
-    // this wave's escape records go to their final rank
-    const uint32_t wave_base = tile_prefix + __shfl(chunk_excl, wave * cpw, 64);
-    if (wave_count <= kStageCap) {
-      const GlobalSink g{&a};
-      for (uint32_t i = lane; i < wave_count; i += 64) g.put(wave_base + i, stage_pos[wave][i], stage_val[wave][i]);
-    } else {
-      // more escapes than the staging holds: go over this wave's chunks again (their lines are
-      // still in cache) and write the records straight to their place
-      const GlobalSink g{&a};
-      uint32_t r = wave_base;
-      for (uint32_t c = 0; c < cpw; ++c) {
-        const uint32_t chunk = wave_chunk0 + c;
-        if (chunk >= a.n_chunks) break;
-        const uint64_t cbase = (uint64_t)chunk * kChunk;
-        r += cbase + kChunk <= a.n ? compress_chunk_bf16<true, false>(a, lut, park, cbase, lane, r, g)
-                                   : compress_chunk_bf16<false, false>(a, lut, park, cbase, lane, r, g);
-      }
-    }
+  // exclusive offsets of the range's chunks (thread q <-> chunk q) and the range total
+  const uint32_t my = (uint32_t)tid < nb ? s_off[tid] : 0u;
+  const uint32_t incl = wave_incl_scan(my);
+  if (lane == 63) s_red[0][wave] = incl;
+  __syncthreads();
+  uint32_t wave_off = 0, agg = 0;
+#pragma unroll
+  for (int j = 0; j < NW; ++j) {
+    const uint32_t t = s_red[0][j];
+    wave_off += j < wave ? t : 0u;
+    agg += t;
+  }
+  if ((uint32_t)tid < nb) s_off[tid] = wave_off + incl - my;
+  if (tid == 0) {
+    s_off[nb] = agg;
+    st_agent(&a.state[b], ((uint64_t)epoch << 32) | agg);
   }
 
-  // the last workgroup to get here finishes the stream; every store of escape values has
-  // completed (vmcnt) before its workgroup is counted
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  // the exchange: wait until every workgroup's word carries this launch's epoch
+  uint32_t lower = 0, all = 0;
+  bool timed_out = false;
+  const uint64_t t0 = wall_clock64();
+  for (;;) {
+    uint32_t lo = 0, al = 0;
+    int ready = 1;
+    for (uint32_t i = tid; i < W; i += T) {
+      const uint64_t s = ld_agent(&a.state[i]);
+      if ((uint32_t)(s >> 32) != epoch) ready = 0;
+      al += (uint32_t)s;
+      lo += i < b ? (uint32_t)s : 0u;
+    }
+    if (__syncthreads_and(ready)) {
+      lower = lo;
+      all = al;
+      break;
+    }
+    const int expired = tid == 0 && (uint64_t)(wall_clock64() - t0) > a.spin_ticks;
+    if (__syncthreads_or(expired)) {
+      timed_out = true;
+      break;
+    }
+    __builtin_amdgcn_s_sleep(2);
+  }
+  lower = wave_last(wave_incl_scan(lower));
+  all = wave_last(wave_incl_scan(all));
+  if (lane == 0) {
+    s_red[1][wave] = lower;
+    s_red[2][wave] = all;
+  }
   __syncthreads();
-  if (tid == 0)
-    s_last = __hip_atomic_fetch_add(&a.ws_hdr[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gridDim.x - 1 ? 1u : 0u;
-  __syncthreads();
-  if (s_last) compress_finalize(a, tid);
+  lower = 0;
+  all = 0;
+#pragma unroll
+  for (int j = 0; j < NW; ++j) {
+    lower += s_red[1][j];
+    all += s_red[2][j];
+  }
+  const uint32_t prefix = base + lower, M = base + all;
+  const bool single = (a.flags & (kSegFirst | kSegLast)) == (kSegFirst | kSegLast);
+
+  if (!timed_out) {
+    uint32_t* tab = reinterpret_cast<uint32_t*>(a.out + a.off_tab);
+    if ((uint32_t)tid < nb) tab[r0 + tid] = prefix + s_off[tid];
+
+    // escape records to their final rank; values go behind the positions when M is final
+    const uint64_t off_val = a.off_pos + a16(2ull * M);
+    GlobalSink g;
+    g.pos = reinterpret_cast<uint16_t*>(a.out + a.off_pos);
+    g.pos_room = a.capacity > a.off_pos ? (a.capacity - a.off_pos) / 2 : 0;
+    g.val = single ? a.out + off_val : a.val_stage;
+    g.val_room = single ? (a.capacity > off_val ? a.capacity - off_val : 0) : ~0ull;
+    if (wave_count <= kStageCap) {
+      uint32_t woff = 0;
+      for (uint32_t k = wave; k < nb; k += NW) {
+        const uint32_t lo = s_off[k], c = s_off[k + 1] - lo;
+        for (uint32_t i = lane; i < c; i += 64) g.put(prefix + lo + i, stage_pos[wave][woff + i], stage_val[wave][woff + i]);
+        woff += c;
+      }
+    } else {
+      // more escapes than the staging holds: go over this wave's chunks again and write the
+      // records straight to their place
+      for (uint32_t k = wave; k < nb; k += NW) {
+        const uint64_t cbase = (uint64_t)(r0 + k) * kChunk;
+        const uint32_t r = prefix + s_off[k];
+        if (cbase + kChunk <= a.n) compress_chunk_bf16<true, false>(a, lut, park, cbase, lane, r, g);
+        else compress_chunk_bf16<false, false>(a, lut, park, cbase, lane, r, g);
+      }
+    }
+  } else if (tid == 0) {
+    __hip_atomic_fetch_or(&a.ws_hdr[2], (uint32_t)SPLITZIP_STATUS_INTERNAL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+
+  // workgroup 0 closes the launch: it left the exchange, so every workgroup has read the epoch
+  if (b == 0 && wave == 0) {
+    uint32_t err = 0;
+    if (lane == 0) {
+      err = ld_agent(&a.ws_hdr[2]) | (timed_out ? (uint32_t)SPLITZIP_STATUS_INTERNAL : 0u);
+      st_agent(&a.ws_hdr[0], epoch + 1u ? epoch + 1u : 1u);
+      st_agent(&a.ws_hdr[1], M);
+      st_agent(&a.ws_hdr[2], single ? 0u : err);   // a call of several launches reports in its finishing launch
+    }
+    if (single) compress_write_trailer(a, M, err, lane);
+  }
+}
+
+// Last launch of a call that took several: M is known now.  Moves the staged escape values
+// behind the position array and writes the trailer.
+__global__ __launch_bounds__(kThreads) void compress_finish_kernel(const CompressArgs a) {
+  const uint32_t M = ld_agent(&a.ws_hdr[1]);
+  const uint64_t off_val = a.off_pos + a16(2ull * M);
+  const uint64_t room = a.capacity > off_val ? a.capacity - off_val : 0;
+  const uint64_t m = M < room ? M : room;
+  const uint64_t nvec = m / 16;
+  const u32x4* src = reinterpret_cast<const u32x4*>(a.val_stage);
+  u32x4* dst = reinterpret_cast<u32x4*>(a.out + off_val);
+  const uint64_t gtid = blockIdx.x * (uint64_t)kThreads + threadIdx.x, gsz = (uint64_t)gridDim.x * kThreads;
+  for (uint64_t i = gtid; i < nvec; i += gsz) dst[i] = src[i];
+  for (uint64_t i = nvec * 16 + gtid; i < m; i += gsz) a.out[off_val + i] = a.val_stage[i];
+  if (blockIdx.x == 0 && threadIdx.x < 64) {
+    uint32_t err = 0;
+    if (threadIdx.x == 0) {
+      err = ld_agent(&a.ws_hdr[2]);
+      st_agent(&a.ws_hdr[2], 0u);
+    }
+    compress_write_trailer(a, M, err, threadIdx.x);
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -549,9 +591,8 @@ __global__ __launch_bounds__(kThreads) void decompress_bf16_kernel(const Decompr
 // small kernels
 // ---------------------------------------------------------------------------
 
-__global__ void workspace_init_kernel(uint4* p, uint64_t nvec) {
-  for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < nvec; i += (uint64_t)gridDim.x * blockDim.x)
-    p[i] = make_uint4(0, 0, 0, 0);
+__global__ void workspace_init_kernel(uint32_t* p, uint32_t nwords) {
+  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < nwords; i += gridDim.x * blockDim.x) p[i] = i == 0 ? 1u : 0u;
 }
 
 // Per step a workgroup reads four coalesced 4 KB runs and writes three: the codec's 4:3 traffic
@@ -602,12 +643,6 @@ int cu_count() {
   return cached[dev];
 }
 
-// most tiles a call of n elements can have (cpw = 1); sizes the look-back state in the workspace
-uint64_t max_tiles(uint64_t n) {
-  const uint64_t chunks = (n + kChunk - 1) / kChunk;
-  return (chunks + kMinTileChunks - 1) / kMinTileChunks;
-}
-
 // chunks per wave: the largest power of two (up to `most`) that still leaves `want` tiles per CU
 uint32_t pick_cpw(uint64_t n_chunks, uint32_t most, uint32_t want_tiles_per_cu) {
   const uint64_t want = (uint64_t)cu_count() * want_tiles_per_cu;
@@ -630,6 +665,26 @@ bool codebook_ok(const splitzip_codebook* cb, int dtype) {
     }
   }
   return members == 16;
+}
+
+template <int T>
+void launch_compress(unsigned grid, hipStream_t stream, const CompressArgs& a) {
+  hipLaunchKernelGGL(compress_bf16_kernel<T>, dim3(grid), dim3(T), 0, stream, a);
+}
+
+// workgroups of T threads that can be resident on the current device at the same time
+template <int T>
+uint32_t resident_workgroups() {
+  static uint32_t cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+  if (!cached[dev]) {
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, compress_bf16_kernel<T>, T, 0) != hipSuccess || per_cu <= 0)
+      return 0;
+    cached[dev] = (uint32_t)per_cu * (uint32_t)cu_count();
+  }
+  return cached[dev];
 }
 
 }  // namespace
@@ -703,16 +758,15 @@ size_t splitzip_compress_bound(uint64_t n_elems, int dtype) { return splitzip_to
 
 size_t splitzip_workspace_bytes(uint64_t n_elems, int dtype) {
   if (!dtype_ok(dtype) || n_elems >> 32) return 0;
-  return (size_t)(kWsHeaderBytes + a256(8 * max_tiles(n_elems)) + a256(n_elems));
+  return (size_t)(kWsHeaderBytes + 8 * kMaxWorkgroups + a256(n_elems));
 }
 
 int splitzip_workspace_init(void* d_workspace, size_t workspace_bytes, void* stream) {
-  if (!d_workspace || !aligned16(d_workspace) || workspace_bytes < kWsHeaderBytes) return SPLITZIP_ERR_INVALID_ARG;
-  // the escape-value staging at the end needs no clearing, but one pass over everything is simplest
-  const uint64_t nvec = workspace_bytes / 16;
-  const unsigned blocks = (unsigned)((nvec + 255) / 256 < 1024 ? (nvec + 255) / 256 : 1024);
-  hipLaunchKernelGGL(workspace_init_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
-                     static_cast<uint4*>(d_workspace), nvec);
+  if (!d_workspace || !aligned16(d_workspace) || workspace_bytes < kWsHeaderBytes + 8 * kMaxWorkgroups)
+    return SPLITZIP_ERR_INVALID_ARG;
+  // header and exchange words; the epoch starts at 1 so that a cleared word never looks published
+  hipLaunchKernelGGL(workspace_init_kernel, dim3(8), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<uint32_t*>(d_workspace), (uint32_t)((kWsHeaderBytes + 8 * kMaxWorkgroups) / 4));
   return hipGetLastError() == hipSuccess ? SPLITZIP_OK : SPLITZIP_ERR_HIP;
 }
 
@@ -739,23 +793,57 @@ int splitzip_compress(const void* d_in, uint64_t n_elems, int dtype, const split
   uint8_t* ws = static_cast<uint8_t*>(d_workspace);
   a.ws_hdr = reinterpret_cast<uint32_t*>(ws);
   a.state = reinterpret_cast<uint64_t*>(ws + kWsHeaderBytes);
-  a.val_stage = ws + kWsHeaderBytes + a256(8 * max_tiles(n_elems));
+  a.val_stage = ws + kWsHeaderBytes + 8 * kMaxWorkgroups;
   a.sizes = d_sizes;
   a.off_tab = L.off_tab; a.off_sm = L.off_sm; a.off_code = L.off_code; a.off_pos = L.off_pos;
   a.sm_bytes = L.sm_bytes; a.code_bytes = L.code_bytes;
-  static const int cpw_env = env_int("SPLITZIP_COMPRESS_CPW", 0);
-  static const int tiles_per_cu = env_int("SPLITZIP_COMPRESS_TILES_PER_CU", 4);
-  a.cpw = cpw_env ? (uint32_t)cpw_env : pick_cpw(L.n_chunks, 8, (uint32_t)tiles_per_cu);
-  if (a.cpw > kMaxCpw) a.cpw = kMaxCpw;
   a.n_chunks = (uint32_t)L.n_chunks;
-  a.n_tiles = (uint32_t)((L.n_chunks + (uint64_t)kWaves * a.cpw - 1) / (kWaves * a.cpw));
   a.dtype = (uint32_t)dtype;
   memcpy(a.dec, cb->dec, 16);
   for (unsigned v = 0; v < 256; ++v) a.lut[v] = cb->member[v] ? cb->enc[v] : 0x100u;
+  static const int spin_env = env_int("SPLITZIP_SPIN_TICKS", 0);
+  a.spin_ticks = spin_env ? (uint64_t)spin_env : kSpinTicks;
 
-  const unsigned grid = a.n_tiles ? a.n_tiles : 1u;
-  hipLaunchKernelGGL(compress_bf16_kernel, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
-  return hipGetLastError() == hipSuccess ? SPLITZIP_OK : SPLITZIP_ERR_HIP;
+  // the grid: every workgroup resident at once, at least one chunk per wave where the tensor allows
+  static const int threads = env_int("SPLITZIP_COMPRESS_THREADS", 512);
+  static const int wgs_per_cu = env_int("SPLITZIP_COMPRESS_WGS_PER_CU", 2);
+  const int T = threads == 256 || threads == 1024 ? threads : 512;
+  uint32_t resident = T == 256 ? resident_workgroups<256>() : T == 512 ? resident_workgroups<512>() : resident_workgroups<1024>();
+  if (!resident) return SPLITZIP_ERR_HIP;
+  uint32_t w_max = (uint32_t)cu_count() * (uint32_t)wgs_per_cu;
+  if (w_max > resident) w_max = resident;
+  if (w_max > kMaxWorkgroups) w_max = kMaxWorkgroups;
+  static const int max_wgs = env_int("SPLITZIP_COMPRESS_MAX_WGS", 0);   // small grids, to exercise calls of several launches
+  if (max_wgs && w_max > (uint32_t)max_wgs) w_max = (uint32_t)max_wgs;
+  const uint64_t seg_cap = (uint64_t)w_max * kMaxRange;   // chunks one launch can take
+  const hipStream_t st = static_cast<hipStream_t>(stream);
+  static const int missing = env_int("SPLITZIP_TEST_AWAIT_EXTRA_WGS", 0);   // error-path tests only
+
+  uint64_t done = 0;
+  const bool several = L.n_chunks > seg_cap;
+  do {
+    const uint64_t left = L.n_chunks - done;
+    const uint32_t seg = (uint32_t)(left < seg_cap ? left : seg_cap);
+    a.seg_chunk0 = (uint32_t)done;
+    a.seg_chunks = seg;
+    a.flags = (done == 0 ? kSegFirst : 0u) | (done + seg == L.n_chunks ? kSegLast : 0u);
+    const uint32_t nw = (uint32_t)T / 64;
+    uint32_t grid = (seg + nw - 1) / nw;
+    if (grid > w_max) grid = w_max;
+    if (grid < 1) grid = 1;
+    a.expect_wgs = grid + (uint32_t)missing;
+    if (a.expect_wgs > kMaxWorkgroups) return SPLITZIP_ERR_INVALID_ARG;
+    if (T == 256) launch_compress<256>(grid, st, a);
+    else if (T == 512) launch_compress<512>(grid, st, a);
+    else launch_compress<1024>(grid, st, a);
+    if (hipGetLastError() != hipSuccess) return SPLITZIP_ERR_HIP;
+    done += seg;
+  } while (done < L.n_chunks);
+  if (several) {
+    hipLaunchKernelGGL(compress_finish_kernel, dim3(64), dim3(kThreads), 0, st, a);
+    if (hipGetLastError() != hipSuccess) return SPLITZIP_ERR_HIP;
+  }
+  return SPLITZIP_OK;
 }
 
 int splitzip_decompress(const void* d_comp, size_t comp_bytes, uint64_t n_elems, int dtype,
