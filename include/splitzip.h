@@ -17,8 +17,10 @@
  * the caller's stream and results (including sizes) are written by kernels.
  * Calls return 0 (SPLITZIP_OK) or a negative splitzip_error.
  *
- * Compressed stream (little endian; each section starts 16-byte aligned, pad
- * bytes are zero; A16(x) = x rounded up to 16; C = ceil(N/1024)):
+ * Compressed stream (little endian; the offset table follows the header, every
+ * other section starts 256-byte aligned so that the planes fall on whole cache
+ * lines and HBM channel granules; pad bytes are zero; A(x) = x rounded up to
+ * 256; C = ceil(N/1024)):
  *
  *   header     64 B        u32 magic "SZP1", u16 version 1, u8 dtype, u8 code
  *                          bits (4), u32 chunk elements (1024), u32 0,
@@ -32,7 +34,7 @@
  *   esc_pos    2M B        u16 chunk-relative positions, ascending elements
  *   esc_val    M B         u8 raw exponents, same order
  *
- *   total = 64 + A16(4(C+1)) + A16(sm) + A16(ceil(N/2)) + A16(2M) + M
+ *   total = A(64 + 4(C+1)) + A(sm) + A(ceil(N/2)) + A(2M) + M
  *
  * The payload (planes + 3M) is the paper's B_SZ = N + N/2 + 3M (section 3.2).
  */

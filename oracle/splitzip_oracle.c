@@ -35,8 +35,11 @@
  * so those byte-level conventions are "parity unpinned" by the paper; they
  * are pinned by a hand-assembled example in tests/golden instead.
  *
- * Stream layout (little endian, every section starts 16-byte aligned, pad
- * bytes are zero; A16(x) rounds x up to a multiple of 16; C = ceil(N/1024)):
+ * Stream layout (little endian; the offset table follows the header directly,
+ * every other section starts 256-byte aligned; pad bytes are zero; A(x) rounds
+ * x up to a multiple of 256; C = ceil(N/1024)).  The paper fixes the payload
+ * bytes only (section 3.2); header, table and padding are this build's
+ * metadata:
  *
  *   header     64 B          see write_header()
  *   chunk_off  4*(C+1) B     u32 exclusive prefix sums of per-chunk escape
@@ -48,7 +51,7 @@
  *   esc_pos    2M B          u16 chunk-relative positions, element order
  *   esc_val    M B           u8 raw exponents, same order
  *
- *   total = 64 + A16(4(C+1)) + A16(sm) + A16(ceil(N/2)) + A16(2M) + M
+ *   total = A(64 + 4(C+1)) + A(sm) + A(ceil(N/2)) + A(2M) + M
  */
 #include <stddef.h>
 #include <stdint.h>
@@ -67,7 +70,8 @@
 #define CHUNK 1024u
 #define HEADER_BYTES 64u
 
-static uint64_t a16(uint64_t x) { return (x + 15u) & ~(uint64_t)15u; }
+/* section alignment: 256 bytes (two 128-byte cache lines, one HBM channel granule) */
+static uint64_t a256(uint64_t x) { return (x + 255u) & ~(uint64_t)255u; }
 
 static int dtype_ok(int dtype) { return dtype == ORACLE_BF16 || dtype == ORACLE_E5M2; }
 
@@ -112,8 +116,8 @@ uint64_t oracle_payload_bytes(uint64_t n, uint64_t m, int dtype) {
 /* whole stream: payload + header + chunk offset table + alignment pads */
 uint64_t oracle_total_bytes(uint64_t n, uint64_t m, int dtype) {
   uint64_t c = (n + CHUNK - 1u) / CHUNK;
-  return HEADER_BYTES + a16(4u * (c + 1u)) + a16(oracle_sm_bytes(n, dtype)) + a16((n + 1u) / 2u) +
-         a16(2u * m) + m;
+  return a256(HEADER_BYTES + 4u * (c + 1u)) + a256(oracle_sm_bytes(n, dtype)) + a256((n + 1u) / 2u) +
+         a256(2u * m) + m;
 }
 
 /* ---- calibration (section 3.3) ----------------------------------------- */
@@ -233,10 +237,10 @@ int oracle_compress(const void* in, uint64_t n, int dtype, const uint8_t dec[16]
 
   uint64_t c = (n + CHUNK - 1u) / CHUNK;
   uint64_t off_tab = HEADER_BYTES;
-  uint64_t off_sm = off_tab + a16(4u * (c + 1u));
-  uint64_t off_code = off_sm + a16(oracle_sm_bytes(n, dtype));
-  uint64_t off_pos = off_code + a16((n + 1u) / 2u);
-  uint64_t off_val = off_pos + a16(2u * m);
+  uint64_t off_sm = a256(off_tab + 4u * (c + 1u));
+  uint64_t off_code = off_sm + a256(oracle_sm_bytes(n, dtype));
+  uint64_t off_pos = off_code + a256((n + 1u) / 2u);
+  uint64_t off_val = off_pos + a256(2u * m);
 
   memset(out, 0, total); /* pads, unused nibbles and tail bits are zero */
   write_header(out, n, m, total, dtype, dec);
@@ -302,10 +306,10 @@ int oracle_decompress(const uint8_t* blob, uint64_t blob_bytes, uint64_t n, int 
 
   uint64_t c = (n + CHUNK - 1u) / CHUNK;
   uint64_t off_tab = HEADER_BYTES;
-  uint64_t off_sm = off_tab + a16(4u * (c + 1u));
-  uint64_t off_code = off_sm + a16(oracle_sm_bytes(n, dtype));
-  uint64_t off_pos = off_code + a16((n + 1u) / 2u);
-  uint64_t off_val = off_pos + a16(2u * m);
+  uint64_t off_sm = a256(off_tab + 4u * (c + 1u));
+  uint64_t off_code = off_sm + a256(oracle_sm_bytes(n, dtype));
+  uint64_t off_pos = off_code + a256((n + 1u) / 2u);
+  uint64_t off_val = off_pos + a256(2u * m);
 
   if (get32(blob + off_tab) != 0 || get32(blob + off_tab + 4u * c) != m) return ORACLE_ERR_FORMAT;
   for (uint64_t ch = 0; ch < c; ++ch) {

@@ -47,17 +47,17 @@ constexpr int kWaves = kThreads / 64;
 constexpr uint32_t kMaxCpw = 16;                          // decompress: chunks per wave per tile, at most
 constexpr uint32_t kMaxRange = 256;                       // compress: chunks per workgroup per launch, at most
 constexpr uint32_t kMaxWorkgroups = 4096;                 // compress: words of exchange state in the workspace
+constexpr uint32_t kWsTableBytes = 8 * kMaxWorkgroups;
 constexpr uint32_t kStageCap = 512;                       // escapes a wave can stage in LDS
 constexpr uint32_t kWsHeaderBytes = 64;                   // epoch, running escape count, error flags
 constexpr uint32_t kSegFirst = 1u, kSegLast = 2u;         // CompressArgs.flags
 constexpr uint64_t kSpinTicks = 200000000ull;             // 2 s of the 100 MHz wall clock
 
-__host__ __device__ inline uint64_t a16(uint64_t x) { return (x + 15u) & ~(uint64_t)15u; }
 __host__ __device__ inline uint64_t a256(uint64_t x) { return (x + 255u) & ~(uint64_t)255u; }
 
 struct Layout {
   uint64_t n, n_chunks, sm_bytes, code_bytes;
-  uint64_t off_tab, off_sm, off_code, off_pos;  // the value section starts at off_pos + a16(2M)
+  uint64_t off_tab, off_sm, off_code, off_pos;  // the value section starts at off_pos + a256(2M)
 };
 
 __host__ __device__ inline Layout make_layout(uint64_t n, int dtype) {
@@ -67,9 +67,9 @@ __host__ __device__ inline Layout make_layout(uint64_t n, int dtype) {
   L.sm_bytes = dtype == SPLITZIP_BF16 ? n : (3 * n + 7) / 8;
   L.code_bytes = (n + 1) / 2;
   L.off_tab = kHeaderBytes;
-  L.off_sm = L.off_tab + a16(4 * (L.n_chunks + 1));
-  L.off_code = L.off_sm + a16(L.sm_bytes);
-  L.off_pos = L.off_code + a16(L.code_bytes);
+  L.off_sm = a256(L.off_tab + 4 * (L.n_chunks + 1));
+  L.off_code = L.off_sm + a256(L.sm_bytes);
+  L.off_pos = L.off_code + a256(L.code_bytes);
   return L;
 }
 
@@ -133,9 +133,10 @@ struct CompressArgs {
 struct LdsSink {
   uint16_t* pos;
   uint8_t* val;
+  uint32_t tag;   // OR-ed into the position: which of the wave's chunks the record belongs to
   __device__ inline void put(uint32_t r, uint32_t p, uint32_t e) const {
     if (r < kStageCap) {
-      pos[r] = (uint16_t)p;
+      pos[r] = (uint16_t)(p | tag);
       val[r] = (uint8_t)e;
     }
   }
@@ -191,13 +192,10 @@ __device__ inline void emit_half_bf16(uint32_t* park, const uint32_t (&w)[4], ui
   }
 }
 
-// One chunk by one wave: load, dense transform, (optionally) plane stores, escape
-// ranks inside the chunk, escape records into `sink` starting at rank `base`.
-// Returns the chunk's escape count (wave-uniform).
-template <bool FULL, bool STORE, typename Sink>
-__device__ inline uint32_t compress_chunk_bf16(const CompressArgs& a, const uint16_t* lut, uint32_t* park,
-                                               uint64_t cbase, int lane, uint32_t base, const Sink& sink) {
-  uint32_t w[2][4], F[2];
+// One chunk's words into registers: lane l holds elements [8 l, 8 l + 8) of each half-chunk.
+// Elements past N read as zero.
+template <bool FULL>
+__device__ inline void load_chunk_bf16(const CompressArgs& a, uint64_t cbase, int lane, uint32_t (&w)[2][4]) {
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     const uint64_t g0 = cbase + h * kHalf + lane * 8;   // first element of this lane's group
@@ -216,6 +214,16 @@ __device__ inline uint32_t compress_chunk_bf16(const CompressArgs& a, const uint
       }
     }
   }
+}
+
+// One chunk by one wave, its words in w: dense transform, (optionally) plane stores, escape
+// ranks inside the chunk, escape records into `sink` starting at rank `base`.
+// Returns the chunk's escape count (wave-uniform).
+template <bool FULL, bool STORE, typename Sink>
+__device__ inline uint32_t process_chunk_bf16(const CompressArgs& a, const uint16_t* lut, uint32_t* park,
+                                              uint64_t cbase, int lane, const uint32_t (&w)[2][4], uint32_t base,
+                                              const Sink& sink) {
+  uint32_t F[2];
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     const uint64_t g0 = cbase + h * kHalf + lane * 8;
@@ -230,13 +238,16 @@ __device__ inline uint32_t compress_chunk_bf16(const CompressArgs& a, const uint
       F[h] &= keep;
     }
     if (STORE) {
-      // Sections are padded to 16 bytes and a lane's group never straddles the padded end, so
+      // Sections are padded to 256 bytes and a lane's group never straddles the padded end, so
       // whole-group stores also write the zero padding.
-      if (FULL || g0 < a16(a.sm_bytes)) st_stream(reinterpret_cast<u32x2*>(a.out + a.off_sm + g0), sm);
-      if (FULL || (g0 >> 1) < a16(a.code_bytes))
+      if (FULL || g0 < a256(a.sm_bytes)) st_stream(reinterpret_cast<u32x2*>(a.out + a.off_sm + g0), sm);
+      if (FULL || (g0 >> 1) < a256(a.code_bytes))
         st_stream(reinterpret_cast<uint32_t*>(a.out + a.off_code + (g0 >> 1)), code);
     }
   }
+#ifdef EXP_NO_SCAN
+  return (F[0] | F[1]) == 0x12345678u;
+#endif
   // escapes per lane; both halves scanned at once (16 bits each: a half has at most 512)
   const uint32_t packed = __popc(F[0]) | (__popc(F[1]) << 16);
   const uint32_t incl = wave_incl_scan(packed);
@@ -253,15 +264,14 @@ __device__ inline uint32_t compress_chunk_bf16(const CompressArgs& a, const uint
 
 // header, sizes record and the zero padding behind the positions: one wave, once M is known
 __device__ void compress_write_trailer(const CompressArgs& a, uint32_t M, uint32_t err_flags, int lane) {
-  const uint64_t off_val = a.off_pos + a16(2ull * M);
+  const uint64_t off_val = a.off_pos + a256(2ull * M);
   const uint64_t total = off_val + M;
-  for (uint64_t i = 2ull * M + lane; i < a16(2ull * M); i += 64)
+  for (uint64_t i = 2ull * M + lane; i < a256(2ull * M); i += 64)
     if (a.off_pos + i < a.capacity) a.out[a.off_pos + i] = 0;
+  // chunk_off[C] = M, then zero padding up to the sign+mantissa plane
+  uint32_t* tab = reinterpret_cast<uint32_t*>(a.out + a.off_tab);
+  for (uint64_t i = (uint64_t)a.n_chunks + lane; a.off_tab + 4 * i < a.off_sm; i += 64) tab[i] = i == a.n_chunks ? M : 0u;
   if (lane == 0) {
-    uint32_t* tab = reinterpret_cast<uint32_t*>(a.out + a.off_tab);
-    // chunk_off[C] = M, then zero padding up to the 16-byte boundary
-    tab[a.n_chunks] = M;
-    for (uint64_t i = (uint64_t)a.n_chunks + 1; 4 * i < a16(4ull * ((uint64_t)a.n_chunks + 1)); ++i) tab[i] = 0;
     uint32_t h[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) h[i] = 0;
@@ -286,28 +296,37 @@ __device__ void compress_write_trailer(const CompressArgs& a, uint32_t M, uint32
 
 // One launch covers the chunks [seg_chunk0, seg_chunk0 + seg_chunks) with a grid in which every
 // workgroup is resident at the same time.  Workgroup b owns a contiguous range of at most
-// kMaxRange chunks.  After its dense pass it publishes the escape count of its range in state[b]
-// (tagged with the launch's epoch, so that the words never need clearing) and reads the words of
-// all workgroups: the counts before b give its offset, all of them give M.  The wait ends when
-// the slowest workgroup has published; it is bounded by spin_ticks of the wall clock, after which
-// the launch gives up with SPLITZIP_STATUS_INTERNAL instead of hanging.
+// kMaxRange chunks, dealt round-robin to its waves.  After its dense pass it publishes the escape
+// count of its range in state[b] (tagged with the launch's epoch, so that the words never need
+// clearing) and one wave reads the words of all workgroups: the counts before b give its offset,
+// all of them give M.  The wait ends when the slowest workgroup has published; it is bounded by
+// spin_ticks of the wall clock, after which the launch gives up with SPLITZIP_STATUS_INTERNAL
+// instead of hanging.
 template <int T>
 __global__ __launch_bounds__(T) void compress_bf16_kernel(const CompressArgs a) {
   constexpr int NW = T / 64;
-  static_assert(T >= (int)kMaxRange && NW <= 16, "the range scan uses one thread per chunk");
+  static_assert(kMaxRange <= 256 && NW >= 4 && NW <= 16, "one wave scans the range, four chunks per lane");
   __shared__ uint16_t lut[256];
-  __shared__ uint16_t stage_pos[NW][kStageCap];
+  __shared__ uint16_t stage_pk[NW][kStageCap];   // position | (chunk's index in the range / NW) << 10
   __shared__ uint8_t stage_val[NW][kStageCap];
-  __shared__ uint32_t s_off[kMaxRange + 1];
+  __shared__ uint32_t s_off[kMaxRange + 1];      // escapes of chunk k of the range, then of the chunks before it
+  __shared__ uint16_t s_wstart[kMaxRange];       // records its wave had staged before chunk k
   __shared__ u32x4 s_park[T];
-  __shared__ uint32_t s_red[3][16];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  __shared__ uint32_t s_red[16];
+  __shared__ uint32_t s_misc[4];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: loops over chunks stay scalar
   const uint32_t W = a.expect_wgs, b = blockIdx.x;
   uint32_t* park = reinterpret_cast<uint32_t*>(&s_park[tid]);
+#ifdef EXP_TIMING
+  const uint64_t ts0 = wall_clock64();
+#endif
 
   if (tid < 256) lut[tid] = a.lut[tid];
   const uint32_t epoch = ld_agent(&a.ws_hdr[0]);
   const uint32_t base = (a.flags & kSegFirst) ? 0u : ld_agent(&a.ws_hdr[1]);
+  const uint32_t err_before = b == 0 ? ld_agent(&a.ws_hdr[2]) : 0u;   // sticky flags of earlier launches
+  const bool single = (a.flags & (kSegFirst | kSegLast)) == (kSegFirst | kSegLast);
   __syncthreads();
 
   // this workgroup's range: seg_chunks dealt evenly, the first `rem` workgroups get one more
@@ -315,95 +334,127 @@ __global__ __launch_bounds__(T) void compress_bf16_kernel(const CompressArgs a) 
   const uint32_t nb = per + (b < rem ? 1u : 0u);
   const uint32_t r0 = a.seg_chunk0 + b * per + (b < rem ? b : rem);
 
-  const LdsSink lds{stage_pos[wave], stage_val[wave]};
+  // dense pass; the next chunk's loads are issued before this chunk is worked on
   uint32_t wave_count = 0;
-  for (uint32_t k = wave; k < nb; k += NW) {
+  uint32_t w[2][4], nx[2][4];
+  if ((uint32_t)wave < nb) {
+    const uint64_t cbase = (uint64_t)(r0 + wave) * kChunk;
+    if (cbase + kChunk <= a.n) load_chunk_bf16<true>(a, cbase, lane, w);
+    else load_chunk_bf16<false>(a, cbase, lane, w);
+  }
+  for (uint32_t k = wave, it = 0; k < nb; k += NW, ++it) {
     const uint64_t cbase = (uint64_t)(r0 + k) * kChunk;
+    if (k + NW < nb) {
+      const uint64_t nbase = cbase + (uint64_t)NW * kChunk;
+      if (nbase + kChunk <= a.n) load_chunk_bf16<true>(a, nbase, lane, nx);
+      else load_chunk_bf16<false>(a, nbase, lane, nx);
+    }
+    const LdsSink lds{stage_pk[wave], stage_val[wave], it << 10};
     const uint32_t cnt = cbase + kChunk <= a.n
-                             ? compress_chunk_bf16<true, true>(a, lut, park, cbase, lane, wave_count, lds)
-                             : compress_chunk_bf16<false, true>(a, lut, park, cbase, lane, wave_count, lds);
-    if (lane == 0) s_off[k] = cnt;
+                             ? process_chunk_bf16<true, true>(a, lut, park, cbase, lane, w, wave_count, lds)
+                             : process_chunk_bf16<false, true>(a, lut, park, cbase, lane, w, wave_count, lds);
+    if (lane == 0) {
+      s_off[k] = cnt;
+      s_wstart[k] = (uint16_t)(wave_count < 0xffffu ? wave_count : 0xffffu);
+    }
     wave_count += cnt;
-  }
-  __syncthreads();
-
-  // exclusive offsets of the range's chunks (thread q <-> chunk q) and the range total
-  const uint32_t my = (uint32_t)tid < nb ? s_off[tid] : 0u;
-  const uint32_t incl = wave_incl_scan(my);
-  if (lane == 63) s_red[0][wave] = incl;
-  __syncthreads();
-  uint32_t wave_off = 0, agg = 0;
 #pragma unroll
-  for (int j = 0; j < NW; ++j) {
-    const uint32_t t = s_red[0][j];
-    wave_off += j < wave ? t : 0u;
-    agg += t;
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int d = 0; d < 4; ++d) w[h][d] = nx[h][d];
   }
-  if ((uint32_t)tid < nb) s_off[tid] = wave_off + incl - my;
-  if (tid == 0) {
-    s_off[nb] = agg;
-    st_agent(&a.state[b], ((uint64_t)epoch << 32) | agg);
-  }
+  if (lane == 0) s_red[wave] = wave_count;
+  __syncthreads();
+#ifdef EXP_TIMING
+  const uint64_t ts1 = wall_clock64();
+#endif
 
-  // the exchange: wait until every workgroup's word carries this launch's epoch
-  uint32_t lower = 0, all = 0;
-  bool timed_out = false;
-  const uint64_t t0 = wall_clock64();
-  for (;;) {
-    uint32_t lo = 0, al = 0;
-    int ready = 1;
-    for (uint32_t i = tid; i < W; i += T) {
-      const uint64_t s = ld_agent(&a.state[i]);
-      if ((uint32_t)(s >> 32) != epoch) ready = 0;
-      al += (uint32_t)s;
-      lo += i < b ? (uint32_t)s : 0u;
-    }
-    if (__syncthreads_and(ready)) {
-      lower = lo;
-      all = al;
+  if (wave == 0) {
+    // publish the range total, then wait until every workgroup's word carries this launch's epoch
+    const uint32_t agg = wave_last(wave_incl_scan(lane < NW ? s_red[lane] : 0u));
+    if (lane == 0) st_agent(&a.state[b], ((uint64_t)epoch << 32) | agg);
+    uint32_t lo, al, spins = 0, gave_up = 0;
+    const uint64_t t0 = wall_clock64();
+    for (;;) {
+      lo = 0;
+      al = 0;
+      int ready = 1;
+      for (uint32_t i = lane; i < W; i += 64) {
+        const uint64_t s = ld_agent(&a.state[i]);
+        if ((uint32_t)(s >> 32) != epoch) ready = 0;
+        al += (uint32_t)s;
+        lo += i < b ? (uint32_t)s : 0u;
+      }
+#ifdef EXP_NO_WAIT
       break;
+#endif
+      if (__ballot(ready) == ~0ull) break;
+      if ((++spins & 15u) == 0 && (uint64_t)(wall_clock64() - t0) > a.spin_ticks) {
+        gave_up = 1;
+        break;
+      }
+      __builtin_amdgcn_s_sleep(1);
     }
-    const int expired = tid == 0 && (uint64_t)(wall_clock64() - t0) > a.spin_ticks;
-    if (__syncthreads_or(expired)) {
-      timed_out = true;
-      break;
+    lo = base + wave_last(wave_incl_scan(lo));
+    al = base + wave_last(wave_incl_scan(al));
+    if (lane == 0) {
+      s_misc[0] = lo;
+      s_misc[1] = al;
+      s_misc[2] = gave_up;
     }
-    __builtin_amdgcn_s_sleep(2);
-  }
-  lower = wave_last(wave_incl_scan(lower));
-  all = wave_last(wave_incl_scan(all));
-  if (lane == 0) {
-    s_red[1][wave] = lower;
-    s_red[2][wave] = all;
+    // workgroup 0 closes the launch: it has seen every workgroup's word, so all of them have
+    // read the header words
+    if (b == 0) {
+      const uint32_t err = err_before | (gave_up ? (uint32_t)SPLITZIP_STATUS_INTERNAL : 0u);
+      if (lane == 0) {
+        st_agent(&a.ws_hdr[0], epoch + 1u ? epoch + 1u : 1u);
+        st_agent(&a.ws_hdr[1], al);
+        st_agent(&a.ws_hdr[2], single ? 0u : err);   // a call of several launches reports in its finishing launch
+      }
+      if (single) compress_write_trailer(a, al, err, lane);
+    }
+  } else if (wave == 1) {
+    // meanwhile: exclusive offsets of the range's chunks, four per lane, in place; s_off[nb] = total
+    uint32_t v[4], sum = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t q = 4 * lane + j;
+      v[j] = q < nb ? s_off[q] : 0u;
+      sum += v[j];
+    }
+    const uint32_t incl = wave_incl_scan(sum);
+    uint32_t run = incl - sum;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t q = 4 * lane + j;
+      if (q < nb) s_off[q] = run;
+      run += v[j];
+    }
+    if (lane == 63) s_off[nb] = incl;
   }
   __syncthreads();
-  lower = 0;
-  all = 0;
-#pragma unroll
-  for (int j = 0; j < NW; ++j) {
-    lower += s_red[1][j];
-    all += s_red[2][j];
-  }
-  const uint32_t prefix = base + lower, M = base + all;
-  const bool single = (a.flags & (kSegFirst | kSegLast)) == (kSegFirst | kSegLast);
+  const uint32_t prefix = s_misc[0], M = s_misc[1];
+  const bool timed_out = s_misc[2] != 0;
+#ifdef EXP_TIMING
+  const uint64_t ts2 = wall_clock64();
+#endif
 
   if (!timed_out) {
     uint32_t* tab = reinterpret_cast<uint32_t*>(a.out + a.off_tab);
     if ((uint32_t)tid < nb) tab[r0 + tid] = prefix + s_off[tid];
 
     // escape records to their final rank; values go behind the positions when M is final
-    const uint64_t off_val = a.off_pos + a16(2ull * M);
+    const uint64_t off_val = a.off_pos + a256(2ull * M);
     GlobalSink g;
     g.pos = reinterpret_cast<uint16_t*>(a.out + a.off_pos);
     g.pos_room = a.capacity > a.off_pos ? (a.capacity - a.off_pos) / 2 : 0;
     g.val = single ? a.out + off_val : a.val_stage;
     g.val_room = single ? (a.capacity > off_val ? a.capacity - off_val : 0) : ~0ull;
     if (wave_count <= kStageCap) {
-      uint32_t woff = 0;
-      for (uint32_t k = wave; k < nb; k += NW) {
-        const uint32_t lo = s_off[k], c = s_off[k + 1] - lo;
-        for (uint32_t i = lane; i < c; i += 64) g.put(prefix + lo + i, stage_pos[wave][woff + i], stage_val[wave][woff + i]);
-        woff += c;
+      // staged record i of this wave belongs to chunk k and is the (i - s_wstart[k])-th of it
+      for (uint32_t i = lane; i < wave_count; i += 64) {
+        const uint32_t pk = stage_pk[wave][i], k = (pk >> 10) * NW + wave;
+        g.put(prefix + s_off[k] + (i - s_wstart[k]), pk & 1023u, stage_val[wave][i]);
       }
     } else {
       // more escapes than the staging holds: go over this wave's chunks again and write the
@@ -411,32 +462,32 @@ __global__ __launch_bounds__(T) void compress_bf16_kernel(const CompressArgs a) 
       for (uint32_t k = wave; k < nb; k += NW) {
         const uint64_t cbase = (uint64_t)(r0 + k) * kChunk;
         const uint32_t r = prefix + s_off[k];
-        if (cbase + kChunk <= a.n) compress_chunk_bf16<true, false>(a, lut, park, cbase, lane, r, g);
-        else compress_chunk_bf16<false, false>(a, lut, park, cbase, lane, r, g);
+        if (cbase + kChunk <= a.n) {
+          load_chunk_bf16<true>(a, cbase, lane, w);
+          process_chunk_bf16<true, false>(a, lut, park, cbase, lane, w, r, g);
+        } else {
+          load_chunk_bf16<false>(a, cbase, lane, w);
+          process_chunk_bf16<false, false>(a, lut, park, cbase, lane, w, r, g);
+        }
       }
     }
   } else if (tid == 0) {
     __hip_atomic_fetch_or(&a.ws_hdr[2], (uint32_t)SPLITZIP_STATUS_INTERNAL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
-
-  // workgroup 0 closes the launch: it left the exchange, so every workgroup has read the epoch
-  if (b == 0 && wave == 0) {
-    uint32_t err = 0;
-    if (lane == 0) {
-      err = ld_agent(&a.ws_hdr[2]) | (timed_out ? (uint32_t)SPLITZIP_STATUS_INTERNAL : 0u);
-      st_agent(&a.ws_hdr[0], epoch + 1u ? epoch + 1u : 1u);
-      st_agent(&a.ws_hdr[1], M);
-      st_agent(&a.ws_hdr[2], single ? 0u : err);   // a call of several launches reports in its finishing launch
-    }
-    if (single) compress_write_trailer(a, M, err, lane);
+#ifdef EXP_TIMING
+  __syncthreads();
+  if (tid == 0) {
+    uint64_t* t = reinterpret_cast<uint64_t*>(a.val_stage) + 4 * b;
+    t[0] = ts0; t[1] = ts1; t[2] = ts2; t[3] = wall_clock64();
   }
+#endif
 }
 
 // Last launch of a call that took several: M is known now.  Moves the staged escape values
 // behind the position array and writes the trailer.
 __global__ __launch_bounds__(kThreads) void compress_finish_kernel(const CompressArgs a) {
   const uint32_t M = ld_agent(&a.ws_hdr[1]);
-  const uint64_t off_val = a.off_pos + a16(2ull * M);
+  const uint64_t off_val = a.off_pos + a256(2ull * M);
   const uint64_t room = a.capacity > off_val ? a.capacity - off_val : 0;
   const uint64_t m = M < room ? M : room;
   const uint64_t nvec = m / 16;
@@ -479,7 +530,7 @@ __device__ void decompress_check_header(const DecompressArgs& a, uint32_t M) {
   const uint64_t n = h[4] | ((uint64_t)h[5] << 32), m = h[6] | ((uint64_t)h[7] << 32);
   const uint64_t total = h[8] | ((uint64_t)h[9] << 32);
   bool ok = h[0] == 0x31505a53u && h[1] == (1u | (a.dtype << 16) | (4u << 24)) && h[2] == kChunk &&
-            h[3] == 0 && n == a.n && m == M && total == a.off_pos + a16(2 * m) + m &&
+            h[3] == 0 && n == a.n && m == M && total == a.off_pos + a256(2 * m) + m &&
             total <= a.comp_bytes && h[14] == 0 && h[15] == 0;
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -502,8 +553,8 @@ __device__ inline void decompress_chunk_bf16(const DecompressArgs& a, const uint
     const uint64_t g0 = cbase + h * kHalf + lane * 8;
     sm[h] = u32x2{0u, 0u};
     cd[h] = 0;
-    if (FULL || g0 < a16(a.sm_bytes)) sm[h] = ld_stream(reinterpret_cast<const u32x2*>(a.comp + a.off_sm + g0));
-    if (FULL || (g0 >> 1) < a16(a.code_bytes))
+    if (FULL || g0 < a256(a.sm_bytes)) sm[h] = ld_stream(reinterpret_cast<const u32x2*>(a.comp + a.off_sm + g0));
+    if (FULL || (g0 >> 1) < a256(a.code_bytes))
       cd[h] = ld_stream(reinterpret_cast<const uint32_t*>(a.comp + a.off_code + (g0 >> 1)));
   }
 #pragma unroll
@@ -542,7 +593,7 @@ __global__ __launch_bounds__(kThreads) void decompress_bf16_kernel(const Decompr
   const uint32_t* tab = reinterpret_cast<const uint32_t*>(a.comp + a.off_tab);
   // M as the offset table states it; escapes are only trusted if their sections lie inside the stream
   uint32_t M = tab[a.n_chunks];
-  const uint64_t off_val = a.off_pos + a16(2ull * M);
+  const uint64_t off_val = a.off_pos + a256(2ull * M);
   const bool esc_ok = M <= a.n && off_val + M <= a.comp_bytes;
   if (blockIdx.x == 0 && tid == 0) {
     decompress_check_header(a, M);
@@ -751,22 +802,22 @@ int splitzip_calibrate(const void* h_sample, uint64_t n_elems, int dtype, splitz
 size_t splitzip_total_bytes(uint64_t n_elems, uint64_t n_escapes, int dtype) {
   if (!dtype_ok(dtype) || n_elems >> 32) return 0;
   const Layout L = make_layout(n_elems, dtype);
-  return (size_t)(L.off_pos + a16(2 * n_escapes) + n_escapes);
+  return (size_t)(L.off_pos + a256(2 * n_escapes) + n_escapes);
 }
 size_t splitzip_fixed_bytes(uint64_t n_elems, int dtype) { return splitzip_total_bytes(n_elems, 0, dtype); }
 size_t splitzip_compress_bound(uint64_t n_elems, int dtype) { return splitzip_total_bytes(n_elems, n_elems, dtype); }
 
 size_t splitzip_workspace_bytes(uint64_t n_elems, int dtype) {
   if (!dtype_ok(dtype) || n_elems >> 32) return 0;
-  return (size_t)(kWsHeaderBytes + 8 * kMaxWorkgroups + a256(n_elems));
+  return (size_t)(kWsHeaderBytes + kWsTableBytes + a256(n_elems));
 }
 
 int splitzip_workspace_init(void* d_workspace, size_t workspace_bytes, void* stream) {
-  if (!d_workspace || !aligned16(d_workspace) || workspace_bytes < kWsHeaderBytes + 8 * kMaxWorkgroups)
+  if (!d_workspace || !aligned16(d_workspace) || workspace_bytes < kWsHeaderBytes + kWsTableBytes)
     return SPLITZIP_ERR_INVALID_ARG;
   // header and exchange words; the epoch starts at 1 so that a cleared word never looks published
   hipLaunchKernelGGL(workspace_init_kernel, dim3(8), dim3(256), 0, static_cast<hipStream_t>(stream),
-                     static_cast<uint32_t*>(d_workspace), (uint32_t)((kWsHeaderBytes + 8 * kMaxWorkgroups) / 4));
+                     static_cast<uint32_t*>(d_workspace), (uint32_t)((kWsHeaderBytes + kWsTableBytes) / 4));
   return hipGetLastError() == hipSuccess ? SPLITZIP_OK : SPLITZIP_ERR_HIP;
 }
 
@@ -793,7 +844,7 @@ int splitzip_compress(const void* d_in, uint64_t n_elems, int dtype, const split
   uint8_t* ws = static_cast<uint8_t*>(d_workspace);
   a.ws_hdr = reinterpret_cast<uint32_t*>(ws);
   a.state = reinterpret_cast<uint64_t*>(ws + kWsHeaderBytes);
-  a.val_stage = ws + kWsHeaderBytes + 8 * kMaxWorkgroups;
+  a.val_stage = ws + kWsHeaderBytes + kWsTableBytes;
   a.sizes = d_sizes;
   a.off_tab = L.off_tab; a.off_sm = L.off_sm; a.off_code = L.off_code; a.off_pos = L.off_pos;
   a.sm_bytes = L.sm_bytes; a.code_bytes = L.code_bytes;
@@ -804,17 +855,18 @@ int splitzip_compress(const void* d_in, uint64_t n_elems, int dtype, const split
   static const int spin_env = env_int("SPLITZIP_SPIN_TICKS", 0);
   a.spin_ticks = spin_env ? (uint64_t)spin_env : kSpinTicks;
 
-  // the grid: every workgroup resident at once, at least one chunk per wave where the tensor allows
-  static const int threads = env_int("SPLITZIP_COMPRESS_THREADS", 512);
-  static const int wgs_per_cu = env_int("SPLITZIP_COMPRESS_WGS_PER_CU", 2);
-  const int T = threads == 256 || threads == 1024 ? threads : 512;
+  // the grid: every workgroup resident at once, not more workgroups than tiles
+  static const int threads = env_int("SPLITZIP_COMPRESS_THREADS", 1024);
+  static const int wgs_per_cu = env_int("SPLITZIP_COMPRESS_WGS_PER_CU", 1);
+  const int T = threads == 256 || threads == 512 ? threads : 1024;
+  const uint32_t nw = (uint32_t)T / 64;
   uint32_t resident = T == 256 ? resident_workgroups<256>() : T == 512 ? resident_workgroups<512>() : resident_workgroups<1024>();
   if (!resident) return SPLITZIP_ERR_HIP;
   uint32_t w_max = (uint32_t)cu_count() * (uint32_t)wgs_per_cu;
   if (w_max > resident) w_max = resident;
-  if (w_max > kMaxWorkgroups) w_max = kMaxWorkgroups;
   static const int max_wgs = env_int("SPLITZIP_COMPRESS_MAX_WGS", 0);   // small grids, to exercise calls of several launches
   if (max_wgs && w_max > (uint32_t)max_wgs) w_max = (uint32_t)max_wgs;
+  if (w_max > kMaxWorkgroups) w_max = kMaxWorkgroups;
   const uint64_t seg_cap = (uint64_t)w_max * kMaxRange;   // chunks one launch can take
   const hipStream_t st = static_cast<hipStream_t>(stream);
   static const int missing = env_int("SPLITZIP_TEST_AWAIT_EXTRA_WGS", 0);   // error-path tests only
@@ -827,8 +879,7 @@ int splitzip_compress(const void* d_in, uint64_t n_elems, int dtype, const split
     a.seg_chunk0 = (uint32_t)done;
     a.seg_chunks = seg;
     a.flags = (done == 0 ? kSegFirst : 0u) | (done + seg == L.n_chunks ? kSegLast : 0u);
-    const uint32_t nw = (uint32_t)T / 64;
-    uint32_t grid = (seg + nw - 1) / nw;
+    uint32_t grid = (seg + nw - 1) / nw;    // at least one chunk per wave where the tensor allows
     if (grid > w_max) grid = w_max;
     if (grid < 1) grid = 1;
     a.expect_wgs = grid + (uint32_t)missing;

@@ -244,7 +244,7 @@ def test_bad_stream_is_flagged_not_followed():
     for mut in (set_(0, 0x58), set_(6, 1), set_(16, int(blob[16]) ^ 1), set_(40, int(blob[40]) ^ 1)):
         y, st = run(mut)                     # header disagrees: flagged
         assert st & sz.STATUS_BAD_STREAM
-    off_pos = blob.size - m - (2 * m + 15) // 16 * 16
+    off_pos = blob.size - m - (2 * m + 255) // 256 * 256
     y, st = run(set_(off_pos + 1, 0xFF))     # position outside the chunk: skipped and flagged
     assert st & sz.STATUS_BAD_STREAM
     c = (n + 1023) // 1024

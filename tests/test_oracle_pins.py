@@ -20,8 +20,8 @@ BF16, E5M2 = oracle.BF16, oracle.E5M2
 # helpers that do NOT use the oracle
 # --------------------------------------------------------------------------
 
-def a16(x):
-    return (x + 15) // 16 * 16
+def a256(x):
+    return (x + 255) // 256 * 256
 
 
 def bf16_fields_from_float_semantics(words):
@@ -45,10 +45,10 @@ def parse_stream(blob, dtype):
     c = (n + 1023) // 1024
     sm_bytes = n if dtype == BF16 else (3 * n + 7) // 8
     o_tab = 64
-    o_sm = o_tab + a16(4 * (c + 1))
-    o_code = o_sm + a16(sm_bytes)
-    o_pos = o_code + a16((n + 1) // 2)
-    o_val = o_pos + a16(2 * m)
+    o_sm = a256(o_tab + 4 * (c + 1))
+    o_code = o_sm + a256(sm_bytes)
+    o_pos = o_code + a256((n + 1) // 2)
+    o_val = o_pos + a256(2 * m)
     d = dict(n=n, m=m, total=total, c=c, dec=blob[40:56].copy(),
              chunk_off=blob[o_tab:o_tab + 4 * (c + 1)].copy().view(np.uint32),
              sm=blob[o_sm:o_sm + sm_bytes], code=blob[o_code:o_code + (n + 1) // 2],
@@ -79,6 +79,8 @@ def read_golden(path):
             words = [int(t, 16) for t in line[6:].split()]
         elif line.startswith("blob:"):
             in_blob = True
+        elif in_blob and line.startswith("zeros"):
+            blob += [0] * int(line.split()[1])          # "zeros n": n pad bytes
         elif in_blob:
             blob += [int(t, 16) for t in line.split()]
     return np.array(dec, np.uint8), words, np.array(blob, np.uint8)
@@ -213,7 +215,7 @@ def test_printed_ratio_pairs(golden_dir):
 
 
 def test_total_bytes_itemised():
-    """whole stream = header + offset table + planes + escapes, every section 16-byte aligned"""
+    """whole stream = header + offset table + planes + escapes, every section 256-byte aligned"""
     for dtype in (BF16, E5M2):
         for n in [0, 1, 2, 7, 8, 9, 15, 16, 17, 1023, 1024, 1025, 2047, 2048, 2049, 4096, 100000]:
             for m in sorted({0, 1, 7, 8, 9, min(n, 1000), n}):
@@ -221,7 +223,7 @@ def test_total_bytes_itemised():
                     continue
                 c = (n + 1023) // 1024
                 sm = n if dtype == BF16 else (3 * n + 7) // 8
-                want = 64 + a16(4 * (c + 1)) + a16(sm) + a16((n + 1) // 2) + a16(2 * m) + m
+                want = a256(64 + 4 * (c + 1)) + a256(sm) + a256((n + 1) // 2) + a256(2 * m) + m
                 assert oracle.total_bytes(n, m, dtype) == want
 
 
@@ -273,7 +275,7 @@ def check_stream(x, cb, blob, m):
     assert p["n"] == n and p["m"] == m and p["total"] == blob.size == p["end"]
     # closed-form sizes
     sm = n if dtype == BF16 else (3 * n + 7) // 8
-    assert blob.size == 64 + a16(4 * (p["c"] + 1)) + a16(sm) + a16((n + 1) // 2) + a16(2 * m) + m
+    assert blob.size == a256(64 + 4 * (p["c"] + 1)) + a256(sm) + a256((n + 1) // 2) + a256(2 * m) + m
     assert all(not pad.any() for pad in p["pads"])
     # escapes: ascending element order, chunk-relative
     idx = np.flatnonzero(is_esc)
@@ -473,6 +475,6 @@ def test_decompress_rejects_malformed():
     bad(None, n_=n - 1)                       # caller's N differs
     bad(None, cb_=oracle.codebook_from_dec(SEQ_BF16[::-1].copy(), BF16))   # other codebook
     p = parse_stream(blob, BF16)
-    o_pos = blob.size - m - a16(2 * m)
+    o_pos = blob.size - m - a256(2 * m)
     bad(setb(o_pos + 1, 0xFF))                # position outside its chunk
     bad(setb(64, 1))                          # chunk_off[0] != 0
