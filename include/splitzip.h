@@ -65,7 +65,8 @@ typedef enum {
 enum {
   SPLITZIP_STATUS_OVERFLOW = 1u,   /* compress: escapes did not fit out_capacity; total_bytes is the size needed */
   SPLITZIP_STATUS_BAD_STREAM = 2u, /* decompress: header / offsets / positions inconsistent; offending records skipped */
-  SPLITZIP_STATUS_INTERNAL = 4u    /* compress: workspace was not initialised or is shared by overlapping calls */
+  SPLITZIP_STATUS_INTERNAL = 4u    /* compress: the workgroups' exchange timed out (workspace not initialised, shared by
+                                      overlapping calls, or the launch could not become resident) */
 };
 
 /* The three calibration tables of section 3.3.  Plain data, host memory,
@@ -103,12 +104,19 @@ size_t splitzip_fixed_bytes(uint64_t n_elems, int dtype);
 size_t splitzip_total_bytes(uint64_t n_elems, uint64_t n_escapes, int dtype);
 size_t splitzip_compress_bound(uint64_t n_elems, int dtype);
 
-/* Device scratch a compress call of up to n_elems needs (scan state of the
- * escape compaction plus staging for the escape values, about n_elems bytes).
- * A workspace must be prepared once with splitzip_workspace_init and can then
- * serve any number of compress calls of up to that size; each call leaves it
- * ready for the next.  Calls that share a workspace must not overlap in time
- * (same stream, or otherwise ordered). */
+/* Device scratch a compress call of up to n_elems needs: the words through
+ * which the workgroups of a launch exchange their escape counts, and staging
+ * for the escape values of tensors too large for one launch (about n_elems
+ * bytes in all).  A workspace must be prepared once with
+ * splitzip_workspace_init and can then serve any number of compress calls of
+ * up to that size; each call leaves it ready for the next.  Calls that share
+ * a workspace must not overlap in time (same stream, or otherwise ordered).
+ * All workgroups of a compress launch wait for one another, so they must be
+ * resident together: one launch never asks for more than the device holds,
+ * but compress calls running concurrently on several streams of one device
+ * share that room -- keep them to a handful.  A wait that does not end within
+ * two seconds gives up with SPLITZIP_STATUS_INTERNAL; re-initialise the
+ * workspace after that. */
 size_t splitzip_workspace_bytes(uint64_t n_elems, int dtype);
 int splitzip_workspace_init(void* d_workspace, size_t workspace_bytes, void* stream);
 
@@ -116,7 +124,7 @@ int splitzip_workspace_init(void* d_workspace, size_t workspace_bytes, void* str
  * detection, counting and position-ordered compaction, appendix A) on device
  * buffers, enqueued on `stream` (a hipStream_t; NULL = default stream).
  *   d_in        N words (16-bit for BF16, 8-bit for E5M2), 16-byte aligned, read only
- *   d_out       >= out_capacity bytes, 16-byte aligned; receives the stream
+ *   d_out       >= out_capacity bytes, 16-byte aligned (256 for full speed); receives the stream
  *   d_sizes     device (or pinned host) splitzip_sizes, written by the kernel
  * out_capacity below splitzip_fixed_bytes() -> SPLITZIP_ERR_CAPACITY, nothing
  * enqueued.  If the fixed part fits but the escapes do not, everything that
