@@ -262,6 +262,160 @@ __device__ inline uint32_t process_chunk_bf16(const CompressArgs& a, const uint1
   return total;
 }
 
+// ---- FP8 E5M2 (appendix "SplitZip on FP8"): byte = s eeeee mm, e = (x >> 2) & 31, a = s m1 m0 ----
+// One chunk by one wave; lane l owns the 16 consecutive elements [16 l, 16 l + 16): one 16-byte
+// load, 8 bytes of codes, 6 bytes of the 3-bit plane (lanes 2p and 2p+1 share 12 bytes: the even
+// lane stores 8 of them, the odd lane 4).  The encode table is indexed by the whole byte.
+
+// a of the four bytes of w, packed LSB first into 12 bits
+__device__ inline uint32_t pack3_e5m2(uint32_t w) {
+  const uint32_t t = ((w >> 5) & 0x04040404u) | (w & 0x03030303u);
+  const uint32_t u = (t | (t >> 5)) & 0x003f003fu;
+  return (u | (u >> 10)) & 0xfffu;
+}
+// inverse: 12 bits -> the sign and mantissa bits of four bytes, exponent field zero
+__device__ inline uint32_t unpack3_e5m2(uint32_t r) {
+  const uint32_t u = (r | (r << 10)) & 0x003f003fu;
+  const uint32_t t = (u | (u << 5)) & 0x07070707u;
+  return ((t & 0x04040404u) << 5) | (t & 0x03030303u);
+}
+
+template <bool FULL>
+__device__ inline void load_chunk_e5m2(const CompressArgs& a, uint64_t cbase, int lane, uint32_t (&w)[4]) {
+  const uint64_t g0 = cbase + lane * 16;
+  uint32_t nvalid = 16;
+  if (!FULL) nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 16 ? a.n - g0 : 16);
+  if (FULL || nvalid == 16) {
+    const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(a.in + g0));
+    w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+  } else {
+    const uint8_t* p = a.in + g0;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      uint32_t x = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if ((uint32_t)(4 * d + j) < nvalid) x |= (uint32_t)p[4 * d + j] << (8 * j);
+      w[d] = x;
+    }
+  }
+}
+
+template <bool FULL, bool STORE, typename Sink>
+__device__ inline uint32_t process_chunk_e5m2(const CompressArgs& a, const uint16_t* lut, uint32_t* park,
+                                              uint64_t cbase, int lane, const uint32_t (&w)[4], uint32_t base,
+                                              const Sink& sink) {
+  const uint64_t g0 = cbase + lane * 16;
+  uint32_t r[4], u[8];
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    r[d] = pack3_e5m2(w[d]);
+    const uint32_t b0 = w[d] & 0xffu, b1 = (w[d] >> 8) & 0xffu, b2 = (w[d] >> 16) & 0xffu, b3 = w[d] >> 24;
+    // low byte: code pair; high byte: flag pair in the same nibble layout
+    u[2 * d] = (uint32_t)lut[b0] + ((uint32_t)lut[b1] << 4);
+    u[2 * d + 1] = (uint32_t)lut[b2] + ((uint32_t)lut[b3] << 4);
+  }
+  // the lane's 48 plane bits: lo holds bits 0..31, hi bits 32..47
+  uint32_t lo = r[0] | (r[1] << 12) | (r[2] << 24), hi = (r[2] >> 8) | (r[3] << 4);
+  uint32_t code[2], F[2];
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const uint32_t x01 = byte_perm(u[4 * q + 1], u[4 * q], 0x05010400u), x23 = byte_perm(u[4 * q + 3], u[4 * q + 2], 0x05010400u);
+    code[q] = byte_perm(x23, x01, 0x05040100u);
+    F[q] = byte_perm(x23, x01, 0x07060302u);
+  }
+  if (!FULL) {
+    // elements past N contribute zero nibbles (their plane bits are already 0)
+    const uint32_t nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 16 ? a.n - g0 : 16);
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const uint32_t nv = nvalid > (uint32_t)(8 * q) ? nvalid - 8 * q : 0u;
+      const uint32_t keep = nv >= 8 ? ~0u : ((1u << (4 * nv)) - 1u);
+      code[q] &= keep;
+      F[q] &= keep;
+    }
+  }
+  if (STORE) {
+    // plane bytes of this lane pair: [12 p, 12 p + 12) of the chunk's 384
+    const uint32_t lo_up = __builtin_amdgcn_update_dpp(0u, lo, 0xF5, 0xf, 0xf, false);   // quad_perm [1,1,3,3]: the odd neighbour's lo
+    const uint64_t sm_off = (cbase / 8) * 3 + (uint32_t)(lane >> 1) * 12;
+    uint8_t* sm_dst = a.out + a.off_sm + sm_off;
+    uint32_t d0, d1;
+    if (lane & 1) {
+      d0 = (lo >> 16) | (hi << 16);
+      d1 = 0;
+    } else {
+      d0 = lo;
+      d1 = (hi & 0xffffu) | (lo_up << 16);
+    }
+    if (FULL) {
+      if (lane & 1) st_stream(reinterpret_cast<uint32_t*>(sm_dst + 8), d0);
+      else st_stream(reinterpret_cast<u32x2*>(sm_dst), u32x2{d0, d1});
+      st_stream(reinterpret_cast<u32x2*>(a.out + a.off_code + (g0 >> 1)), u32x2{code[0], code[1]});
+    } else {
+      // dword by dword up to the padded end of each plane; the pad can reach 128 bytes past the
+      // chunk's own 384 plane bytes
+      const uint64_t sm_end = a256(a.sm_bytes);
+      if (lane & 1) {
+        if (sm_off + 8 < sm_end) *reinterpret_cast<uint32_t*>(sm_dst + 8) = d0;
+      } else {
+        if (sm_off < sm_end) *reinterpret_cast<uint32_t*>(sm_dst) = d0;
+        if (sm_off + 4 < sm_end) *reinterpret_cast<uint32_t*>(sm_dst + 4) = d1;
+      }
+      const uint64_t past = (cbase / 8) * 3 + 384 + 4 * (uint32_t)lane;
+      if (lane < 32 && past < sm_end) *reinterpret_cast<uint32_t*>(a.out + a.off_sm + past) = 0;
+      if ((g0 >> 1) < a256(a.code_bytes))
+        *reinterpret_cast<u32x2*>(a.out + a.off_code + (g0 >> 1)) = u32x2{code[0], code[1]};
+    }
+  }
+  const uint32_t mine = __popc(F[0]) + __popc(F[1]);
+  const uint32_t incl = wave_incl_scan(mine);
+  const uint32_t total = wave_last(incl);
+  if (total && mine) {
+    // element order inside the chunk: lane, element
+    *reinterpret_cast<u32x4*>(park) = u32x4{w[0], w[1], w[2], w[3]};
+    const uint8_t* x = reinterpret_cast<const uint8_t*>(park);
+    uint32_t rr = base + incl - mine;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      uint32_t m = F[q];
+      while (m) {
+        const uint32_t jj = 8 * q + ((uint32_t)(__ffs(m) - 1) >> 2);
+        m &= m - 1;
+        sink.put(rr, lane * 16 + jj, ((uint32_t)x[jj] >> 2) & 0x1fu);
+        ++rr;
+      }
+    }
+  }
+  return total;
+}
+
+// the two formats as seen by the compress kernel
+struct Bf16 {
+  struct Regs { uint32_t w[2][4]; };
+  // a chunk goes the fast way if it is complete (then nothing of a pad is its business: N is a multiple of 1024 there)
+  __device__ static inline bool full(const CompressArgs& a, uint64_t cbase) { return cbase + kChunk <= a.n; }
+  template <bool FULL>
+  __device__ static inline void load(const CompressArgs& a, uint64_t cbase, int lane, Regs& r) { load_chunk_bf16<FULL>(a, cbase, lane, r.w); }
+  template <bool FULL, bool STORE, typename Sink>
+  __device__ static inline uint32_t process(const CompressArgs& a, const uint16_t* lut, uint32_t* park, uint64_t cbase,
+                                            int lane, const Regs& r, uint32_t base, const Sink& sink) {
+    return process_chunk_bf16<FULL, STORE>(a, lut, park, cbase, lane, r.w, base, sink);
+  }
+};
+struct E5m2 {
+  struct Regs { uint32_t w[4]; };
+  // the tensor's last chunk always goes the careful way: 384 plane bytes per chunk leave a pad behind an odd chunk count
+  __device__ static inline bool full(const CompressArgs& a, uint64_t cbase) { return cbase + kChunk < a.n; }
+  template <bool FULL>
+  __device__ static inline void load(const CompressArgs& a, uint64_t cbase, int lane, Regs& r) { load_chunk_e5m2<FULL>(a, cbase, lane, r.w); }
+  template <bool FULL, bool STORE, typename Sink>
+  __device__ static inline uint32_t process(const CompressArgs& a, const uint16_t* lut, uint32_t* park, uint64_t cbase,
+                                            int lane, const Regs& r, uint32_t base, const Sink& sink) {
+    return process_chunk_e5m2<FULL, STORE>(a, lut, park, cbase, lane, r.w, base, sink);
+  }
+};
+
 // header, sizes record and the zero padding behind the positions: one wave, once M is known
 __device__ void compress_write_trailer(const CompressArgs& a, uint32_t M, uint32_t err_flags, int lane) {
   const uint64_t off_val = a.off_pos + a256(2ull * M);
@@ -302,8 +456,8 @@ __device__ void compress_write_trailer(const CompressArgs& a, uint32_t M, uint32
 // all of them give M.  The wait ends when the slowest workgroup has published; it is bounded by
 // spin_ticks of the wall clock, after which the launch gives up with SPLITZIP_STATUS_INTERNAL
 // instead of hanging.
-template <int T>
-__global__ __launch_bounds__(T) void compress_bf16_kernel(const CompressArgs a) {
+template <int T, typename F>
+__global__ __launch_bounds__(T) void compress_kernel(const CompressArgs a) {
   constexpr int NW = T / 64;
   static_assert(kMaxRange <= 256 && NW >= 4 && NW <= 16, "one wave scans the range, four chunks per lane");
   __shared__ uint16_t lut[256];
@@ -336,32 +490,29 @@ __global__ __launch_bounds__(T) void compress_bf16_kernel(const CompressArgs a) 
 
   // dense pass; the next chunk's loads are issued before this chunk is worked on
   uint32_t wave_count = 0;
-  uint32_t w[2][4], nx[2][4];
+  typename F::Regs w, nx;
   if ((uint32_t)wave < nb) {
     const uint64_t cbase = (uint64_t)(r0 + wave) * kChunk;
-    if (cbase + kChunk <= a.n) load_chunk_bf16<true>(a, cbase, lane, w);
-    else load_chunk_bf16<false>(a, cbase, lane, w);
+    if (F::full(a, cbase)) F::template load<true>(a, cbase, lane, w);
+    else F::template load<false>(a, cbase, lane, w);
   }
   for (uint32_t k = wave, it = 0; k < nb; k += NW, ++it) {
     const uint64_t cbase = (uint64_t)(r0 + k) * kChunk;
     if (k + NW < nb) {
       const uint64_t nbase = cbase + (uint64_t)NW * kChunk;
-      if (nbase + kChunk <= a.n) load_chunk_bf16<true>(a, nbase, lane, nx);
-      else load_chunk_bf16<false>(a, nbase, lane, nx);
+      if (F::full(a, nbase)) F::template load<true>(a, nbase, lane, nx);
+      else F::template load<false>(a, nbase, lane, nx);
     }
     const LdsSink lds{stage_pk[wave], stage_val[wave], it << 10};
-    const uint32_t cnt = cbase + kChunk <= a.n
-                             ? process_chunk_bf16<true, true>(a, lut, park, cbase, lane, w, wave_count, lds)
-                             : process_chunk_bf16<false, true>(a, lut, park, cbase, lane, w, wave_count, lds);
+    const uint32_t cnt = F::full(a, cbase)
+                             ? F::template process<true, true>(a, lut, park, cbase, lane, w, wave_count, lds)
+                             : F::template process<false, true>(a, lut, park, cbase, lane, w, wave_count, lds);
     if (lane == 0) {
       s_off[k] = cnt;
       s_wstart[k] = (uint16_t)(wave_count < 0xffffu ? wave_count : 0xffffu);
     }
     wave_count += cnt;
-#pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-      for (int d = 0; d < 4; ++d) w[h][d] = nx[h][d];
+    w = nx;
   }
   if (lane == 0) s_red[wave] = wave_count;
   __syncthreads();
@@ -462,12 +613,12 @@ __global__ __launch_bounds__(T) void compress_bf16_kernel(const CompressArgs a) 
       for (uint32_t k = wave; k < nb; k += NW) {
         const uint64_t cbase = (uint64_t)(r0 + k) * kChunk;
         const uint32_t r = prefix + s_off[k];
-        if (cbase + kChunk <= a.n) {
-          load_chunk_bf16<true>(a, cbase, lane, w);
-          process_chunk_bf16<true, false>(a, lut, park, cbase, lane, w, r, g);
+        if (F::full(a, cbase)) {
+          F::template load<true>(a, cbase, lane, w);
+          F::template process<true, false>(a, lut, park, cbase, lane, w, r, g);
         } else {
-          load_chunk_bf16<false>(a, cbase, lane, w);
-          process_chunk_bf16<false, false>(a, lut, park, cbase, lane, w, r, g);
+          F::template load<false>(a, cbase, lane, w);
+          F::template process<false, false>(a, lut, park, cbase, lane, w, r, g);
         }
       }
     }
@@ -585,10 +736,87 @@ __device__ inline void decompress_chunk_bf16(const DecompressArgs& a, const uint
   }
 }
 
-__global__ __launch_bounds__(kThreads) void decompress_bf16_kernel(const DecompressArgs a) {
+// E5M2 dense decode of one chunk by one wave: 16 elements per lane.  Lanes 2p and 2p+1 share 12
+// plane bytes: the even lane loads the first 8, the odd lane the last 4.
+template <bool FULL>
+__device__ inline void decompress_chunk_e5m2(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane) {
+  const uint64_t g0 = cbase + lane * 16;
+  const uint64_t sm_off = (cbase / 8) * 3 + (uint32_t)(lane >> 1) * 12;
+  const uint8_t* sm_src = a.comp + a.off_sm + sm_off;
+  const uint64_t sm_end = a256(a.sm_bytes);
+  uint32_t d0 = 0, d1 = 0;
+  u32x2 cd = u32x2{0u, 0u};
+  if (lane & 1) {
+    if (FULL || sm_off + 8 < sm_end) d0 = ld_stream(reinterpret_cast<const uint32_t*>(sm_src + 8));
+  } else if (FULL || sm_off + 4 < sm_end) {
+    const u32x2 v = ld_stream(reinterpret_cast<const u32x2*>(sm_src));   // 8 bytes below a multiple of 256: both in the stream
+    d0 = v.x;
+    d1 = v.y;
+  } else if (sm_off < sm_end) {
+    d0 = ld_stream(reinterpret_cast<const uint32_t*>(sm_src));
+  }
+  if (FULL || (g0 >> 1) < a256(a.code_bytes)) cd = ld_stream(reinterpret_cast<const u32x2*>(a.comp + a.off_code + (g0 >> 1)));
+  const uint32_t d1_dn = __builtin_amdgcn_update_dpp(0u, d1, 0xA0, 0xf, 0xf, false);   // quad_perm [0,0,2,2]: the even neighbour's second dword
+  // the lane's 48 plane bits
+  const uint32_t lo = (lane & 1) ? (d1_dn >> 16) | (d0 << 16) : d0;
+  const uint32_t hi = (lane & 1) ? d0 >> 16 : d1 & 0xffffu;
+  const uint32_t r[4] = {lo & 0xfffu, (lo >> 12) & 0xfffu, (lo >> 24) | ((hi & 0xfu) << 8), (hi >> 4) & 0xfffu};
+  const uint32_t cdw[2] = {cd.x, cd.y};
+  uint32_t o[4];
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    // two code bytes -> four exponents already in place (bits 2..6 of each byte)
+    const uint32_t c01 = (cdw[d >> 1] >> (16 * (d & 1))) & 0xffu, c23 = (cdw[d >> 1] >> (16 * (d & 1) + 8)) & 0xffu;
+    o[d] = unpack3_e5m2(r[d]) | tbl[c01] | (tbl[c23] << 16);
+  }
+  uint32_t nvalid = 16;
+  if (!FULL) nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 16 ? a.n - g0 : 16);
+  if (FULL || nvalid == 16) {
+    st_stream(reinterpret_cast<u32x4*>(a.out + g0), u32x4{o[0], o[1], o[2], o[3]});
+  } else {
+    uint8_t* q = a.out + g0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+      if ((uint32_t)j < nvalid) q[j] = (uint8_t)(o[j >> 2] >> (8 * (j & 3)));
+  }
+}
+
+// the two formats as seen by the decompress kernel
+struct DBf16 {
+  // table entry for a code byte: both exponents in place for one dword of output
+  __device__ static inline uint32_t table(int cb, const uint8_t* dec) { return ((uint32_t)dec[cb & 15] << 7) | ((uint32_t)dec[cb >> 4] << 23); }
+  __device__ static inline bool full(const DecompressArgs& a, uint64_t cbase) { return cbase + kChunk <= a.n; }
+  template <bool FULL>
+  __device__ static inline void chunk(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane) { decompress_chunk_bf16<FULL>(a, tbl, cbase, lane); }
+  // the scatter correction of one element: exponent field := val, sign and mantissa from the stream
+  __device__ static inline bool patch(const DecompressArgs& a, uint64_t i, uint32_t val) {
+    const uint32_t sa = a.comp[a.off_sm + i];
+    reinterpret_cast<uint16_t*>(a.out)[i] = (uint16_t)(((sa & 0x80u) << 8) | (val << 7) | (sa & 0x7fu));
+    return true;
+  }
+};
+struct DE5m2 {
+  __device__ static inline uint32_t table(int cb, const uint8_t* dec) { return ((uint32_t)dec[cb & 15] << 2) | ((uint32_t)dec[cb >> 4] << 10); }
+  __device__ static inline bool full(const DecompressArgs& a, uint64_t cbase) { return cbase + kChunk < a.n; }
+  template <bool FULL>
+  __device__ static inline void chunk(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane) { decompress_chunk_e5m2<FULL>(a, tbl, cbase, lane); }
+  __device__ static inline bool patch(const DecompressArgs& a, uint64_t i, uint32_t val) {
+    if (val > 31u) return false;
+    const uint64_t bit = 3 * i;
+    const uint8_t* p = a.comp + a.off_sm + (bit >> 3);
+    uint32_t two = p[0];
+    if ((bit & 7) > 5) two |= (uint32_t)p[1] << 8;   // the field straddles a byte; the next byte is inside the plane
+    const uint32_t sa = (two >> (bit & 7)) & 7u;
+    a.out[i] = (uint8_t)(((sa & 4u) << 5) | (val << 2) | (sa & 3u));
+    return true;
+  }
+};
+
+template <typename F>
+__global__ __launch_bounds__(kThreads) void decompress_kernel(const DecompressArgs a) {
   __shared__ uint32_t tbl[256];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  tbl[tid] = ((uint32_t)a.dec[tid & 15] << 7) | ((uint32_t)a.dec[tid >> 4] << 23);
+  tbl[tid] = F::table(tid, a.dec);
 
   const uint32_t* tab = reinterpret_cast<const uint32_t*>(a.comp + a.off_tab);
   // M as the offset table states it; escapes are only trusted if their sections lie inside the stream
@@ -611,10 +839,10 @@ __global__ __launch_bounds__(kThreads) void decompress_bf16_kernel(const Decompr
     if (chunk >= a.n_chunks) break;
     const uint64_t cbase = (uint64_t)chunk * kChunk;
     const uint32_t lo = tab[chunk], hi = tab[chunk + 1];
-    if (cbase + kChunk <= a.n)
-      decompress_chunk_bf16<true>(a, tbl, cbase, lane);
+    if (F::full(a, cbase))
+      F::template chunk<true>(a, tbl, cbase, lane);
     else
-      decompress_chunk_bf16<false>(a, tbl, cbase, lane);
+      F::template chunk<false>(a, tbl, cbase, lane);
     // sparse overwrite (the exponent field of x at every recorded position), by the wave that
     // wrote the chunk, once its dense stores have completed
     if (hi == lo) continue;
@@ -627,13 +855,7 @@ __global__ __launch_bounds__(kThreads) void decompress_bf16_kernel(const Decompr
     for (uint32_t j = lo + lane; j < hi; j += 64) {
       const uint32_t pos = pos_arr[j];
       const uint32_t val = val_arr[j];
-      if (pos >= clen) {
-        flag_bad(a);
-        continue;
-      }
-      const uint32_t sa = a.comp[a.off_sm + cbase + pos];
-      reinterpret_cast<uint16_t*>(a.out)[cbase + pos] =
-          (uint16_t)(((sa & 0x80u) << 8) | (val << 7) | (sa & 0x7fu));
+      if (pos >= clen || !F::patch(a, cbase + pos, val)) flag_bad(a);
     }
   }
 }
@@ -720,7 +942,8 @@ bool codebook_ok(const splitzip_codebook* cb, int dtype) {
 
 template <int T>
 void launch_compress(unsigned grid, hipStream_t stream, const CompressArgs& a) {
-  hipLaunchKernelGGL(compress_bf16_kernel<T>, dim3(grid), dim3(T), 0, stream, a);
+  if (a.dtype == SPLITZIP_BF16) hipLaunchKernelGGL((compress_kernel<T, Bf16>), dim3(grid), dim3(T), 0, stream, a);
+  else hipLaunchKernelGGL((compress_kernel<T, E5m2>), dim3(grid), dim3(T), 0, stream, a);
 }
 
 // workgroups of T threads that can be resident on the current device at the same time
@@ -731,7 +954,8 @@ uint32_t resident_workgroups() {
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
   if (!cached[dev]) {
     int per_cu = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, compress_bf16_kernel<T>, T, 0) != hipSuccess || per_cu <= 0)
+    // both formats' kernels use the same LDS; the BF16 one needs more registers
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, compress_kernel<T, Bf16>, T, 0) != hipSuccess || per_cu <= 0)
       return 0;
     cached[dev] = (uint32_t)per_cu * (uint32_t)cu_count();
   }
@@ -830,7 +1054,6 @@ int splitzip_compress(const void* d_in, uint64_t n_elems, int dtype, const split
     return SPLITZIP_ERR_INVALID_ARG;
   if (!codebook_ok(cb, dtype)) return SPLITZIP_ERR_INVALID_ARG;
   if (n_elems >> 32) return SPLITZIP_ERR_UNSUPPORTED;
-  if (dtype != SPLITZIP_BF16) return SPLITZIP_ERR_UNSUPPORTED;
   if (out_capacity < splitzip_fixed_bytes(n_elems, dtype)) return SPLITZIP_ERR_CAPACITY;
   if (workspace_bytes < splitzip_workspace_bytes(n_elems, dtype)) return SPLITZIP_ERR_CAPACITY;
 
@@ -851,7 +1074,11 @@ int splitzip_compress(const void* d_in, uint64_t n_elems, int dtype, const split
   a.n_chunks = (uint32_t)L.n_chunks;
   a.dtype = (uint32_t)dtype;
   memcpy(a.dec, cb->dec, 16);
-  for (unsigned v = 0; v < 256; ++v) a.lut[v] = cb->member[v] ? cb->enc[v] : 0x100u;
+  // indexed by the exponent (BF16) or by the whole byte (E5M2: e = (x >> 2) & 31)
+  for (unsigned v = 0; v < 256; ++v) {
+    const unsigned e = dtype == SPLITZIP_BF16 ? v : (v >> 2) & 31u;
+    a.lut[v] = cb->member[e] ? cb->enc[e] : 0x100u;
+  }
   static const int spin_env = env_int("SPLITZIP_SPIN_TICKS", 0);
   a.spin_ticks = spin_env ? (uint64_t)spin_env : kSpinTicks;
 
@@ -904,7 +1131,6 @@ int splitzip_decompress(const void* d_comp, size_t comp_bytes, uint64_t n_elems,
     return SPLITZIP_ERR_INVALID_ARG;
   if (!codebook_ok(cb, dtype)) return SPLITZIP_ERR_INVALID_ARG;
   if (n_elems >> 32) return SPLITZIP_ERR_UNSUPPORTED;
-  if (dtype != SPLITZIP_BF16) return SPLITZIP_ERR_UNSUPPORTED;
   if (comp_bytes < splitzip_fixed_bytes(n_elems, dtype)) return SPLITZIP_ERR_CAPACITY;
 
   const Layout L = make_layout(n_elems, dtype);
@@ -927,7 +1153,8 @@ int splitzip_decompress(const void* d_comp, size_t comp_bytes, uint64_t n_elems,
   memcpy(a.dec, cb->dec, 16);
 
   const unsigned grid = a.n_tiles ? a.n_tiles : 1u;
-  hipLaunchKernelGGL(decompress_bf16_kernel, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
+  if (dtype == SPLITZIP_BF16) hipLaunchKernelGGL(decompress_kernel<DBf16>, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
+  else hipLaunchKernelGGL(decompress_kernel<DE5m2>, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
   return hipGetLastError() == hipSuccess ? SPLITZIP_OK : SPLITZIP_ERR_HIP;
 }
 

@@ -100,7 +100,7 @@ def calibrated(dtype, seed=1, tokens=1024, layer=0, kind="K"):
     return oracle.calibrate(synth(dtype, tokens, seed, layer, kind), DT[dtype])
 
 
-DTYPES = [sz.BF16]
+DTYPES = [sz.BF16, sz.FP8_E5M2]
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
@@ -140,6 +140,18 @@ def test_all_bf16_bit_patterns():
              oracle.codebook_from_dec(np.array([0, 255] + list(range(120, 134)), np.uint8), oracle.BF16)]
     for i, cb in enumerate(books):
         check_parity(g, x, cb, f"patterns/cb{i}")
+
+
+def test_all_e5m2_bit_patterns():
+    """every byte value, many times over in random order, under a calibrated-like, an adversarial and an extreme codebook"""
+    rng = np.random.default_rng(8)
+    x = rng.permutation(np.tile(np.arange(256, dtype=np.uint8), 41))[:-3].copy()
+    g = Gpu(x.size, sz.FP8_E5M2)
+    books = [oracle.codebook_from_dec(np.arange(7, 23, dtype=np.uint8), oracle.E5M2),
+             oracle.codebook_from_dec(np.array([0, 31, 1, 30, 2, 29, 3, 28, 4, 27, 5, 26, 6, 25, 24, 23], np.uint8), oracle.E5M2),
+             oracle.codebook_from_dec(np.arange(16, 32, dtype=np.uint8), oracle.E5M2)]
+    for i, cb in enumerate(books):
+        check_parity(g, x, cb, f"e5m2 patterns/cb{i}")
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
@@ -250,6 +262,16 @@ def test_bad_stream_is_flagged_not_followed():
     c = (n + 1023) // 1024
     y, st = run(set_(64 + 4 * c + 3, 0x7F))  # M in the offset table far beyond the stream
     assert st & sz.STATUS_BAD_STREAM
+
+
+def test_full_size_e5m2_tensor():
+    """config 4 at its real tensor size [32768, 8, 128] E5M2 (32 MiB): V of layer 17"""
+    n = 32768 * 1024
+    g = Gpu(n, sz.FP8_E5M2)
+    cb_or = calibrated(sz.FP8_E5M2, seed=1, tokens=1024, layer=0, kind="V")
+    x = kv_synth.to_numpy_words(kv_synth.kv_e5m2(32768, 0, 17, "V", device="cuda"))
+    total, m = check_parity(g, x, cb_or, "config4 L17V")
+    print(f"config4 L17V: eps={m / n:.5f} ratio={n / total:.4f}", flush=True)
 
 
 def test_full_size_tensors_of_the_benchmark_workload():
