@@ -181,13 +181,13 @@ def main():
         "B_hide_GBps": round(min(comp_gbps, dec_gbps) / (total_raw / blob_bytes), 1),
         "paper_context": {"compress_GBps": 613.3, "decompress_GBps": 2181.8, "ratio": 1.324, "hardware": "NVIDIA H200, real Qwen3-32B BF16 KV"},
         "roofline": {
-            "kernel": "compress_bf16_kernel" if dtype == sz.BF16 else "compress_e5m2_kernel",
+            "kernel": "compress_kernel<1024, Bf16>" if dtype == sz.BF16 else "compress_kernel<1024, E5m2>",
             "bound": "hbm", "achieved": round(c_ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": round(c_ach / HBM_PEAK_GBPS, 4), "traffic": None,
             "launch_us": round(c_launch_us, 2), "algorithmic_bytes_per_launch": int(alg_bytes),
         },
         "roofline_decompress": {
-            "kernel": "decompress_bf16_kernel" if dtype == sz.BF16 else "decompress_e5m2_kernel",
+            "kernel": "decompress_kernel<DBf16>" if dtype == sz.BF16 else "decompress_kernel<DE5m2>",
             "bound": "hbm", "achieved": round(d_ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": round(d_ach / HBM_PEAK_GBPS, 4), "traffic": None,
             "launch_us": round(d_launch_us, 2), "algorithmic_bytes_per_launch": int(alg_bytes),
