@@ -153,6 +153,40 @@ int splitzip_decompress(const void* d_comp, size_t comp_bytes, uint64_t n_elems,
                         const splitzip_codebook* cb, void* d_out, splitzip_sizes* d_sizes,
                         void* stream);
 
+/* Several tensors per launch -- all layers' K and V of a KV cache, or of a
+ * prefill chunk (the pipeline of the appendix "The Potential of Hiding Codec
+ * Overhead with Pipeline Overlap" feeds the codec such batches).  Each item is
+ * compressed exactly as splitzip_compress would (same stream bytes); what a
+ * single call pays per tensor for the exchange between workgroups, the wait
+ * for the slowest of them and the launch is paid once per launch of up to 64
+ * tensors, because the exchange of one tensor is hidden under the dense pass
+ * of the next.  `items` is a HOST array, read before the call returns.
+ * d_sizes is a device array of n_items records.  Argument errors are found
+ * before anything is enqueued.  Same workspace rules as splitzip_compress
+ * (size it for the largest item). */
+typedef struct {
+  const void* d_in;
+  uint64_t n_elems;
+  void* d_out;
+  size_t out_capacity;
+  const splitzip_codebook* cb;
+} splitzip_item;
+int splitzip_compress_batch(const splitzip_item* items, uint32_t n_items, int dtype, void* d_workspace,
+                            size_t workspace_bytes, splitzip_sizes* d_sizes, void* stream);
+
+/* Several streams per launch; each item as splitzip_decompress.  d_sizes
+ * (nullable) is ONE record: the status bits of all items are OR-ed into it,
+ * total_bytes / n_escapes are those of whichever item wrote last. */
+typedef struct {
+  const void* d_comp;
+  size_t comp_bytes;
+  uint64_t n_elems;
+  void* d_out;
+  const splitzip_codebook* cb;
+} splitzip_ditem;
+int splitzip_decompress_batch(const splitzip_ditem* items, uint32_t n_items, int dtype, splitzip_sizes* d_sizes,
+                              void* stream);
+
 /* Measurement aid: a plain streaming kernel that reads read_bytes from d_src
  * and writes write_bytes (<= read_bytes) to d_dst with 128-bit accesses, i.e.
  * the memory traffic of the codec without its arithmetic.  Both sizes are

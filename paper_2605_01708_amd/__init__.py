@@ -12,18 +12,24 @@ from .binding import (  # noqa: F401
     STATUS_INTERNAL,
     STATUS_OVERFLOW,
     Codebook,
+    CompressBatch,
+    DecompressBatch,
     SplitZipError,
     Workspace,
     calibrate,
     codebook_from_dec,
     compress,
+    compress_batch,
     compress_bound,
     decompress,
+    decompress_batch,
     fixed_bytes,
     lib,
     lib_path,
     new_sizes,
+    new_sizes_array,
     read_sizes,
+    read_sizes_array,
     total_bytes,
     traffic_probe,
     workspace_bytes,

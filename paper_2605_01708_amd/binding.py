@@ -38,6 +38,16 @@ class _CSizes(C.Structure):
                 ("reserved", C.c_uint32)]
 
 
+class _CItem(C.Structure):
+    _fields_ = [("d_in", C.c_void_p), ("n_elems", C.c_uint64), ("d_out", C.c_void_p), ("out_capacity", C.c_size_t),
+                ("cb", C.POINTER(_CCodebook))]
+
+
+class _CDItem(C.Structure):
+    _fields_ = [("d_comp", C.c_void_p), ("comp_bytes", C.c_size_t), ("n_elems", C.c_uint64), ("d_out", C.c_void_p),
+                ("cb", C.POINTER(_CCodebook))]
+
+
 _lib = None
 
 
@@ -71,6 +81,10 @@ def lib():
         L.splitzip_compress.argtypes = [vp, u64, i, cbp, vp, sz, vp, sz, vp, vp]
         L.splitzip_decompress.restype = i
         L.splitzip_decompress.argtypes = [vp, sz, u64, i, cbp, vp, vp, vp]
+        L.splitzip_compress_batch.restype = i
+        L.splitzip_compress_batch.argtypes = [C.POINTER(_CItem), C.c_uint32, i, vp, sz, vp, vp]
+        L.splitzip_decompress_batch.restype = i
+        L.splitzip_decompress_batch.argtypes = [C.POINTER(_CDItem), C.c_uint32, i, vp, vp]
         L.splitzip_traffic_probe.restype = i
         L.splitzip_traffic_probe.argtypes = [vp, sz, vp, sz, vp]
         _lib = L
@@ -192,6 +206,69 @@ def decompress(comp: torch.Tensor, comp_bytes: int, n_elems: int, cb: Codebook, 
     _check(lib().splitzip_decompress(comp.data_ptr(), comp_bytes, n_elems, cb.dtype, C.byref(cb.c),
                                      out.data_ptr(), sizes.data_ptr() if sizes is not None else None,
                                      _stream_ptr(stream)), "splitzip_decompress")
+
+
+def new_sizes_array(n: int, device="cuda") -> torch.Tensor:
+    """n zeroed device splitzip_sizes records, one row of 3 x int64 each."""
+    return torch.zeros(n, 3, dtype=torch.int64, device=device)
+
+
+def read_sizes_array(sizes: torch.Tensor):
+    """[(total_bytes, n_escapes, status), ...] -- copies to the host (synchronises)."""
+    h = sizes.cpu().tolist()
+    return [(int(r[0]), int(r[1]), int(r[2]) & 0xFFFFFFFF) for r in h]
+
+
+class CompressBatch:
+    """The marshalled item list of a splitzip_compress_batch call; build once, launch many times."""
+
+    def __init__(self, xs, cbs, outs, capacities=None):
+        if not (len(xs) == len(cbs) == len(outs)):
+            raise ValueError("xs, cbs and outs must have the same length")
+        self.n = len(xs)
+        self.dtype = cbs[0].dtype if cbs else BF16
+        self.items = (_CItem * max(self.n, 1))()
+        self._keep = (list(xs), list(cbs), list(outs))
+        for k, (x, cb, out) in enumerate(zip(xs, cbs, outs)):
+            if x.element_size() != _elem_size(cb.dtype) or not x.is_contiguous() or cb.dtype != self.dtype:
+                raise ValueError("every x must be a contiguous tensor of raw words of one dtype")
+            cap = out.numel() * out.element_size() if capacities is None else capacities[k]
+            self.items[k] = _CItem(x.data_ptr(), x.numel(), out.data_ptr(), cap, C.pointer(cb.c))
+
+    def launch(self, workspace: "Workspace", sizes: torch.Tensor, stream=None) -> None:
+        _check(lib().splitzip_compress_batch(self.items, self.n, self.dtype, workspace.buf.data_ptr(), workspace.nbytes,
+                                             sizes.data_ptr(), _stream_ptr(stream)), "splitzip_compress_batch")
+
+
+class DecompressBatch:
+    """The marshalled item list of a splitzip_decompress_batch call."""
+
+    def __init__(self, comps, comp_bytes, n_elems, cbs, outs):
+        if not (len(comps) == len(comp_bytes) == len(n_elems) == len(cbs) == len(outs)):
+            raise ValueError("all lists must have the same length")
+        self.n = len(comps)
+        self.dtype = cbs[0].dtype if cbs else BF16
+        self.items = (_CDItem * max(self.n, 1))()
+        self._keep = (list(comps), list(cbs), list(outs))
+        for k, (c, cbytes, n, cb, out) in enumerate(zip(comps, comp_bytes, n_elems, cbs, outs)):
+            if out.numel() < n or out.element_size() != _elem_size(cb.dtype) or not out.is_contiguous() or cb.dtype != self.dtype:
+                raise ValueError("every out must be a contiguous tensor of at least n_elems raw words of one dtype")
+            self.items[k] = _CDItem(c.data_ptr(), cbytes, n, out.data_ptr(), C.pointer(cb.c))
+
+    def launch(self, sizes: torch.Tensor | None = None, stream=None) -> None:
+        _check(lib().splitzip_decompress_batch(self.items, self.n, self.dtype,
+                                               sizes.data_ptr() if sizes is not None else None, _stream_ptr(stream)),
+               "splitzip_decompress_batch")
+
+
+def compress_batch(xs, cbs, outs, workspace: Workspace, sizes: torch.Tensor, stream=None, capacities=None) -> None:
+    """splitzip_compress_batch: xs[k] -> outs[k] with codebook cbs[k]; sizes = new_sizes_array(len(xs))."""
+    CompressBatch(xs, cbs, outs, capacities).launch(workspace, sizes, stream)
+
+
+def decompress_batch(comps, comp_bytes, n_elems, cbs, outs, sizes: torch.Tensor | None = None, stream=None) -> None:
+    """splitzip_decompress_batch: comps[k] (comp_bytes[k] bytes, n_elems[k] words) -> outs[k]."""
+    DecompressBatch(comps, comp_bytes, n_elems, cbs, outs).launch(sizes, stream)
 
 
 def traffic_probe(src: torch.Tensor, read_bytes: int, dst: torch.Tensor, write_bytes: int, stream=None) -> None:

@@ -111,19 +111,38 @@ __device__ inline T ld_agent(const T* p) { return __hip_atomic_load(p, __ATOMIC_
 // compress
 // ---------------------------------------------------------------------------
 
-struct CompressArgs {
+// what the dense pass and the trailer need to know of one tensor and its stream
+struct Planes {
   const uint8_t* in;
   uint8_t* out;
   uint64_t n, capacity;
+  uint64_t off_tab, off_sm, off_code, off_pos, sm_bytes, code_bytes;
+  uint32_t n_chunks, dtype;
+};
+
+__host__ __device__ inline Planes make_planes(const void* in, void* out, uint64_t n, uint64_t capacity, int dtype) {
+  const Layout L = make_layout(n, dtype);
+  Planes p;
+  p.in = static_cast<const uint8_t*>(in);
+  p.out = static_cast<uint8_t*>(out);
+  p.n = n;
+  p.capacity = capacity;
+  p.off_tab = L.off_tab; p.off_sm = L.off_sm; p.off_code = L.off_code; p.off_pos = L.off_pos;
+  p.sm_bytes = L.sm_bytes; p.code_bytes = L.code_bytes;
+  p.n_chunks = (uint32_t)L.n_chunks;
+  p.dtype = (uint32_t)dtype;
+  return p;
+}
+
+struct CompressArgs {
+  Planes p;
   uint32_t* ws_hdr;      // [0] epoch of this launch, [1] escapes of the earlier segments, [2] sticky error flags
   uint64_t* state;       // one word per workgroup: epoch << 32 | escapes in its range
   uint8_t* val_stage;    // n bytes: escape values of a call of several launches, until M is known
   splitzip_sizes* sizes;
-  uint64_t off_tab, off_sm, off_code, off_pos, sm_bytes, code_bytes, spin_ticks;
-  uint32_t n_chunks;     // of the whole tensor
+  uint64_t spin_ticks;
   uint32_t seg_chunk0, seg_chunks;   // the chunks this launch covers
   uint32_t flags;        // kSegFirst | kSegLast
-  uint32_t dtype;
   uint32_t expect_wgs;   // workgroups whose counts are awaited (= the grid size)
   uint8_t dec[16];
   uint16_t lut[256];     // exponent -> code | (non-member ? 0x100 : 0)   (the "marked" table of appendix A)
@@ -195,7 +214,7 @@ __device__ inline void emit_half_bf16(uint32_t* park, const uint32_t (&w)[4], ui
 // One chunk's words into registers: lane l holds elements [8 l, 8 l + 8) of each half-chunk.
 // Elements past N read as zero.
 template <bool FULL>
-__device__ inline void load_chunk_bf16(const CompressArgs& a, uint64_t cbase, int lane, uint32_t (&w)[2][4]) {
+__device__ inline void load_chunk_bf16(const Planes& a, uint64_t cbase, int lane, uint32_t (&w)[2][4]) {
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     const uint64_t g0 = cbase + h * kHalf + lane * 8;   // first element of this lane's group
@@ -220,7 +239,7 @@ __device__ inline void load_chunk_bf16(const CompressArgs& a, uint64_t cbase, in
 // ranks inside the chunk, escape records into `sink` starting at rank `base`.
 // Returns the chunk's escape count (wave-uniform).
 template <bool FULL, bool STORE, typename Sink>
-__device__ inline uint32_t process_chunk_bf16(const CompressArgs& a, const uint16_t* lut, uint32_t* park,
+__device__ inline uint32_t process_chunk_bf16(const Planes& a, const uint16_t* lut, uint32_t* park,
                                               uint64_t cbase, int lane, const uint32_t (&w)[2][4], uint32_t base,
                                               const Sink& sink) {
   uint32_t F[2];
@@ -281,7 +300,7 @@ __device__ inline uint32_t unpack3_e5m2(uint32_t r) {
 }
 
 template <bool FULL>
-__device__ inline void load_chunk_e5m2(const CompressArgs& a, uint64_t cbase, int lane, uint32_t (&w)[4]) {
+__device__ inline void load_chunk_e5m2(const Planes& a, uint64_t cbase, int lane, uint32_t (&w)[4]) {
   const uint64_t g0 = cbase + lane * 16;
   uint32_t nvalid = 16;
   if (!FULL) nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 16 ? a.n - g0 : 16);
@@ -302,7 +321,7 @@ __device__ inline void load_chunk_e5m2(const CompressArgs& a, uint64_t cbase, in
 }
 
 template <bool FULL, bool STORE, typename Sink>
-__device__ inline uint32_t process_chunk_e5m2(const CompressArgs& a, const uint16_t* lut, uint32_t* park,
+__device__ inline uint32_t process_chunk_e5m2(const Planes& a, const uint16_t* lut, uint32_t* park,
                                               uint64_t cbase, int lane, const uint32_t (&w)[4], uint32_t base,
                                               const Sink& sink) {
   const uint64_t g0 = cbase + lane * 16;
@@ -394,11 +413,11 @@ __device__ inline uint32_t process_chunk_e5m2(const CompressArgs& a, const uint1
 struct Bf16 {
   struct Regs { uint32_t w[2][4]; };
   // a chunk goes the fast way if it is complete (then nothing of a pad is its business: N is a multiple of 1024 there)
-  __device__ static inline bool full(const CompressArgs& a, uint64_t cbase) { return cbase + kChunk <= a.n; }
+  __device__ static inline bool full(const Planes& a, uint64_t cbase) { return cbase + kChunk <= a.n; }
   template <bool FULL>
-  __device__ static inline void load(const CompressArgs& a, uint64_t cbase, int lane, Regs& r) { load_chunk_bf16<FULL>(a, cbase, lane, r.w); }
+  __device__ static inline void load(const Planes& a, uint64_t cbase, int lane, Regs& r) { load_chunk_bf16<FULL>(a, cbase, lane, r.w); }
   template <bool FULL, bool STORE, typename Sink>
-  __device__ static inline uint32_t process(const CompressArgs& a, const uint16_t* lut, uint32_t* park, uint64_t cbase,
+  __device__ static inline uint32_t process(const Planes& a, const uint16_t* lut, uint32_t* park, uint64_t cbase,
                                             int lane, const Regs& r, uint32_t base, const Sink& sink) {
     return process_chunk_bf16<FULL, STORE>(a, lut, park, cbase, lane, r.w, base, sink);
   }
@@ -406,18 +425,19 @@ struct Bf16 {
 struct E5m2 {
   struct Regs { uint32_t w[4]; };
   // the tensor's last chunk always goes the careful way: 384 plane bytes per chunk leave a pad behind an odd chunk count
-  __device__ static inline bool full(const CompressArgs& a, uint64_t cbase) { return cbase + kChunk < a.n; }
+  __device__ static inline bool full(const Planes& a, uint64_t cbase) { return cbase + kChunk < a.n; }
   template <bool FULL>
-  __device__ static inline void load(const CompressArgs& a, uint64_t cbase, int lane, Regs& r) { load_chunk_e5m2<FULL>(a, cbase, lane, r.w); }
+  __device__ static inline void load(const Planes& a, uint64_t cbase, int lane, Regs& r) { load_chunk_e5m2<FULL>(a, cbase, lane, r.w); }
   template <bool FULL, bool STORE, typename Sink>
-  __device__ static inline uint32_t process(const CompressArgs& a, const uint16_t* lut, uint32_t* park, uint64_t cbase,
+  __device__ static inline uint32_t process(const Planes& a, const uint16_t* lut, uint32_t* park, uint64_t cbase,
                                             int lane, const Regs& r, uint32_t base, const Sink& sink) {
     return process_chunk_e5m2<FULL, STORE>(a, lut, park, cbase, lane, r.w, base, sink);
   }
 };
 
 // header, sizes record and the zero padding behind the positions: one wave, once M is known
-__device__ void compress_write_trailer(const CompressArgs& a, uint32_t M, uint32_t err_flags, int lane) {
+__device__ void compress_write_trailer(const Planes& a, const uint8_t* dec, splitzip_sizes* sizes, uint32_t M,
+                                       uint32_t err_flags, int lane) {
   const uint64_t off_val = a.off_pos + a256(2ull * M);
   const uint64_t total = off_val + M;
   for (uint64_t i = 2ull * M + lane; i < a256(2ull * M); i += 64)
@@ -437,41 +457,182 @@ __device__ void compress_write_trailer(const CompressArgs& a, uint32_t M, uint32
     h[8] = (uint32_t)total; h[9] = (uint32_t)(total >> 32);
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-      h[10 + i] = a.dec[4 * i] | (a.dec[4 * i + 1] << 8) | (a.dec[4 * i + 2] << 16) | ((uint32_t)a.dec[4 * i + 3] << 24);
+      h[10 + i] = dec[4 * i] | (dec[4 * i + 1] << 8) | (dec[4 * i + 2] << 16) | ((uint32_t)dec[4 * i + 3] << 24);
     uint4* ho = reinterpret_cast<uint4*>(a.out);
 #pragma unroll
     for (int i = 0; i < 4; ++i) ho[i] = make_uint4(h[4 * i], h[4 * i + 1], h[4 * i + 2], h[4 * i + 3]);
-    a.sizes->total_bytes = total;
-    a.sizes->n_escapes = M;
-    a.sizes->status = (total > a.capacity ? SPLITZIP_STATUS_OVERFLOW : 0u) | err_flags;
-    a.sizes->reserved = 0;
+    sizes->total_bytes = total;
+    sizes->n_escapes = M;
+    sizes->status = (total > a.capacity ? SPLITZIP_STATUS_OVERFLOW : 0u) | err_flags;
+    sizes->reserved = 0;
   }
 }
 
+// ---- building blocks of the compress kernels ----
+// A workgroup owns a contiguous range [r0, r0 + nb) of a tensor's chunks, nb <= kMaxRange, dealt
+// round-robin to its NW waves (chunk k of the range belongs to wave k mod NW).  LDS per range:
+//   stage_pk/val[wave][.]  the wave's escape records, position | (k / NW) << 10 and exponent
+//   s_off[k]               escapes of chunk k, after the scan: escapes of the chunks before it
+//   s_wstart[k]            records its wave had staged before chunk k
+struct RangeLds {
+  uint16_t* stage_pk;    // this wave's kStageCap entries
+  uint8_t* stage_val;
+  uint32_t* s_off;       // kMaxRange + 1
+  uint16_t* s_wstart;    // kMaxRange
+};
+
+// this workgroup's share of `chunks` chunks starting at chunk0: dealt evenly, the first `rem`
+// workgroups get one more
+__device__ inline void my_range(uint32_t chunk0, uint32_t chunks, uint32_t wgs, uint32_t b, uint32_t& r0, uint32_t& nb) {
+  const uint32_t per = chunks / wgs, rem = chunks % wgs;
+  nb = per + (b < rem ? 1u : 0u);
+  r0 = chunk0 + b * per + (b < rem ? b : rem);
+}
+
+// dense pass of one wave over its chunks of the range; the next chunk's loads are issued before
+// this chunk is worked on.  Returns the wave's escape count.
+template <int NW, typename F>
+__device__ inline uint32_t dense_pass(const Planes& P, const uint16_t* lut, uint32_t* park, const RangeLds& L,
+                                      uint32_t r0, uint32_t nb, int wave, int lane) {
+  uint32_t wave_count = 0;
+  typename F::Regs w, nx;
+  if ((uint32_t)wave < nb) {
+    const uint64_t cbase = (uint64_t)(r0 + wave) * kChunk;
+    if (F::full(P, cbase)) F::template load<true>(P, cbase, lane, w);
+    else F::template load<false>(P, cbase, lane, w);
+  }
+  for (uint32_t k = wave, it = 0; k < nb; k += NW, ++it) {
+    const uint64_t cbase = (uint64_t)(r0 + k) * kChunk;
+    if (k + NW < nb) {
+      const uint64_t nbase = cbase + (uint64_t)NW * kChunk;
+      if (F::full(P, nbase)) F::template load<true>(P, nbase, lane, nx);
+      else F::template load<false>(P, nbase, lane, nx);
+    }
+    const LdsSink lds{L.stage_pk, L.stage_val, it << 10};
+    const uint32_t cnt = F::full(P, cbase) ? F::template process<true, true>(P, lut, park, cbase, lane, w, wave_count, lds)
+                                           : F::template process<false, true>(P, lut, park, cbase, lane, w, wave_count, lds);
+    if (lane == 0) {
+      L.s_off[k] = cnt;
+      L.s_wstart[k] = (uint16_t)(wave_count < 0xffffu ? wave_count : 0xffffu);
+    }
+    wave_count += cnt;
+    w = nx;
+  }
+  return wave_count;
+}
+
+// one wave: exclusive offsets of the range's chunks, four per lane, in place; s_off[nb] = total
+__device__ inline void scan_range(uint32_t* s_off, uint32_t nb, int lane) {
+  uint32_t v[4], sum = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const uint32_t q = 4 * lane + j;
+    v[j] = q < nb ? s_off[q] : 0u;
+    sum += v[j];
+  }
+  const uint32_t incl = wave_incl_scan(sum);
+  uint32_t run = incl - sum;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const uint32_t q = 4 * lane + j;
+    if (q < nb) s_off[q] = run;
+    run += v[j];
+  }
+  if (lane == 63) s_off[nb] = incl;
+}
+
+// one wave: wait until the words of all `wgs` workgroups carry `tag`, then sum the counts of the
+// workgroups before b (lower) and of all.  Returns false if the wait was given up: it is bounded
+// by spin_ticks of the 100 MHz wall clock (or not begun at all if `dead`).
+__device__ inline bool exchange(const uint64_t* state, uint32_t tag, uint32_t wgs, uint32_t b, int lane,
+                                uint64_t spin_ticks, bool dead, uint32_t& lower, uint32_t& all) {
+  uint32_t lo = 0, al = 0, spins = 0;
+  bool ok = !dead;
+  const uint64_t t0 = wall_clock64();
+  while (ok) {
+    lo = 0;
+    al = 0;
+    int ready = 1;
+    for (uint32_t i = lane; i < wgs; i += 64) {
+      const uint64_t s = ld_agent(&state[i]);
+      if ((uint32_t)(s >> 32) != tag) ready = 0;
+      al += (uint32_t)s;
+      lo += i < b ? (uint32_t)s : 0u;
+    }
+    if (__ballot(ready) == ~0ull) break;
+    if ((++spins & 15u) == 0 && (uint64_t)(wall_clock64() - t0) > spin_ticks) ok = false;
+    else __builtin_amdgcn_s_sleep(1);
+  }
+  lower = wave_last(wave_incl_scan(lo));
+  all = wave_last(wave_incl_scan(al));
+  return ok;
+}
+
+// all waves: the range's entries of the stream's offset table and this wave's escape records to
+// their final rank.  `prefix` = escapes before the range in the whole tensor.
+template <int NW, typename F>
+__device__ inline void write_out(const Planes& P, const uint16_t* lut, uint32_t* park, const RangeLds& L,
+                                 uint32_t r0, uint32_t nb, uint32_t wave_count, uint32_t prefix,
+                                 const GlobalSink& g, int tid, int wave, int lane) {
+  uint32_t* tab = reinterpret_cast<uint32_t*>(P.out + P.off_tab);
+  if ((uint32_t)tid < nb) tab[r0 + tid] = prefix + L.s_off[tid];
+  if (wave_count <= kStageCap) {
+    // staged record i of this wave belongs to chunk k and is the (i - s_wstart[k])-th of it
+    for (uint32_t i = lane; i < wave_count; i += 64) {
+      const uint32_t pk = L.stage_pk[i], k = (pk >> 10) * NW + wave;
+      g.put(prefix + L.s_off[k] + (i - L.s_wstart[k]), pk & 1023u, L.stage_val[i]);
+    }
+  } else {
+    // more escapes than the staging holds: go over this wave's chunks again and write the
+    // records straight to their place
+    typename F::Regs w;
+    for (uint32_t k = wave; k < nb; k += NW) {
+      const uint64_t cbase = (uint64_t)(r0 + k) * kChunk;
+      const uint32_t r = prefix + L.s_off[k];
+      if (F::full(P, cbase)) {
+        F::template load<true>(P, cbase, lane, w);
+        F::template process<true, false>(P, lut, park, cbase, lane, w, r, g);
+      } else {
+        F::template load<false>(P, cbase, lane, w);
+        F::template process<false, false>(P, lut, park, cbase, lane, w, r, g);
+      }
+    }
+  }
+}
+
+// where escape records of a tensor go when M is final: positions and, behind them, values
+__device__ inline GlobalSink final_sink(const Planes& P, uint32_t M) {
+  const uint64_t off_val = P.off_pos + a256(2ull * M);
+  GlobalSink g;
+  g.pos = reinterpret_cast<uint16_t*>(P.out + P.off_pos);
+  g.pos_room = P.capacity > P.off_pos ? (P.capacity - P.off_pos) / 2 : 0;
+  g.val = P.out + off_val;
+  g.val_room = P.capacity > off_val ? P.capacity - off_val : 0;
+  return g;
+}
+
 // One launch covers the chunks [seg_chunk0, seg_chunk0 + seg_chunks) with a grid in which every
-// workgroup is resident at the same time.  Workgroup b owns a contiguous range of at most
-// kMaxRange chunks, dealt round-robin to its waves.  After its dense pass it publishes the escape
+// workgroup is resident at the same time.  After its dense pass a workgroup publishes the escape
 // count of its range in state[b] (tagged with the launch's epoch, so that the words never need
 // clearing) and one wave reads the words of all workgroups: the counts before b give its offset,
-// all of them give M.  The wait ends when the slowest workgroup has published; it is bounded by
-// spin_ticks of the wall clock, after which the launch gives up with SPLITZIP_STATUS_INTERNAL
-// instead of hanging.
+// all of them give M.  The wait ends when the slowest workgroup has published.
 template <int T, typename F>
 __global__ __launch_bounds__(T) void compress_kernel(const CompressArgs a) {
   constexpr int NW = T / 64;
   static_assert(kMaxRange <= 256 && NW >= 4 && NW <= 16, "one wave scans the range, four chunks per lane");
   __shared__ uint16_t lut[256];
-  __shared__ uint16_t stage_pk[NW][kStageCap];   // position | (chunk's index in the range / NW) << 10
+  __shared__ uint16_t stage_pk[NW][kStageCap];
   __shared__ uint8_t stage_val[NW][kStageCap];
-  __shared__ uint32_t s_off[kMaxRange + 1];      // escapes of chunk k of the range, then of the chunks before it
-  __shared__ uint16_t s_wstart[kMaxRange];       // records its wave had staged before chunk k
+  __shared__ uint32_t s_off[kMaxRange + 1];
+  __shared__ uint16_t s_wstart[kMaxRange];
   __shared__ u32x4 s_park[T];
   __shared__ uint32_t s_red[16];
   __shared__ uint32_t s_misc[4];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: loops over chunks stay scalar
-  const uint32_t W = a.expect_wgs, b = blockIdx.x;
+  const uint32_t b = blockIdx.x;
   uint32_t* park = reinterpret_cast<uint32_t*>(&s_park[tid]);
+  const RangeLds L{stage_pk[wave], stage_val[wave], s_off, s_wstart};
 #ifdef EXP_TIMING
   const uint64_t ts0 = wall_clock64();
 #endif
@@ -483,37 +644,9 @@ __global__ __launch_bounds__(T) void compress_kernel(const CompressArgs a) {
   const bool single = (a.flags & (kSegFirst | kSegLast)) == (kSegFirst | kSegLast);
   __syncthreads();
 
-  // this workgroup's range: seg_chunks dealt evenly, the first `rem` workgroups get one more
-  const uint32_t per = a.seg_chunks / gridDim.x, rem = a.seg_chunks % gridDim.x;
-  const uint32_t nb = per + (b < rem ? 1u : 0u);
-  const uint32_t r0 = a.seg_chunk0 + b * per + (b < rem ? b : rem);
-
-  // dense pass; the next chunk's loads are issued before this chunk is worked on
-  uint32_t wave_count = 0;
-  typename F::Regs w, nx;
-  if ((uint32_t)wave < nb) {
-    const uint64_t cbase = (uint64_t)(r0 + wave) * kChunk;
-    if (F::full(a, cbase)) F::template load<true>(a, cbase, lane, w);
-    else F::template load<false>(a, cbase, lane, w);
-  }
-  for (uint32_t k = wave, it = 0; k < nb; k += NW, ++it) {
-    const uint64_t cbase = (uint64_t)(r0 + k) * kChunk;
-    if (k + NW < nb) {
-      const uint64_t nbase = cbase + (uint64_t)NW * kChunk;
-      if (F::full(a, nbase)) F::template load<true>(a, nbase, lane, nx);
-      else F::template load<false>(a, nbase, lane, nx);
-    }
-    const LdsSink lds{stage_pk[wave], stage_val[wave], it << 10};
-    const uint32_t cnt = F::full(a, cbase)
-                             ? F::template process<true, true>(a, lut, park, cbase, lane, w, wave_count, lds)
-                             : F::template process<false, true>(a, lut, park, cbase, lane, w, wave_count, lds);
-    if (lane == 0) {
-      s_off[k] = cnt;
-      s_wstart[k] = (uint16_t)(wave_count < 0xffffu ? wave_count : 0xffffu);
-    }
-    wave_count += cnt;
-    w = nx;
-  }
+  uint32_t r0, nb;
+  my_range(a.seg_chunk0, a.seg_chunks, gridDim.x, b, r0, nb);
+  const uint32_t wave_count = dense_pass<NW, F>(a.p, lut, park, L, r0, nb, wave, lane);
   if (lane == 0) s_red[wave] = wave_count;
   __syncthreads();
 #ifdef EXP_TIMING
@@ -521,67 +654,28 @@ __global__ __launch_bounds__(T) void compress_kernel(const CompressArgs a) {
 #endif
 
   if (wave == 0) {
-    // publish the range total, then wait until every workgroup's word carries this launch's epoch
     const uint32_t agg = wave_last(wave_incl_scan(lane < NW ? s_red[lane] : 0u));
     if (lane == 0) st_agent(&a.state[b], ((uint64_t)epoch << 32) | agg);
-    uint32_t lo, al, spins = 0, gave_up = 0;
-    const uint64_t t0 = wall_clock64();
-    for (;;) {
-      lo = 0;
-      al = 0;
-      int ready = 1;
-      for (uint32_t i = lane; i < W; i += 64) {
-        const uint64_t s = ld_agent(&a.state[i]);
-        if ((uint32_t)(s >> 32) != epoch) ready = 0;
-        al += (uint32_t)s;
-        lo += i < b ? (uint32_t)s : 0u;
-      }
-#ifdef EXP_NO_WAIT
-      break;
-#endif
-      if (__ballot(ready) == ~0ull) break;
-      if ((++spins & 15u) == 0 && (uint64_t)(wall_clock64() - t0) > a.spin_ticks) {
-        gave_up = 1;
-        break;
-      }
-      __builtin_amdgcn_s_sleep(1);
-    }
-    lo = base + wave_last(wave_incl_scan(lo));
-    al = base + wave_last(wave_incl_scan(al));
+    uint32_t lo, al;
+    const bool ok = exchange(a.state, epoch, a.expect_wgs, b, lane, a.spin_ticks, false, lo, al);
     if (lane == 0) {
-      s_misc[0] = lo;
-      s_misc[1] = al;
-      s_misc[2] = gave_up;
+      s_misc[0] = base + lo;
+      s_misc[1] = base + al;
+      s_misc[2] = ok ? 0u : 1u;
     }
     // workgroup 0 closes the launch: it has seen every workgroup's word, so all of them have
     // read the header words
     if (b == 0) {
-      const uint32_t err = err_before | (gave_up ? (uint32_t)SPLITZIP_STATUS_INTERNAL : 0u);
+      const uint32_t err = err_before | (ok ? 0u : (uint32_t)SPLITZIP_STATUS_INTERNAL);
       if (lane == 0) {
-        st_agent(&a.ws_hdr[0], epoch + 1u ? epoch + 1u : 1u);
-        st_agent(&a.ws_hdr[1], al);
+        st_agent(&a.ws_hdr[0], epoch + 1u);
+        st_agent(&a.ws_hdr[1], base + al);
         st_agent(&a.ws_hdr[2], single ? 0u : err);   // a call of several launches reports in its finishing launch
       }
-      if (single) compress_write_trailer(a, al, err, lane);
+      if (single) compress_write_trailer(a.p, a.dec, a.sizes, base + al, err, lane);
     }
   } else if (wave == 1) {
-    // meanwhile: exclusive offsets of the range's chunks, four per lane, in place; s_off[nb] = total
-    uint32_t v[4], sum = 0;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const uint32_t q = 4 * lane + j;
-      v[j] = q < nb ? s_off[q] : 0u;
-      sum += v[j];
-    }
-    const uint32_t incl = wave_incl_scan(sum);
-    uint32_t run = incl - sum;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const uint32_t q = 4 * lane + j;
-      if (q < nb) s_off[q] = run;
-      run += v[j];
-    }
-    if (lane == 63) s_off[nb] = incl;
+    scan_range(s_off, nb, lane);   // meanwhile
   }
   __syncthreads();
   const uint32_t prefix = s_misc[0], M = s_misc[1];
@@ -591,37 +685,13 @@ __global__ __launch_bounds__(T) void compress_kernel(const CompressArgs a) {
 #endif
 
   if (!timed_out) {
-    uint32_t* tab = reinterpret_cast<uint32_t*>(a.out + a.off_tab);
-    if ((uint32_t)tid < nb) tab[r0 + tid] = prefix + s_off[tid];
-
-    // escape records to their final rank; values go behind the positions when M is final
-    const uint64_t off_val = a.off_pos + a256(2ull * M);
-    GlobalSink g;
-    g.pos = reinterpret_cast<uint16_t*>(a.out + a.off_pos);
-    g.pos_room = a.capacity > a.off_pos ? (a.capacity - a.off_pos) / 2 : 0;
-    g.val = single ? a.out + off_val : a.val_stage;
-    g.val_room = single ? (a.capacity > off_val ? a.capacity - off_val : 0) : ~0ull;
-    if (wave_count <= kStageCap) {
-      // staged record i of this wave belongs to chunk k and is the (i - s_wstart[k])-th of it
-      for (uint32_t i = lane; i < wave_count; i += 64) {
-        const uint32_t pk = stage_pk[wave][i], k = (pk >> 10) * NW + wave;
-        g.put(prefix + s_off[k] + (i - s_wstart[k]), pk & 1023u, stage_val[wave][i]);
-      }
-    } else {
-      // more escapes than the staging holds: go over this wave's chunks again and write the
-      // records straight to their place
-      for (uint32_t k = wave; k < nb; k += NW) {
-        const uint64_t cbase = (uint64_t)(r0 + k) * kChunk;
-        const uint32_t r = prefix + s_off[k];
-        if (F::full(a, cbase)) {
-          F::template load<true>(a, cbase, lane, w);
-          F::template process<true, false>(a, lut, park, cbase, lane, w, r, g);
-        } else {
-          F::template load<false>(a, cbase, lane, w);
-          F::template process<false, false>(a, lut, park, cbase, lane, w, r, g);
-        }
-      }
+    // values go behind the positions when M is final, else into the workspace
+    GlobalSink g = final_sink(a.p, M);
+    if (!single) {
+      g.val = a.val_stage;
+      g.val_room = ~0ull;
     }
+    write_out<NW, F>(a.p, lut, park, L, r0, nb, wave_count, prefix, g, tid, wave, lane);
   } else if (tid == 0) {
     __hip_atomic_fetch_or(&a.ws_hdr[2], (uint32_t)SPLITZIP_STATUS_INTERNAL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
@@ -634,26 +704,136 @@ __global__ __launch_bounds__(T) void compress_kernel(const CompressArgs a) {
 #endif
 }
 
+// ---- several tensors in one launch ----
+constexpr uint32_t kBatchMax = 64;     // tensors per launch: their descriptors travel as kernel arguments
+constexpr uint32_t kBatchLuts = 2;     // codebooks per launch
+constexpr uint32_t kRing = 4;          // exchange slots: a workgroup can be two tensors ahead of the slowest
+constexpr uint32_t kRingWgs = 1024;    // words per slot
+
+struct BatchItem {
+  const uint8_t* in;
+  uint8_t* out;
+  uint64_t n, capacity;
+};
+struct CompressBatchArgs {
+  BatchItem item[kBatchMax];
+  uint8_t lut_of[kBatchMax];
+  splitzip_sizes* sizes;     // n_items records
+  uint32_t* ws_hdr;
+  uint64_t* state;           // kRing slots of kRingWgs words: (epoch + item) << 32 | escapes in the workgroup's range
+  uint64_t spin_ticks;
+  uint32_t n_items, dtype, expect_wgs, reserved;
+  uint8_t dec[kBatchLuts][16];
+  uint16_t lut[kBatchLuts][256];
+};
+
+// The same persistent grid works through the tensors one after the other, and the exchange of
+// tensor i is taken out of the critical path: a workgroup publishes its count for tensor i, then
+// completes tensor i - 1 (whose counts every workgroup published a whole dense pass ago, so the
+// read finds them at once) and goes on to tensor i + 1.  Staging in LDS is double buffered.  What
+// a single launch pays per tensor -- the wait for the slowest workgroup, the exchange, the
+// write-out and the launch itself -- is paid once per batch here.
+template <int T, typename F>
+__global__ __launch_bounds__(T) void compress_batch_kernel(const CompressBatchArgs a) {
+  constexpr int NW = T / 64;
+  __shared__ uint16_t lut[kBatchLuts][256];
+  __shared__ uint16_t stage_pk[2][NW][kStageCap];
+  __shared__ uint8_t stage_val[2][NW][kStageCap];
+  __shared__ uint32_t s_off[2][kMaxRange + 1];
+  __shared__ uint16_t s_wstart[2][kMaxRange];
+  __shared__ u32x4 s_park[T];
+  __shared__ uint32_t s_red[16];
+  __shared__ uint32_t s_misc[4];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t b = blockIdx.x, W = gridDim.x;
+  uint32_t* park = reinterpret_cast<uint32_t*>(&s_park[tid]);
+
+  for (int i = tid; i < (int)(kBatchLuts * 256); i += T) lut[i >> 8][i & 255] = a.lut[i >> 8][i & 255];
+  const uint32_t epoch = ld_agent(&a.ws_hdr[0]);
+  const uint32_t err_before = b == 0 ? ld_agent(&a.ws_hdr[2]) : 0u;
+  if (tid == 0) s_misc[3] = 0;   // set once an exchange was given up: later ones are not waited for
+  __syncthreads();
+
+  Planes Pprev = make_planes(nullptr, nullptr, 0, 0, (int)a.dtype);
+  uint32_t prev_count = 0, prev_r0 = 0, prev_nb = 0;
+  for (uint32_t i = 0; i <= a.n_items; ++i) {
+    const bool have = i < a.n_items;
+    const uint32_t set = i & 1u;
+    const RangeLds L{stage_pk[set][wave], stage_val[set][wave], s_off[set], s_wstart[set]};
+    Planes P = Pprev;
+    uint32_t r0 = 0, nb = 0, wave_count = 0;
+    if (have) {
+      P = make_planes(a.item[i].in, a.item[i].out, a.item[i].n, a.item[i].capacity, (int)a.dtype);
+      my_range(0, P.n_chunks, W, b, r0, nb);
+      wave_count = dense_pass<NW, F>(P, lut[a.lut_of[i]], park, L, r0, nb, wave, lane);
+      if (lane == 0) s_red[wave] = wave_count;
+    }
+    __syncthreads();
+    if (wave == 0) {
+      if (have) {
+        const uint32_t agg = wave_last(wave_incl_scan(lane < NW ? s_red[lane] : 0u));
+        if (lane == 0) st_agent(&a.state[(i % kRing) * kRingWgs + b], ((uint64_t)(epoch + i) << 32) | agg);
+      }
+      if (i > 0) {
+        // complete tensor i - 1
+        uint32_t lo, al;
+        const bool ok = exchange(a.state + ((i - 1) % kRing) * kRingWgs, epoch + i - 1, a.expect_wgs, b, lane,
+                                 a.spin_ticks, s_misc[3] != 0, lo, al);
+        if (lane == 0) {
+          s_misc[0] = lo;
+          s_misc[1] = al;
+          s_misc[2] = ok ? 0u : 1u;
+          if (!ok) s_misc[3] = 1;
+        }
+        if (b == 0) {
+          const uint32_t err = err_before | (ok ? 0u : (uint32_t)SPLITZIP_STATUS_INTERNAL);
+          compress_write_trailer(Pprev, a.dec[a.lut_of[i - 1]], a.sizes + (i - 1), al, err, lane);
+          if (!have && lane == 0) {
+            // the launch ends here; every workgroup has read the header words long ago
+            st_agent(&a.ws_hdr[0], epoch + a.n_items);
+            st_agent(&a.ws_hdr[2], 0u);
+          }
+        }
+      }
+    } else if (wave == 1 && have) {
+      scan_range(s_off[set], nb, lane);
+    }
+    __syncthreads();
+    if (i > 0 && s_misc[2] == 0) {
+      const uint32_t pset = set ^ 1u;
+      const RangeLds Lp{stage_pk[pset][wave], stage_val[pset][wave], s_off[pset], s_wstart[pset]};
+      write_out<NW, F>(Pprev, lut[a.lut_of[i - 1]], park, Lp, prev_r0, prev_nb, prev_count, s_misc[0],
+                       final_sink(Pprev, s_misc[1]), tid, wave, lane);
+    }
+    __syncthreads();   // the previous tensor's LDS set is free again, s_misc may be rewritten
+    Pprev = P;
+    prev_count = wave_count;
+    prev_r0 = r0;
+    prev_nb = nb;
+  }
+}
+
 // Last launch of a call that took several: M is known now.  Moves the staged escape values
 // behind the position array and writes the trailer.
 __global__ __launch_bounds__(kThreads) void compress_finish_kernel(const CompressArgs a) {
   const uint32_t M = ld_agent(&a.ws_hdr[1]);
-  const uint64_t off_val = a.off_pos + a256(2ull * M);
-  const uint64_t room = a.capacity > off_val ? a.capacity - off_val : 0;
+  const uint64_t off_val = a.p.off_pos + a256(2ull * M);
+  const uint64_t room = a.p.capacity > off_val ? a.p.capacity - off_val : 0;
   const uint64_t m = M < room ? M : room;
   const uint64_t nvec = m / 16;
   const u32x4* src = reinterpret_cast<const u32x4*>(a.val_stage);
-  u32x4* dst = reinterpret_cast<u32x4*>(a.out + off_val);
+  u32x4* dst = reinterpret_cast<u32x4*>(a.p.out + off_val);
   const uint64_t gtid = blockIdx.x * (uint64_t)kThreads + threadIdx.x, gsz = (uint64_t)gridDim.x * kThreads;
   for (uint64_t i = gtid; i < nvec; i += gsz) dst[i] = src[i];
-  for (uint64_t i = nvec * 16 + gtid; i < m; i += gsz) a.out[off_val + i] = a.val_stage[i];
+  for (uint64_t i = nvec * 16 + gtid; i < m; i += gsz) a.p.out[off_val + i] = a.val_stage[i];
   if (blockIdx.x == 0 && threadIdx.x < 64) {
     uint32_t err = 0;
     if (threadIdx.x == 0) {
       err = ld_agent(&a.ws_hdr[2]);
       st_agent(&a.ws_hdr[2], 0u);
     }
-    compress_write_trailer(a, M, err, threadIdx.x);
+    compress_write_trailer(a.p, a.dec, a.sizes, M, err, threadIdx.x);
   }
 }
 
@@ -676,7 +856,7 @@ __device__ inline void flag_bad(const DecompressArgs& a) {
 }
 
 // header checks: one thread of workgroup 0
-__device__ void decompress_check_header(const DecompressArgs& a, uint32_t M) {
+__device__ void decompress_check_header(const DecompressArgs& a, const uint8_t* dec, uint32_t M) {
   const uint32_t* h = reinterpret_cast<const uint32_t*>(a.comp);
   const uint64_t n = h[4] | ((uint64_t)h[5] << 32), m = h[6] | ((uint64_t)h[7] << 32);
   const uint64_t total = h[8] | ((uint64_t)h[9] << 32);
@@ -685,8 +865,8 @@ __device__ void decompress_check_header(const DecompressArgs& a, uint32_t M) {
             total <= a.comp_bytes && h[14] == 0 && h[15] == 0;
 #pragma unroll
   for (int i = 0; i < 4; ++i)
-    ok = ok && h[10 + i] == (a.dec[4 * i] | (a.dec[4 * i + 1] << 8) | (a.dec[4 * i + 2] << 16) |
-                             ((uint32_t)a.dec[4 * i + 3] << 24));
+    ok = ok && h[10 + i] == (dec[4 * i] | (dec[4 * i + 1] << 8) | (dec[4 * i + 2] << 16) |
+                             ((uint32_t)dec[4 * i + 3] << 24));
   if (!ok) flag_bad(a);
   if (a.sizes) {
     a.sizes->total_bytes = total;
@@ -812,19 +992,19 @@ struct DE5m2 {
   }
 };
 
+// one workgroup: tile `tile` of the tensor described by a (4 waves x cpw chunks)
 template <typename F>
-__global__ __launch_bounds__(kThreads) void decompress_kernel(const DecompressArgs a) {
-  __shared__ uint32_t tbl[256];
+__device__ inline void decompress_tile(const DecompressArgs& a, const uint8_t* dec, uint32_t tile, uint32_t* tbl) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  tbl[tid] = F::table(tid, a.dec);
+  tbl[tid] = F::table(tid, dec);
 
   const uint32_t* tab = reinterpret_cast<const uint32_t*>(a.comp + a.off_tab);
   // M as the offset table states it; escapes are only trusted if their sections lie inside the stream
   uint32_t M = tab[a.n_chunks];
   const uint64_t off_val = a.off_pos + a256(2ull * M);
   const bool esc_ok = M <= a.n && off_val + M <= a.comp_bytes;
-  if (blockIdx.x == 0 && tid == 0) {
-    decompress_check_header(a, M);
+  if (tile == 0 && tid == 0) {
+    decompress_check_header(a, dec, M);
     if (!esc_ok) flag_bad(a);
   }
   if (!esc_ok) M = 0;
@@ -833,7 +1013,7 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(const DecompressAr
   __syncthreads();
 
   const uint32_t cpw = a.cpw;
-  const uint32_t wave_chunk0 = (blockIdx.x * kWaves + wave) * cpw;
+  const uint32_t wave_chunk0 = (tile * kWaves + wave) * cpw;
   for (uint32_t c = 0; c < cpw; ++c) {
     const uint32_t chunk = wave_chunk0 + c;
     if (chunk >= a.n_chunks) break;
@@ -858,6 +1038,48 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(const DecompressAr
       if (pos >= clen || !F::patch(a, cbase + pos, val)) flag_bad(a);
     }
   }
+}
+
+template <typename F>
+__global__ __launch_bounds__(kThreads) void decompress_kernel(const DecompressArgs a) {
+  __shared__ uint32_t tbl[256];
+  decompress_tile<F>(a, a.dec, blockIdx.x, tbl);
+}
+
+// several streams in one launch: blockIdx.y picks the stream, blockIdx.x the tile
+struct DBatchItem {
+  const uint8_t* comp;
+  uint8_t* out;
+  uint64_t n, comp_bytes;
+};
+struct DecompressBatchArgs {
+  DBatchItem item[kBatchMax];
+  uint8_t dec_of[kBatchMax];
+  splitzip_sizes* sizes;   // nullable; one record, status bits sticky
+  uint32_t cpw, dtype;
+  uint8_t dec[kBatchLuts][16];
+};
+
+template <typename F>
+__global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const DecompressBatchArgs b) {
+  __shared__ uint32_t tbl[256];
+  const DBatchItem it = b.item[blockIdx.y];
+  const Layout L = make_layout(it.n, (int)b.dtype);
+  const uint32_t n_tiles = (uint32_t)((L.n_chunks + (uint64_t)kWaves * b.cpw - 1) / (kWaves * b.cpw));
+  if (blockIdx.x >= (n_tiles ? n_tiles : 1u)) return;
+  DecompressArgs a;
+  a.comp = it.comp;
+  a.out = it.out;
+  a.n = it.n;
+  a.comp_bytes = it.comp_bytes;
+  a.sizes = b.sizes;
+  a.off_tab = L.off_tab; a.off_sm = L.off_sm; a.off_code = L.off_code; a.off_pos = L.off_pos;
+  a.sm_bytes = L.sm_bytes; a.code_bytes = L.code_bytes;
+  a.n_chunks = (uint32_t)L.n_chunks;
+  a.n_tiles = n_tiles;
+  a.cpw = b.cpw;
+  a.dtype = b.dtype;
+  decompress_tile<F>(a, b.dec[b.dec_of[blockIdx.y]], blockIdx.x, tbl);   // a.dec stays unset: the table comes from the kernel arguments
 }
 
 // ---------------------------------------------------------------------------
@@ -942,7 +1164,7 @@ bool codebook_ok(const splitzip_codebook* cb, int dtype) {
 
 template <int T>
 void launch_compress(unsigned grid, hipStream_t stream, const CompressArgs& a) {
-  if (a.dtype == SPLITZIP_BF16) hipLaunchKernelGGL((compress_kernel<T, Bf16>), dim3(grid), dim3(T), 0, stream, a);
+  if (a.p.dtype == SPLITZIP_BF16) hipLaunchKernelGGL((compress_kernel<T, Bf16>), dim3(grid), dim3(T), 0, stream, a);
   else hipLaunchKernelGGL((compress_kernel<T, E5m2>), dim3(grid), dim3(T), 0, stream, a);
 }
 
@@ -956,6 +1178,20 @@ uint32_t resident_workgroups() {
     int per_cu = 0;
     // both formats' kernels use the same LDS; the BF16 one needs more registers
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, compress_kernel<T, Bf16>, T, 0) != hipSuccess || per_cu <= 0)
+      return 0;
+    cached[dev] = (uint32_t)per_cu * (uint32_t)cu_count();
+  }
+  return cached[dev];
+}
+
+// the same for the batch kernel (more LDS)
+uint32_t resident_workgroups_batch() {
+  static uint32_t cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+  if (!cached[dev]) {
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, compress_batch_kernel<1024, Bf16>, 1024, 0) != hipSuccess || per_cu <= 0)
       return 0;
     cached[dev] = (uint32_t)per_cu * (uint32_t)cu_count();
   }
@@ -1060,19 +1296,12 @@ int splitzip_compress(const void* d_in, uint64_t n_elems, int dtype, const split
   const Layout L = make_layout(n_elems, dtype);
   CompressArgs a;
   memset(&a, 0, sizeof a);
-  a.in = static_cast<const uint8_t*>(d_in);
-  a.out = static_cast<uint8_t*>(d_out);
-  a.n = n_elems;
-  a.capacity = out_capacity;
+  a.p = make_planes(d_in, d_out, n_elems, out_capacity, dtype);
   uint8_t* ws = static_cast<uint8_t*>(d_workspace);
   a.ws_hdr = reinterpret_cast<uint32_t*>(ws);
   a.state = reinterpret_cast<uint64_t*>(ws + kWsHeaderBytes);
   a.val_stage = ws + kWsHeaderBytes + kWsTableBytes;
   a.sizes = d_sizes;
-  a.off_tab = L.off_tab; a.off_sm = L.off_sm; a.off_code = L.off_code; a.off_pos = L.off_pos;
-  a.sm_bytes = L.sm_bytes; a.code_bytes = L.code_bytes;
-  a.n_chunks = (uint32_t)L.n_chunks;
-  a.dtype = (uint32_t)dtype;
   memcpy(a.dec, cb->dec, 16);
   // indexed by the exponent (BF16) or by the whole byte (E5M2: e = (x >> 2) & 31)
   for (unsigned v = 0; v < 256; ++v) {
@@ -1157,6 +1386,135 @@ int splitzip_decompress(const void* d_comp, size_t comp_bytes, uint64_t n_elems,
   if (dtype == SPLITZIP_BF16) hipLaunchKernelGGL(decompress_kernel<DBf16>, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
   else hipLaunchKernelGGL(decompress_kernel<DE5m2>, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
   return hipGetLastError() == hipSuccess ? SPLITZIP_OK : SPLITZIP_ERR_HIP;
+}
+
+int splitzip_compress_batch(const splitzip_item* items, uint32_t n_items, int dtype, void* d_workspace,
+                            size_t workspace_bytes, splitzip_sizes* d_sizes, void* stream) {
+  if (!dtype_ok(dtype) || (n_items && (!items || !d_sizes)) || !d_workspace || !aligned16(d_workspace) ||
+      (reinterpret_cast<uintptr_t>(d_sizes) & 7u))
+    return SPLITZIP_ERR_INVALID_ARG;
+  uint64_t n_max = 0;
+  for (uint32_t i = 0; i < n_items; ++i) {
+    const splitzip_item& it = items[i];
+    if (!it.d_out || (it.n_elems && !it.d_in) || !aligned16(it.d_in) || !aligned16(it.d_out) || !codebook_ok(it.cb, dtype))
+      return SPLITZIP_ERR_INVALID_ARG;
+    if (it.n_elems >> 32) return SPLITZIP_ERR_UNSUPPORTED;
+    if (it.out_capacity < splitzip_fixed_bytes(it.n_elems, dtype)) return SPLITZIP_ERR_CAPACITY;
+    if (it.n_elems > n_max) n_max = it.n_elems;
+  }
+  if (workspace_bytes < splitzip_workspace_bytes(n_max, dtype)) return SPLITZIP_ERR_CAPACITY;
+
+  static const int wgs_per_cu = env_int("SPLITZIP_COMPRESS_WGS_PER_CU", 1);
+  const uint32_t resident = resident_workgroups_batch();
+  if (!resident) return SPLITZIP_ERR_HIP;
+  uint32_t W = (uint32_t)cu_count() * (uint32_t)wgs_per_cu;
+  if (W > resident) W = resident;
+  if (W > kRingWgs) W = kRingWgs;
+  static const int max_wgs = env_int("SPLITZIP_COMPRESS_MAX_WGS", 0);
+  if (max_wgs && W > (uint32_t)max_wgs) W = (uint32_t)max_wgs;
+  const uint64_t chunk_cap = (uint64_t)W * kMaxRange;   // chunks of one tensor the batch kernel can take
+  static const int spin_env = env_int("SPLITZIP_SPIN_TICKS", 0);
+  const hipStream_t st = static_cast<hipStream_t>(stream);
+  uint8_t* ws = static_cast<uint8_t*>(d_workspace);
+
+  uint32_t i = 0;
+  while (i < n_items) {
+    // a tensor beyond the batch kernel's reach goes through the single call, in its place in the order
+    if ((items[i].n_elems + kChunk - 1) / kChunk > chunk_cap) {
+      const int rc = splitzip_compress(items[i].d_in, items[i].n_elems, dtype, items[i].cb, items[i].d_out,
+                                       items[i].out_capacity, d_workspace, workspace_bytes, d_sizes + i, stream);
+      if (rc != SPLITZIP_OK) return rc;
+      ++i;
+      continue;
+    }
+    // one launch: up to kBatchMax tensors that share at most kBatchLuts codebooks
+    CompressBatchArgs a;
+    memset(&a, 0, sizeof a);
+    uint32_t k = 0, n_luts = 0;
+    for (; i + k < n_items && k < kBatchMax; ++k) {
+      const splitzip_item& it = items[i + k];
+      if ((it.n_elems + kChunk - 1) / kChunk > chunk_cap) break;
+      uint32_t id = 0;
+      while (id < n_luts && memcmp(a.dec[id], it.cb->dec, 16) != 0) ++id;
+      if (id == n_luts) {
+        if (n_luts == kBatchLuts) break;
+        memcpy(a.dec[id], it.cb->dec, 16);
+        for (unsigned v = 0; v < 256; ++v) {
+          const unsigned e = dtype == SPLITZIP_BF16 ? v : (v >> 2) & 31u;
+          a.lut[id][v] = it.cb->member[e] ? it.cb->enc[e] : 0x100u;
+        }
+        ++n_luts;
+      }
+      a.item[k].in = static_cast<const uint8_t*>(it.d_in);
+      a.item[k].out = static_cast<uint8_t*>(it.d_out);
+      a.item[k].n = it.n_elems;
+      a.item[k].capacity = it.out_capacity;
+      a.lut_of[k] = (uint8_t)id;
+    }
+    a.sizes = d_sizes + i;
+    a.ws_hdr = reinterpret_cast<uint32_t*>(ws);
+    a.state = reinterpret_cast<uint64_t*>(ws + kWsHeaderBytes);
+    a.spin_ticks = spin_env ? (uint64_t)spin_env : kSpinTicks;
+    a.n_items = k;
+    a.dtype = (uint32_t)dtype;
+    a.expect_wgs = W;
+    if (dtype == SPLITZIP_BF16) hipLaunchKernelGGL((compress_batch_kernel<1024, Bf16>), dim3(W), dim3(1024), 0, st, a);
+    else hipLaunchKernelGGL((compress_batch_kernel<1024, E5m2>), dim3(W), dim3(1024), 0, st, a);
+    if (hipGetLastError() != hipSuccess) return SPLITZIP_ERR_HIP;
+    i += k;
+  }
+  return SPLITZIP_OK;
+}
+
+int splitzip_decompress_batch(const splitzip_ditem* items, uint32_t n_items, int dtype, splitzip_sizes* d_sizes,
+                              void* stream) {
+  if (!dtype_ok(dtype) || (n_items && !items) || (reinterpret_cast<uintptr_t>(d_sizes) & 7u)) return SPLITZIP_ERR_INVALID_ARG;
+  for (uint32_t i = 0; i < n_items; ++i) {
+    const splitzip_ditem& it = items[i];
+    if (!it.d_comp || (it.n_elems && !it.d_out) || !aligned16(it.d_comp) || !aligned16(it.d_out) || !codebook_ok(it.cb, dtype))
+      return SPLITZIP_ERR_INVALID_ARG;
+    if (it.n_elems >> 32) return SPLITZIP_ERR_UNSUPPORTED;
+    if (it.comp_bytes < splitzip_fixed_bytes(it.n_elems, dtype)) return SPLITZIP_ERR_CAPACITY;
+  }
+  static const int cpw_env = env_int("SPLITZIP_DECOMPRESS_CPW", 0);
+  static const int tiles_per_cu = env_int("SPLITZIP_DECOMPRESS_TILES_PER_CU", 8);
+  uint32_t i = 0;
+  while (i < n_items) {
+    DecompressBatchArgs a;
+    memset(&a, 0, sizeof a);
+    uint32_t k = 0, n_decs = 0;
+    uint64_t chunks_all = 0, chunks_max = 0;
+    for (; i + k < n_items && k < kBatchMax; ++k) {
+      const splitzip_ditem& it = items[i + k];
+      uint32_t id = 0;
+      while (id < n_decs && memcmp(a.dec[id], it.cb->dec, 16) != 0) ++id;
+      if (id == n_decs) {
+        if (n_decs == kBatchLuts) break;
+        memcpy(a.dec[id], it.cb->dec, 16);
+        ++n_decs;
+      }
+      a.item[k].comp = static_cast<const uint8_t*>(it.d_comp);
+      a.item[k].out = static_cast<uint8_t*>(it.d_out);
+      a.item[k].n = it.n_elems;
+      a.item[k].comp_bytes = it.comp_bytes;
+      a.dec_of[k] = (uint8_t)id;
+      const uint64_t c = (it.n_elems + kChunk - 1) / kChunk;
+      chunks_all += c;
+      if (c > chunks_max) chunks_max = c;
+    }
+    a.sizes = d_sizes;
+    a.dtype = (uint32_t)dtype;
+    a.cpw = cpw_env ? (uint32_t)cpw_env : pick_cpw(chunks_all, dtype == SPLITZIP_BF16 ? 1 : 4, (uint32_t)tiles_per_cu);
+    if (a.cpw > kMaxCpw) a.cpw = kMaxCpw;
+    uint64_t gx = (chunks_max + (uint64_t)kWaves * a.cpw - 1) / (kWaves * a.cpw);
+    if (gx < 1) gx = 1;
+    const dim3 grid((unsigned)gx, k);
+    if (dtype == SPLITZIP_BF16) hipLaunchKernelGGL(decompress_batch_kernel<DBf16>, grid, dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
+    else hipLaunchKernelGGL(decompress_batch_kernel<DE5m2>, grid, dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
+    if (hipGetLastError() != hipSuccess) return SPLITZIP_ERR_HIP;
+    i += k;
+  }
+  return SPLITZIP_OK;
 }
 
 int splitzip_traffic_probe(const void* d_src, size_t read_bytes, void* d_dst, size_t write_bytes, void* stream) {

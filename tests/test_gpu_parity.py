@@ -264,6 +264,57 @@ def test_bad_stream_is_flagged_not_followed():
     assert st & sz.STATUS_BAD_STREAM
 
 
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_batch_calls_match_the_oracle_item_by_item(dtype):
+    """one batch launch over tensors of mixed sizes (empty, ragged, all-escape, several ranges) and two codebooks:
+    every stream is the oracle's, every tensor comes back"""
+    es = 2 if dtype == sz.BF16 else 1
+    cbs_or = [calibrated(dtype, kind="K"), calibrated(dtype, kind="V")]
+    if dtype == sz.BF16:
+        cbs_or.append(oracle.codebook_from_dec(np.arange(230, 246, dtype=np.uint8), oracle.BF16))
+    else:
+        cbs_or.append(oracle.codebook_from_dec(np.array([0, 31, 1, 30, 2, 29, 3, 28, 4, 27, 5, 26, 6, 25, 24, 23], np.uint8), oracle.E5M2))
+    sizes = [300 * 1024, 0, 1, 8191, 123457, 64 * 1024, 1025, 700 * 1024 + 5, 2048, 40000, 17, 256 * 1024]
+    xs_np, books = [], []
+    for k, n in enumerate(sizes):
+        x = synth(dtype, (n + 1023) // 1024 + 1, 20 + k, layer=k % 3, kind="KV"[k % 2])[:n].copy()
+        if k % 4 == 3 and n:
+            x[:: max(1, n // 50)] = 0
+        xs_np.append(x)
+        books.append(cbs_or[2] if k in (5, 10) else cbs_or[k % 2])     # the third codebook forces a second launch
+    gcb = [gpu_codebook(c) for c in cbs_or]
+    gbooks = [gcb[cbs_or.index(c)] for c in books]
+    xs = [words_tensor(x) for x in xs_np]
+    outs = [torch.full((sz.compress_bound(x.size, dtype) + 512,), POISON, dtype=torch.uint8, device="cuda") for x in xs_np]
+    ws = sz.Workspace(max(sizes), dtype)
+    rec = sz.new_sizes_array(len(xs))
+    rec.fill_(-1)
+    batch = sz.CompressBatch(xs, gbooks, outs)
+    for rep in range(2):                                   # the second launch re-uses the workspace
+        batch.launch(ws, rec)
+        torch.cuda.synchronize()
+        got = sz.read_sizes_array(rec)
+        for k, x in enumerate(xs_np):
+            ref, m = oracle.compress(x, books[k])
+            total, gm, status = got[k]
+            assert (total, gm, status) == (ref.size, m, 0), f"item {k}: {got[k]} vs {(ref.size, m)}"
+            blob = outs[k][:total].cpu().numpy()
+            assert np.array_equal(blob, ref), f"item {k} (n={x.size}): stream differs from the oracle's"
+            assert (outs[k][total:total + 256].cpu().numpy() == POISON).all()
+    # and back, in one launch
+    ys = [torch.full((x.size + 64,), 0x5A5A if es == 2 else 0x5A, dtype=torch.int16 if es == 2 else torch.uint8, device="cuda")
+          for x in xs_np]
+    st = sz.new_sizes()
+    sz.decompress_batch(outs, [g[0] for g in got], [x.size for x in xs_np], gbooks, ys, st)
+    torch.cuda.synchronize()
+    assert sz.read_sizes(st)[2] == 0
+    for k, x in enumerate(xs_np):
+        y = ys[k].cpu().numpy()
+        y = y.view(np.uint16) if es == 2 else y
+        assert np.array_equal(y[: x.size], x), f"item {k}: batch round trip differs"
+        assert (ys[k][x.size:].cpu().numpy() == (0x5A if es == 1 else 0x5A5A)).all()
+
+
 def test_full_size_e5m2_tensor():
     """config 4 at its real tensor size [32768, 8, 128] E5M2 (32 MiB): V of layer 17"""
     n = 32768 * 1024
