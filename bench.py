@@ -1,13 +1,18 @@
 #!/usr/bin/env python3
 """SplitZip codec benchmark on one MI355X.
 
-One step = one pass of the whole hot path over the workload: every tensor is
-compressed (one launch each), then every stream is decompressed (one launch
-each).  Inputs, streams and outputs are resident in HBM; the tensors of a
-pass are all distinct and together far larger than the 256 MB last-level
-cache, so every launch streams from HBM.
+One step = one pass of the whole hot path over the workload: every tensor of
+the KV cache is compressed (one splitzip_compress_batch call = one launch for
+all of them), then every stream is decompressed (one splitzip_decompress_batch
+call).  Inputs, streams and outputs are resident in HBM; the tensors of a pass
+are all distinct and together far larger than the 256 MB last-level cache, so
+the kernels stream from HBM.  The round trip is verified bit for bit before
+anything is timed (the paper's protocol, section 4.1).
 
-Prints ONE JSON line (see README for the fields).
+The same pass with one launch per tensor (splitzip_compress /
+splitzip_decompress) is timed as well and reported under "per_tensor_calls".
+
+Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -23,7 +28,14 @@ import kv_synth
 import paper_2605_01708_amd as sz
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
-TOKENS = {"config1": 32768, "config0": 4096}
+
+WORKLOADS = {
+    "config1": "Llama-3-8B-shaped BF16 KV cache: 32 layers x {K,V} x [32768,8,128] (4 GiB), one codebook per kind",
+    "config0": "single BF16 K tensor [4096,8,128] (8 MiB, cache resident)",
+    "config2": "escape stress: 8 x BF16 [16384,8,128] with 0.5 % outliers and 0.1 % zeros/subnormals",
+    "config3": "streaming prefill chunks, Llama-3-70B shape: BF16 [2048,8,128] K and V per layer (4 MiB calls)",
+    "config4": "FP8 E5M2 KV cache: 32 layers x {K,V} x [32768,8,128] (2 GiB), one codebook per kind",
+}
 
 
 def parse():
@@ -31,128 +43,196 @@ def parse():
     p.add_argument("--gpus", type=int, default=1)
     p.add_argument("--steps", type=int, default=10)
     p.add_argument("--warmup", type=int, default=2)
-    p.add_argument("--workload", default="config1", choices=["config1", "config0", "config4"])
-    p.add_argument("--layers", type=int, default=32, help="layers of the KV cache (config1/4: 32)")
+    p.add_argument("--workload", default="config1", choices=sorted(WORKLOADS))
+    p.add_argument("--layers", type=int, default=0, help="layers of the KV cache (default: the workload's own)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--cpu-sample-tensors", type=int, default=8)
     return p.parse_args()
 
 
 def build_workload(args):
-    """tensors (device, raw words), codebooks per kind"""
+    """[(kind, device tensor of raw words)], {kind: codebook}, dtype"""
     dev = "cuda"
-    if args.workload == "config0":
-        dtype = sz.BF16
-        xs = [("K", kv_synth.kv_bf16(4096, 0, 0, "K", dev))]
-        cbs = {"K": sz.calibrate(kv_synth.kv_bf16(4096, 1, 0, "K"), dtype)}
-        return dtype, xs, cbs
-    dtype = sz.BF16 if args.workload == "config1" else sz.FP8_E5M2
-    gen = kv_synth.kv_bf16 if dtype == sz.BF16 else kv_synth.kv_e5m2
-    xs = []
-    for layer in range(args.layers):
-        for kind in ("K", "V"):
-            xs.append((kind, gen(32768, 0, layer, kind, dev)))
+    w = args.workload
+    if w == "config0":
+        return [("K", kv_synth.kv_bf16(4096, 0, 0, "K", dev))], {"K": sz.calibrate(kv_synth.kv_bf16(4096, 1, 0, "K"), sz.BF16)}, sz.BF16
+    if w == "config2":
+        xs = [("K", kv_synth.kv_bf16_outliers(16384, 0, layer, dev)) for layer in range(args.layers or 8)]
+        return xs, {"K": sz.calibrate(kv_synth.kv_bf16(1024, 1, 0, "K"), sz.BF16)}, sz.BF16     # outlier-free calibration
+    dtype = sz.FP8_E5M2 if w == "config4" else sz.BF16
+    gen = kv_synth.kv_e5m2 if dtype == sz.FP8_E5M2 else kv_synth.kv_bf16
+    layers = args.layers or (80 if w == "config3" else 32)
+    tokens = 2048 if w == "config3" else 32768
+    xs = [(kind, gen(tokens, 0, layer, kind, dev)) for layer in range(layers) for kind in ("K", "V")]
     # one codebook per tensor kind from a seed-1 sample of 1024 tokens spread over the layers
-    cbs = {}
-    per = max(1, 1024 // args.layers)
-    for kind in ("K", "V"):
-        sample = torch.cat([gen(per, 1, layer, kind) for layer in range(args.layers)])
-        cbs[kind] = sz.calibrate(sample, dtype)
-    return dtype, xs, cbs
+    per = max(1, 1024 // layers)
+    cbs = {kind: sz.calibrate(torch.cat([gen(per, 1, layer, kind) for layer in range(layers)]), dtype) for kind in ("K", "V")}
+    return xs, cbs, dtype
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary of this workload
+    (FETCH_SIZE + WRITE_SIZE runs of this same script, scaled by a plain copy kernel), or None."""
+    import glob
+    import re
+
+    here = os.path.dirname(os.path.abspath(__file__))
+    for path in glob.glob(os.path.join(here, "profiles", "*hbm_counters*")):
+        for line in open(path):
+            m = re.search(r'traffic_bytes_per_launch workload=(\S+) kernel="([^"]+)" bytes=(\d+)', line)
+            if m and m.group(1) == workload and m.group(2) == kernel:
+                return int(m.group(3))
+    return None
+
+
+def mean(v):
+    return sum(v) / len(v)
+
+
+def std(v):
+    m = mean(v)
+    return (sum((x - m) ** 2 for x in v) / len(v)) ** 0.5
 
 
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py measures one GPU: the codec has no cross-GPU step (run with --gpus 1)", file=sys.stderr)
+        print("bench.py measures one GPU: the codec has no cross-GPU step and this build uses one device "
+              "(run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
-    dtype, xs, cbs = build_workload(args)
+    xs, cbs, dtype = build_workload(args)
     es = 2 if dtype == sz.BF16 else 1
     n = xs[0][1].numel()
     nt = len(xs)
     raw_bytes = n * es
+    total_raw = raw_bytes * nt
     # stream capacity: the fixed part plus room for 3 % escapes
     cap = (sz.total_bytes(n, n * 3 // 100, dtype) + 255) // 256 * 256
     comps = [torch.empty(cap, dtype=torch.uint8, device="cuda") for _ in range(nt)]
     outs = [torch.empty_like(x) for _, x in xs]
-    sizes = [sz.new_sizes() for _ in range(nt)]
+    books = [cbs[kind] for kind, _ in xs]
+    rec = sz.new_sizes_array(nt)
     dsizes = sz.new_sizes()
     ws = sz.Workspace(n, dtype)
+    cbatch = sz.CompressBatch([x for _, x in xs], books, comps)
     torch.cuda.synchronize()
 
-    def compress_all():
-        for i, (kind, x) in enumerate(xs):
-            sz.compress(x, cbs[kind], comps[i], ws, sizes[i])
-
-    def decompress_all(totals):
-        for i, (kind, x) in enumerate(xs):
-            sz.decompress(comps[i], totals[i], n, cbs[kind], outs[i], dsizes)
-
-    # verify the round trip bit for bit before timing (the paper's protocol, section 4.1)
-    compress_all()
+    # ---- verify before timing: batch streams == per-tensor streams, round trip bit exact
+    cbatch.launch(ws, rec)
     torch.cuda.synchronize()
-    rec = [sz.read_sizes(s) for s in sizes]
-    assert all(r[2] == 0 for r in rec), f"compress status {rec}"
-    totals = [r[0] for r in rec]
-    escapes = sum(r[1] for r in rec)
-    decompress_all(totals)
+    got = sz.read_sizes_array(rec)
+    assert all(g[2] == 0 for g in got), f"compress status {got}"
+    totals = [g[0] for g in got]
+    escapes = sum(g[1] for g in got)
+    dbatch = sz.DecompressBatch(comps, totals, [n] * nt, books, outs)
+    dbatch.launch(dsizes)
     torch.cuda.synchronize()
     assert sz.read_sizes(dsizes)[2] == 0, "decompress flagged a bad stream"
     for (kind, x), y in zip(xs, outs):
         assert torch.equal(x, y), "round trip is not bit exact"
+    one = sz.new_sizes()
+    probe_out = torch.empty(cap, dtype=torch.uint8, device="cuda")
+    for i in (0, nt - 1):
+        sz.compress(xs[i][1], books[i], probe_out, ws, one)
+        torch.cuda.synchronize()
+        assert sz.read_sizes(one) == got[i] and torch.equal(probe_out[: totals[i]], comps[i][: totals[i]]), \
+            "batch and single call disagree"
 
     ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
+
+    # ---- the timed region: K steps of (compress batch, decompress batch); events on the launch stream
     for _ in range(args.warmup):
-        compress_all()
-        decompress_all(totals)
+        cbatch.launch(ws, rec)
+        dbatch.launch(dsizes)
     torch.cuda.synchronize()
-    t_c, t_d = [], []
+    marks = []
     wall0 = time.perf_counter()
     for _ in range(args.steps):
         e0, e1, e2 = ev(), ev(), ev()
         e0.record()
-        compress_all()
+        cbatch.launch(ws, rec)
         e1.record()
-        decompress_all(totals)
+        dbatch.launch(dsizes)
         e2.record()
-        t_c.append((e0, e1))
-        t_d.append((e1, e2))
+        marks.append((e0, e1, e2))
     torch.cuda.synchronize()
     wall = time.perf_counter() - wall0
-    ms_c = [a.elapsed_time(b) for a, b in t_c]
-    ms_d = [a.elapsed_time(b) for a, b in t_d]
-    mean = lambda v: sum(v) / len(v)  # noqa: E731
-    std = lambda v: (sum((x - mean(v)) ** 2 for x in v) / len(v)) ** 0.5  # noqa: E731
-    total_raw = raw_bytes * nt
+    ms_c = [a.elapsed_time(b) for a, b, _ in marks]
+    ms_d = [b.elapsed_time(c) for _, b, c in marks]
+    ms_step = wall / args.steps * 1e3
     comp_gbps = total_raw / (mean(ms_c) * 1e-3) / 1e9
     dec_gbps = total_raw / (mean(ms_d) * 1e-3) / 1e9
-    ms_step = wall / args.steps * 1e3
     blob_bytes = sum(totals)
-    # algorithmic traffic of one launch: read the words, write the stream (and the reverse)
-    alg_bytes = raw_bytes + blob_bytes / nt
-    c_launch_us = mean(ms_c) * 1e3 / nt
-    d_launch_us = mean(ms_d) * 1e3 / nt
-    c_ach = alg_bytes / (c_launch_us * 1e-6) / 1e9
-    d_ach = alg_bytes / (d_launch_us * 1e-6) / 1e9
+    # algorithmic traffic of one launch (= the whole batch): read the words, write the streams (and the reverse)
+    alg_bytes = total_raw + blob_bytes
+    c_ach = alg_bytes / (mean(ms_c) * 1e-3) / 1e9
+    d_ach = alg_bytes / (mean(ms_d) * 1e-3) / 1e9
+    launches = (nt + 63) // 64      # a batch call takes 64 tensors per launch
 
-    # plain streaming kernel with the codec's traffic (reads 4, writes 3 parts) into the decode outputs
-    wbytes = raw_bytes * 3 // 4 // 16 * 16
-    for _ in range(2):
+    # ---- the same pass, one launch per tensor
+    sizes1 = [sz.new_sizes() for _ in range(nt)]
+
+    def compress_each():
         for i, (kind, x) in enumerate(xs):
-            sz.traffic_probe(x, raw_bytes, outs[i], wbytes)
+            sz.compress(x, books[i], comps[i], ws, sizes1[i])
+
+    def decompress_each():
+        for i in range(nt):
+            sz.decompress(comps[i], totals[i], n, books[i], outs[i], dsizes)
+
+    lat = {}
+    if args.workload == "config3":
+        # per-call latency as a caller sees it: enqueue one call, wait for it (host clock around both)
+        for name, call in (("compress", lambda i: sz.compress(xs[i][1], books[i], comps[i], ws, sizes1[i])),
+                           ("decompress", lambda i: sz.decompress(comps[i], totals[i], n, books[i], outs[i], dsizes))):
+            ts = []
+            for rep in range(4):
+                for i in range(nt):
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    call(i)
+                    torch.cuda.synchronize()
+                    ts.append((time.perf_counter() - t0) * 1e6)
+            ts = sorted(ts[nt:])
+            lat[name] = {"p50_us": round(ts[len(ts) // 2], 2), "p99_us": round(ts[int(len(ts) * 0.99)], 2), "calls": len(ts),
+                         "how": "host clock around one call + stream synchronize"}
+    compress_each()
+    decompress_each()
+    torch.cuda.synchronize()
+    reps = max(2, args.steps // 2)
+    f0, f1, f2 = ev(), ev(), ev()
+    f0.record()
+    for _ in range(reps):
+        compress_each()
+    f1.record()
+    for _ in range(reps):
+        decompress_each()
+    f2.record()
+    torch.cuda.synchronize()
+    c1_us = f0.elapsed_time(f1) * 1e3 / reps / nt
+    d1_us = f1.elapsed_time(f2) * 1e3 / reps / nt
+    alg1 = alg_bytes / nt
+
+    # ---- plain streaming kernel with the codec's traffic (same bytes read and written per tensor, no arithmetic)
+    wbytes = (blob_bytes // nt) // 16 * 16
+    wbytes = min(wbytes, outs[0].numel() * es)
+    for i in range(nt):
+        sz.traffic_probe(xs[i][1], raw_bytes, outs[i], wbytes)
     p0, p1 = ev(), ev()
     p0.record()
     for _ in range(3):
-        for i, (kind, x) in enumerate(xs):
-            sz.traffic_probe(x, raw_bytes, outs[i], wbytes)
+        for i in range(nt):
+            sz.traffic_probe(xs[i][1], raw_bytes, outs[i], wbytes)
     p1.record()
     torch.cuda.synchronize()
     probe_gbps = (raw_bytes + wbytes) * nt * 3 / (p0.elapsed_time(p1) * 1e-3) / 1e9
 
+    fmt = "Bf16" if dtype == sz.BF16 else "E5m2"
+    ratio = total_raw / blob_bytes
     result = {
         "metric": "SplitZip compress+decompress throughput, uncompressed GB/s, 1 MI355X",
         "value": round(2 * total_raw / (ms_step * 1e-3) / 1e9, 1),
@@ -166,41 +246,50 @@ def main():
         "vs_baseline": None,
         "dtype": "u16" if dtype == sz.BF16 else "u8",
         "data": "synthetic",
-        "config": {
-            "workload": {"config1": "Llama-3-8B-shaped BF16 KV cache: 32 layers x {K,V} x [32768,8,128], 64 launches per direction",
-                         "config0": "single BF16 K tensor [4096,8,128] (cache resident)",
-                         "config4": "FP8 E5M2 KV cache: 32 layers x {K,V} x [32768,8,128]"}[args.workload],
-            "tensors": nt, "elems_per_tensor": n, "uncompressed_bytes": total_raw,
-        },
+        "config": {"workload": f"{args.workload}: {WORKLOADS[args.workload]}", "tensors": nt, "elems_per_tensor": n,
+                   "uncompressed_bytes": total_raw, "launches_per_step": 2 * launches},
         "compress_GBps": round(comp_gbps, 1),
         "compress_GBps_std": round(std([total_raw / (m * 1e-3) / 1e9 for m in ms_c]), 1),
         "decompress_GBps": round(dec_gbps, 1),
         "decompress_GBps_std": round(std([total_raw / (m * 1e-3) / 1e9 for m in ms_d]), 1),
-        "ratio": round(total_raw / blob_bytes, 4),
+        "ratio": round(ratio, 4),
         "escape_rate": round(escapes / (n * nt), 6),
-        "B_hide_GBps": round(min(comp_gbps, dec_gbps) / (total_raw / blob_bytes), 1),
-        "paper_context": {"compress_GBps": 613.3, "decompress_GBps": 2181.8, "ratio": 1.324, "hardware": "NVIDIA H200, real Qwen3-32B BF16 KV"},
+        "B_hide_GBps": round(min(comp_gbps, dec_gbps) / ratio, 1),
+        "paper_context": {"compress_GBps": 613.3, "decompress_GBps": 2181.8, "ratio": 1.324,
+                          "hardware": "NVIDIA H200, real Qwen3-32B BF16 KV (Table 2)"},
         "roofline": {
-            "kernel": "compress_kernel<1024, Bf16>" if dtype == sz.BF16 else "compress_kernel<1024, E5m2>",
+            "kernel": f"compress_batch_kernel<1024, {fmt}>",
             "bound": "hbm", "achieved": round(c_ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": round(c_ach / HBM_PEAK_GBPS, 4), "traffic": None,
-            "launch_us": round(c_launch_us, 2), "algorithmic_bytes_per_launch": int(alg_bytes),
+            "launch_us": round(mean(ms_c) * 1e3 / launches, 2), "algorithmic_bytes_per_launch": int(alg_bytes / launches),
         },
         "roofline_decompress": {
-            "kernel": "decompress_kernel<DBf16>" if dtype == sz.BF16 else "decompress_kernel<DE5m2>",
+            "kernel": f"decompress_batch_kernel<D{fmt}>",
             "bound": "hbm", "achieved": round(d_ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": round(d_ach / HBM_PEAK_GBPS, 4), "traffic": None,
-            "launch_us": round(d_launch_us, 2), "algorithmic_bytes_per_launch": int(alg_bytes),
+            "launch_us": round(mean(ms_d) * 1e3 / launches, 2), "algorithmic_bytes_per_launch": int(alg_bytes / launches),
+        },
+        "per_tensor_calls": {
+            "compress_GBps": round(raw_bytes / c1_us * 1e-3, 1), "compress_launch_us": round(c1_us, 2),
+            "compress_frac_of_peak": round(alg1 / c1_us * 1e-3 / HBM_PEAK_GBPS, 4),
+            "decompress_GBps": round(raw_bytes / d1_us * 1e-3, 1), "decompress_launch_us": round(d1_us, 2),
+            "decompress_frac_of_peak": round(alg1 / d1_us * 1e-3 / HBM_PEAK_GBPS, 4),
+            "kernels": [f"compress_kernel<1024, {fmt}>", f"decompress_kernel<D{fmt}>"],
         },
         "copy_kernel_same_traffic_GBps": round(probe_gbps, 1),
     }
+    if lat:
+        result["per_call_latency"] = lat
+    if not args.layers:     # the counter summaries were taken at the workload's own size
+        for key in ("roofline", "roofline_decompress"):
+            result[key]["traffic"] = measured_traffic(args.workload, result[key]["kernel"])
 
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(args, dtype, xs, cbs, comps, totals, n, es)
+        result["cpu_baseline"] = cpu_baseline(args, dtype, xs, books, comps, totals, n, es)
     print(json.dumps(result))
 
 
-def cpu_baseline(args, dtype, xs, cbs, comps, totals, n, es):
+def cpu_baseline(args, dtype, xs, books, comps, totals, n, es):
     """The oracle as it stands, one thread, on the first few tensors of the same workload;
     its streams are also compared with the GPU's (parity at full size)."""
     import numpy as np
@@ -211,9 +300,8 @@ def cpu_baseline(args, dtype, xs, cbs, comps, totals, n, es):
     odt = oracle.BF16 if dtype == sz.BF16 else oracle.E5M2
     t_c = t_d = 0.0
     for i in range(k):
-        kind, x = xs[i]
-        xh = kv_synth.to_numpy_words(x)
-        cb = oracle.codebook_from_dec(np.array(cbs[kind].dec, np.uint8), odt)
+        xh = kv_synth.to_numpy_words(xs[i][1])
+        cb = oracle.codebook_from_dec(np.array(books[i].dec, np.uint8), odt)
         t0 = time.perf_counter()
         blob, m = oracle.compress(xh, cb)
         t1 = time.perf_counter()
