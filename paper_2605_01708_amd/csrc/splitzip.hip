@@ -1403,6 +1403,7 @@ int splitzip_compress_batch(const splitzip_item* items, uint32_t n_items, int dt
     if (it.n_elems > n_max) n_max = it.n_elems;
   }
   if (workspace_bytes < splitzip_workspace_bytes(n_max, dtype)) return SPLITZIP_ERR_CAPACITY;
+  if (n_items == 0) return SPLITZIP_OK;
 
   static const int wgs_per_cu = env_int("SPLITZIP_COMPRESS_WGS_PER_CU", 1);
   const uint32_t resident = resident_workgroups_batch();

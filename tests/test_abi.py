@@ -27,7 +27,8 @@ def test_library_exports_every_declared_symbol():
     assert {"splitzip_calibrate", "splitzip_compress", "splitzip_decompress", "splitzip_workspace_init",
             "splitzip_fixed_bytes", "splitzip_total_bytes", "splitzip_compress_bound",
             "splitzip_workspace_bytes", "splitzip_codebook_from_dec", "splitzip_strerror",
-            "splitzip_version", "splitzip_traffic_probe"} <= set(names)
+            "splitzip_version", "splitzip_traffic_probe", "splitzip_compress_batch",
+            "splitzip_decompress_batch"} <= set(names)
     L = C.CDLL(sz.lib_path())
     for n in names:
         assert hasattr(L, n), n
@@ -126,5 +127,35 @@ def test_argument_validation_without_gpu():
     assert decomp(bytes=sz.fixed_bytes(n, sz.BF16) - 1) == -3
     assert decomp(n=1 << 32) == -2
     assert decomp(dtype=2) == -1
+    # batch calls: every item is checked before anything is enqueued
+    from paper_2605_01708_amd.binding import _CDItem, _CItem
+    items = (_CItem * 2)(_CItem(base, n, base + 1024, 1 << 20, C.pointer(cb.c)),
+                         _CItem(base, n, base + 1024, 1 << 20, C.pointer(cb.c)))
+    bcomp = lambda its, k, ws=base + 2048, wsb=1 << 20, sizes=base + 3072: L.splitzip_compress_batch(  # noqa: E731
+        its, k, sz.BF16, ws, wsb, sizes, None)
+    assert bcomp(None, 2) == -1
+    assert bcomp(items, 2, ws=None) == -1
+    assert bcomp(items, 2, sizes=None) == -1
+    assert bcomp(items, 2, wsb=16) == -3
+    items[1].out_capacity = sz.fixed_bytes(n, sz.BF16) - 1
+    assert bcomp(items, 2) == -3
+    items[1].out_capacity = 1 << 20
+    items[1].d_in = base + 2
+    assert bcomp(items, 2) == -1
+    items[1].d_in = base
+    items[1].n_elems = 1 << 32
+    assert bcomp(items, 2) == -2
+    items[1].n_elems = n
+    items[1].cb = C.pointer(e5.c)
+    assert bcomp(items, 2) == -1
+    assert bcomp(items, 0) == 0                                   # an empty list is fine and launches nothing
+    ditems = (_CDItem * 2)(_CDItem(base, 1 << 20, n, base + 1024, C.pointer(cb.c)),
+                           _CDItem(base, sz.fixed_bytes(n, sz.BF16) - 1, n, base + 1024, C.pointer(cb.c)))
+    assert L.splitzip_decompress_batch(ditems, 2, sz.BF16, None, None) == -3
+    ditems[1].comp_bytes = 1 << 20
+    ditems[1].d_comp = None
+    assert L.splitzip_decompress_batch(ditems, 2, sz.BF16, None, None) == -1
+    assert L.splitzip_decompress_batch(None, 2, sz.BF16, None, None) == -1
+    assert L.splitzip_decompress_batch(ditems, 0, sz.BF16, None, None) == 0
     assert L.splitzip_workspace_init(None, 1024, None) == -1
     assert L.splitzip_traffic_probe(None, 16, base, 16, None) == -1

@@ -315,6 +315,47 @@ def test_batch_calls_match_the_oracle_item_by_item(dtype):
         assert (ys[k][x.size:].cpu().numpy() == (0x5A if es == 1 else 0x5A5A)).all()
 
 
+def run_env_case(case, **env):
+    import os
+    import subprocess
+    import sys
+    here = os.path.dirname(os.path.abspath(__file__))
+    e = dict(os.environ, **{k: str(v) for k, v in env.items()})
+    print(f"subprocess case {case} env {env}", flush=True)
+    r = subprocess.run([sys.executable, "-u", os.path.join(here, "gpu_env_case.py"), case], env=e, capture_output=True,
+                       text=True, timeout=110)
+    assert r.returncode == 0 and "CASE-OK" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
+
+
+def test_tensor_that_takes_several_launches():
+    """a small grid (4 workgroups) makes a 5 Mi-element tensor take one launch per segment plus the finishing one"""
+    run_env_case("several_launches", SPLITZIP_COMPRESS_MAX_WGS=4)
+
+
+def test_exchange_that_never_completes_is_reported():
+    """the wait between workgroups is bounded: forced from the host, it ends with STATUS_INTERNAL, not a hang"""
+    run_env_case("exchange_timeout", SPLITZIP_TEST_AWAIT_EXTRA_WGS=1, SPLITZIP_SPIN_TICKS=20000)
+
+
+def test_escape_stress_full_size():
+    """config 2 at its real tensor size [16384, 8, 128]: ~0.7 % escapes, bursts included"""
+    x = kv_synth.to_numpy_words(kv_synth.kv_bf16_outliers(16384, 0, 3, device="cuda"))
+    cb = calibrated(sz.BF16)
+    g = Gpu(x.size, sz.BF16)
+    total, m = check_parity(g, x, cb, "config2 L3")
+    print(f"config2 L3: eps={m / x.size:.5f} ratio={2 * x.size / total:.4f}", flush=True)
+    assert 0.004 < m / x.size < 0.05
+
+
+def test_streaming_chunk_shape():
+    """config 3's call shape: [2048, 8, 128] K and V of a deep layer, per-kind codebooks"""
+    g = Gpu(2048 * 1024, sz.BF16)
+    for layer, kind in ((79, "K"), (40, "V")):
+        cb = calibrated(sz.BF16, seed=1, tokens=1024, layer=0, kind=kind)
+        x = synth(sz.BF16, 2048, 0, layer, kind)
+        check_parity(g, x, cb, f"config3 L{layer}{kind}")
+
+
 def test_full_size_e5m2_tensor():
     """config 4 at its real tensor size [32768, 8, 128] E5M2 (32 MiB): V of layer 17"""
     n = 32768 * 1024
