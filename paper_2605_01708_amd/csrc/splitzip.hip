@@ -489,12 +489,18 @@ __device__ inline void my_range(uint32_t chunk0, uint32_t chunks, uint32_t wgs, 
   r0 = chunk0 + b * per + (b < rem ? b : rem);
 }
 
+struct NoHook {
+  __device__ inline void operator()() const {}
+};
+
 // dense pass of one wave over its chunks of the range; the next chunk's loads are issued before
-// this chunk is worked on.  Returns the wave's escape count.
-template <int NW, typename F>
+// this chunk is worked on.  `mid` is called once, half way through (not at all by a wave without
+// chunks).  Returns the wave's escape count.
+template <int NW, typename F, typename Hook>
 __device__ inline uint32_t dense_pass(const Planes& P, const uint16_t* lut, uint32_t* park, const RangeLds& L,
-                                      uint32_t r0, uint32_t nb, int wave, int lane) {
+                                      uint32_t r0, uint32_t nb, int wave, int lane, Hook& mid) {
   uint32_t wave_count = 0;
+  const uint32_t mid_it = nb > (uint32_t)wave ? ((nb - wave + NW - 1) / NW) / 2 : 0u;
   typename F::Regs w, nx;
   if ((uint32_t)wave < nb) {
     const uint64_t cbase = (uint64_t)(r0 + wave) * kChunk;
@@ -508,6 +514,7 @@ __device__ inline uint32_t dense_pass(const Planes& P, const uint16_t* lut, uint
       if (F::full(P, nbase)) F::template load<true>(P, nbase, lane, nx);
       else F::template load<false>(P, nbase, lane, nx);
     }
+    if (it == mid_it) mid();
     const LdsSink lds{L.stage_pk, L.stage_val, it << 10};
     const uint32_t cnt = F::full(P, cbase) ? F::template process<true, true>(P, lut, park, cbase, lane, w, wave_count, lds)
                                            : F::template process<false, true>(P, lut, park, cbase, lane, w, wave_count, lds);
@@ -646,7 +653,8 @@ __global__ __launch_bounds__(T) void compress_kernel(const CompressArgs a) {
 
   uint32_t r0, nb;
   my_range(a.seg_chunk0, a.seg_chunks, gridDim.x, b, r0, nb);
-  const uint32_t wave_count = dense_pass<NW, F>(a.p, lut, park, L, r0, nb, wave, lane);
+  NoHook no_hook;
+  const uint32_t wave_count = dense_pass<NW, F>(a.p, lut, park, L, r0, nb, wave, lane, no_hook);
   if (lane == 0) s_red[wave] = wave_count;
   __syncthreads();
 #ifdef EXP_TIMING
@@ -719,20 +727,43 @@ struct CompressBatchArgs {
   BatchItem item[kBatchMax];
   uint8_t lut_of[kBatchMax];
   splitzip_sizes* sizes;     // n_items records
-  uint32_t* ws_hdr;
-  uint64_t* state;           // kRing slots of kRingWgs words: (epoch + item) << 32 | escapes in the workgroup's range
+  uint32_t* ws_hdr;          // [0] epoch, [2] sticky error flags, [3] groups that are through
+  uint64_t* state;           // per group kRing slots of group_wgs words: (epoch + item) << 32 | escapes in the range
   uint64_t spin_ticks;
-  uint32_t n_items, dtype, expect_wgs, reserved;
+  uint32_t n_items, dtype;
+  uint32_t group_wgs;        // workgroups that share one tensor; the grid is n_groups * group_wgs
+  uint32_t await_extra;      // error-path tests: words awaited beyond the group's
   uint8_t dec[kBatchLuts][16];
   uint16_t lut[kBatchLuts][256];
 };
 
+// wave 0, half way through a dense pass: the loads of the previous tensor's exchange words, so that
+// their latency is hidden.  Up to 256 workgroups per group (four words per lane).
+struct ExchangePrefetch {
+  const uint64_t* slot;
+  uint32_t wgs;
+  int lane;
+  bool enabled, issued;
+  uint64_t v[4];
+  __device__ inline void operator()() {
+    if (!enabled) return;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t i = lane + 64 * j;
+      v[j] = i < wgs ? ld_agent(&slot[i]) : 0ull;
+    }
+    issued = true;
+  }
+};
+
 // The same persistent grid works through the tensors one after the other, and the exchange of
 // tensor i is taken out of the critical path: a workgroup publishes its count for tensor i, then
-// completes tensor i - 1 (whose counts every workgroup published a whole dense pass ago, so the
-// read finds them at once) and goes on to tensor i + 1.  Staging in LDS is double buffered.  What
-// a single launch pays per tensor -- the wait for the slowest workgroup, the exchange, the
-// write-out and the launch itself -- is paid once per batch here.
+// completes tensor i - 1 (whose counts every workgroup published a whole dense pass ago; the words
+// are even fetched half way through the dense pass of tensor i, so the read costs nothing) and
+// goes on to tensor i + 1.  Staging in LDS is double buffered.  What a single launch pays per
+// tensor -- the wait for the slowest workgroup, the exchange, the write-out and the launch itself
+// -- is paid once per batch here.  Small tensors are shared by a group of workgroups only; the
+// groups work on different tensors at the same time (tensor i belongs to group i mod n_groups).
 template <int T, typename F>
 __global__ __launch_bounds__(T) void compress_batch_kernel(const CompressBatchArgs a) {
   constexpr int NW = T / 64;
@@ -746,7 +777,8 @@ __global__ __launch_bounds__(T) void compress_batch_kernel(const CompressBatchAr
   __shared__ uint32_t s_misc[4];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const uint32_t b = blockIdx.x, W = gridDim.x;
+  const uint32_t G = a.group_wgs, n_groups = gridDim.x / G;
+  const uint32_t grp = blockIdx.x / G, b = blockIdx.x % G;
   uint32_t* park = reinterpret_cast<uint32_t*>(&s_park[tid]);
 
   for (int i = tid; i < (int)(kBatchLuts * 256); i += T) lut[i >> 8][i & 255] = a.lut[i >> 8][i & 255];
@@ -755,31 +787,60 @@ __global__ __launch_bounds__(T) void compress_batch_kernel(const CompressBatchAr
   if (tid == 0) s_misc[3] = 0;   // set once an exchange was given up: later ones are not waited for
   __syncthreads();
 
+  uint64_t* const ring = a.state + (uint64_t)grp * kRing * G;   // this group's slots
   Planes Pprev = make_planes(nullptr, nullptr, 0, 0, (int)a.dtype);
-  uint32_t prev_count = 0, prev_r0 = 0, prev_nb = 0;
-  for (uint32_t i = 0; i <= a.n_items; ++i) {
+  uint32_t prev_count = 0, prev_r0 = 0, prev_nb = 0, prev_item = 0;
+  // this group's tensors: grp, grp + n_groups, ...; seq counts them
+  for (uint32_t seq = 0;; ++seq) {
+    const uint32_t i = grp + seq * n_groups;
     const bool have = i < a.n_items;
-    const uint32_t set = i & 1u;
+    if (!have && seq == 0) break;   // a group without tensors
+    const uint32_t set = seq & 1u;
     const RangeLds L{stage_pk[set][wave], stage_val[set][wave], s_off[set], s_wstart[set]};
     Planes P = Pprev;
     uint32_t r0 = 0, nb = 0, wave_count = 0;
+    ExchangePrefetch pf;
+    pf.slot = ring + ((seq + kRing - 1) % kRing) * G;
+    pf.wgs = G;
+    pf.lane = lane;
+    pf.enabled = wave == 0 && seq > 0 && G <= 256 && a.await_extra == 0;
+    pf.issued = false;
     if (have) {
       P = make_planes(a.item[i].in, a.item[i].out, a.item[i].n, a.item[i].capacity, (int)a.dtype);
-      my_range(0, P.n_chunks, W, b, r0, nb);
-      wave_count = dense_pass<NW, F>(P, lut[a.lut_of[i]], park, L, r0, nb, wave, lane);
+      my_range(0, P.n_chunks, G, b, r0, nb);
+      wave_count = dense_pass<NW, F>(P, lut[a.lut_of[i]], park, L, r0, nb, wave, lane, pf);
       if (lane == 0) s_red[wave] = wave_count;
     }
     __syncthreads();
     if (wave == 0) {
       if (have) {
         const uint32_t agg = wave_last(wave_incl_scan(lane < NW ? s_red[lane] : 0u));
-        if (lane == 0) st_agent(&a.state[(i % kRing) * kRingWgs + b], ((uint64_t)(epoch + i) << 32) | agg);
+        if (lane == 0) st_agent(&ring[(seq % kRing) * G + b], ((uint64_t)(epoch + i) << 32) | agg);
       }
-      if (i > 0) {
-        // complete tensor i - 1
-        uint32_t lo, al;
-        const bool ok = exchange(a.state + ((i - 1) % kRing) * kRingWgs, epoch + i - 1, a.expect_wgs, b, lane,
-                                 a.spin_ticks, s_misc[3] != 0, lo, al);
+      if (seq > 0) {
+        // complete the previous tensor: from the prefetched words if they were all there
+        const uint32_t tag = epoch + prev_item;
+        uint32_t lo = 0, al = 0;
+        bool ok = true, done = false;
+        if (pf.issued) {
+          int ready = 1;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const uint32_t q = lane + 64 * j;
+            if (q < G) {
+              if ((uint32_t)(pf.v[j] >> 32) != tag) ready = 0;
+              al += (uint32_t)pf.v[j];
+              lo += q < b ? (uint32_t)pf.v[j] : 0u;
+            }
+          }
+          if (__ballot(ready) == ~0ull) {
+            lo = wave_last(wave_incl_scan(lo));
+            al = wave_last(wave_incl_scan(al));
+            done = true;
+          }
+        }
+        if (!done)
+          ok = exchange(ring + ((seq - 1) % kRing) * G, tag, G + a.await_extra, b, lane, a.spin_ticks, s_misc[3] != 0, lo, al);
         if (lane == 0) {
           s_misc[0] = lo;
           s_misc[1] = al;
@@ -788,11 +849,17 @@ __global__ __launch_bounds__(T) void compress_batch_kernel(const CompressBatchAr
         }
         if (b == 0) {
           const uint32_t err = err_before | (ok ? 0u : (uint32_t)SPLITZIP_STATUS_INTERNAL);
-          compress_write_trailer(Pprev, a.dec[a.lut_of[i - 1]], a.sizes + (i - 1), al, err, lane);
+          compress_write_trailer(Pprev, a.dec[a.lut_of[prev_item]], a.sizes + prev_item, al, err, lane);
           if (!have && lane == 0) {
-            // the launch ends here; every workgroup has read the header words long ago
-            st_agent(&a.ws_hdr[0], epoch + a.n_items);
-            st_agent(&a.ws_hdr[2], 0u);
+            // this group is through.  The last group to get here closes the launch: by then every
+            // workgroup has read the header words, because each group completed an exchange.
+            const uint32_t through = __hip_atomic_fetch_add(&a.ws_hdr[3], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const uint32_t active = a.n_items < n_groups ? a.n_items : n_groups;
+            if (through + 1 == active) {
+              st_agent(&a.ws_hdr[3], 0u);
+              st_agent(&a.ws_hdr[2], 0u);
+              st_agent(&a.ws_hdr[0], epoch + a.n_items);
+            }
           }
         }
       }
@@ -800,17 +867,19 @@ __global__ __launch_bounds__(T) void compress_batch_kernel(const CompressBatchAr
       scan_range(s_off[set], nb, lane);
     }
     __syncthreads();
-    if (i > 0 && s_misc[2] == 0) {
+    if (seq > 0 && s_misc[2] == 0) {
       const uint32_t pset = set ^ 1u;
       const RangeLds Lp{stage_pk[pset][wave], stage_val[pset][wave], s_off[pset], s_wstart[pset]};
-      write_out<NW, F>(Pprev, lut[a.lut_of[i - 1]], park, Lp, prev_r0, prev_nb, prev_count, s_misc[0],
+      write_out<NW, F>(Pprev, lut[a.lut_of[prev_item]], park, Lp, prev_r0, prev_nb, prev_count, s_misc[0],
                        final_sink(Pprev, s_misc[1]), tid, wave, lane);
     }
+    if (!have) break;
     __syncthreads();   // the previous tensor's LDS set is free again, s_misc may be rewritten
     Pprev = P;
     prev_count = wave_count;
     prev_r0 = r0;
     prev_nb = nb;
+    prev_item = i;
   }
 }
 
@@ -1415,6 +1484,7 @@ int splitzip_compress_batch(const splitzip_item* items, uint32_t n_items, int dt
   if (max_wgs && W > (uint32_t)max_wgs) W = (uint32_t)max_wgs;
   const uint64_t chunk_cap = (uint64_t)W * kMaxRange;   // chunks of one tensor the batch kernel can take
   static const int spin_env = env_int("SPLITZIP_SPIN_TICKS", 0);
+  static const int missing = env_int("SPLITZIP_TEST_AWAIT_EXTRA_WGS", 0);   // error-path tests only
   const hipStream_t st = static_cast<hipStream_t>(stream);
   uint8_t* ws = static_cast<uint8_t*>(d_workspace);
 
@@ -1458,9 +1528,22 @@ int splitzip_compress_batch(const splitzip_item* items, uint32_t n_items, int dt
     a.spin_ticks = spin_env ? (uint64_t)spin_env : kSpinTicks;
     a.n_items = k;
     a.dtype = (uint32_t)dtype;
-    a.expect_wgs = W;
-    if (dtype == SPLITZIP_BF16) hipLaunchKernelGGL((compress_batch_kernel<1024, Bf16>), dim3(W), dim3(1024), 0, st, a);
-    else hipLaunchKernelGGL((compress_batch_kernel<1024, E5m2>), dim3(W), dim3(1024), 0, st, a);
+    // Workgroups per tensor: all of them for large tensors; for small ones a power-of-two share that
+    // leaves each workgroup about 64 chunks, the groups working on different tensors side by side.
+    uint64_t chunks_max = 0;
+    for (uint32_t q = 0; q < k; ++q) {
+      const uint64_t c = (a.item[q].n + kChunk - 1) / kChunk;
+      if (c > chunks_max) chunks_max = c;
+    }
+    uint32_t G = W;
+    while (G > 8 && G % 2 == 0 && (uint64_t)(G / 2) * 64 >= chunks_max) G /= 2;
+    while ((uint64_t)G * kMaxRange < chunks_max) G *= 2;   // never beyond W: chunks_max <= chunk_cap
+    if (G > W) G = W;
+    a.group_wgs = G;
+    a.await_extra = (uint32_t)missing;
+    const uint32_t grid = (W / G) * G;
+    if (dtype == SPLITZIP_BF16) hipLaunchKernelGGL((compress_batch_kernel<1024, Bf16>), dim3(grid), dim3(1024), 0, st, a);
+    else hipLaunchKernelGGL((compress_batch_kernel<1024, E5m2>), dim3(grid), dim3(1024), 0, st, a);
     if (hipGetLastError() != hipSuccess) return SPLITZIP_ERR_HIP;
     i += k;
   }
