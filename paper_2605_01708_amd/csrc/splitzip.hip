@@ -943,9 +943,10 @@ __device__ void decompress_check_header(const DecompressArgs& a, const uint8_t* 
   }
 }
 
-// dense decode of one chunk by one wave: two half-chunks, 8 elements per lane each
+// BF16 dense decode of one chunk by one wave into registers: two half-chunks, 8 elements per lane
+// each; o[4 h + d] holds elements 2 d and 2 d + 1 of the lane's group in half h
 template <bool FULL>
-__device__ inline void decompress_chunk_bf16(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane) {
+__device__ inline void decode_chunk_bf16(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane, uint32_t (&o)[8]) {
   u32x2 sm[2];
   uint32_t cd[2];
 #pragma unroll
@@ -959,36 +960,43 @@ __device__ inline void decompress_chunk_bf16(const DecompressArgs& a, const uint
   }
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
-    const uint64_t g0 = cbase + h * kHalf + lane * 8;
     const uint32_t smw[2] = {sm[h].x, sm[h].y};
-    uint32_t o[4];
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
       // code byte b -> both exponents already in place (bits 7..14 and 23..30)
       const uint32_t cb = (cd[h] >> (8 * b)) & 0xffu;
       // [a0, a0, a1, a1], then keep mantissa in the low and sign in the high byte of each half-word (eq. (2))
       const uint32_t p = byte_perm(0u, smw[b >> 1], (b & 1) ? 0x03030202u : 0x01010000u);
-      o[b] = (p & 0x807f807fu) | tbl[cb];
+      o[4 * h + b] = (p & 0x807f807fu) | tbl[cb];
     }
+  }
+}
+
+template <bool FULL>
+__device__ inline void store_chunk_bf16(const DecompressArgs& a, uint64_t cbase, int lane, const uint32_t (&o)[8]) {
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const uint64_t g0 = cbase + h * kHalf + lane * 8;
     uint32_t nvalid = 8;
     if (!FULL) nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 8 ? a.n - g0 : 8);
     if (FULL || nvalid == 8) {
-      st_stream(reinterpret_cast<u32x4*>(a.out + 2 * g0), u32x4{o[0], o[1], o[2], o[3]});
+      st_stream(reinterpret_cast<u32x4*>(a.out + 2 * g0), u32x4{o[4 * h], o[4 * h + 1], o[4 * h + 2], o[4 * h + 3]});
     } else {
       uint16_t* q = reinterpret_cast<uint16_t*>(a.out) + g0;
 #pragma unroll
       for (int d = 0; d < 4; ++d) {
-        if ((uint32_t)(2 * d) < nvalid) q[2 * d] = (uint16_t)o[d];
-        if ((uint32_t)(2 * d + 1) < nvalid) q[2 * d + 1] = (uint16_t)(o[d] >> 16);
+        if ((uint32_t)(2 * d) < nvalid) q[2 * d] = (uint16_t)o[4 * h + d];
+        if ((uint32_t)(2 * d + 1) < nvalid) q[2 * d + 1] = (uint16_t)(o[4 * h + d] >> 16);
       }
     }
   }
 }
 
-// E5M2 dense decode of one chunk by one wave: 16 elements per lane.  Lanes 2p and 2p+1 share 12
-// plane bytes: the even lane loads the first 8, the odd lane the last 4.
+// E5M2 dense decode of one chunk by one wave into registers: 16 elements per lane, o[d] holds
+// elements 4 d .. 4 d + 3.  Lanes 2p and 2p+1 share 12 plane bytes: the even lane loads the first
+// 8, the odd lane the last 4.
 template <bool FULL>
-__device__ inline void decompress_chunk_e5m2(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane) {
+__device__ inline void decode_chunk_e5m2(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane, uint32_t (&o)[4]) {
   const uint64_t g0 = cbase + lane * 16;
   const uint64_t sm_off = (cbase / 8) * 3 + (uint32_t)(lane >> 1) * 12;
   const uint8_t* sm_src = a.comp + a.off_sm + sm_off;
@@ -1011,13 +1019,17 @@ __device__ inline void decompress_chunk_e5m2(const DecompressArgs& a, const uint
   const uint32_t hi = (lane & 1) ? d0 >> 16 : d1 & 0xffffu;
   const uint32_t r[4] = {lo & 0xfffu, (lo >> 12) & 0xfffu, (lo >> 24) | ((hi & 0xfu) << 8), (hi >> 4) & 0xfffu};
   const uint32_t cdw[2] = {cd.x, cd.y};
-  uint32_t o[4];
 #pragma unroll
   for (int d = 0; d < 4; ++d) {
     // two code bytes -> four exponents already in place (bits 2..6 of each byte)
     const uint32_t c01 = (cdw[d >> 1] >> (16 * (d & 1))) & 0xffu, c23 = (cdw[d >> 1] >> (16 * (d & 1) + 8)) & 0xffu;
     o[d] = unpack3_e5m2(r[d]) | tbl[c01] | (tbl[c23] << 16);
   }
+}
+
+template <bool FULL>
+__device__ inline void store_chunk_e5m2(const DecompressArgs& a, uint64_t cbase, int lane, const uint32_t (&o)[4]) {
+  const uint64_t g0 = cbase + lane * 16;
   uint32_t nvalid = 16;
   if (!FULL) nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 16 ? a.n - g0 : 16);
   if (FULL || nvalid == 16) {
@@ -1030,14 +1042,32 @@ __device__ inline void decompress_chunk_e5m2(const DecompressArgs& a, const uint
   }
 }
 
+// in-register scatter correction: dword r of the owning lane gets (o & ~mask) | bits; r is
+// wave-uniform, so the choice of the register is a scalar branch
+template <int R>
+__device__ inline void patch_regs(uint32_t (&o)[R], uint32_t r, bool mine, uint32_t mask, uint32_t bits) {
+#pragma unroll
+  for (int q = 0; q < R; ++q)
+    if (r == (uint32_t)q && mine) o[q] = (o[q] & ~mask) | bits;
+}
+
 // the two formats as seen by the decompress kernel
 struct DBf16 {
+  struct Out { uint32_t o[8]; };
   // table entry for a code byte: both exponents in place for one dword of output
   __device__ static inline uint32_t table(int cb, const uint8_t* dec) { return ((uint32_t)dec[cb & 15] << 7) | ((uint32_t)dec[cb >> 4] << 23); }
   __device__ static inline bool full(const DecompressArgs& a, uint64_t cbase) { return cbase + kChunk <= a.n; }
   template <bool FULL>
-  __device__ static inline void chunk(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane) { decompress_chunk_bf16<FULL>(a, tbl, cbase, lane); }
-  // the scatter correction of one element: exponent field := val, sign and mantissa from the stream
+  __device__ static inline void decode(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane, Out& r) { decode_chunk_bf16<FULL>(a, tbl, cbase, lane, r.o); }
+  template <bool FULL>
+  __device__ static inline void store(const DecompressArgs& a, uint64_t cbase, int lane, const Out& r) { store_chunk_bf16<FULL>(a, cbase, lane, r.o); }
+  // the scatter correction of the element at chunk position pos (wave-uniform), in the registers of the lane that holds it
+  __device__ static inline bool patch_reg(Out& r, int lane, uint32_t pos, uint32_t val) {
+    const uint32_t q = pos & 511u, e = q & 7u, sh = 16u * (e & 1u);
+    patch_regs<8>(r.o, 4u * (pos >> 9) + (e >> 1), (uint32_t)lane == (q >> 3), 0x7f80u << sh, val << (7u + sh));
+    return true;
+  }
+  // the same on the tensor in memory: exponent field := val, sign and mantissa from the stream
   __device__ static inline bool patch(const DecompressArgs& a, uint64_t i, uint32_t val) {
     const uint32_t sa = a.comp[a.off_sm + i];
     reinterpret_cast<uint16_t*>(a.out)[i] = (uint16_t)(((sa & 0x80u) << 8) | (val << 7) | (sa & 0x7fu));
@@ -1045,10 +1075,19 @@ struct DBf16 {
   }
 };
 struct DE5m2 {
+  struct Out { uint32_t o[4]; };
   __device__ static inline uint32_t table(int cb, const uint8_t* dec) { return ((uint32_t)dec[cb & 15] << 2) | ((uint32_t)dec[cb >> 4] << 10); }
   __device__ static inline bool full(const DecompressArgs& a, uint64_t cbase) { return cbase + kChunk < a.n; }
   template <bool FULL>
-  __device__ static inline void chunk(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane) { decompress_chunk_e5m2<FULL>(a, tbl, cbase, lane); }
+  __device__ static inline void decode(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane, Out& r) { decode_chunk_e5m2<FULL>(a, tbl, cbase, lane, r.o); }
+  template <bool FULL>
+  __device__ static inline void store(const DecompressArgs& a, uint64_t cbase, int lane, const Out& r) { store_chunk_e5m2<FULL>(a, cbase, lane, r.o); }
+  __device__ static inline bool patch_reg(Out& r, int lane, uint32_t pos, uint32_t val) {
+    if (val > 31u) return false;
+    const uint32_t e = pos & 15u, sh = 8u * (e & 3u);
+    patch_regs<4>(r.o, e >> 2, (uint32_t)lane == (pos >> 4), 0x7cu << sh, val << (2u + sh));
+    return true;
+  }
   __device__ static inline bool patch(const DecompressArgs& a, uint64_t i, uint32_t val) {
     if (val > 31u) return false;
     const uint64_t bit = 3 * i;
@@ -1061,15 +1100,23 @@ struct DE5m2 {
   }
 };
 
+constexpr uint32_t kRegPatchMax = 32;   // escapes of a chunk that are applied in registers, before the store
+
 // one workgroup: tile `tile` of the tensor described by a (4 waves x cpw chunks)
 template <typename F>
 __device__ inline void decompress_tile(const DecompressArgs& a, const uint8_t* dec, uint32_t tile, uint32_t* tbl) {
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t* tab = reinterpret_cast<const uint32_t*>(a.comp + a.off_tab);
+  const uint32_t cpw = a.cpw;
+  const uint32_t wave_chunk0 = (tile * kWaves + wave) * cpw;
+  // first of all the loads everything else waits for: this wave's slice of the offset table (lane c
+  // <-> its chunk c, one entry more for the end) and M as the table states it
+  const uint32_t my_tab = (uint32_t)lane <= cpw && wave_chunk0 + lane <= a.n_chunks ? tab[wave_chunk0 + lane] : 0u;
+  uint32_t M = tab[a.n_chunks];
   tbl[tid] = F::table(tid, dec);
 
-  const uint32_t* tab = reinterpret_cast<const uint32_t*>(a.comp + a.off_tab);
-  // M as the offset table states it; escapes are only trusted if their sections lie inside the stream
-  uint32_t M = tab[a.n_chunks];
+  // escapes are only trusted if their sections lie inside the stream
   const uint64_t off_val = a.off_pos + a256(2ull * M);
   const bool esc_ok = M <= a.n && off_val + M <= a.comp_bytes;
   if (tile == 0 && tid == 0) {
@@ -1081,30 +1128,46 @@ __device__ inline void decompress_tile(const DecompressArgs& a, const uint8_t* d
   const uint8_t* val_arr = a.comp + off_val;
   __syncthreads();
 
-  const uint32_t cpw = a.cpw;
-  const uint32_t wave_chunk0 = (tile * kWaves + wave) * cpw;
   for (uint32_t c = 0; c < cpw; ++c) {
     const uint32_t chunk = wave_chunk0 + c;
     if (chunk >= a.n_chunks) break;
     const uint64_t cbase = (uint64_t)chunk * kChunk;
-    const uint32_t lo = tab[chunk], hi = tab[chunk + 1];
-    if (F::full(a, cbase))
-      F::template chunk<true>(a, tbl, cbase, lane);
-    else
-      F::template chunk<false>(a, tbl, cbase, lane);
-    // sparse overwrite (the exponent field of x at every recorded position), by the wave that
-    // wrote the chunk, once its dense stores have completed
-    if (hi == lo) continue;
+    const uint32_t lo = __builtin_amdgcn_readlane(my_tab, c), hi = __builtin_amdgcn_readlane(my_tab, c + 1);
     const uint32_t clen = (uint32_t)(a.n - cbase < kChunk ? a.n - cbase : kChunk);
-    if (hi < lo || hi - lo > clen || hi > M) {
-      if (lane == 0) flag_bad(a);
-      continue;
+    const bool esc_valid = hi >= lo && hi - lo <= clen && hi <= M;
+    const uint32_t cnt = esc_valid ? hi - lo : 0u;
+    if (!esc_valid && lane == 0) flag_bad(a);
+    // a few escapes (the usual case): their records are fetched while the planes are on their way,
+    // and applied to the decoded words in registers before the one store
+    const bool in_regs = cnt > 0 && cnt <= kRegPatchMax;
+    uint32_t pos = 0, val = 0;
+    if (in_regs && (uint32_t)lane < cnt) {
+      pos = pos_arr[lo + lane];
+      val = val_arr[lo + lane];
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    for (uint32_t j = lo + lane; j < hi; j += 64) {
-      const uint32_t pos = pos_arr[j];
-      const uint32_t val = val_arr[j];
-      if (pos >= clen || !F::patch(a, cbase + pos, val)) flag_bad(a);
+    typename F::Out r;
+    const bool full = F::full(a, cbase);
+    if (full) F::template decode<true>(a, tbl, cbase, lane, r);
+    else F::template decode<false>(a, tbl, cbase, lane, r);
+    if (in_regs) {
+      for (uint32_t j = 0; j < cnt; ++j) {
+        const uint32_t p = __builtin_amdgcn_readlane(pos, j), v = __builtin_amdgcn_readlane(val, j);
+        if (p >= clen || !F::patch_reg(r, lane, p, v)) {
+          if (lane == 0) flag_bad(a);
+        }
+      }
+    }
+    if (full) F::template store<true>(a, cbase, lane, r);
+    else F::template store<false>(a, cbase, lane, r);
+    if (cnt > kRegPatchMax) {
+      // many escapes: sparse overwrite of the tensor in memory by the wave that wrote the chunk,
+      // once its dense stores have completed
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      for (uint32_t j = lo + lane; j < hi; j += 64) {
+        const uint32_t p = pos_arr[j];
+        const uint32_t v = val_arr[j];
+        if (p >= clen || !F::patch(a, cbase + p, v)) flag_bad(a);
+      }
     }
   }
 }
@@ -1213,6 +1276,15 @@ uint32_t pick_cpw(uint64_t n_chunks, uint32_t most, uint32_t want_tiles_per_cu) 
   uint32_t cpw = most;
   while (cpw > 1 && (n_chunks + (uint64_t)kWaves * cpw - 1) / (kWaves * cpw) < want) cpw >>= 1;
   return cpw;
+}
+
+// Chunks per wave of a decompress launch over n_chunks chunks in all.  Measured on 64 MiB BF16 /
+// 32 MiB E5M2 tensors: BF16 wants one chunk per wave for a single tensor (32 768 chunks) and two for
+// a whole cache in one launch; E5M2 wants four and eight.
+uint32_t pick_decompress_cpw(uint64_t n_chunks, int dtype, int tiles_per_cu_env) {
+  const uint32_t most = dtype == SPLITZIP_BF16 ? 2 : 8;
+  const uint32_t want = tiles_per_cu_env ? (uint32_t)tiles_per_cu_env : (dtype == SPLITZIP_BF16 ? 32u : 8u);
+  return pick_cpw(n_chunks, most, want);
 }
 
 // tables must describe one bijection between 16 codes and 16 distinct exponents
@@ -1442,9 +1514,8 @@ int splitzip_decompress(const void* d_comp, size_t comp_bytes, uint64_t n_elems,
   a.off_tab = L.off_tab; a.off_sm = L.off_sm; a.off_code = L.off_code; a.off_pos = L.off_pos;
   a.sm_bytes = L.sm_bytes; a.code_bytes = L.code_bytes;
   static const int cpw_env = env_int("SPLITZIP_DECOMPRESS_CPW", 0);
-  static const int tiles_per_cu = env_int("SPLITZIP_DECOMPRESS_TILES_PER_CU", 8);
-  // measured on 64 MiB / 32 MiB tensors: BF16 is fastest with one chunk per wave, E5M2 with four
-  a.cpw = cpw_env ? (uint32_t)cpw_env : pick_cpw(L.n_chunks, dtype == SPLITZIP_BF16 ? 1 : 4, (uint32_t)tiles_per_cu);
+  static const int tiles_per_cu = env_int("SPLITZIP_DECOMPRESS_TILES_PER_CU", 0);
+  a.cpw = cpw_env ? (uint32_t)cpw_env : pick_decompress_cpw(L.n_chunks, dtype, tiles_per_cu);
   if (a.cpw > kMaxCpw) a.cpw = kMaxCpw;
   a.n_chunks = (uint32_t)L.n_chunks;
   a.n_tiles = (uint32_t)((L.n_chunks + (uint64_t)kWaves * a.cpw - 1) / (kWaves * a.cpw));
@@ -1561,7 +1632,7 @@ int splitzip_decompress_batch(const splitzip_ditem* items, uint32_t n_items, int
     if (it.comp_bytes < splitzip_fixed_bytes(it.n_elems, dtype)) return SPLITZIP_ERR_CAPACITY;
   }
   static const int cpw_env = env_int("SPLITZIP_DECOMPRESS_CPW", 0);
-  static const int tiles_per_cu = env_int("SPLITZIP_DECOMPRESS_TILES_PER_CU", 8);
+  static const int tiles_per_cu = env_int("SPLITZIP_DECOMPRESS_TILES_PER_CU", 0);
   uint32_t i = 0;
   while (i < n_items) {
     DecompressBatchArgs a;
@@ -1588,7 +1659,7 @@ int splitzip_decompress_batch(const splitzip_ditem* items, uint32_t n_items, int
     }
     a.sizes = d_sizes;
     a.dtype = (uint32_t)dtype;
-    a.cpw = cpw_env ? (uint32_t)cpw_env : pick_cpw(chunks_all, dtype == SPLITZIP_BF16 ? 1 : 4, (uint32_t)tiles_per_cu);
+    a.cpw = cpw_env ? (uint32_t)cpw_env : pick_decompress_cpw(chunks_all, dtype, tiles_per_cu);
     if (a.cpw > kMaxCpw) a.cpw = kMaxCpw;
     uint64_t gx = (chunks_max + (uint64_t)kWaves * a.cpw - 1) / (kWaves * a.cpw);
     if (gx < 1) gx = 1;
