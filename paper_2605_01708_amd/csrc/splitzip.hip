@@ -220,7 +220,11 @@ __device__ inline void load_chunk_bf16(const Planes& a, uint64_t cbase, int lane
     const uint64_t g0 = cbase + h * kHalf + lane * 8;   // first element of this lane's group
     uint32_t nvalid = 8;
     if (!FULL) nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 8 ? a.n - g0 : 8);
-    if (FULL || nvalid == 8) {
+    if (FULL) {
+      // chunk pointer (wave-uniform) + a 32-bit lane offset: no 64-bit vector arithmetic
+      const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(a.in + 2 * cbase) + (uint32_t)(h * 64 + lane));
+      w[h][0] = v.x; w[h][1] = v.y; w[h][2] = v.z; w[h][3] = v.w;
+    } else if (nvalid == 8) {
       const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(a.in + 2 * g0));
       w[h][0] = v.x; w[h][1] = v.y; w[h][2] = v.z; w[h][3] = v.w;
     } else {
@@ -259,14 +263,15 @@ __device__ inline uint32_t process_chunk_bf16(const Planes& a, const uint16_t* l
     if (STORE) {
       // Sections are padded to 256 bytes and a lane's group never straddles the padded end, so
       // whole-group stores also write the zero padding.
-      if (FULL || g0 < a256(a.sm_bytes)) st_stream(reinterpret_cast<u32x2*>(a.out + a.off_sm + g0), sm);
-      if (FULL || (g0 >> 1) < a256(a.code_bytes))
-        st_stream(reinterpret_cast<uint32_t*>(a.out + a.off_code + (g0 >> 1)), code);
+      if (FULL) {
+        st_stream(reinterpret_cast<u32x2*>(a.out + a.off_sm + cbase) + (uint32_t)(h * 64 + lane), sm);
+        st_stream(reinterpret_cast<uint32_t*>(a.out + a.off_code + (cbase >> 1)) + (uint32_t)(h * 64 + lane), code);
+      } else {
+        if (g0 < a256(a.sm_bytes)) st_stream(reinterpret_cast<u32x2*>(a.out + a.off_sm + g0), sm);
+        if ((g0 >> 1) < a256(a.code_bytes)) st_stream(reinterpret_cast<uint32_t*>(a.out + a.off_code + (g0 >> 1)), code);
+      }
     }
   }
-#ifdef EXP_NO_SCAN
-  return (F[0] | F[1]) == 0x12345678u;
-#endif
   // escapes per lane; both halves scanned at once (16 bits each: a half has at most 512)
   const uint32_t packed = __popc(F[0]) | (__popc(F[1]) << 16);
   const uint32_t incl = wave_incl_scan(packed);
@@ -284,7 +289,7 @@ __device__ inline uint32_t process_chunk_bf16(const Planes& a, const uint16_t* l
 // ---- FP8 E5M2 (appendix "SplitZip on FP8"): byte = s eeeee mm, e = (x >> 2) & 31, a = s m1 m0 ----
 // One chunk by one wave; lane l owns the 16 consecutive elements [16 l, 16 l + 16): one 16-byte
 // load, 8 bytes of codes, 6 bytes of the 3-bit plane (lanes 2p and 2p+1 share 12 bytes: the even
-// lane stores 8 of them, the odd lane 4).  The encode table is indexed by the whole byte.
+// lane stores 8 of them, the odd lane 4).
 
 // a of the four bytes of w, packed LSB first into 12 bits
 __device__ inline uint32_t pack3_e5m2(uint32_t w) {
@@ -304,7 +309,10 @@ __device__ inline void load_chunk_e5m2(const Planes& a, uint64_t cbase, int lane
   const uint64_t g0 = cbase + lane * 16;
   uint32_t nvalid = 16;
   if (!FULL) nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 16 ? a.n - g0 : 16);
-  if (FULL || nvalid == 16) {
+  if (FULL) {
+    const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(a.in + cbase) + (uint32_t)lane);
+    w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+  } else if (nvalid == 16) {
     const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(a.in + g0));
     w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
   } else {
@@ -329,10 +337,10 @@ __device__ inline uint32_t process_chunk_e5m2(const Planes& a, const uint16_t* l
 #pragma unroll
   for (int d = 0; d < 4; ++d) {
     r[d] = pack3_e5m2(w[d]);
-    const uint32_t b0 = w[d] & 0xffu, b1 = (w[d] >> 8) & 0xffu, b2 = (w[d] >> 16) & 0xffu, b3 = w[d] >> 24;
+    const uint32_t e0 = (w[d] >> 2) & 31u, e1 = (w[d] >> 10) & 31u, e2 = (w[d] >> 18) & 31u, e3 = (w[d] >> 26) & 31u;
     // low byte: code pair; high byte: flag pair in the same nibble layout
-    u[2 * d] = (uint32_t)lut[b0] + ((uint32_t)lut[b1] << 4);
-    u[2 * d + 1] = (uint32_t)lut[b2] + ((uint32_t)lut[b3] << 4);
+    u[2 * d] = (uint32_t)lut[e0] + ((uint32_t)lut[e1] << 4);
+    u[2 * d + 1] = (uint32_t)lut[e2] + ((uint32_t)lut[e3] << 4);
   }
   // the lane's 48 plane bits: lo holds bits 0..31, hi bits 32..47
   uint32_t lo = r[0] | (r[1] << 12) | (r[2] << 24), hi = (r[2] >> 8) | (r[3] << 4);
@@ -358,7 +366,7 @@ __device__ inline uint32_t process_chunk_e5m2(const Planes& a, const uint16_t* l
     // plane bytes of this lane pair: [12 p, 12 p + 12) of the chunk's 384
     const uint32_t lo_up = __builtin_amdgcn_update_dpp(0u, lo, 0xF5, 0xf, 0xf, false);   // quad_perm [1,1,3,3]: the odd neighbour's lo
     const uint64_t sm_off = (cbase / 8) * 3 + (uint32_t)(lane >> 1) * 12;
-    uint8_t* sm_dst = a.out + a.off_sm + sm_off;
+    uint8_t* sm_dst = a.out + a.off_sm + (cbase / 8) * 3 + (uint32_t)(lane >> 1) * 12;   // uniform pointer + lane offset
     uint32_t d0, d1;
     if (lane & 1) {
       d0 = (lo >> 16) | (hi << 16);
@@ -370,7 +378,7 @@ __device__ inline uint32_t process_chunk_e5m2(const Planes& a, const uint16_t* l
     if (FULL) {
       if (lane & 1) st_stream(reinterpret_cast<uint32_t*>(sm_dst + 8), d0);
       else st_stream(reinterpret_cast<u32x2*>(sm_dst), u32x2{d0, d1});
-      st_stream(reinterpret_cast<u32x2*>(a.out + a.off_code + (g0 >> 1)), u32x2{code[0], code[1]});
+      st_stream(reinterpret_cast<u32x2*>(a.out + a.off_code + (cbase >> 1)) + (uint32_t)lane, u32x2{code[0], code[1]});
     } else {
       // dword by dword up to the padded end of each plane; the pad can reach 128 bytes past the
       // chunk's own 384 plane bytes
@@ -640,9 +648,6 @@ __global__ __launch_bounds__(T) void compress_kernel(const CompressArgs a) {
   const uint32_t b = blockIdx.x;
   uint32_t* park = reinterpret_cast<uint32_t*>(&s_park[tid]);
   const RangeLds L{stage_pk[wave], stage_val[wave], s_off, s_wstart};
-#ifdef EXP_TIMING
-  const uint64_t ts0 = wall_clock64();
-#endif
 
   if (tid < 256) lut[tid] = a.lut[tid];
   const uint32_t epoch = ld_agent(&a.ws_hdr[0]);
@@ -657,9 +662,6 @@ __global__ __launch_bounds__(T) void compress_kernel(const CompressArgs a) {
   const uint32_t wave_count = dense_pass<NW, F>(a.p, lut, park, L, r0, nb, wave, lane, no_hook);
   if (lane == 0) s_red[wave] = wave_count;
   __syncthreads();
-#ifdef EXP_TIMING
-  const uint64_t ts1 = wall_clock64();
-#endif
 
   if (wave == 0) {
     const uint32_t agg = wave_last(wave_incl_scan(lane < NW ? s_red[lane] : 0u));
@@ -688,9 +690,6 @@ __global__ __launch_bounds__(T) void compress_kernel(const CompressArgs a) {
   __syncthreads();
   const uint32_t prefix = s_misc[0], M = s_misc[1];
   const bool timed_out = s_misc[2] != 0;
-#ifdef EXP_TIMING
-  const uint64_t ts2 = wall_clock64();
-#endif
 
   if (!timed_out) {
     // values go behind the positions when M is final, else into the workspace
@@ -703,13 +702,6 @@ __global__ __launch_bounds__(T) void compress_kernel(const CompressArgs a) {
   } else if (tid == 0) {
     __hip_atomic_fetch_or(&a.ws_hdr[2], (uint32_t)SPLITZIP_STATUS_INTERNAL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
-#ifdef EXP_TIMING
-  __syncthreads();
-  if (tid == 0) {
-    uint64_t* t = reinterpret_cast<uint64_t*>(a.val_stage) + 4 * b;
-    t[0] = ts0; t[1] = ts1; t[2] = ts2; t[3] = wall_clock64();
-  }
-#endif
 }
 
 // ---- several tensors in one launch ----
@@ -1444,11 +1436,7 @@ int splitzip_compress(const void* d_in, uint64_t n_elems, int dtype, const split
   a.val_stage = ws + kWsHeaderBytes + kWsTableBytes;
   a.sizes = d_sizes;
   memcpy(a.dec, cb->dec, 16);
-  // indexed by the exponent (BF16) or by the whole byte (E5M2: e = (x >> 2) & 31)
-  for (unsigned v = 0; v < 256; ++v) {
-    const unsigned e = dtype == SPLITZIP_BF16 ? v : (v >> 2) & 31u;
-    a.lut[v] = cb->member[e] ? cb->enc[e] : 0x100u;
-  }
+  for (unsigned v = 0; v < 256; ++v) a.lut[v] = cb->member[v] ? cb->enc[v] : 0x100u;   // indexed by the exponent
   static const int spin_env = env_int("SPLITZIP_SPIN_TICKS", 0);
   a.spin_ticks = spin_env ? (uint64_t)spin_env : kSpinTicks;
 
@@ -1581,10 +1569,7 @@ int splitzip_compress_batch(const splitzip_item* items, uint32_t n_items, int dt
       if (id == n_luts) {
         if (n_luts == kBatchLuts) break;
         memcpy(a.dec[id], it.cb->dec, 16);
-        for (unsigned v = 0; v < 256; ++v) {
-          const unsigned e = dtype == SPLITZIP_BF16 ? v : (v >> 2) & 31u;
-          a.lut[id][v] = it.cb->member[e] ? it.cb->enc[e] : 0x100u;
-        }
+        for (unsigned v = 0; v < 256; ++v) a.lut[id][v] = it.cb->member[v] ? it.cb->enc[v] : 0x100u;
         ++n_luts;
       }
       a.item[k].in = static_cast<const uint8_t*>(it.d_in);
