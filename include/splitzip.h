@@ -93,6 +93,19 @@ typedef struct {
 int splitzip_calibrate(const void* h_sample, uint64_t n_elems, int dtype, splitzip_codebook* out,
                        uint64_t* hist_out);
 
+/* The same from a histogram of exponent counts (host memory, 256 entries; for
+ * E5M2 the first 32 count). */
+int splitzip_codebook_from_hist(const uint64_t hist[256], int dtype, splitzip_codebook* out);
+
+/* Section 3.3 with the counting on the device: adds the exponent counts of a
+ * DEVICE sample of n_elems words to d_hist (256 device words, 8-byte aligned,
+ * zeroed by the caller before the first sample; several calls accumulate a
+ * calibration set of several tensors).  Enqueued on `stream`.  The caller
+ * copies the 2 KB to the host and calls splitzip_codebook_from_hist.  This is
+ * the paper's "dynamic" codebook (ablation "pre-calibration vs. dynamic
+ * codebook") when done per call. */
+int splitzip_histogram(const void* d_sample, uint64_t n_elems, int dtype, uint64_t* d_hist, void* stream);
+
 /* Tables for a given list of 16 distinct exponents (code k = dec[k]); used to
  * restore a saved codebook.  INVALID_ARG on duplicates / out-of-range values. */
 int splitzip_codebook_from_dec(const uint8_t dec[16], int dtype, splitzip_codebook* out);

@@ -18,12 +18,14 @@ from .binding import (  # noqa: F401
     Workspace,
     calibrate,
     codebook_from_dec,
+    codebook_from_hist,
     compress,
     compress_batch,
     compress_bound,
     decompress,
     decompress_batch,
     fixed_bytes,
+    histogram,
     lib,
     lib_path,
     new_sizes,

@@ -81,6 +81,10 @@ def lib():
         L.splitzip_compress.argtypes = [vp, u64, i, cbp, vp, sz, vp, sz, vp, vp]
         L.splitzip_decompress.restype = i
         L.splitzip_decompress.argtypes = [vp, sz, u64, i, cbp, vp, vp, vp]
+        L.splitzip_codebook_from_hist.restype = i
+        L.splitzip_codebook_from_hist.argtypes = [C.POINTER(C.c_uint64), i, cbp]
+        L.splitzip_histogram.restype = i
+        L.splitzip_histogram.argtypes = [vp, u64, i, vp, vp]
         L.splitzip_compress_batch.restype = i
         L.splitzip_compress_batch.argtypes = [C.POINTER(_CItem), C.c_uint32, i, vp, sz, vp, vp]
         L.splitzip_decompress_batch.restype = i
@@ -141,6 +145,26 @@ def codebook_from_dec(dec, dtype: int) -> Codebook:
     cb = _CCodebook()
     _check(lib().splitzip_codebook_from_dec(arr, dtype, C.byref(cb)), "splitzip_codebook_from_dec")
     return Codebook(cb)
+
+
+def codebook_from_hist(hist, dtype: int) -> Codebook:
+    """splitzip_codebook_from_hist on a host list / tensor of 256 exponent counts."""
+    vals = [int(v) for v in (hist.tolist() if hasattr(hist, "tolist") else hist)]
+    arr = (C.c_uint64 * 256)(*vals)
+    cb = _CCodebook()
+    _check(lib().splitzip_codebook_from_hist(arr, dtype, C.byref(cb)), "splitzip_codebook_from_hist")
+    return Codebook(cb)
+
+
+def histogram(x: torch.Tensor, dtype: int, hist: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """splitzip_histogram: adds the exponent counts of the device words x to hist (256 x int64 on the
+    device; a zeroed one is made if none is given) and returns it."""
+    if x.element_size() != _elem_size(dtype) or not x.is_contiguous():
+        raise ValueError("x must be a contiguous tensor of raw words of the dtype")
+    if hist is None:
+        hist = torch.zeros(256, dtype=torch.int64, device=x.device)
+    _check(lib().splitzip_histogram(x.data_ptr(), x.numel(), dtype, hist.data_ptr(), _stream_ptr(stream)), "splitzip_histogram")
+    return hist
 
 
 def fixed_bytes(n: int, dtype: int) -> int:

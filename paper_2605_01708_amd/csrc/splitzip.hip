@@ -1210,6 +1210,49 @@ __global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const Decomp
 // small kernels
 // ---------------------------------------------------------------------------
 
+// Calibration histogram (section 3.3) of a device sample: exponent counts, added to hist[256].
+// Every workgroup counts into eight copies of the bins in LDS -- lane l uses copy l mod 8, which
+// keeps the lanes that meet on one of the few common exponents apart -- and adds its non-zero
+// totals to the global bins at the end.
+template <bool BF16>
+__global__ __launch_bounds__(1024) void histogram_kernel(const uint8_t* in, uint64_t n, uint64_t* hist) {
+  __shared__ uint32_t bins[8][256];
+  const int tid = threadIdx.x;
+  for (int i = tid; i < 8 * 256; i += 1024) (&bins[0][0])[i] = 0;
+  __syncthreads();
+  uint32_t* mine = bins[tid & 7];
+  const uint64_t bytes = n * (BF16 ? 2 : 1), nvec = bytes / 16;
+  const u32x4* v = reinterpret_cast<const u32x4*>(in);
+  for (uint64_t i = blockIdx.x * 1024ull + tid; i < nvec; i += (uint64_t)gridDim.x * 1024) {
+    const u32x4 q = ld_stream(v + i);
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      if (BF16) {
+        atomicAdd(&mine[(w[d] >> 7) & 0xffu], 1u);
+        atomicAdd(&mine[(w[d] >> 23) & 0xffu], 1u);
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) atomicAdd(&mine[(w[d] >> (8 * j + 2)) & 31u], 1u);
+      }
+    }
+  }
+  // the words behind the last whole vector, by workgroup 0
+  if (blockIdx.x == 0) {
+    for (uint64_t i = nvec * 16 + (uint64_t)tid * (BF16 ? 2 : 1); i < bytes; i += 1024 * (BF16 ? 2 : 1)) {
+      const uint32_t e = BF16 ? ((uint32_t)(in[i] | (in[i + 1] << 8)) >> 7) & 0xffu : ((uint32_t)in[i] >> 2) & 31u;
+      atomicAdd(&mine[e], 1u);
+    }
+  }
+  __syncthreads();
+  if (tid < 256) {
+    uint64_t c = 0;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) c += bins[r][tid];
+    if (c) atomicAdd(reinterpret_cast<unsigned long long*>(&hist[tid]), (unsigned long long)c);
+  }
+}
+
 __global__ void workspace_init_kernel(uint32_t* p, uint32_t nwords) {
   for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < nwords; i += gridDim.x * blockDim.x) p[i] = i == 0 ? 1u : 0u;
 }
@@ -1375,6 +1418,12 @@ int splitzip_calibrate(const void* h_sample, uint64_t n_elems, int dtype, splitz
     const uint8_t* p = static_cast<const uint8_t*>(h_sample);
     for (uint64_t i = 0; i < n_elems; ++i) hist[(p[i] >> 2) & 0x1f]++;
   }
+  if (hist_out) memcpy(hist_out, hist, sizeof hist);
+  return splitzip_codebook_from_hist(hist, dtype, out);
+}
+
+int splitzip_codebook_from_hist(const uint64_t hist[256], int dtype, splitzip_codebook* out) {
+  if (!hist || !out || !dtype_ok(dtype)) return SPLITZIP_ERR_INVALID_ARG;
   // rank exponents by (count descending, value ascending): insertion into a sorted top-16 list
   const unsigned nv = exp_values(dtype);
   uint8_t top[16];
@@ -1388,8 +1437,26 @@ int splitzip_calibrate(const void* h_sample, uint64_t n_elems, int dtype, splitz
     top[at] = (uint8_t)v;
     if (filled < 16) ++filled;
   }
-  if (hist_out) memcpy(hist_out, hist, sizeof hist);
   return splitzip_codebook_from_dec(top, dtype, out);
+}
+
+int splitzip_histogram(const void* d_sample, uint64_t n_elems, int dtype, uint64_t* d_hist, void* stream) {
+  if (!dtype_ok(dtype) || !d_hist || (n_elems && !d_sample) || !aligned16(d_sample) ||
+      (reinterpret_cast<uintptr_t>(d_hist) & 7u))
+    return SPLITZIP_ERR_INVALID_ARG;
+  if (n_elems >> 32) return SPLITZIP_ERR_UNSUPPORTED;
+  if (n_elems == 0) return SPLITZIP_OK;
+  const uint64_t nvec = (n_elems * (dtype == SPLITZIP_BF16 ? 2 : 1) + 15) / 16;
+  uint64_t grid = (nvec + 4 * 1024 - 1) / (4 * 1024);   // at least four vectors per thread
+  const uint64_t most = (uint64_t)cu_count() * 2;
+  if (grid > most) grid = most;
+  if (grid < 1) grid = 1;
+  const hipStream_t st = static_cast<hipStream_t>(stream);
+  if (dtype == SPLITZIP_BF16)
+    hipLaunchKernelGGL(histogram_kernel<true>, dim3((unsigned)grid), dim3(1024), 0, st, static_cast<const uint8_t*>(d_sample), n_elems, d_hist);
+  else
+    hipLaunchKernelGGL(histogram_kernel<false>, dim3((unsigned)grid), dim3(1024), 0, st, static_cast<const uint8_t*>(d_sample), n_elems, d_hist);
+  return hipGetLastError() == hipSuccess ? SPLITZIP_OK : SPLITZIP_ERR_HIP;
 }
 
 size_t splitzip_total_bytes(uint64_t n_elems, uint64_t n_escapes, int dtype) {

@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
             "splitzip_fixed_bytes", "splitzip_total_bytes", "splitzip_compress_bound",
             "splitzip_workspace_bytes", "splitzip_codebook_from_dec", "splitzip_strerror",
             "splitzip_version", "splitzip_traffic_probe", "splitzip_compress_batch",
-            "splitzip_decompress_batch"} <= set(names)
+            "splitzip_decompress_batch", "splitzip_histogram", "splitzip_codebook_from_hist"} <= set(names)
     L = C.CDLL(sz.lib_path())
     for n in names:
         assert hasattr(L, n), n
@@ -47,6 +47,21 @@ def test_host_calibrate_matches_oracle(dtype, gen):
         assert cb.member == ref.member.tolist()
         assert hist == ref.hist.tolist()
         assert cb.dtype == dtype
+
+
+def test_codebook_from_hist_ranks_like_calibrate():
+    """the tables built from a histogram are those of calibrate on the sample that has it (same reading of ties)"""
+    for dtype, gen in ((sz.BF16, kv_synth.kv_bf16), (sz.FP8_E5M2, kv_synth.kv_e5m2)):
+        s = gen(9, 4)
+        cb, hist = sz.calibrate(s, dtype, return_hist=True)
+        cb2 = sz.codebook_from_hist(hist, dtype)
+        assert (cb2.dec, cb2.enc, cb2.member, cb2.dtype) == (cb.dec, cb.enc, cb.member, cb.dtype)
+    h = [0] * 256
+    h[130] = h[120] = h[3] = 50
+    h[125] = 70
+    assert sz.codebook_from_hist(h, sz.BF16).dec == [125, 3, 120, 130, 0, 1, 2, 4, 5, 6, 7, 8, 9, 10, 11, 12]
+    assert sz.lib().splitzip_codebook_from_hist(None, sz.BF16, None) == -1
+    assert sz.lib().splitzip_histogram(None, 16, sz.BF16, None, None) == -1
 
 
 def test_host_calibrate_ties_and_empty():

@@ -315,6 +315,33 @@ def test_batch_calls_match_the_oracle_item_by_item(dtype):
         assert (ys[k][x.size:].cpu().numpy() == (0x5A if es == 1 else 0x5A5A)).all()
 
 
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_device_histogram_matches_the_oracle_calibration(dtype):
+    """exponent counts of device samples, ragged sizes included, accumulated over several calls; the codebook
+    built from them is the oracle's"""
+    total = np.zeros(256, np.int64)
+    hist = None
+    parts = []
+    for k, n in enumerate((0, 1, 7, 16, 1000, 8191, 300 * 1024 + 13, 1024 * 1024)):
+        x = synth(dtype, (n + 1023) // 1024 + 1, 30 + k, layer=k % 4, kind="KV"[k % 2])[:n].copy()
+        if n > 100:
+            x[:: 97] = 0                                    # zeros and a few maximal exponents
+            x[5:: 1013] = 0x7F80 if dtype == sz.BF16 else 0x7C
+        parts.append(x)
+        ref = oracle.calibrate(x, DT[dtype])
+        one = sz.histogram(words_tensor(x) if n else torch.zeros(0, dtype=torch.int16 if dtype == sz.BF16 else torch.uint8, device="cuda"), dtype)
+        torch.cuda.synchronize()
+        assert one.cpu().tolist() == ref.hist.tolist(), f"n={n}"
+        if n:
+            hist = sz.histogram(words_tensor(x), dtype, hist)
+        total += ref.hist.astype(np.int64)
+    torch.cuda.synchronize()
+    assert hist.cpu().tolist() == total.tolist()
+    ref_all = oracle.calibrate(np.concatenate(parts), DT[dtype])
+    cb = sz.codebook_from_hist(hist.cpu(), dtype)
+    assert cb.dec == ref_all.dec.tolist() and cb.enc == ref_all.enc.tolist() and cb.member == ref_all.member.tolist()
+
+
 def run_env_case(case, **env):
     import os
     import subprocess
