@@ -1659,7 +1659,7 @@ int splitzip_compress_batch(const splitzip_item* items, uint32_t n_items, int dt
       if (c > chunks_max) chunks_max = c;
     }
     uint32_t G = W;
-    while (G > 8 && G % 2 == 0 && (uint64_t)(G / 2) * 64 >= chunks_max) G /= 2;
+    while (G > 8 && G % 2 == 0 && (uint64_t)(G / 2) * 64 >= chunks_max && W / (G / 2) <= k) G /= 2;   // never more groups than tensors
     while ((uint64_t)G * kMaxRange < chunks_max) G *= 2;   // never beyond W: chunks_max <= chunk_cap
     if (G > W) G = W;
     a.group_wgs = G;
