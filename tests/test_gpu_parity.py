@@ -342,6 +342,56 @@ def test_device_histogram_matches_the_oracle_calibration(dtype):
     assert cb.dec == ref_all.dec.tolist() and cb.enc == ref_all.enc.tolist() and cb.member == ref_all.member.tolist()
 
 
+def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
+    """compress + decompress (single and batch) captured once, replayed with new data between the replays and
+    the library's own eager calls in between: every replay must give the oracle's streams.  The exchange
+    words are tagged from a counter in the workspace, so a replay never mistakes an earlier launch's words
+    for its own."""
+    dtype = sz.BF16
+    cb_or = calibrated(dtype)
+    cb = gpu_codebook(cb_or)
+    n = 300 * 1024 + 77
+    datas = [synth(dtype, 301, 40 + r)[:n].copy() for r in range(3)]
+    for d in datas:
+        d[:: 1231] = 0
+    x = words_tensor(datas[0])
+    x2 = words_tensor(datas[0][: 70000].copy())
+    ws = sz.Workspace(n, dtype)
+    outs = [torch.zeros(sz.compress_bound(n, dtype), dtype=torch.uint8, device="cuda") for _ in range(3)]
+    y = torch.zeros_like(x)
+    rec1, rec2, dst = sz.new_sizes(), sz.new_sizes_array(2), sz.new_sizes()
+    batch = sz.CompressBatch([x, x2], [cb, cb], outs[1:])
+    ref0, m0 = oracle.compress(datas[0], cb_or)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        sz.compress(x, cb, outs[0], ws, rec1)              # warm-up outside the capture
+        torch.cuda.current_stream().synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            sz.compress(x, cb, outs[0], ws, rec1)
+            batch.launch(ws, rec2)
+            sz.decompress(outs[0], ref0.size + 4096, n, cb, y, dst)   # comp_bytes: a bound, the header holds the size
+    torch.cuda.synchronize()
+    for rep, d in enumerate(datas + datas[:1]):
+        x.copy_(words_tensor(d))
+        x2.copy_(words_tensor(d[: 70000].copy()))
+        y.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        ref, m = oracle.compress(d, cb_or)
+        ref2, mm2 = oracle.compress(d[: 70000].copy(), cb_or)
+        assert sz.read_sizes(rec1) == (ref.size, m, 0), f"replay {rep}"
+        assert np.array_equal(outs[0][: ref.size].cpu().numpy(), ref), f"replay {rep}: single call stream"
+        got = sz.read_sizes_array(rec2)
+        assert got == [(ref.size, m, 0), (ref2.size, mm2, 0)], f"replay {rep}: {got}"
+        assert np.array_equal(outs[1][: ref.size].cpu().numpy(), ref) and np.array_equal(outs[2][: ref2.size].cpu().numpy(), ref2)
+        assert sz.read_sizes(dst)[2] == 0 and torch.equal(y, x), f"replay {rep}: round trip"
+        # eager work of the library between the replays
+        sz.compress(x2, cb, outs[2], ws, rec1)
+        torch.cuda.synchronize()
+        assert sz.read_sizes(rec1) == (ref2.size, mm2, 0)
+
+
 def run_env_case(case, **env):
     import os
     import subprocess
