@@ -1,0 +1,78 @@
+// SplitZip for MI355X: calibration histogram, workspace initialisation and the plain streaming kernel used as a measurement aid.
+// Part of the single translation unit splitzip.hip (included inside its anonymous namespace).
+#ifndef SPLITZIP_AUX_KERNELS_HPP
+#define SPLITZIP_AUX_KERNELS_HPP
+
+// ---------------------------------------------------------------------------
+// small kernels
+// ---------------------------------------------------------------------------
+
+// Calibration histogram (section 3.3) of a device sample: exponent counts, added to hist[256].
+// Every workgroup counts into eight copies of the bins in LDS -- lane l uses copy l mod 8, which
+// keeps the lanes that meet on one of the few common exponents apart -- and adds its non-zero
+// totals to the global bins at the end.
+template <bool BF16>
+__global__ __launch_bounds__(1024) void histogram_kernel(const uint8_t* in, uint64_t n, uint64_t* hist) {
+  __shared__ uint32_t bins[8][256];
+  const int tid = threadIdx.x;
+  for (int i = tid; i < 8 * 256; i += 1024) (&bins[0][0])[i] = 0;
+  __syncthreads();
+  uint32_t* mine = bins[tid & 7];
+  const uint64_t bytes = n * (BF16 ? 2 : 1), nvec = bytes / 16;
+  const u32x4* v = reinterpret_cast<const u32x4*>(in);
+  for (uint64_t i = blockIdx.x * 1024ull + tid; i < nvec; i += (uint64_t)gridDim.x * 1024) {
+    const u32x4 q = ld_stream(v + i);
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      if (BF16) {
+        atomicAdd(&mine[(w[d] >> 7) & 0xffu], 1u);
+        atomicAdd(&mine[(w[d] >> 23) & 0xffu], 1u);
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) atomicAdd(&mine[(w[d] >> (8 * j + 2)) & 31u], 1u);
+      }
+    }
+  }
+  // the words behind the last whole vector, by workgroup 0
+  if (blockIdx.x == 0) {
+    for (uint64_t i = nvec * 16 + (uint64_t)tid * (BF16 ? 2 : 1); i < bytes; i += 1024 * (BF16 ? 2 : 1)) {
+      const uint32_t e = BF16 ? ((uint32_t)(in[i] | (in[i + 1] << 8)) >> 7) & 0xffu : ((uint32_t)in[i] >> 2) & 31u;
+      atomicAdd(&mine[e], 1u);
+    }
+  }
+  __syncthreads();
+  if (tid < 256) {
+    uint64_t c = 0;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) c += bins[r][tid];
+    if (c) atomicAdd(reinterpret_cast<unsigned long long*>(&hist[tid]), (unsigned long long)c);
+  }
+}
+
+__global__ void workspace_init_kernel(uint32_t* p, uint32_t nwords) {
+  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < nwords; i += gridDim.x * blockDim.x) p[i] = i == 0 ? 1u : 0u;
+}
+
+// Per step a workgroup reads four coalesced 4 KB runs and writes three: the codec's 4:3 traffic
+// without its arithmetic.
+__global__ __launch_bounds__(kThreads) void traffic_probe_kernel(const u32x4* src, uint64_t nread,
+                                                                  u32x4* dst, uint64_t nwrite) {
+  const uint64_t steps = (nread + 4 * kThreads - 1) / (4 * kThreads);
+  for (uint64_t s = blockIdx.x; s < steps; s += gridDim.x) {
+    u32x4 v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint64_t idx = (4 * s + i) * kThreads + threadIdx.x;
+      v[i] = idx < nread ? ld_stream(src + idx) : u32x4{0u, 0u, 0u, 0u};
+    }
+    v[0].x ^= v[3].x; v[1].y ^= v[3].y; v[2].z ^= v[3].z; v[0].w ^= v[3].w;
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+      const uint64_t idx = (3 * s + i) * kThreads + threadIdx.x;
+      if (idx < nwrite) st_stream(dst + idx, v[i]);
+    }
+  }
+}
+
+#endif  // SPLITZIP_AUX_KERNELS_HPP

@@ -1,0 +1,77 @@
+// SplitZip for MI355X: stream layout and small device helpers shared by all kernels.
+// Part of the single translation unit splitzip.hip (included inside its anonymous namespace).
+#ifndef SPLITZIP_COMMON_HPP
+#define SPLITZIP_COMMON_HPP
+
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr uint32_t kChunk = 1024;
+constexpr uint32_t kHalf = 512;
+constexpr uint32_t kHeaderBytes = 64;
+constexpr int kThreads = 256;                             // decompress / helper kernels
+constexpr int kWaves = kThreads / 64;
+constexpr uint32_t kMaxCpw = 16;                          // decompress: chunks per wave per tile, at most
+constexpr uint32_t kMaxRange = 256;                       // compress: chunks per workgroup per launch, at most
+constexpr uint32_t kMaxWorkgroups = 4096;                 // compress: words of exchange state in the workspace
+constexpr uint32_t kWsTableBytes = 8 * kMaxWorkgroups;
+constexpr uint32_t kStageCap = 512;                       // escapes a wave can stage in LDS
+constexpr uint32_t kWsHeaderBytes = 64;                   // epoch, running escape count, error flags
+constexpr uint32_t kSegFirst = 1u, kSegLast = 2u;         // CompressArgs.flags
+constexpr uint64_t kSpinTicks = 200000000ull;             // 2 s of the 100 MHz wall clock
+
+__host__ __device__ inline uint64_t a256(uint64_t x) { return (x + 255u) & ~(uint64_t)255u; }
+
+struct Layout {
+  uint64_t n, n_chunks, sm_bytes, code_bytes;
+  uint64_t off_tab, off_sm, off_code, off_pos;  // the value section starts at off_pos + a256(2M)
+};
+
+__host__ __device__ inline Layout make_layout(uint64_t n, int dtype) {
+  Layout L;
+  L.n = n;
+  L.n_chunks = (n + kChunk - 1) / kChunk;
+  L.sm_bytes = dtype == SPLITZIP_BF16 ? n : (3 * n + 7) / 8;
+  L.code_bytes = (n + 1) / 2;
+  L.off_tab = kHeaderBytes;
+  L.off_sm = a256(L.off_tab + 4 * (L.n_chunks + 1));
+  L.off_code = L.off_sm + a256(L.sm_bytes);
+  L.off_pos = L.off_code + a256(L.code_bytes);
+  return L;
+}
+
+// ---------------------------------------------------------------------------
+// device helpers
+// ---------------------------------------------------------------------------
+
+template <typename T>
+__device__ inline T ld_stream(const T* p) { return __builtin_nontemporal_load(p); }
+template <typename T>
+__device__ inline void st_stream(T* p, T v) { __builtin_nontemporal_store(v, p); }
+
+// v_perm_b32: result byte i = byte sel[i] of the 8-byte pool {hi:4..7, lo:0..3}; 0x0c gives 0x00.
+__device__ inline uint32_t byte_perm(uint32_t hi, uint32_t lo, uint32_t sel) {
+  return __builtin_amdgcn_perm(hi, lo, sel);
+}
+
+// inclusive prefix sum over the 64 lanes with DPP moves: Kogge-Stone inside rows of 16 lanes,
+// then the row totals are carried over with the two row-broadcast steps
+__device__ inline uint32_t wave_incl_scan(uint32_t v) {
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x111, 0xf, 0xf, false);  // row_shr:1
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x112, 0xf, 0xf, false);  // row_shr:2
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x114, 0xf, 0xf, false);  // row_shr:4
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x118, 0xf, 0xf, false);  // row_shr:8
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1, 3
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2, 3
+  return v;
+}
+
+__device__ inline uint32_t wave_last(uint32_t v) { return __builtin_amdgcn_readlane(v, 63); }
+
+// agent-scope relaxed accesses: performed at the device-wide coherence point, no fences
+template <typename T>
+__device__ inline void st_agent(T* p, T v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+template <typename T>
+__device__ inline T ld_agent(const T* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+#endif  // SPLITZIP_COMMON_HPP

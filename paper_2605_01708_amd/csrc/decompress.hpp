@@ -1,0 +1,314 @@
+// SplitZip for MI355X: the decompress kernels (dense decode of both formats, scatter correction in registers, single-tensor and batch kernels).
+// Part of the single translation unit splitzip.hip (included inside its anonymous namespace).
+#ifndef SPLITZIP_DECOMPRESS_HPP
+#define SPLITZIP_DECOMPRESS_HPP
+
+// ---------------------------------------------------------------------------
+// decompress
+// ---------------------------------------------------------------------------
+
+struct DecompressArgs {
+  const uint8_t* comp;
+  uint8_t* out;
+  uint64_t n, comp_bytes;
+  splitzip_sizes* sizes;   // nullable
+  uint64_t off_tab, off_sm, off_code, off_pos, sm_bytes, code_bytes;
+  uint32_t n_chunks, n_tiles, cpw, dtype;
+  uint8_t dec[16];
+};
+
+__device__ inline void flag_bad(const DecompressArgs& a) {
+  if (a.sizes) atomicOr(&a.sizes->status, SPLITZIP_STATUS_BAD_STREAM);
+}
+
+// header checks: one thread of workgroup 0
+__device__ void decompress_check_header(const DecompressArgs& a, const uint8_t* dec, uint32_t M) {
+  const uint32_t* h = reinterpret_cast<const uint32_t*>(a.comp);
+  const uint64_t n = h[4] | ((uint64_t)h[5] << 32), m = h[6] | ((uint64_t)h[7] << 32);
+  const uint64_t total = h[8] | ((uint64_t)h[9] << 32);
+  bool ok = h[0] == 0x31505a53u && h[1] == (1u | (a.dtype << 16) | (4u << 24)) && h[2] == kChunk &&
+            h[3] == 0 && n == a.n && m == M && total == a.off_pos + a256(2 * m) + m &&
+            total <= a.comp_bytes && h[14] == 0 && h[15] == 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    ok = ok && h[10 + i] == (dec[4 * i] | (dec[4 * i + 1] << 8) | (dec[4 * i + 2] << 16) |
+                             ((uint32_t)dec[4 * i + 3] << 24));
+  if (!ok) flag_bad(a);
+  if (a.sizes) {
+    a.sizes->total_bytes = total;
+    a.sizes->n_escapes = m;
+  }
+}
+
+// BF16 dense decode of one chunk by one wave into registers: two half-chunks, 8 elements per lane
+// each; o[4 h + d] holds elements 2 d and 2 d + 1 of the lane's group in half h
+template <bool FULL>
+__device__ inline void decode_chunk_bf16(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane, uint32_t (&o)[8]) {
+  u32x2 sm[2];
+  uint32_t cd[2];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const uint64_t g0 = cbase + h * kHalf + lane * 8;
+    sm[h] = u32x2{0u, 0u};
+    cd[h] = 0;
+    if (FULL || g0 < a256(a.sm_bytes)) sm[h] = ld_stream(reinterpret_cast<const u32x2*>(a.comp + a.off_sm + g0));
+    if (FULL || (g0 >> 1) < a256(a.code_bytes))
+      cd[h] = ld_stream(reinterpret_cast<const uint32_t*>(a.comp + a.off_code + (g0 >> 1)));
+  }
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const uint32_t smw[2] = {sm[h].x, sm[h].y};
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      // code byte b -> both exponents already in place (bits 7..14 and 23..30)
+      const uint32_t cb = (cd[h] >> (8 * b)) & 0xffu;
+      // [a0, a0, a1, a1], then keep mantissa in the low and sign in the high byte of each half-word (eq. (2))
+      const uint32_t p = byte_perm(0u, smw[b >> 1], (b & 1) ? 0x03030202u : 0x01010000u);
+      o[4 * h + b] = (p & 0x807f807fu) | tbl[cb];
+    }
+  }
+}
+
+template <bool FULL>
+__device__ inline void store_chunk_bf16(const DecompressArgs& a, uint64_t cbase, int lane, const uint32_t (&o)[8]) {
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const uint64_t g0 = cbase + h * kHalf + lane * 8;
+    uint32_t nvalid = 8;
+    if (!FULL) nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 8 ? a.n - g0 : 8);
+    if (FULL || nvalid == 8) {
+      st_stream(reinterpret_cast<u32x4*>(a.out + 2 * g0), u32x4{o[4 * h], o[4 * h + 1], o[4 * h + 2], o[4 * h + 3]});
+    } else {
+      uint16_t* q = reinterpret_cast<uint16_t*>(a.out) + g0;
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        if ((uint32_t)(2 * d) < nvalid) q[2 * d] = (uint16_t)o[4 * h + d];
+        if ((uint32_t)(2 * d + 1) < nvalid) q[2 * d + 1] = (uint16_t)(o[4 * h + d] >> 16);
+      }
+    }
+  }
+}
+
+// E5M2 dense decode of one chunk by one wave into registers: 16 elements per lane, o[d] holds
+// elements 4 d .. 4 d + 3.  Lanes 2p and 2p+1 share 12 plane bytes: the even lane loads the first
+// 8, the odd lane the last 4.
+template <bool FULL>
+__device__ inline void decode_chunk_e5m2(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane, uint32_t (&o)[4]) {
+  const uint64_t g0 = cbase + lane * 16;
+  const uint64_t sm_off = (cbase / 8) * 3 + (uint32_t)(lane >> 1) * 12;
+  const uint8_t* sm_src = a.comp + a.off_sm + sm_off;
+  const uint64_t sm_end = a256(a.sm_bytes);
+  uint32_t d0 = 0, d1 = 0;
+  u32x2 cd = u32x2{0u, 0u};
+  if (lane & 1) {
+    if (FULL || sm_off + 8 < sm_end) d0 = ld_stream(reinterpret_cast<const uint32_t*>(sm_src + 8));
+  } else if (FULL || sm_off + 4 < sm_end) {
+    const u32x2 v = ld_stream(reinterpret_cast<const u32x2*>(sm_src));   // 8 bytes below a multiple of 256: both in the stream
+    d0 = v.x;
+    d1 = v.y;
+  } else if (sm_off < sm_end) {
+    d0 = ld_stream(reinterpret_cast<const uint32_t*>(sm_src));
+  }
+  if (FULL || (g0 >> 1) < a256(a.code_bytes)) cd = ld_stream(reinterpret_cast<const u32x2*>(a.comp + a.off_code + (g0 >> 1)));
+  const uint32_t d1_dn = __builtin_amdgcn_update_dpp(0u, d1, 0xA0, 0xf, 0xf, false);   // quad_perm [0,0,2,2]: the even neighbour's second dword
+  // the lane's 48 plane bits
+  const uint32_t lo = (lane & 1) ? (d1_dn >> 16) | (d0 << 16) : d0;
+  const uint32_t hi = (lane & 1) ? d0 >> 16 : d1 & 0xffffu;
+  const uint32_t r[4] = {lo & 0xfffu, (lo >> 12) & 0xfffu, (lo >> 24) | ((hi & 0xfu) << 8), (hi >> 4) & 0xfffu};
+  const uint32_t cdw[2] = {cd.x, cd.y};
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    // two code bytes -> four exponents already in place (bits 2..6 of each byte)
+    const uint32_t c01 = (cdw[d >> 1] >> (16 * (d & 1))) & 0xffu, c23 = (cdw[d >> 1] >> (16 * (d & 1) + 8)) & 0xffu;
+    o[d] = unpack3_e5m2(r[d]) | tbl[c01] | (tbl[c23] << 16);
+  }
+}
+
+template <bool FULL>
+__device__ inline void store_chunk_e5m2(const DecompressArgs& a, uint64_t cbase, int lane, const uint32_t (&o)[4]) {
+  const uint64_t g0 = cbase + lane * 16;
+  uint32_t nvalid = 16;
+  if (!FULL) nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 16 ? a.n - g0 : 16);
+  if (FULL || nvalid == 16) {
+    st_stream(reinterpret_cast<u32x4*>(a.out + g0), u32x4{o[0], o[1], o[2], o[3]});
+  } else {
+    uint8_t* q = a.out + g0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+      if ((uint32_t)j < nvalid) q[j] = (uint8_t)(o[j >> 2] >> (8 * (j & 3)));
+  }
+}
+
+// in-register scatter correction: dword r of the owning lane gets (o & ~mask) | bits; r is
+// wave-uniform, so the choice of the register is a scalar branch
+template <int R>
+__device__ inline void patch_regs(uint32_t (&o)[R], uint32_t r, bool mine, uint32_t mask, uint32_t bits) {
+#pragma unroll
+  for (int q = 0; q < R; ++q)
+    if (r == (uint32_t)q && mine) o[q] = (o[q] & ~mask) | bits;
+}
+
+// the two formats as seen by the decompress kernel
+struct DBf16 {
+  struct Out { uint32_t o[8]; };
+  // table entry for a code byte: both exponents in place for one dword of output
+  __device__ static inline uint32_t table(int cb, const uint8_t* dec) { return ((uint32_t)dec[cb & 15] << 7) | ((uint32_t)dec[cb >> 4] << 23); }
+  __device__ static inline bool full(const DecompressArgs& a, uint64_t cbase) { return cbase + kChunk <= a.n; }
+  template <bool FULL>
+  __device__ static inline void decode(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane, Out& r) { decode_chunk_bf16<FULL>(a, tbl, cbase, lane, r.o); }
+  template <bool FULL>
+  __device__ static inline void store(const DecompressArgs& a, uint64_t cbase, int lane, const Out& r) { store_chunk_bf16<FULL>(a, cbase, lane, r.o); }
+  // the scatter correction of the element at chunk position pos (wave-uniform), in the registers of the lane that holds it
+  __device__ static inline bool patch_reg(Out& r, int lane, uint32_t pos, uint32_t val) {
+    const uint32_t q = pos & 511u, e = q & 7u, sh = 16u * (e & 1u);
+    patch_regs<8>(r.o, 4u * (pos >> 9) + (e >> 1), (uint32_t)lane == (q >> 3), 0x7f80u << sh, val << (7u + sh));
+    return true;
+  }
+  // the same on the tensor in memory: exponent field := val, sign and mantissa from the stream
+  __device__ static inline bool patch(const DecompressArgs& a, uint64_t i, uint32_t val) {
+    const uint32_t sa = a.comp[a.off_sm + i];
+    reinterpret_cast<uint16_t*>(a.out)[i] = (uint16_t)(((sa & 0x80u) << 8) | (val << 7) | (sa & 0x7fu));
+    return true;
+  }
+};
+struct DE5m2 {
+  struct Out { uint32_t o[4]; };
+  __device__ static inline uint32_t table(int cb, const uint8_t* dec) { return ((uint32_t)dec[cb & 15] << 2) | ((uint32_t)dec[cb >> 4] << 10); }
+  __device__ static inline bool full(const DecompressArgs& a, uint64_t cbase) { return cbase + kChunk < a.n; }
+  template <bool FULL>
+  __device__ static inline void decode(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane, Out& r) { decode_chunk_e5m2<FULL>(a, tbl, cbase, lane, r.o); }
+  template <bool FULL>
+  __device__ static inline void store(const DecompressArgs& a, uint64_t cbase, int lane, const Out& r) { store_chunk_e5m2<FULL>(a, cbase, lane, r.o); }
+  __device__ static inline bool patch_reg(Out& r, int lane, uint32_t pos, uint32_t val) {
+    if (val > 31u) return false;
+    const uint32_t e = pos & 15u, sh = 8u * (e & 3u);
+    patch_regs<4>(r.o, e >> 2, (uint32_t)lane == (pos >> 4), 0x7cu << sh, val << (2u + sh));
+    return true;
+  }
+  __device__ static inline bool patch(const DecompressArgs& a, uint64_t i, uint32_t val) {
+    if (val > 31u) return false;
+    const uint64_t bit = 3 * i;
+    const uint8_t* p = a.comp + a.off_sm + (bit >> 3);
+    uint32_t two = p[0];
+    if ((bit & 7) > 5) two |= (uint32_t)p[1] << 8;   // the field straddles a byte; the next byte is inside the plane
+    const uint32_t sa = (two >> (bit & 7)) & 7u;
+    a.out[i] = (uint8_t)(((sa & 4u) << 5) | (val << 2) | (sa & 3u));
+    return true;
+  }
+};
+
+constexpr uint32_t kRegPatchMax = 32;   // escapes of a chunk that are applied in registers, before the store
+
+// one workgroup: tile `tile` of the tensor described by a (4 waves x cpw chunks)
+template <typename F>
+__device__ inline void decompress_tile(const DecompressArgs& a, const uint8_t* dec, uint32_t tile, uint32_t* tbl) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t* tab = reinterpret_cast<const uint32_t*>(a.comp + a.off_tab);
+  const uint32_t cpw = a.cpw;
+  const uint32_t wave_chunk0 = (tile * kWaves + wave) * cpw;
+  // first of all the loads everything else waits for: this wave's slice of the offset table (lane c
+  // <-> its chunk c, one entry more for the end) and M as the table states it
+  const uint32_t my_tab = (uint32_t)lane <= cpw && wave_chunk0 + lane <= a.n_chunks ? tab[wave_chunk0 + lane] : 0u;
+  uint32_t M = tab[a.n_chunks];
+  tbl[tid] = F::table(tid, dec);
+
+  // escapes are only trusted if their sections lie inside the stream
+  const uint64_t off_val = a.off_pos + a256(2ull * M);
+  const bool esc_ok = M <= a.n && off_val + M <= a.comp_bytes;
+  if (tile == 0 && tid == 0) {
+    decompress_check_header(a, dec, M);
+    if (!esc_ok) flag_bad(a);
+  }
+  if (!esc_ok) M = 0;
+  const uint16_t* pos_arr = reinterpret_cast<const uint16_t*>(a.comp + a.off_pos);
+  const uint8_t* val_arr = a.comp + off_val;
+  __syncthreads();
+
+  for (uint32_t c = 0; c < cpw; ++c) {
+    const uint32_t chunk = wave_chunk0 + c;
+    if (chunk >= a.n_chunks) break;
+    const uint64_t cbase = (uint64_t)chunk * kChunk;
+    const uint32_t lo = __builtin_amdgcn_readlane(my_tab, c), hi = __builtin_amdgcn_readlane(my_tab, c + 1);
+    const uint32_t clen = (uint32_t)(a.n - cbase < kChunk ? a.n - cbase : kChunk);
+    const bool esc_valid = hi >= lo && hi - lo <= clen && hi <= M;
+    const uint32_t cnt = esc_valid ? hi - lo : 0u;
+    if (!esc_valid && lane == 0) flag_bad(a);
+    // a few escapes (the usual case): their records are fetched while the planes are on their way,
+    // and applied to the decoded words in registers before the one store
+    const bool in_regs = cnt > 0 && cnt <= kRegPatchMax;
+    uint32_t pos = 0, val = 0;
+    if (in_regs && (uint32_t)lane < cnt) {
+      pos = pos_arr[lo + lane];
+      val = val_arr[lo + lane];
+    }
+    typename F::Out r;
+    const bool full = F::full(a, cbase);
+    if (full) F::template decode<true>(a, tbl, cbase, lane, r);
+    else F::template decode<false>(a, tbl, cbase, lane, r);
+    if (in_regs) {
+      for (uint32_t j = 0; j < cnt; ++j) {
+        const uint32_t p = __builtin_amdgcn_readlane(pos, j), v = __builtin_amdgcn_readlane(val, j);
+        if (p >= clen || !F::patch_reg(r, lane, p, v)) {
+          if (lane == 0) flag_bad(a);
+        }
+      }
+    }
+    if (full) F::template store<true>(a, cbase, lane, r);
+    else F::template store<false>(a, cbase, lane, r);
+    if (cnt > kRegPatchMax) {
+      // many escapes: sparse overwrite of the tensor in memory by the wave that wrote the chunk,
+      // once its dense stores have completed
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      for (uint32_t j = lo + lane; j < hi; j += 64) {
+        const uint32_t p = pos_arr[j];
+        const uint32_t v = val_arr[j];
+        if (p >= clen || !F::patch(a, cbase + p, v)) flag_bad(a);
+      }
+    }
+  }
+}
+
+template <typename F>
+__global__ __launch_bounds__(kThreads) void decompress_kernel(const DecompressArgs a) {
+  __shared__ uint32_t tbl[256];
+  decompress_tile<F>(a, a.dec, blockIdx.x, tbl);
+}
+
+// several streams in one launch: blockIdx.y picks the stream, blockIdx.x the tile
+struct DBatchItem {
+  const uint8_t* comp;
+  uint8_t* out;
+  uint64_t n, comp_bytes;
+};
+struct DecompressBatchArgs {
+  DBatchItem item[kBatchMax];
+  uint8_t dec_of[kBatchMax];
+  splitzip_sizes* sizes;   // nullable; one record, status bits sticky
+  uint32_t cpw, dtype;
+  uint8_t dec[kBatchLuts][16];
+};
+
+template <typename F>
+__global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const DecompressBatchArgs b) {
+  __shared__ uint32_t tbl[256];
+  const DBatchItem it = b.item[blockIdx.y];
+  const Layout L = make_layout(it.n, (int)b.dtype);
+  const uint32_t n_tiles = (uint32_t)((L.n_chunks + (uint64_t)kWaves * b.cpw - 1) / (kWaves * b.cpw));
+  if (blockIdx.x >= (n_tiles ? n_tiles : 1u)) return;
+  DecompressArgs a;
+  a.comp = it.comp;
+  a.out = it.out;
+  a.n = it.n;
+  a.comp_bytes = it.comp_bytes;
+  a.sizes = b.sizes;
+  a.off_tab = L.off_tab; a.off_sm = L.off_sm; a.off_code = L.off_code; a.off_pos = L.off_pos;
+  a.sm_bytes = L.sm_bytes; a.code_bytes = L.code_bytes;
+  a.n_chunks = (uint32_t)L.n_chunks;
+  a.n_tiles = n_tiles;
+  a.cpw = b.cpw;
+  a.dtype = b.dtype;
+  decompress_tile<F>(a, b.dec[b.dec_of[blockIdx.y]], blockIdx.x, tbl);   // a.dec stays unset: the table comes from the kernel arguments
+}
+
+#endif  // SPLITZIP_DECOMPRESS_HPP

@@ -1,32 +1,17 @@
-// SplitZip codec for MI355X (gfx950): HIP kernels and the C ABI of include/splitzip.h.
+// SplitZip codec for MI355X (gfx950): the C ABI of include/splitzip.h and the host side of its
+// kernels.  One translation unit; the kernels live in the headers included below:
+//   common.hpp      stream layout, wave scan, agent-scope accesses
+//   compress.hpp    dense transform (paper section 3.2 eq. (1), encode table, nibble pack, planes)
+//                   fused with escape detection, counting and position-ordered compaction
+//                   (appendix "Quad64 Vectorized Encoding" fuses only the counting); one launch
+//                   per tensor, or one launch for a batch of tensors
+//   decompress.hpp  nibble unpack, decode table, eq. (2), scatter correction in registers; one
+//                   launch per tensor or per batch
+//   aux_kernels.hpp calibration histogram (section 3.3), workspace initialisation, traffic probe
 //
-// One compress call is ONE kernel launch (tensors of up to 64 Mi elements or
-// so; larger ones take one launch per segment and a small finishing launch).
-// The dense transform (paper section 3.2 eq. (1), encode table, nibble pack,
-// sign+mantissa plane) is fused with escape detection, per-chunk counting and
-// the position-ordered compaction of the escape stream (appendix A fuses only
-// the counting).  The input is read exactly once: escapes are staged in LDS
-// while their words are in registers.  The launch is a persistent grid that
-// fits the chip; every workgroup owns one contiguous range of chunks, and the
-// one cross-workgroup step is a flat exchange of the per-range escape counts
-// through one word per workgroup: each workgroup publishes its count, reads
-// everybody's, and then knows both its own offset (counts of the ranges before
-// it) and M, so positions, values and the offset table go straight to their
-// final place.  No atomic read-modify-write is used: on this chip every
-// device-wide atomic on one address costs about 12 ns, serialised.
-// One decompress call is ONE kernel launch as well: nibble unpack, decode
-// table, eq. (2), and the sparse overwrite done by the wave that owns the
-// chunk once its own dense stores have completed.
-//
-// Work decomposition (wavefront = 64 lanes):
-//   chunk = 1024 elements (the escape-position granule), owned by one wave and
-//           processed as two half-chunks of 512 elements; in a half-chunk lane
-//           l owns elements [8 l, 8 l + 8): every global access of a wave is
-//           one fully coalesced run (16, 8 or 4 bytes per lane).
-//   compress: the chunks of a workgroup's range are dealt round-robin to its
-//           waves, so a workgroup reads one moving window.
-//   decompress: one workgroup per tile of 4 waves x cpw chunks.
-// All plane traffic uses non-temporal loads / stores: nothing is re-used.
+// Work decomposition (wavefront = 64 lanes): a chunk of 1024 elements (the escape-position
+// granule) is owned by one wave; every global access of a wave is one fully coalesced run of 16,
+// 8 or 4 bytes per lane; all plane traffic uses non-temporal loads and stores, nothing is re-used.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdlib.h>
@@ -36,1247 +21,10 @@
 
 namespace {
 
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-constexpr uint32_t kChunk = 1024;
-constexpr uint32_t kHalf = 512;
-constexpr uint32_t kHeaderBytes = 64;
-constexpr int kThreads = 256;                             // decompress / helper kernels
-constexpr int kWaves = kThreads / 64;
-constexpr uint32_t kMaxCpw = 16;                          // decompress: chunks per wave per tile, at most
-constexpr uint32_t kMaxRange = 256;                       // compress: chunks per workgroup per launch, at most
-constexpr uint32_t kMaxWorkgroups = 4096;                 // compress: words of exchange state in the workspace
-constexpr uint32_t kWsTableBytes = 8 * kMaxWorkgroups;
-constexpr uint32_t kStageCap = 512;                       // escapes a wave can stage in LDS
-constexpr uint32_t kWsHeaderBytes = 64;                   // epoch, running escape count, error flags
-constexpr uint32_t kSegFirst = 1u, kSegLast = 2u;         // CompressArgs.flags
-constexpr uint64_t kSpinTicks = 200000000ull;             // 2 s of the 100 MHz wall clock
-
-__host__ __device__ inline uint64_t a256(uint64_t x) { return (x + 255u) & ~(uint64_t)255u; }
-
-struct Layout {
-  uint64_t n, n_chunks, sm_bytes, code_bytes;
-  uint64_t off_tab, off_sm, off_code, off_pos;  // the value section starts at off_pos + a256(2M)
-};
-
-__host__ __device__ inline Layout make_layout(uint64_t n, int dtype) {
-  Layout L;
-  L.n = n;
-  L.n_chunks = (n + kChunk - 1) / kChunk;
-  L.sm_bytes = dtype == SPLITZIP_BF16 ? n : (3 * n + 7) / 8;
-  L.code_bytes = (n + 1) / 2;
-  L.off_tab = kHeaderBytes;
-  L.off_sm = a256(L.off_tab + 4 * (L.n_chunks + 1));
-  L.off_code = L.off_sm + a256(L.sm_bytes);
-  L.off_pos = L.off_code + a256(L.code_bytes);
-  return L;
-}
-
-// ---------------------------------------------------------------------------
-// device helpers
-// ---------------------------------------------------------------------------
-
-template <typename T>
-__device__ inline T ld_stream(const T* p) { return __builtin_nontemporal_load(p); }
-template <typename T>
-__device__ inline void st_stream(T* p, T v) { __builtin_nontemporal_store(v, p); }
-
-// v_perm_b32: result byte i = byte sel[i] of the 8-byte pool {hi:4..7, lo:0..3}; 0x0c gives 0x00.
-__device__ inline uint32_t byte_perm(uint32_t hi, uint32_t lo, uint32_t sel) {
-  return __builtin_amdgcn_perm(hi, lo, sel);
-}
-
-// inclusive prefix sum over the 64 lanes with DPP moves: Kogge-Stone inside rows of 16 lanes,
-// then the row totals are carried over with the two row-broadcast steps
-__device__ inline uint32_t wave_incl_scan(uint32_t v) {
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x111, 0xf, 0xf, false);  // row_shr:1
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x112, 0xf, 0xf, false);  // row_shr:2
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x114, 0xf, 0xf, false);  // row_shr:4
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x118, 0xf, 0xf, false);  // row_shr:8
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1, 3
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2, 3
-  return v;
-}
-
-__device__ inline uint32_t wave_last(uint32_t v) { return __builtin_amdgcn_readlane(v, 63); }
-
-// agent-scope relaxed accesses: performed at the device-wide coherence point, no fences
-template <typename T>
-__device__ inline void st_agent(T* p, T v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-template <typename T>
-__device__ inline T ld_agent(const T* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-
-// ---------------------------------------------------------------------------
-// compress
-// ---------------------------------------------------------------------------
-
-// what the dense pass and the trailer need to know of one tensor and its stream
-struct Planes {
-  const uint8_t* in;
-  uint8_t* out;
-  uint64_t n, capacity;
-  uint64_t off_tab, off_sm, off_code, off_pos, sm_bytes, code_bytes;
-  uint32_t n_chunks, dtype;
-};
-
-__host__ __device__ inline Planes make_planes(const void* in, void* out, uint64_t n, uint64_t capacity, int dtype) {
-  const Layout L = make_layout(n, dtype);
-  Planes p;
-  p.in = static_cast<const uint8_t*>(in);
-  p.out = static_cast<uint8_t*>(out);
-  p.n = n;
-  p.capacity = capacity;
-  p.off_tab = L.off_tab; p.off_sm = L.off_sm; p.off_code = L.off_code; p.off_pos = L.off_pos;
-  p.sm_bytes = L.sm_bytes; p.code_bytes = L.code_bytes;
-  p.n_chunks = (uint32_t)L.n_chunks;
-  p.dtype = (uint32_t)dtype;
-  return p;
-}
-
-struct CompressArgs {
-  Planes p;
-  uint32_t* ws_hdr;      // [0] epoch of this launch, [1] escapes of the earlier segments, [2] sticky error flags
-  uint64_t* state;       // one word per workgroup: epoch << 32 | escapes in its range
-  uint8_t* val_stage;    // n bytes: escape values of a call of several launches, until M is known
-  splitzip_sizes* sizes;
-  uint64_t spin_ticks;
-  uint32_t seg_chunk0, seg_chunks;   // the chunks this launch covers
-  uint32_t flags;        // kSegFirst | kSegLast
-  uint32_t expect_wgs;   // workgroups whose counts are awaited (= the grid size)
-  uint8_t dec[16];
-  uint16_t lut[256];     // exponent -> code | (non-member ? 0x100 : 0)   (the "marked" table of appendix A)
-};
-
-// where a chunk's escape records go: LDS staging (first pass) or their final place
-struct LdsSink {
-  uint16_t* pos;
-  uint8_t* val;
-  uint32_t tag;   // OR-ed into the position: which of the wave's chunks the record belongs to
-  __device__ inline void put(uint32_t r, uint32_t p, uint32_t e) const {
-    if (r < kStageCap) {
-      pos[r] = (uint16_t)(p | tag);
-      val[r] = (uint8_t)e;
-    }
-  }
-};
-struct GlobalSink {
-  uint16_t* pos;
-  uint8_t* val;
-  uint64_t pos_room, val_room;   // records that fit below the capacity
-  __device__ inline void put(uint32_t r, uint32_t p, uint32_t e) const {
-    if (r < pos_room) pos[r] = (uint16_t)p;
-    if (r < val_room) val[r] = (uint8_t)e;
-  }
-};
-
-// Dense transform of 8 BF16 elements held in four dwords.
-//   sm   : 8 sign+mantissa bytes, a = ((x >> 8) & 0x80) | (x & 0x7f)        (eq. (1))
-//   code : 8 nibbles, element j in nibble j
-//   F    : 8 nibbles, nibble j = 1 if element j is an escape
-__device__ inline void encode8_bf16(const uint32_t (&w)[4], const uint16_t* lut, u32x2& sm,
-                                    uint32_t& code, uint32_t& F) {
-  uint32_t t[4], u[4];
-#pragma unroll
-  for (int d = 0; d < 4; ++d) {
-    // bytes 0 and 2 of t hold a of the low / high half-word
-    t[d] = (w[d] & 0x007f007fu) | ((w[d] >> 8) & 0x00800080u);
-    const uint32_t e0 = (w[d] >> 7) & 0xffu, e1 = (w[d] >> 23) & 0xffu;
-    // low byte: code pair; high byte: flag pair in the same nibble layout
-    u[d] = (uint32_t)lut[e0] + ((uint32_t)lut[e1] << 4);
-  }
-  sm.x = byte_perm(t[1], t[0], 0x06040200u);
-  sm.y = byte_perm(t[3], t[2], 0x06040200u);
-  // x = [code(u_lo), code(u_hi), flag(u_lo), flag(u_hi)]
-  const uint32_t x01 = byte_perm(u[1], u[0], 0x05010400u), x23 = byte_perm(u[3], u[2], 0x05010400u);
-  code = byte_perm(x23, x01, 0x05040100u);
-  F = byte_perm(x23, x01, 0x07060302u);
-}
-
-// escape records of one lane's 8 elements (flag nibbles in m), ranks r, r+1, ...
-// The lane parks its four dwords in its own 16 bytes of LDS so that the escaping element can be
-// picked with a run-time index (registers cannot be indexed that way).
-template <typename Sink>
-__device__ inline void emit_half_bf16(uint32_t* park, const uint32_t (&w)[4], uint32_t m, uint32_t r,
-                                      uint32_t pos0, const Sink& sink) {
-  if (m) {
-    *reinterpret_cast<u32x4*>(park) = u32x4{w[0], w[1], w[2], w[3]};
-    const uint16_t* x = reinterpret_cast<const uint16_t*>(park);
-    do {
-      const uint32_t jj = (uint32_t)(__ffs(m) - 1) >> 2;
-      m &= m - 1;
-      sink.put(r, pos0 + jj, ((uint32_t)x[jj] >> 7) & 0xffu);
-      ++r;
-    } while (m);
-  }
-}
-
-// One chunk's words into registers: lane l holds elements [8 l, 8 l + 8) of each half-chunk.
-// Elements past N read as zero.
-template <bool FULL>
-__device__ inline void load_chunk_bf16(const Planes& a, uint64_t cbase, int lane, uint32_t (&w)[2][4]) {
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const uint64_t g0 = cbase + h * kHalf + lane * 8;   // first element of this lane's group
-    uint32_t nvalid = 8;
-    if (!FULL) nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 8 ? a.n - g0 : 8);
-    if (FULL) {
-      // chunk pointer (wave-uniform) + a 32-bit lane offset: no 64-bit vector arithmetic
-      const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(a.in + 2 * cbase) + (uint32_t)(h * 64 + lane));
-      w[h][0] = v.x; w[h][1] = v.y; w[h][2] = v.z; w[h][3] = v.w;
-    } else if (nvalid == 8) {
-      const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(a.in + 2 * g0));
-      w[h][0] = v.x; w[h][1] = v.y; w[h][2] = v.z; w[h][3] = v.w;
-    } else {
-      const uint16_t* p = reinterpret_cast<const uint16_t*>(a.in) + g0;
-#pragma unroll
-      for (int d = 0; d < 4; ++d) {
-        const uint32_t lo = (uint32_t)(2 * d) < nvalid ? p[2 * d] : 0u;
-        const uint32_t hi = (uint32_t)(2 * d + 1) < nvalid ? p[2 * d + 1] : 0u;
-        w[h][d] = lo | (hi << 16);
-      }
-    }
-  }
-}
-
-// One chunk by one wave, its words in w: dense transform, (optionally) plane stores, escape
-// ranks inside the chunk, escape records into `sink` starting at rank `base`.
-// Returns the chunk's escape count (wave-uniform).
-template <bool FULL, bool STORE, typename Sink>
-__device__ inline uint32_t process_chunk_bf16(const Planes& a, const uint16_t* lut, uint32_t* park,
-                                              uint64_t cbase, int lane, const uint32_t (&w)[2][4], uint32_t base,
-                                              const Sink& sink) {
-  uint32_t F[2];
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const uint64_t g0 = cbase + h * kHalf + lane * 8;
-    u32x2 sm;
-    uint32_t code;
-    encode8_bf16(w[h], lut, sm, code, F[h]);
-    if (!FULL) {
-      const uint32_t nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 8 ? a.n - g0 : 8);
-      // elements past N contribute zero nibbles (their sm bytes are already 0)
-      const uint32_t keep = nvalid == 8 ? ~0u : ((1u << (4 * nvalid)) - 1u);
-      code &= keep;
-      F[h] &= keep;
-    }
-    if (STORE) {
-      // Sections are padded to 256 bytes and a lane's group never straddles the padded end, so
-      // whole-group stores also write the zero padding.
-      if (FULL) {
-        st_stream(reinterpret_cast<u32x2*>(a.out + a.off_sm + cbase) + (uint32_t)(h * 64 + lane), sm);
-        st_stream(reinterpret_cast<uint32_t*>(a.out + a.off_code + (cbase >> 1)) + (uint32_t)(h * 64 + lane), code);
-      } else {
-        if (g0 < a256(a.sm_bytes)) st_stream(reinterpret_cast<u32x2*>(a.out + a.off_sm + g0), sm);
-        if ((g0 >> 1) < a256(a.code_bytes)) st_stream(reinterpret_cast<uint32_t*>(a.out + a.off_code + (g0 >> 1)), code);
-      }
-    }
-  }
-  // escapes per lane; both halves scanned at once (16 bits each: a half has at most 512)
-  const uint32_t packed = __popc(F[0]) | (__popc(F[1]) << 16);
-  const uint32_t incl = wave_incl_scan(packed);
-  const uint32_t tot = wave_last(incl);
-  const uint32_t excl = incl - packed;
-  const uint32_t tot0 = tot & 0xffffu, total = tot0 + (tot >> 16);
-  if (total) {
-    // element order inside the chunk: half, lane, element
-    emit_half_bf16(park, w[0], F[0], base + (excl & 0xffffu), lane * 8, sink);
-    emit_half_bf16(park, w[1], F[1], base + tot0 + (excl >> 16), kHalf + lane * 8, sink);
-  }
-  return total;
-}
-
-// ---- FP8 E5M2 (appendix "SplitZip on FP8"): byte = s eeeee mm, e = (x >> 2) & 31, a = s m1 m0 ----
-// One chunk by one wave; lane l owns the 16 consecutive elements [16 l, 16 l + 16): one 16-byte
-// load, 8 bytes of codes, 6 bytes of the 3-bit plane (lanes 2p and 2p+1 share 12 bytes: the even
-// lane stores 8 of them, the odd lane 4).
-
-// a of the four bytes of w, packed LSB first into 12 bits
-__device__ inline uint32_t pack3_e5m2(uint32_t w) {
-  const uint32_t t = ((w >> 5) & 0x04040404u) | (w & 0x03030303u);
-  const uint32_t u = (t | (t >> 5)) & 0x003f003fu;
-  return (u | (u >> 10)) & 0xfffu;
-}
-// inverse: 12 bits -> the sign and mantissa bits of four bytes, exponent field zero
-__device__ inline uint32_t unpack3_e5m2(uint32_t r) {
-  const uint32_t u = (r | (r << 10)) & 0x003f003fu;
-  const uint32_t t = (u | (u << 5)) & 0x07070707u;
-  return ((t & 0x04040404u) << 5) | (t & 0x03030303u);
-}
-
-template <bool FULL>
-__device__ inline void load_chunk_e5m2(const Planes& a, uint64_t cbase, int lane, uint32_t (&w)[4]) {
-  const uint64_t g0 = cbase + lane * 16;
-  uint32_t nvalid = 16;
-  if (!FULL) nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 16 ? a.n - g0 : 16);
-  if (FULL) {
-    const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(a.in + cbase) + (uint32_t)lane);
-    w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
-  } else if (nvalid == 16) {
-    const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(a.in + g0));
-    w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
-  } else {
-    const uint8_t* p = a.in + g0;
-#pragma unroll
-    for (int d = 0; d < 4; ++d) {
-      uint32_t x = 0;
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        if ((uint32_t)(4 * d + j) < nvalid) x |= (uint32_t)p[4 * d + j] << (8 * j);
-      w[d] = x;
-    }
-  }
-}
-
-template <bool FULL, bool STORE, typename Sink>
-__device__ inline uint32_t process_chunk_e5m2(const Planes& a, const uint16_t* lut, uint32_t* park,
-                                              uint64_t cbase, int lane, const uint32_t (&w)[4], uint32_t base,
-                                              const Sink& sink) {
-  const uint64_t g0 = cbase + lane * 16;
-  uint32_t r[4], u[8];
-#pragma unroll
-  for (int d = 0; d < 4; ++d) {
-    r[d] = pack3_e5m2(w[d]);
-    const uint32_t e0 = (w[d] >> 2) & 31u, e1 = (w[d] >> 10) & 31u, e2 = (w[d] >> 18) & 31u, e3 = (w[d] >> 26) & 31u;
-    // low byte: code pair; high byte: flag pair in the same nibble layout
-    u[2 * d] = (uint32_t)lut[e0] + ((uint32_t)lut[e1] << 4);
-    u[2 * d + 1] = (uint32_t)lut[e2] + ((uint32_t)lut[e3] << 4);
-  }
-  // the lane's 48 plane bits: lo holds bits 0..31, hi bits 32..47
-  uint32_t lo = r[0] | (r[1] << 12) | (r[2] << 24), hi = (r[2] >> 8) | (r[3] << 4);
-  uint32_t code[2], F[2];
-#pragma unroll
-  for (int q = 0; q < 2; ++q) {
-    const uint32_t x01 = byte_perm(u[4 * q + 1], u[4 * q], 0x05010400u), x23 = byte_perm(u[4 * q + 3], u[4 * q + 2], 0x05010400u);
-    code[q] = byte_perm(x23, x01, 0x05040100u);
-    F[q] = byte_perm(x23, x01, 0x07060302u);
-  }
-  if (!FULL) {
-    // elements past N contribute zero nibbles (their plane bits are already 0)
-    const uint32_t nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 16 ? a.n - g0 : 16);
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const uint32_t nv = nvalid > (uint32_t)(8 * q) ? nvalid - 8 * q : 0u;
-      const uint32_t keep = nv >= 8 ? ~0u : ((1u << (4 * nv)) - 1u);
-      code[q] &= keep;
-      F[q] &= keep;
-    }
-  }
-  if (STORE) {
-    // plane bytes of this lane pair: [12 p, 12 p + 12) of the chunk's 384
-    const uint32_t lo_up = __builtin_amdgcn_update_dpp(0u, lo, 0xF5, 0xf, 0xf, false);   // quad_perm [1,1,3,3]: the odd neighbour's lo
-    const uint64_t sm_off = (cbase / 8) * 3 + (uint32_t)(lane >> 1) * 12;
-    uint8_t* sm_dst = a.out + a.off_sm + (cbase / 8) * 3 + (uint32_t)(lane >> 1) * 12;   // uniform pointer + lane offset
-    uint32_t d0, d1;
-    if (lane & 1) {
-      d0 = (lo >> 16) | (hi << 16);
-      d1 = 0;
-    } else {
-      d0 = lo;
-      d1 = (hi & 0xffffu) | (lo_up << 16);
-    }
-    if (FULL) {
-      if (lane & 1) st_stream(reinterpret_cast<uint32_t*>(sm_dst + 8), d0);
-      else st_stream(reinterpret_cast<u32x2*>(sm_dst), u32x2{d0, d1});
-      st_stream(reinterpret_cast<u32x2*>(a.out + a.off_code + (cbase >> 1)) + (uint32_t)lane, u32x2{code[0], code[1]});
-    } else {
-      // dword by dword up to the padded end of each plane; the pad can reach 128 bytes past the
-      // chunk's own 384 plane bytes
-      const uint64_t sm_end = a256(a.sm_bytes);
-      if (lane & 1) {
-        if (sm_off + 8 < sm_end) *reinterpret_cast<uint32_t*>(sm_dst + 8) = d0;
-      } else {
-        if (sm_off < sm_end) *reinterpret_cast<uint32_t*>(sm_dst) = d0;
-        if (sm_off + 4 < sm_end) *reinterpret_cast<uint32_t*>(sm_dst + 4) = d1;
-      }
-      const uint64_t past = (cbase / 8) * 3 + 384 + 4 * (uint32_t)lane;
-      if (lane < 32 && past < sm_end) *reinterpret_cast<uint32_t*>(a.out + a.off_sm + past) = 0;
-      if ((g0 >> 1) < a256(a.code_bytes))
-        *reinterpret_cast<u32x2*>(a.out + a.off_code + (g0 >> 1)) = u32x2{code[0], code[1]};
-    }
-  }
-  const uint32_t mine = __popc(F[0]) + __popc(F[1]);
-  const uint32_t incl = wave_incl_scan(mine);
-  const uint32_t total = wave_last(incl);
-  if (total && mine) {
-    // element order inside the chunk: lane, element
-    *reinterpret_cast<u32x4*>(park) = u32x4{w[0], w[1], w[2], w[3]};
-    const uint8_t* x = reinterpret_cast<const uint8_t*>(park);
-    uint32_t rr = base + incl - mine;
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      uint32_t m = F[q];
-      while (m) {
-        const uint32_t jj = 8 * q + ((uint32_t)(__ffs(m) - 1) >> 2);
-        m &= m - 1;
-        sink.put(rr, lane * 16 + jj, ((uint32_t)x[jj] >> 2) & 0x1fu);
-        ++rr;
-      }
-    }
-  }
-  return total;
-}
-
-// the two formats as seen by the compress kernel
-struct Bf16 {
-  struct Regs { uint32_t w[2][4]; };
-  // a chunk goes the fast way if it is complete (then nothing of a pad is its business: N is a multiple of 1024 there)
-  __device__ static inline bool full(const Planes& a, uint64_t cbase) { return cbase + kChunk <= a.n; }
-  template <bool FULL>
-  __device__ static inline void load(const Planes& a, uint64_t cbase, int lane, Regs& r) { load_chunk_bf16<FULL>(a, cbase, lane, r.w); }
-  template <bool FULL, bool STORE, typename Sink>
-  __device__ static inline uint32_t process(const Planes& a, const uint16_t* lut, uint32_t* park, uint64_t cbase,
-                                            int lane, const Regs& r, uint32_t base, const Sink& sink) {
-    return process_chunk_bf16<FULL, STORE>(a, lut, park, cbase, lane, r.w, base, sink);
-  }
-};
-struct E5m2 {
-  struct Regs { uint32_t w[4]; };
-  // the tensor's last chunk always goes the careful way: 384 plane bytes per chunk leave a pad behind an odd chunk count
-  __device__ static inline bool full(const Planes& a, uint64_t cbase) { return cbase + kChunk < a.n; }
-  template <bool FULL>
-  __device__ static inline void load(const Planes& a, uint64_t cbase, int lane, Regs& r) { load_chunk_e5m2<FULL>(a, cbase, lane, r.w); }
-  template <bool FULL, bool STORE, typename Sink>
-  __device__ static inline uint32_t process(const Planes& a, const uint16_t* lut, uint32_t* park, uint64_t cbase,
-                                            int lane, const Regs& r, uint32_t base, const Sink& sink) {
-    return process_chunk_e5m2<FULL, STORE>(a, lut, park, cbase, lane, r.w, base, sink);
-  }
-};
-
-// header, sizes record and the zero padding behind the positions: one wave, once M is known
-__device__ void compress_write_trailer(const Planes& a, const uint8_t* dec, splitzip_sizes* sizes, uint32_t M,
-                                       uint32_t err_flags, int lane) {
-  const uint64_t off_val = a.off_pos + a256(2ull * M);
-  const uint64_t total = off_val + M;
-  for (uint64_t i = 2ull * M + lane; i < a256(2ull * M); i += 64)
-    if (a.off_pos + i < a.capacity) a.out[a.off_pos + i] = 0;
-  // chunk_off[C] = M, then zero padding up to the sign+mantissa plane
-  uint32_t* tab = reinterpret_cast<uint32_t*>(a.out + a.off_tab);
-  for (uint64_t i = (uint64_t)a.n_chunks + lane; a.off_tab + 4 * i < a.off_sm; i += 64) tab[i] = i == a.n_chunks ? M : 0u;
-  if (lane == 0) {
-    uint32_t h[16];
-#pragma unroll
-    for (int i = 0; i < 16; ++i) h[i] = 0;
-    h[0] = 0x31505a53u;                           // "SZP1"
-    h[1] = 1u | (a.dtype << 16) | (4u << 24);      // version, dtype, code bits
-    h[2] = kChunk;
-    h[4] = (uint32_t)a.n; h[5] = (uint32_t)(a.n >> 32);
-    h[6] = M;
-    h[8] = (uint32_t)total; h[9] = (uint32_t)(total >> 32);
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      h[10 + i] = dec[4 * i] | (dec[4 * i + 1] << 8) | (dec[4 * i + 2] << 16) | ((uint32_t)dec[4 * i + 3] << 24);
-    uint4* ho = reinterpret_cast<uint4*>(a.out);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) ho[i] = make_uint4(h[4 * i], h[4 * i + 1], h[4 * i + 2], h[4 * i + 3]);
-    sizes->total_bytes = total;
-    sizes->n_escapes = M;
-    sizes->status = (total > a.capacity ? SPLITZIP_STATUS_OVERFLOW : 0u) | err_flags;
-    sizes->reserved = 0;
-  }
-}
-
-// ---- building blocks of the compress kernels ----
-// A workgroup owns a contiguous range [r0, r0 + nb) of a tensor's chunks, nb <= kMaxRange, dealt
-// round-robin to its NW waves (chunk k of the range belongs to wave k mod NW).  LDS per range:
-//   stage_pk/val[wave][.]  the wave's escape records, position | (k / NW) << 10 and exponent
-//   s_off[k]               escapes of chunk k, after the scan: escapes of the chunks before it
-//   s_wstart[k]            records its wave had staged before chunk k
-struct RangeLds {
-  uint16_t* stage_pk;    // this wave's kStageCap entries
-  uint8_t* stage_val;
-  uint32_t* s_off;       // kMaxRange + 1
-  uint16_t* s_wstart;    // kMaxRange
-};
-
-// this workgroup's share of `chunks` chunks starting at chunk0: dealt evenly, the first `rem`
-// workgroups get one more
-__device__ inline void my_range(uint32_t chunk0, uint32_t chunks, uint32_t wgs, uint32_t b, uint32_t& r0, uint32_t& nb) {
-  const uint32_t per = chunks / wgs, rem = chunks % wgs;
-  nb = per + (b < rem ? 1u : 0u);
-  r0 = chunk0 + b * per + (b < rem ? b : rem);
-}
-
-struct NoHook {
-  __device__ inline void operator()() const {}
-};
-
-// dense pass of one wave over its chunks of the range; the next chunk's loads are issued before
-// this chunk is worked on.  `mid` is called once, half way through (not at all by a wave without
-// chunks).  Returns the wave's escape count.
-template <int NW, typename F, typename Hook>
-__device__ inline uint32_t dense_pass(const Planes& P, const uint16_t* lut, uint32_t* park, const RangeLds& L,
-                                      uint32_t r0, uint32_t nb, int wave, int lane, Hook& mid) {
-  uint32_t wave_count = 0;
-  const uint32_t mid_it = nb > (uint32_t)wave ? ((nb - wave + NW - 1) / NW) / 2 : 0u;
-  typename F::Regs w, nx;
-  if ((uint32_t)wave < nb) {
-    const uint64_t cbase = (uint64_t)(r0 + wave) * kChunk;
-    if (F::full(P, cbase)) F::template load<true>(P, cbase, lane, w);
-    else F::template load<false>(P, cbase, lane, w);
-  }
-  for (uint32_t k = wave, it = 0; k < nb; k += NW, ++it) {
-    const uint64_t cbase = (uint64_t)(r0 + k) * kChunk;
-    if (k + NW < nb) {
-      const uint64_t nbase = cbase + (uint64_t)NW * kChunk;
-      if (F::full(P, nbase)) F::template load<true>(P, nbase, lane, nx);
-      else F::template load<false>(P, nbase, lane, nx);
-    }
-    if (it == mid_it) mid();
-    const LdsSink lds{L.stage_pk, L.stage_val, it << 10};
-    const uint32_t cnt = F::full(P, cbase) ? F::template process<true, true>(P, lut, park, cbase, lane, w, wave_count, lds)
-                                           : F::template process<false, true>(P, lut, park, cbase, lane, w, wave_count, lds);
-    if (lane == 0) {
-      L.s_off[k] = cnt;
-      L.s_wstart[k] = (uint16_t)(wave_count < 0xffffu ? wave_count : 0xffffu);
-    }
-    wave_count += cnt;
-    w = nx;
-  }
-  return wave_count;
-}
-
-// one wave: exclusive offsets of the range's chunks, four per lane, in place; s_off[nb] = total
-__device__ inline void scan_range(uint32_t* s_off, uint32_t nb, int lane) {
-  uint32_t v[4], sum = 0;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const uint32_t q = 4 * lane + j;
-    v[j] = q < nb ? s_off[q] : 0u;
-    sum += v[j];
-  }
-  const uint32_t incl = wave_incl_scan(sum);
-  uint32_t run = incl - sum;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const uint32_t q = 4 * lane + j;
-    if (q < nb) s_off[q] = run;
-    run += v[j];
-  }
-  if (lane == 63) s_off[nb] = incl;
-}
-
-// one wave: wait until the words of all `wgs` workgroups carry `tag`, then sum the counts of the
-// workgroups before b (lower) and of all.  Returns false if the wait was given up: it is bounded
-// by spin_ticks of the 100 MHz wall clock (or not begun at all if `dead`).
-__device__ inline bool exchange(const uint64_t* state, uint32_t tag, uint32_t wgs, uint32_t b, int lane,
-                                uint64_t spin_ticks, bool dead, uint32_t& lower, uint32_t& all) {
-  uint32_t lo = 0, al = 0, spins = 0;
-  bool ok = !dead;
-  const uint64_t t0 = wall_clock64();
-  while (ok) {
-    lo = 0;
-    al = 0;
-    int ready = 1;
-    for (uint32_t i = lane; i < wgs; i += 64) {
-      const uint64_t s = ld_agent(&state[i]);
-      if ((uint32_t)(s >> 32) != tag) ready = 0;
-      al += (uint32_t)s;
-      lo += i < b ? (uint32_t)s : 0u;
-    }
-    if (__ballot(ready) == ~0ull) break;
-    if ((++spins & 15u) == 0 && (uint64_t)(wall_clock64() - t0) > spin_ticks) ok = false;
-    else __builtin_amdgcn_s_sleep(1);
-  }
-  lower = wave_last(wave_incl_scan(lo));
-  all = wave_last(wave_incl_scan(al));
-  return ok;
-}
-
-// all waves: the range's entries of the stream's offset table and this wave's escape records to
-// their final rank.  `prefix` = escapes before the range in the whole tensor.
-template <int NW, typename F>
-__device__ inline void write_out(const Planes& P, const uint16_t* lut, uint32_t* park, const RangeLds& L,
-                                 uint32_t r0, uint32_t nb, uint32_t wave_count, uint32_t prefix,
-                                 const GlobalSink& g, int tid, int wave, int lane) {
-  uint32_t* tab = reinterpret_cast<uint32_t*>(P.out + P.off_tab);
-  if ((uint32_t)tid < nb) tab[r0 + tid] = prefix + L.s_off[tid];
-  if (wave_count <= kStageCap) {
-    // staged record i of this wave belongs to chunk k and is the (i - s_wstart[k])-th of it
-    for (uint32_t i = lane; i < wave_count; i += 64) {
-      const uint32_t pk = L.stage_pk[i], k = (pk >> 10) * NW + wave;
-      g.put(prefix + L.s_off[k] + (i - L.s_wstart[k]), pk & 1023u, L.stage_val[i]);
-    }
-  } else {
-    // more escapes than the staging holds: go over this wave's chunks again and write the
-    // records straight to their place
-    typename F::Regs w;
-    for (uint32_t k = wave; k < nb; k += NW) {
-      const uint64_t cbase = (uint64_t)(r0 + k) * kChunk;
-      const uint32_t r = prefix + L.s_off[k];
-      if (F::full(P, cbase)) {
-        F::template load<true>(P, cbase, lane, w);
-        F::template process<true, false>(P, lut, park, cbase, lane, w, r, g);
-      } else {
-        F::template load<false>(P, cbase, lane, w);
-        F::template process<false, false>(P, lut, park, cbase, lane, w, r, g);
-      }
-    }
-  }
-}
-
-// where escape records of a tensor go when M is final: positions and, behind them, values
-__device__ inline GlobalSink final_sink(const Planes& P, uint32_t M) {
-  const uint64_t off_val = P.off_pos + a256(2ull * M);
-  GlobalSink g;
-  g.pos = reinterpret_cast<uint16_t*>(P.out + P.off_pos);
-  g.pos_room = P.capacity > P.off_pos ? (P.capacity - P.off_pos) / 2 : 0;
-  g.val = P.out + off_val;
-  g.val_room = P.capacity > off_val ? P.capacity - off_val : 0;
-  return g;
-}
-
-// One launch covers the chunks [seg_chunk0, seg_chunk0 + seg_chunks) with a grid in which every
-// workgroup is resident at the same time.  After its dense pass a workgroup publishes the escape
-// count of its range in state[b] (tagged with the launch's epoch, so that the words never need
-// clearing) and one wave reads the words of all workgroups: the counts before b give its offset,
-// all of them give M.  The wait ends when the slowest workgroup has published.
-template <int T, typename F>
-__global__ __launch_bounds__(T) void compress_kernel(const CompressArgs a) {
-  constexpr int NW = T / 64;
-  static_assert(kMaxRange <= 256 && NW >= 4 && NW <= 16, "one wave scans the range, four chunks per lane");
-  __shared__ uint16_t lut[256];
-  __shared__ uint16_t stage_pk[NW][kStageCap];
-  __shared__ uint8_t stage_val[NW][kStageCap];
-  __shared__ uint32_t s_off[kMaxRange + 1];
-  __shared__ uint16_t s_wstart[kMaxRange];
-  __shared__ u32x4 s_park[T];
-  __shared__ uint32_t s_red[16];
-  __shared__ uint32_t s_misc[4];
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: loops over chunks stay scalar
-  const uint32_t b = blockIdx.x;
-  uint32_t* park = reinterpret_cast<uint32_t*>(&s_park[tid]);
-  const RangeLds L{stage_pk[wave], stage_val[wave], s_off, s_wstart};
-
-  if (tid < 256) lut[tid] = a.lut[tid];
-  const uint32_t epoch = ld_agent(&a.ws_hdr[0]);
-  const uint32_t base = (a.flags & kSegFirst) ? 0u : ld_agent(&a.ws_hdr[1]);
-  const uint32_t err_before = b == 0 ? ld_agent(&a.ws_hdr[2]) : 0u;   // sticky flags of earlier launches
-  const bool single = (a.flags & (kSegFirst | kSegLast)) == (kSegFirst | kSegLast);
-  __syncthreads();
-
-  uint32_t r0, nb;
-  my_range(a.seg_chunk0, a.seg_chunks, gridDim.x, b, r0, nb);
-  NoHook no_hook;
-  const uint32_t wave_count = dense_pass<NW, F>(a.p, lut, park, L, r0, nb, wave, lane, no_hook);
-  if (lane == 0) s_red[wave] = wave_count;
-  __syncthreads();
-
-  if (wave == 0) {
-    const uint32_t agg = wave_last(wave_incl_scan(lane < NW ? s_red[lane] : 0u));
-    if (lane == 0) st_agent(&a.state[b], ((uint64_t)epoch << 32) | agg);
-    uint32_t lo, al;
-    const bool ok = exchange(a.state, epoch, a.expect_wgs, b, lane, a.spin_ticks, false, lo, al);
-    if (lane == 0) {
-      s_misc[0] = base + lo;
-      s_misc[1] = base + al;
-      s_misc[2] = ok ? 0u : 1u;
-    }
-    // workgroup 0 closes the launch: it has seen every workgroup's word, so all of them have
-    // read the header words
-    if (b == 0) {
-      const uint32_t err = err_before | (ok ? 0u : (uint32_t)SPLITZIP_STATUS_INTERNAL);
-      if (lane == 0) {
-        st_agent(&a.ws_hdr[0], epoch + 1u);
-        st_agent(&a.ws_hdr[1], base + al);
-        st_agent(&a.ws_hdr[2], single ? 0u : err);   // a call of several launches reports in its finishing launch
-      }
-      if (single) compress_write_trailer(a.p, a.dec, a.sizes, base + al, err, lane);
-    }
-  } else if (wave == 1) {
-    scan_range(s_off, nb, lane);   // meanwhile
-  }
-  __syncthreads();
-  const uint32_t prefix = s_misc[0], M = s_misc[1];
-  const bool timed_out = s_misc[2] != 0;
-
-  if (!timed_out) {
-    // values go behind the positions when M is final, else into the workspace
-    GlobalSink g = final_sink(a.p, M);
-    if (!single) {
-      g.val = a.val_stage;
-      g.val_room = ~0ull;
-    }
-    write_out<NW, F>(a.p, lut, park, L, r0, nb, wave_count, prefix, g, tid, wave, lane);
-  } else if (tid == 0) {
-    __hip_atomic_fetch_or(&a.ws_hdr[2], (uint32_t)SPLITZIP_STATUS_INTERNAL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
-}
-
-// ---- several tensors in one launch ----
-constexpr uint32_t kBatchMax = 64;     // tensors per launch: their descriptors travel as kernel arguments
-constexpr uint32_t kBatchLuts = 2;     // codebooks per launch
-constexpr uint32_t kRing = 4;          // exchange slots: a workgroup can be two tensors ahead of the slowest
-constexpr uint32_t kRingWgs = 1024;    // words per slot
-
-struct BatchItem {
-  const uint8_t* in;
-  uint8_t* out;
-  uint64_t n, capacity;
-};
-struct CompressBatchArgs {
-  BatchItem item[kBatchMax];
-  uint8_t lut_of[kBatchMax];
-  splitzip_sizes* sizes;     // n_items records
-  uint32_t* ws_hdr;          // [0] epoch, [2] sticky error flags, [3] groups that are through
-  uint64_t* state;           // per group kRing slots of group_wgs words: (epoch + item) << 32 | escapes in the range
-  uint64_t spin_ticks;
-  uint32_t n_items, dtype;
-  uint32_t group_wgs;        // workgroups that share one tensor; the grid is n_groups * group_wgs
-  uint32_t await_extra;      // error-path tests: words awaited beyond the group's
-  uint8_t dec[kBatchLuts][16];
-  uint16_t lut[kBatchLuts][256];
-};
-
-// wave 0, half way through a dense pass: the loads of the previous tensor's exchange words, so that
-// their latency is hidden.  Up to 256 workgroups per group (four words per lane).
-struct ExchangePrefetch {
-  const uint64_t* slot;
-  uint32_t wgs;
-  int lane;
-  bool enabled, issued;
-  uint64_t v[4];
-  __device__ inline void operator()() {
-    if (!enabled) return;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const uint32_t i = lane + 64 * j;
-      v[j] = i < wgs ? ld_agent(&slot[i]) : 0ull;
-    }
-    issued = true;
-  }
-};
-
-// The same persistent grid works through the tensors one after the other, and the exchange of
-// tensor i is taken out of the critical path: a workgroup publishes its count for tensor i, then
-// completes tensor i - 1 (whose counts every workgroup published a whole dense pass ago; the words
-// are even fetched half way through the dense pass of tensor i, so the read costs nothing) and
-// goes on to tensor i + 1.  Staging in LDS is double buffered.  What a single launch pays per
-// tensor -- the wait for the slowest workgroup, the exchange, the write-out and the launch itself
-// -- is paid once per batch here.  Small tensors are shared by a group of workgroups only; the
-// groups work on different tensors at the same time (tensor i belongs to group i mod n_groups).
-template <int T, typename F>
-__global__ __launch_bounds__(T) void compress_batch_kernel(const CompressBatchArgs a) {
-  constexpr int NW = T / 64;
-  __shared__ uint16_t lut[kBatchLuts][256];
-  __shared__ uint16_t stage_pk[2][NW][kStageCap];
-  __shared__ uint8_t stage_val[2][NW][kStageCap];
-  __shared__ uint32_t s_off[2][kMaxRange + 1];
-  __shared__ uint16_t s_wstart[2][kMaxRange];
-  __shared__ u32x4 s_park[T];
-  __shared__ uint32_t s_red[16];
-  __shared__ uint32_t s_misc[4];
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const uint32_t G = a.group_wgs, n_groups = gridDim.x / G;
-  const uint32_t grp = blockIdx.x / G, b = blockIdx.x % G;
-  uint32_t* park = reinterpret_cast<uint32_t*>(&s_park[tid]);
-
-  for (int i = tid; i < (int)(kBatchLuts * 256); i += T) lut[i >> 8][i & 255] = a.lut[i >> 8][i & 255];
-  const uint32_t epoch = ld_agent(&a.ws_hdr[0]);
-  const uint32_t err_before = b == 0 ? ld_agent(&a.ws_hdr[2]) : 0u;
-  if (tid == 0) s_misc[3] = 0;   // set once an exchange was given up: later ones are not waited for
-  __syncthreads();
-
-  uint64_t* const ring = a.state + (uint64_t)grp * kRing * G;   // this group's slots
-  Planes Pprev = make_planes(nullptr, nullptr, 0, 0, (int)a.dtype);
-  uint32_t prev_count = 0, prev_r0 = 0, prev_nb = 0, prev_item = 0;
-  // this group's tensors: grp, grp + n_groups, ...; seq counts them
-  for (uint32_t seq = 0;; ++seq) {
-    const uint32_t i = grp + seq * n_groups;
-    const bool have = i < a.n_items;
-    if (!have && seq == 0) break;   // a group without tensors
-    const uint32_t set = seq & 1u;
-    const RangeLds L{stage_pk[set][wave], stage_val[set][wave], s_off[set], s_wstart[set]};
-    Planes P = Pprev;
-    uint32_t r0 = 0, nb = 0, wave_count = 0;
-    ExchangePrefetch pf;
-    pf.slot = ring + ((seq + kRing - 1) % kRing) * G;
-    pf.wgs = G;
-    pf.lane = lane;
-    pf.enabled = wave == 0 && seq > 0 && G <= 256 && a.await_extra == 0;
-    pf.issued = false;
-    if (have) {
-      P = make_planes(a.item[i].in, a.item[i].out, a.item[i].n, a.item[i].capacity, (int)a.dtype);
-      my_range(0, P.n_chunks, G, b, r0, nb);
-      wave_count = dense_pass<NW, F>(P, lut[a.lut_of[i]], park, L, r0, nb, wave, lane, pf);
-      if (lane == 0) s_red[wave] = wave_count;
-    }
-    __syncthreads();
-    if (wave == 0) {
-      if (have) {
-        const uint32_t agg = wave_last(wave_incl_scan(lane < NW ? s_red[lane] : 0u));
-        if (lane == 0) st_agent(&ring[(seq % kRing) * G + b], ((uint64_t)(epoch + i) << 32) | agg);
-      }
-      if (seq > 0) {
-        // complete the previous tensor: from the prefetched words if they were all there
-        const uint32_t tag = epoch + prev_item;
-        uint32_t lo = 0, al = 0;
-        bool ok = true, done = false;
-        if (pf.issued) {
-          int ready = 1;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const uint32_t q = lane + 64 * j;
-            if (q < G) {
-              if ((uint32_t)(pf.v[j] >> 32) != tag) ready = 0;
-              al += (uint32_t)pf.v[j];
-              lo += q < b ? (uint32_t)pf.v[j] : 0u;
-            }
-          }
-          if (__ballot(ready) == ~0ull) {
-            lo = wave_last(wave_incl_scan(lo));
-            al = wave_last(wave_incl_scan(al));
-            done = true;
-          }
-        }
-        if (!done)
-          ok = exchange(ring + ((seq - 1) % kRing) * G, tag, G + a.await_extra, b, lane, a.spin_ticks, s_misc[3] != 0, lo, al);
-        if (lane == 0) {
-          s_misc[0] = lo;
-          s_misc[1] = al;
-          s_misc[2] = ok ? 0u : 1u;
-          if (!ok) s_misc[3] = 1;
-        }
-        if (b == 0) {
-          const uint32_t err = err_before | (ok ? 0u : (uint32_t)SPLITZIP_STATUS_INTERNAL);
-          compress_write_trailer(Pprev, a.dec[a.lut_of[prev_item]], a.sizes + prev_item, al, err, lane);
-          if (!have && lane == 0) {
-            // this group is through.  The last group to get here closes the launch: by then every
-            // workgroup has read the header words, because each group completed an exchange.
-            const uint32_t through = __hip_atomic_fetch_add(&a.ws_hdr[3], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const uint32_t active = a.n_items < n_groups ? a.n_items : n_groups;
-            if (through + 1 == active) {
-              st_agent(&a.ws_hdr[3], 0u);
-              st_agent(&a.ws_hdr[2], 0u);
-              st_agent(&a.ws_hdr[0], epoch + a.n_items);
-            }
-          }
-        }
-      }
-    } else if (wave == 1 && have) {
-      scan_range(s_off[set], nb, lane);
-    }
-    __syncthreads();
-    if (seq > 0 && s_misc[2] == 0) {
-      const uint32_t pset = set ^ 1u;
-      const RangeLds Lp{stage_pk[pset][wave], stage_val[pset][wave], s_off[pset], s_wstart[pset]};
-      write_out<NW, F>(Pprev, lut[a.lut_of[prev_item]], park, Lp, prev_r0, prev_nb, prev_count, s_misc[0],
-                       final_sink(Pprev, s_misc[1]), tid, wave, lane);
-    }
-    if (!have) break;
-    __syncthreads();   // the previous tensor's LDS set is free again, s_misc may be rewritten
-    Pprev = P;
-    prev_count = wave_count;
-    prev_r0 = r0;
-    prev_nb = nb;
-    prev_item = i;
-  }
-}
-
-// Last launch of a call that took several: M is known now.  Moves the staged escape values
-// behind the position array and writes the trailer.
-__global__ __launch_bounds__(kThreads) void compress_finish_kernel(const CompressArgs a) {
-  const uint32_t M = ld_agent(&a.ws_hdr[1]);
-  const uint64_t off_val = a.p.off_pos + a256(2ull * M);
-  const uint64_t room = a.p.capacity > off_val ? a.p.capacity - off_val : 0;
-  const uint64_t m = M < room ? M : room;
-  const uint64_t nvec = m / 16;
-  const u32x4* src = reinterpret_cast<const u32x4*>(a.val_stage);
-  u32x4* dst = reinterpret_cast<u32x4*>(a.p.out + off_val);
-  const uint64_t gtid = blockIdx.x * (uint64_t)kThreads + threadIdx.x, gsz = (uint64_t)gridDim.x * kThreads;
-  for (uint64_t i = gtid; i < nvec; i += gsz) dst[i] = src[i];
-  for (uint64_t i = nvec * 16 + gtid; i < m; i += gsz) a.p.out[off_val + i] = a.val_stage[i];
-  if (blockIdx.x == 0 && threadIdx.x < 64) {
-    uint32_t err = 0;
-    if (threadIdx.x == 0) {
-      err = ld_agent(&a.ws_hdr[2]);
-      st_agent(&a.ws_hdr[2], 0u);
-    }
-    compress_write_trailer(a.p, a.dec, a.sizes, M, err, threadIdx.x);
-  }
-}
-
-// ---------------------------------------------------------------------------
-// decompress
-// ---------------------------------------------------------------------------
-
-struct DecompressArgs {
-  const uint8_t* comp;
-  uint8_t* out;
-  uint64_t n, comp_bytes;
-  splitzip_sizes* sizes;   // nullable
-  uint64_t off_tab, off_sm, off_code, off_pos, sm_bytes, code_bytes;
-  uint32_t n_chunks, n_tiles, cpw, dtype;
-  uint8_t dec[16];
-};
-
-__device__ inline void flag_bad(const DecompressArgs& a) {
-  if (a.sizes) atomicOr(&a.sizes->status, SPLITZIP_STATUS_BAD_STREAM);
-}
-
-// header checks: one thread of workgroup 0
-__device__ void decompress_check_header(const DecompressArgs& a, const uint8_t* dec, uint32_t M) {
-  const uint32_t* h = reinterpret_cast<const uint32_t*>(a.comp);
-  const uint64_t n = h[4] | ((uint64_t)h[5] << 32), m = h[6] | ((uint64_t)h[7] << 32);
-  const uint64_t total = h[8] | ((uint64_t)h[9] << 32);
-  bool ok = h[0] == 0x31505a53u && h[1] == (1u | (a.dtype << 16) | (4u << 24)) && h[2] == kChunk &&
-            h[3] == 0 && n == a.n && m == M && total == a.off_pos + a256(2 * m) + m &&
-            total <= a.comp_bytes && h[14] == 0 && h[15] == 0;
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-    ok = ok && h[10 + i] == (dec[4 * i] | (dec[4 * i + 1] << 8) | (dec[4 * i + 2] << 16) |
-                             ((uint32_t)dec[4 * i + 3] << 24));
-  if (!ok) flag_bad(a);
-  if (a.sizes) {
-    a.sizes->total_bytes = total;
-    a.sizes->n_escapes = m;
-  }
-}
-
-// BF16 dense decode of one chunk by one wave into registers: two half-chunks, 8 elements per lane
-// each; o[4 h + d] holds elements 2 d and 2 d + 1 of the lane's group in half h
-template <bool FULL>
-__device__ inline void decode_chunk_bf16(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane, uint32_t (&o)[8]) {
-  u32x2 sm[2];
-  uint32_t cd[2];
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const uint64_t g0 = cbase + h * kHalf + lane * 8;
-    sm[h] = u32x2{0u, 0u};
-    cd[h] = 0;
-    if (FULL || g0 < a256(a.sm_bytes)) sm[h] = ld_stream(reinterpret_cast<const u32x2*>(a.comp + a.off_sm + g0));
-    if (FULL || (g0 >> 1) < a256(a.code_bytes))
-      cd[h] = ld_stream(reinterpret_cast<const uint32_t*>(a.comp + a.off_code + (g0 >> 1)));
-  }
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const uint32_t smw[2] = {sm[h].x, sm[h].y};
-#pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      // code byte b -> both exponents already in place (bits 7..14 and 23..30)
-      const uint32_t cb = (cd[h] >> (8 * b)) & 0xffu;
-      // [a0, a0, a1, a1], then keep mantissa in the low and sign in the high byte of each half-word (eq. (2))
-      const uint32_t p = byte_perm(0u, smw[b >> 1], (b & 1) ? 0x03030202u : 0x01010000u);
-      o[4 * h + b] = (p & 0x807f807fu) | tbl[cb];
-    }
-  }
-}
-
-template <bool FULL>
-__device__ inline void store_chunk_bf16(const DecompressArgs& a, uint64_t cbase, int lane, const uint32_t (&o)[8]) {
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const uint64_t g0 = cbase + h * kHalf + lane * 8;
-    uint32_t nvalid = 8;
-    if (!FULL) nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 8 ? a.n - g0 : 8);
-    if (FULL || nvalid == 8) {
-      st_stream(reinterpret_cast<u32x4*>(a.out + 2 * g0), u32x4{o[4 * h], o[4 * h + 1], o[4 * h + 2], o[4 * h + 3]});
-    } else {
-      uint16_t* q = reinterpret_cast<uint16_t*>(a.out) + g0;
-#pragma unroll
-      for (int d = 0; d < 4; ++d) {
-        if ((uint32_t)(2 * d) < nvalid) q[2 * d] = (uint16_t)o[4 * h + d];
-        if ((uint32_t)(2 * d + 1) < nvalid) q[2 * d + 1] = (uint16_t)(o[4 * h + d] >> 16);
-      }
-    }
-  }
-}
-
-// E5M2 dense decode of one chunk by one wave into registers: 16 elements per lane, o[d] holds
-// elements 4 d .. 4 d + 3.  Lanes 2p and 2p+1 share 12 plane bytes: the even lane loads the first
-// 8, the odd lane the last 4.
-template <bool FULL>
-__device__ inline void decode_chunk_e5m2(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane, uint32_t (&o)[4]) {
-  const uint64_t g0 = cbase + lane * 16;
-  const uint64_t sm_off = (cbase / 8) * 3 + (uint32_t)(lane >> 1) * 12;
-  const uint8_t* sm_src = a.comp + a.off_sm + sm_off;
-  const uint64_t sm_end = a256(a.sm_bytes);
-  uint32_t d0 = 0, d1 = 0;
-  u32x2 cd = u32x2{0u, 0u};
-  if (lane & 1) {
-    if (FULL || sm_off + 8 < sm_end) d0 = ld_stream(reinterpret_cast<const uint32_t*>(sm_src + 8));
-  } else if (FULL || sm_off + 4 < sm_end) {
-    const u32x2 v = ld_stream(reinterpret_cast<const u32x2*>(sm_src));   // 8 bytes below a multiple of 256: both in the stream
-    d0 = v.x;
-    d1 = v.y;
-  } else if (sm_off < sm_end) {
-    d0 = ld_stream(reinterpret_cast<const uint32_t*>(sm_src));
-  }
-  if (FULL || (g0 >> 1) < a256(a.code_bytes)) cd = ld_stream(reinterpret_cast<const u32x2*>(a.comp + a.off_code + (g0 >> 1)));
-  const uint32_t d1_dn = __builtin_amdgcn_update_dpp(0u, d1, 0xA0, 0xf, 0xf, false);   // quad_perm [0,0,2,2]: the even neighbour's second dword
-  // the lane's 48 plane bits
-  const uint32_t lo = (lane & 1) ? (d1_dn >> 16) | (d0 << 16) : d0;
-  const uint32_t hi = (lane & 1) ? d0 >> 16 : d1 & 0xffffu;
-  const uint32_t r[4] = {lo & 0xfffu, (lo >> 12) & 0xfffu, (lo >> 24) | ((hi & 0xfu) << 8), (hi >> 4) & 0xfffu};
-  const uint32_t cdw[2] = {cd.x, cd.y};
-#pragma unroll
-  for (int d = 0; d < 4; ++d) {
-    // two code bytes -> four exponents already in place (bits 2..6 of each byte)
-    const uint32_t c01 = (cdw[d >> 1] >> (16 * (d & 1))) & 0xffu, c23 = (cdw[d >> 1] >> (16 * (d & 1) + 8)) & 0xffu;
-    o[d] = unpack3_e5m2(r[d]) | tbl[c01] | (tbl[c23] << 16);
-  }
-}
-
-template <bool FULL>
-__device__ inline void store_chunk_e5m2(const DecompressArgs& a, uint64_t cbase, int lane, const uint32_t (&o)[4]) {
-  const uint64_t g0 = cbase + lane * 16;
-  uint32_t nvalid = 16;
-  if (!FULL) nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 16 ? a.n - g0 : 16);
-  if (FULL || nvalid == 16) {
-    st_stream(reinterpret_cast<u32x4*>(a.out + g0), u32x4{o[0], o[1], o[2], o[3]});
-  } else {
-    uint8_t* q = a.out + g0;
-#pragma unroll
-    for (int j = 0; j < 16; ++j)
-      if ((uint32_t)j < nvalid) q[j] = (uint8_t)(o[j >> 2] >> (8 * (j & 3)));
-  }
-}
-
-// in-register scatter correction: dword r of the owning lane gets (o & ~mask) | bits; r is
-// wave-uniform, so the choice of the register is a scalar branch
-template <int R>
-__device__ inline void patch_regs(uint32_t (&o)[R], uint32_t r, bool mine, uint32_t mask, uint32_t bits) {
-#pragma unroll
-  for (int q = 0; q < R; ++q)
-    if (r == (uint32_t)q && mine) o[q] = (o[q] & ~mask) | bits;
-}
-
-// the two formats as seen by the decompress kernel
-struct DBf16 {
-  struct Out { uint32_t o[8]; };
-  // table entry for a code byte: both exponents in place for one dword of output
-  __device__ static inline uint32_t table(int cb, const uint8_t* dec) { return ((uint32_t)dec[cb & 15] << 7) | ((uint32_t)dec[cb >> 4] << 23); }
-  __device__ static inline bool full(const DecompressArgs& a, uint64_t cbase) { return cbase + kChunk <= a.n; }
-  template <bool FULL>
-  __device__ static inline void decode(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane, Out& r) { decode_chunk_bf16<FULL>(a, tbl, cbase, lane, r.o); }
-  template <bool FULL>
-  __device__ static inline void store(const DecompressArgs& a, uint64_t cbase, int lane, const Out& r) { store_chunk_bf16<FULL>(a, cbase, lane, r.o); }
-  // the scatter correction of the element at chunk position pos (wave-uniform), in the registers of the lane that holds it
-  __device__ static inline bool patch_reg(Out& r, int lane, uint32_t pos, uint32_t val) {
-    const uint32_t q = pos & 511u, e = q & 7u, sh = 16u * (e & 1u);
-    patch_regs<8>(r.o, 4u * (pos >> 9) + (e >> 1), (uint32_t)lane == (q >> 3), 0x7f80u << sh, val << (7u + sh));
-    return true;
-  }
-  // the same on the tensor in memory: exponent field := val, sign and mantissa from the stream
-  __device__ static inline bool patch(const DecompressArgs& a, uint64_t i, uint32_t val) {
-    const uint32_t sa = a.comp[a.off_sm + i];
-    reinterpret_cast<uint16_t*>(a.out)[i] = (uint16_t)(((sa & 0x80u) << 8) | (val << 7) | (sa & 0x7fu));
-    return true;
-  }
-};
-struct DE5m2 {
-  struct Out { uint32_t o[4]; };
-  __device__ static inline uint32_t table(int cb, const uint8_t* dec) { return ((uint32_t)dec[cb & 15] << 2) | ((uint32_t)dec[cb >> 4] << 10); }
-  __device__ static inline bool full(const DecompressArgs& a, uint64_t cbase) { return cbase + kChunk < a.n; }
-  template <bool FULL>
-  __device__ static inline void decode(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane, Out& r) { decode_chunk_e5m2<FULL>(a, tbl, cbase, lane, r.o); }
-  template <bool FULL>
-  __device__ static inline void store(const DecompressArgs& a, uint64_t cbase, int lane, const Out& r) { store_chunk_e5m2<FULL>(a, cbase, lane, r.o); }
-  __device__ static inline bool patch_reg(Out& r, int lane, uint32_t pos, uint32_t val) {
-    if (val > 31u) return false;
-    const uint32_t e = pos & 15u, sh = 8u * (e & 3u);
-    patch_regs<4>(r.o, e >> 2, (uint32_t)lane == (pos >> 4), 0x7cu << sh, val << (2u + sh));
-    return true;
-  }
-  __device__ static inline bool patch(const DecompressArgs& a, uint64_t i, uint32_t val) {
-    if (val > 31u) return false;
-    const uint64_t bit = 3 * i;
-    const uint8_t* p = a.comp + a.off_sm + (bit >> 3);
-    uint32_t two = p[0];
-    if ((bit & 7) > 5) two |= (uint32_t)p[1] << 8;   // the field straddles a byte; the next byte is inside the plane
-    const uint32_t sa = (two >> (bit & 7)) & 7u;
-    a.out[i] = (uint8_t)(((sa & 4u) << 5) | (val << 2) | (sa & 3u));
-    return true;
-  }
-};
-
-constexpr uint32_t kRegPatchMax = 32;   // escapes of a chunk that are applied in registers, before the store
-
-// one workgroup: tile `tile` of the tensor described by a (4 waves x cpw chunks)
-template <typename F>
-__device__ inline void decompress_tile(const DecompressArgs& a, const uint8_t* dec, uint32_t tile, uint32_t* tbl) {
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const uint32_t* tab = reinterpret_cast<const uint32_t*>(a.comp + a.off_tab);
-  const uint32_t cpw = a.cpw;
-  const uint32_t wave_chunk0 = (tile * kWaves + wave) * cpw;
-  // first of all the loads everything else waits for: this wave's slice of the offset table (lane c
-  // <-> its chunk c, one entry more for the end) and M as the table states it
-  const uint32_t my_tab = (uint32_t)lane <= cpw && wave_chunk0 + lane <= a.n_chunks ? tab[wave_chunk0 + lane] : 0u;
-  uint32_t M = tab[a.n_chunks];
-  tbl[tid] = F::table(tid, dec);
-
-  // escapes are only trusted if their sections lie inside the stream
-  const uint64_t off_val = a.off_pos + a256(2ull * M);
-  const bool esc_ok = M <= a.n && off_val + M <= a.comp_bytes;
-  if (tile == 0 && tid == 0) {
-    decompress_check_header(a, dec, M);
-    if (!esc_ok) flag_bad(a);
-  }
-  if (!esc_ok) M = 0;
-  const uint16_t* pos_arr = reinterpret_cast<const uint16_t*>(a.comp + a.off_pos);
-  const uint8_t* val_arr = a.comp + off_val;
-  __syncthreads();
-
-  for (uint32_t c = 0; c < cpw; ++c) {
-    const uint32_t chunk = wave_chunk0 + c;
-    if (chunk >= a.n_chunks) break;
-    const uint64_t cbase = (uint64_t)chunk * kChunk;
-    const uint32_t lo = __builtin_amdgcn_readlane(my_tab, c), hi = __builtin_amdgcn_readlane(my_tab, c + 1);
-    const uint32_t clen = (uint32_t)(a.n - cbase < kChunk ? a.n - cbase : kChunk);
-    const bool esc_valid = hi >= lo && hi - lo <= clen && hi <= M;
-    const uint32_t cnt = esc_valid ? hi - lo : 0u;
-    if (!esc_valid && lane == 0) flag_bad(a);
-    // a few escapes (the usual case): their records are fetched while the planes are on their way,
-    // and applied to the decoded words in registers before the one store
-    const bool in_regs = cnt > 0 && cnt <= kRegPatchMax;
-    uint32_t pos = 0, val = 0;
-    if (in_regs && (uint32_t)lane < cnt) {
-      pos = pos_arr[lo + lane];
-      val = val_arr[lo + lane];
-    }
-    typename F::Out r;
-    const bool full = F::full(a, cbase);
-    if (full) F::template decode<true>(a, tbl, cbase, lane, r);
-    else F::template decode<false>(a, tbl, cbase, lane, r);
-    if (in_regs) {
-      for (uint32_t j = 0; j < cnt; ++j) {
-        const uint32_t p = __builtin_amdgcn_readlane(pos, j), v = __builtin_amdgcn_readlane(val, j);
-        if (p >= clen || !F::patch_reg(r, lane, p, v)) {
-          if (lane == 0) flag_bad(a);
-        }
-      }
-    }
-    if (full) F::template store<true>(a, cbase, lane, r);
-    else F::template store<false>(a, cbase, lane, r);
-    if (cnt > kRegPatchMax) {
-      // many escapes: sparse overwrite of the tensor in memory by the wave that wrote the chunk,
-      // once its dense stores have completed
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      for (uint32_t j = lo + lane; j < hi; j += 64) {
-        const uint32_t p = pos_arr[j];
-        const uint32_t v = val_arr[j];
-        if (p >= clen || !F::patch(a, cbase + p, v)) flag_bad(a);
-      }
-    }
-  }
-}
-
-template <typename F>
-__global__ __launch_bounds__(kThreads) void decompress_kernel(const DecompressArgs a) {
-  __shared__ uint32_t tbl[256];
-  decompress_tile<F>(a, a.dec, blockIdx.x, tbl);
-}
-
-// several streams in one launch: blockIdx.y picks the stream, blockIdx.x the tile
-struct DBatchItem {
-  const uint8_t* comp;
-  uint8_t* out;
-  uint64_t n, comp_bytes;
-};
-struct DecompressBatchArgs {
-  DBatchItem item[kBatchMax];
-  uint8_t dec_of[kBatchMax];
-  splitzip_sizes* sizes;   // nullable; one record, status bits sticky
-  uint32_t cpw, dtype;
-  uint8_t dec[kBatchLuts][16];
-};
-
-template <typename F>
-__global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const DecompressBatchArgs b) {
-  __shared__ uint32_t tbl[256];
-  const DBatchItem it = b.item[blockIdx.y];
-  const Layout L = make_layout(it.n, (int)b.dtype);
-  const uint32_t n_tiles = (uint32_t)((L.n_chunks + (uint64_t)kWaves * b.cpw - 1) / (kWaves * b.cpw));
-  if (blockIdx.x >= (n_tiles ? n_tiles : 1u)) return;
-  DecompressArgs a;
-  a.comp = it.comp;
-  a.out = it.out;
-  a.n = it.n;
-  a.comp_bytes = it.comp_bytes;
-  a.sizes = b.sizes;
-  a.off_tab = L.off_tab; a.off_sm = L.off_sm; a.off_code = L.off_code; a.off_pos = L.off_pos;
-  a.sm_bytes = L.sm_bytes; a.code_bytes = L.code_bytes;
-  a.n_chunks = (uint32_t)L.n_chunks;
-  a.n_tiles = n_tiles;
-  a.cpw = b.cpw;
-  a.dtype = b.dtype;
-  decompress_tile<F>(a, b.dec[b.dec_of[blockIdx.y]], blockIdx.x, tbl);   // a.dec stays unset: the table comes from the kernel arguments
-}
-
-// ---------------------------------------------------------------------------
-// small kernels
-// ---------------------------------------------------------------------------
-
-// Calibration histogram (section 3.3) of a device sample: exponent counts, added to hist[256].
-// Every workgroup counts into eight copies of the bins in LDS -- lane l uses copy l mod 8, which
-// keeps the lanes that meet on one of the few common exponents apart -- and adds its non-zero
-// totals to the global bins at the end.
-template <bool BF16>
-__global__ __launch_bounds__(1024) void histogram_kernel(const uint8_t* in, uint64_t n, uint64_t* hist) {
-  __shared__ uint32_t bins[8][256];
-  const int tid = threadIdx.x;
-  for (int i = tid; i < 8 * 256; i += 1024) (&bins[0][0])[i] = 0;
-  __syncthreads();
-  uint32_t* mine = bins[tid & 7];
-  const uint64_t bytes = n * (BF16 ? 2 : 1), nvec = bytes / 16;
-  const u32x4* v = reinterpret_cast<const u32x4*>(in);
-  for (uint64_t i = blockIdx.x * 1024ull + tid; i < nvec; i += (uint64_t)gridDim.x * 1024) {
-    const u32x4 q = ld_stream(v + i);
-    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-    for (int d = 0; d < 4; ++d) {
-      if (BF16) {
-        atomicAdd(&mine[(w[d] >> 7) & 0xffu], 1u);
-        atomicAdd(&mine[(w[d] >> 23) & 0xffu], 1u);
-      } else {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) atomicAdd(&mine[(w[d] >> (8 * j + 2)) & 31u], 1u);
-      }
-    }
-  }
-  // the words behind the last whole vector, by workgroup 0
-  if (blockIdx.x == 0) {
-    for (uint64_t i = nvec * 16 + (uint64_t)tid * (BF16 ? 2 : 1); i < bytes; i += 1024 * (BF16 ? 2 : 1)) {
-      const uint32_t e = BF16 ? ((uint32_t)(in[i] | (in[i + 1] << 8)) >> 7) & 0xffu : ((uint32_t)in[i] >> 2) & 31u;
-      atomicAdd(&mine[e], 1u);
-    }
-  }
-  __syncthreads();
-  if (tid < 256) {
-    uint64_t c = 0;
-#pragma unroll
-    for (int r = 0; r < 8; ++r) c += bins[r][tid];
-    if (c) atomicAdd(reinterpret_cast<unsigned long long*>(&hist[tid]), (unsigned long long)c);
-  }
-}
-
-__global__ void workspace_init_kernel(uint32_t* p, uint32_t nwords) {
-  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < nwords; i += gridDim.x * blockDim.x) p[i] = i == 0 ? 1u : 0u;
-}
-
-// Per step a workgroup reads four coalesced 4 KB runs and writes three: the codec's 4:3 traffic
-// without its arithmetic.
-__global__ __launch_bounds__(kThreads) void traffic_probe_kernel(const u32x4* src, uint64_t nread,
-                                                                  u32x4* dst, uint64_t nwrite) {
-  const uint64_t steps = (nread + 4 * kThreads - 1) / (4 * kThreads);
-  for (uint64_t s = blockIdx.x; s < steps; s += gridDim.x) {
-    u32x4 v[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const uint64_t idx = (4 * s + i) * kThreads + threadIdx.x;
-      v[i] = idx < nread ? ld_stream(src + idx) : u32x4{0u, 0u, 0u, 0u};
-    }
-    v[0].x ^= v[3].x; v[1].y ^= v[3].y; v[2].z ^= v[3].z; v[0].w ^= v[3].w;
-#pragma unroll
-    for (int i = 0; i < 3; ++i) {
-      const uint64_t idx = (3 * s + i) * kThreads + threadIdx.x;
-      if (idx < nwrite) st_stream(dst + idx, v[i]);
-    }
-  }
-}
+#include "common.hpp"
+#include "compress.hpp"
+#include "decompress.hpp"
+#include "aux_kernels.hpp"
 
 // ---------------------------------------------------------------------------
 // host side
