@@ -656,10 +656,10 @@ template <int T, typename F>
 __global__ __launch_bounds__(T) void compress_batch_kernel(const CompressBatchArgs a) {
   constexpr int NW = T / 64;
   __shared__ uint16_t lut[kBatchLuts][256];
-  __shared__ uint16_t stage_pk[2][NW][kStageCap];
-  __shared__ uint8_t stage_val[2][NW][kStageCap];
-  __shared__ uint32_t s_off[2][kMaxRange + 1];
-  __shared__ uint16_t s_wstart[2][kMaxRange];
+  __shared__ uint16_t stage_pk[3][NW][kStageCap];   // three sets: a wave may stage tensor i + 1 while another still writes out i - 1
+  __shared__ uint8_t stage_val[3][NW][kStageCap];
+  __shared__ uint32_t s_off[3][kMaxRange + 1];
+  __shared__ uint16_t s_wstart[3][kMaxRange];
   __shared__ u32x4 s_park[T];
   __shared__ uint32_t s_red[16];
   __shared__ uint32_t s_misc[4];
@@ -683,7 +683,7 @@ __global__ __launch_bounds__(T) void compress_batch_kernel(const CompressBatchAr
     const uint32_t i = grp + seq * n_groups;
     const bool have = i < a.n_items;
     if (!have && seq == 0) break;   // a group without tensors
-    const uint32_t set = seq & 1u;
+    const uint32_t set = seq % 3u;
     const RangeLds L{stage_pk[set][wave], stage_val[set][wave], s_off[set], s_wstart[set]};
     Planes P = Pprev;
     uint32_t r0 = 0, nb = 0, wave_count = 0;
@@ -756,13 +756,14 @@ __global__ __launch_bounds__(T) void compress_batch_kernel(const CompressBatchAr
     }
     __syncthreads();
     if (seq > 0 && s_misc[2] == 0) {
-      const uint32_t pset = set ^ 1u;
+      const uint32_t pset = (seq + 2u) % 3u;
       const RangeLds Lp{stage_pk[pset][wave], stage_val[pset][wave], s_off[pset], s_wstart[pset]};
       write_out<NW, F>(Pprev, lut[a.lut_of[prev_item]], park, Lp, prev_r0, prev_nb, prev_count, s_misc[0],
                        final_sink(Pprev, s_misc[1]), tid, wave, lane);
     }
     if (!have) break;
-    __syncthreads();   // the previous tensor's LDS set is free again, s_misc may be rewritten
+    // no barrier here: the next tensor is staged in the third LDS set, and s_misc / s_red are only
+    // rewritten behind the next barrier, which every wave reaches after its write-out
     Pprev = P;
     prev_count = wave_count;
     prev_r0 = r0;
