@@ -106,6 +106,21 @@ int splitzip_codebook_from_hist(const uint64_t hist[256], int dtype, splitzip_co
  * codebook") when done per call. */
 int splitzip_histogram(const void* d_sample, uint64_t n_elems, int dtype, uint64_t* d_hist, void* stream);
 
+/* A codebook that never leaves the device (calibration per call without a
+ * host round trip): splitzip_codebook_device ranks 256 device counts exactly
+ * as splitzip_codebook_from_hist does and writes the three tables into a
+ * splitzip_codebook in DEVICE memory (4-byte aligned); the _dcb calls are
+ * splitzip_compress / splitzip_decompress with such a codebook.  The tables
+ * are read by the kernels, so they cannot be checked by the host: a codebook
+ * that was not written by splitzip_codebook_device gives undefined streams
+ * (never out-of-bounds accesses).  All enqueued on `stream`. */
+int splitzip_codebook_device(const uint64_t* d_hist, int dtype, splitzip_codebook* d_cb, void* stream);
+int splitzip_compress_dcb(const void* d_in, uint64_t n_elems, int dtype, const splitzip_codebook* d_cb,
+                          void* d_out, size_t out_capacity, void* d_workspace, size_t workspace_bytes,
+                          splitzip_sizes* d_sizes, void* stream);
+int splitzip_decompress_dcb(const void* d_comp, size_t comp_bytes, uint64_t n_elems, int dtype,
+                            const splitzip_codebook* d_cb, void* d_out, splitzip_sizes* d_sizes, void* stream);
+
 /* Tables for a given list of 16 distinct exponents (code k = dec[k]); used to
  * restore a saved codebook.  INVALID_ARG on duplicates / out-of-range values. */
 int splitzip_codebook_from_dec(const uint8_t dec[16], int dtype, splitzip_codebook* out);

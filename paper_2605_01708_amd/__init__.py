@@ -14,16 +14,20 @@ from .binding import (  # noqa: F401
     Codebook,
     CompressBatch,
     DecompressBatch,
+    DeviceCodebook,
     SplitZipError,
     Workspace,
     calibrate,
+    codebook_device,
     codebook_from_dec,
     codebook_from_hist,
     compress,
     compress_batch,
     compress_bound,
+    compress_dcb,
     decompress,
     decompress_batch,
+    decompress_dcb,
     fixed_bytes,
     histogram,
     lib,

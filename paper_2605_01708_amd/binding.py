@@ -85,6 +85,12 @@ def lib():
         L.splitzip_codebook_from_hist.argtypes = [C.POINTER(C.c_uint64), i, cbp]
         L.splitzip_histogram.restype = i
         L.splitzip_histogram.argtypes = [vp, u64, i, vp, vp]
+        L.splitzip_codebook_device.restype = i
+        L.splitzip_codebook_device.argtypes = [vp, i, vp, vp]
+        L.splitzip_compress_dcb.restype = i
+        L.splitzip_compress_dcb.argtypes = [vp, u64, i, vp, vp, sz, vp, sz, vp, vp]
+        L.splitzip_decompress_dcb.restype = i
+        L.splitzip_decompress_dcb.argtypes = [vp, sz, u64, i, vp, vp, vp, vp]
         L.splitzip_compress_batch.restype = i
         L.splitzip_compress_batch.argtypes = [C.POINTER(_CItem), C.c_uint32, i, vp, sz, vp, vp]
         L.splitzip_decompress_batch.restype = i
@@ -165,6 +171,47 @@ def histogram(x: torch.Tensor, dtype: int, hist: torch.Tensor | None = None, str
         hist = torch.zeros(256, dtype=torch.int64, device=x.device)
     _check(lib().splitzip_histogram(x.data_ptr(), x.numel(), dtype, hist.data_ptr(), _stream_ptr(stream)), "splitzip_histogram")
     return hist
+
+
+class DeviceCodebook:
+    """A splitzip_codebook in device memory, written by splitzip_codebook_device."""
+
+    def __init__(self, dtype: int, device="cuda"):
+        self.dtype = dtype
+        self.buf = torch.zeros((C.sizeof(_CCodebook) + 7) // 8, dtype=torch.int64, device=device)
+
+    def to_host(self) -> Codebook:
+        """Copy of the tables on the host (synchronises)."""
+        raw = self.buf.cpu().numpy().tobytes()[: C.sizeof(_CCodebook)]
+        return Codebook(_CCodebook.from_buffer_copy(raw))
+
+
+def codebook_device(hist: torch.Tensor, dtype: int, out: DeviceCodebook | None = None, stream=None) -> DeviceCodebook:
+    """splitzip_codebook_device: the tables for 256 device counts, written to device memory."""
+    out = DeviceCodebook(dtype, hist.device) if out is None else out
+    _check(lib().splitzip_codebook_device(hist.data_ptr(), dtype, out.buf.data_ptr(), _stream_ptr(stream)), "splitzip_codebook_device")
+    return out
+
+
+def compress_dcb(x: torch.Tensor, d_cb: DeviceCodebook, out: torch.Tensor, workspace: "Workspace", sizes: torch.Tensor,
+                 stream=None, capacity: int | None = None) -> None:
+    """splitzip_compress_dcb: splitzip_compress with a codebook in device memory."""
+    if x.element_size() != _elem_size(d_cb.dtype) or not x.is_contiguous():
+        raise ValueError("x must be a contiguous tensor of raw words of the codebook's dtype")
+    cap = out.numel() * out.element_size() if capacity is None else capacity
+    _check(lib().splitzip_compress_dcb(x.data_ptr(), x.numel(), d_cb.dtype, d_cb.buf.data_ptr(), out.data_ptr(), cap,
+                                       workspace.buf.data_ptr(), workspace.nbytes, sizes.data_ptr(), _stream_ptr(stream)),
+           "splitzip_compress_dcb")
+
+
+def decompress_dcb(comp: torch.Tensor, comp_bytes: int, n_elems: int, d_cb: DeviceCodebook, out: torch.Tensor,
+                   sizes: torch.Tensor | None = None, stream=None) -> None:
+    """splitzip_decompress_dcb: splitzip_decompress with a codebook in device memory."""
+    if out.numel() < n_elems or out.element_size() != _elem_size(d_cb.dtype) or not out.is_contiguous():
+        raise ValueError("out must be a contiguous tensor of at least n_elems raw words")
+    _check(lib().splitzip_decompress_dcb(comp.data_ptr(), comp_bytes, n_elems, d_cb.dtype, d_cb.buf.data_ptr(), out.data_ptr(),
+                                         sizes.data_ptr() if sizes is not None else None, _stream_ptr(stream)),
+           "splitzip_decompress_dcb")
 
 
 def fixed_bytes(n: int, dtype: int) -> int:

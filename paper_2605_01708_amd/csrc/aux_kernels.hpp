@@ -50,6 +50,24 @@ __global__ __launch_bounds__(1024) void histogram_kernel(const uint8_t* in, uint
   }
 }
 
+// Section 3.3 on the device: the three tables from 256 exponent counts.  One workgroup; thread v
+// ranks exponent v by (count descending, exponent ascending) among the format's exponents, the 16
+// first ranks form the codebook.
+__global__ __launch_bounds__(256) void codebook_kernel(const uint64_t* hist, uint32_t n_values, uint32_t dtype,
+                                                       splitzip_codebook* cb) {
+  __shared__ uint64_t h[256];
+  const uint32_t v = threadIdx.x;
+  h[v] = v < n_values ? hist[v] : 0;
+  __syncthreads();
+  uint32_t rank = 0;
+  for (uint32_t u = 0; u < n_values; ++u) rank += (h[u] > h[v] || (h[u] == h[v] && u < v)) ? 1u : 0u;
+  const bool in = v < n_values && rank < 16;
+  cb->enc[v] = in ? (uint8_t)rank : (uint8_t)0;
+  cb->member[v] = in ? 1 : 0;
+  if (in) cb->dec[rank] = (uint8_t)v;
+  if (v == 0) cb->dtype = dtype;
+}
+
 __global__ void workspace_init_kernel(uint32_t* p, uint32_t nwords) {
   for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < nwords; i += gridDim.x * blockDim.x) p[i] = i == 0 ? 1u : 0u;
 }

@@ -40,6 +40,7 @@ struct CompressArgs {
   uint32_t seg_chunk0, seg_chunks;   // the chunks this launch covers
   uint32_t flags;        // kSegFirst | kSegLast
   uint32_t expect_wgs;   // workgroups whose counts are awaited (= the grid size)
+  const splitzip_codebook* d_cb;   // nullable: a codebook in device memory, used instead of dec / lut below
   uint8_t dec[16];
   uint16_t lut[256];     // exponent -> code | (non-member ? 0x100 : 0)   (the "marked" table of appendix A)
 };
@@ -545,7 +546,8 @@ __global__ __launch_bounds__(T) void compress_kernel(const CompressArgs a) {
   uint32_t* park = reinterpret_cast<uint32_t*>(&s_park[tid]);
   const RangeLds L{stage_pk[wave], stage_val[wave], s_off, s_wstart};
 
-  if (tid < 256) lut[tid] = a.lut[tid];
+  if (tid < 256) lut[tid] = a.d_cb ? (a.d_cb->member[tid] ? (uint16_t)a.d_cb->enc[tid] : (uint16_t)0x100u) : a.lut[tid];
+  const uint8_t* dec = a.d_cb ? a.d_cb->dec : a.dec;
   const uint32_t epoch = ld_agent(&a.ws_hdr[0]);
   const uint32_t base = (a.flags & kSegFirst) ? 0u : ld_agent(&a.ws_hdr[1]);
   const uint32_t err_before = b == 0 ? ld_agent(&a.ws_hdr[2]) : 0u;   // sticky flags of earlier launches
@@ -578,7 +580,7 @@ __global__ __launch_bounds__(T) void compress_kernel(const CompressArgs a) {
         st_agent(&a.ws_hdr[1], base + al);
         st_agent(&a.ws_hdr[2], single ? 0u : err);   // a call of several launches reports in its finishing launch
       }
-      if (single) compress_write_trailer(a.p, a.dec, a.sizes, base + al, err, lane);
+      if (single) compress_write_trailer(a.p, dec, a.sizes, base + al, err, lane);
     }
   } else if (wave == 1) {
     scan_range(s_off, nb, lane);   // meanwhile
@@ -791,7 +793,7 @@ __global__ __launch_bounds__(kThreads) void compress_finish_kernel(const Compres
       err = ld_agent(&a.ws_hdr[2]);
       st_agent(&a.ws_hdr[2], 0u);
     }
-    compress_write_trailer(a.p, a.dec, a.sizes, M, err, threadIdx.x);
+    compress_write_trailer(a.p, a.d_cb ? a.d_cb->dec : a.dec, a.sizes, M, err, threadIdx.x);
   }
 }
 

@@ -14,6 +14,7 @@ struct DecompressArgs {
   splitzip_sizes* sizes;   // nullable
   uint64_t off_tab, off_sm, off_code, off_pos, sm_bytes, code_bytes;
   uint32_t n_chunks, n_tiles, cpw, dtype;
+  const uint8_t* d_dec;    // nullable: the 16 decode entries in device memory, used instead of dec
   uint8_t dec[16];
 };
 
@@ -272,7 +273,7 @@ __device__ inline void decompress_tile(const DecompressArgs& a, const uint8_t* d
 template <typename F>
 __global__ __launch_bounds__(kThreads) void decompress_kernel(const DecompressArgs a) {
   __shared__ uint32_t tbl[256];
-  decompress_tile<F>(a, a.dec, blockIdx.x, tbl);
+  decompress_tile<F>(a, a.d_dec ? a.d_dec : a.dec, blockIdx.x, tbl);
 }
 
 // several streams in one launch: blockIdx.y picks the stream, blockIdx.x the tile

@@ -229,14 +229,19 @@ int splitzip_workspace_init(void* d_workspace, size_t workspace_bytes, void* str
   return hipGetLastError() == hipSuccess ? SPLITZIP_OK : SPLITZIP_ERR_HIP;
 }
 
-int splitzip_compress(const void* d_in, uint64_t n_elems, int dtype, const splitzip_codebook* cb,
-                      void* d_out, size_t out_capacity, void* d_workspace, size_t workspace_bytes,
-                      splitzip_sizes* d_sizes, void* stream) {
+}  // extern "C"
+
+namespace {
+
+// splitzip_compress with the codebook either on the host (cb) or in device memory (d_cb)
+int compress_impl(const void* d_in, uint64_t n_elems, int dtype, const splitzip_codebook* cb, const splitzip_codebook* d_cb,
+                  void* d_out, size_t out_capacity, void* d_workspace, size_t workspace_bytes, splitzip_sizes* d_sizes,
+                  void* stream) {
   if (!dtype_ok(dtype) || !d_out || !d_workspace || !d_sizes || (n_elems && !d_in)) return SPLITZIP_ERR_INVALID_ARG;
   if (!aligned16(d_in) || !aligned16(d_out) || !aligned16(d_workspace) ||
       (reinterpret_cast<uintptr_t>(d_sizes) & 7u))
     return SPLITZIP_ERR_INVALID_ARG;
-  if (!codebook_ok(cb, dtype)) return SPLITZIP_ERR_INVALID_ARG;
+  if (d_cb ? (reinterpret_cast<uintptr_t>(d_cb) & 3u) != 0 : !codebook_ok(cb, dtype)) return SPLITZIP_ERR_INVALID_ARG;
   if (n_elems >> 32) return SPLITZIP_ERR_UNSUPPORTED;
   if (out_capacity < splitzip_fixed_bytes(n_elems, dtype)) return SPLITZIP_ERR_CAPACITY;
   if (workspace_bytes < splitzip_workspace_bytes(n_elems, dtype)) return SPLITZIP_ERR_CAPACITY;
@@ -250,8 +255,11 @@ int splitzip_compress(const void* d_in, uint64_t n_elems, int dtype, const split
   a.state = reinterpret_cast<uint64_t*>(ws + kWsHeaderBytes);
   a.val_stage = ws + kWsHeaderBytes + kWsTableBytes;
   a.sizes = d_sizes;
-  memcpy(a.dec, cb->dec, 16);
-  for (unsigned v = 0; v < 256; ++v) a.lut[v] = cb->member[v] ? cb->enc[v] : 0x100u;   // indexed by the exponent
+  a.d_cb = d_cb;
+  if (!d_cb) {
+    memcpy(a.dec, cb->dec, 16);
+    for (unsigned v = 0; v < 256; ++v) a.lut[v] = cb->member[v] ? cb->enc[v] : 0x100u;   // indexed by the exponent
+  }
   static const int spin_env = env_int("SPLITZIP_SPIN_TICKS", 0);
   a.spin_ticks = spin_env ? (uint64_t)spin_env : kSpinTicks;
 
@@ -297,12 +305,13 @@ int splitzip_compress(const void* d_in, uint64_t n_elems, int dtype, const split
   return SPLITZIP_OK;
 }
 
-int splitzip_decompress(const void* d_comp, size_t comp_bytes, uint64_t n_elems, int dtype,
-                        const splitzip_codebook* cb, void* d_out, splitzip_sizes* d_sizes, void* stream) {
+// splitzip_decompress with the codebook either on the host (cb) or in device memory (d_cb)
+int decompress_impl(const void* d_comp, size_t comp_bytes, uint64_t n_elems, int dtype, const splitzip_codebook* cb,
+                    const splitzip_codebook* d_cb, void* d_out, splitzip_sizes* d_sizes, void* stream) {
   if (!dtype_ok(dtype) || !d_comp || (n_elems && !d_out)) return SPLITZIP_ERR_INVALID_ARG;
   if (!aligned16(d_comp) || !aligned16(d_out) || (reinterpret_cast<uintptr_t>(d_sizes) & 7u))
     return SPLITZIP_ERR_INVALID_ARG;
-  if (!codebook_ok(cb, dtype)) return SPLITZIP_ERR_INVALID_ARG;
+  if (d_cb ? (reinterpret_cast<uintptr_t>(d_cb) & 3u) != 0 : !codebook_ok(cb, dtype)) return SPLITZIP_ERR_INVALID_ARG;
   if (n_elems >> 32) return SPLITZIP_ERR_UNSUPPORTED;
   if (comp_bytes < splitzip_fixed_bytes(n_elems, dtype)) return SPLITZIP_ERR_CAPACITY;
 
@@ -323,12 +332,49 @@ int splitzip_decompress(const void* d_comp, size_t comp_bytes, uint64_t n_elems,
   a.n_chunks = (uint32_t)L.n_chunks;
   a.n_tiles = (uint32_t)((L.n_chunks + (uint64_t)kWaves * a.cpw - 1) / (kWaves * a.cpw));
   a.dtype = (uint32_t)dtype;
-  memcpy(a.dec, cb->dec, 16);
+  a.d_dec = d_cb ? d_cb->dec : nullptr;   // an address in device memory, not read here
+  if (!d_cb) memcpy(a.dec, cb->dec, 16);
 
   const unsigned grid = a.n_tiles ? a.n_tiles : 1u;
   if (dtype == SPLITZIP_BF16) hipLaunchKernelGGL(decompress_kernel<DBf16>, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
   else hipLaunchKernelGGL(decompress_kernel<DE5m2>, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
   return hipGetLastError() == hipSuccess ? SPLITZIP_OK : SPLITZIP_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int splitzip_compress(const void* d_in, uint64_t n_elems, int dtype, const splitzip_codebook* cb,
+                      void* d_out, size_t out_capacity, void* d_workspace, size_t workspace_bytes,
+                      splitzip_sizes* d_sizes, void* stream) {
+  return compress_impl(d_in, n_elems, dtype, cb, nullptr, d_out, out_capacity, d_workspace, workspace_bytes, d_sizes, stream);
+}
+
+int splitzip_decompress(const void* d_comp, size_t comp_bytes, uint64_t n_elems, int dtype,
+                        const splitzip_codebook* cb, void* d_out, splitzip_sizes* d_sizes, void* stream) {
+  return decompress_impl(d_comp, comp_bytes, n_elems, dtype, cb, nullptr, d_out, d_sizes, stream);
+}
+
+int splitzip_codebook_device(const uint64_t* d_hist, int dtype, splitzip_codebook* d_cb, void* stream) {
+  if (!dtype_ok(dtype) || !d_hist || !d_cb || (reinterpret_cast<uintptr_t>(d_hist) & 7u) || (reinterpret_cast<uintptr_t>(d_cb) & 3u))
+    return SPLITZIP_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(codebook_kernel, dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream), d_hist, exp_values(dtype),
+                     (uint32_t)dtype, d_cb);
+  return hipGetLastError() == hipSuccess ? SPLITZIP_OK : SPLITZIP_ERR_HIP;
+}
+
+int splitzip_compress_dcb(const void* d_in, uint64_t n_elems, int dtype, const splitzip_codebook* d_cb,
+                          void* d_out, size_t out_capacity, void* d_workspace, size_t workspace_bytes,
+                          splitzip_sizes* d_sizes, void* stream) {
+  if (!d_cb) return SPLITZIP_ERR_INVALID_ARG;
+  return compress_impl(d_in, n_elems, dtype, nullptr, d_cb, d_out, out_capacity, d_workspace, workspace_bytes, d_sizes, stream);
+}
+
+int splitzip_decompress_dcb(const void* d_comp, size_t comp_bytes, uint64_t n_elems, int dtype,
+                            const splitzip_codebook* d_cb, void* d_out, splitzip_sizes* d_sizes, void* stream) {
+  if (!d_cb) return SPLITZIP_ERR_INVALID_ARG;
+  return decompress_impl(d_comp, comp_bytes, n_elems, dtype, nullptr, d_cb, d_out, d_sizes, stream);
 }
 
 int splitzip_compress_batch(const splitzip_item* items, uint32_t n_items, int dtype, void* d_workspace,

@@ -28,7 +28,8 @@ def test_library_exports_every_declared_symbol():
             "splitzip_fixed_bytes", "splitzip_total_bytes", "splitzip_compress_bound",
             "splitzip_workspace_bytes", "splitzip_codebook_from_dec", "splitzip_strerror",
             "splitzip_version", "splitzip_traffic_probe", "splitzip_compress_batch",
-            "splitzip_decompress_batch", "splitzip_histogram", "splitzip_codebook_from_hist"} <= set(names)
+            "splitzip_decompress_batch", "splitzip_histogram", "splitzip_codebook_from_hist",
+            "splitzip_codebook_device", "splitzip_compress_dcb", "splitzip_decompress_dcb"} <= set(names)
     L = C.CDLL(sz.lib_path())
     for n in names:
         assert hasattr(L, n), n
@@ -172,5 +173,13 @@ def test_argument_validation_without_gpu():
     assert L.splitzip_decompress_batch(ditems, 2, sz.BF16, None, None) == -1
     assert L.splitzip_decompress_batch(None, 2, sz.BF16, None, None) == -1
     assert L.splitzip_decompress_batch(ditems, 0, sz.BF16, None, None) == 0
+    # device-codebook calls: the codebook pointer is all the host can check
+    assert L.splitzip_compress_dcb(base, n, sz.BF16, None, base + 1024, 1 << 20, base + 2048, 1 << 20, base + 3072, None) == -1
+    assert L.splitzip_compress_dcb(base, n, sz.BF16, base + 512 + 2, base + 1024, 1 << 20, base + 2048, 1 << 20, base + 3072, None) == -1
+    assert L.splitzip_compress_dcb(base, n, sz.BF16, base + 512, base + 1024, 16, base + 2048, 1 << 20, base + 3072, None) == -3
+    assert L.splitzip_decompress_dcb(base, 1 << 20, n, sz.BF16, None, base + 1024, None, None) == -1
+    assert L.splitzip_decompress_dcb(base, 16, n, sz.BF16, base + 512, base + 1024, None, None) == -3
+    assert L.splitzip_codebook_device(None, sz.BF16, base, None) == -1
+    assert L.splitzip_codebook_device(base, 7, base + 512, None) == -1
     assert L.splitzip_workspace_init(None, 1024, None) == -1
     assert L.splitzip_traffic_probe(None, 16, base, 16, None) == -1

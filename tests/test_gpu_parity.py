@@ -392,6 +392,43 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
         assert sz.read_sizes(rec1) == (ref2.size, mm2, 0)
 
 
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_codebook_that_never_leaves_the_device(dtype):
+    """device histogram -> device ranking -> compress / decompress with the device codebook: tables, stream and
+    tensor are those of the oracle calibrated on the same sample (ties and unseen exponents included)"""
+    n = 200 * 1024 + 321
+    x = synth(dtype, 201, 50)[:n].copy()
+    x[:: 777] = 0
+    sample = x[: 40000].copy()
+    sample[:5] = (0x7F80 if dtype == sz.BF16 else 0x7C)            # a rare exponent with a small count
+    ref_cb = oracle.calibrate(sample, DT[dtype])
+    hist = sz.histogram(words_tensor(sample), dtype)
+    dcb = sz.codebook_device(hist, dtype)
+    torch.cuda.synchronize()
+    host = dcb.to_host()
+    assert (host.dec, host.enc, host.member, host.dtype) == (ref_cb.dec.tolist(), ref_cb.enc.tolist(), ref_cb.member.tolist(), dtype)
+    # a histogram with ties and fewer than 16 exponents seen
+    h = torch.zeros(256, dtype=torch.int64)
+    h[20] = h[9] = h[11] = 5
+    h[15] = 9
+    tied = sz.codebook_device(h.cuda(), dtype).to_host()
+    assert tied.dec == sz.codebook_from_hist(h, dtype).dec == [15, 9, 11, 20, 0, 1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 13]
+    # compress and decompress with it
+    ref, m = oracle.compress(x, ref_cb)
+    g = Gpu(n, dtype)
+    g.out.fill_(POISON)
+    xd = words_tensor(x)
+    sz.compress_dcb(xd, dcb, g.out, g.ws, g.sizes)
+    torch.cuda.synchronize()
+    assert sz.read_sizes(g.sizes) == (ref.size, m, 0)
+    assert np.array_equal(g.out[: ref.size].cpu().numpy(), ref), "stream differs from the oracle's"
+    y = torch.zeros_like(xd)
+    st = sz.new_sizes()
+    sz.decompress_dcb(g.out, ref.size, n, dcb, y, st)
+    torch.cuda.synchronize()
+    assert sz.read_sizes(st)[2] == 0 and torch.equal(y, xd)
+
+
 def run_env_case(case, **env):
     import os
     import subprocess
