@@ -191,8 +191,8 @@ __device__ inline uint32_t process_chunk_bf16(const Planes& a, const uint16_t* l
 // a of the four bytes of w, packed LSB first into 12 bits
 __device__ inline uint32_t pack3_e5m2(uint32_t w) {
   const uint32_t t = ((w >> 5) & 0x04040404u) | (w & 0x03030303u);
-  const uint32_t u = (t | (t >> 5)) & 0x003f003fu;
-  return (u | (u >> 10)) & 0xfffu;
+  const uint32_t x = t + (t << 5);   // bytes 0|1 meet in bits 5..10, bytes 2|3 in bits 21..26; no field overlaps another
+  return ((x >> 5) & 0x3fu) | ((x >> 15) & 0xfc0u);
 }
 // inverse: 12 bits -> the sign and mantissa bits of four bytes, exponent field zero
 __device__ inline uint32_t unpack3_e5m2(uint32_t r) {
@@ -261,30 +261,25 @@ __device__ inline uint32_t process_chunk_e5m2(const Planes& a, const uint16_t* l
   }
   if (STORE) {
     // plane bytes of this lane pair: [12 p, 12 p + 12) of the chunk's 384
-    const uint32_t lo_up = __builtin_amdgcn_update_dpp(0u, lo, 0xF5, 0xf, 0xf, false);   // quad_perm [1,1,3,3]: the odd neighbour's lo
+    // quad_perm [1,1,3,3]: the odd neighbour's bits
+    const uint32_t lo_up = __builtin_amdgcn_update_dpp(0u, lo, 0xF5, 0xf, 0xf, false);
+    const uint32_t hi_up = __builtin_amdgcn_update_dpp(0u, hi, 0xF5, 0xf, 0xf, false);
     const uint64_t sm_off = (cbase / 8) * 3 + (uint32_t)(lane >> 1) * 12;
     uint8_t* sm_dst = a.out + a.off_sm + (cbase / 8) * 3 + (uint32_t)(lane >> 1) * 12;   // uniform pointer + lane offset
-    uint32_t d0, d1;
-    if (lane & 1) {
-      d0 = (lo >> 16) | (hi << 16);
-      d1 = 0;
-    } else {
-      d0 = lo;
-      d1 = (hi & 0xffffu) | (lo_up << 16);
-    }
+    // the pair's 12 bytes, all in the even lane
+    const uint32_t d0 = lo, d1 = (hi & 0xffffu) | (lo_up << 16), d2 = (lo_up >> 16) | (hi_up << 16);
     if (FULL) {
-      if (lane & 1) st_stream(reinterpret_cast<uint32_t*>(sm_dst + 8), d0);
-      else st_stream(reinterpret_cast<u32x2*>(sm_dst), u32x2{d0, d1});
+      // even lanes only: one instruction writes the chunk's 384 bytes back to back
+      if (!(lane & 1)) st_stream(reinterpret_cast<u32x3*>(sm_dst), u32x3{d0, d1, d2});
       st_stream(reinterpret_cast<u32x2*>(a.out + a.off_code + (cbase >> 1)) + (uint32_t)lane, u32x2{code[0], code[1]});
     } else {
       // dword by dword up to the padded end of each plane; the pad can reach 128 bytes past the
       // chunk's own 384 plane bytes
       const uint64_t sm_end = a256(a.sm_bytes);
-      if (lane & 1) {
-        if (sm_off + 8 < sm_end) *reinterpret_cast<uint32_t*>(sm_dst + 8) = d0;
-      } else {
+      if (!(lane & 1)) {
         if (sm_off < sm_end) *reinterpret_cast<uint32_t*>(sm_dst) = d0;
         if (sm_off + 4 < sm_end) *reinterpret_cast<uint32_t*>(sm_dst + 4) = d1;
+        if (sm_off + 8 < sm_end) *reinterpret_cast<uint32_t*>(sm_dst + 8) = d2;
       }
       const uint64_t past = (cbase / 8) * 3 + 384 + 4 * (uint32_t)lane;
       if (lane < 32 && past < sm_end) *reinterpret_cast<uint32_t*>(a.out + a.off_sm + past) = 0;
@@ -317,6 +312,7 @@ __device__ inline uint32_t process_chunk_e5m2(const Planes& a, const uint16_t* l
 // the two formats as seen by the compress kernel
 struct Bf16 {
   struct Regs { uint32_t w[2][4]; };
+  static constexpr uint32_t kPerStep = 2;   // chunks (2 KB each) a wave takes per step of the dense pass
   // a chunk goes the fast way if it is complete (then nothing of a pad is its business: N is a multiple of 1024 there)
   __device__ static inline bool full(const Planes& a, uint64_t cbase) { return cbase + kChunk <= a.n; }
   template <bool FULL>
@@ -329,6 +325,7 @@ struct Bf16 {
 };
 struct E5m2 {
   struct Regs { uint32_t w[4]; };
+  static constexpr uint32_t kPerStep = 1;   // 1 KB each: a second chunk per step costs more in registers and code than it hides
   // the tensor's last chunk always goes the careful way: 384 plane bytes per chunk leave a pad behind an odd chunk count
   __device__ static inline bool full(const Planes& a, uint64_t cbase) { return cbase + kChunk < a.n; }
   template <bool FULL>
@@ -398,37 +395,51 @@ struct NoHook {
   __device__ inline void operator()() const {}
 };
 
-// dense pass of one wave over its chunks of the range; the next chunk's loads are issued before
-// this chunk is worked on.  `mid` is called once, half way through (not at all by a wave without
-// chunks).  Returns the wave's escape count.
+// dense pass of one wave over its chunks of the range, F::kPerStep of them per step; the loads of
+// the next step are issued before this step's chunks are worked on (what a wave has in flight at
+// that point is what keeps the memory system busy: 2 KB per wave for either format).  `mid` is
+// called once, half way through (not at all by a wave without chunks).  Returns the wave's
+// escape count.
 template <int NW, typename F, typename Hook>
 __device__ inline uint32_t dense_pass(const Planes& P, const uint16_t* lut, uint32_t* park, const RangeLds& L,
                                       uint32_t r0, uint32_t nb, int wave, int lane, Hook& mid) {
+  constexpr uint32_t S = F::kPerStep;
   uint32_t wave_count = 0;
-  const uint32_t mid_it = nb > (uint32_t)wave ? ((nb - wave + NW - 1) / NW) / 2 : 0u;
-  typename F::Regs w, nx;
-  if ((uint32_t)wave < nb) {
-    const uint64_t cbase = (uint64_t)(r0 + wave) * kChunk;
-    if (F::full(P, cbase)) F::template load<true>(P, cbase, lane, w);
-    else F::template load<false>(P, cbase, lane, w);
-  }
-  for (uint32_t k = wave, it = 0; k < nb; k += NW, ++it) {
-    const uint64_t cbase = (uint64_t)(r0 + k) * kChunk;
-    if (k + NW < nb) {
-      const uint64_t nbase = cbase + (uint64_t)NW * kChunk;
-      if (F::full(P, nbase)) F::template load<true>(P, nbase, lane, nx);
-      else F::template load<false>(P, nbase, lane, nx);
+  const uint32_t mine = nb > (uint32_t)wave ? (nb - wave + NW - 1) / NW : 0u;   // chunks of this wave
+  const uint32_t mid_it = mine / 2;
+  typename F::Regs w[S], nx[S];
+  // the wave's it-th chunk into r (nothing if it has no such chunk)
+  auto fetch = [&](uint32_t it, typename F::Regs& r) {
+    if (it < mine) {
+      const uint64_t cbase = (uint64_t)(r0 + wave + it * NW) * kChunk;
+      if (F::full(P, cbase)) F::template load<true>(P, cbase, lane, r);
+      else F::template load<false>(P, cbase, lane, r);
     }
-    if (it == mid_it) mid();
-    const LdsSink lds{L.stage_pk, L.stage_val, it << 10};
-    const uint32_t cnt = F::full(P, cbase) ? F::template process<true, true>(P, lut, park, cbase, lane, w, wave_count, lds)
-                                           : F::template process<false, true>(P, lut, park, cbase, lane, w, wave_count, lds);
-    if (lane == 0) {
-      L.s_off[k] = cnt;
-      L.s_wstart[k] = (uint16_t)(wave_count < 0xffffu ? wave_count : 0xffffu);
+  };
+#pragma unroll
+  for (uint32_t s = 0; s < S; ++s) fetch(s, w[s]);
+  for (uint32_t it0 = 0; it0 < mine; it0 += S) {
+#pragma unroll
+    for (uint32_t s = 0; s < S; ++s) fetch(it0 + S + s, nx[s]);
+#pragma unroll
+    for (uint32_t s = 0; s < S; ++s) {
+      const uint32_t it = it0 + s;
+      if (it < mine) {
+        const uint32_t k = wave + it * NW;
+        const uint64_t cbase = (uint64_t)(r0 + k) * kChunk;
+        if (it == mid_it) mid();
+        const LdsSink lds{L.stage_pk, L.stage_val, it << 10};
+        const uint32_t cnt = F::full(P, cbase) ? F::template process<true, true>(P, lut, park, cbase, lane, w[s], wave_count, lds)
+                                               : F::template process<false, true>(P, lut, park, cbase, lane, w[s], wave_count, lds);
+        if (lane == 0) {
+          L.s_off[k] = cnt;
+          L.s_wstart[k] = (uint16_t)(wave_count < 0xffffu ? wave_count : 0xffffu);
+        }
+        wave_count += cnt;
+      }
     }
-    wave_count += cnt;
-    w = nx;
+#pragma unroll
+    for (uint32_t s = 0; s < S; ++s) w[s] = nx[s];
   }
   return wave_count;
 }
