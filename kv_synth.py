@@ -57,6 +57,12 @@ def kv_e5m2(tokens: int, seed: int, layer: int = 0, kind: str = "K", device="cpu
     return kv_values(tokens, seed, layer, kind, device).to(torch.float8_e5m2).view(torch.uint8).reshape(-1)
 
 
+def kv_e4m3(tokens: int, seed: int, layer: int = 0, kind: str = "K", device="cpu") -> torch.Tensor:
+    """FP8 E4M3 KV tensor as flat uint8 words (round to nearest even of the same law; E4M3 has no
+    infinities and the law stays far below its largest finite value, 448)."""
+    return kv_values(tokens, seed, layer, kind, device).to(torch.float8_e4m3fn).view(torch.uint8).reshape(-1)
+
+
 def kv_bf16_outliers(tokens: int, seed: int, layer: int = 0, device="cpu",
                      p_outlier: float = 0.005, p_zero: float = 0.001) -> torch.Tensor:
     """Escape-stress tensor: the base law, with a fraction p_outlier of the

@@ -446,6 +446,18 @@ def test_tensor_that_takes_several_launches():
     run_env_case("several_launches", SPLITZIP_COMPRESS_MAX_WGS=4)
 
 
+def test_tensor_beyond_one_launch_at_full_width():
+    """307 M BF16 elements (586 MiB, ragged): at the default grid one launch reaches 64 Mi elements, so this
+    takes five segment launches and the finishing one; the offset table alone is 1.2 MB"""
+    x_dev = kv_synth.kv_bf16(300007, 5, 9, "V", device="cuda")
+    x = kv_synth.to_numpy_words(x_dev)[:-517].copy()
+    del x_dev
+    torch.cuda.empty_cache()
+    g = Gpu(x.size, sz.BF16)
+    total, m = check_parity(g, x, calibrated(sz.BF16, kind="V"), "large")
+    print(f"large: n={x.size} eps={m / x.size:.5f} ratio={2 * x.size / total:.4f}", flush=True)
+
+
 def test_exchange_that_never_completes_is_reported():
     """the wait between workgroups is bounded: forced from the host, it ends with STATUS_INTERNAL, not a hang"""
     run_env_case("exchange_timeout", SPLITZIP_TEST_AWAIT_EXTRA_WGS=1, SPLITZIP_SPIN_TICKS=20000)
