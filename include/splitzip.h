@@ -50,7 +50,9 @@ extern "C" {
 
 typedef enum {
   SPLITZIP_BF16 = 0,     /* 16-bit words: 1 sign, 8 exponent, 7 mantissa bits */
-  SPLITZIP_FP8_E5M2 = 1  /* 8-bit words: 1 sign, 5 exponent, 2 mantissa bits (paper appendix "SplitZip on FP8") */
+  SPLITZIP_FP8_E5M2 = 1, /* 8-bit words: 1 sign, 5 exponent, 2 mantissa bits (paper appendix "SplitZip on FP8") */
+  SPLITZIP_FP8_E4M3 = 2  /* 8-bit words: 1 sign, 4 exponent, 3 mantissa bits; accepted by the splitzip_variant_* calls only
+                            (a 4-bit code cannot shrink a 4-bit exponent, same appendix) */
 } splitzip_dtype;
 
 typedef enum {
@@ -221,6 +223,78 @@ int splitzip_decompress_batch(const splitzip_ditem* items, uint32_t n_items, int
  * rounded down to a multiple of 16. */
 int splitzip_traffic_probe(const void* d_src, size_t read_bytes, void* d_dst, size_t write_bytes,
                            void* stream);
+
+/* ---- Format variants of the paper's ablations --------------------------------
+ *
+ * The same codec with its knobs turned the way the ablations turn them
+ * (sections "Ablation on Top-k Exponent Coding" and "Ablation on
+ * Escape-Position Metadata", appendices "Ablation on Chunk Size" and
+ * "SplitZip on FP8"): 3-bit codes over a top-8 codebook, a top-15 codebook
+ * with the last 4-bit code as an escape sentinel and no stored positions,
+ * 256-element chunks with 8-bit positions, 32-bit absolute positions without
+ * chunks, and E4M3 words.  These calls exist to measure those formats beside
+ * the main one on the same device; they run through one generic set of kernels
+ * (dense pass with per-chunk counts, scan, escape pass; dense decode with the
+ * correction applied in LDS) that is NOT the tuned path of splitzip_compress
+ * and splitzip_decompress.  The main format is one of the variants, so all of
+ * them can be compared through the same kernels.
+ *
+ * Version-2 stream: as the layout at the top of this file, with
+ *   header     u16 version 2, u8 code bits, u32 chunk elements (0 in the
+ *              absolute mode), and in place of the u32 0: u8 escape mode,
+ *              u8 k, u16 0; dec[] slots >= k are 0
+ *   chunk_off  4(C+1) B with C = ceil(N / chunk); absent in the absolute mode
+ *   sm plane   ceil(N sb / 8) B, sb = 8, 3, 4 bits for BF16, E5M2, E4M3
+ *   code plane ceil(N cb / 8) B; both planes are LSB-first bit streams
+ *   esc_pos    u16[M] (chunk > 256) or u8[M]; nothing in the sentinel mode;
+ *              u32[M] element indices in the absolute mode
+ *   esc_val    u8[M]
+ * With (BF16 or E5M2, 4, 16, SPLITZIP_ESC_POS, 1024) every byte behind the
+ * header equals the main format's stream. */
+typedef enum {
+  SPLITZIP_ESC_POS = 0,      /* chunk-relative positions + exponents (the main format's way) */
+  SPLITZIP_ESC_SENTINEL = 1, /* the all-ones code marks an escape; exponents only, in element order */
+  SPLITZIP_ESC_ABS32 = 2     /* 32-bit element indices + exponents, no chunks and no offset table */
+} splitzip_escape_mode;
+
+typedef struct {
+  uint32_t dtype;       /* splitzip_dtype */
+  uint32_t code_bits;   /* 3 or 4 */
+  uint32_t k;           /* codebook entries in use: 1 .. 2^code_bits (one less in the sentinel mode) */
+  uint32_t escape_mode; /* splitzip_escape_mode */
+  uint32_t chunk_elems; /* 256 or 1024; ignored in the absolute mode */
+} splitzip_variant;
+
+/* 1 if the library can run this variant, else 0 */
+int splitzip_variant_supported(const splitzip_variant* v);
+
+/* Sizes as for the main format (0 for an unsupported variant or n_elems >= 2^32). */
+size_t splitzip_variant_total_bytes(uint64_t n_elems, uint64_t n_escapes, const splitzip_variant* v);
+size_t splitzip_variant_compress_bound(uint64_t n_elems, const splitzip_variant* v);
+/* Device scratch of one compress call: per-chunk counts and their offsets.  No initialisation needed. */
+size_t splitzip_variant_workspace_bytes(uint64_t n_elems, const splitzip_variant* v);
+
+/* Section 3.3 with v->k entries: counts the exponents of a HOST sample and
+ * ranks them as splitzip_calibrate does; the first k of that ranking form the
+ * codebook (out->dec[k..15] = 0, only those k are members).  hist_out as for
+ * splitzip_calibrate (E4M3 uses the first 16 bins). */
+int splitzip_variant_calibrate(const void* h_sample, uint64_t n_elems, const splitzip_variant* v,
+                               splitzip_codebook* out, uint64_t* hist_out);
+/* The same from the first k entries of a decoding table. */
+int splitzip_variant_codebook_from_dec(const uint8_t* dec, const splitzip_variant* v, splitzip_codebook* out);
+
+/* Compress / decompress in the variant's format.  Arguments, alignment rules,
+ * the sizes record (total_bytes, n_escapes, status; OVERFLOW and BAD_STREAM as
+ * for the main calls) and the error codes are those of splitzip_compress and
+ * splitzip_decompress; d_workspace needs splitzip_variant_workspace_bytes and
+ * 16-byte alignment.  Three kernel launches per compress call (four in the
+ * absolute mode), one per decompress call (two in the absolute mode), all on
+ * `stream`. */
+int splitzip_variant_compress(const void* d_in, uint64_t n_elems, const splitzip_variant* v,
+                              const splitzip_codebook* cb, void* d_out, size_t out_capacity, void* d_workspace,
+                              size_t workspace_bytes, splitzip_sizes* d_sizes, void* stream);
+int splitzip_variant_decompress(const void* d_comp, size_t comp_bytes, uint64_t n_elems, const splitzip_variant* v,
+                                const splitzip_codebook* cb, void* d_out, splitzip_sizes* d_sizes, void* stream);
 
 const char* splitzip_strerror(int err);
 int splitzip_version(void);

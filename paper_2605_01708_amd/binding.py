@@ -10,6 +10,8 @@ import torch
 
 BF16 = 0
 FP8_E5M2 = 1
+FP8_E4M3 = 2   # accepted by the variant_* calls only
+ESC_POS, ESC_SENTINEL, ESC_ABS32 = 0, 1, 2
 
 STATUS_OVERFLOW = 1
 STATUS_BAD_STREAM = 2
@@ -46,6 +48,16 @@ class _CItem(C.Structure):
 class _CDItem(C.Structure):
     _fields_ = [("d_comp", C.c_void_p), ("comp_bytes", C.c_size_t), ("n_elems", C.c_uint64), ("d_out", C.c_void_p),
                 ("cb", C.POINTER(_CCodebook))]
+
+
+class Variant(C.Structure):
+    """splitzip_variant: one of the formats of the paper's ablations"""
+    _fields_ = [("dtype", C.c_uint32), ("code_bits", C.c_uint32), ("k", C.c_uint32), ("escape_mode", C.c_uint32),
+                ("chunk_elems", C.c_uint32)]
+
+    def __repr__(self):
+        return (f"Variant(dtype={self.dtype}, code_bits={self.code_bits}, k={self.k}, "
+                f"escape_mode={self.escape_mode}, chunk_elems={self.chunk_elems})")
 
 
 _lib = None
@@ -97,6 +109,22 @@ def lib():
         L.splitzip_decompress_batch.argtypes = [C.POINTER(_CDItem), C.c_uint32, i, vp, vp]
         L.splitzip_traffic_probe.restype = i
         L.splitzip_traffic_probe.argtypes = [vp, sz, vp, sz, vp]
+        vrp = C.POINTER(Variant)
+        L.splitzip_variant_supported.restype = i
+        L.splitzip_variant_supported.argtypes = [vrp]
+        L.splitzip_variant_total_bytes.restype = sz
+        L.splitzip_variant_total_bytes.argtypes = [u64, u64, vrp]
+        for f in (L.splitzip_variant_compress_bound, L.splitzip_variant_workspace_bytes):
+            f.restype = sz
+            f.argtypes = [u64, vrp]
+        L.splitzip_variant_calibrate.restype = i
+        L.splitzip_variant_calibrate.argtypes = [vp, u64, vrp, cbp, C.POINTER(C.c_uint64)]
+        L.splitzip_variant_codebook_from_dec.restype = i
+        L.splitzip_variant_codebook_from_dec.argtypes = [C.POINTER(C.c_uint8), vrp, cbp]
+        L.splitzip_variant_compress.restype = i
+        L.splitzip_variant_compress.argtypes = [vp, u64, vrp, cbp, vp, sz, vp, sz, vp, vp]
+        L.splitzip_variant_decompress.restype = i
+        L.splitzip_variant_decompress.argtypes = [vp, sz, u64, vrp, cbp, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -345,3 +373,67 @@ def decompress_batch(comps, comp_bytes, n_elems, cbs, outs, sizes: torch.Tensor 
 def traffic_probe(src: torch.Tensor, read_bytes: int, dst: torch.Tensor, write_bytes: int, stream=None) -> None:
     _check(lib().splitzip_traffic_probe(src.data_ptr(), read_bytes, dst.data_ptr(), write_bytes,
                                         _stream_ptr(stream)), "splitzip_traffic_probe")
+
+
+# ---- format variants of the ablations -----------------------------------------------------------
+
+def variant(dtype: int, code_bits: int = 4, k: int = 16, escape_mode: int = 0, chunk_elems: int = 1024) -> Variant:
+    return Variant(dtype, code_bits, k, escape_mode, chunk_elems)
+
+
+def variant_supported(v: Variant) -> bool:
+    return bool(lib().splitzip_variant_supported(C.byref(v)))
+
+
+def variant_total_bytes(n: int, m: int, v: Variant) -> int:
+    return int(lib().splitzip_variant_total_bytes(n, m, C.byref(v)))
+
+
+def variant_compress_bound(n: int, v: Variant) -> int:
+    return int(lib().splitzip_variant_compress_bound(n, C.byref(v)))
+
+
+def variant_workspace_bytes(n: int, v: Variant) -> int:
+    return int(lib().splitzip_variant_workspace_bytes(n, C.byref(v)))
+
+
+def variant_calibrate(sample: torch.Tensor, v: Variant, return_hist: bool = False):
+    """splitzip_variant_calibrate on a HOST tensor of raw words."""
+    if sample.device.type != "cpu":
+        raise ValueError("calibration runs on the host: pass a CPU tensor")
+    s = sample.contiguous()
+    if s.element_size() != _elem_size(v.dtype):
+        raise ValueError("sample element size does not match dtype")
+    cb = _CCodebook()
+    hist = (C.c_uint64 * 256)()
+    _check(lib().splitzip_variant_calibrate(s.data_ptr(), s.numel(), C.byref(v), C.byref(cb), hist),
+           "splitzip_variant_calibrate")
+    return (Codebook(cb), list(hist)) if return_hist else Codebook(cb)
+
+
+def variant_codebook_from_dec(dec, v: Variant) -> Codebook:
+    vals = [int(x) for x in dec][:16]
+    arr = (C.c_uint8 * 16)(*(vals + [0] * (16 - len(vals))))
+    cb = _CCodebook()
+    _check(lib().splitzip_variant_codebook_from_dec(arr, C.byref(v), C.byref(cb)), "splitzip_variant_codebook_from_dec")
+    return Codebook(cb)
+
+
+def variant_compress(x: torch.Tensor, v: Variant, cb: Codebook, out: torch.Tensor, workspace: torch.Tensor,
+                     sizes: torch.Tensor, stream=None, capacity: int | None = None) -> None:
+    """splitzip_variant_compress; workspace is a device uint8 tensor of variant_workspace_bytes."""
+    if x.element_size() != _elem_size(v.dtype) or not x.is_contiguous():
+        raise ValueError("x must be a contiguous tensor of raw words of the variant's dtype")
+    cap = out.numel() * out.element_size() if capacity is None else capacity
+    _check(lib().splitzip_variant_compress(x.data_ptr(), x.numel(), C.byref(v), C.byref(cb.c), out.data_ptr(), cap,
+                                           workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                           sizes.data_ptr(), _stream_ptr(stream)), "splitzip_variant_compress")
+
+
+def variant_decompress(comp: torch.Tensor, comp_bytes: int, n_elems: int, v: Variant, cb: Codebook, out: torch.Tensor,
+                       sizes: torch.Tensor | None = None, stream=None) -> None:
+    if out.numel() < n_elems or out.element_size() != _elem_size(v.dtype) or not out.is_contiguous():
+        raise ValueError("out must be a contiguous tensor of at least n_elems raw words")
+    _check(lib().splitzip_variant_decompress(comp.data_ptr(), comp_bytes, n_elems, C.byref(v), C.byref(cb.c),
+                                             out.data_ptr(), sizes.data_ptr() if sizes is not None else None,
+                                             _stream_ptr(stream)), "splitzip_variant_decompress")

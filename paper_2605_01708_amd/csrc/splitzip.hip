@@ -8,6 +8,8 @@
 //   decompress.hpp  nibble unpack, decode table, eq. (2), scatter correction in registers; one
 //                   launch per tensor or per batch
 //   aux_kernels.hpp calibration histogram (section 3.3), workspace initialisation, traffic probe
+//   variants.hpp    the formats of the ablations (top-8 / 3-bit codes, top-15 + sentinel, chunk 256,
+//                   absolute positions, E4M3) through one plain set of kernels
 //
 // Work decomposition (wavefront = 64 lanes): a chunk of 1024 elements (the escape-position
 // granule) is owned by one wave; every global access of a wave is one fully coalesced run of 16,
@@ -25,6 +27,7 @@ namespace {
 #include "compress.hpp"
 #include "decompress.hpp"
 #include "aux_kernels.hpp"
+#include "variants.hpp"
 
 // ---------------------------------------------------------------------------
 // host side
@@ -122,11 +125,212 @@ uint32_t resident_workgroups_batch() {
   return cached[dev];
 }
 
+// ---------------------------------------------------------------------------
+// format variants: host side
+// ---------------------------------------------------------------------------
+
+bool variant_ok(const splitzip_variant* v) {
+  if (!v || v->dtype > SPLITZIP_FP8_E4M3) return false;
+  if (v->code_bits != 3 && v->code_bits != 4) return false;
+  if (v->escape_mode > SPLITZIP_ESC_ABS32) return false;
+  const uint32_t codes = 1u << v->code_bits;
+  const uint32_t kmax = v->escape_mode == SPLITZIP_ESC_SENTINEL ? codes - 1 : codes;
+  if (v->k < 1 || v->k > kmax || v->k > v_exp_values(v->dtype)) return false;
+  if (v->escape_mode != SPLITZIP_ESC_ABS32 && v->chunk_elems != 256 && v->chunk_elems != 1024) return false;
+  return true;
+}
+
+// exactly the first k entries of dec are members, with codes 0 .. k-1
+bool variant_codebook_ok(const splitzip_codebook* cb, const splitzip_variant* v) {
+  if (!cb || cb->dtype != v->dtype) return false;
+  unsigned members = 0;
+  for (unsigned e = 0; e < 256; ++e) {
+    if (cb->member[e] > 1) return false;
+    if (cb->member[e]) {
+      if (e >= v_exp_values(v->dtype) || cb->enc[e] >= v->k || cb->dec[cb->enc[e]] != e) return false;
+      ++members;
+    }
+  }
+  return members == v->k;
+}
+
+// the part of VArgs that follows from (n, variant): layout and chunking
+void variant_layout(uint64_t n, const splitzip_variant* v, VArgs* a) {
+  memset(a, 0, sizeof *a);
+  const bool absolute = v->escape_mode == SPLITZIP_ESC_ABS32;
+  a->n = n;
+  a->dtype = v->dtype; a->code_bits = v->code_bits; a->k = v->k; a->mode = v->escape_mode;
+  a->chunk_shift = absolute || v->chunk_elems == 1024 ? 10 : 8;
+  a->pos_bytes = v_pos_bytes(v->escape_mode, v->chunk_elems);
+  a->n_chunks = (n + (1ull << a->chunk_shift) - 1) >> a->chunk_shift;
+  a->sm_bytes = (n * v_sm_bits(v->dtype) + 7) / 8;
+  a->code_bytes = (n * v->code_bits + 7) / 8;
+  a->off_tab = kHeaderBytes;
+  a->off_sm = a256(kHeaderBytes + (absolute ? 0 : 4 * (a->n_chunks + 1)));
+  a->off_code = a->off_sm + a256(a->sm_bytes);
+  a->off_pos = a->off_code + a256(a->code_bytes);
+}
+
+#define SPLITZIP_V_DISPATCH2(KERNEL, grid, block, st, args)                                                        \
+  do {                                                                                                             \
+    const int key_ = (int)(args).dtype * 2 + ((args).code_bits == 4 ? 1 : 0);                                      \
+    switch (key_) {                                                                                                \
+      case 0: hipLaunchKernelGGL((KERNEL<SPLITZIP_BF16, 3>), grid, block, 0, st, args); break;                     \
+      case 1: hipLaunchKernelGGL((KERNEL<SPLITZIP_BF16, 4>), grid, block, 0, st, args); break;                     \
+      case 2: hipLaunchKernelGGL((KERNEL<SPLITZIP_FP8_E5M2, 3>), grid, block, 0, st, args); break;                 \
+      case 3: hipLaunchKernelGGL((KERNEL<SPLITZIP_FP8_E5M2, 4>), grid, block, 0, st, args); break;                 \
+      case 4: hipLaunchKernelGGL((KERNEL<SPLITZIP_FP8_E4M3, 3>), grid, block, 0, st, args); break;                 \
+      default: hipLaunchKernelGGL((KERNEL<SPLITZIP_FP8_E4M3, 4>), grid, block, 0, st, args); break;                \
+    }                                                                                                              \
+  } while (0)
+#define SPLITZIP_V_DISPATCH1(KERNEL, grid, block, st, args)                                                        \
+  do {                                                                                                             \
+    switch ((args).dtype) {                                                                                        \
+      case SPLITZIP_BF16: hipLaunchKernelGGL((KERNEL<SPLITZIP_BF16>), grid, block, 0, st, args); break;            \
+      case SPLITZIP_FP8_E5M2: hipLaunchKernelGGL((KERNEL<SPLITZIP_FP8_E5M2>), grid, block, 0, st, args); break;    \
+      default: hipLaunchKernelGGL((KERNEL<SPLITZIP_FP8_E4M3>), grid, block, 0, st, args); break;                   \
+    }                                                                                                              \
+  } while (0)
+
 }  // namespace
 
 extern "C" {
 
 int splitzip_version(void) { return 1; }
+
+
+// ---- format variants ---------------------------------------------------------
+
+int splitzip_variant_supported(const splitzip_variant* v) { return variant_ok(v) ? 1 : 0; }
+
+size_t splitzip_variant_total_bytes(uint64_t n_elems, uint64_t n_escapes, const splitzip_variant* v) {
+  if (!variant_ok(v) || (n_elems >> 32)) return 0;
+  VArgs a;
+  variant_layout(n_elems, v, &a);
+  return a.off_pos + a256(a.pos_bytes * n_escapes) + n_escapes;
+}
+
+size_t splitzip_variant_compress_bound(uint64_t n_elems, const splitzip_variant* v) {
+  return splitzip_variant_total_bytes(n_elems, n_elems, v);
+}
+
+size_t splitzip_variant_workspace_bytes(uint64_t n_elems, const splitzip_variant* v) {
+  if (!variant_ok(v) || (n_elems >> 32)) return 0;
+  VArgs a;
+  variant_layout(n_elems, v, &a);
+  return a256(4 * a.n_chunks + 4) + a256(4 * (a.n_chunks + 1));
+}
+
+int splitzip_variant_codebook_from_dec(const uint8_t* dec, const splitzip_variant* v, splitzip_codebook* out) {
+  if (!dec || !out || !variant_ok(v)) return SPLITZIP_ERR_INVALID_ARG;
+  memset(out, 0, sizeof *out);
+  out->dtype = v->dtype;
+  for (uint32_t j = 0; j < v->k; ++j) {
+    if (dec[j] >= v_exp_values(v->dtype) || out->member[dec[j]]) return SPLITZIP_ERR_INVALID_ARG;
+    out->dec[j] = dec[j];
+    out->enc[dec[j]] = (uint8_t)j;
+    out->member[dec[j]] = 1;
+  }
+  return SPLITZIP_OK;
+}
+
+int splitzip_variant_calibrate(const void* h_sample, uint64_t n_elems, const splitzip_variant* v,
+                               splitzip_codebook* out, uint64_t* hist_out) {
+  if (!out || !variant_ok(v) || (n_elems && !h_sample)) return SPLITZIP_ERR_INVALID_ARG;
+  uint64_t hist[256] = {0};
+  if (v->dtype == SPLITZIP_BF16) {
+    const uint16_t* p = static_cast<const uint16_t*>(h_sample);
+    for (uint64_t i = 0; i < n_elems; ++i) hist[(p[i] >> 7) & 0xff]++;
+  } else {
+    const uint8_t* p = static_cast<const uint8_t*>(h_sample);
+    const unsigned shift = v->dtype == SPLITZIP_FP8_E5M2 ? 2 : 3, mask = v->dtype == SPLITZIP_FP8_E5M2 ? 0x1f : 0xf;
+    for (uint64_t i = 0; i < n_elems; ++i) hist[(p[i] >> shift) & mask]++;
+  }
+  if (hist_out) memcpy(hist_out, hist, sizeof hist);
+  // the ranking of splitzip_codebook_from_hist, cut at k
+  const unsigned nv = v_exp_values(v->dtype);
+  uint8_t top[16];
+  unsigned filled = 0;
+  for (unsigned e = 0; e < nv; ++e) {
+    unsigned at = filled;
+    while (at > 0 && hist[top[at - 1]] < hist[e]) --at;
+    if (at >= 16) continue;
+    const unsigned last = filled < 16 ? filled : 15;
+    for (unsigned i = last; i > at; --i) top[i] = top[i - 1];
+    top[at] = (uint8_t)e;
+    if (filled < 16) ++filled;
+  }
+  return splitzip_variant_codebook_from_dec(top, v, out);
+}
+
+int splitzip_variant_compress(const void* d_in, uint64_t n_elems, const splitzip_variant* v,
+                              const splitzip_codebook* cb, void* d_out, size_t out_capacity, void* d_workspace,
+                              size_t workspace_bytes, splitzip_sizes* d_sizes, void* stream) {
+  if (!variant_ok(v) || !variant_codebook_ok(cb, v) || !d_out || !d_sizes || !d_workspace || (n_elems && !d_in))
+    return SPLITZIP_ERR_INVALID_ARG;
+  if (!aligned16(d_in) || !aligned16(d_out) || !aligned16(d_workspace) || (reinterpret_cast<uintptr_t>(d_sizes) & 7u))
+    return SPLITZIP_ERR_INVALID_ARG;
+  if (n_elems >> 32) return SPLITZIP_ERR_UNSUPPORTED;
+  if (out_capacity < splitzip_variant_total_bytes(n_elems, 0, v) ||
+      workspace_bytes < splitzip_variant_workspace_bytes(n_elems, v))
+    return SPLITZIP_ERR_CAPACITY;
+
+  VArgs a;
+  variant_layout(n_elems, v, &a);
+  a.in = static_cast<const uint8_t*>(d_in);
+  a.out = static_cast<uint8_t*>(d_out);
+  a.capacity = out_capacity;
+  a.sizes = d_sizes;
+  a.counts = static_cast<uint32_t*>(d_workspace);
+  a.offs = v->escape_mode == SPLITZIP_ESC_ABS32
+               ? reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(d_workspace) + a256(4 * a.n_chunks + 4))
+               : reinterpret_cast<uint32_t*>(a.out + a.off_tab);
+  memcpy(a.dec, cb->dec, 16);
+  for (uint32_t j = v->k; j < 16; ++j) a.dec[j] = 0;
+  const uint8_t escape = (uint8_t)(0x80u | (v->escape_mode == SPLITZIP_ESC_SENTINEL ? (1u << v->code_bits) - 1u : 0u));
+  for (unsigned e = 0; e < 256; ++e) a.lut[e] = cb->member[e] ? cb->enc[e] : escape;
+
+  const hipStream_t st = static_cast<hipStream_t>(stream);
+  const uint64_t blocks = (n_elems + kVBlock - 1) / kVBlock;
+  const unsigned grid = (unsigned)((blocks + kWaves - 1) / kWaves);
+  if (grid) SPLITZIP_V_DISPATCH2(v_dense_kernel, dim3(grid), dim3(kThreads), st, a);
+  hipLaunchKernelGGL(v_scan_kernel, dim3(1), dim3(1024), 0, st, a);
+  if (grid) SPLITZIP_V_DISPATCH1(v_emit_kernel, dim3(grid), dim3(kThreads), st, a);
+  return hipGetLastError() == hipSuccess ? SPLITZIP_OK : SPLITZIP_ERR_HIP;
+}
+
+int splitzip_variant_decompress(const void* d_comp, size_t comp_bytes, uint64_t n_elems, const splitzip_variant* v,
+                                const splitzip_codebook* cb, void* d_out, splitzip_sizes* d_sizes, void* stream) {
+  if (!variant_ok(v) || !variant_codebook_ok(cb, v) || !d_comp || (n_elems && !d_out)) return SPLITZIP_ERR_INVALID_ARG;
+  if (!aligned16(d_comp) || !aligned16(d_out) || (reinterpret_cast<uintptr_t>(d_sizes) & 7u))
+    return SPLITZIP_ERR_INVALID_ARG;
+  if (n_elems >> 32) return SPLITZIP_ERR_UNSUPPORTED;
+  if (comp_bytes < splitzip_variant_total_bytes(n_elems, 0, v)) return SPLITZIP_ERR_CAPACITY;
+
+  VArgs a;
+  variant_layout(n_elems, v, &a);
+  a.in = static_cast<const uint8_t*>(d_comp);
+  a.out = static_cast<uint8_t*>(d_out);
+  a.capacity = comp_bytes;
+  a.sizes = d_sizes;
+  a.offs = const_cast<uint32_t*>(reinterpret_cast<const uint32_t*>(a.in + a.off_tab));   // read only; unused in the absolute mode
+  memcpy(a.dec, cb->dec, 16);
+  for (uint32_t j = v->k; j < 16; ++j) a.dec[j] = 0;
+
+  const hipStream_t st = static_cast<hipStream_t>(stream);
+  const uint64_t blocks = (n_elems + kVBlock - 1) / kVBlock;
+  const unsigned grid = blocks ? (unsigned)((blocks + kWaves - 1) / kWaves) : 1u;
+  SPLITZIP_V_DISPATCH2(v_decode_kernel, dim3(grid), dim3(kThreads), st, a);
+  if (v->escape_mode == SPLITZIP_ESC_ABS32 && n_elems) {
+    // M is known to the device only: a grid that strides over whatever the header says
+    const uint64_t most = (comp_bytes - a.off_pos) / 5;
+    uint64_t g = (most + kThreads - 1) / kThreads;
+    const uint64_t cap = (uint64_t)cu_count() * 8;
+    if (g > cap) g = cap;
+    if (g) SPLITZIP_V_DISPATCH1(v_scatter_kernel, dim3((unsigned)g), dim3(kThreads), st, a);
+  }
+  return hipGetLastError() == hipSuccess ? SPLITZIP_OK : SPLITZIP_ERR_HIP;
+}
 
 const char* splitzip_strerror(int err) {
   switch (err) {

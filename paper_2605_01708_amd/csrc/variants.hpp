@@ -1,0 +1,463 @@
+// SplitZip for MI355X: the format variants of the paper's ablations (sections "Ablation on Top-k
+// Exponent Coding" and "Ablation on Escape-Position Metadata", appendices "Ablation on Chunk Size"
+// and "SplitZip on FP8") through one generic set of kernels.  Part of the single translation unit
+// splitzip.hip (included inside its anonymous namespace).
+//
+// These kernels follow the paper's own structure (appendix "Quad64 Vectorized Encoding"): a dense
+// pass that also counts the escapes of every chunk, a scan of the counts, and a second pass over
+// the input that writes the escape records to their final place.  They are deliberately plain --
+// a block of 1024 elements per wave, eight elements per lane and step, both planes packed as
+// LSB-first bit streams of any width and staged through LDS so that global accesses stay whole
+// dwords -- because their job is to compare the formats with one another on equal terms, the main
+// format included.  The tuned path for the main format is compress.hpp / decompress.hpp.
+#ifndef SPLITZIP_VARIANTS_HPP
+#define SPLITZIP_VARIANTS_HPP
+
+constexpr uint32_t kVBlock = 1024;   // elements a wave handles at a time
+constexpr uint32_t kVStep = 512;     // ... in two steps of 8 elements per lane
+
+// per-format field arithmetic: e, a and the inverse (eq. (1) and (2); FP8 by analogy)
+template <int DT>
+struct VFmt;
+template <>
+struct VFmt<SPLITZIP_BF16> {
+  static constexpr int ES = 2, SB = 8, EXPS = 256;
+  __device__ static inline uint32_t exponent(uint32_t x) { return (x >> 7) & 0xffu; }
+  __device__ static inline uint32_t signmant(uint32_t x) { return ((x >> 8) & 0x80u) | (x & 0x7fu); }
+  __device__ static inline uint32_t combine(uint32_t a, uint32_t e) { return ((a & 0x80u) << 8) | (e << 7) | (a & 0x7fu); }
+};
+template <>
+struct VFmt<SPLITZIP_FP8_E5M2> {
+  static constexpr int ES = 1, SB = 3, EXPS = 32;
+  __device__ static inline uint32_t exponent(uint32_t x) { return (x >> 2) & 0x1fu; }
+  __device__ static inline uint32_t signmant(uint32_t x) { return ((x >> 5) & 0x4u) | (x & 0x3u); }
+  __device__ static inline uint32_t combine(uint32_t a, uint32_t e) { return ((a & 0x4u) << 5) | (e << 2) | (a & 0x3u); }
+};
+template <>
+struct VFmt<SPLITZIP_FP8_E4M3> {
+  static constexpr int ES = 1, SB = 4, EXPS = 16;
+  __device__ static inline uint32_t exponent(uint32_t x) { return (x >> 3) & 0xfu; }
+  __device__ static inline uint32_t signmant(uint32_t x) { return ((x >> 4) & 0x8u) | (x & 0x7u); }
+  __device__ static inline uint32_t combine(uint32_t a, uint32_t e) { return ((a & 0x8u) << 4) | (e << 3) | (a & 0x7u); }
+};
+
+__host__ __device__ inline uint32_t v_sm_bits(uint32_t dtype) { return dtype == SPLITZIP_BF16 ? 8u : dtype == SPLITZIP_FP8_E5M2 ? 3u : 4u; }
+__host__ __device__ inline uint32_t v_exp_values(uint32_t dtype) { return dtype == SPLITZIP_BF16 ? 256u : dtype == SPLITZIP_FP8_E5M2 ? 32u : 16u; }
+__host__ __device__ inline uint32_t v_pos_bytes(uint32_t mode, uint32_t chunk) {
+  return mode == SPLITZIP_ESC_SENTINEL ? 0u : mode == SPLITZIP_ESC_ABS32 ? 4u : chunk > 256u ? 2u : 1u;
+}
+
+// what every variant kernel needs to know about a call
+struct VArgs {
+  const uint8_t* in;     // compress: the words; decompress: the stream
+  uint8_t* out;          // compress: the stream; decompress: the words
+  uint64_t capacity;     // bytes of the stream buffer (compress: room, decompress: what the caller holds)
+  uint64_t n;
+  uint32_t dtype, code_bits, k, mode;
+  uint32_t chunk_shift;  // log2 of the chunk the counts are kept for (10 in the absolute mode: the wave's block)
+  uint32_t pos_bytes;
+  uint64_t n_chunks;     // of that chunk size
+  uint64_t sm_bytes, code_bytes;
+  uint64_t off_tab, off_sm, off_code, off_pos;
+  uint32_t* counts;      // workspace: escapes per chunk
+  uint32_t* offs;        // exclusive offsets, n_chunks + 1: in the stream, or in the workspace in the absolute mode
+  splitzip_sizes* sizes;
+  uint8_t dec[16];
+  uint8_t lut[256];      // exponent -> code, | 0x80 for an escape
+};
+
+// eight elements of a lane: words beyond N read as zero
+template <int DT>
+__device__ inline void v_load8(const VArgs& a, uint64_t g0, uint32_t (&x)[8]) {
+  using F = VFmt<DT>;
+  if (g0 + 8 <= a.n) {
+    if (F::ES == 2) {
+      const u32x4 v = *reinterpret_cast<const u32x4*>(a.in + 2 * g0);
+      x[0] = v.x & 0xffffu; x[1] = v.x >> 16; x[2] = v.y & 0xffffu; x[3] = v.y >> 16;
+      x[4] = v.z & 0xffffu; x[5] = v.z >> 16; x[6] = v.w & 0xffffu; x[7] = v.w >> 16;
+    } else {
+      const u32x2 v = *reinterpret_cast<const u32x2*>(a.in + g0);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { x[j] = (v.x >> (8 * j)) & 0xffu; x[4 + j] = (v.y >> (8 * j)) & 0xffu; }
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      x[j] = 0;
+      if (g0 + j < a.n) x[j] = F::ES == 2 ? reinterpret_cast<const uint16_t*>(a.in)[g0 + j] : a.in[g0 + j];
+    }
+  }
+}
+
+// A wave's LDS accesses are carried out in program order; this keeps the compiler from reordering
+// accesses it takes for unrelated because they go through different types, and waits for the data.
+__device__ inline void v_lds_settle() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+// NB bytes of v to / from a lane's slot in LDS (slot = lane * NB; 8 and 4 are aligned)
+template <int NB>
+__device__ inline void v_lds_put(uint8_t* p, uint64_t v) {
+  if (NB == 8) *reinterpret_cast<uint64_t*>(p) = v;
+  else if (NB == 4) *reinterpret_cast<uint32_t*>(p) = (uint32_t)v;
+  else { p[0] = (uint8_t)v; p[1] = (uint8_t)(v >> 8); p[2] = (uint8_t)(v >> 16); }
+}
+template <int NB>
+__device__ inline uint64_t v_lds_get(const uint8_t* p) {
+  if (NB == 8) return *reinterpret_cast<const uint64_t*>(p);
+  if (NB == 4) return *reinterpret_cast<const uint32_t*>(p);
+  return (uint64_t)p[0] | ((uint64_t)p[1] << 8) | ((uint64_t)p[2] << 16);
+}
+
+// split + encode of a lane's eight elements: packed a, packed codes, escape mask (bit j = element j)
+template <int DT, int CB>
+__device__ inline void v_encode8(const VArgs& a, const uint8_t* lut, uint64_t g0, const uint32_t (&x)[8], uint64_t& smw,
+                                 uint32_t& cw, uint32_t& esc) {
+  using F = VFmt<DT>;
+  smw = 0; cw = 0; esc = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const uint32_t t = lut[F::exponent(x[j])];
+    const bool valid = g0 + j < a.n;
+    smw |= (uint64_t)F::signmant(x[j]) << (F::SB * j);   // zero for words beyond N
+    if (valid) {
+      cw |= (t & 0x7fu) << (CB * j);
+      esc |= (t >> 7) << j;
+    }
+  }
+}
+
+// compress pass 1: both planes and the escape count of every chunk
+template <int DT, int CB>
+__global__ __launch_bounds__(kThreads) void v_dense_kernel(const VArgs a) {
+  using F = VFmt<DT>;
+  __shared__ uint8_t lut[256];
+  __shared__ __attribute__((aligned(16))) uint8_t s_sm[kWaves][64 * F::SB];
+  __shared__ __attribute__((aligned(16))) uint8_t s_code[kWaves][64 * CB];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  lut[tid] = a.lut[tid];
+  __syncthreads();
+  const uint64_t blk = (uint64_t)blockIdx.x * kWaves + wave;
+  if (blk * kVBlock >= a.n) return;
+  uint32_t carry = 0;   // escapes of step 0, for 1024-element chunks
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+    const uint64_t g = blk * kVBlock + s * kVStep, g0 = g + lane * 8;
+    uint32_t x[8];
+    v_load8<DT>(a, g0, x);
+    uint64_t smw;
+    uint32_t cw, esc;
+    v_encode8<DT, CB>(a, lut, g0, x, smw, cw, esc);
+    v_lds_put<F::SB>(&s_sm[wave][lane * F::SB], smw);
+    v_lds_put<CB>(&s_code[wave][lane * CB], cw);
+    v_lds_settle();
+    // the step's plane bytes leave as whole dwords, up to the padded end of the section
+    const uint64_t sm0 = g / 8 * F::SB, code0 = g / 8 * CB;
+    for (uint32_t i = lane; i < 16u * F::SB; i += 64)
+      if (sm0 + 4 * i < a256(a.sm_bytes))
+        st_stream(reinterpret_cast<uint32_t*>(a.out + a.off_sm + sm0) + i, reinterpret_cast<const uint32_t*>(s_sm[wave])[i]);
+    if ((uint32_t)lane < 16u * CB && code0 + 4 * lane < a256(a.code_bytes))
+      st_stream(reinterpret_cast<uint32_t*>(a.out + a.off_code + code0) + lane, reinterpret_cast<const uint32_t*>(s_code[wave])[lane]);
+    v_lds_settle();   // the staging is written again in the next step
+    const uint32_t incl = wave_incl_scan(__popc(esc));
+    const uint32_t t31 = __builtin_amdgcn_readlane(incl, 31), t63 = __builtin_amdgcn_readlane(incl, 63);
+    if (a.chunk_shift == 10) {
+      if (s == 0) carry = t63;
+      else if (lane == 0) a.counts[blk] = carry + t63;
+    } else if (lane == 0) {   // two 256-element chunks per step
+      const uint64_t c0 = g >> 8;
+      if (c0 < a.n_chunks) a.counts[c0] = t31;
+      if (c0 + 1 < a.n_chunks) a.counts[c0 + 1] = t63 - t31;
+    }
+  }
+}
+
+// compress pass 2: exclusive scan of the counts, header, sizes record, zero padding.  One workgroup.
+__global__ __launch_bounds__(1024) void v_scan_kernel(const VArgs a) {
+  __shared__ uint32_t s_wave[16];
+  const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const uint64_t per = (a.n_chunks + 1023) / 1024, lo = tid * per, hi = lo + per < a.n_chunks ? lo + per : a.n_chunks;
+  uint32_t sum = 0;
+  for (uint64_t c = lo; c < hi; ++c) sum += a.counts[c];
+  const uint32_t incl = wave_incl_scan(sum);
+  if (lane == 63) s_wave[wave] = incl;
+  __syncthreads();
+  uint32_t before = 0, M = 0;
+  for (uint32_t w = 0; w < 16; ++w) {
+    if (w < wave) before += s_wave[w];
+    M += s_wave[w];
+  }
+  uint32_t run = before + incl - sum;
+  for (uint64_t c = lo; c < hi; ++c) {
+    a.offs[c] = run;
+    run += a.counts[c];
+  }
+  if (tid == 0) a.offs[a.n_chunks] = M;
+
+  const uint64_t pos_sec = a256((uint64_t)a.pos_bytes * M), total = a.off_pos + pos_sec + M;
+  // zero padding: behind the table, behind what the dense pass covered of each plane, behind the positions
+  const uint64_t tab_end = a.mode == SPLITZIP_ESC_ABS32 ? kHeaderBytes : a.off_tab + 4 * (a.n_chunks + 1);
+  for (uint64_t i = tab_end + tid; i < a.off_sm; i += 1024) a.out[i] = 0;
+  const uint64_t blocks = (a.n + kVBlock - 1) / kVBlock;
+  const uint64_t sm_cov = blocks * (kVBlock / 8) * v_sm_bits(a.dtype), code_cov = blocks * (kVBlock / 8) * a.code_bits;
+  for (uint64_t i = sm_cov + tid; i < a256(a.sm_bytes); i += 1024) a.out[a.off_sm + i] = 0;
+  for (uint64_t i = code_cov + tid; i < a256(a.code_bytes); i += 1024) a.out[a.off_code + i] = 0;
+  for (uint64_t i = (uint64_t)a.pos_bytes * M + tid; i < pos_sec; i += 1024)
+    if (a.off_pos + i < a.capacity) a.out[a.off_pos + i] = 0;
+  if (tid == 0) {
+    // header (see include/splitzip.h)
+    uint32_t h[16];
+    h[0] = 0x31505A53u;   // "SZP1"
+    h[1] = 2u | (a.dtype << 16) | (a.code_bits << 24);
+    h[2] = a.mode == SPLITZIP_ESC_ABS32 ? 0u : 1u << a.chunk_shift;
+    h[3] = a.mode | (a.k << 8);
+    h[4] = (uint32_t)a.n; h[5] = (uint32_t)(a.n >> 32);
+    h[6] = M; h[7] = 0;
+    h[8] = (uint32_t)total; h[9] = (uint32_t)(total >> 32);
+    for (int i = 0; i < 4; ++i)
+      h[10 + i] = a.dec[4 * i] | (a.dec[4 * i + 1] << 8) | (a.dec[4 * i + 2] << 16) | ((uint32_t)a.dec[4 * i + 3] << 24);
+    h[14] = h[15] = 0;
+    for (int i = 0; i < 16; ++i) reinterpret_cast<uint32_t*>(a.out)[i] = h[i];
+    a.sizes->total_bytes = total;
+    a.sizes->n_escapes = M;
+    a.sizes->status = total > a.capacity ? SPLITZIP_STATUS_OVERFLOW : 0u;
+    a.sizes->reserved = 0;
+  }
+}
+
+// compress pass 3: the escape records, each at its final rank (what does not fit the capacity is dropped)
+template <int DT>
+__global__ __launch_bounds__(kThreads) void v_emit_kernel(const VArgs a) {
+  using F = VFmt<DT>;
+  __shared__ uint8_t lut[256];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  lut[tid] = a.lut[tid];
+  __syncthreads();
+  const uint64_t blk = (uint64_t)blockIdx.x * kWaves + wave;
+  if (blk * kVBlock >= a.n) return;
+  const uint32_t per_blk = kVBlock >> a.chunk_shift;   // chunks per block: 1 or 4
+  const uint64_t c_first = blk * per_blk, c_end = c_first + per_blk < a.n_chunks ? c_first + per_blk : a.n_chunks;
+  if (a.offs[c_end] == a.offs[c_first]) return;         // nothing escaped in this block
+  const uint32_t M = a.offs[a.n_chunks];
+  const uint64_t off_val = a.off_pos + a256((uint64_t)a.pos_bytes * M);
+  uint32_t carry = 0;
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+    const uint64_t g = blk * kVBlock + s * kVStep, g0 = g + lane * 8;
+    uint32_t x[8];
+    v_load8<DT>(a, g0, x);
+    uint32_t esc = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (g0 + j < a.n) esc |= (uint32_t)(lut[F::exponent(x[j])] >> 7) << j;
+    const uint32_t cnt = __popc(esc), incl = wave_incl_scan(cnt);
+    const uint32_t t31 = __builtin_amdgcn_readlane(incl, 31), t63 = __builtin_amdgcn_readlane(incl, 63);
+    uint32_t r;
+    if (a.chunk_shift == 10) {
+      r = a.offs[blk] + carry + incl - cnt;
+      carry = t63;
+    } else {
+      const uint64_t c = (g >> 8) + (lane >> 5);
+      r = (c < a.n_chunks ? a.offs[c] : 0u) + incl - cnt - (lane >= 32 ? t31 : 0u);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      if (!((esc >> j) & 1u)) continue;
+      const uint64_t i = g0 + j;
+      if (a.mode == SPLITZIP_ESC_POS) {
+        const uint32_t p = (uint32_t)i & ((1u << a.chunk_shift) - 1u);
+        const uint64_t at = a.off_pos + (uint64_t)a.pos_bytes * r;
+        if (at + a.pos_bytes <= a.capacity) {
+          if (a.pos_bytes == 2) *reinterpret_cast<uint16_t*>(a.out + at) = (uint16_t)p;
+          else a.out[at] = (uint8_t)p;
+        }
+      } else if (a.mode == SPLITZIP_ESC_ABS32) {
+        const uint64_t at = a.off_pos + 4ull * r;
+        if (at + 4 <= a.capacity) *reinterpret_cast<uint32_t*>(a.out + at) = (uint32_t)i;
+      }
+      if (off_val + r < a.capacity) a.out[off_val + r] = (uint8_t)F::exponent(x[j]);
+      ++r;
+    }
+  }
+}
+
+// ---- decompress -----------------------------------------------------------------------------
+
+// an inconsistent header or record: sticky bit in the caller's sizes record (nullable)
+__device__ inline void v_flag_bad(const VArgs& a) {
+  if (a.sizes) atomicOr(&a.sizes->status, SPLITZIP_STATUS_BAD_STREAM);
+}
+
+// header against the call; returns M through *m_out
+__device__ inline bool v_check_header(const VArgs& a, uint32_t* m_out) {
+  const uint32_t* h = reinterpret_cast<const uint32_t*>(a.in);
+  const uint64_t n = h[4] | ((uint64_t)h[5] << 32), M = h[6] | ((uint64_t)h[7] << 32), total = h[8] | ((uint64_t)h[9] << 32);
+  bool ok = h[0] == 0x31505A53u && h[1] == (2u | (a.dtype << 16) | (a.code_bits << 24)) &&
+            h[2] == (a.mode == SPLITZIP_ESC_ABS32 ? 0u : 1u << a.chunk_shift) && h[3] == (a.mode | (a.k << 8)) && n == a.n &&
+            M <= n && h[14] == 0 && h[15] == 0;
+  for (int i = 0; i < 16; ++i) ok = ok && a.in[40 + i] == ((uint32_t)i < a.k ? a.dec[i] : 0);
+  ok = ok && total == a.off_pos + a256(a.pos_bytes * M) + M && total <= a.capacity;
+  *m_out = (uint32_t)M;
+  return ok;
+}
+
+// One block of 1024 elements per wave: the block's plane bytes into LDS, decode into an LDS tile,
+// correct the tile from the chunk's escape records (or, in the sentinel mode, fetch the exponent of
+// every sentinel while decoding), store the tile.  In the absolute mode the correction is left to
+// v_scatter_kernel.
+template <int DT, int CB>
+__global__ __launch_bounds__(kThreads) void v_decode_kernel(const VArgs a) {
+  using F = VFmt<DT>;
+  __shared__ uint8_t s_dec[16];
+  __shared__ uint32_t s_hdr[2];
+  __shared__ __attribute__((aligned(16))) uint8_t s_sm[kWaves][128 * F::SB];
+  __shared__ __attribute__((aligned(16))) uint8_t s_code[kWaves][128 * CB];
+  __shared__ __attribute__((aligned(16))) uint8_t s_tile[kWaves][kVBlock * F::ES];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid < 16) s_dec[tid] = (uint32_t)tid < a.k ? a.dec[tid] : 0;
+  if (tid == 0) {
+    uint32_t M;
+    const bool ok = v_check_header(a, &M);
+    s_hdr[0] = ok;
+    s_hdr[1] = M;
+    if (blockIdx.x == 0) {
+      if (a.sizes) {
+        const uint32_t* h = reinterpret_cast<const uint32_t*>(a.in);
+        a.sizes->total_bytes = h[8] | ((uint64_t)h[9] << 32);
+        a.sizes->n_escapes = M;
+      }
+      if (!ok) v_flag_bad(a);
+    }
+  }
+  __syncthreads();
+  if (!s_hdr[0]) return;   // nothing of a stream with a bad header is followed
+  const uint32_t M = s_hdr[1];
+  const uint64_t off_val = a.off_pos + a256((uint64_t)a.pos_bytes * M);
+  const uint64_t blk = (uint64_t)blockIdx.x * kWaves + wave;
+  if (blk * kVBlock >= a.n) return;
+  const uint32_t sentinel = (1u << CB) - 1u;
+  bool bad = false;
+
+  // the block's slices of both planes (whole dwords; the sections are padded, so nothing past them is read)
+  const uint64_t sm0 = blk * (kVBlock / 8) * F::SB, code0 = blk * (kVBlock / 8) * CB;
+  for (uint32_t i = lane; i < 32u * F::SB; i += 64)
+    reinterpret_cast<uint32_t*>(s_sm[wave])[i] =
+        sm0 + 4 * i < a256(a.sm_bytes) ? ld_stream(reinterpret_cast<const uint32_t*>(a.in + a.off_sm + sm0) + i) : 0u;
+  for (uint32_t i = lane; i < 32u * CB; i += 64)
+    reinterpret_cast<uint32_t*>(s_code[wave])[i] =
+        code0 + 4 * i < a256(a.code_bytes) ? ld_stream(reinterpret_cast<const uint32_t*>(a.in + a.off_code + code0) + i) : 0u;
+
+  v_lds_settle();
+  uint32_t carry = 0;
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+    const uint64_t g = blk * kVBlock + s * kVStep, g0 = g + lane * 8;
+    const uint64_t smw = v_lds_get<F::SB>(&s_sm[wave][(s * 64 + lane) * F::SB]);
+    const uint32_t cw = (uint32_t)v_lds_get<CB>(&s_code[wave][(s * 64 + lane) * CB]);
+    uint32_t w[8], sent = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const uint32_t av = (uint32_t)(smw >> (F::SB * j)) & ((1u << F::SB) - 1u), code = (cw >> (CB * j)) & sentinel;
+      if (a.mode == SPLITZIP_ESC_SENTINEL && code == sentinel) sent |= 1u << j;
+      else if (code >= a.k && g0 + j < a.n) bad = true;
+      w[j] = F::combine(av, s_dec[code & 15u]);
+    }
+    if (a.mode == SPLITZIP_ESC_SENTINEL) {
+      // rank of every sentinel inside its chunk, then its exponent from the value array
+      for (int j = 0; j < 8; ++j)
+        if (g0 + j >= a.n) sent &= ~(1u << j);
+      const uint32_t cnt = __popc(sent), incl = wave_incl_scan(cnt);
+      const uint32_t t31 = __builtin_amdgcn_readlane(incl, 31), t63 = __builtin_amdgcn_readlane(incl, 63);
+      uint32_t r, r_end;
+      if (a.chunk_shift == 10) {
+        r = a.offs[blk] + carry + incl - cnt;
+        r_end = a.offs[blk + 1];
+        carry = t63;
+      } else {
+        const uint64_t c = (g >> 8) + (lane >> 5);
+        r = (c < a.n_chunks ? a.offs[c] : 0u) + incl - cnt - (lane >= 32 ? t31 : 0u);
+        r_end = c < a.n_chunks ? a.offs[c + 1] : 0u;
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        if (!((sent >> j) & 1u)) continue;
+        uint32_t e = 0;
+        if (r < r_end && r < M) e = a.in[off_val + r];
+        else bad = true;
+        if (e >= (uint32_t)F::EXPS) { bad = true; e = 0; }
+        const uint32_t av = (uint32_t)(smw >> (F::SB * j)) & ((1u << F::SB) - 1u);
+        w[j] = F::combine(av, e);
+        ++r;
+      }
+    }
+    if (F::ES == 2)
+      *reinterpret_cast<u32x4*>(&s_tile[wave][(s * kVStep + lane * 8) * 2]) =
+          u32x4{w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16)};
+    else
+      *reinterpret_cast<u32x2*>(&s_tile[wave][s * kVStep + lane * 8]) =
+          u32x2{w[0] | (w[1] << 8) | (w[2] << 16) | (w[3] << 24), w[4] | (w[5] << 8) | (w[6] << 16) | (w[7] << 24)};
+  }
+
+  v_lds_settle();
+  if (a.mode == SPLITZIP_ESC_POS) {
+    // the records of the block's chunks, one lane each, straight into the tile
+    const uint32_t per_blk = kVBlock >> a.chunk_shift, chunk = 1u << a.chunk_shift;
+    for (uint32_t q = 0; q < per_blk; ++q) {
+      const uint64_t c = blk * per_blk + q;
+      if (c >= a.n_chunks) break;
+      const uint32_t lo = a.offs[c], hi = a.offs[c + 1];
+      const uint64_t first = c << a.chunk_shift, len = first + chunk <= a.n ? chunk : a.n - first;
+      if (hi < lo || hi - lo > len || hi > M) { bad = true; continue; }
+      for (uint32_t i = lo + lane; i < hi; i += 64) {
+        const uint32_t p = a.pos_bytes == 2 ? reinterpret_cast<const uint16_t*>(a.in + a.off_pos)[i] : a.in[a.off_pos + i];
+        const uint32_t e = a.in[off_val + i];
+        if (p >= len || e >= (uint32_t)F::EXPS) { bad = true; continue; }
+        const uint32_t at = q * chunk + p;
+        if (F::ES == 2) {
+          uint16_t* t = reinterpret_cast<uint16_t*>(s_tile[wave]) + at;
+          *t = (uint16_t)F::combine(F::signmant(*t), e);
+        } else {
+          uint8_t* t = s_tile[wave] + at;
+          *t = (uint8_t)F::combine(F::signmant(*t), e);
+        }
+      }
+    }
+  }
+
+  v_lds_settle();
+  // the tile, 16 bytes per lane and step
+  const uint64_t e0 = blk * kVBlock;
+  const uint32_t bytes = F::ES * kVBlock;
+  if (e0 + kVBlock <= a.n) {
+    for (uint32_t i = lane; i < bytes / 16; i += 64)
+      st_stream(reinterpret_cast<u32x4*>(a.out + e0 * F::ES) + i, reinterpret_cast<const u32x4*>(s_tile[wave])[i]);
+  } else {
+    for (uint32_t i = lane; e0 + i < a.n; i += 64) {
+      if (F::ES == 2) reinterpret_cast<uint16_t*>(a.out)[e0 + i] = reinterpret_cast<const uint16_t*>(s_tile[wave])[i];
+      else a.out[e0 + i] = s_tile[wave][i];
+    }
+  }
+  if (bad) v_flag_bad(a);
+}
+
+// absolute mode: every record overwrites the exponent field of its element (runs after v_decode_kernel)
+template <int DT>
+__global__ __launch_bounds__(kThreads) void v_scatter_kernel(const VArgs a) {
+  using F = VFmt<DT>;
+  uint32_t M;
+  if (!v_check_header(a, &M)) return;
+  const uint64_t off_val = a.off_pos + a256(4ull * M);
+  bool bad = false;
+  for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < M; i += (uint64_t)gridDim.x * kThreads) {
+    const uint64_t p = reinterpret_cast<const uint32_t*>(a.in + a.off_pos)[i];
+    const uint32_t e = a.in[off_val + i];
+    if (p >= a.n || e >= (uint32_t)F::EXPS) { bad = true; continue; }
+    if (F::ES == 2) {
+      uint16_t* t = reinterpret_cast<uint16_t*>(a.out) + p;
+      *t = (uint16_t)F::combine(F::signmant(*t), e);
+    } else {
+      a.out[p] = (uint8_t)F::combine(F::signmant(a.out[p]), e);
+    }
+  }
+  if (bad) v_flag_bad(a);
+}
+
+#endif  // SPLITZIP_VARIANTS_HPP
