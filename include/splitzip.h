@@ -287,9 +287,9 @@ int splitzip_variant_codebook_from_dec(const uint8_t* dec, const splitzip_varian
  * the sizes record (total_bytes, n_escapes, status; OVERFLOW and BAD_STREAM as
  * for the main calls) and the error codes are those of splitzip_compress and
  * splitzip_decompress; d_workspace needs splitzip_variant_workspace_bytes and
- * 16-byte alignment.  Three kernel launches per compress call (four in the
- * absolute mode), one per decompress call (two in the absolute mode), all on
- * `stream`. */
+ * 16-byte alignment.  Four kernel launches per compress call (dense pass,
+ * two for the scan of the per-chunk counts, escape pass), one per decompress
+ * call (two in the absolute mode), all on `stream`. */
 int splitzip_variant_compress(const void* d_in, uint64_t n_elems, const splitzip_variant* v,
                               const splitzip_codebook* cb, void* d_out, size_t out_capacity, void* d_workspace,
                               size_t workspace_bytes, splitzip_sizes* d_sizes, void* stream);

@@ -169,6 +169,22 @@ void variant_layout(uint64_t n, const splitzip_variant* v, VArgs* a) {
   a->off_sm = a256(kHeaderBytes + (absolute ? 0 : 4 * (a->n_chunks + 1)));
   a->off_code = a->off_sm + a256(a->sm_bytes);
   a->off_pos = a->off_code + a256(a->code_bytes);
+  a->n_tiles = (uint32_t)((a->n_chunks + kVScanTile - 1) / kVScanTile);
+  if (a->n_tiles == 0) a->n_tiles = 1;
+}
+
+// header words of a stream of this call (M and total, words 6..9, are the kernels' business) and the tables
+void variant_tables(const splitzip_variant* v, const splitzip_codebook* cb, VArgs* a) {
+  memcpy(a->dec, cb->dec, 16);
+  for (uint32_t j = v->k; j < 16; ++j) a->dec[j] = 0;
+  a->hdr[0] = 0x31505A53u;   // "SZP1"
+  a->hdr[1] = 2u | (a->dtype << 16) | (a->code_bits << 24);
+  a->hdr[2] = a->mode == SPLITZIP_ESC_ABS32 ? 0u : 1u << a->chunk_shift;
+  a->hdr[3] = a->mode | (a->k << 8);
+  a->hdr[4] = (uint32_t)a->n;
+  a->hdr[5] = (uint32_t)(a->n >> 32);
+  for (int i = 0; i < 4; ++i)
+    a->hdr[10 + i] = a->dec[4 * i] | (a->dec[4 * i + 1] << 8) | (a->dec[4 * i + 2] << 16) | ((uint32_t)a->dec[4 * i + 3] << 24);
 }
 
 #define SPLITZIP_V_DISPATCH2(KERNEL, grid, block, st, args)                                                        \
@@ -218,7 +234,7 @@ size_t splitzip_variant_workspace_bytes(uint64_t n_elems, const splitzip_variant
   if (!variant_ok(v) || (n_elems >> 32)) return 0;
   VArgs a;
   variant_layout(n_elems, v, &a);
-  return a256(4 * a.n_chunks + 4) + a256(4 * (a.n_chunks + 1));
+  return a256(4 * a.n_chunks + 4) + a256(4 * (a.n_chunks + 1)) + a256(4 * (uint64_t)a.n_tiles);
 }
 
 int splitzip_variant_codebook_from_dec(const uint8_t* dec, const splitzip_variant* v, splitzip_codebook* out) {
@@ -282,11 +298,11 @@ int splitzip_variant_compress(const void* d_in, uint64_t n_elems, const splitzip
   a.capacity = out_capacity;
   a.sizes = d_sizes;
   a.counts = static_cast<uint32_t*>(d_workspace);
-  a.offs = v->escape_mode == SPLITZIP_ESC_ABS32
-               ? reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(d_workspace) + a256(4 * a.n_chunks + 4))
-               : reinterpret_cast<uint32_t*>(a.out + a.off_tab);
-  memcpy(a.dec, cb->dec, 16);
-  for (uint32_t j = v->k; j < 16; ++j) a.dec[j] = 0;
+  uint8_t* ws = static_cast<uint8_t*>(d_workspace);
+  a.offs = v->escape_mode == SPLITZIP_ESC_ABS32 ? reinterpret_cast<uint32_t*>(ws + a256(4 * a.n_chunks + 4))
+                                                : reinterpret_cast<uint32_t*>(a.out + a.off_tab);
+  a.tile_sums = reinterpret_cast<uint32_t*>(ws + a256(4 * a.n_chunks + 4) + a256(4 * (a.n_chunks + 1)));
+  variant_tables(v, cb, &a);
   const uint8_t escape = (uint8_t)(0x80u | (v->escape_mode == SPLITZIP_ESC_SENTINEL ? (1u << v->code_bits) - 1u : 0u));
   for (unsigned e = 0; e < 256; ++e) a.lut[e] = cb->member[e] ? cb->enc[e] : escape;
 
@@ -294,7 +310,8 @@ int splitzip_variant_compress(const void* d_in, uint64_t n_elems, const splitzip
   const uint64_t blocks = (n_elems + kVBlock - 1) / kVBlock;
   const unsigned grid = (unsigned)((blocks + kWaves - 1) / kWaves);
   if (grid) SPLITZIP_V_DISPATCH2(v_dense_kernel, dim3(grid), dim3(kThreads), st, a);
-  hipLaunchKernelGGL(v_scan_kernel, dim3(1), dim3(1024), 0, st, a);
+  hipLaunchKernelGGL(v_tile_sum_kernel, dim3(a.n_tiles), dim3(1024), 0, st, a);
+  hipLaunchKernelGGL(v_scan_kernel, dim3(a.n_tiles), dim3(1024), 0, st, a);
   if (grid) SPLITZIP_V_DISPATCH1(v_emit_kernel, dim3(grid), dim3(kThreads), st, a);
   return hipGetLastError() == hipSuccess ? SPLITZIP_OK : SPLITZIP_ERR_HIP;
 }
@@ -314,8 +331,7 @@ int splitzip_variant_decompress(const void* d_comp, size_t comp_bytes, uint64_t 
   a.capacity = comp_bytes;
   a.sizes = d_sizes;
   a.offs = const_cast<uint32_t*>(reinterpret_cast<const uint32_t*>(a.in + a.off_tab));   // read only; unused in the absolute mode
-  memcpy(a.dec, cb->dec, 16);
-  for (uint32_t j = v->k; j < 16; ++j) a.dec[j] = 0;
+  variant_tables(v, cb, &a);
 
   const hipStream_t st = static_cast<hipStream_t>(stream);
   const uint64_t blocks = (n_elems + kVBlock - 1) / kVBlock;

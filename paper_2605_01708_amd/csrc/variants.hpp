@@ -61,7 +61,10 @@ struct VArgs {
   uint64_t off_tab, off_sm, off_code, off_pos;
   uint32_t* counts;      // workspace: escapes per chunk
   uint32_t* offs;        // exclusive offsets, n_chunks + 1: in the stream, or in the workspace in the absolute mode
+  uint32_t* tile_sums;   // workspace: escapes per tile of kVScanTile chunks
+  uint32_t n_tiles;
   splitzip_sizes* sizes;
+  uint32_t hdr[16];      // the header of a stream of this call, words 6..9 (M, total) left 0
   uint8_t dec[16];
   uint8_t lut[256];      // exponent -> code, | 0x80 for an escape
 };
@@ -170,26 +173,54 @@ __global__ __launch_bounds__(kThreads) void v_dense_kernel(const VArgs a) {
   }
 }
 
-// compress pass 2: exclusive scan of the counts, header, sizes record, zero padding.  One workgroup.
-__global__ __launch_bounds__(1024) void v_scan_kernel(const VArgs a) {
-  __shared__ uint32_t s_wave[16];
-  const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const uint64_t per = (a.n_chunks + 1023) / 1024, lo = tid * per, hi = lo + per < a.n_chunks ? lo + per : a.n_chunks;
-  uint32_t sum = 0;
-  for (uint64_t c = lo; c < hi; ++c) sum += a.counts[c];
-  const uint32_t incl = wave_incl_scan(sum);
+constexpr uint32_t kVScanTile = 1024;   // counts per workgroup of the two scan kernels
+
+// sum of 1024 values, one per thread, in every thread (two barriers)
+__device__ inline uint32_t v_block_sum(uint32_t v, uint32_t* s_wave /*16*/, uint32_t& incl_out, uint32_t& before_out) {
+  const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t incl = wave_incl_scan(v);
+  __syncthreads();   // s_wave may still be read from an earlier call
   if (lane == 63) s_wave[wave] = incl;
   __syncthreads();
-  uint32_t before = 0, M = 0;
+  uint32_t before = 0, all = 0;
   for (uint32_t w = 0; w < 16; ++w) {
     if (w < wave) before += s_wave[w];
-    M += s_wave[w];
+    all += s_wave[w];
   }
-  uint32_t run = before + incl - sum;
-  for (uint64_t c = lo; c < hi; ++c) {
-    a.offs[c] = run;
-    run += a.counts[c];
+  incl_out = incl;
+  before_out = before;
+  return all;
+}
+
+// compress pass 2a: the escapes of every tile of 1024 chunks
+__global__ __launch_bounds__(1024) void v_tile_sum_kernel(const VArgs a) {
+  __shared__ uint32_t s_wave[16];
+  const uint64_t c = (uint64_t)blockIdx.x * kVScanTile + threadIdx.x;
+  uint32_t incl, before;
+  const uint32_t all = v_block_sum(c < a.n_chunks ? a.counts[c] : 0u, s_wave, incl, before);
+  if (threadIdx.x == 0) a.tile_sums[blockIdx.x] = all;
+}
+
+// compress pass 2b: exclusive offsets of all chunks; workgroup 0 also writes the header, the sizes record and
+// the zero padding
+__global__ __launch_bounds__(1024) void v_scan_kernel(const VArgs a) {
+  __shared__ uint32_t s_wave[16];
+  const uint32_t tid = threadIdx.x, b = blockIdx.x;
+  // escapes in the tiles before this one, and in all of them
+  uint32_t part = 0, every = 0;
+  for (uint32_t t = tid; t < a.n_tiles; t += 1024) {
+    const uint32_t v = a.tile_sums[t];
+    if (t < b) part += v;
+    every += v;
   }
+  uint32_t incl, before;
+  const uint32_t base = v_block_sum(part, s_wave, incl, before);
+  const uint32_t M = v_block_sum(every, s_wave, incl, before);
+  const uint64_t c = (uint64_t)b * kVScanTile + tid;
+  const uint32_t mine = c < a.n_chunks ? a.counts[c] : 0u;
+  v_block_sum(mine, s_wave, incl, before);
+  if (c < a.n_chunks) a.offs[c] = base + before + incl - mine;
+  if (b != 0) return;
   if (tid == 0) a.offs[a.n_chunks] = M;
 
   const uint64_t pos_sec = a256((uint64_t)a.pos_bytes * M), total = a.off_pos + pos_sec + M;
@@ -202,20 +233,14 @@ __global__ __launch_bounds__(1024) void v_scan_kernel(const VArgs a) {
   for (uint64_t i = code_cov + tid; i < a256(a.code_bytes); i += 1024) a.out[a.off_code + i] = 0;
   for (uint64_t i = (uint64_t)a.pos_bytes * M + tid; i < pos_sec; i += 1024)
     if (a.off_pos + i < a.capacity) a.out[a.off_pos + i] = 0;
+  if (tid < 16) {
+    uint32_t w = a.hdr[tid];
+    if (tid == 6) w = M;
+    if (tid == 8) w = (uint32_t)total;
+    if (tid == 9) w = (uint32_t)(total >> 32);
+    reinterpret_cast<uint32_t*>(a.out)[tid] = w;
+  }
   if (tid == 0) {
-    // header (see include/splitzip.h)
-    uint32_t h[16];
-    h[0] = 0x31505A53u;   // "SZP1"
-    h[1] = 2u | (a.dtype << 16) | (a.code_bits << 24);
-    h[2] = a.mode == SPLITZIP_ESC_ABS32 ? 0u : 1u << a.chunk_shift;
-    h[3] = a.mode | (a.k << 8);
-    h[4] = (uint32_t)a.n; h[5] = (uint32_t)(a.n >> 32);
-    h[6] = M; h[7] = 0;
-    h[8] = (uint32_t)total; h[9] = (uint32_t)(total >> 32);
-    for (int i = 0; i < 4; ++i)
-      h[10 + i] = a.dec[4 * i] | (a.dec[4 * i + 1] << 8) | (a.dec[4 * i + 2] << 16) | ((uint32_t)a.dec[4 * i + 3] << 24);
-    h[14] = h[15] = 0;
-    for (int i = 0; i < 16; ++i) reinterpret_cast<uint32_t*>(a.out)[i] = h[i];
     a.sizes->total_bytes = total;
     a.sizes->n_escapes = M;
     a.sizes->status = total > a.capacity ? SPLITZIP_STATUS_OVERFLOW : 0u;
@@ -286,64 +311,83 @@ __device__ inline void v_flag_bad(const VArgs& a) {
   if (a.sizes) atomicOr(&a.sizes->status, SPLITZIP_STATUS_BAD_STREAM);
 }
 
-// header against the call; returns M through *m_out
-__device__ inline bool v_check_header(const VArgs& a, uint32_t* m_out) {
-  const uint32_t* h = reinterpret_cast<const uint32_t*>(a.in);
-  const uint64_t n = h[4] | ((uint64_t)h[5] << 32), M = h[6] | ((uint64_t)h[7] << 32), total = h[8] | ((uint64_t)h[9] << 32);
-  bool ok = h[0] == 0x31505A53u && h[1] == (2u | (a.dtype << 16) | (a.code_bits << 24)) &&
-            h[2] == (a.mode == SPLITZIP_ESC_ABS32 ? 0u : 1u << a.chunk_shift) && h[3] == (a.mode | (a.k << 8)) && n == a.n &&
-            M <= n && h[14] == 0 && h[15] == 0;
-  for (int i = 0; i < 16; ++i) ok = ok && a.in[40 + i] == ((uint32_t)i < a.k ? a.dec[i] : 0);
-  ok = ok && total == a.off_pos + a256(a.pos_bytes * M) + M && total <= a.capacity;
+// The header as every wave reads it: lane i < 16 holds word i.  Words 6..9 (M, total) are checked against the
+// layout, the others against what the call expects.  Wave-uniform result; M through m_out.
+__device__ inline bool v_check_header(const VArgs& a, uint32_t hw, int lane, uint32_t* m_out) {
+  const bool word_ok = lane >= 16 || (lane >= 6 && lane <= 9) || hw == a.hdr[lane & 15];
+  const uint64_t M = __builtin_amdgcn_readlane(hw, 6) | ((uint64_t)__builtin_amdgcn_readlane(hw, 7) << 32);
+  const uint64_t total = __builtin_amdgcn_readlane(hw, 8) | ((uint64_t)__builtin_amdgcn_readlane(hw, 9) << 32);
   *m_out = (uint32_t)M;
-  return ok;
+  return __builtin_amdgcn_ballot_w64(!word_ok) == 0 && M <= a.n && total == a.off_pos + a256(a.pos_bytes * M) + M &&
+         total <= a.capacity;
 }
 
-// One block of 1024 elements per wave: the block's plane bytes into LDS, decode into an LDS tile,
-// correct the tile from the chunk's escape records (or, in the sentinel mode, fetch the exponent of
-// every sentinel while decoding), store the tile.  In the absolute mode the correction is left to
-// v_scatter_kernel.
+// One block of 1024 elements per wave.  Everything that depends on nothing -- the header, the offsets of the
+// block's chunks, the block's slices of both planes -- is fetched at once; the escape records of the chunks
+// follow as soon as the offsets are known and travel while the planes are decoded into an LDS tile; the records
+// are applied to the tile (in the sentinel mode the exponent of every sentinel is fetched while decoding
+// instead), and the tile is stored.  In the absolute mode the correction is left to v_scatter_kernel.
 template <int DT, int CB>
 __global__ __launch_bounds__(kThreads) void v_decode_kernel(const VArgs a) {
   using F = VFmt<DT>;
   __shared__ uint8_t s_dec[16];
-  __shared__ uint32_t s_hdr[2];
   __shared__ __attribute__((aligned(16))) uint8_t s_sm[kWaves][128 * F::SB];
   __shared__ __attribute__((aligned(16))) uint8_t s_code[kWaves][128 * CB];
   __shared__ __attribute__((aligned(16))) uint8_t s_tile[kWaves][kVBlock * F::ES];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (tid < 16) s_dec[tid] = (uint32_t)tid < a.k ? a.dec[tid] : 0;
-  if (tid == 0) {
-    uint32_t M;
-    const bool ok = v_check_header(a, &M);
-    s_hdr[0] = ok;
-    s_hdr[1] = M;
-    if (blockIdx.x == 0) {
-      if (a.sizes) {
-        const uint32_t* h = reinterpret_cast<const uint32_t*>(a.in);
-        a.sizes->total_bytes = h[8] | ((uint64_t)h[9] << 32);
-        a.sizes->n_escapes = M;
-      }
-      if (!ok) v_flag_bad(a);
-    }
-  }
-  __syncthreads();
-  if (!s_hdr[0]) return;   // nothing of a stream with a bad header is followed
-  const uint32_t M = s_hdr[1];
-  const uint64_t off_val = a.off_pos + a256((uint64_t)a.pos_bytes * M);
   const uint64_t blk = (uint64_t)blockIdx.x * kWaves + wave;
-  if (blk * kVBlock >= a.n) return;
+  const bool live = blk * kVBlock < a.n;
+  const uint32_t per_blk = kVBlock >> a.chunk_shift, chunk = 1u << a.chunk_shift;
+  const uint64_t c_first = blk * per_blk;
+
+  const uint32_t hw = lane < 16 ? reinterpret_cast<const uint32_t*>(a.in)[lane] : 0u;
+  uint32_t my_off = 0;   // lane q holds the offset of chunk c_first + q
+  if (live && a.mode != SPLITZIP_ESC_ABS32 && (uint32_t)lane <= per_blk && c_first + lane <= a.n_chunks)
+    my_off = a.offs[c_first + lane];
+  if (live) {
+    // the block's slices of both planes (whole dwords; the sections are padded, so nothing past them is read)
+    const uint64_t sm0 = blk * (kVBlock / 8) * F::SB, code0 = blk * (kVBlock / 8) * CB;
+    for (uint32_t i = lane; i < 32u * F::SB; i += 64)
+      reinterpret_cast<uint32_t*>(s_sm[wave])[i] =
+          sm0 + 4 * i < a256(a.sm_bytes) ? ld_stream(reinterpret_cast<const uint32_t*>(a.in + a.off_sm + sm0) + i) : 0u;
+    for (uint32_t i = lane; i < 32u * CB; i += 64)
+      reinterpret_cast<uint32_t*>(s_code[wave])[i] =
+          code0 + 4 * i < a256(a.code_bytes) ? ld_stream(reinterpret_cast<const uint32_t*>(a.in + a.off_code + code0) + i) : 0u;
+  }
+  uint32_t M;
+  const bool ok = v_check_header(a, hw, lane, &M);
+  if (blockIdx.x == 0 && tid == 0) {
+    if (a.sizes) {
+      a.sizes->total_bytes = __builtin_amdgcn_readlane(hw, 8) | ((uint64_t)__builtin_amdgcn_readlane(hw, 9) << 32);
+      a.sizes->n_escapes = M;
+    }
+    if (!ok) v_flag_bad(a);
+  }
+  __syncthreads();         // s_dec
+  if (!ok || !live) return;   // nothing of a stream with a bad header is followed
+  const uint64_t off_val = a.off_pos + a256((uint64_t)a.pos_bytes * M);
   const uint32_t sentinel = (1u << CB) - 1u;
   bool bad = false;
 
-  // the block's slices of both planes (whole dwords; the sections are padded, so nothing past them is read)
-  const uint64_t sm0 = blk * (kVBlock / 8) * F::SB, code0 = blk * (kVBlock / 8) * CB;
-  for (uint32_t i = lane; i < 32u * F::SB; i += 64)
-    reinterpret_cast<uint32_t*>(s_sm[wave])[i] =
-        sm0 + 4 * i < a256(a.sm_bytes) ? ld_stream(reinterpret_cast<const uint32_t*>(a.in + a.off_sm + sm0) + i) : 0u;
-  for (uint32_t i = lane; i < 32u * CB; i += 64)
-    reinterpret_cast<uint32_t*>(s_code[wave])[i] =
-        code0 + 4 * i < a256(a.code_bytes) ? ld_stream(reinterpret_cast<const uint32_t*>(a.in + a.off_code + code0) + i) : 0u;
+  // chunk-relative records: the first 64 of every chunk of the block are fetched now
+  uint32_t rec_p[4] = {0, 0, 0, 0}, rec_e[4] = {0, 0, 0, 0}, rec_lo[4], rec_n[4] = {0, 0, 0, 0};
+  if (a.mode == SPLITZIP_ESC_POS) {
+#pragma unroll
+    for (uint32_t q = 0; q < 4; ++q) {
+      rec_lo[q] = 0;
+      if (q >= per_blk || c_first + q >= a.n_chunks) continue;
+      const uint32_t lo = __builtin_amdgcn_readlane(my_off, q), hi = __builtin_amdgcn_readlane(my_off, q + 1);
+      const uint64_t first = (c_first + q) << a.chunk_shift, len = first + chunk <= a.n ? chunk : a.n - first;
+      if (hi < lo || hi - lo > len || hi > M) { bad = true; continue; }
+      rec_lo[q] = lo;
+      rec_n[q] = hi - lo;
+      if ((uint32_t)lane < hi - lo) {
+        rec_p[q] = a.pos_bytes == 2 ? reinterpret_cast<const uint16_t*>(a.in + a.off_pos)[lo + lane] : a.in[a.off_pos + lo + lane];
+        rec_e[q] = a.in[off_val + lo + lane];
+      }
+    }
+  }
 
   v_lds_settle();
   uint32_t carry = 0;
@@ -368,13 +412,16 @@ __global__ __launch_bounds__(kThreads) void v_decode_kernel(const VArgs a) {
       const uint32_t t31 = __builtin_amdgcn_readlane(incl, 31), t63 = __builtin_amdgcn_readlane(incl, 63);
       uint32_t r, r_end;
       if (a.chunk_shift == 10) {
-        r = a.offs[blk] + carry + incl - cnt;
-        r_end = a.offs[blk + 1];
+        r = __builtin_amdgcn_readlane(my_off, 0) + carry + incl - cnt;
+        r_end = __builtin_amdgcn_readlane(my_off, 1);
         carry = t63;
       } else {
-        const uint64_t c = (g >> 8) + (lane >> 5);
-        r = (c < a.n_chunks ? a.offs[c] : 0u) + incl - cnt - (lane >= 32 ? t31 : 0u);
-        r_end = c < a.n_chunks ? a.offs[c + 1] : 0u;
+        const uint32_t q = 2 * s + (lane >> 5);   // the chunk of this half-wave, inside the block
+        const bool there = c_first + q < a.n_chunks;
+        const uint32_t o0 = __builtin_amdgcn_readlane(my_off, 2 * s), o1 = __builtin_amdgcn_readlane(my_off, 2 * s + 1),
+                       o2 = __builtin_amdgcn_readlane(my_off, 2 * s + 2);
+        r = there ? (lane < 32 ? o0 : o1) + incl - cnt - (lane >= 32 ? t31 : 0u) : 0u;
+        r_end = there ? (lane < 32 ? o1 : o2) : 0u;
       }
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
@@ -399,16 +446,16 @@ __global__ __launch_bounds__(kThreads) void v_decode_kernel(const VArgs a) {
   v_lds_settle();
   if (a.mode == SPLITZIP_ESC_POS) {
     // the records of the block's chunks, one lane each, straight into the tile
-    const uint32_t per_blk = kVBlock >> a.chunk_shift, chunk = 1u << a.chunk_shift;
-    for (uint32_t q = 0; q < per_blk; ++q) {
-      const uint64_t c = blk * per_blk + q;
-      if (c >= a.n_chunks) break;
-      const uint32_t lo = a.offs[c], hi = a.offs[c + 1];
-      const uint64_t first = c << a.chunk_shift, len = first + chunk <= a.n ? chunk : a.n - first;
-      if (hi < lo || hi - lo > len || hi > M) { bad = true; continue; }
-      for (uint32_t i = lo + lane; i < hi; i += 64) {
-        const uint32_t p = a.pos_bytes == 2 ? reinterpret_cast<const uint16_t*>(a.in + a.off_pos)[i] : a.in[a.off_pos + i];
-        const uint32_t e = a.in[off_val + i];
+#pragma unroll
+    for (uint32_t q = 0; q < 4; ++q) {
+      if (q >= per_blk || rec_n[q] == 0) continue;
+      const uint64_t first = (c_first + q) << a.chunk_shift, len = first + chunk <= a.n ? chunk : a.n - first;
+      for (uint32_t i = lane; i < rec_n[q]; i += 64) {
+        uint32_t p = rec_p[q], e = rec_e[q];
+        if (i >= 64) {   // a chunk with more than 64 escapes: the rest is fetched here
+          p = a.pos_bytes == 2 ? reinterpret_cast<const uint16_t*>(a.in + a.off_pos)[rec_lo[q] + i] : a.in[a.off_pos + rec_lo[q] + i];
+          e = a.in[off_val + rec_lo[q] + i];
+        }
         if (p >= len || e >= (uint32_t)F::EXPS) { bad = true; continue; }
         const uint32_t at = q * chunk + p;
         if (F::ES == 2) {
@@ -442,8 +489,9 @@ __global__ __launch_bounds__(kThreads) void v_decode_kernel(const VArgs a) {
 template <int DT>
 __global__ __launch_bounds__(kThreads) void v_scatter_kernel(const VArgs a) {
   using F = VFmt<DT>;
+  const int lane = threadIdx.x & 63;
   uint32_t M;
-  if (!v_check_header(a, &M)) return;
+  if (!v_check_header(a, lane < 16 ? reinterpret_cast<const uint32_t*>(a.in)[lane] : 0u, lane, &M)) return;
   const uint64_t off_val = a.off_pos + a256(4ull * M);
   bool bad = false;
   for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < M; i += (uint64_t)gridDim.x * kThreads) {
