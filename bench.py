@@ -327,11 +327,56 @@ def main():
         for key in ("roofline", "roofline_decompress"):
             result[key]["traffic"] = measured_traffic(args.workload, result[key]["kernel"])
 
+    result["paged"] = paged_calls(dtype, xs[0][1], books[0], ws, c1_us, d1_us)
     if not args.no_variants:
         result["format_variants"] = format_variants()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(args, dtype, xs, books, comps, totals, n, es)
     print(json.dumps(result))
+
+
+def paged_calls(dtype, x, cb, ws, c_contig_us, d_contig_us, block_tokens=16, reps=10):
+    """splitzip_compress_paged / _decompress_paged on the workload's first tensor, held in a pool of shuffled pages
+    of block_tokens tokens each (the layout of a paged KV cache); the stream must equal the contiguous call's."""
+    n, es = x.numel(), x.element_size()
+    be = block_tokens * 1024
+    n_blocks = (n + be - 1) // be
+    stride = be * es
+    perm = torch.randperm(n_blocks, generator=torch.Generator().manual_seed(7)).to(torch.int32)
+    pool = torch.empty(n_blocks * be, dtype=x.dtype, device="cuda")
+    padded = torch.zeros(n_blocks * be, dtype=x.dtype, device="cuda")
+    padded[:n] = x
+    pool.view(n_blocks, be)[perm.long().cuda()] = padded.view(n_blocks, be)
+    table = perm.cuda()
+    src = sz.Paged(pool, table, be, stride, 0, n_blocks)
+    cap = (sz.total_bytes(n, n * 3 // 100, dtype) + 255) // 256 * 256
+    out_p = torch.empty(cap, dtype=torch.uint8, device="cuda")
+    out_c = torch.empty(cap, dtype=torch.uint8, device="cuda")
+    rec = sz.new_sizes()
+    sz.compress_paged(src, n, cb, out_p, ws, rec)
+    sz.compress(x, cb, out_c, ws, rec)
+    torch.cuda.synchronize()
+    total = sz.read_sizes(rec)[0]
+    assert torch.equal(out_p[:total], out_c[:total]), "paged stream differs from the contiguous one"
+    pool2 = torch.zeros_like(pool)
+    dst = sz.Paged(pool2, table, be, stride, 0, n_blocks)
+    sz.decompress_paged(out_p, total, n, cb, dst)
+    torch.cuda.synchronize()
+    assert torch.equal(pool2, pool), "paged round trip differs"
+    e0, e1, e2 = ev(), ev(), ev()
+    e0.record()
+    for _ in range(reps):
+        sz.compress_paged(src, n, cb, out_p, ws, rec)
+    e1.record()
+    for _ in range(reps):
+        sz.decompress_paged(out_p, total, n, cb, dst)
+    e2.record()
+    torch.cuda.synchronize()
+    c_us, d_us = e0.elapsed_time(e1) * 1e3 / reps, e1.elapsed_time(e2) * 1e3 / reps
+    return {"how": f"one tensor in a pool of {n_blocks} shuffled pages of {block_tokens} tokens, one call each way",
+            "compress_GBps": round(n * es / c_us * 1e-3, 1), "decompress_GBps": round(n * es / d_us * 1e-3, 1),
+            "contiguous_compress_GBps": round(n * es / c_contig_us * 1e-3, 1),
+            "contiguous_decompress_GBps": round(n * es / d_contig_us * 1e-3, 1)}
 
 
 def format_variants(tokens=32768, reps=10):

@@ -224,6 +224,43 @@ int splitzip_decompress_batch(const splitzip_ditem* items, uint32_t n_items, int
 int splitzip_traffic_probe(const void* d_src, size_t read_bytes, void* d_dst, size_t write_bytes,
                            void* stream);
 
+/* ---- Paged and strided tensors ------------------------------------------------
+ *
+ * Serving stacks keep the KV cache in fixed-size pages of a pool and find a
+ * sequence's pages through a block table (the serving integration of the
+ * paper's section 4, "Experiments", moves such caches).  These calls compress a tensor straight
+ * out of such a pool and decompress straight into one: the stream is exactly
+ * that of splitzip_compress on the gathered, contiguous tensor.  Logical
+ * element i lives at
+ *   d_pool + d_block_table[i / block_elems] * page_stride_bytes + offset_bytes
+ *          + (i % block_elems) * element size.
+ * A tensor whose tokens are strided (token stride above heads x head_dim) is
+ * the same thing with one token per page and the identity as the table. */
+typedef struct {
+  void* d_pool;                  /* device address of the pool, 16-byte aligned */
+  const uint32_t* d_block_table; /* device array of n_blocks page indices into the pool; entries at or above
+                                    n_pool_blocks are clamped to the last page (never an access outside the pool) */
+  uint32_t n_blocks;             /* entries of the table; n_blocks * block_elems >= n_elems */
+  uint32_t n_pool_blocks;        /* pages in the pool */
+  uint32_t block_elems;          /* elements of this tensor per page: a power of two, at least 1024 */
+  uint32_t reserved;             /* 0 */
+  uint64_t page_stride_bytes;    /* distance between pages of the pool, a multiple of 16 */
+  uint64_t offset_bytes;         /* where this tensor's elements start inside every page (the V half, a layer's
+                                    slot), a multiple of 16; offset + block_elems * element size <= page stride */
+} splitzip_paged;
+
+/* splitzip_compress / splitzip_decompress with the words in a paged pool.  All
+ * other arguments, the stream format, the sizes record and the error codes are
+ * those of the contiguous calls; a description that breaks one of the rules
+ * above gives SPLITZIP_ERR_INVALID_ARG.  Decompress writes the n_elems words
+ * and nothing else of the pool. */
+int splitzip_compress_paged(const splitzip_paged* src, uint64_t n_elems, int dtype, const splitzip_codebook* cb,
+                            void* d_out, size_t out_capacity, void* d_workspace, size_t workspace_bytes,
+                            splitzip_sizes* d_sizes, void* stream);
+int splitzip_decompress_paged(const void* d_comp, size_t comp_bytes, uint64_t n_elems, int dtype,
+                              const splitzip_codebook* cb, const splitzip_paged* dst, splitzip_sizes* d_sizes,
+                              void* stream);
+
 /* ---- Format variants of the paper's ablations --------------------------------
  *
  * The same codec with its knobs turned the way the ablations turn them

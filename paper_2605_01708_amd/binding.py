@@ -50,6 +50,12 @@ class _CDItem(C.Structure):
                 ("cb", C.POINTER(_CCodebook))]
 
 
+class _CPaged(C.Structure):
+    _fields_ = [("d_pool", C.c_void_p), ("d_block_table", C.c_void_p), ("n_blocks", C.c_uint32),
+                ("n_pool_blocks", C.c_uint32), ("block_elems", C.c_uint32), ("reserved", C.c_uint32),
+                ("page_stride_bytes", C.c_uint64), ("offset_bytes", C.c_uint64)]
+
+
 class Variant(C.Structure):
     """splitzip_variant: one of the formats of the paper's ablations"""
     _fields_ = [("dtype", C.c_uint32), ("code_bits", C.c_uint32), ("k", C.c_uint32), ("escape_mode", C.c_uint32),
@@ -109,6 +115,11 @@ def lib():
         L.splitzip_decompress_batch.argtypes = [C.POINTER(_CDItem), C.c_uint32, i, vp, vp]
         L.splitzip_traffic_probe.restype = i
         L.splitzip_traffic_probe.argtypes = [vp, sz, vp, sz, vp]
+        pgp = C.POINTER(_CPaged)
+        L.splitzip_compress_paged.restype = i
+        L.splitzip_compress_paged.argtypes = [pgp, u64, i, cbp, vp, sz, vp, sz, vp, vp]
+        L.splitzip_decompress_paged.restype = i
+        L.splitzip_decompress_paged.argtypes = [vp, sz, u64, i, cbp, pgp, vp, vp]
         vrp = C.POINTER(Variant)
         L.splitzip_variant_supported.restype = i
         L.splitzip_variant_supported.argtypes = [vrp]
@@ -437,3 +448,37 @@ def variant_decompress(comp: torch.Tensor, comp_bytes: int, n_elems: int, v: Var
     _check(lib().splitzip_variant_decompress(comp.data_ptr(), comp_bytes, n_elems, C.byref(v), C.byref(cb.c),
                                              out.data_ptr(), sizes.data_ptr() if sizes is not None else None,
                                              _stream_ptr(stream)), "splitzip_variant_decompress")
+
+
+# ---- paged / strided tensors ------------------------------------------------------------------------
+
+class Paged:
+    """splitzip_paged: a tensor whose words sit in pages of a pool, found through a block table.
+
+    pool: device tensor (any dtype) holding the pages; block_table: device int32/uint32 tensor of page indices;
+    block_elems: elements of this tensor per page; page_stride_bytes / offset_bytes as in include/splitzip.h."""
+
+    def __init__(self, pool: torch.Tensor, block_table: torch.Tensor, block_elems: int, page_stride_bytes: int,
+                 offset_bytes: int = 0, n_pool_blocks: int | None = None):
+        if block_table.element_size() != 4 or not block_table.is_contiguous():
+            raise ValueError("block_table must be a contiguous tensor of 32-bit page indices")
+        self.pool, self.block_table = pool, block_table            # keep the tensors alive
+        pool_bytes = pool.numel() * pool.element_size()
+        npool = pool_bytes // page_stride_bytes if n_pool_blocks is None else n_pool_blocks
+        self.c = _CPaged(pool.data_ptr(), block_table.data_ptr(), block_table.numel(), npool, block_elems, 0,
+                         page_stride_bytes, offset_bytes)
+
+
+def compress_paged(src: Paged, n_elems: int, cb: Codebook, out: torch.Tensor, workspace: Workspace,
+                   sizes: torch.Tensor, stream=None, capacity: int | None = None) -> None:
+    cap = out.numel() * out.element_size() if capacity is None else capacity
+    _check(lib().splitzip_compress_paged(C.byref(src.c), n_elems, cb.dtype, C.byref(cb.c), out.data_ptr(), cap,
+                                         workspace.buf.data_ptr(), workspace.nbytes, sizes.data_ptr(),
+                                         _stream_ptr(stream)), "splitzip_compress_paged")
+
+
+def decompress_paged(comp: torch.Tensor, comp_bytes: int, n_elems: int, cb: Codebook, dst: Paged,
+                     sizes: torch.Tensor | None = None, stream=None) -> None:
+    _check(lib().splitzip_decompress_paged(comp.data_ptr(), comp_bytes, n_elems, cb.dtype, C.byref(cb.c),
+                                           C.byref(dst.c), sizes.data_ptr() if sizes is not None else None,
+                                           _stream_ptr(stream)), "splitzip_decompress_paged")

@@ -41,9 +41,38 @@ __host__ __device__ inline Layout make_layout(uint64_t n, int dtype) {
   return L;
 }
 
+// Where the words of a tensor live: one contiguous run, or pages of 2^page_shift elements (a multiple of the
+// chunk, so a chunk never straddles two pages) found through a table of page indices into a pool.
+struct Words {
+  uint8_t* base;           // contiguous: the tensor; paged: the pool plus the tensor's offset inside every page
+  const uint32_t* table;   // null for a contiguous tensor; else logical page -> index of the page in the pool
+  uint64_t page_stride;    // bytes from one page of the pool to the next
+  uint32_t page_shift;     // log2 of the elements per page, >= 10
+  uint32_t n_pages;        // pages in the pool: indices read from the table are clamped below this
+};
+
+__host__ __device__ inline Words contiguous_words(const void* p) {
+  Words w;
+  w.base = static_cast<uint8_t*>(const_cast<void*>(p));
+  w.table = nullptr;
+  w.page_stride = 0;
+  w.page_shift = 10;
+  w.n_pages = 0;
+  return w;
+}
+
 // ---------------------------------------------------------------------------
 // device helpers
 // ---------------------------------------------------------------------------
+
+// address of element i (ES bytes each)
+template <int ES>
+__device__ inline uint8_t* words_at(const Words& w, uint64_t i) {
+  if (!w.table) return w.base + ES * i;
+  uint32_t page = w.table[i >> w.page_shift];
+  if (page >= w.n_pages) page = w.n_pages - 1;   // a bad table entry never leaves the pool
+  return w.base + (uint64_t)page * w.page_stride + ES * (i & ((1ull << w.page_shift) - 1));
+}
 
 template <typename T>
 __device__ inline T ld_stream(const T* p) { return __builtin_nontemporal_load(p); }

@@ -9,17 +9,17 @@
 
 // what the dense pass and the trailer need to know of one tensor and its stream
 struct Planes {
-  const uint8_t* in;
+  Words w;        // the tensor's words (read only here)
   uint8_t* out;
   uint64_t n, capacity;
   uint64_t off_tab, off_sm, off_code, off_pos, sm_bytes, code_bytes;
   uint32_t n_chunks, dtype;
 };
 
-__host__ __device__ inline Planes make_planes(const void* in, void* out, uint64_t n, uint64_t capacity, int dtype) {
+__host__ __device__ inline Planes make_planes(const Words& in, void* out, uint64_t n, uint64_t capacity, int dtype) {
   const Layout L = make_layout(n, dtype);
   Planes p;
-  p.in = static_cast<const uint8_t*>(in);
+  p.w = in;
   p.out = static_cast<uint8_t*>(out);
   p.n = n;
   p.capacity = capacity;
@@ -119,13 +119,13 @@ __device__ inline void load_chunk_bf16(const Planes& a, uint64_t cbase, int lane
     if (!FULL) nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 8 ? a.n - g0 : 8);
     if (FULL) {
       // chunk pointer (wave-uniform) + a 32-bit lane offset: no 64-bit vector arithmetic
-      const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(a.in + 2 * cbase) + (uint32_t)(h * 64 + lane));
+      const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(words_at<2>(a.w, cbase)) + (uint32_t)(h * 64 + lane));
       w[h][0] = v.x; w[h][1] = v.y; w[h][2] = v.z; w[h][3] = v.w;
     } else if (nvalid == 8) {
-      const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(a.in + 2 * g0));
+      const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(words_at<2>(a.w, g0)));
       w[h][0] = v.x; w[h][1] = v.y; w[h][2] = v.z; w[h][3] = v.w;
     } else {
-      const uint16_t* p = reinterpret_cast<const uint16_t*>(a.in) + g0;
+      const uint16_t* p = reinterpret_cast<const uint16_t*>(words_at<2>(a.w, g0));
 #pragma unroll
       for (int d = 0; d < 4; ++d) {
         const uint32_t lo = (uint32_t)(2 * d) < nvalid ? p[2 * d] : 0u;
@@ -207,13 +207,13 @@ __device__ inline void load_chunk_e5m2(const Planes& a, uint64_t cbase, int lane
   uint32_t nvalid = 16;
   if (!FULL) nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 16 ? a.n - g0 : 16);
   if (FULL) {
-    const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(a.in + cbase) + (uint32_t)lane);
+    const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(words_at<1>(a.w, cbase)) + (uint32_t)lane);
     w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
   } else if (nvalid == 16) {
-    const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(a.in + g0));
+    const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(words_at<1>(a.w, g0)));
     w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
   } else {
-    const uint8_t* p = a.in + g0;
+    const uint8_t* p = words_at<1>(a.w, g0);
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
       uint32_t x = 0;
@@ -689,7 +689,7 @@ __global__ __launch_bounds__(T) void compress_batch_kernel(const CompressBatchAr
   __syncthreads();
 
   uint64_t* const ring = a.state + (uint64_t)grp * kRing * G;   // this group's slots
-  Planes Pprev = make_planes(nullptr, nullptr, 0, 0, (int)a.dtype);
+  Planes Pprev = make_planes(contiguous_words(nullptr), nullptr, 0, 0, (int)a.dtype);
   uint32_t prev_count = 0, prev_r0 = 0, prev_nb = 0, prev_item = 0;
   // this group's tensors: grp, grp + n_groups, ...; seq counts them
   for (uint32_t seq = 0;; ++seq) {
@@ -707,7 +707,7 @@ __global__ __launch_bounds__(T) void compress_batch_kernel(const CompressBatchAr
     pf.enabled = wave == 0 && seq > 0 && G <= 256 && a.await_extra == 0;
     pf.issued = false;
     if (have) {
-      P = make_planes(a.item[i].in, a.item[i].out, a.item[i].n, a.item[i].capacity, (int)a.dtype);
+      P = make_planes(contiguous_words(a.item[i].in), a.item[i].out, a.item[i].n, a.item[i].capacity, (int)a.dtype);
       my_range(0, P.n_chunks, G, b, r0, nb);
       wave_count = dense_pass<NW, F>(P, lut[a.lut_of[i]], park, L, r0, nb, wave, lane, pf);
       if (lane == 0) s_red[wave] = wave_count;

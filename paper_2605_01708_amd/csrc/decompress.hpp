@@ -9,7 +9,7 @@
 
 struct DecompressArgs {
   const uint8_t* comp;
-  uint8_t* out;
+  Words w;                 // where the decoded words go
   uint64_t n, comp_bytes;
   splitzip_sizes* sizes;   // nullable
   uint64_t off_tab, off_sm, off_code, off_pos, sm_bytes, code_bytes;
@@ -78,9 +78,9 @@ __device__ inline void store_chunk_bf16(const DecompressArgs& a, uint64_t cbase,
     uint32_t nvalid = 8;
     if (!FULL) nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 8 ? a.n - g0 : 8);
     if (FULL || nvalid == 8) {
-      st_stream(reinterpret_cast<u32x4*>(a.out + 2 * g0), u32x4{o[4 * h], o[4 * h + 1], o[4 * h + 2], o[4 * h + 3]});
+      st_stream(reinterpret_cast<u32x4*>(FULL ? words_at<2>(a.w, cbase) + 2 * (h * kHalf + lane * 8) : words_at<2>(a.w, g0)), u32x4{o[4 * h], o[4 * h + 1], o[4 * h + 2], o[4 * h + 3]});
     } else {
-      uint16_t* q = reinterpret_cast<uint16_t*>(a.out) + g0;
+      uint16_t* q = reinterpret_cast<uint16_t*>(words_at<2>(a.w, g0));
 #pragma unroll
       for (int d = 0; d < 4; ++d) {
         if ((uint32_t)(2 * d) < nvalid) q[2 * d] = (uint16_t)o[4 * h + d];
@@ -131,9 +131,9 @@ __device__ inline void store_chunk_e5m2(const DecompressArgs& a, uint64_t cbase,
   uint32_t nvalid = 16;
   if (!FULL) nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 16 ? a.n - g0 : 16);
   if (FULL || nvalid == 16) {
-    st_stream(reinterpret_cast<u32x4*>(a.out + g0), u32x4{o[0], o[1], o[2], o[3]});
+    st_stream(reinterpret_cast<u32x4*>(FULL ? words_at<1>(a.w, cbase) + lane * 16 : words_at<1>(a.w, g0)), u32x4{o[0], o[1], o[2], o[3]});
   } else {
-    uint8_t* q = a.out + g0;
+    uint8_t* q = words_at<1>(a.w, g0);
 #pragma unroll
     for (int j = 0; j < 16; ++j)
       if ((uint32_t)j < nvalid) q[j] = (uint8_t)(o[j >> 2] >> (8 * (j & 3)));
@@ -168,7 +168,7 @@ struct DBf16 {
   // the same on the tensor in memory: exponent field := val, sign and mantissa from the stream
   __device__ static inline bool patch(const DecompressArgs& a, uint64_t i, uint32_t val) {
     const uint32_t sa = a.comp[a.off_sm + i];
-    reinterpret_cast<uint16_t*>(a.out)[i] = (uint16_t)(((sa & 0x80u) << 8) | (val << 7) | (sa & 0x7fu));
+    *reinterpret_cast<uint16_t*>(words_at<2>(a.w, i)) = (uint16_t)(((sa & 0x80u) << 8) | (val << 7) | (sa & 0x7fu));
     return true;
   }
 };
@@ -193,7 +193,7 @@ struct DE5m2 {
     uint32_t two = p[0];
     if ((bit & 7) > 5) two |= (uint32_t)p[1] << 8;   // the field straddles a byte; the next byte is inside the plane
     const uint32_t sa = (two >> (bit & 7)) & 7u;
-    a.out[i] = (uint8_t)(((sa & 4u) << 5) | (val << 2) | (sa & 3u));
+    *words_at<1>(a.w, i) = (uint8_t)(((sa & 4u) << 5) | (val << 2) | (sa & 3u));
     return true;
   }
 };
@@ -299,7 +299,7 @@ __global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const Decomp
   if (blockIdx.x >= (n_tiles ? n_tiles : 1u)) return;
   DecompressArgs a;
   a.comp = it.comp;
-  a.out = it.out;
+  a.w = contiguous_words(it.out);
   a.n = it.n;
   a.comp_bytes = it.comp_bytes;
   a.sizes = b.sizes;

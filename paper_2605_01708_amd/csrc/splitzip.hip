@@ -453,10 +453,30 @@ int splitzip_workspace_init(void* d_workspace, size_t workspace_bytes, void* str
 
 namespace {
 
-// splitzip_compress with the codebook either on the host (cb) or in device memory (d_cb)
-int compress_impl(const void* d_in, uint64_t n_elems, int dtype, const splitzip_codebook* cb, const splitzip_codebook* d_cb,
+// a splitzip_paged as the kernels see it; false if the description is not usable for n_elems words of dtype
+bool paged_words(const splitzip_paged* pg, uint64_t n_elems, int dtype, Words* w) {
+  if (!pg || !pg->d_pool || !pg->d_block_table || !aligned16(pg->d_pool) ||
+      (reinterpret_cast<uintptr_t>(pg->d_block_table) & 3u))
+    return false;
+  const uint64_t es = dtype == SPLITZIP_BF16 ? 2 : 1;
+  const uint32_t be = pg->block_elems;
+  if (be < kChunk || (be & (be - 1u)) || pg->n_pool_blocks == 0) return false;
+  if ((pg->page_stride_bytes & 15u) || (pg->offset_bytes & 15u)) return false;
+  if (pg->offset_bytes + (uint64_t)be * es > pg->page_stride_bytes) return false;       // the tensor's part of a page fits the page
+  if ((uint64_t)pg->n_blocks * be < n_elems) return false;                                // the table covers the tensor
+  w->base = static_cast<uint8_t*>(pg->d_pool) + pg->offset_bytes;
+  w->table = pg->d_block_table;
+  w->page_stride = pg->page_stride_bytes;
+  w->page_shift = (uint32_t)__builtin_ctz(be);
+  w->n_pages = pg->n_pool_blocks;
+  return true;
+}
+
+// splitzip_compress with the codebook either on the host (cb) or in device memory (d_cb); the words contiguous or paged
+int compress_impl(const Words& in, uint64_t n_elems, int dtype, const splitzip_codebook* cb, const splitzip_codebook* d_cb,
                   void* d_out, size_t out_capacity, void* d_workspace, size_t workspace_bytes, splitzip_sizes* d_sizes,
                   void* stream) {
+  const void* d_in = in.base;
   if (!dtype_ok(dtype) || !d_out || !d_workspace || !d_sizes || (n_elems && !d_in)) return SPLITZIP_ERR_INVALID_ARG;
   if (!aligned16(d_in) || !aligned16(d_out) || !aligned16(d_workspace) ||
       (reinterpret_cast<uintptr_t>(d_sizes) & 7u))
@@ -469,7 +489,7 @@ int compress_impl(const void* d_in, uint64_t n_elems, int dtype, const splitzip_
   const Layout L = make_layout(n_elems, dtype);
   CompressArgs a;
   memset(&a, 0, sizeof a);
-  a.p = make_planes(d_in, d_out, n_elems, out_capacity, dtype);
+  a.p = make_planes(in, d_out, n_elems, out_capacity, dtype);
   uint8_t* ws = static_cast<uint8_t*>(d_workspace);
   a.ws_hdr = reinterpret_cast<uint32_t*>(ws);
   a.state = reinterpret_cast<uint64_t*>(ws + kWsHeaderBytes);
@@ -525,9 +545,10 @@ int compress_impl(const void* d_in, uint64_t n_elems, int dtype, const splitzip_
   return SPLITZIP_OK;
 }
 
-// splitzip_decompress with the codebook either on the host (cb) or in device memory (d_cb)
+// splitzip_decompress with the codebook either on the host (cb) or in device memory (d_cb); the words contiguous or paged
 int decompress_impl(const void* d_comp, size_t comp_bytes, uint64_t n_elems, int dtype, const splitzip_codebook* cb,
-                    const splitzip_codebook* d_cb, void* d_out, splitzip_sizes* d_sizes, void* stream) {
+                    const splitzip_codebook* d_cb, const Words& out, splitzip_sizes* d_sizes, void* stream) {
+  const void* d_out = out.base;
   if (!dtype_ok(dtype) || !d_comp || (n_elems && !d_out)) return SPLITZIP_ERR_INVALID_ARG;
   if (!aligned16(d_comp) || !aligned16(d_out) || (reinterpret_cast<uintptr_t>(d_sizes) & 7u))
     return SPLITZIP_ERR_INVALID_ARG;
@@ -539,7 +560,7 @@ int decompress_impl(const void* d_comp, size_t comp_bytes, uint64_t n_elems, int
   DecompressArgs a;
   memset(&a, 0, sizeof a);
   a.comp = static_cast<const uint8_t*>(d_comp);
-  a.out = static_cast<uint8_t*>(d_out);
+  a.w = out;
   a.n = n_elems;
   a.comp_bytes = comp_bytes;
   a.sizes = d_sizes;
@@ -568,12 +589,12 @@ extern "C" {
 int splitzip_compress(const void* d_in, uint64_t n_elems, int dtype, const splitzip_codebook* cb,
                       void* d_out, size_t out_capacity, void* d_workspace, size_t workspace_bytes,
                       splitzip_sizes* d_sizes, void* stream) {
-  return compress_impl(d_in, n_elems, dtype, cb, nullptr, d_out, out_capacity, d_workspace, workspace_bytes, d_sizes, stream);
+  return compress_impl(contiguous_words(d_in), n_elems, dtype, cb, nullptr, d_out, out_capacity, d_workspace, workspace_bytes, d_sizes, stream);
 }
 
 int splitzip_decompress(const void* d_comp, size_t comp_bytes, uint64_t n_elems, int dtype,
                         const splitzip_codebook* cb, void* d_out, splitzip_sizes* d_sizes, void* stream) {
-  return decompress_impl(d_comp, comp_bytes, n_elems, dtype, cb, nullptr, d_out, d_sizes, stream);
+  return decompress_impl(d_comp, comp_bytes, n_elems, dtype, cb, nullptr, contiguous_words(d_out), d_sizes, stream);
 }
 
 int splitzip_codebook_device(const uint64_t* d_hist, int dtype, splitzip_codebook* d_cb, void* stream) {
@@ -584,17 +605,33 @@ int splitzip_codebook_device(const uint64_t* d_hist, int dtype, splitzip_codeboo
   return hipGetLastError() == hipSuccess ? SPLITZIP_OK : SPLITZIP_ERR_HIP;
 }
 
+int splitzip_compress_paged(const splitzip_paged* src, uint64_t n_elems, int dtype, const splitzip_codebook* cb,
+                            void* d_out, size_t out_capacity, void* d_workspace, size_t workspace_bytes,
+                            splitzip_sizes* d_sizes, void* stream) {
+  Words w;
+  if (!dtype_ok(dtype) || !paged_words(src, n_elems, dtype, &w)) return SPLITZIP_ERR_INVALID_ARG;
+  return compress_impl(w, n_elems, dtype, cb, nullptr, d_out, out_capacity, d_workspace, workspace_bytes, d_sizes, stream);
+}
+
+int splitzip_decompress_paged(const void* d_comp, size_t comp_bytes, uint64_t n_elems, int dtype,
+                              const splitzip_codebook* cb, const splitzip_paged* dst, splitzip_sizes* d_sizes,
+                              void* stream) {
+  Words w;
+  if (!dtype_ok(dtype) || !paged_words(dst, n_elems, dtype, &w)) return SPLITZIP_ERR_INVALID_ARG;
+  return decompress_impl(d_comp, comp_bytes, n_elems, dtype, cb, nullptr, w, d_sizes, stream);
+}
+
 int splitzip_compress_dcb(const void* d_in, uint64_t n_elems, int dtype, const splitzip_codebook* d_cb,
                           void* d_out, size_t out_capacity, void* d_workspace, size_t workspace_bytes,
                           splitzip_sizes* d_sizes, void* stream) {
   if (!d_cb) return SPLITZIP_ERR_INVALID_ARG;
-  return compress_impl(d_in, n_elems, dtype, nullptr, d_cb, d_out, out_capacity, d_workspace, workspace_bytes, d_sizes, stream);
+  return compress_impl(contiguous_words(d_in), n_elems, dtype, nullptr, d_cb, d_out, out_capacity, d_workspace, workspace_bytes, d_sizes, stream);
 }
 
 int splitzip_decompress_dcb(const void* d_comp, size_t comp_bytes, uint64_t n_elems, int dtype,
                             const splitzip_codebook* d_cb, void* d_out, splitzip_sizes* d_sizes, void* stream) {
   if (!d_cb) return SPLITZIP_ERR_INVALID_ARG;
-  return decompress_impl(d_comp, comp_bytes, n_elems, dtype, nullptr, d_cb, d_out, d_sizes, stream);
+  return decompress_impl(d_comp, comp_bytes, n_elems, dtype, nullptr, d_cb, contiguous_words(d_out), d_sizes, stream);
 }
 
 int splitzip_compress_batch(const splitzip_item* items, uint32_t n_items, int dtype, void* d_workspace,
