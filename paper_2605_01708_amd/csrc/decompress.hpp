@@ -14,6 +14,7 @@ struct DecompressArgs {
   splitzip_sizes* sizes;   // nullable
   uint64_t off_tab, off_sm, off_code, off_pos, sm_bytes, code_bytes;
   uint32_t n_chunks, n_tiles, cpw, dtype;
+  uint32_t reg_patch_max;  // chunks with at most this many escapes are corrected in registers, the others in an LDS tile
   const uint8_t* d_dec;    // nullable: the 16 decode entries in device memory, used instead of dec
   uint8_t dec[16];
 };
@@ -165,10 +166,23 @@ struct DBf16 {
     patch_regs<8>(r.o, 4u * (pos >> 9) + (e >> 1), (uint32_t)lane == (q >> 3), 0x7f80u << sh, val << (7u + sh));
     return true;
   }
-  // the same on the tensor in memory: exponent field := val, sign and mantissa from the stream
-  __device__ static inline bool patch(const DecompressArgs& a, uint64_t i, uint32_t val) {
-    const uint32_t sa = a.comp[a.off_sm + i];
-    *reinterpret_cast<uint16_t*>(words_at<2>(a.w, i)) = (uint16_t)(((sa & 0x80u) << 8) | (val << 7) | (sa & 0x7fu));
+  // The chunk as an LDS tile in element order (2 KB), for chunks with many escapes: registers -> tile, the
+  // correction of one element by one lane, tile -> registers.
+  static constexpr uint32_t kTileDwords = 512;
+  __device__ static inline void to_tile(const Out& r, uint32_t* tile, int lane) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) reinterpret_cast<u32x4*>(tile)[h * 64 + lane] = u32x4{r.o[4 * h], r.o[4 * h + 1], r.o[4 * h + 2], r.o[4 * h + 3]};
+  }
+  __device__ static inline void from_tile(Out& r, const uint32_t* tile, int lane) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const u32x4 v = reinterpret_cast<const u32x4*>(tile)[h * 64 + lane];
+      r.o[4 * h] = v.x; r.o[4 * h + 1] = v.y; r.o[4 * h + 2] = v.z; r.o[4 * h + 3] = v.w;
+    }
+  }
+  __device__ static inline bool patch_tile(uint32_t* tile, uint32_t pos, uint32_t val) {
+    uint16_t* t = reinterpret_cast<uint16_t*>(tile) + pos;
+    *t = (uint16_t)((*t & ~0x7f80u) | (val << 7));
     return true;
   }
 };
@@ -186,23 +200,32 @@ struct DE5m2 {
     patch_regs<4>(r.o, e >> 2, (uint32_t)lane == (pos >> 4), 0x7cu << sh, val << (2u + sh));
     return true;
   }
-  __device__ static inline bool patch(const DecompressArgs& a, uint64_t i, uint32_t val) {
+  static constexpr uint32_t kTileDwords = 256;
+  __device__ static inline void to_tile(const Out& r, uint32_t* tile, int lane) {
+    reinterpret_cast<u32x4*>(tile)[lane] = u32x4{r.o[0], r.o[1], r.o[2], r.o[3]};
+  }
+  __device__ static inline void from_tile(Out& r, const uint32_t* tile, int lane) {
+    const u32x4 v = reinterpret_cast<const u32x4*>(tile)[lane];
+    r.o[0] = v.x; r.o[1] = v.y; r.o[2] = v.z; r.o[3] = v.w;
+  }
+  __device__ static inline bool patch_tile(uint32_t* tile, uint32_t pos, uint32_t val) {
     if (val > 31u) return false;
-    const uint64_t bit = 3 * i;
-    const uint8_t* p = a.comp + a.off_sm + (bit >> 3);
-    uint32_t two = p[0];
-    if ((bit & 7) > 5) two |= (uint32_t)p[1] << 8;   // the field straddles a byte; the next byte is inside the plane
-    const uint32_t sa = (two >> (bit & 7)) & 7u;
-    *words_at<1>(a.w, i) = (uint8_t)(((sa & 4u) << 5) | (val << 2) | (sa & 3u));
+    uint8_t* t = reinterpret_cast<uint8_t*>(tile) + pos;
+    *t = (uint8_t)((*t & ~0x7cu) | (val << 2));
     return true;
   }
 };
 
-constexpr uint32_t kRegPatchMax = 32;   // escapes of a chunk that are applied in registers, before the store
+constexpr uint32_t kRegPatchDefault = 4;   // escapes of a chunk that are still applied in registers
 
-// one workgroup: tile `tile` of the tensor described by a (4 waves x cpw chunks)
+// a wave's LDS accesses are carried out in program order; this keeps the compiler from reordering accesses it
+// takes for unrelated because they go through different types
+__device__ inline void lds_settle() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+// one workgroup: tile `tile` of the tensor described by a (4 waves x cpw chunks); lds_chunk: kTileDwords per wave
 template <typename F>
-__device__ inline void decompress_tile(const DecompressArgs& a, const uint8_t* dec, uint32_t tile, uint32_t* tbl) {
+__device__ inline void decompress_tile(const DecompressArgs& a, const uint8_t* dec, uint32_t tile, uint32_t* tbl,
+                                       uint32_t* lds_chunk) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const uint32_t* tab = reinterpret_cast<const uint32_t*>(a.comp + a.off_tab);
@@ -235,11 +258,13 @@ __device__ inline void decompress_tile(const DecompressArgs& a, const uint8_t* d
     const bool esc_valid = hi >= lo && hi - lo <= clen && hi <= M;
     const uint32_t cnt = esc_valid ? hi - lo : 0u;
     if (!esc_valid && lane == 0) flag_bad(a);
-    // a few escapes (the usual case): their records are fetched while the planes are on their way,
-    // and applied to the decoded words in registers before the one store
-    const bool in_regs = cnt > 0 && cnt <= kRegPatchMax;
+    // The chunk's records (the first 64 of them) are fetched while the planes are on their way.  A few
+    // escapes, the usual case, are applied to the decoded words in registers, one after the other; more
+    // of them are applied in parallel, one lane each, to the chunk laid out in LDS.  Either way every
+    // word is stored once.
+    const bool in_regs = cnt > 0 && cnt <= a.reg_patch_max;
     uint32_t pos = 0, val = 0;
-    if (in_regs && (uint32_t)lane < cnt) {
+    if ((uint32_t)lane < cnt) {
       pos = pos_arr[lo + lane];
       val = val_arr[lo + lane];
     }
@@ -255,25 +280,32 @@ __device__ inline void decompress_tile(const DecompressArgs& a, const uint8_t* d
         }
       }
     }
+    if (cnt > a.reg_patch_max) {
+      uint32_t* t = lds_chunk + (uint32_t)wave * F::kTileDwords;
+      F::to_tile(r, t, lane);
+      lds_settle();
+      for (uint32_t j = lane; j < cnt; j += 64) {
+        uint32_t p = pos, v = val;
+        if (j >= 64) {
+          p = pos_arr[lo + j];
+          v = val_arr[lo + j];
+        }
+        if (p >= clen || !F::patch_tile(t, p, v)) flag_bad(a);
+      }
+      lds_settle();
+      F::from_tile(r, t, lane);
+      lds_settle();   // the tile is written again for the wave's next chunk
+    }
     if (full) F::template store<true>(a, cbase, lane, r);
     else F::template store<false>(a, cbase, lane, r);
-    if (cnt > kRegPatchMax) {
-      // many escapes: sparse overwrite of the tensor in memory by the wave that wrote the chunk,
-      // once its dense stores have completed
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      for (uint32_t j = lo + lane; j < hi; j += 64) {
-        const uint32_t p = pos_arr[j];
-        const uint32_t v = val_arr[j];
-        if (p >= clen || !F::patch(a, cbase + p, v)) flag_bad(a);
-      }
-    }
   }
 }
 
 template <typename F>
 __global__ __launch_bounds__(kThreads) void decompress_kernel(const DecompressArgs a) {
   __shared__ uint32_t tbl[256];
-  decompress_tile<F>(a, a.d_dec ? a.d_dec : a.dec, blockIdx.x, tbl);
+  __shared__ __attribute__((aligned(16))) uint32_t lds_chunk[kWaves * F::kTileDwords];
+  decompress_tile<F>(a, a.d_dec ? a.d_dec : a.dec, blockIdx.x, tbl, lds_chunk);
 }
 
 // several streams in one launch: blockIdx.y picks the stream, blockIdx.x the tile
@@ -286,13 +318,14 @@ struct DecompressBatchArgs {
   DBatchItem item[kBatchMax];
   uint8_t dec_of[kBatchMax];
   splitzip_sizes* sizes;   // nullable; one record, status bits sticky
-  uint32_t cpw, dtype;
+  uint32_t cpw, dtype, reg_patch_max;
   uint8_t dec[kBatchLuts][16];
 };
 
 template <typename F>
 __global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const DecompressBatchArgs b) {
   __shared__ uint32_t tbl[256];
+  __shared__ __attribute__((aligned(16))) uint32_t lds_chunk[kWaves * F::kTileDwords];
   const DBatchItem it = b.item[blockIdx.y];
   const Layout L = make_layout(it.n, (int)b.dtype);
   const uint32_t n_tiles = (uint32_t)((L.n_chunks + (uint64_t)kWaves * b.cpw - 1) / (kWaves * b.cpw));
@@ -309,7 +342,8 @@ __global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const Decomp
   a.n_tiles = n_tiles;
   a.cpw = b.cpw;
   a.dtype = b.dtype;
-  decompress_tile<F>(a, b.dec[b.dec_of[blockIdx.y]], blockIdx.x, tbl);   // a.dec stays unset: the table comes from the kernel arguments
+  a.reg_patch_max = b.reg_patch_max;
+  decompress_tile<F>(a, b.dec[b.dec_of[blockIdx.y]], blockIdx.x, tbl, lds_chunk);   // a.dec stays unset: the table comes from the kernel arguments
 }
 
 #endif  // SPLITZIP_DECOMPRESS_HPP

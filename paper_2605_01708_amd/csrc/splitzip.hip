@@ -570,6 +570,8 @@ int decompress_impl(const void* d_comp, size_t comp_bytes, uint64_t n_elems, int
   static const int tiles_per_cu = env_int("SPLITZIP_DECOMPRESS_TILES_PER_CU", 0);
   a.cpw = cpw_env ? (uint32_t)cpw_env : pick_decompress_cpw(L.n_chunks, dtype, tiles_per_cu);
   if (a.cpw > kMaxCpw) a.cpw = kMaxCpw;
+  static const int reg_patch = env_int("SPLITZIP_DECOMPRESS_REG_PATCH", (int)kRegPatchDefault);
+  a.reg_patch_max = (uint32_t)reg_patch;
   a.n_chunks = (uint32_t)L.n_chunks;
   a.n_tiles = (uint32_t)((L.n_chunks + (uint64_t)kWaves * a.cpw - 1) / (kWaves * a.cpw));
   a.dtype = (uint32_t)dtype;
@@ -764,6 +766,8 @@ int splitzip_decompress_batch(const splitzip_ditem* items, uint32_t n_items, int
     a.dtype = (uint32_t)dtype;
     a.cpw = cpw_env ? (uint32_t)cpw_env : pick_decompress_cpw(chunks_all, dtype, tiles_per_cu);
     if (a.cpw > kMaxCpw) a.cpw = kMaxCpw;
+    static const int reg_patch = env_int("SPLITZIP_DECOMPRESS_REG_PATCH", (int)kRegPatchDefault);
+    a.reg_patch_max = (uint32_t)reg_patch;
     uint64_t gx = (chunks_max + (uint64_t)kWaves * a.cpw - 1) / (kWaves * a.cpw);
     if (gx < 1) gx = 1;
     const dim3 grid((unsigned)gx, k);
