@@ -234,10 +234,15 @@ __device__ inline uint32_t process_chunk_e5m2(const Planes& a, const uint16_t* l
 #pragma unroll
   for (int d = 0; d < 4; ++d) {
     r[d] = pack3_e5m2(w[d]);
-    const uint32_t e0 = (w[d] >> 2) & 31u, e1 = (w[d] >> 10) & 31u, e2 = (w[d] >> 18) & 31u, e3 = (w[d] >> 26) & 31u;
+    // entry of a byte: at byte offset (byte & 0x7c) of the table (see kLutShift)
+    const uint8_t* lb = reinterpret_cast<const uint8_t*>(lut);
+    const uint32_t t0 = *reinterpret_cast<const uint16_t*>(lb + (w[d] & 0x7cu));
+    const uint32_t t1 = *reinterpret_cast<const uint16_t*>(lb + ((w[d] >> 8) & 0x7cu));
+    const uint32_t t2 = *reinterpret_cast<const uint16_t*>(lb + ((w[d] >> 16) & 0x7cu));
+    const uint32_t t3 = *reinterpret_cast<const uint16_t*>(lb + ((w[d] >> 24) & 0x7cu));
     // low byte: code pair; high byte: flag pair in the same nibble layout
-    u[2 * d] = (uint32_t)lut[e0] + ((uint32_t)lut[e1] << 4);
-    u[2 * d + 1] = (uint32_t)lut[e2] + ((uint32_t)lut[e3] << 4);
+    u[2 * d] = t0 + (t1 << 4);
+    u[2 * d + 1] = t2 + (t3 << 4);
   }
   // the lane's 48 plane bits: lo holds bits 0..31, hi bits 32..47
   uint32_t lo = r[0] | (r[1] << 12) | (r[2] << 24), hi = (r[2] >> 8) | (r[3] << 4);
@@ -313,6 +318,7 @@ __device__ inline uint32_t process_chunk_e5m2(const Planes& a, const uint16_t* l
 struct Bf16 {
   struct Regs { uint32_t w[2][4]; };
   static constexpr uint32_t kPerStep = 2;   // chunks (2 KB each) a wave takes per step of the dense pass
+  static constexpr int kLutShift = 0;       // the LDS encode table holds the entry of exponent e in slot e
   // a chunk goes the fast way if it is complete (then nothing of a pad is its business: N is a multiple of 1024 there)
   __device__ static inline bool full(const Planes& a, uint64_t cbase) { return cbase + kChunk <= a.n; }
   template <bool FULL>
@@ -326,6 +332,9 @@ struct Bf16 {
 struct E5m2 {
   struct Regs { uint32_t w[4]; };
   static constexpr uint32_t kPerStep = 1;   // 1 KB each: a second chunk per step costs more in registers and code than it hides
+  // The LDS encode table holds the entry of exponent e in slots 2 e and 2 e + 1: its byte offset is then
+  // the word's byte with the sign and mantissa bits masked off, one instruction per element.
+  static constexpr int kLutShift = 1;
   // the tensor's last chunk always goes the careful way: 384 plane bytes per chunk leave a pad behind an odd chunk count
   __device__ static inline bool full(const Planes& a, uint64_t cbase) { return cbase + kChunk < a.n; }
   template <bool FULL>
@@ -557,7 +566,10 @@ __global__ __launch_bounds__(T) void compress_kernel(const CompressArgs a) {
   uint32_t* park = reinterpret_cast<uint32_t*>(&s_park[tid]);
   const RangeLds L{stage_pk[wave], stage_val[wave], s_off, s_wstart};
 
-  if (tid < 256) lut[tid] = a.d_cb ? (a.d_cb->member[tid] ? (uint16_t)a.d_cb->enc[tid] : (uint16_t)0x100u) : a.lut[tid];
+  if (tid < 256) {
+    const int e = tid >> F::kLutShift;   // LDS slot tid holds the entry of exponent e
+    lut[tid] = a.d_cb ? (a.d_cb->member[e] ? (uint16_t)a.d_cb->enc[e] : (uint16_t)0x100u) : a.lut[e];
+  }
   const uint8_t* dec = a.d_cb ? a.d_cb->dec : a.dec;
   const uint32_t epoch = ld_agent(&a.ws_hdr[0]);
   const uint32_t base = (a.flags & kSegFirst) ? 0u : ld_agent(&a.ws_hdr[1]);
@@ -682,7 +694,7 @@ __global__ __launch_bounds__(T) void compress_batch_kernel(const CompressBatchAr
   const uint32_t grp = blockIdx.x / G, b = blockIdx.x % G;
   uint32_t* park = reinterpret_cast<uint32_t*>(&s_park[tid]);
 
-  for (int i = tid; i < (int)(kBatchLuts * 256); i += T) lut[i >> 8][i & 255] = a.lut[i >> 8][i & 255];
+  for (int i = tid; i < (int)(kBatchLuts * 256); i += T) lut[i >> 8][i & 255] = a.lut[i >> 8][(i & 255) >> F::kLutShift];
   const uint32_t epoch = ld_agent(&a.ws_hdr[0]);
   const uint32_t err_before = b == 0 ? ld_agent(&a.ws_hdr[2]) : 0u;
   if (tid == 0) s_misc[3] = 0;   // set once an exchange was given up: later ones are not waited for
