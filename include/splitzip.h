@@ -142,11 +142,14 @@ size_t splitzip_compress_bound(uint64_t n_elems, int dtype);
  * up to that size; each call leaves it ready for the next.  Calls that share
  * a workspace must not overlap in time (same stream, or otherwise ordered).
  * All workgroups of a compress launch wait for one another, so they must be
- * resident together: one launch never asks for more than the device holds,
- * but compress calls running concurrently on several streams of one device
- * share that room -- keep them to a handful.  A wait that does not end within
- * two seconds gives up with SPLITZIP_STATUS_INTERNAL; re-initialise the
- * workspace after that. */
+ * resident together.  One launch never asks for more than the device holds.
+ * Launches that run at the same time on different streams of one device share
+ * that room: two single-tensor compress calls always fit side by side (each
+ * with its own workspace); a batch compress call fills the device alone, so
+ * order it against every other compress call (same stream, or events).  A wait
+ * that does not end within two seconds gives up with
+ * SPLITZIP_STATUS_INTERNAL instead of hanging; re-initialise the workspace
+ * after that.  Decompress calls and the variant calls have no such rule. */
 size_t splitzip_workspace_bytes(uint64_t n_elems, int dtype);
 int splitzip_workspace_init(void* d_workspace, size_t workspace_bytes, void* stream);
 

@@ -317,7 +317,10 @@ __device__ inline uint32_t process_chunk_e5m2(const Planes& a, const uint16_t* l
 // the two formats as seen by the compress kernel
 struct Bf16 {
   struct Regs { uint32_t w[2][4]; };
-  static constexpr uint32_t kPerStep = 2;   // chunks (2 KB each) a wave takes per step of the dense pass
+  // Chunks (2 KB each) a wave takes per step of the dense pass in the batch kernel.  The single-tensor kernel
+  // takes one: two cost it more than 64 registers per lane, and with 64 two of its launches fit a compute unit
+  // side by side, so that two compress calls on different streams can never starve each other of room.
+  static constexpr uint32_t kBatchPerStep = 2;
   static constexpr int kLutShift = 0;       // the LDS encode table holds the entry of exponent e in slot e
   // a chunk goes the fast way if it is complete (then nothing of a pad is its business: N is a multiple of 1024 there)
   __device__ static inline bool full(const Planes& a, uint64_t cbase) { return cbase + kChunk <= a.n; }
@@ -331,7 +334,7 @@ struct Bf16 {
 };
 struct E5m2 {
   struct Regs { uint32_t w[4]; };
-  static constexpr uint32_t kPerStep = 1;   // 1 KB each: a second chunk per step costs more in registers and code than it hides
+  static constexpr uint32_t kBatchPerStep = 1;   // 1 KB each: a second chunk per step costs more in registers and code than it hides
   // The LDS encode table holds the entry of exponent e in slots 2 e and 2 e + 1: its byte offset is then
   // the word's byte with the sign and mantissa bits masked off, one instruction per element.
   static constexpr int kLutShift = 1;
@@ -404,15 +407,14 @@ struct NoHook {
   __device__ inline void operator()() const {}
 };
 
-// dense pass of one wave over its chunks of the range, F::kPerStep of them per step; the loads of
+// dense pass of one wave over its chunks of the range, S of them per step; the loads of
 // the next step are issued before this step's chunks are worked on (what a wave has in flight at
-// that point is what keeps the memory system busy: 2 KB per wave for either format).  `mid` is
+// that point is what keeps the memory system busy: 2 to 4 KB per wave).  `mid` is
 // called once, half way through (not at all by a wave without chunks).  Returns the wave's
 // escape count.
-template <int NW, typename F, typename Hook>
+template <int NW, typename F, uint32_t S, typename Hook>
 __device__ inline uint32_t dense_pass(const Planes& P, const uint16_t* lut, uint32_t* park, const RangeLds& L,
                                       uint32_t r0, uint32_t nb, int wave, int lane, Hook& mid) {
-  constexpr uint32_t S = F::kPerStep;
   uint32_t wave_count = 0;
   const uint32_t mine = nb > (uint32_t)wave ? (nb - wave + NW - 1) / NW : 0u;   // chunks of this wave
   const uint32_t mid_it = mine / 2;
@@ -549,7 +551,7 @@ __device__ inline GlobalSink final_sink(const Planes& P, uint32_t M) {
 // clearing) and one wave reads the words of all workgroups: the counts before b give its offset,
 // all of them give M.  The wait ends when the slowest workgroup has published.
 template <int T, typename F>
-__global__ __launch_bounds__(T) void compress_kernel(const CompressArgs a) {
+__global__ __launch_bounds__(T, (T == 1024 ? 8 : 1)) void compress_kernel(const CompressArgs a) {
   constexpr int NW = T / 64;
   static_assert(kMaxRange <= 256 && NW >= 4 && NW <= 16, "one wave scans the range, four chunks per lane");
   __shared__ uint16_t lut[256];
@@ -580,7 +582,7 @@ __global__ __launch_bounds__(T) void compress_kernel(const CompressArgs a) {
   uint32_t r0, nb;
   my_range(a.seg_chunk0, a.seg_chunks, gridDim.x, b, r0, nb);
   NoHook no_hook;
-  const uint32_t wave_count = dense_pass<NW, F>(a.p, lut, park, L, r0, nb, wave, lane, no_hook);
+  const uint32_t wave_count = dense_pass<NW, F, 1>(a.p, lut, park, L, r0, nb, wave, lane, no_hook);
   if (lane == 0) s_red[wave] = wave_count;
   __syncthreads();
 
@@ -721,7 +723,7 @@ __global__ __launch_bounds__(T) void compress_batch_kernel(const CompressBatchAr
     if (have) {
       P = make_planes(contiguous_words(a.item[i].in), a.item[i].out, a.item[i].n, a.item[i].capacity, (int)a.dtype);
       my_range(0, P.n_chunks, G, b, r0, nb);
-      wave_count = dense_pass<NW, F>(P, lut[a.lut_of[i]], park, L, r0, nb, wave, lane, pf);
+      wave_count = dense_pass<NW, F, F::kBatchPerStep>(P, lut[a.lut_of[i]], park, L, r0, nb, wave, lane, pf);
       if (lane == 0) s_red[wave] = wave_count;
     }
     __syncthreads();

@@ -441,6 +441,29 @@ def run_env_case(case, **env):
     assert r.returncode == 0 and "CASE-OK" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
 
 
+def test_two_compress_calls_on_two_streams_at_once():
+    """two single-tensor compress calls, each with its own workspace, may run side by side: both launches fit the
+    device together, so neither can starve the other of room (streams and results as in the serial case)"""
+    n = 32768 * 1024 // 4
+    cb_or = calibrated(sz.BF16)
+    cb = gpu_codebook(cb_or)
+    xs = [kv_synth.kv_bf16(n // 1024, 0, layer, "K", device="cuda") for layer in (2, 5)]
+    refs = [oracle.compress(kv_synth.to_numpy_words(x), cb_or) for x in xs]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    wss = [sz.Workspace(n, sz.BF16) for _ in range(2)]
+    outs = [torch.empty(sz.compress_bound(n, sz.BF16), dtype=torch.uint8, device="cuda") for _ in range(2)]
+    recs = [sz.new_sizes() for _ in range(2)]
+    torch.cuda.synchronize()
+    for rep in range(20):
+        for k in range(2):
+            sz.compress(xs[k], cb, outs[k], wss[k], recs[k], stream=streams[k])
+    torch.cuda.synchronize()
+    for k in range(2):
+        ref, m = refs[k]
+        assert sz.read_sizes(recs[k]) == (ref.size, m, 0)
+        assert np.array_equal(outs[k][: ref.size].cpu().numpy(), ref)
+
+
 def test_tensor_that_takes_several_launches():
     """a small grid (4 workgroups) makes a 5 Mi-element tensor take one launch per segment plus the finishing one"""
     run_env_case("several_launches", SPLITZIP_COMPRESS_MAX_WGS=4)
