@@ -65,13 +65,18 @@ __host__ __device__ inline Words contiguous_words(const void* p) {
 // device helpers
 // ---------------------------------------------------------------------------
 
-// address of element i (ES bytes each)
+// pool page of the chunk with index `chunk` (only for a paged tensor)
+__device__ inline uint32_t page_of_chunk(const Words& w, uint64_t chunk) {
+  const uint32_t page = w.table[chunk >> (w.page_shift - 10)];
+  return page < w.n_pages ? page : w.n_pages - 1;   // a bad table entry never leaves the pool
+}
+
+// address of the first element of the chunk that starts at element cbase; `page` is its pool page, read earlier
+// with page_of_chunk (ignored for a contiguous tensor)
 template <int ES>
-__device__ inline uint8_t* words_at(const Words& w, uint64_t i) {
-  if (!w.table) return w.base + ES * i;
-  uint32_t page = w.table[i >> w.page_shift];
-  if (page >= w.n_pages) page = w.n_pages - 1;   // a bad table entry never leaves the pool
-  return w.base + (uint64_t)page * w.page_stride + ES * (i & ((1ull << w.page_shift) - 1));
+__device__ inline uint8_t* chunk_at(const Words& w, uint64_t cbase, uint32_t page) {
+  if (!w.table) return w.base + ES * cbase;
+  return w.base + (uint64_t)page * w.page_stride + ES * (cbase & ((1ull << w.page_shift) - 1));
 }
 
 template <typename T>

@@ -111,7 +111,7 @@ __device__ inline void emit_half_bf16(uint32_t* park, const uint32_t (&w)[4], ui
 // One chunk's words into registers: lane l holds elements [8 l, 8 l + 8) of each half-chunk.
 // Elements past N read as zero.
 template <bool FULL>
-__device__ inline void load_chunk_bf16(const Planes& a, uint64_t cbase, int lane, uint32_t (&w)[2][4]) {
+__device__ inline void load_chunk_bf16(const Planes& a, const uint8_t* cptr, uint64_t cbase, int lane, uint32_t (&w)[2][4]) {
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     const uint64_t g0 = cbase + h * kHalf + lane * 8;   // first element of this lane's group
@@ -119,13 +119,13 @@ __device__ inline void load_chunk_bf16(const Planes& a, uint64_t cbase, int lane
     if (!FULL) nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 8 ? a.n - g0 : 8);
     if (FULL) {
       // chunk pointer (wave-uniform) + a 32-bit lane offset: no 64-bit vector arithmetic
-      const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(words_at<2>(a.w, cbase)) + (uint32_t)(h * 64 + lane));
+      const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(cptr) + (uint32_t)(h * 64 + lane));
       w[h][0] = v.x; w[h][1] = v.y; w[h][2] = v.z; w[h][3] = v.w;
     } else if (nvalid == 8) {
-      const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(words_at<2>(a.w, g0)));
+      const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(cptr + 2 * (g0 - cbase)));
       w[h][0] = v.x; w[h][1] = v.y; w[h][2] = v.z; w[h][3] = v.w;
     } else {
-      const uint16_t* p = reinterpret_cast<const uint16_t*>(words_at<2>(a.w, g0));
+      const uint16_t* p = reinterpret_cast<const uint16_t*>(cptr + 2 * (g0 - cbase));
 #pragma unroll
       for (int d = 0; d < 4; ++d) {
         const uint32_t lo = (uint32_t)(2 * d) < nvalid ? p[2 * d] : 0u;
@@ -202,18 +202,18 @@ __device__ inline uint32_t unpack3_e5m2(uint32_t r) {
 }
 
 template <bool FULL>
-__device__ inline void load_chunk_e5m2(const Planes& a, uint64_t cbase, int lane, uint32_t (&w)[4]) {
+__device__ inline void load_chunk_e5m2(const Planes& a, const uint8_t* cptr, uint64_t cbase, int lane, uint32_t (&w)[4]) {
   const uint64_t g0 = cbase + lane * 16;
   uint32_t nvalid = 16;
   if (!FULL) nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 16 ? a.n - g0 : 16);
   if (FULL) {
-    const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(words_at<1>(a.w, cbase)) + (uint32_t)lane);
+    const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(cptr) + (uint32_t)lane);
     w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
   } else if (nvalid == 16) {
-    const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(words_at<1>(a.w, g0)));
+    const u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(cptr + (g0 - cbase)));
     w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
   } else {
-    const uint8_t* p = words_at<1>(a.w, g0);
+    const uint8_t* p = cptr + (g0 - cbase);
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
       uint32_t x = 0;
@@ -316,6 +316,7 @@ __device__ inline uint32_t process_chunk_e5m2(const Planes& a, const uint16_t* l
 
 // the two formats as seen by the compress kernel
 struct Bf16 {
+  static constexpr int ES = 2;   // bytes per word
   struct Regs { uint32_t w[2][4]; };
   // Chunks (2 KB each) a wave takes per step of the dense pass in the batch kernel.  The single-tensor kernel
   // takes one: two cost it more than 64 registers per lane, and with 64 two of its launches fit a compute unit
@@ -325,7 +326,7 @@ struct Bf16 {
   // a chunk goes the fast way if it is complete (then nothing of a pad is its business: N is a multiple of 1024 there)
   __device__ static inline bool full(const Planes& a, uint64_t cbase) { return cbase + kChunk <= a.n; }
   template <bool FULL>
-  __device__ static inline void load(const Planes& a, uint64_t cbase, int lane, Regs& r) { load_chunk_bf16<FULL>(a, cbase, lane, r.w); }
+  __device__ static inline void load(const Planes& a, const uint8_t* cptr, uint64_t cbase, int lane, Regs& r) { load_chunk_bf16<FULL>(a, cptr, cbase, lane, r.w); }
   template <bool FULL, bool STORE, typename Sink>
   __device__ static inline uint32_t process(const Planes& a, const uint16_t* lut, uint32_t* park, uint64_t cbase,
                                             int lane, const Regs& r, uint32_t base, const Sink& sink) {
@@ -333,6 +334,7 @@ struct Bf16 {
   }
 };
 struct E5m2 {
+  static constexpr int ES = 1;
   struct Regs { uint32_t w[4]; };
   static constexpr uint32_t kBatchPerStep = 1;   // 1 KB each: a second chunk per step costs more in registers and code than it hides
   // The LDS encode table holds the entry of exponent e in slots 2 e and 2 e + 1: its byte offset is then
@@ -341,7 +343,7 @@ struct E5m2 {
   // the tensor's last chunk always goes the careful way: 384 plane bytes per chunk leave a pad behind an odd chunk count
   __device__ static inline bool full(const Planes& a, uint64_t cbase) { return cbase + kChunk < a.n; }
   template <bool FULL>
-  __device__ static inline void load(const Planes& a, uint64_t cbase, int lane, Regs& r) { load_chunk_e5m2<FULL>(a, cbase, lane, r.w); }
+  __device__ static inline void load(const Planes& a, const uint8_t* cptr, uint64_t cbase, int lane, Regs& r) { load_chunk_e5m2<FULL>(a, cptr, cbase, lane, r.w); }
   template <bool FULL, bool STORE, typename Sink>
   __device__ static inline uint32_t process(const Planes& a, const uint16_t* lut, uint32_t* park, uint64_t cbase,
                                             int lane, const Regs& r, uint32_t base, const Sink& sink) {
@@ -419,12 +421,17 @@ __device__ inline uint32_t dense_pass(const Planes& P, const uint16_t* lut, uint
   const uint32_t mine = nb > (uint32_t)wave ? (nb - wave + NW - 1) / NW : 0u;   // chunks of this wave
   const uint32_t mid_it = mine / 2;
   typename F::Regs w[S], nx[S];
+  // paged tensor: the pool pages of all of the wave's chunks at once (lane it <-> its it-th chunk), so that no
+  // table read stands in front of a chunk's loads later
+  uint32_t my_pages = 0;
+  if (P.w.table && (uint32_t)lane < mine) my_pages = page_of_chunk(P.w, r0 + wave + (uint32_t)lane * NW);
   // the wave's it-th chunk into r (nothing if it has no such chunk)
   auto fetch = [&](uint32_t it, typename F::Regs& r) {
     if (it < mine) {
       const uint64_t cbase = (uint64_t)(r0 + wave + it * NW) * kChunk;
-      if (F::full(P, cbase)) F::template load<true>(P, cbase, lane, r);
-      else F::template load<false>(P, cbase, lane, r);
+      const uint8_t* cptr = chunk_at<F::ES>(P.w, cbase, __builtin_amdgcn_readlane(my_pages, it));
+      if (F::full(P, cbase)) F::template load<true>(P, cptr, cbase, lane, r);
+      else F::template load<false>(P, cptr, cbase, lane, r);
     }
   };
 #pragma unroll
@@ -523,11 +530,12 @@ __device__ inline void write_out(const Planes& P, const uint16_t* lut, uint32_t*
     for (uint32_t k = wave; k < nb; k += NW) {
       const uint64_t cbase = (uint64_t)(r0 + k) * kChunk;
       const uint32_t r = prefix + L.s_off[k];
+      const uint8_t* cptr = chunk_at<F::ES>(P.w, cbase, P.w.table ? page_of_chunk(P.w, r0 + k) : 0u);
       if (F::full(P, cbase)) {
-        F::template load<true>(P, cbase, lane, w);
+        F::template load<true>(P, cptr, cbase, lane, w);
         F::template process<true, false>(P, lut, park, cbase, lane, w, r, g);
       } else {
-        F::template load<false>(P, cbase, lane, w);
+        F::template load<false>(P, cptr, cbase, lane, w);
         F::template process<false, false>(P, lut, park, cbase, lane, w, r, g);
       }
     }

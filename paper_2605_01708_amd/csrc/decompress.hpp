@@ -72,16 +72,16 @@ __device__ inline void decode_chunk_bf16(const DecompressArgs& a, const uint32_t
 }
 
 template <bool FULL>
-__device__ inline void store_chunk_bf16(const DecompressArgs& a, uint64_t cbase, int lane, const uint32_t (&o)[8]) {
+__device__ inline void store_chunk_bf16(const DecompressArgs& a, uint8_t* cptr, uint64_t cbase, int lane, const uint32_t (&o)[8]) {
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     const uint64_t g0 = cbase + h * kHalf + lane * 8;
     uint32_t nvalid = 8;
     if (!FULL) nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 8 ? a.n - g0 : 8);
     if (FULL || nvalid == 8) {
-      st_stream(reinterpret_cast<u32x4*>(FULL ? words_at<2>(a.w, cbase) + 2 * (h * kHalf + lane * 8) : words_at<2>(a.w, g0)), u32x4{o[4 * h], o[4 * h + 1], o[4 * h + 2], o[4 * h + 3]});
+      st_stream(reinterpret_cast<u32x4*>(cptr) + (uint32_t)(h * 64 + lane), u32x4{o[4 * h], o[4 * h + 1], o[4 * h + 2], o[4 * h + 3]});
     } else {
-      uint16_t* q = reinterpret_cast<uint16_t*>(words_at<2>(a.w, g0));
+      uint16_t* q = reinterpret_cast<uint16_t*>(cptr + 2 * (g0 - cbase));
 #pragma unroll
       for (int d = 0; d < 4; ++d) {
         if ((uint32_t)(2 * d) < nvalid) q[2 * d] = (uint16_t)o[4 * h + d];
@@ -127,14 +127,14 @@ __device__ inline void decode_chunk_e5m2(const DecompressArgs& a, const uint32_t
 }
 
 template <bool FULL>
-__device__ inline void store_chunk_e5m2(const DecompressArgs& a, uint64_t cbase, int lane, const uint32_t (&o)[4]) {
+__device__ inline void store_chunk_e5m2(const DecompressArgs& a, uint8_t* cptr, uint64_t cbase, int lane, const uint32_t (&o)[4]) {
   const uint64_t g0 = cbase + lane * 16;
   uint32_t nvalid = 16;
   if (!FULL) nvalid = g0 >= a.n ? 0u : (uint32_t)(a.n - g0 < 16 ? a.n - g0 : 16);
   if (FULL || nvalid == 16) {
-    st_stream(reinterpret_cast<u32x4*>(FULL ? words_at<1>(a.w, cbase) + lane * 16 : words_at<1>(a.w, g0)), u32x4{o[0], o[1], o[2], o[3]});
+    st_stream(reinterpret_cast<u32x4*>(cptr) + (uint32_t)lane, u32x4{o[0], o[1], o[2], o[3]});
   } else {
-    uint8_t* q = words_at<1>(a.w, g0);
+    uint8_t* q = cptr + (g0 - cbase);
 #pragma unroll
     for (int j = 0; j < 16; ++j)
       if ((uint32_t)j < nvalid) q[j] = (uint8_t)(o[j >> 2] >> (8 * (j & 3)));
@@ -152,6 +152,7 @@ __device__ inline void patch_regs(uint32_t (&o)[R], uint32_t r, bool mine, uint3
 
 // the two formats as seen by the decompress kernel
 struct DBf16 {
+  static constexpr int ES = 2;   // bytes per word
   struct Out { uint32_t o[8]; };
   // table entry for a code byte: both exponents in place for one dword of output
   __device__ static inline uint32_t table(int cb, const uint8_t* dec) { return ((uint32_t)dec[cb & 15] << 7) | ((uint32_t)dec[cb >> 4] << 23); }
@@ -159,7 +160,7 @@ struct DBf16 {
   template <bool FULL>
   __device__ static inline void decode(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane, Out& r) { decode_chunk_bf16<FULL>(a, tbl, cbase, lane, r.o); }
   template <bool FULL>
-  __device__ static inline void store(const DecompressArgs& a, uint64_t cbase, int lane, const Out& r) { store_chunk_bf16<FULL>(a, cbase, lane, r.o); }
+  __device__ static inline void store(const DecompressArgs& a, uint8_t* cptr, uint64_t cbase, int lane, const Out& r) { store_chunk_bf16<FULL>(a, cptr, cbase, lane, r.o); }
   // the scatter correction of the element at chunk position pos (wave-uniform), in the registers of the lane that holds it
   __device__ static inline bool patch_reg(Out& r, int lane, uint32_t pos, uint32_t val) {
     const uint32_t q = pos & 511u, e = q & 7u, sh = 16u * (e & 1u);
@@ -187,13 +188,14 @@ struct DBf16 {
   }
 };
 struct DE5m2 {
+  static constexpr int ES = 1;
   struct Out { uint32_t o[4]; };
   __device__ static inline uint32_t table(int cb, const uint8_t* dec) { return ((uint32_t)dec[cb & 15] << 2) | ((uint32_t)dec[cb >> 4] << 10); }
   __device__ static inline bool full(const DecompressArgs& a, uint64_t cbase) { return cbase + kChunk < a.n; }
   template <bool FULL>
   __device__ static inline void decode(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane, Out& r) { decode_chunk_e5m2<FULL>(a, tbl, cbase, lane, r.o); }
   template <bool FULL>
-  __device__ static inline void store(const DecompressArgs& a, uint64_t cbase, int lane, const Out& r) { store_chunk_e5m2<FULL>(a, cbase, lane, r.o); }
+  __device__ static inline void store(const DecompressArgs& a, uint8_t* cptr, uint64_t cbase, int lane, const Out& r) { store_chunk_e5m2<FULL>(a, cptr, cbase, lane, r.o); }
   __device__ static inline bool patch_reg(Out& r, int lane, uint32_t pos, uint32_t val) {
     if (val > 31u) return false;
     const uint32_t e = pos & 15u, sh = 8u * (e & 3u);
@@ -235,6 +237,9 @@ __device__ inline void decompress_tile(const DecompressArgs& a, const uint8_t* d
   // <-> its chunk c, one entry more for the end) and M as the table states it
   const uint32_t my_tab = (uint32_t)lane <= cpw && wave_chunk0 + lane <= a.n_chunks ? tab[wave_chunk0 + lane] : 0u;
   uint32_t M = tab[a.n_chunks];
+  // paged tensor: the pool pages of the wave's chunks, lane c <-> its chunk c
+  uint32_t my_pages = 0;
+  if (a.w.table && (uint32_t)lane < cpw && wave_chunk0 + lane < a.n_chunks) my_pages = page_of_chunk(a.w, wave_chunk0 + lane);
   tbl[tid] = F::table(tid, dec);
 
   // escapes are only trusted if their sections lie inside the stream
@@ -296,8 +301,9 @@ __device__ inline void decompress_tile(const DecompressArgs& a, const uint8_t* d
       F::from_tile(r, t, lane);
       lds_settle();   // the tile is written again for the wave's next chunk
     }
-    if (full) F::template store<true>(a, cbase, lane, r);
-    else F::template store<false>(a, cbase, lane, r);
+    uint8_t* cptr = chunk_at<F::ES>(a.w, cbase, __builtin_amdgcn_readlane(my_pages, c));
+    if (full) F::template store<true>(a, cptr, cbase, lane, r);
+    else F::template store<false>(a, cptr, cbase, lane, r);
   }
 }
 
