@@ -264,6 +264,18 @@ int splitzip_decompress_paged(const void* d_comp, size_t comp_bytes, uint64_t n_
                               const splitzip_codebook* cb, const splitzip_paged* dst, splitzip_sizes* d_sizes,
                               void* stream);
 
+/* The batch calls with every tensor in a paged pool behind ONE block table -- all layers' K and V of one
+ * sequence, the usual layout of a serving stack.  `paging` gives the table and the page geometry
+ * (d_block_table, n_blocks, n_pool_blocks, block_elems, page_stride_bytes; its d_pool is ignored and its
+ * offset_bytes only enters the check that a page holds block_elems words behind it).  item.d_in (item.d_out
+ * for decompress) is the address of the tensor's words in page 0 of ITS pool -- pool base plus the tensor's
+ * offset inside a page -- so every tensor may sit in a pool of its own as long as all share the table and
+ * the geometry.  Everything else as splitzip_compress_batch / splitzip_decompress_batch. */
+int splitzip_compress_batch_paged(const splitzip_item* items, uint32_t n_items, int dtype, const splitzip_paged* paging,
+                                  void* d_workspace, size_t workspace_bytes, splitzip_sizes* d_sizes, void* stream);
+int splitzip_decompress_batch_paged(const splitzip_ditem* items, uint32_t n_items, int dtype, const splitzip_paged* paging,
+                                    splitzip_sizes* d_sizes, void* stream);
+
 /* ---- Format variants of the paper's ablations --------------------------------
  *
  * The same codec with its knobs turned the way the ablations turn them

@@ -120,6 +120,10 @@ def lib():
         L.splitzip_compress_paged.argtypes = [pgp, u64, i, cbp, vp, sz, vp, sz, vp, vp]
         L.splitzip_decompress_paged.restype = i
         L.splitzip_decompress_paged.argtypes = [vp, sz, u64, i, cbp, pgp, vp, vp]
+        L.splitzip_compress_batch_paged.restype = i
+        L.splitzip_compress_batch_paged.argtypes = [C.POINTER(_CItem), C.c_uint32, i, pgp, vp, sz, vp, vp]
+        L.splitzip_decompress_batch_paged.restype = i
+        L.splitzip_decompress_batch_paged.argtypes = [C.POINTER(_CDItem), C.c_uint32, i, pgp, vp, vp]
         vrp = C.POINTER(Variant)
         L.splitzip_variant_supported.restype = i
         L.splitzip_variant_supported.argtypes = [vrp]
@@ -482,3 +486,46 @@ def decompress_paged(comp: torch.Tensor, comp_bytes: int, n_elems: int, cb: Code
     _check(lib().splitzip_decompress_paged(comp.data_ptr(), comp_bytes, n_elems, cb.dtype, C.byref(cb.c),
                                            C.byref(dst.c), sizes.data_ptr() if sizes is not None else None,
                                            _stream_ptr(stream)), "splitzip_decompress_paged")
+
+
+class CompressBatchPaged:
+    """splitzip_compress_batch_paged: tensors k = 0.. in pools that share one block table.  pools[k] is a device tensor
+    whose first byte is the tensor's first word in page 0 (a view into the pool at the tensor's offset); n_elems[k] its
+    logical length; paging a Paged that carries the table and the page geometry."""
+
+    def __init__(self, pools, n_elems, cbs, outs, paging: Paged, capacities=None):
+        if not (len(pools) == len(n_elems) == len(cbs) == len(outs)):
+            raise ValueError("all lists must have the same length")
+        self.n = len(pools)
+        self.dtype = cbs[0].dtype if cbs else BF16
+        self.paging = paging
+        self.items = (_CItem * max(self.n, 1))()
+        self._keep = (list(pools), list(cbs), list(outs))
+        for k, (pool, n, cb, out) in enumerate(zip(pools, n_elems, cbs, outs)):
+            cap = out.numel() * out.element_size() if capacities is None else capacities[k]
+            self.items[k] = _CItem(pool.data_ptr(), n, out.data_ptr(), cap, C.pointer(cb.c))
+
+    def launch(self, workspace: "Workspace", sizes: torch.Tensor, stream=None) -> None:
+        _check(lib().splitzip_compress_batch_paged(self.items, self.n, self.dtype, C.byref(self.paging.c),
+                                                   workspace.buf.data_ptr(), workspace.nbytes, sizes.data_ptr(),
+                                                   _stream_ptr(stream)), "splitzip_compress_batch_paged")
+
+
+class DecompressBatchPaged:
+    """splitzip_decompress_batch_paged: the reverse, into pools that share one block table."""
+
+    def __init__(self, comps, comp_bytes, n_elems, cbs, pools, paging: Paged):
+        if not (len(comps) == len(comp_bytes) == len(n_elems) == len(cbs) == len(pools)):
+            raise ValueError("all lists must have the same length")
+        self.n = len(comps)
+        self.dtype = cbs[0].dtype if cbs else BF16
+        self.paging = paging
+        self.items = (_CDItem * max(self.n, 1))()
+        self._keep = (list(comps), list(cbs), list(pools))
+        for k, (c, cbytes, n, cb, pool) in enumerate(zip(comps, comp_bytes, n_elems, cbs, pools)):
+            self.items[k] = _CDItem(c.data_ptr(), cbytes, n, pool.data_ptr(), C.pointer(cb.c))
+
+    def launch(self, sizes: torch.Tensor | None = None, stream=None) -> None:
+        _check(lib().splitzip_decompress_batch_paged(self.items, self.n, self.dtype, C.byref(self.paging.c),
+                                                     sizes.data_ptr() if sizes is not None else None, _stream_ptr(stream)),
+               "splitzip_decompress_batch_paged")

@@ -61,6 +61,13 @@ __host__ __device__ inline Words contiguous_words(const void* p) {
   return w;
 }
 
+// the words of one tensor of a batch: its own base, the batch's table and page geometry (none: contiguous)
+__host__ __device__ inline Words item_words(const Words& paging, const void* base) {
+  Words w = paging;
+  w.base = static_cast<uint8_t*>(const_cast<void*>(base));
+  return w;
+}
+
 // ---------------------------------------------------------------------------
 // device helpers
 // ---------------------------------------------------------------------------

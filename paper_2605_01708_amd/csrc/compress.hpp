@@ -656,6 +656,7 @@ struct CompressBatchArgs {
   uint32_t n_items, dtype;
   uint32_t group_wgs;        // workgroups that share one tensor; the grid is n_groups * group_wgs
   uint32_t await_extra;      // error-path tests: words awaited beyond the group's
+  Words paging;              // table and page geometry shared by all tensors (table null: contiguous tensors); base unused
   uint8_t dec[kBatchLuts][16];
   uint16_t lut[kBatchLuts][256];
 };
@@ -729,7 +730,7 @@ __global__ __launch_bounds__(T) void compress_batch_kernel(const CompressBatchAr
     pf.enabled = wave == 0 && seq > 0 && G <= 256 && a.await_extra == 0;
     pf.issued = false;
     if (have) {
-      P = make_planes(contiguous_words(a.item[i].in), a.item[i].out, a.item[i].n, a.item[i].capacity, (int)a.dtype);
+      P = make_planes(item_words(a.paging, a.item[i].in), a.item[i].out, a.item[i].n, a.item[i].capacity, (int)a.dtype);
       my_range(0, P.n_chunks, G, b, r0, nb);
       wave_count = dense_pass<NW, F, F::kBatchPerStep>(P, lut[a.lut_of[i]], park, L, r0, nb, wave, lane, pf);
       if (lane == 0) s_red[wave] = wave_count;

@@ -325,6 +325,7 @@ struct DecompressBatchArgs {
   uint8_t dec_of[kBatchMax];
   splitzip_sizes* sizes;   // nullable; one record, status bits sticky
   uint32_t cpw, dtype, reg_patch_max;
+  Words paging;            // as in CompressBatchArgs
   uint8_t dec[kBatchLuts][16];
 };
 
@@ -338,7 +339,7 @@ __global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const Decomp
   if (blockIdx.x >= (n_tiles ? n_tiles : 1u)) return;
   DecompressArgs a;
   a.comp = it.comp;
-  a.w = contiguous_words(it.out);
+  a.w = item_words(b.paging, it.out);
   a.n = it.n;
   a.comp_bytes = it.comp_bytes;
   a.sizes = b.sizes;

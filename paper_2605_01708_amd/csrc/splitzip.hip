@@ -453,22 +453,28 @@ int splitzip_workspace_init(void* d_workspace, size_t workspace_bytes, void* str
 
 namespace {
 
-// a splitzip_paged as the kernels see it; false if the description is not usable for n_elems words of dtype
-bool paged_words(const splitzip_paged* pg, uint64_t n_elems, int dtype, Words* w) {
-  if (!pg || !pg->d_pool || !pg->d_block_table || !aligned16(pg->d_pool) ||
-      (reinterpret_cast<uintptr_t>(pg->d_block_table) & 3u))
-    return false;
+// table and page geometry of a splitzip_paged as the kernels see them (base left null); false if unusable for
+// words of dtype
+bool paging_geometry(const splitzip_paged* pg, int dtype, Words* w) {
+  if (!pg || !pg->d_block_table || (reinterpret_cast<uintptr_t>(pg->d_block_table) & 3u)) return false;
   const uint64_t es = dtype == SPLITZIP_BF16 ? 2 : 1;
   const uint32_t be = pg->block_elems;
   if (be < kChunk || (be & (be - 1u)) || pg->n_pool_blocks == 0) return false;
   if ((pg->page_stride_bytes & 15u) || (pg->offset_bytes & 15u)) return false;
   if (pg->offset_bytes + (uint64_t)be * es > pg->page_stride_bytes) return false;       // the tensor's part of a page fits the page
-  if ((uint64_t)pg->n_blocks * be < n_elems) return false;                                // the table covers the tensor
-  w->base = static_cast<uint8_t*>(pg->d_pool) + pg->offset_bytes;
+  w->base = nullptr;
   w->table = pg->d_block_table;
   w->page_stride = pg->page_stride_bytes;
   w->page_shift = (uint32_t)__builtin_ctz(be);
   w->n_pages = pg->n_pool_blocks;
+  return true;
+}
+
+// a splitzip_paged as the kernels see it; false if the description is not usable for n_elems words of dtype
+bool paged_words(const splitzip_paged* pg, uint64_t n_elems, int dtype, Words* w) {
+  if (!paging_geometry(pg, dtype, w) || !pg->d_pool || !aligned16(pg->d_pool)) return false;
+  if ((uint64_t)pg->n_blocks * pg->block_elems < n_elems) return false;                   // the table covers the tensor
+  w->base = static_cast<uint8_t*>(pg->d_pool) + pg->offset_bytes;
   return true;
 }
 
@@ -636,8 +642,13 @@ int splitzip_decompress_dcb(const void* d_comp, size_t comp_bytes, uint64_t n_el
   return decompress_impl(d_comp, comp_bytes, n_elems, dtype, nullptr, d_cb, contiguous_words(d_out), d_sizes, stream);
 }
 
-int splitzip_compress_batch(const splitzip_item* items, uint32_t n_items, int dtype, void* d_workspace,
-                            size_t workspace_bytes, splitzip_sizes* d_sizes, void* stream) {
+}  // extern "C"
+
+namespace {
+
+// the batch calls; paging: table and page geometry shared by all items, or contiguous tensors (table null)
+int compress_batch_impl(const splitzip_item* items, uint32_t n_items, int dtype, const Words& paging, uint64_t paged_room,
+                        void* d_workspace, size_t workspace_bytes, splitzip_sizes* d_sizes, void* stream) {
   if (!dtype_ok(dtype) || (n_items && (!items || !d_sizes)) || !d_workspace || !aligned16(d_workspace) ||
       (reinterpret_cast<uintptr_t>(d_sizes) & 7u))
     return SPLITZIP_ERR_INVALID_ARG;
@@ -647,6 +658,7 @@ int splitzip_compress_batch(const splitzip_item* items, uint32_t n_items, int dt
     if (!it.d_out || (it.n_elems && !it.d_in) || !aligned16(it.d_in) || !aligned16(it.d_out) || !codebook_ok(it.cb, dtype))
       return SPLITZIP_ERR_INVALID_ARG;
     if (it.n_elems >> 32) return SPLITZIP_ERR_UNSUPPORTED;
+    if (paging.table && it.n_elems > paged_room) return SPLITZIP_ERR_INVALID_ARG;   // the table does not cover the tensor
     if (it.out_capacity < splitzip_fixed_bytes(it.n_elems, dtype)) return SPLITZIP_ERR_CAPACITY;
     if (it.n_elems > n_max) n_max = it.n_elems;
   }
@@ -671,8 +683,8 @@ int splitzip_compress_batch(const splitzip_item* items, uint32_t n_items, int dt
   while (i < n_items) {
     // a tensor beyond the batch kernel's reach goes through the single call, in its place in the order
     if ((items[i].n_elems + kChunk - 1) / kChunk > chunk_cap) {
-      const int rc = splitzip_compress(items[i].d_in, items[i].n_elems, dtype, items[i].cb, items[i].d_out,
-                                       items[i].out_capacity, d_workspace, workspace_bytes, d_sizes + i, stream);
+      const int rc = compress_impl(item_words(paging, items[i].d_in), items[i].n_elems, dtype, items[i].cb, nullptr,
+                                   items[i].d_out, items[i].out_capacity, d_workspace, workspace_bytes, d_sizes + i, stream);
       if (rc != SPLITZIP_OK) return rc;
       ++i;
       continue;
@@ -704,6 +716,7 @@ int splitzip_compress_batch(const splitzip_item* items, uint32_t n_items, int dt
     a.spin_ticks = spin_env ? (uint64_t)spin_env : kSpinTicks;
     a.n_items = k;
     a.dtype = (uint32_t)dtype;
+    a.paging = paging;
     // Workgroups per tensor: all of them for large tensors; for small ones a power-of-two share that
     // leaves each workgroup about 64 chunks, the groups working on different tensors side by side.
     uint64_t chunks_max = 0;
@@ -726,14 +739,15 @@ int splitzip_compress_batch(const splitzip_item* items, uint32_t n_items, int dt
   return SPLITZIP_OK;
 }
 
-int splitzip_decompress_batch(const splitzip_ditem* items, uint32_t n_items, int dtype, splitzip_sizes* d_sizes,
-                              void* stream) {
+int decompress_batch_impl(const splitzip_ditem* items, uint32_t n_items, int dtype, const Words& paging, uint64_t paged_room,
+                          splitzip_sizes* d_sizes, void* stream) {
   if (!dtype_ok(dtype) || (n_items && !items) || (reinterpret_cast<uintptr_t>(d_sizes) & 7u)) return SPLITZIP_ERR_INVALID_ARG;
   for (uint32_t i = 0; i < n_items; ++i) {
     const splitzip_ditem& it = items[i];
     if (!it.d_comp || (it.n_elems && !it.d_out) || !aligned16(it.d_comp) || !aligned16(it.d_out) || !codebook_ok(it.cb, dtype))
       return SPLITZIP_ERR_INVALID_ARG;
     if (it.n_elems >> 32) return SPLITZIP_ERR_UNSUPPORTED;
+    if (paging.table && it.n_elems > paged_room) return SPLITZIP_ERR_INVALID_ARG;
     if (it.comp_bytes < splitzip_fixed_bytes(it.n_elems, dtype)) return SPLITZIP_ERR_CAPACITY;
   }
   static const int cpw_env = env_int("SPLITZIP_DECOMPRESS_CPW", 0);
@@ -764,6 +778,7 @@ int splitzip_decompress_batch(const splitzip_ditem* items, uint32_t n_items, int
     }
     a.sizes = d_sizes;
     a.dtype = (uint32_t)dtype;
+    a.paging = paging;
     a.cpw = cpw_env ? (uint32_t)cpw_env : pick_decompress_cpw(chunks_all, dtype, tiles_per_cu);
     if (a.cpw > kMaxCpw) a.cpw = kMaxCpw;
     static const int reg_patch = env_int("SPLITZIP_DECOMPRESS_REG_PATCH", (int)kRegPatchDefault);
@@ -777,6 +792,35 @@ int splitzip_decompress_batch(const splitzip_ditem* items, uint32_t n_items, int
     i += k;
   }
   return SPLITZIP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int splitzip_compress_batch(const splitzip_item* items, uint32_t n_items, int dtype, void* d_workspace,
+                            size_t workspace_bytes, splitzip_sizes* d_sizes, void* stream) {
+  return compress_batch_impl(items, n_items, dtype, contiguous_words(nullptr), 0, d_workspace, workspace_bytes, d_sizes, stream);
+}
+
+int splitzip_decompress_batch(const splitzip_ditem* items, uint32_t n_items, int dtype, splitzip_sizes* d_sizes,
+                              void* stream) {
+  return decompress_batch_impl(items, n_items, dtype, contiguous_words(nullptr), 0, d_sizes, stream);
+}
+
+int splitzip_compress_batch_paged(const splitzip_item* items, uint32_t n_items, int dtype, const splitzip_paged* paging,
+                                  void* d_workspace, size_t workspace_bytes, splitzip_sizes* d_sizes, void* stream) {
+  Words w;
+  if (!dtype_ok(dtype) || !paging_geometry(paging, dtype, &w)) return SPLITZIP_ERR_INVALID_ARG;
+  return compress_batch_impl(items, n_items, dtype, w, (uint64_t)paging->n_blocks * paging->block_elems, d_workspace,
+                             workspace_bytes, d_sizes, stream);
+}
+
+int splitzip_decompress_batch_paged(const splitzip_ditem* items, uint32_t n_items, int dtype, const splitzip_paged* paging,
+                                    splitzip_sizes* d_sizes, void* stream) {
+  Words w;
+  if (!dtype_ok(dtype) || !paging_geometry(paging, dtype, &w)) return SPLITZIP_ERR_INVALID_ARG;
+  return decompress_batch_impl(items, n_items, dtype, w, (uint64_t)paging->n_blocks * paging->block_elems, d_sizes, stream);
 }
 
 int splitzip_traffic_probe(const void* d_src, size_t read_bytes, void* d_dst, size_t write_bytes, void* stream) {

@@ -44,6 +44,15 @@ def test_page_descriptions_are_checked():
         assert f(desc(n_blocks=2)) == -1                    # the table does not cover the tensor
         assert f(desc(n_pool=0)) == -1
         assert f(desc(), n=1 << 32) == -1                   # (the table cannot cover it)
+    # the batch forms: the same geometry rules (the pool of the description is not looked at), every item must fit the table
+    from paper_2605_01708_amd.binding import _CItem, _CDItem
+    items = (_CItem * 2)(_CItem(buf, 5000, buf, 1 << 20, C.pointer(cb.c)), _CItem(buf, 9000, buf, 1 << 20, C.pointer(cb.c)))
+    ditems = (_CDItem * 1)(_CDItem(buf, 1 << 20, 9000, buf, C.pointer(cb.c)))
+    for bad in (desc(table=None), desc(block_elems=1000), desc(stride=4080), desc(n_pool=0), desc()):   # desc(): 4 x 2048 < 9000
+        assert L.splitzip_compress_batch_paged(items, 2, sz.BF16, C.byref(bad), buf, 1 << 24, buf, None) == -1
+        assert L.splitzip_decompress_batch_paged(ditems, 1, sz.BF16, C.byref(bad), None, None) == -1
+    assert L.splitzip_compress_batch_paged(items, 2, sz.BF16, None, buf, 1 << 24, buf, None) == -1
+    assert L.splitzip_compress_batch_paged(items, 0, sz.BF16, C.byref(desc(pool=None)), buf, 1 << 24, buf, None) == 0
     assert L.splitzip_compress_paged(None, 10, sz.BF16, C.byref(cb.c), buf, 1 << 20, buf, 1 << 20, buf, None) == -1
     assert L.splitzip_decompress_paged(buf, 1 << 20, 10, 7, C.byref(cb.c), C.byref(desc()), None, None) == -1
 
@@ -133,3 +142,70 @@ def test_table_entries_outside_the_pool_are_clamped():
     x2[2 * be:3 * be] = last
     ref, m_ref = oracle.compress(x2, cb_or)
     assert (total, m, status) == (ref.size, m_ref, 0) and np.array_equal(out[:total].cpu().numpy(), ref)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype", [sz.BF16, sz.FP8_E5M2])
+def test_batch_of_tensors_behind_one_block_table(dtype):
+    """K and V of several layers in one pool per layer ([pages, 2, block, 8, 128]: V behind K inside every page), one block
+    table for the sequence; one launch each way; streams are those of the gathered tensors"""
+    es = 2 if dtype == sz.BF16 else 1
+    layers, be, n = 3, 4096, 37 * 1024 + 500               # a ragged last page
+    n_blocks = -(-n // be)
+    n_pool = n_blocks + 3
+    stride = 2 * be * es                                     # K part, then V part
+    rng = np.random.default_rng(5)
+    table_np = rng.permutation(n_pool)[:n_blocks].astype(np.int32)
+    cbs_or = {k: oracle.calibrate(kv_synth.to_numpy_words(GEN[dtype](1024, 1, 0, k)), DT[dtype]) for k in "KV"}
+    cbs = {k: sz.codebook_from_dec(cbs_or[k].dec.tolist(), dtype) for k in "KV"}
+    pools_np, words = [], []
+    for layer in range(layers):
+        pool = np.full(n_pool * stride, 0xEE, np.uint8)
+        for half, kind in enumerate("KV"):
+            x = kv_synth.to_numpy_words(GEN[dtype](-(-n // 1024), 3, layer, kind))[:n].copy()
+            words.append((layer, half, kind, x))
+            xb = x.view(np.uint8)
+            for b in range(n_blocks):
+                piece = xb[b * be * es:(b + 1) * be * es]
+                at = int(table_np[b]) * stride + half * be * es
+                pool[at:at + piece.size] = piece
+        pools_np.append(pool)
+    pools = [torch.from_numpy(p).cuda() for p in pools_np]
+    table = torch.from_numpy(table_np).cuda()
+    paging = sz.Paged(pools[0], table, be, stride, 0, n_pool)    # the pool of this description is ignored by the batch calls
+    views = [pools[layer][half * be * es:] for layer, half, _, _ in words]
+    books = [cbs[kind] for _, _, kind, _ in words]
+    k = len(words)
+    outs = [torch.full((sz.compress_bound(n, dtype) + 256,), 0xA5, dtype=torch.uint8, device="cuda") for _ in range(k)]
+    rec = sz.new_sizes_array(k)
+    ws = sz.Workspace(n, dtype)
+    sz.CompressBatchPaged(views, [n] * k, books, outs, paging, capacities=[o.numel() - 256 for o in outs]).launch(ws, rec)
+    torch.cuda.synchronize()
+    got = sz.read_sizes_array(rec)
+    for i, (layer, half, kind, x) in enumerate(words):
+        ref, m = oracle.compress(x, cbs_or[kind])
+        assert got[i] == (ref.size, m, 0), (i, got[i], ref.size, m)
+        assert np.array_equal(outs[i][:ref.size].cpu().numpy(), ref), f"item {i} differs"
+        assert (outs[i][ref.size:ref.size + 256].cpu().numpy() == 0xA5).all()
+    # back into fresh pools
+    pools2 = [torch.full_like(p, 0x77) for p in pools]
+    views2 = [pools2[layer][half * be * es:] for layer, half, _, _ in words]
+    st = sz.new_sizes()
+    sz.DecompressBatchPaged(outs, [g[0] for g in got], [n] * k, books, views2, paging).launch(st)
+    torch.cuda.synchronize()
+    assert sz.read_sizes(st)[2] == 0
+    for layer in range(layers):
+        want = np.full(pools_np[layer].size, 0x77, np.uint8)
+        for (ly, half, kind, x) in words:
+            if ly != layer:
+                continue
+            xb = x.view(np.uint8)
+            for b in range(n_blocks):
+                piece = xb[b * be * es:(b + 1) * be * es]
+                at = int(table_np[b]) * stride + half * be * es
+                want[at:at + piece.size] = piece
+        assert np.array_equal(pools2[layer].cpu().numpy(), want), f"layer {layer}"
+    # a table too short for a tensor is refused
+    short = sz.Paged(pools[0], table[:2].contiguous(), be, stride, 0, n_pool)
+    with pytest.raises(sz.SplitZipError):
+        sz.CompressBatchPaged(views, [n] * k, books, outs, short).launch(ws, rec)
