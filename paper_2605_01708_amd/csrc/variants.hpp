@@ -96,6 +96,11 @@ __device__ inline void v_load8(const VArgs& a, uint64_t g0, uint32_t (&x)[8]) {
 // accesses it takes for unrelated because they go through different types, and waits for the data.
 __device__ inline void v_lds_settle() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
+// how many of the eight elements starting at g0 exist (the valid ones are always a prefix of the group)
+__device__ inline uint32_t v_nvalid(const VArgs& a, uint64_t g0) {
+  return g0 >= a.n ? 0u : (a.n - g0 < 8 ? (uint32_t)(a.n - g0) : 8u);
+}
+
 // NB bytes of v to / from a lane's slot in LDS (slot = lane * NB; 8 and 4 are aligned)
 template <int NB>
 __device__ inline void v_lds_put(uint8_t* p, uint64_t v) {
@@ -110,7 +115,8 @@ __device__ inline uint64_t v_lds_get(const uint8_t* p) {
   return (uint64_t)p[0] | ((uint64_t)p[1] << 8) | ((uint64_t)p[2] << 16);
 }
 
-// split + encode of a lane's eight elements: packed a, packed codes, escape mask (bit j = element j)
+// split + encode of a lane's eight elements: packed a, packed codes, escape mask (bit j = element j).  Words beyond
+// N were loaded as zero; their codes and escape bits are masked off at the end (no per-element branches).
 template <int DT, int CB>
 __device__ inline void v_encode8(const VArgs& a, const uint8_t* lut, uint64_t g0, const uint32_t (&x)[8], uint64_t& smw,
                                  uint32_t& cw, uint32_t& esc) {
@@ -119,12 +125,14 @@ __device__ inline void v_encode8(const VArgs& a, const uint8_t* lut, uint64_t g0
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     const uint32_t t = lut[F::exponent(x[j])];
-    const bool valid = g0 + j < a.n;
     smw |= (uint64_t)F::signmant(x[j]) << (F::SB * j);   // zero for words beyond N
-    if (valid) {
-      cw |= (t & 0x7fu) << (CB * j);
-      esc |= (t >> 7) << j;
-    }
+    cw |= (t & 0x7fu) << (CB * j);
+    esc |= (t >> 7) << j;
+  }
+  const uint32_t nv = v_nvalid(a, g0);
+  if (nv < 8) {
+    cw &= (1u << (CB * nv)) - 1u;
+    esc &= (1u << nv) - 1u;
   }
 }
 
@@ -271,8 +279,8 @@ __global__ __launch_bounds__(kThreads) void v_emit_kernel(const VArgs a) {
     v_load8<DT>(a, g0, x);
     uint32_t esc = 0;
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
-      if (g0 + j < a.n) esc |= (uint32_t)(lut[F::exponent(x[j])] >> 7) << j;
+    for (int j = 0; j < 8; ++j) esc |= (uint32_t)(lut[F::exponent(x[j])] >> 7) << j;
+    esc &= (1u << v_nvalid(a, g0)) - 1u;
     const uint32_t cnt = __popc(esc), incl = wave_incl_scan(cnt);
     const uint32_t t31 = __builtin_amdgcn_readlane(incl, 31), t63 = __builtin_amdgcn_readlane(incl, 63);
     uint32_t r;
@@ -368,6 +376,8 @@ __global__ __launch_bounds__(kThreads) void v_decode_kernel(const VArgs a) {
   if (!ok || !live) return;   // nothing of a stream with a bad header is followed
   const uint64_t off_val = a.off_pos + a256((uint64_t)a.pos_bytes * M);
   const uint32_t sentinel = (1u << CB) - 1u;
+  // codes the codebook does not have can only occur if it leaves some unused (wave-uniform: no per-element work otherwise)
+  const bool check_codes = a.k + (a.mode == SPLITZIP_ESC_SENTINEL ? 1u : 0u) < (1u << CB);
   bool bad = false;
 
   // chunk-relative records: the first 64 of every chunk of the block are fetched now
@@ -396,18 +406,19 @@ __global__ __launch_bounds__(kThreads) void v_decode_kernel(const VArgs a) {
     const uint64_t g = blk * kVBlock + s * kVStep, g0 = g + lane * 8;
     const uint64_t smw = v_lds_get<F::SB>(&s_sm[wave][(s * 64 + lane) * F::SB]);
     const uint32_t cw = (uint32_t)v_lds_get<CB>(&s_code[wave][(s * 64 + lane) * CB]);
-    uint32_t w[8], sent = 0;
+    const uint32_t vmask = (1u << v_nvalid(a, g0)) - 1u;   // bit j: element j exists
+    uint32_t w[8], sent = 0, unknown = 0;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const uint32_t av = (uint32_t)(smw >> (F::SB * j)) & ((1u << F::SB) - 1u), code = (cw >> (CB * j)) & sentinel;
-      if (a.mode == SPLITZIP_ESC_SENTINEL && code == sentinel) sent |= 1u << j;
-      else if (code >= a.k && g0 + j < a.n) bad = true;
+      sent |= (uint32_t)(code == sentinel) << j;
+      if (check_codes) unknown |= (uint32_t)(code >= a.k) << j;
       w[j] = F::combine(av, s_dec[code & 15u]);
     }
+    sent = a.mode == SPLITZIP_ESC_SENTINEL ? sent & vmask : 0u;
+    if (unknown & vmask & ~sent) bad = true;
     if (a.mode == SPLITZIP_ESC_SENTINEL) {
       // rank of every sentinel inside its chunk, then its exponent from the value array
-      for (int j = 0; j < 8; ++j)
-        if (g0 + j >= a.n) sent &= ~(1u << j);
       const uint32_t cnt = __popc(sent), incl = wave_incl_scan(cnt);
       const uint32_t t31 = __builtin_amdgcn_readlane(incl, 31), t63 = __builtin_amdgcn_readlane(incl, 63);
       uint32_t r, r_end;
