@@ -50,8 +50,9 @@ struct LdsSink {
   uint16_t* pos;
   uint8_t* val;
   uint32_t tag;   // OR-ed into the position: which of the wave's chunks the record belongs to
+  uint32_t cap;   // records the staging holds
   __device__ inline void put(uint32_t r, uint32_t p, uint32_t e) const {
-    if (r < kStageCap) {
+    if (r < cap) {
       pos[r] = (uint16_t)(p | tag);
       val[r] = (uint8_t)e;
     }
@@ -322,6 +323,10 @@ struct Bf16 {
   // takes one: two cost it more than 64 registers per lane, and with 64 two of its launches fit a compute unit
   // side by side, so that two compress calls on different streams can never starve each other of room.
   static constexpr uint32_t kBatchPerStep = 2;
+  // batch kernel: one workgroup of 1024 per CU (its 125 registers allow no more waves), 512 staged escapes per wave
+  static constexpr int kBatchThreads = 1024, kBatchWgsPerCu = 1, kBatchWavesPerSimd = 1;
+  static constexpr bool kBatchLutAtFixedPlace = false;   // bound by memory, not by instructions: measured a few percent slower with it
+  static constexpr uint32_t kBatchStageCap = kStageCap;
   static constexpr int kLutShift = 0;       // the LDS encode table holds the entry of exponent e in slot e
   // a chunk goes the fast way if it is complete (then nothing of a pad is its business: N is a multiple of 1024 there)
   __device__ static inline bool full(const Planes& a, uint64_t cbase) { return cbase + kChunk <= a.n; }
@@ -336,6 +341,14 @@ struct Bf16 {
 struct E5m2 {
   static constexpr int ES = 1;
   struct Regs { uint32_t w[4]; };
+  // batch kernel: four workgroups of 512 per CU, eight waves per SIMD at 64 registers.  Small workgroups matter
+  // more than the wave count: while one of them exchanges counts and writes escape records out, the others keep
+  // the CU's memory pipeline busy (measured: 4 x 256 threads gains as much as 4 x 512 over 1 x 1024).  256 staged
+  // escapes per wave are plenty: FP8 exponents miss the codebook far less often than BF16 ones, and a wave that
+  // does overflow takes the second pass of write_out.
+  static constexpr int kBatchThreads = 512, kBatchWgsPerCu = 4, kBatchWavesPerSimd = 8;
+  static constexpr uint32_t kBatchStageCap = 256;
+  static constexpr bool kBatchLutAtFixedPlace = true;
   static constexpr uint32_t kBatchPerStep = 1;   // 1 KB each: a second chunk per step costs more in registers and code than it hides
   // The LDS encode table holds the entry of exponent e in slots 2 e and 2 e + 1: its byte offset is then
   // the word's byte with the sign and mantissa bits masked off, one instruction per element.
@@ -391,10 +404,11 @@ __device__ void compress_write_trailer(const Planes& a, const uint8_t* dec, spli
 //   s_off[k]               escapes of chunk k, after the scan: escapes of the chunks before it
 //   s_wstart[k]            records its wave had staged before chunk k
 struct RangeLds {
-  uint16_t* stage_pk;    // this wave's kStageCap entries
+  uint16_t* stage_pk;    // this wave's `cap` entries
   uint8_t* stage_val;
   uint32_t* s_off;       // kMaxRange + 1
   uint16_t* s_wstart;    // kMaxRange
+  uint32_t cap;          // escape records a wave can stage
 };
 
 // this workgroup's share of `chunks` chunks starting at chunk0: dealt evenly, the first `rem`
@@ -446,7 +460,7 @@ __device__ inline uint32_t dense_pass(const Planes& P, const uint16_t* lut, uint
         const uint32_t k = wave + it * NW;
         const uint64_t cbase = (uint64_t)(r0 + k) * kChunk;
         if (it == mid_it) mid();
-        const LdsSink lds{L.stage_pk, L.stage_val, it << 10};
+        const LdsSink lds{L.stage_pk, L.stage_val, it << 10, L.cap};
         const uint32_t cnt = F::full(P, cbase) ? F::template process<true, true>(P, lut, park, cbase, lane, w[s], wave_count, lds)
                                                : F::template process<false, true>(P, lut, park, cbase, lane, w[s], wave_count, lds);
         if (lane == 0) {
@@ -517,7 +531,7 @@ __device__ inline void write_out(const Planes& P, const uint16_t* lut, uint32_t*
                                  const GlobalSink& g, int tid, int wave, int lane) {
   uint32_t* tab = reinterpret_cast<uint32_t*>(P.out + P.off_tab);
   if ((uint32_t)tid < nb) tab[r0 + tid] = prefix + L.s_off[tid];
-  if (wave_count <= kStageCap) {
+  if (wave_count <= L.cap) {
     // staged record i of this wave belongs to chunk k and is the (i - s_wstart[k])-th of it
     for (uint32_t i = lane; i < wave_count; i += 64) {
       const uint32_t pk = L.stage_pk[i], k = (pk >> 10) * NW + wave;
@@ -574,7 +588,7 @@ __global__ __launch_bounds__(T, (T == 1024 ? 8 : 1)) void compress_kernel(const 
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: loops over chunks stay scalar
   const uint32_t b = blockIdx.x;
   uint32_t* park = reinterpret_cast<uint32_t*>(&s_park[tid]);
-  const RangeLds L{stage_pk[wave], stage_val[wave], s_off, s_wstart};
+  const RangeLds L{stage_pk[wave], stage_val[wave], s_off, s_wstart, kStageCap};
 
   if (tid < 256) {
     const int e = tid >> F::kLutShift;   // LDS slot tid holds the entry of exponent e
@@ -661,11 +675,12 @@ struct CompressBatchArgs {
   uint16_t lut[kBatchLuts][256];
 };
 
-// wave 0, half way through a dense pass: the loads of the previous tensor's exchange words, so that
-// their latency is hidden.  Up to 256 workgroups per group (four words per lane).
+// Half way through a dense pass: the loads of the previous tensor's exchange words, so that their
+// latency is hidden.  Wave w of the first kBatchWgsPerCu waves fetches the words [256 w, 256 w + 256) of
+// the group (four per lane), reduces them at the end of its pass, and wave 0 puts the parts together.
 struct ExchangePrefetch {
   const uint64_t* slot;
-  uint32_t wgs;
+  uint32_t first, wgs;
   int lane;
   bool enabled, issued;
   uint64_t v[4];
@@ -673,10 +688,27 @@ struct ExchangePrefetch {
     if (!enabled) return;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const uint32_t i = lane + 64 * j;
+      const uint32_t i = first + lane + 64 * j;
       v[j] = i < wgs ? ld_agent(&slot[i]) : 0ull;
     }
     issued = true;
+  }
+  // the wave's part: true if all of its words carry the tag; lower = counts of the workgroups before b, all = of all
+  __device__ inline bool reduce(uint32_t tag, uint32_t b, uint32_t& lower, uint32_t& all) const {
+    uint32_t lo = 0, al = 0;
+    int ready = 1;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t q = first + lane + 64 * j;
+      if (q < wgs) {
+        if ((uint32_t)(v[j] >> 32) != tag) ready = 0;
+        al += (uint32_t)v[j];
+        lo += q < b ? (uint32_t)v[j] : 0u;
+      }
+    }
+    lower = wave_last(wave_incl_scan(lo));
+    all = wave_last(wave_incl_scan(al));
+    return __ballot(ready) == ~0ull;
   }
 };
 
@@ -689,11 +721,18 @@ struct ExchangePrefetch {
 // -- is paid once per batch here.  Small tensors are shared by a group of workgroups only; the
 // groups work on different tensors at the same time (tensor i belongs to group i mod n_groups).
 template <int T, typename F>
-__global__ __launch_bounds__(T) void compress_batch_kernel(const CompressBatchArgs a) {
+__global__ __launch_bounds__(T, F::kBatchWavesPerSimd) void compress_batch_kernel(const CompressBatchArgs a) {
   constexpr int NW = T / 64;
+  constexpr uint32_t CAP = F::kBatchStageCap;
+  constexpr int PFW = F::kBatchWgsPerCu;   // waves that fetch exchange words ahead, 256 each: the group has at most 256 PFW workgroups
+  static_assert(PFW <= NW && PFW <= 4, "prefetching waves");
+  __shared__ uint32_t s_pf[4][4];          // parts of the waves 1 .. PFW - 1: ready, lower, all
   __shared__ uint16_t lut[kBatchLuts][256];
-  __shared__ uint16_t stage_pk[3][NW][kStageCap];   // three sets: a wave may stage tensor i + 1 while another still writes out i - 1
-  __shared__ uint8_t stage_val[3][NW][kStageCap];
+  // kBatchLutAtFixedPlace: the table of the tensor whose dense pass is running, at an address the compiler
+  // knows: its lookups carry the table's place as an immediate, one address instruction less per element
+  __shared__ uint16_t lut_now[256];
+  __shared__ uint16_t stage_pk[3][NW][CAP];   // three sets: a wave may stage tensor i + 1 while another still writes out i - 1
+  __shared__ uint8_t stage_val[3][NW][CAP];
   __shared__ uint32_t s_off[3][kMaxRange + 1];
   __shared__ uint16_t s_wstart[3][kMaxRange];
   __shared__ u32x4 s_park[T];
@@ -706,6 +745,8 @@ __global__ __launch_bounds__(T) void compress_batch_kernel(const CompressBatchAr
   uint32_t* park = reinterpret_cast<uint32_t*>(&s_park[tid]);
 
   for (int i = tid; i < (int)(kBatchLuts * 256); i += T) lut[i >> 8][i & 255] = a.lut[i >> 8][(i & 255) >> F::kLutShift];
+  if (F::kBatchLutAtFixedPlace && grp < a.n_items)
+    for (int i = tid; i < 256; i += T) lut_now[i] = a.lut[a.lut_of[grp]][i >> F::kLutShift];
   const uint32_t epoch = ld_agent(&a.ws_hdr[0]);
   const uint32_t err_before = b == 0 ? ld_agent(&a.ws_hdr[2]) : 0u;
   if (tid == 0) s_misc[3] = 0;   // set once an exchange was given up: later ones are not waited for
@@ -720,20 +761,30 @@ __global__ __launch_bounds__(T) void compress_batch_kernel(const CompressBatchAr
     const bool have = i < a.n_items;
     if (!have && seq == 0) break;   // a group without tensors
     const uint32_t set = seq % 3u;
-    const RangeLds L{stage_pk[set][wave], stage_val[set][wave], s_off[set], s_wstart[set]};
+    const RangeLds L{stage_pk[set][wave], stage_val[set][wave], s_off[set], s_wstart[set], CAP};
     Planes P = Pprev;
     uint32_t r0 = 0, nb = 0, wave_count = 0;
     ExchangePrefetch pf;
     pf.slot = ring + ((seq + kRing - 1) % kRing) * G;
+    pf.first = 256u * (uint32_t)wave;
     pf.wgs = G;
     pf.lane = lane;
-    pf.enabled = wave == 0 && seq > 0 && G <= 256 && a.await_extra == 0;
+    pf.enabled = wave < PFW && seq > 0 && G <= 256u * PFW && a.await_extra == 0;
     pf.issued = false;
     if (have) {
       P = make_planes(item_words(a.paging, a.item[i].in), a.item[i].out, a.item[i].n, a.item[i].capacity, (int)a.dtype);
       my_range(0, P.n_chunks, G, b, r0, nb);
-      wave_count = dense_pass<NW, F, F::kBatchPerStep>(P, lut[a.lut_of[i]], park, L, r0, nb, wave, lane, pf);
+      wave_count = dense_pass<NW, F, F::kBatchPerStep>(P, F::kBatchLutAtFixedPlace ? lut_now : lut[a.lut_of[i]], park, L, r0, nb, wave, lane, pf);
       if (lane == 0) s_red[wave] = wave_count;
+    }
+    if (PFW > 1 && wave > 0 && wave < PFW) {
+      uint32_t lo = 0, al = 0;
+      const bool ready = pf.issued && pf.reduce(epoch + prev_item, b, lo, al);
+      if (lane == 0) {
+        s_pf[wave][0] = ready ? 1u : 0u;
+        s_pf[wave][1] = lo;
+        s_pf[wave][2] = al;
+      }
     }
     __syncthreads();
     if (wave == 0) {
@@ -747,20 +798,12 @@ __global__ __launch_bounds__(T) void compress_batch_kernel(const CompressBatchAr
         uint32_t lo = 0, al = 0;
         bool ok = true, done = false;
         if (pf.issued) {
-          int ready = 1;
+          done = pf.reduce(tag, b, lo, al);
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const uint32_t q = lane + 64 * j;
-            if (q < G) {
-              if ((uint32_t)(pf.v[j] >> 32) != tag) ready = 0;
-              al += (uint32_t)pf.v[j];
-              lo += q < b ? (uint32_t)pf.v[j] : 0u;
-            }
-          }
-          if (__ballot(ready) == ~0ull) {
-            lo = wave_last(wave_incl_scan(lo));
-            al = wave_last(wave_incl_scan(al));
-            done = true;
+          for (int w = 1; w < PFW; ++w) {
+            done = done && s_pf[w][0] != 0;
+            lo += s_pf[w][1];
+            al += s_pf[w][2];
           }
         }
         if (!done)
@@ -789,11 +832,15 @@ __global__ __launch_bounds__(T) void compress_batch_kernel(const CompressBatchAr
       }
     } else if (wave == 1 && have) {
       scan_range(s_off[set], nb, lane);
+    } else if (F::kBatchLutAtFixedPlace && wave >= 2 && i + n_groups < a.n_items) {
+      // every dense pass of tensor i is over: the table of this group's next tensor
+      const uint16_t* next = lut[a.lut_of[i + n_groups]];
+      for (int j = tid - 128; j < 256; j += T - 128) lut_now[j] = next[j];
     }
     __syncthreads();
     if (seq > 0 && s_misc[2] == 0) {
       const uint32_t pset = (seq + 2u) % 3u;
-      const RangeLds Lp{stage_pk[pset][wave], stage_val[pset][wave], s_off[pset], s_wstart[pset]};
+      const RangeLds Lp{stage_pk[pset][wave], stage_val[pset][wave], s_off[pset], s_wstart[pset], CAP};
       write_out<NW, F>(Pprev, lut[a.lut_of[prev_item]], park, Lp, prev_r0, prev_nb, prev_count, s_misc[0],
                        final_sink(Pprev, s_misc[1]), tid, wave, lane);
     }

@@ -112,17 +112,19 @@ uint32_t resident_workgroups() {
 }
 
 // the same for the batch kernel (more LDS)
-uint32_t resident_workgroups_batch() {
-  static uint32_t cached[64] = {0};
+uint32_t resident_workgroups_batch(int dtype) {
+  static uint32_t cached[2][64] = {{0}};
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
-  if (!cached[dev]) {
+  const int f = dtype == SPLITZIP_BF16 ? 0 : 1;
+  if (!cached[f][dev]) {
     int per_cu = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, compress_batch_kernel<1024, Bf16>, 1024, 0) != hipSuccess || per_cu <= 0)
-      return 0;
-    cached[dev] = (uint32_t)per_cu * (uint32_t)cu_count();
+    const hipError_t rc = f == 0 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, compress_batch_kernel<Bf16::kBatchThreads, Bf16>, Bf16::kBatchThreads, 0)
+                                 : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, compress_batch_kernel<E5m2::kBatchThreads, E5m2>, E5m2::kBatchThreads, 0);
+    if (rc != hipSuccess || per_cu <= 0) return 0;
+    cached[f][dev] = (uint32_t)per_cu * (uint32_t)cu_count();
   }
-  return cached[dev];
+  return cached[f][dev];
 }
 
 // ---------------------------------------------------------------------------
@@ -665,8 +667,9 @@ int compress_batch_impl(const splitzip_item* items, uint32_t n_items, int dtype,
   if (workspace_bytes < splitzip_workspace_bytes(n_max, dtype)) return SPLITZIP_ERR_CAPACITY;
   if (n_items == 0) return SPLITZIP_OK;
 
-  static const int wgs_per_cu = env_int("SPLITZIP_COMPRESS_WGS_PER_CU", 1);
-  const uint32_t resident = resident_workgroups_batch();
+  static const int wgs_per_cu_env = env_int("SPLITZIP_COMPRESS_WGS_PER_CU", 0);   // 0: what the kernel of the dtype is built for
+  const int wgs_per_cu = wgs_per_cu_env > 0 ? wgs_per_cu_env : (dtype == SPLITZIP_BF16 ? Bf16::kBatchWgsPerCu : E5m2::kBatchWgsPerCu);
+  const uint32_t resident = resident_workgroups_batch(dtype);
   if (!resident) return SPLITZIP_ERR_HIP;
   uint32_t W = (uint32_t)cu_count() * (uint32_t)wgs_per_cu;
   if (W > resident) W = resident;
@@ -731,8 +734,8 @@ int compress_batch_impl(const splitzip_item* items, uint32_t n_items, int dtype,
     a.group_wgs = G;
     a.await_extra = (uint32_t)missing;
     const uint32_t grid = (W / G) * G;
-    if (dtype == SPLITZIP_BF16) hipLaunchKernelGGL((compress_batch_kernel<1024, Bf16>), dim3(grid), dim3(1024), 0, st, a);
-    else hipLaunchKernelGGL((compress_batch_kernel<1024, E5m2>), dim3(grid), dim3(1024), 0, st, a);
+    if (dtype == SPLITZIP_BF16) hipLaunchKernelGGL((compress_batch_kernel<Bf16::kBatchThreads, Bf16>), dim3(grid), dim3(Bf16::kBatchThreads), 0, st, a);
+    else hipLaunchKernelGGL((compress_batch_kernel<E5m2::kBatchThreads, E5m2>), dim3(grid), dim3(E5m2::kBatchThreads), 0, st, a);
     if (hipGetLastError() != hipSuccess) return SPLITZIP_ERR_HIP;
     i += k;
   }
