@@ -14,7 +14,7 @@ constexpr int kThreads = 256;                             // decompress / helper
 constexpr int kWaves = kThreads / 64;
 constexpr uint32_t kMaxCpw = 16;                          // decompress: chunks per wave per tile, at most
 constexpr uint32_t kMaxRange = 256;                       // compress: chunks per workgroup per launch, at most
-constexpr uint32_t kMaxWorkgroups = 4096;                 // compress: words of exchange state in the workspace
+constexpr uint32_t kMaxWorkgroups = 8192;                 // compress: words of exchange state in the workspace
 constexpr uint32_t kWsTableBytes = 8 * kMaxWorkgroups;
 constexpr uint32_t kStageCap = 512;                       // escapes a wave can stage in LDS
 constexpr uint32_t kWsHeaderBytes = 64;                   // epoch, running escape count, error flags

@@ -341,12 +341,12 @@ struct Bf16 {
 struct E5m2 {
   static constexpr int ES = 1;
   struct Regs { uint32_t w[4]; };
-  // batch kernel: four workgroups of 512 per CU, eight waves per SIMD at 64 registers.  Small workgroups matter
-  // more than the wave count: while one of them exchanges counts and writes escape records out, the others keep
-  // the CU's memory pipeline busy (measured: 4 x 256 threads gains as much as 4 x 512 over 1 x 1024).  256 staged
-  // escapes per wave are plenty: FP8 exponents miss the codebook far less often than BF16 ones, and a wave that
-  // does overflow takes the second pass of write_out.
-  static constexpr int kBatchThreads = 512, kBatchWgsPerCu = 4, kBatchWavesPerSimd = 8;
+  // batch kernel: eight workgroups of 256 per CU, eight waves per SIMD at 64 registers.  Many small workgroups
+  // matter more than the wave count: while one of them exchanges counts and writes escape records out, the others
+  // keep the CU's memory pipeline busy (measured on 64 tensors of 32 MiB: 1 x 1024 threads 2.2 TB/s, 4 x 256 and
+  // 4 x 512 2.45, 8 x 256 2.65).  256 staged escapes per wave are plenty: FP8 exponents miss the codebook far less
+  // often than BF16 ones, and a wave that does overflow takes the second pass of write_out.
+  static constexpr int kBatchThreads = 256, kBatchWgsPerCu = 8, kBatchWavesPerSimd = 8;
   static constexpr uint32_t kBatchStageCap = 256;
   static constexpr bool kBatchLutAtFixedPlace = true;
   static constexpr uint32_t kBatchPerStep = 1;   // 1 KB each: a second chunk per step costs more in registers and code than it hides
@@ -653,7 +653,7 @@ __global__ __launch_bounds__(T, (T == 1024 ? 8 : 1)) void compress_kernel(const 
 constexpr uint32_t kBatchMax = 64;     // tensors per launch: their descriptors travel as kernel arguments
 constexpr uint32_t kBatchLuts = 2;     // codebooks per launch
 constexpr uint32_t kRing = 4;          // exchange slots: a workgroup can be two tensors ahead of the slowest
-constexpr uint32_t kRingWgs = 1024;    // words per slot
+constexpr uint32_t kRingWgs = 2048;    // words per slot
 
 struct BatchItem {
   const uint8_t* in;
@@ -676,8 +676,9 @@ struct CompressBatchArgs {
 };
 
 // Half way through a dense pass: the loads of the previous tensor's exchange words, so that their
-// latency is hidden.  Wave w of the first kBatchWgsPerCu waves fetches the words [256 w, 256 w + 256) of
-// the group (four per lane), reduces them at the end of its pass, and wave 0 puts the parts together.
+// latency is hidden.  Wave w of the first few waves (one per 256 workgroups a group can have, four at most)
+// fetches the words [256 w, 256 w + 256) of the group, four per lane, reduces them at the end of its pass,
+// and wave 0 puts the parts together.  A larger group goes without: wave 0 reads its words when it needs them.
 struct ExchangePrefetch {
   const uint64_t* slot;
   uint32_t first, wgs;
@@ -724,7 +725,7 @@ template <int T, typename F>
 __global__ __launch_bounds__(T, F::kBatchWavesPerSimd) void compress_batch_kernel(const CompressBatchArgs a) {
   constexpr int NW = T / 64;
   constexpr uint32_t CAP = F::kBatchStageCap;
-  constexpr int PFW = F::kBatchWgsPerCu;   // waves that fetch exchange words ahead, 256 each: the group has at most 256 PFW workgroups
+  constexpr int PFW = F::kBatchWgsPerCu < 4 ? F::kBatchWgsPerCu : 4;   // waves that fetch exchange words ahead, 256 each: for groups of up to 256 PFW workgroups
   static_assert(PFW <= NW && PFW <= 4, "prefetching waves");
   __shared__ uint32_t s_pf[4][4];          // parts of the waves 1 .. PFW - 1: ready, lower, all
   __shared__ uint16_t lut[kBatchLuts][256];

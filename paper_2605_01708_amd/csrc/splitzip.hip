@@ -731,9 +731,15 @@ int compress_batch_impl(const splitzip_item* items, uint32_t n_items, int dtype,
     while (G > 8 && G % 2 == 0 && (uint64_t)(G / 2) * 64 >= chunks_max && W / (G / 2) <= k) G /= 2;   // never more groups than tensors
     while ((uint64_t)G * kMaxRange < chunks_max) G *= 2;   // never beyond W: chunks_max <= chunk_cap
     if (G > W) G = W;
+    // A group larger than the kernel fetches exchange words ahead for would put the exchange back on every
+    // workgroup's critical path (and have each read that many more words): a smaller grid serves such tensors better.
+    const uint32_t kernel_wgs_per_cu = (uint32_t)(dtype == SPLITZIP_BF16 ? Bf16::kBatchWgsPerCu : E5m2::kBatchWgsPerCu);
+    const uint32_t ahead = 256u * (kernel_wgs_per_cu < 4u ? kernel_wgs_per_cu : 4u);
+    uint32_t Wk = W;
+    if (G > ahead && (uint64_t)ahead * kMaxRange >= chunks_max) Wk = G = ahead;
     a.group_wgs = G;
     a.await_extra = (uint32_t)missing;
-    const uint32_t grid = (W / G) * G;
+    const uint32_t grid = (Wk / G) * G;
     if (dtype == SPLITZIP_BF16) hipLaunchKernelGGL((compress_batch_kernel<Bf16::kBatchThreads, Bf16>), dim3(grid), dim3(Bf16::kBatchThreads), 0, st, a);
     else hipLaunchKernelGGL((compress_batch_kernel<E5m2::kBatchThreads, E5m2>), dim3(grid), dim3(E5m2::kBatchThreads), 0, st, a);
     if (hipGetLastError() != hipSuccess) return SPLITZIP_ERR_HIP;
