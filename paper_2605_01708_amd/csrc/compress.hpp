@@ -323,8 +323,9 @@ struct Bf16 {
   // takes one: two cost it more than 64 registers per lane, and with 64 two of its launches fit a compute unit
   // side by side, so that two compress calls on different streams can never starve each other of room.
   static constexpr uint32_t kBatchPerStep = 2;
-  // batch kernel: one workgroup of 1024 per CU (its 125 registers allow no more waves), 512 staged escapes per wave
-  static constexpr int kBatchThreads = 1024, kBatchWgsPerCu = 1, kBatchWavesPerSimd = 1;
+  // batch kernel: two workgroups of 512 per CU (its 125 registers allow no more than 16 waves), 512 staged escapes
+  // per wave.  Against one workgroup of 1024: the same on 64 MiB tensors, 2 to 4 % faster on 4 to 32 MiB ones.
+  static constexpr int kBatchThreads = 512, kBatchWgsPerCu = 2, kBatchWavesPerSimd = 4;
   static constexpr bool kBatchLutAtFixedPlace = false;   // bound by memory, not by instructions: measured a few percent slower with it
   static constexpr uint32_t kBatchStageCap = kStageCap;
   static constexpr int kLutShift = 0;       // the LDS encode table holds the entry of exponent e in slot e
