@@ -28,6 +28,7 @@ import kv_synth
 import paper_2605_01708_amd as sz
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
+BATCH_THREADS = {"Bf16": 512, "E5m2": 256}   # workgroup size of compress_batch_kernel per word type (its template argument)
 
 WORKLOADS = {
     "config1": "Llama-3-8B-shaped BF16 KV cache: 32 layers x {K,V} x [32768,8,128] (4 GiB), one codebook per kind",
@@ -317,7 +318,7 @@ def main():
         "paper_context": {"compress_GBps": 613.3, "decompress_GBps": 2181.8, "ratio": 1.324,
                           "hardware": "NVIDIA H200, real Qwen3-32B BF16 KV (Table 2)"},
         "roofline": {
-            "kernel": f"compress_batch_kernel<1024, {fmt}>",
+            "kernel": f"compress_batch_kernel<{BATCH_THREADS[fmt]}, {fmt}>",
             "bound": "hbm", "achieved": round(c_ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": round(c_ach / HBM_PEAK_GBPS, 4), "traffic": None,
             "launch_us": round(mean(ms_c) * 1e3 / launches, 2), "algorithmic_bytes_per_launch": int(alg_bytes / launches),
