@@ -526,3 +526,60 @@ def test_full_size_tensors_of_the_benchmark_workload():
         x = kv_synth.to_numpy_words(x_dev)
         total, m = check_parity(g, x, cb_or, f"config1 L{layer}{kind}")
         print(f"config1 L{layer}{kind}: eps={m / n:.5f} ratio={2 * n / total:.4f}", flush=True)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_full_size_tensors_through_the_batch_calls(dtype):
+    """the launch configuration the benchmark times, at its real tensor size: four [32768, 8, 128] tensors (K and V of
+    two layers, per-kind codebooks) in one batch launch each way; every stream is the oracle's, byte for byte"""
+    es = 2 if dtype == sz.BF16 else 1
+    gen = kv_synth.kv_bf16 if dtype == sz.BF16 else kv_synth.kv_e5m2
+    n = 32768 * 1024
+    cbs_or = {k: calibrated(dtype, seed=1, tokens=1024, layer=0, kind=k) for k in "KV"}
+    gcb = {k: gpu_codebook(c) for k, c in cbs_or.items()}
+    items = [(0, "K"), (0, "V"), (31, "K"), (31, "V")]
+    xs = [gen(32768, 0, layer, kind, device="cuda") for layer, kind in items]
+    outs = [torch.full((sz.total_bytes(n, n // 20, dtype) + 512,), POISON, dtype=torch.uint8, device="cuda") for _ in items]
+    ws = sz.Workspace(n, dtype)
+    rec = sz.new_sizes_array(len(items))
+    sz.compress_batch(xs, [gcb[k] for _, k in items], outs, ws, rec, capacities=[o.numel() - 512 for o in outs])
+    torch.cuda.synchronize()
+    got = sz.read_sizes_array(rec)
+    for i, (layer, kind) in enumerate(items):
+        print(f"case full-size batch dtype={dtype} L{layer}{kind}", flush=True)
+        ref, m = oracle.compress(kv_synth.to_numpy_words(xs[i]), cbs_or[kind])
+        assert got[i] == (ref.size, m, 0), (i, got[i], ref.size, m)
+        assert np.array_equal(outs[i][:ref.size].cpu().numpy(), ref), f"L{layer}{kind}: batch stream differs from the oracle's"
+        assert (outs[i][ref.size:ref.size + 512].cpu().numpy() == POISON).all()
+    ys = [torch.empty_like(x) for x in xs]
+    st = sz.new_sizes()
+    sz.decompress_batch(outs, [g[0] for g in got], [n] * len(items), [gcb[k] for _, k in items], ys, st)
+    torch.cuda.synchronize()
+    assert sz.read_sizes(st)[2] == 0
+    for x, y in zip(xs, ys):
+        assert torch.equal(x, y), "batch round trip differs"
+
+
+def test_batch_tensor_larger_than_a_full_group():
+    """an E5M2 tensor of 70 Mi elements has more chunks than the largest group the batch kernel forms can share at 64
+    per workgroup: the grid is cut down to one group of that size; a small tensor rides in the same launch"""
+    dtype = sz.FP8_E5M2
+    cb_or = calibrated(dtype, seed=1, tokens=1024, layer=0, kind="K")
+    cb = gpu_codebook(cb_or)
+    xs = [kv_synth.kv_e5m2(70 * 1024, 0, 5, "K", device="cuda"), kv_synth.kv_e5m2(300, 0, 6, "K", device="cuda")[:-77].contiguous()]
+    outs = [torch.full((sz.total_bytes(x.numel(), x.numel() // 20, dtype) + 512,), POISON, dtype=torch.uint8, device="cuda") for x in xs]
+    ws = sz.Workspace(xs[0].numel(), dtype)
+    rec = sz.new_sizes_array(2)
+    sz.compress_batch(xs, [cb, cb], outs, ws, rec, capacities=[o.numel() - 512 for o in outs])
+    torch.cuda.synchronize()
+    got = sz.read_sizes_array(rec)
+    ys = [torch.empty_like(x) for x in xs]
+    st = sz.new_sizes()
+    sz.decompress_batch(outs, [g[0] for g in got], [x.numel() for x in xs], [cb, cb], ys, st)
+    torch.cuda.synchronize()
+    assert sz.read_sizes(st)[2] == 0
+    for i, x in enumerate(xs):
+        ref, m = oracle.compress(kv_synth.to_numpy_words(x), cb_or)
+        assert got[i] == (ref.size, m, 0), (i, got[i], ref.size, m)
+        assert np.array_equal(outs[i][:ref.size].cpu().numpy(), ref), f"item {i}: stream differs from the oracle's"
+        assert torch.equal(x, ys[i])
