@@ -781,7 +781,8 @@ __global__ __launch_bounds__(T, F::kBatchWavesPerSimd) void compress_batch_kerne
     }
     if (PFW > 1 && wave > 0 && wave < PFW) {
       uint32_t lo = 0, al = 0;
-      const bool ready = pf.issued && pf.reduce(epoch + prev_item, b, lo, al);
+      // a wave whose words lie beyond the group has nothing to wait for
+      const bool ready = pf.first >= G || (pf.issued && pf.reduce(epoch + prev_item, b, lo, al));
       if (lane == 0) {
         s_pf[wave][0] = ready ? 1u : 0u;
         s_pf[wave][1] = lo;
