@@ -273,10 +273,15 @@ __device__ inline uint32_t process_chunk_e5m2(const Planes& a, const uint16_t* l
     const uint64_t sm_off = (cbase / 8) * 3 + (uint32_t)(lane >> 1) * 12;
     uint8_t* sm_dst = a.out + a.off_sm + (cbase / 8) * 3 + (uint32_t)(lane >> 1) * 12;   // uniform pointer + lane offset
     // the pair's 12 bytes, all in the even lane
-    const uint32_t d0 = lo, d1 = (hi & 0xffffu) | (lo_up << 16), d2 = (lo_up >> 16) | (hi_up << 16);
+    uint32_t d0 = lo, d1 = (hi & 0xffffu) | (lo_up << 16), d2 = (lo_up >> 16) | (hi_up << 16);
     if (FULL) {
-      // even lanes only: one instruction writes the chunk's 384 bytes back to back
-      if (!(lane & 1)) st_stream(reinterpret_cast<u32x3*>(sm_dst), u32x3{d0, d1, d2});
+      // Both lanes of a pair write the pair's 12 bytes (quad_perm [0,0,2,2]: the even neighbour's bits): one
+      // instruction writes the chunk's 384 bytes back to back, and it is issued whatever the lane -- so the
+      // compiler can count on it when it works out how long a wave must wait for the loads issued before it.
+      const uint32_t lo_dn = __builtin_amdgcn_update_dpp(0u, lo, 0xA0, 0xf, 0xf, false);
+      const uint32_t hi_dn = __builtin_amdgcn_update_dpp(0u, hi, 0xA0, 0xf, 0xf, false);
+      d0 = lo_dn; d1 = (hi_dn & 0xffffu) | (lo_up << 16);
+      st_stream(reinterpret_cast<u32x3*>(sm_dst), u32x3{d0, d1, d2});
       st_stream(reinterpret_cast<u32x2*>(a.out + a.off_code + (cbase >> 1)) + (uint32_t)lane, u32x2{code[0], code[1]});
     } else {
       // dword by dword up to the padded end of each plane; the pad can reach 128 bytes past the
@@ -319,6 +324,12 @@ __device__ inline uint32_t process_chunk_e5m2(const Planes& a, const uint16_t* l
 struct Bf16 {
   static constexpr int ES = 2;   // bytes per word
   struct Regs { uint32_t w[2][4]; };
+  __device__ static inline void arrived(Regs& r) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int d = 0; d < 4; ++d) asm volatile("" : "+v"(r.w[h][d]));
+  }
   // Chunks (2 KB each) a wave takes per step of the dense pass in the batch kernel.  The single-tensor kernel
   // takes one: two cost it more than 64 registers per lane, and with 64 two of its launches fit a compute unit
   // side by side, so that two compress calls on different streams can never starve each other of room.
@@ -342,6 +353,10 @@ struct Bf16 {
 struct E5m2 {
   static constexpr int ES = 1;
   struct Regs { uint32_t w[4]; };
+  __device__ static inline void arrived(Regs& r) {
+#pragma unroll
+    for (int d = 0; d < 4; ++d) asm volatile("" : "+v"(r.w[d]));
+  }
   // batch kernel: eight workgroups of 256 per CU, eight waves per SIMD at 64 registers.  Many small workgroups
   // matter more than the wave count: while one of them exchanges counts and writes escape records out, the others
   // keep the CU's memory pipeline busy (measured on 64 tensors of 32 MiB: 1 x 1024 threads 2.2 TB/s, 4 x 256 and
@@ -449,6 +464,37 @@ __device__ inline uint32_t dense_pass(const Planes& P, const uint16_t* lut, uint
       else F::template load<false>(P, cptr, cbase, lane, r);
     }
   };
+  if constexpr (S == 1) {
+    // Only the tensor's last chunk can be ragged, and it is the last of its wave: the loop takes complete chunks
+    // only (no branch between two ways of storing stands between a chunk's loads and the wait for them), the
+    // ragged one comes after it.
+    const bool last_ragged = mine > 0 && !F::full(P, (uint64_t)(r0 + wave + (mine - 1) * NW) * kChunk);
+    const uint32_t fast = mine - (last_ragged ? 1u : 0u);
+    auto chunk = [&](uint32_t it, auto complete) {
+      const uint32_t k = wave + it * NW;
+      const uint64_t cbase = (uint64_t)(r0 + k) * kChunk;
+      if (it == mid_it) mid();
+      const LdsSink lds{L.stage_pk, L.stage_val, it << 10, L.cap};
+      const uint32_t cnt = F::template process<decltype(complete)::value, true>(P, lut, park, cbase, lane, w[0], wave_count, lds);
+      if (lane == 0) {
+        L.s_off[k] = cnt;
+        L.s_wstart[k] = (uint16_t)(wave_count < 0xffffu ? wave_count : 0xffffu);
+      }
+      wave_count += cnt;
+    };
+    fetch(0, w[0]);
+    // The first chunk has to be there before the loop is entered: a load still pending on entry would put the
+    // compiler's wait into the loop header, where every iteration pays it in full (all loads and stores issued
+    // so far), the next chunk's loads included.
+    F::arrived(w[0]);
+    for (uint32_t it = 0; it < fast; ++it) {
+      fetch(it + 1, nx[0]);
+      chunk(it, std::true_type{});
+      w[0] = nx[0];
+    }
+    if (last_ragged) chunk(mine - 1, std::false_type{});
+    return wave_count;
+  }
 #pragma unroll
   for (uint32_t s = 0; s < S; ++s) fetch(s, w[s]);
   for (uint32_t it0 = 0; it0 < mine; it0 += S) {
