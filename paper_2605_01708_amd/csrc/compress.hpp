@@ -330,14 +330,10 @@ struct Bf16 {
 #pragma unroll
       for (int d = 0; d < 4; ++d) asm volatile("" : "+v"(r.w[h][d]));
   }
-  // Chunks (2 KB each) a wave takes per step of the dense pass in the batch kernel.  The single-tensor kernel
-  // takes one: two cost it more than 64 registers per lane, and with 64 two of its launches fit a compute unit
-  // side by side, so that two compress calls on different streams can never starve each other of room.
-  static constexpr uint32_t kBatchPerStep = 2;
-  // batch kernel: two workgroups of 512 per CU (its 125 registers allow no more than 16 waves), 512 staged escapes
-  // per wave.  Against one workgroup of 1024: the same on 64 MiB tensors, 2 to 4 % faster on 4 to 32 MiB ones.
+  // batch kernel: two workgroups of 512 per CU, 512 staged escapes per wave.  Against one workgroup of 1024: the
+  // same on 64 MiB tensors, 2 to 4 % faster on 4 to 32 MiB ones; four workgroups of 512 (eight waves per SIMD) are
+  // no faster, eight of 256 are 3 % slower.
   static constexpr int kBatchThreads = 512, kBatchWgsPerCu = 2, kBatchWavesPerSimd = 4;
-  static constexpr bool kBatchLutAtFixedPlace = false;   // bound by memory, not by instructions: measured a few percent slower with it
   static constexpr uint32_t kBatchStageCap = kStageCap;
   static constexpr int kLutShift = 0;       // the LDS encode table holds the entry of exponent e in slot e
   // a chunk goes the fast way if it is complete (then nothing of a pad is its business: N is a multiple of 1024 there)
@@ -364,8 +360,6 @@ struct E5m2 {
   // often than BF16 ones, and a wave that does overflow takes the second pass of write_out.
   static constexpr int kBatchThreads = 256, kBatchWgsPerCu = 8, kBatchWavesPerSimd = 8;
   static constexpr uint32_t kBatchStageCap = 256;
-  static constexpr bool kBatchLutAtFixedPlace = true;
-  static constexpr uint32_t kBatchPerStep = 1;   // 1 KB each: a second chunk per step costs more in registers and code than it hides
   // The LDS encode table holds the entry of exponent e in slots 2 e and 2 e + 1: its byte offset is then
   // the word's byte with the sign and mantissa bits masked off, one instruction per element.
   static constexpr int kLutShift = 1;
@@ -439,18 +433,17 @@ struct NoHook {
   __device__ inline void operator()() const {}
 };
 
-// dense pass of one wave over its chunks of the range, S of them per step; the loads of
-// the next step are issued before this step's chunks are worked on (what a wave has in flight at
-// that point is what keeps the memory system busy: 2 to 4 KB per wave).  `mid` is
-// called once, half way through (not at all by a wave without chunks).  Returns the wave's
-// escape count.
-template <int NW, typename F, uint32_t S, typename Hook>
+// dense pass of one wave over its chunks of the range; the loads of the next chunk are issued before
+// this chunk is worked on (what a wave has in flight at that point is what keeps the memory system
+// busy: 1 to 2 KB per wave).  `mid` is called once, half way through (not at all by a wave without
+// chunks).  Returns the wave's escape count.
+template <int NW, typename F, typename Hook>
 __device__ inline uint32_t dense_pass(const Planes& P, const uint16_t* lut, uint32_t* park, const RangeLds& L,
                                       uint32_t r0, uint32_t nb, int wave, int lane, Hook& mid) {
   uint32_t wave_count = 0;
   const uint32_t mine = nb > (uint32_t)wave ? (nb - wave + NW - 1) / NW : 0u;   // chunks of this wave
   const uint32_t mid_it = mine / 2;
-  typename F::Regs w[S], nx[S];
+  typename F::Regs w, nx;
   // paged tensor: the pool pages of all of the wave's chunks at once (lane it <-> its it-th chunk), so that no
   // table read stands in front of a chunk's loads later
   uint32_t my_pages = 0;
@@ -464,62 +457,34 @@ __device__ inline uint32_t dense_pass(const Planes& P, const uint16_t* lut, uint
       else F::template load<false>(P, cptr, cbase, lane, r);
     }
   };
-  if constexpr (S == 1) {
-    // Only the tensor's last chunk can be ragged, and it is the last of its wave: the loop takes complete chunks
-    // only (no branch between two ways of storing stands between a chunk's loads and the wait for them), the
-    // ragged one comes after it.
-    const bool last_ragged = mine > 0 && !F::full(P, (uint64_t)(r0 + wave + (mine - 1) * NW) * kChunk);
-    const uint32_t fast = mine - (last_ragged ? 1u : 0u);
-    auto chunk = [&](uint32_t it, auto complete) {
-      const uint32_t k = wave + it * NW;
-      const uint64_t cbase = (uint64_t)(r0 + k) * kChunk;
-      if (it == mid_it) mid();
-      const LdsSink lds{L.stage_pk, L.stage_val, it << 10, L.cap};
-      const uint32_t cnt = F::template process<decltype(complete)::value, true>(P, lut, park, cbase, lane, w[0], wave_count, lds);
-      if (lane == 0) {
-        L.s_off[k] = cnt;
-        L.s_wstart[k] = (uint16_t)(wave_count < 0xffffu ? wave_count : 0xffffu);
-      }
-      wave_count += cnt;
-    };
-    fetch(0, w[0]);
-    // The first chunk has to be there before the loop is entered: a load still pending on entry would put the
-    // compiler's wait into the loop header, where every iteration pays it in full (all loads and stores issued
-    // so far), the next chunk's loads included.
-    F::arrived(w[0]);
-    for (uint32_t it = 0; it < fast; ++it) {
-      fetch(it + 1, nx[0]);
-      chunk(it, std::true_type{});
-      w[0] = nx[0];
+  // Only the tensor's last chunk can be ragged, and it is the last of its wave: the loop takes complete chunks
+  // only (no branch between two ways of storing stands between a chunk's loads and the wait for them), the
+  // ragged one comes after it.
+  const bool last_ragged = mine > 0 && !F::full(P, (uint64_t)(r0 + wave + (mine - 1) * NW) * kChunk);
+  const uint32_t fast = mine - (last_ragged ? 1u : 0u);
+  auto chunk = [&](uint32_t it, auto complete) {
+    const uint32_t k = wave + it * NW;
+    const uint64_t cbase = (uint64_t)(r0 + k) * kChunk;
+    if (it == mid_it) mid();
+    const LdsSink lds{L.stage_pk, L.stage_val, it << 10, L.cap};
+    const uint32_t cnt = F::template process<decltype(complete)::value, true>(P, lut, park, cbase, lane, w, wave_count, lds);
+    if (lane == 0) {
+      L.s_off[k] = cnt;
+      L.s_wstart[k] = (uint16_t)(wave_count < 0xffffu ? wave_count : 0xffffu);
     }
-    if (last_ragged) chunk(mine - 1, std::false_type{});
-    return wave_count;
+    wave_count += cnt;
+  };
+  fetch(0, w);
+  // The first chunk has to be there before the loop is entered: a load still pending on entry would put the
+  // compiler's wait into the loop header, where every iteration pays it in full (all loads and stores issued
+  // so far), the next chunk's loads included.
+  F::arrived(w);
+  for (uint32_t it = 0; it < fast; ++it) {
+    fetch(it + 1, nx);
+    chunk(it, std::true_type{});
+    w = nx;
   }
-#pragma unroll
-  for (uint32_t s = 0; s < S; ++s) fetch(s, w[s]);
-  for (uint32_t it0 = 0; it0 < mine; it0 += S) {
-#pragma unroll
-    for (uint32_t s = 0; s < S; ++s) fetch(it0 + S + s, nx[s]);
-#pragma unroll
-    for (uint32_t s = 0; s < S; ++s) {
-      const uint32_t it = it0 + s;
-      if (it < mine) {
-        const uint32_t k = wave + it * NW;
-        const uint64_t cbase = (uint64_t)(r0 + k) * kChunk;
-        if (it == mid_it) mid();
-        const LdsSink lds{L.stage_pk, L.stage_val, it << 10, L.cap};
-        const uint32_t cnt = F::full(P, cbase) ? F::template process<true, true>(P, lut, park, cbase, lane, w[s], wave_count, lds)
-                                               : F::template process<false, true>(P, lut, park, cbase, lane, w[s], wave_count, lds);
-        if (lane == 0) {
-          L.s_off[k] = cnt;
-          L.s_wstart[k] = (uint16_t)(wave_count < 0xffffu ? wave_count : 0xffffu);
-        }
-        wave_count += cnt;
-      }
-    }
-#pragma unroll
-    for (uint32_t s = 0; s < S; ++s) w[s] = nx[s];
-  }
+  if (last_ragged) chunk(mine - 1, std::false_type{});
   return wave_count;
 }
 
@@ -651,7 +616,7 @@ __global__ __launch_bounds__(T, (T == 1024 ? 8 : 1)) void compress_kernel(const 
   uint32_t r0, nb;
   my_range(a.seg_chunk0, a.seg_chunks, gridDim.x, b, r0, nb);
   NoHook no_hook;
-  const uint32_t wave_count = dense_pass<NW, F, 1>(a.p, lut, park, L, r0, nb, wave, lane, no_hook);
+  const uint32_t wave_count = dense_pass<NW, F>(a.p, lut, park, L, r0, nb, wave, lane, no_hook);
   if (lane == 0) s_red[wave] = wave_count;
   __syncthreads();
 
@@ -776,8 +741,8 @@ __global__ __launch_bounds__(T, F::kBatchWavesPerSimd) void compress_batch_kerne
   static_assert(PFW <= NW && PFW <= 4, "prefetching waves");
   __shared__ uint32_t s_pf[4][4];          // parts of the waves 1 .. PFW - 1: ready, lower, all
   __shared__ uint16_t lut[kBatchLuts][256];
-  // kBatchLutAtFixedPlace: the table of the tensor whose dense pass is running, at an address the compiler
-  // knows: its lookups carry the table's place as an immediate, one address instruction less per element
+  // the table of the tensor whose dense pass is running, at an address the compiler knows: its lookups carry
+  // the table's place as an immediate, one address instruction less per element
   __shared__ uint16_t lut_now[256];
   __shared__ uint16_t stage_pk[3][NW][CAP];   // three sets: a wave may stage tensor i + 1 while another still writes out i - 1
   __shared__ uint8_t stage_val[3][NW][CAP];
@@ -793,7 +758,7 @@ __global__ __launch_bounds__(T, F::kBatchWavesPerSimd) void compress_batch_kerne
   uint32_t* park = reinterpret_cast<uint32_t*>(&s_park[tid]);
 
   for (int i = tid; i < (int)(kBatchLuts * 256); i += T) lut[i >> 8][i & 255] = a.lut[i >> 8][(i & 255) >> F::kLutShift];
-  if (F::kBatchLutAtFixedPlace && grp < a.n_items)
+  if (grp < a.n_items)
     for (int i = tid; i < 256; i += T) lut_now[i] = a.lut[a.lut_of[grp]][i >> F::kLutShift];
   const uint32_t epoch = ld_agent(&a.ws_hdr[0]);
   const uint32_t err_before = b == 0 ? ld_agent(&a.ws_hdr[2]) : 0u;
@@ -822,7 +787,7 @@ __global__ __launch_bounds__(T, F::kBatchWavesPerSimd) void compress_batch_kerne
     if (have) {
       P = make_planes(item_words(a.paging, a.item[i].in), a.item[i].out, a.item[i].n, a.item[i].capacity, (int)a.dtype);
       my_range(0, P.n_chunks, G, b, r0, nb);
-      wave_count = dense_pass<NW, F, F::kBatchPerStep>(P, F::kBatchLutAtFixedPlace ? lut_now : lut[a.lut_of[i]], park, L, r0, nb, wave, lane, pf);
+      wave_count = dense_pass<NW, F>(P, lut_now, park, L, r0, nb, wave, lane, pf);
       if (lane == 0) s_red[wave] = wave_count;
     }
     if (PFW > 1 && wave > 0 && wave < PFW) {
@@ -881,7 +846,7 @@ __global__ __launch_bounds__(T, F::kBatchWavesPerSimd) void compress_batch_kerne
       }
     } else if (wave == 1 && have) {
       scan_range(s_off[set], nb, lane);
-    } else if (F::kBatchLutAtFixedPlace && wave >= 2 && i + n_groups < a.n_items) {
+    } else if (wave >= 2 && i + n_groups < a.n_items) {
       // every dense pass of tensor i is over: the table of this group's next tensor
       const uint16_t* next = lut[a.lut_of[i + n_groups]];
       for (int j = tid - 128; j < 256; j += T - 128) lut_now[j] = next[j];
