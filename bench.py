@@ -28,6 +28,7 @@ import kv_synth
 import paper_2605_01708_amd as sz
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
+SINGLE_THREADS = {"Bf16": 512, "E5m2": 1024}   # workgroup size of compress_kernel per word type
 BATCH_THREADS = {"Bf16": 512, "E5m2": 256}   # workgroup size of compress_batch_kernel per word type (its template argument)
 
 WORKLOADS = {
@@ -334,7 +335,7 @@ def main():
             "compress_frac_of_peak": round(alg1 / c1_us * 1e-3 / HBM_PEAK_GBPS, 4),
             "decompress_GBps": round(raw_bytes / d1_us * 1e-3, 1), "decompress_launch_us": round(d1_us, 2),
             "decompress_frac_of_peak": round(alg1 / d1_us * 1e-3 / HBM_PEAK_GBPS, 4),
-            "kernels": [f"compress_kernel<1024, {fmt}>", f"decompress_kernel<D{fmt}>"],
+            "kernels": [f"compress_kernel<{SINGLE_THREADS[fmt]}, {fmt}>", f"decompress_kernel<D{fmt}>"],
             "two_streams": {"compress_GBps": round(raw_bytes / two[0] * 1e-3, 1), "compress_us": round(two[0], 2),
                             "compress_frac_of_peak": round(alg1 / two[0] * 1e-3 / HBM_PEAK_GBPS, 4),
                             "decompress_GBps": round(raw_bytes / two[1] * 1e-3, 1), "decompress_us": round(two[1], 2),
