@@ -1,6 +1,8 @@
 """Seeded random cases through every entry point of the library against the oracles: sizes anywhere between
 nothing and a few hundred chunks, exponent laws from "one value" to "uniform over all", codebooks from perfect to
 useless.  Bit-exact streams and round trips, as everywhere."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -12,6 +14,8 @@ import paper_2605_01708_amd as sz
 pytestmark = pytest.mark.gpu
 
 EXPS = {sz.BF16: 256, sz.FP8_E5M2: 32, sz.FP8_E4M3: 16}
+# more seeds on request: SPLITZIP_FUZZ_ROUNDS=10 runs each test on ten consecutive seeds
+ROUNDS = max(1, int(os.environ.get("SPLITZIP_FUZZ_ROUNDS", "1")))
 ODT = {sz.BF16: oracle.BF16, sz.FP8_E5M2: oracle.E5M2}
 
 
@@ -54,9 +58,10 @@ def dev(x):
     return torch.from_numpy(x.view(np.int16).copy() if x.dtype == np.uint16 else x.copy()).cuda()
 
 
-def test_single_and_batch_calls_on_random_cases():
+@pytest.mark.parametrize("round_", range(ROUNDS))
+def test_single_and_batch_calls_on_random_cases(round_):
     assert torch.cuda.is_available()
-    rng = np.random.default_rng(20260501)
+    rng = np.random.default_rng(20260501 + 1000 * round_)
     for dt in (sz.BF16, sz.FP8_E5M2):
         ws = sz.Workspace(400_000, dt)
         for case in range(12):
@@ -97,8 +102,9 @@ def test_single_and_batch_calls_on_random_cases():
             assert torch.equal(y[:xs[0].size], xd[0])
 
 
-def test_variant_calls_on_random_cases():
-    rng = np.random.default_rng(20260502)
+@pytest.mark.parametrize("round_", range(ROUNDS))
+def test_variant_calls_on_random_cases(round_):
+    rng = np.random.default_rng(20260502 + 1000 * round_)
     combos = [(sz.BF16, 4, 16, sz.ESC_POS, 1024), (sz.BF16, 4, 15, sz.ESC_SENTINEL, 256), (sz.BF16, 3, 8, sz.ESC_ABS32, 0),
               (sz.FP8_E5M2, 3, 7, sz.ESC_SENTINEL, 1024), (sz.FP8_E5M2, 4, 16, sz.ESC_POS, 256),
               (sz.FP8_E4M3, 3, 8, sz.ESC_POS, 1024), (sz.FP8_E4M3, 3, 5, sz.ESC_ABS32, 0), (sz.BF16, 4, 3, sz.ESC_POS, 256)]
