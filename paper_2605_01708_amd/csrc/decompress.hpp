@@ -42,28 +42,32 @@ __device__ void decompress_check_header(const DecompressArgs& a, const uint8_t* 
   }
 }
 
-// BF16 dense decode of one chunk by one wave into registers: two half-chunks, 8 elements per lane
-// each; o[4 h + d] holds elements 2 d and 2 d + 1 of the lane's group in half h
-template <bool FULL>
-__device__ inline void decode_chunk_bf16(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane, uint32_t (&o)[8]) {
+// BF16: the plane words of one chunk as a wave holds them, two half-chunks of 8 elements per lane each
+struct PlanesBf16 {
   u32x2 sm[2];
   uint32_t cd[2];
+};
+template <bool FULL>
+__device__ inline void load_planes_bf16(const DecompressArgs& a, uint64_t cbase, int lane, PlanesBf16& in) {
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     const uint64_t g0 = cbase + h * kHalf + lane * 8;
-    sm[h] = u32x2{0u, 0u};
-    cd[h] = 0;
-    if (FULL || g0 < a256(a.sm_bytes)) sm[h] = ld_stream(reinterpret_cast<const u32x2*>(a.comp + a.off_sm + g0));
+    in.sm[h] = u32x2{0u, 0u};
+    in.cd[h] = 0;
+    if (FULL || g0 < a256(a.sm_bytes)) in.sm[h] = ld_stream(reinterpret_cast<const u32x2*>(a.comp + a.off_sm + g0));
     if (FULL || (g0 >> 1) < a256(a.code_bytes))
-      cd[h] = ld_stream(reinterpret_cast<const uint32_t*>(a.comp + a.off_code + (g0 >> 1)));
+      in.cd[h] = ld_stream(reinterpret_cast<const uint32_t*>(a.comp + a.off_code + (g0 >> 1)));
   }
+}
+// dense decode into registers: o[4 h + d] holds elements 2 d and 2 d + 1 of the lane's group in half h
+__device__ inline void decode_chunk_bf16(const PlanesBf16& in, const uint32_t* tbl, uint32_t (&o)[8]) {
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
-    const uint32_t smw[2] = {sm[h].x, sm[h].y};
+    const uint32_t smw[2] = {in.sm[h].x, in.sm[h].y};
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
       // code byte b -> both exponents already in place (bits 7..14 and 23..30)
-      const uint32_t cb = (cd[h] >> (8 * b)) & 0xffu;
+      const uint32_t cb = (in.cd[h] >> (8 * b)) & 0xffu;
       // [a0, a0, a1, a1], then keep mantissa in the low and sign in the high byte of each half-word (eq. (2))
       const uint32_t p = byte_perm(0u, smw[b >> 1], (b & 1) ? 0x03030202u : 0x01010000u);
       o[4 * h + b] = (p & 0x807f807fu) | tbl[cb];
@@ -91,33 +95,31 @@ __device__ inline void store_chunk_bf16(const DecompressArgs& a, uint8_t* cptr, 
   }
 }
 
-// E5M2 dense decode of one chunk by one wave into registers: 16 elements per lane, o[d] holds
-// elements 4 d .. 4 d + 3.  Lanes 2p and 2p+1 share 12 plane bytes: the even lane loads the first
-// 8, the odd lane the last 4.
+// E5M2: the plane words of one chunk as a wave holds them, 16 elements per lane.  Lanes 2p and 2p+1 share 12
+// bytes of the 3-bit plane: the even lane loads bytes 0..7 of them, the odd lane bytes 4..11 -- the same
+// instruction for every lane (no branch, no register written from two places), the overlap costs nothing.
+struct PlanesE5m2 {
+  u32x2 sm, cd;
+};
 template <bool FULL>
-__device__ inline void decode_chunk_e5m2(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane, uint32_t (&o)[4]) {
+__device__ inline void load_planes_e5m2(const DecompressArgs& a, uint64_t cbase, int lane, PlanesE5m2& in) {
   const uint64_t g0 = cbase + lane * 16;
-  const uint64_t sm_off = (cbase / 8) * 3 + (uint32_t)(lane >> 1) * 12;
-  const uint8_t* sm_src = a.comp + a.off_sm + sm_off;
-  const uint64_t sm_end = a256(a.sm_bytes);
-  uint32_t d0 = 0, d1 = 0;
-  u32x2 cd = u32x2{0u, 0u};
-  if (lane & 1) {
-    if (FULL || sm_off + 8 < sm_end) d0 = ld_stream(reinterpret_cast<const uint32_t*>(sm_src + 8));
-  } else if (FULL || sm_off + 4 < sm_end) {
-    const u32x2 v = ld_stream(reinterpret_cast<const u32x2*>(sm_src));   // 8 bytes below a multiple of 256: both in the stream
-    d0 = v.x;
-    d1 = v.y;
-  } else if (sm_off < sm_end) {
-    d0 = ld_stream(reinterpret_cast<const uint32_t*>(sm_src));
-  }
-  if (FULL || (g0 >> 1) < a256(a.code_bytes)) cd = ld_stream(reinterpret_cast<const u32x2*>(a.comp + a.off_code + (g0 >> 1)));
-  const uint32_t d1_dn = __builtin_amdgcn_update_dpp(0u, d1, 0xA0, 0xf, 0xf, false);   // quad_perm [0,0,2,2]: the even neighbour's second dword
-  // the lane's 48 plane bits
-  const uint32_t lo = (lane & 1) ? (d1_dn >> 16) | (d0 << 16) : d0;
-  const uint32_t hi = (lane & 1) ? d0 >> 16 : d1 & 0xffffu;
+  const uint64_t off = (cbase / 8) * 3 + (uint32_t)(lane >> 1) * 12 + ((lane & 1) ? 4u : 0u);
+  const uint8_t* src = a.comp + a.off_sm + off;
+  const uint64_t sm_end = a256(a.sm_bytes);   // a multiple of 256; off is a multiple of 4
+  in.sm = u32x2{0u, 0u};
+  in.cd = u32x2{0u, 0u};
+  if (FULL || off + 8 <= sm_end) in.sm = ld_stream(reinterpret_cast<const u32x2*>(src));
+  else if (off + 4 <= sm_end) in.sm.x = ld_stream(reinterpret_cast<const uint32_t*>(src));
+  if (FULL || (g0 >> 1) < a256(a.code_bytes)) in.cd = ld_stream(reinterpret_cast<const u32x2*>(a.comp + a.off_code + (g0 >> 1)));
+}
+// dense decode into registers: o[d] holds elements 4 d .. 4 d + 3
+__device__ inline void decode_chunk_e5m2(const PlanesE5m2& in, const uint32_t* tbl, int lane, uint32_t (&o)[4]) {
+  // the lane's 48 plane bits: the even lane's start at its first byte, the odd lane's two bytes further on
+  const uint32_t lo = (lane & 1) ? (in.sm.x >> 16) | (in.sm.y << 16) : in.sm.x;
+  const uint32_t hi = (lane & 1) ? in.sm.y >> 16 : in.sm.y & 0xffffu;
   const uint32_t r[4] = {lo & 0xfffu, (lo >> 12) & 0xfffu, (lo >> 24) | ((hi & 0xfu) << 8), (hi >> 4) & 0xfffu};
-  const uint32_t cdw[2] = {cd.x, cd.y};
+  const uint32_t cdw[2] = {in.cd.x, in.cd.y};
 #pragma unroll
   for (int d = 0; d < 4; ++d) {
     // two code bytes -> four exponents already in place (bits 2..6 of each byte)
@@ -157,8 +159,13 @@ struct DBf16 {
   // table entry for a code byte: both exponents in place for one dword of output
   __device__ static inline uint32_t table(int cb, const uint8_t* dec) { return ((uint32_t)dec[cb & 15] << 7) | ((uint32_t)dec[cb >> 4] << 23); }
   __device__ static inline bool full(const DecompressArgs& a, uint64_t cbase) { return cbase + kChunk <= a.n; }
+  typedef PlanesBf16 In;
   template <bool FULL>
-  __device__ static inline void decode(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane, Out& r) { decode_chunk_bf16<FULL>(a, tbl, cbase, lane, r.o); }
+  __device__ static inline void load(const DecompressArgs& a, uint64_t cbase, int lane, In& in) { load_planes_bf16<FULL>(a, cbase, lane, in); }
+  __device__ static inline void decode(const In& in, const uint32_t* tbl, int lane, Out& r) { decode_chunk_bf16(in, tbl, r.o); }
+  __device__ static inline void arrived(In& in) {
+    asm volatile("" : "+v"(in.sm[0].x), "+v"(in.sm[0].y), "+v"(in.sm[1].x), "+v"(in.sm[1].y), "+v"(in.cd[0]), "+v"(in.cd[1]));
+  }
   template <bool FULL>
   __device__ static inline void store(const DecompressArgs& a, uint8_t* cptr, uint64_t cbase, int lane, const Out& r) { store_chunk_bf16<FULL>(a, cptr, cbase, lane, r.o); }
   // the scatter correction of the element at chunk position pos (wave-uniform), in the registers of the lane that holds it
@@ -192,8 +199,11 @@ struct DE5m2 {
   struct Out { uint32_t o[4]; };
   __device__ static inline uint32_t table(int cb, const uint8_t* dec) { return ((uint32_t)dec[cb & 15] << 2) | ((uint32_t)dec[cb >> 4] << 10); }
   __device__ static inline bool full(const DecompressArgs& a, uint64_t cbase) { return cbase + kChunk < a.n; }
+  typedef PlanesE5m2 In;
   template <bool FULL>
-  __device__ static inline void decode(const DecompressArgs& a, const uint32_t* tbl, uint64_t cbase, int lane, Out& r) { decode_chunk_e5m2<FULL>(a, tbl, cbase, lane, r.o); }
+  __device__ static inline void load(const DecompressArgs& a, uint64_t cbase, int lane, In& in) { load_planes_e5m2<FULL>(a, cbase, lane, in); }
+  __device__ static inline void decode(const In& in, const uint32_t* tbl, int lane, Out& r) { decode_chunk_e5m2(in, tbl, lane, r.o); }
+  __device__ static inline void arrived(In& in) { asm volatile("" : "+v"(in.sm.x), "+v"(in.sm.y), "+v"(in.cd.x), "+v"(in.cd.y)); }
   template <bool FULL>
   __device__ static inline void store(const DecompressArgs& a, uint8_t* cptr, uint64_t cbase, int lane, const Out& r) { store_chunk_e5m2<FULL>(a, cptr, cbase, lane, r.o); }
   __device__ static inline bool patch_reg(Out& r, int lane, uint32_t pos, uint32_t val) {
@@ -254,32 +264,51 @@ __device__ inline void decompress_tile(const DecompressArgs& a, const uint8_t* d
   const uint8_t* val_arr = a.comp + off_val;
   __syncthreads();
 
-  for (uint32_t c = 0; c < cpw; ++c) {
-    const uint32_t chunk = wave_chunk0 + c;
-    if (chunk >= a.n_chunks) break;
-    const uint64_t cbase = (uint64_t)chunk * kChunk;
-    const uint32_t lo = __builtin_amdgcn_readlane(my_tab, c), hi = __builtin_amdgcn_readlane(my_tab, c + 1);
+  // The wave's chunks; only the tensor's last chunk can be ragged, and it is the last of its wave.
+  const uint32_t mine = wave_chunk0 < a.n_chunks ? (a.n_chunks - wave_chunk0 < cpw ? a.n_chunks - wave_chunk0 : cpw) : 0u;
+  const bool last_ragged = mine > 0 && !F::full(a, (uint64_t)(wave_chunk0 + mine - 1) * kChunk);
+  const uint32_t fast = mine - (last_ragged ? 1u : 0u);
+  // escape records of the wave's c-th chunk: first record and count, from the offset table (0 records if the entries are inconsistent)
+  auto records = [&](uint32_t c, uint32_t& lo, bool& valid) -> uint32_t {
+    const uint64_t cbase = (uint64_t)(wave_chunk0 + c) * kChunk;
+    const uint32_t hi = __builtin_amdgcn_readlane(my_tab, c + 1);
+    lo = __builtin_amdgcn_readlane(my_tab, c);
     const uint32_t clen = (uint32_t)(a.n - cbase < kChunk ? a.n - cbase : kChunk);
-    const bool esc_valid = hi >= lo && hi - lo <= clen && hi <= M;
-    const uint32_t cnt = esc_valid ? hi - lo : 0u;
-    if (!esc_valid && lane == 0) flag_bad(a);
-    // The chunk's records (the first 64 of them) are fetched while the planes are on their way.  A few
-    // escapes, the usual case, are applied to the decoded words in registers, one after the other; more
-    // of them are applied in parallel, one lane each, to the chunk laid out in LDS.  Either way every
-    // word is stored once.
-    const bool in_regs = cnt > 0 && cnt <= a.reg_patch_max;
-    uint32_t pos = 0, val = 0;
+    valid = hi >= lo && hi - lo <= clen && hi <= M;
+    return valid ? hi - lo : 0u;
+  };
+  // everything chunk c needs from memory: its planes and the first 64 of its records, one lane each
+  struct Fetched {
+    typename F::In in;
+    uint32_t pos, val;
+  };
+  auto fetch = [&](uint32_t c, Fetched& f, auto complete) {
+    uint32_t lo;
+    bool valid;
+    const uint32_t cnt = records(c, lo, valid);
+    f.pos = 0; f.val = 0;
     if ((uint32_t)lane < cnt) {
-      pos = pos_arr[lo + lane];
-      val = val_arr[lo + lane];
+      f.pos = pos_arr[lo + lane];
+      f.val = val_arr[lo + lane];
     }
+    F::template load<decltype(complete)::value>(a, (uint64_t)(wave_chunk0 + c) * kChunk, lane, f.in);
+  };
+  // A few escapes, the usual case, are applied to the decoded words in registers, one after the other; more
+  // of them are applied in parallel, one lane each, to the chunk laid out in LDS.  Either way every word is
+  // stored once.
+  auto chunk = [&](uint32_t c, const Fetched& f, auto complete) {
+    constexpr bool FULL = decltype(complete)::value;
+    const uint64_t cbase = (uint64_t)(wave_chunk0 + c) * kChunk;
+    uint32_t lo;
+    bool esc_valid;
+    const uint32_t cnt = records(c, lo, esc_valid);
+    const uint32_t clen = (uint32_t)(a.n - cbase < kChunk ? a.n - cbase : kChunk);
+    if (!esc_valid && lane == 0) flag_bad(a);
     typename F::Out r;
-    const bool full = F::full(a, cbase);
-    if (full) F::template decode<true>(a, tbl, cbase, lane, r);
-    else F::template decode<false>(a, tbl, cbase, lane, r);
-    if (in_regs) {
+    F::decode(f.in, tbl, lane, r);
+    if (cnt > 0 && cnt <= a.reg_patch_max) {
       for (uint32_t j = 0; j < cnt; ++j) {
-        const uint32_t p = __builtin_amdgcn_readlane(pos, j), v = __builtin_amdgcn_readlane(val, j);
+        const uint32_t p = __builtin_amdgcn_readlane(f.pos, j), v = __builtin_amdgcn_readlane(f.val, j);
         if (p >= clen || !F::patch_reg(r, lane, p, v)) {
           if (lane == 0) flag_bad(a);
         }
@@ -290,7 +319,7 @@ __device__ inline void decompress_tile(const DecompressArgs& a, const uint8_t* d
       F::to_tile(r, t, lane);
       lds_settle();
       for (uint32_t j = lane; j < cnt; j += 64) {
-        uint32_t p = pos, v = val;
+        uint32_t p = f.pos, v = f.val;
         if (j >= 64) {
           p = pos_arr[lo + j];
           v = val_arr[lo + j];
@@ -302,8 +331,26 @@ __device__ inline void decompress_tile(const DecompressArgs& a, const uint8_t* d
       lds_settle();   // the tile is written again for the wave's next chunk
     }
     uint8_t* cptr = chunk_at<F::ES>(a.w, cbase, __builtin_amdgcn_readlane(my_pages, c));
-    if (full) F::template store<true>(a, cptr, cbase, lane, r);
-    else F::template store<false>(a, cptr, cbase, lane, r);
+    F::template store<FULL>(a, cptr, cbase, lane, r);
+  };
+  // The loads of chunk c + 1 are issued before chunk c is decoded.  The first chunk is awaited before the loop,
+  // and the ragged chunk stays out of it altogether, its loads included: the compiler's wait at the bottom of an
+  // iteration then covers the next chunk's loads but not the store issued after them, and no wait stands in
+  // front of the loads.
+  Fetched cur, nxt;
+  if (fast > 0) {
+    fetch(0, cur, std::true_type{});
+    F::arrived(cur.in);
+    asm volatile("" : "+v"(cur.pos), "+v"(cur.val));
+  }
+  for (uint32_t c = 0; c < fast; ++c) {
+    if (c + 1 < fast) fetch(c + 1, nxt, std::true_type{});
+    chunk(c, cur, std::true_type{});
+    cur = nxt;
+  }
+  if (last_ragged) {
+    fetch(mine - 1, cur, std::false_type{});
+    chunk(mine - 1, cur, std::false_type{});
   }
 }
 
