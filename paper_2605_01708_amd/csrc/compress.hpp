@@ -729,7 +729,7 @@ struct ExchangePrefetch {
 // tensor i is taken out of the critical path: a workgroup publishes its count for tensor i, then
 // completes tensor i - 1 (whose counts every workgroup published a whole dense pass ago; the words
 // are even fetched half way through the dense pass of tensor i, so the read costs nothing) and
-// goes on to tensor i + 1.  Staging in LDS is double buffered.  What a single launch pays per
+// goes on to tensor i + 1.  Staging in LDS has three sets (tensor i + 1 may be staged while i - 1 is still written out).  What a single launch pays per
 // tensor -- the wait for the slowest workgroup, the exchange, the write-out and the launch itself
 // -- is paid once per batch here.  Small tensors are shared by a group of workgroups only; the
 // groups work on different tensors at the same time (tensor i belongs to group i mod n_groups).
