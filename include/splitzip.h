@@ -193,7 +193,9 @@ int splitzip_decompress(const void* d_comp, size_t comp_bytes, uint64_t n_elems,
  * single call pays per tensor for the exchange between workgroups, the wait
  * for the slowest of them and the launch is paid once per launch of up to 64
  * tensors, because the exchange of one tensor is hidden under the dense pass
- * of the next.  `items` is a HOST array, read before the call returns.
+ * of the next.  Every item names its own codebook: per-layer codebooks (the
+ * section "Ablation on Layer-Wise Coverage") cost no more than shared ones.
+ * `items` is a HOST array, read before the call returns.
  * d_sizes is a device array of n_items records.  Argument errors are found
  * before anything is enqueued.  Same workspace rules as splitzip_compress
  * (size it for the largest item). */

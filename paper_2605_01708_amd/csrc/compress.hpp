@@ -663,7 +663,6 @@ __global__ __launch_bounds__(T, (T == 1024 ? 8 : 1)) void compress_kernel(const 
 
 // ---- several tensors in one launch ----
 constexpr uint32_t kBatchMax = 64;     // tensors per launch: their descriptors travel as kernel arguments
-constexpr uint32_t kBatchLuts = 2;     // codebooks per launch
 constexpr uint32_t kRing = 4;          // exchange slots: a workgroup can be two tensors ahead of the slowest
 constexpr uint32_t kRingWgs = 2048;    // words per slot
 
@@ -674,7 +673,6 @@ struct BatchItem {
 };
 struct CompressBatchArgs {
   BatchItem item[kBatchMax];
-  uint8_t lut_of[kBatchMax];
   splitzip_sizes* sizes;     // n_items records
   uint32_t* ws_hdr;          // [0] epoch, [2] sticky error flags, [3] groups that are through
   uint64_t* state;           // per group kRing slots of group_wgs words: (epoch + item) << 32 | escapes in the range
@@ -683,9 +681,16 @@ struct CompressBatchArgs {
   uint32_t group_wgs;        // workgroups that share one tensor; the grid is n_groups * group_wgs
   uint32_t await_extra;      // error-path tests: words awaited beyond the group's
   Words paging;              // table and page geometry shared by all tensors (table null: contiguous tensors); base unused
-  uint8_t dec[kBatchLuts][16];
-  uint16_t lut[kBatchLuts][256];
+  uint8_t dec[kBatchMax][16];   // every tensor's codebook, as its 16 decode entries: the kernel builds the encode table from them
 };
+
+// entry of the LDS encode table for exponent e under the codebook dec (wave-uniform): its code, or the escape mark
+__device__ inline uint16_t encode_entry(const uint8_t* dec, uint32_t e) {
+  uint32_t entry = 0x100u;
+#pragma unroll
+  for (uint32_t k = 0; k < 16; ++k) entry = dec[k] == e ? k : entry;
+  return (uint16_t)entry;
+}
 
 // Half way through a dense pass: the loads of the previous tensor's exchange words, so that their
 // latency is hidden.  Wave w of the first few waves (one per 256 workgroups a group can have, four at most)
@@ -740,10 +745,11 @@ __global__ __launch_bounds__(T, F::kBatchWavesPerSimd) void compress_batch_kerne
   constexpr int PFW = F::kBatchWgsPerCu < 4 ? F::kBatchWgsPerCu : 4;   // waves that fetch exchange words ahead, 256 each: for groups of up to 256 PFW workgroups
   static_assert(PFW <= NW && PFW <= 4, "prefetching waves");
   __shared__ uint32_t s_pf[4][4];          // parts of the waves 1 .. PFW - 1: ready, lower, all
-  __shared__ uint16_t lut[kBatchLuts][256];
   // the table of the tensor whose dense pass is running, at an address the compiler knows: its lookups carry
   // the table's place as an immediate, one address instruction less per element
   __shared__ uint16_t lut_now[256];
+  // the tables of the two tensors before it (a wave whose staging overflowed encodes its chunks again in write_out)
+  __shared__ uint16_t lut_old[2][256];
   __shared__ uint16_t stage_pk[3][NW][CAP];   // three sets: a wave may stage tensor i + 1 while another still writes out i - 1
   __shared__ uint8_t stage_val[3][NW][CAP];
   __shared__ uint32_t s_off[3][kMaxRange + 1];
@@ -757,9 +763,8 @@ __global__ __launch_bounds__(T, F::kBatchWavesPerSimd) void compress_batch_kerne
   const uint32_t grp = blockIdx.x / G, b = blockIdx.x % G;
   uint32_t* park = reinterpret_cast<uint32_t*>(&s_park[tid]);
 
-  for (int i = tid; i < (int)(kBatchLuts * 256); i += T) lut[i >> 8][i & 255] = a.lut[i >> 8][(i & 255) >> F::kLutShift];
   if (grp < a.n_items)
-    for (int i = tid; i < 256; i += T) lut_now[i] = a.lut[a.lut_of[grp]][i >> F::kLutShift];
+    for (int i = tid; i < 256; i += T) lut_now[i] = encode_entry(a.dec[grp], (uint32_t)i >> F::kLutShift);
   const uint32_t epoch = ld_agent(&a.ws_hdr[0]);
   const uint32_t err_before = b == 0 ? ld_agent(&a.ws_hdr[2]) : 0u;
   if (tid == 0) s_misc[3] = 0;   // set once an exchange was given up: later ones are not waited for
@@ -830,7 +835,7 @@ __global__ __launch_bounds__(T, F::kBatchWavesPerSimd) void compress_batch_kerne
         }
         if (b == 0) {
           const uint32_t err = err_before | (ok ? 0u : (uint32_t)SPLITZIP_STATUS_INTERNAL);
-          compress_write_trailer(Pprev, a.dec[a.lut_of[prev_item]], a.sizes + prev_item, al, err, lane);
+          compress_write_trailer(Pprev, a.dec[prev_item], a.sizes + prev_item, al, err, lane);
           if (!have && lane == 0) {
             // this group is through.  The last group to get here closes the launch: by then every
             // workgroup has read the header words, because each group completed an exchange.
@@ -846,16 +851,27 @@ __global__ __launch_bounds__(T, F::kBatchWavesPerSimd) void compress_batch_kerne
       }
     } else if (wave == 1 && have) {
       scan_range(s_off[set], nb, lane);
-    } else if (wave >= 2 && i + n_groups < a.n_items) {
-      // every dense pass of tensor i is over: the table of this group's next tensor
-      const uint16_t* next = lut[a.lut_of[i + n_groups]];
-      for (int j = tid - 128; j < 256; j += T - 128) lut_now[j] = next[j];
+    } else if (wave == 2 && have) {
+      // Every dense pass of tensor i is over: its table is kept for its write-out, and the table of this group's
+      // next tensor takes its place -- every entry the escape mark, then the 16 codes by the lanes that own them.
+      // One wave does all of it: its LDS accesses are carried out in program order.
+      const bool more = i + n_groups < a.n_items;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        lut_old[seq & 1u][4 * lane + q] = lut_now[4 * lane + q];
+        if (more) lut_now[4 * lane + q] = 0x100u;
+      }
+      if (more && lane < 16) {
+        const uint32_t e = a.dec[i + n_groups][lane];
+#pragma unroll
+        for (int q = 0; q < (1 << F::kLutShift); ++q) lut_now[(e << F::kLutShift) + q] = (uint16_t)lane;
+      }
     }
     __syncthreads();
     if (seq > 0 && s_misc[2] == 0) {
       const uint32_t pset = (seq + 2u) % 3u;
       const RangeLds Lp{stage_pk[pset][wave], stage_val[pset][wave], s_off[pset], s_wstart[pset], CAP};
-      write_out<NW, F>(Pprev, lut[a.lut_of[prev_item]], park, Lp, prev_r0, prev_nb, prev_count, s_misc[0],
+      write_out<NW, F>(Pprev, lut_old[(seq + 1u) & 1u], park, Lp, prev_r0, prev_nb, prev_count, s_misc[0],
                        final_sink(Pprev, s_misc[1]), tid, wave, lane);
     }
     if (!have) break;

@@ -369,11 +369,10 @@ struct DBatchItem {
 };
 struct DecompressBatchArgs {
   DBatchItem item[kBatchMax];
-  uint8_t dec_of[kBatchMax];
   splitzip_sizes* sizes;   // nullable; one record, status bits sticky
   uint32_t cpw, dtype, reg_patch_max;
   Words paging;            // as in CompressBatchArgs
-  uint8_t dec[kBatchLuts][16];
+  uint8_t dec[kBatchMax][16];   // every stream's codebook
 };
 
 template <typename F>
@@ -397,7 +396,7 @@ __global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const Decomp
   a.cpw = b.cpw;
   a.dtype = b.dtype;
   a.reg_patch_max = b.reg_patch_max;
-  decompress_tile<F>(a, b.dec[b.dec_of[blockIdx.y]], blockIdx.x, tbl, lds_chunk);   // a.dec stays unset: the table comes from the kernel arguments
+  decompress_tile<F>(a, b.dec[blockIdx.y], blockIdx.x, tbl, lds_chunk);   // a.dec stays unset: the table comes from the kernel arguments
 }
 
 #endif  // SPLITZIP_DECOMPRESS_HPP

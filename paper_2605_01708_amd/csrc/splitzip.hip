@@ -698,26 +698,19 @@ int compress_batch_impl(const splitzip_item* items, uint32_t n_items, int dtype,
       ++i;
       continue;
     }
-    // one launch: up to kBatchMax tensors that share at most kBatchLuts codebooks
+    // one launch: up to kBatchMax tensors, each with a codebook of its own (its 16 decode entries travel as
+    // kernel arguments: codebook_ok has shown that they and the encode table describe the same bijection)
     CompressBatchArgs a;
     memset(&a, 0, sizeof a);
-    uint32_t k = 0, n_luts = 0;
+    uint32_t k = 0;
     for (; i + k < n_items && k < kBatchMax; ++k) {
       const splitzip_item& it = items[i + k];
       if ((it.n_elems + kChunk - 1) / kChunk > chunk_cap) break;
-      uint32_t id = 0;
-      while (id < n_luts && memcmp(a.dec[id], it.cb->dec, 16) != 0) ++id;
-      if (id == n_luts) {
-        if (n_luts == kBatchLuts) break;
-        memcpy(a.dec[id], it.cb->dec, 16);
-        for (unsigned v = 0; v < 256; ++v) a.lut[id][v] = it.cb->member[v] ? it.cb->enc[v] : 0x100u;
-        ++n_luts;
-      }
+      memcpy(a.dec[k], it.cb->dec, 16);
       a.item[k].in = static_cast<const uint8_t*>(it.d_in);
       a.item[k].out = static_cast<uint8_t*>(it.d_out);
       a.item[k].n = it.n_elems;
       a.item[k].capacity = it.out_capacity;
-      a.lut_of[k] = (uint8_t)id;
     }
     a.sizes = d_sizes + i;
     a.ws_hdr = reinterpret_cast<uint32_t*>(ws);
@@ -771,22 +764,15 @@ int decompress_batch_impl(const splitzip_ditem* items, uint32_t n_items, int dty
   while (i < n_items) {
     DecompressBatchArgs a;
     memset(&a, 0, sizeof a);
-    uint32_t k = 0, n_decs = 0;
+    uint32_t k = 0;
     uint64_t chunks_all = 0, chunks_max = 0;
     for (; i + k < n_items && k < kBatchMax; ++k) {
       const splitzip_ditem& it = items[i + k];
-      uint32_t id = 0;
-      while (id < n_decs && memcmp(a.dec[id], it.cb->dec, 16) != 0) ++id;
-      if (id == n_decs) {
-        if (n_decs == kBatchLuts) break;
-        memcpy(a.dec[id], it.cb->dec, 16);
-        ++n_decs;
-      }
+      memcpy(a.dec[k], it.cb->dec, 16);
       a.item[k].comp = static_cast<const uint8_t*>(it.d_comp);
       a.item[k].out = static_cast<uint8_t*>(it.d_out);
       a.item[k].n = it.n_elems;
       a.item[k].comp_bytes = it.comp_bytes;
-      a.dec_of[k] = (uint8_t)id;
       const uint64_t c = (it.n_elems + kChunk - 1) / kChunk;
       chunks_all += c;
       if (c > chunks_max) chunks_max = c;

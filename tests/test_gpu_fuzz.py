@@ -67,16 +67,17 @@ def test_single_and_batch_calls_on_random_cases(round_):
         for case in range(12):
             k = int(rng.integers(1, 7))
             xs = [random_words(dt, random_size(rng), rng) for _ in range(k)]
-            # codebooks: calibrated on one of the tensors, or on unrelated data
-            src = xs[int(rng.integers(0, k))] if rng.integers(0, 2) else random_words(dt, 5000, rng)
-            cb_or = oracle.calibrate(src, ODT[dt])
-            cb = sz.codebook_from_dec(cb_or.dec.tolist(), dt)
+            # a codebook per tensor: calibrated on one of the tensors, or on unrelated data
+            cbs_or = [oracle.calibrate(xs[int(rng.integers(0, k))] if rng.integers(0, 2) else random_words(dt, 5000, rng), ODT[dt])
+                      for _ in xs]
+            cbs = [sz.codebook_from_dec(c.dec.tolist(), dt) for c in cbs_or]
+            cb_or, cb = cbs_or[0], cbs[0]
             print(f"case fuzz dtype={dt} #{case}: sizes={[x.size for x in xs]}", flush=True)
-            refs = [oracle.compress(x, cb_or) for x in xs]
+            refs = [oracle.compress(x, c) for x, c in zip(xs, cbs_or)]
             xd = [dev(x) for x in xs]
             outs = [torch.full((sz.compress_bound(x.size, dt) + 512,), 0xA5, dtype=torch.uint8, device="cuda") for x in xs]
             rec = sz.new_sizes_array(k)
-            sz.compress_batch(xd, [cb] * k, outs, ws, rec, capacities=[o.numel() - 512 for o in outs])
+            sz.compress_batch(xd, cbs, outs, ws, rec, capacities=[o.numel() - 512 for o in outs])
             torch.cuda.synchronize()
             got = sz.read_sizes_array(rec)
             for i, (ref, m) in enumerate(refs):
@@ -85,7 +86,7 @@ def test_single_and_batch_calls_on_random_cases(round_):
                 assert (outs[i][ref.size:ref.size + 512].cpu().numpy() == 0xA5).all()
             ys = [torch.empty(max(x.size, 1), dtype=t.dtype, device="cuda") for x, t in zip(xs, xd)]
             st = sz.new_sizes()
-            sz.decompress_batch(outs, [r[0].size for r in refs], [x.size for x in xs], [cb] * k, ys, st)
+            sz.decompress_batch(outs, [r[0].size for r in refs], [x.size for x in xs], cbs, ys, st)
             torch.cuda.synchronize()
             assert sz.read_sizes(st)[2] == 0
             for x, y, t in zip(xs, ys, xd):
