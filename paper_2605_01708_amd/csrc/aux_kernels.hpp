@@ -8,44 +8,58 @@
 // ---------------------------------------------------------------------------
 
 // Calibration histogram (section 3.3) of a device sample: exponent counts, added to hist[256].
-// Every workgroup counts into eight copies of the bins in LDS -- lane l uses copy l mod 8, which
-// keeps the lanes that meet on one of the few common exponents apart -- and adds its non-zero
-// totals to the global bins at the end.
+// Every workgroup counts into 64 copies of the bins in LDS, one per lane, interleaved: the count of bin b in
+// the copy of lane l is word 64 b + l, so a lane only ever touches its own bank and no two lanes of a wave an
+// address in common, whatever they count.  (Eight copies in rows of 256 words, the first version, sent all
+// lanes that count the same exponent -- most of them, the distribution being what it is -- to one bank: 39 % of
+// the LDS cycles were conflict cycles.)  The waves of a workgroup share the copies, hence atomic adds.
+// Non-zero totals go to the global bins at the end.
 template <bool BF16>
 __global__ __launch_bounds__(1024) void histogram_kernel(const uint8_t* in, uint64_t n, uint64_t* hist) {
-  __shared__ uint32_t bins[8][256];
+  constexpr int BINS = BF16 ? 256 : 32;
+  __shared__ uint32_t bins[BINS * 64];
   const int tid = threadIdx.x;
-  for (int i = tid; i < 8 * 256; i += 1024) (&bins[0][0])[i] = 0;
+  for (int i = tid; i < BINS * 64; i += 1024) bins[i] = 0;
   __syncthreads();
-  uint32_t* mine = bins[tid & 7];
+  uint32_t* mine = bins + (tid & 63);
   const uint64_t bytes = n * (BF16 ? 2 : 1), nvec = bytes / 16;
   const u32x4* v = reinterpret_cast<const u32x4*>(in);
-  for (uint64_t i = blockIdx.x * 1024ull + tid; i < nvec; i += (uint64_t)gridDim.x * 1024) {
-    const u32x4 q = ld_stream(v + i);
+  auto count = [&](const u32x4& q) {
     const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
       if (BF16) {
-        atomicAdd(&mine[(w[d] >> 7) & 0xffu], 1u);
-        atomicAdd(&mine[(w[d] >> 23) & 0xffu], 1u);
+        atomicAdd(&mine[((w[d] >> 7) & 0xffu) * 64], 1u);
+        atomicAdd(&mine[((w[d] >> 23) & 0xffu) * 64], 1u);
       } else {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) atomicAdd(&mine[(w[d] >> (8 * j + 2)) & 31u], 1u);
+        for (int j = 0; j < 4; ++j) atomicAdd(&mine[((w[d] >> (8 * j + 2)) & 31u) * 64], 1u);
       }
     }
+  };
+  // four vectors per thread in flight: the loads of a step are all issued before the first is counted
+  const uint64_t step = (uint64_t)gridDim.x * 1024;
+  uint64_t i = blockIdx.x * 1024ull + tid;
+  for (; i + 3 * step < nvec; i += 4 * step) {
+    u32x4 q[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) q[u] = ld_stream(v + i + u * step);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) count(q[u]);
   }
+  for (; i < nvec; i += step) count(ld_stream(v + i));
   // the words behind the last whole vector, by workgroup 0
   if (blockIdx.x == 0) {
     for (uint64_t i = nvec * 16 + (uint64_t)tid * (BF16 ? 2 : 1); i < bytes; i += 1024 * (BF16 ? 2 : 1)) {
       const uint32_t e = BF16 ? ((uint32_t)(in[i] | (in[i + 1] << 8)) >> 7) & 0xffu : ((uint32_t)in[i] >> 2) & 31u;
-      atomicAdd(&mine[e], 1u);
+      atomicAdd(&mine[e * 64], 1u);
     }
   }
   __syncthreads();
-  if (tid < 256) {
+  if (tid < BINS) {
     uint64_t c = 0;
-#pragma unroll
-    for (int r = 0; r < 8; ++r) c += bins[r][tid];
+#pragma unroll 8
+    for (int r = 0; r < 64; ++r) c += bins[tid * 64 + ((r + tid) & 63)];   // thread t starts at copy t: no two on one bank
     if (c) atomicAdd(reinterpret_cast<unsigned long long*>(&hist[tid]), (unsigned long long)c);
   }
 }
