@@ -222,6 +222,25 @@ typedef struct {
 int splitzip_decompress_batch(const splitzip_ditem* items, uint32_t n_items, int dtype, splitzip_sizes* d_sizes,
                               void* stream);
 
+/* Calibration per tensor for a whole batch, on the device (the "dynamic"
+ * codebook of the ablation "pre-calibration vs. dynamic codebook", and the
+ * per-layer codebooks of "Ablation on Layer-Wise Coverage", without a host
+ * round trip): splitzip_calibrate_batch_device counts the exponents of every
+ * items[k].d_in (n_elems words; d_out, out_capacity and cb are not looked at)
+ * into d_hists + 256 k and ranks them into d_cbs[k], exactly as
+ * splitzip_histogram and splitzip_codebook_device do for one tensor, in three
+ * launches per 64 tensors.  d_hists: n_items x 256 device words, 8-byte
+ * aligned, zeroed by the call; d_cbs: n_items splitzip_codebook in device
+ * memory, 4-byte aligned.  The _batch_dcb calls are the batch calls with
+ * tensor k under d_cbs[k]; the items' own cb fields are not looked at.  As
+ * with the _dcb calls the host cannot check such codebooks. */
+int splitzip_calibrate_batch_device(const splitzip_item* items, uint32_t n_items, int dtype, uint64_t* d_hists,
+                                    splitzip_codebook* d_cbs, void* stream);
+int splitzip_compress_batch_dcb(const splitzip_item* items, uint32_t n_items, int dtype, const splitzip_codebook* d_cbs,
+                                void* d_workspace, size_t workspace_bytes, splitzip_sizes* d_sizes, void* stream);
+int splitzip_decompress_batch_dcb(const splitzip_ditem* items, uint32_t n_items, int dtype, const splitzip_codebook* d_cbs,
+                                  splitzip_sizes* d_sizes, void* stream);
+
 /* Measurement aid: a plain streaming kernel that reads read_bytes from d_src
  * and writes write_bytes (<= read_bytes) to d_dst with 128-bit accesses, i.e.
  * the memory traffic of the codec without its arithmetic.  Both sizes are

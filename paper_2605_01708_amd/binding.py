@@ -113,6 +113,12 @@ def lib():
         L.splitzip_compress_batch.argtypes = [C.POINTER(_CItem), C.c_uint32, i, vp, sz, vp, vp]
         L.splitzip_decompress_batch.restype = i
         L.splitzip_decompress_batch.argtypes = [C.POINTER(_CDItem), C.c_uint32, i, vp, vp]
+        L.splitzip_calibrate_batch_device.restype = i
+        L.splitzip_calibrate_batch_device.argtypes = [C.POINTER(_CItem), C.c_uint32, i, vp, vp, vp]
+        L.splitzip_compress_batch_dcb.restype = i
+        L.splitzip_compress_batch_dcb.argtypes = [C.POINTER(_CItem), C.c_uint32, i, vp, vp, sz, vp, vp]
+        L.splitzip_decompress_batch_dcb.restype = i
+        L.splitzip_decompress_batch_dcb.argtypes = [C.POINTER(_CDItem), C.c_uint32, i, vp, vp, vp]
         L.splitzip_traffic_probe.restype = i
         L.splitzip_traffic_probe.argtypes = [vp, sz, vp, sz, vp]
         pgp = C.POINTER(_CPaged)
@@ -373,6 +379,83 @@ class DecompressBatch:
         _check(lib().splitzip_decompress_batch(self.items, self.n, self.dtype,
                                                sizes.data_ptr() if sizes is not None else None, _stream_ptr(stream)),
                "splitzip_decompress_batch")
+
+
+class DeviceCodebooks:
+    """n splitzip_codebook in device memory, written by splitzip_calibrate_batch_device, and the counts they come from."""
+
+    def __init__(self, n: int, dtype: int, device="cuda"):
+        self.n, self.dtype = n, dtype
+        self.buf = torch.zeros(max(n, 1) * C.sizeof(_CCodebook) // 4, dtype=torch.int32, device=device)
+        self.hists = torch.zeros((max(n, 1), 256), dtype=torch.int64, device=device)
+
+    def to_host(self, k: int) -> Codebook:
+        """Copy of the k-th codebook on the host (synchronises)."""
+        w = C.sizeof(_CCodebook) // 4
+        raw = self.buf[k * w:(k + 1) * w].cpu().numpy().tobytes()
+        return Codebook(_CCodebook.from_buffer_copy(raw))
+
+
+def _null_cb():
+    return C.POINTER(_CCodebook)()
+
+
+class CalibrateBatchDevice:
+    """splitzip_calibrate_batch_device: a codebook per tensor, counted and ranked on the device."""
+
+    def __init__(self, xs, dcbs: DeviceCodebooks):
+        self.n, self.dcbs = len(xs), dcbs
+        self.items = (_CItem * max(self.n, 1))()
+        self._keep = list(xs)
+        for k, x in enumerate(xs):
+            if x.element_size() != _elem_size(dcbs.dtype) or not x.is_contiguous():
+                raise ValueError("every x must be a contiguous tensor of raw words of the codebooks' dtype")
+            self.items[k] = _CItem(x.data_ptr(), x.numel(), None, 0, _null_cb())
+
+    def launch(self, stream=None) -> None:
+        _check(lib().splitzip_calibrate_batch_device(self.items, self.n, self.dcbs.dtype, self.dcbs.hists.data_ptr(),
+                                                     self.dcbs.buf.data_ptr(), _stream_ptr(stream)), "splitzip_calibrate_batch_device")
+
+
+class CompressBatchDcb:
+    """splitzip_compress_batch_dcb: tensor k under the k-th codebook of a DeviceCodebooks."""
+
+    def __init__(self, xs, dcbs: DeviceCodebooks, outs, capacities=None):
+        if not (len(xs) == len(outs)) or len(xs) > dcbs.n:
+            raise ValueError("xs and outs must have the same length, at most the number of codebooks")
+        self.n, self.dcbs = len(xs), dcbs
+        self.items = (_CItem * max(self.n, 1))()
+        self._keep = (list(xs), list(outs))
+        for k, (x, out) in enumerate(zip(xs, outs)):
+            if x.element_size() != _elem_size(dcbs.dtype) or not x.is_contiguous():
+                raise ValueError("every x must be a contiguous tensor of raw words of the codebooks' dtype")
+            cap = out.numel() * out.element_size() if capacities is None else capacities[k]
+            self.items[k] = _CItem(x.data_ptr(), x.numel(), out.data_ptr(), cap, _null_cb())
+
+    def launch(self, workspace: "Workspace", sizes: torch.Tensor, stream=None) -> None:
+        _check(lib().splitzip_compress_batch_dcb(self.items, self.n, self.dcbs.dtype, self.dcbs.buf.data_ptr(),
+                                                 workspace.buf.data_ptr(), workspace.nbytes, sizes.data_ptr(),
+                                                 _stream_ptr(stream)), "splitzip_compress_batch_dcb")
+
+
+class DecompressBatchDcb:
+    """splitzip_decompress_batch_dcb: stream k under the k-th codebook of a DeviceCodebooks."""
+
+    def __init__(self, comps, comp_bytes, n_elems, dcbs: DeviceCodebooks, outs):
+        if not (len(comps) == len(comp_bytes) == len(n_elems) == len(outs)) or len(comps) > dcbs.n:
+            raise ValueError("all lists must have the same length, at most the number of codebooks")
+        self.n, self.dcbs = len(comps), dcbs
+        self.items = (_CDItem * max(self.n, 1))()
+        self._keep = (list(comps), list(outs))
+        for k, (c, cbytes, n, out) in enumerate(zip(comps, comp_bytes, n_elems, outs)):
+            if out.numel() < n or out.element_size() != _elem_size(dcbs.dtype) or not out.is_contiguous():
+                raise ValueError("every out must be a contiguous tensor of at least n_elems raw words of the codebooks' dtype")
+            self.items[k] = _CDItem(c.data_ptr(), cbytes, n, out.data_ptr(), _null_cb())
+
+    def launch(self, sizes: torch.Tensor | None = None, stream=None) -> None:
+        _check(lib().splitzip_decompress_batch_dcb(self.items, self.n, self.dcbs.dtype, self.dcbs.buf.data_ptr(),
+                                                   sizes.data_ptr() if sizes is not None else None, _stream_ptr(stream)),
+               "splitzip_decompress_batch_dcb")
 
 
 def compress_batch(xs, cbs, outs, workspace: Workspace, sizes: torch.Tensor, stream=None, capacities=None) -> None:

@@ -15,7 +15,7 @@
 // the LDS cycles were conflict cycles.)  The waves of a workgroup share the copies, hence atomic adds.
 // Non-zero totals go to the global bins at the end.
 template <bool BF16>
-__global__ __launch_bounds__(1024) void histogram_kernel(const uint8_t* in, uint64_t n, uint64_t* hist) {
+__device__ inline void histogram_body(const uint8_t* in, uint64_t n, uint64_t* hist) {
   constexpr int BINS = BF16 ? 256 : 32;
   __shared__ uint32_t bins[BINS * 64];
   const int tid = threadIdx.x;
@@ -64,11 +64,32 @@ __global__ __launch_bounds__(1024) void histogram_kernel(const uint8_t* in, uint
   }
 }
 
-// Section 3.3 on the device: the three tables from 256 exponent counts.  One workgroup; thread v
-// ranks exponent v by (count descending, exponent ascending) among the format's exponents, the 16
-// first ranks form the codebook.
+template <bool BF16>
+__global__ __launch_bounds__(1024) void histogram_kernel(const uint8_t* in, uint64_t n, uint64_t* hist) {
+  histogram_body<BF16>(in, n, hist);
+}
+
+// the same for several samples in one launch: blockIdx.y picks the sample, its counts go to hists + 256 y
+struct HistBatchArgs {
+  const uint8_t* in[64];
+  uint64_t n[64];
+};
+template <bool BF16>
+__global__ __launch_bounds__(1024) void histogram_batch_kernel(const HistBatchArgs a, uint64_t* hists) {
+  histogram_body<BF16>(a.in[blockIdx.y], a.n[blockIdx.y], hists + 256 * blockIdx.y);
+}
+
+__global__ void zero_words_kernel(uint64_t* p, uint64_t nwords) {
+  for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < nwords; i += (uint64_t)gridDim.x * blockDim.x) p[i] = 0;
+}
+
+// Section 3.3 on the device: the three tables from 256 exponent counts.  One workgroup per codebook
+// (workgroup b: counts hist + 256 b, tables cb + b); thread v ranks exponent v by (count descending,
+// exponent ascending) among the format's exponents, the 16 first ranks form the codebook.
 __global__ __launch_bounds__(256) void codebook_kernel(const uint64_t* hist, uint32_t n_values, uint32_t dtype,
                                                        splitzip_codebook* cb) {
+  hist += 256 * blockIdx.x;
+  cb += blockIdx.x;
   __shared__ uint64_t h[256];
   const uint32_t v = threadIdx.x;
   h[v] = v < n_values ? hist[v] : 0;

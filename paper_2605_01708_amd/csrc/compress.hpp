@@ -682,6 +682,8 @@ struct CompressBatchArgs {
   uint32_t await_extra;      // error-path tests: words awaited beyond the group's
   Words paging;              // table and page geometry shared by all tensors (table null: contiguous tensors); base unused
   uint8_t dec[kBatchMax][16];   // every tensor's codebook, as its 16 decode entries: the kernel builds the encode table from them
+  const splitzip_codebook* d_cbs;   // nullable: n_items codebooks in device memory, used instead of dec
+  __device__ inline const uint8_t* dec_of(uint32_t k) const { return d_cbs ? d_cbs[k].dec : dec[k]; }
 };
 
 // entry of the LDS encode table for exponent e under the codebook dec (wave-uniform): its code, or the escape mark
@@ -764,7 +766,7 @@ __global__ __launch_bounds__(T, F::kBatchWavesPerSimd) void compress_batch_kerne
   uint32_t* park = reinterpret_cast<uint32_t*>(&s_park[tid]);
 
   if (grp < a.n_items)
-    for (int i = tid; i < 256; i += T) lut_now[i] = encode_entry(a.dec[grp], (uint32_t)i >> F::kLutShift);
+    for (int i = tid; i < 256; i += T) lut_now[i] = encode_entry(a.dec_of(grp), (uint32_t)i >> F::kLutShift);
   const uint32_t epoch = ld_agent(&a.ws_hdr[0]);
   const uint32_t err_before = b == 0 ? ld_agent(&a.ws_hdr[2]) : 0u;
   if (tid == 0) s_misc[3] = 0;   // set once an exchange was given up: later ones are not waited for
@@ -835,7 +837,7 @@ __global__ __launch_bounds__(T, F::kBatchWavesPerSimd) void compress_batch_kerne
         }
         if (b == 0) {
           const uint32_t err = err_before | (ok ? 0u : (uint32_t)SPLITZIP_STATUS_INTERNAL);
-          compress_write_trailer(Pprev, a.dec[prev_item], a.sizes + prev_item, al, err, lane);
+          compress_write_trailer(Pprev, a.dec_of(prev_item), a.sizes + prev_item, al, err, lane);
           if (!have && lane == 0) {
             // this group is through.  The last group to get here closes the launch: by then every
             // workgroup has read the header words, because each group completed an exchange.
@@ -862,7 +864,7 @@ __global__ __launch_bounds__(T, F::kBatchWavesPerSimd) void compress_batch_kerne
         if (more) lut_now[4 * lane + q] = 0x100u;
       }
       if (more && lane < 16) {
-        const uint32_t e = a.dec[i + n_groups][lane];
+        const uint32_t e = a.dec_of(i + n_groups)[lane] & ((256u >> F::kLutShift) - 1u);   // whatever a device codebook holds, the table is not left
 #pragma unroll
         for (int q = 0; q < (1 << F::kLutShift); ++q) lut_now[(e << F::kLutShift) + q] = (uint16_t)lane;
       }

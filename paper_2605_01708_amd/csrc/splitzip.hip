@@ -655,15 +655,17 @@ int splitzip_decompress_dcb(const void* d_comp, size_t comp_bytes, uint64_t n_el
 namespace {
 
 // the batch calls; paging: table and page geometry shared by all items, or contiguous tensors (table null)
+// d_cbs (nullable): n_items codebooks in device memory, used instead of the items' own
 int compress_batch_impl(const splitzip_item* items, uint32_t n_items, int dtype, const Words& paging, uint64_t paged_room,
-                        void* d_workspace, size_t workspace_bytes, splitzip_sizes* d_sizes, void* stream) {
+                        const splitzip_codebook* d_cbs, void* d_workspace, size_t workspace_bytes, splitzip_sizes* d_sizes,
+                        void* stream) {
   if (!dtype_ok(dtype) || (n_items && (!items || !d_sizes)) || !d_workspace || !aligned16(d_workspace) ||
-      (reinterpret_cast<uintptr_t>(d_sizes) & 7u))
+      (reinterpret_cast<uintptr_t>(d_sizes) & 7u) || (reinterpret_cast<uintptr_t>(d_cbs) & 3u))
     return SPLITZIP_ERR_INVALID_ARG;
   uint64_t n_max = 0;
   for (uint32_t i = 0; i < n_items; ++i) {
     const splitzip_item& it = items[i];
-    if (!it.d_out || (it.n_elems && !it.d_in) || !aligned16(it.d_in) || !aligned16(it.d_out) || !codebook_ok(it.cb, dtype))
+    if (!it.d_out || (it.n_elems && !it.d_in) || !aligned16(it.d_in) || !aligned16(it.d_out) || (!d_cbs && !codebook_ok(it.cb, dtype)))
       return SPLITZIP_ERR_INVALID_ARG;
     if (it.n_elems >> 32) return SPLITZIP_ERR_UNSUPPORTED;
     if (paging.table && it.n_elems > paged_room) return SPLITZIP_ERR_INVALID_ARG;   // the table does not cover the tensor
@@ -692,8 +694,9 @@ int compress_batch_impl(const splitzip_item* items, uint32_t n_items, int dtype,
   while (i < n_items) {
     // a tensor beyond the batch kernel's reach goes through the single call, in its place in the order
     if ((items[i].n_elems + kChunk - 1) / kChunk > chunk_cap) {
-      const int rc = compress_impl(item_words(paging, items[i].d_in), items[i].n_elems, dtype, items[i].cb, nullptr,
-                                   items[i].d_out, items[i].out_capacity, d_workspace, workspace_bytes, d_sizes + i, stream);
+      const int rc = compress_impl(item_words(paging, items[i].d_in), items[i].n_elems, dtype, d_cbs ? nullptr : items[i].cb,
+                                   d_cbs ? d_cbs + i : nullptr, items[i].d_out, items[i].out_capacity, d_workspace,
+                                   workspace_bytes, d_sizes + i, stream);
       if (rc != SPLITZIP_OK) return rc;
       ++i;
       continue;
@@ -706,13 +709,14 @@ int compress_batch_impl(const splitzip_item* items, uint32_t n_items, int dtype,
     for (; i + k < n_items && k < kBatchMax; ++k) {
       const splitzip_item& it = items[i + k];
       if ((it.n_elems + kChunk - 1) / kChunk > chunk_cap) break;
-      memcpy(a.dec[k], it.cb->dec, 16);
+      if (!d_cbs) memcpy(a.dec[k], it.cb->dec, 16);
       a.item[k].in = static_cast<const uint8_t*>(it.d_in);
       a.item[k].out = static_cast<uint8_t*>(it.d_out);
       a.item[k].n = it.n_elems;
       a.item[k].capacity = it.out_capacity;
     }
     a.sizes = d_sizes + i;
+    a.d_cbs = d_cbs ? d_cbs + i : nullptr;
     a.ws_hdr = reinterpret_cast<uint32_t*>(ws);
     a.state = reinterpret_cast<uint64_t*>(ws + kWsHeaderBytes);
     a.spin_ticks = spin_env ? (uint64_t)spin_env : kSpinTicks;
@@ -748,11 +752,12 @@ int compress_batch_impl(const splitzip_item* items, uint32_t n_items, int dtype,
 }
 
 int decompress_batch_impl(const splitzip_ditem* items, uint32_t n_items, int dtype, const Words& paging, uint64_t paged_room,
-                          splitzip_sizes* d_sizes, void* stream) {
-  if (!dtype_ok(dtype) || (n_items && !items) || (reinterpret_cast<uintptr_t>(d_sizes) & 7u)) return SPLITZIP_ERR_INVALID_ARG;
+                          const splitzip_codebook* d_cbs, splitzip_sizes* d_sizes, void* stream) {
+  if (!dtype_ok(dtype) || (n_items && !items) || (reinterpret_cast<uintptr_t>(d_sizes) & 7u) || (reinterpret_cast<uintptr_t>(d_cbs) & 3u))
+    return SPLITZIP_ERR_INVALID_ARG;
   for (uint32_t i = 0; i < n_items; ++i) {
     const splitzip_ditem& it = items[i];
-    if (!it.d_comp || (it.n_elems && !it.d_out) || !aligned16(it.d_comp) || !aligned16(it.d_out) || !codebook_ok(it.cb, dtype))
+    if (!it.d_comp || (it.n_elems && !it.d_out) || !aligned16(it.d_comp) || !aligned16(it.d_out) || (!d_cbs && !codebook_ok(it.cb, dtype)))
       return SPLITZIP_ERR_INVALID_ARG;
     if (it.n_elems >> 32) return SPLITZIP_ERR_UNSUPPORTED;
     if (paging.table && it.n_elems > paged_room) return SPLITZIP_ERR_INVALID_ARG;
@@ -768,7 +773,7 @@ int decompress_batch_impl(const splitzip_ditem* items, uint32_t n_items, int dty
     uint64_t chunks_all = 0, chunks_max = 0;
     for (; i + k < n_items && k < kBatchMax; ++k) {
       const splitzip_ditem& it = items[i + k];
-      memcpy(a.dec[k], it.cb->dec, 16);
+      if (!d_cbs) memcpy(a.dec[k], it.cb->dec, 16);
       a.item[k].comp = static_cast<const uint8_t*>(it.d_comp);
       a.item[k].out = static_cast<uint8_t*>(it.d_out);
       a.item[k].n = it.n_elems;
@@ -778,6 +783,7 @@ int decompress_batch_impl(const splitzip_ditem* items, uint32_t n_items, int dty
       if (c > chunks_max) chunks_max = c;
     }
     a.sizes = d_sizes;
+    a.d_cbs = d_cbs ? d_cbs + i : nullptr;
     a.dtype = (uint32_t)dtype;
     a.paging = paging;
     a.cpw = cpw_env ? (uint32_t)cpw_env : pick_decompress_cpw(chunks_all, dtype, tiles_per_cu);
@@ -801,19 +807,66 @@ extern "C" {
 
 int splitzip_compress_batch(const splitzip_item* items, uint32_t n_items, int dtype, void* d_workspace,
                             size_t workspace_bytes, splitzip_sizes* d_sizes, void* stream) {
-  return compress_batch_impl(items, n_items, dtype, contiguous_words(nullptr), 0, d_workspace, workspace_bytes, d_sizes, stream);
+  return compress_batch_impl(items, n_items, dtype, contiguous_words(nullptr), 0, nullptr, d_workspace, workspace_bytes, d_sizes, stream);
 }
 
 int splitzip_decompress_batch(const splitzip_ditem* items, uint32_t n_items, int dtype, splitzip_sizes* d_sizes,
                               void* stream) {
-  return decompress_batch_impl(items, n_items, dtype, contiguous_words(nullptr), 0, d_sizes, stream);
+  return decompress_batch_impl(items, n_items, dtype, contiguous_words(nullptr), 0, nullptr, d_sizes, stream);
+}
+
+int splitzip_calibrate_batch_device(const splitzip_item* items, uint32_t n_items, int dtype, uint64_t* d_hists,
+                                    splitzip_codebook* d_cbs, void* stream) {
+  if (!dtype_ok(dtype) || (n_items && (!items || !d_hists || !d_cbs)) || (reinterpret_cast<uintptr_t>(d_hists) & 7u) ||
+      (reinterpret_cast<uintptr_t>(d_cbs) & 3u))
+    return SPLITZIP_ERR_INVALID_ARG;
+  for (uint32_t i = 0; i < n_items; ++i) {
+    if ((items[i].n_elems && !items[i].d_in) || !aligned16(items[i].d_in)) return SPLITZIP_ERR_INVALID_ARG;
+    if (items[i].n_elems >> 32) return SPLITZIP_ERR_UNSUPPORTED;
+  }
+  if (n_items == 0) return SPLITZIP_OK;
+  const hipStream_t st = static_cast<hipStream_t>(stream);
+  hipLaunchKernelGGL(zero_words_kernel, dim3(64), dim3(256), 0, st, d_hists, 256ull * n_items);
+  for (uint32_t i = 0; i < n_items; i += 64) {
+    HistBatchArgs a;
+    memset(&a, 0, sizeof a);
+    const uint32_t k = n_items - i < 64 ? n_items - i : 64;
+    uint64_t nvec_max = 1;
+    for (uint32_t q = 0; q < k; ++q) {
+      a.in[q] = static_cast<const uint8_t*>(items[i + q].d_in);
+      a.n[q] = items[i + q].n_elems;
+      const uint64_t nvec = (a.n[q] * (dtype == SPLITZIP_BF16 ? 2 : 1) + 15) / 16;
+      if (nvec > nvec_max) nvec_max = nvec;
+    }
+    // workgroups per sample: at least sixteen vectors per thread, and about four workgroups per CU over the launch
+    uint64_t gx = (nvec_max + 16 * 1024 - 1) / (16 * 1024);
+    const uint64_t most = ((uint64_t)cu_count() * 4 + k - 1) / k;
+    if (gx > most) gx = most;
+    if (gx < 1) gx = 1;
+    if (dtype == SPLITZIP_BF16) hipLaunchKernelGGL(histogram_batch_kernel<true>, dim3((unsigned)gx, k), dim3(1024), 0, st, a, d_hists + 256ull * i);
+    else hipLaunchKernelGGL(histogram_batch_kernel<false>, dim3((unsigned)gx, k), dim3(1024), 0, st, a, d_hists + 256ull * i);
+  }
+  hipLaunchKernelGGL(codebook_kernel, dim3(n_items), dim3(256), 0, st, d_hists, exp_values(dtype), (uint32_t)dtype, d_cbs);
+  return hipGetLastError() == hipSuccess ? SPLITZIP_OK : SPLITZIP_ERR_HIP;
+}
+
+int splitzip_compress_batch_dcb(const splitzip_item* items, uint32_t n_items, int dtype, const splitzip_codebook* d_cbs,
+                                void* d_workspace, size_t workspace_bytes, splitzip_sizes* d_sizes, void* stream) {
+  if (n_items && !d_cbs) return SPLITZIP_ERR_INVALID_ARG;
+  return compress_batch_impl(items, n_items, dtype, contiguous_words(nullptr), 0, d_cbs, d_workspace, workspace_bytes, d_sizes, stream);
+}
+
+int splitzip_decompress_batch_dcb(const splitzip_ditem* items, uint32_t n_items, int dtype, const splitzip_codebook* d_cbs,
+                                  splitzip_sizes* d_sizes, void* stream) {
+  if (n_items && !d_cbs) return SPLITZIP_ERR_INVALID_ARG;
+  return decompress_batch_impl(items, n_items, dtype, contiguous_words(nullptr), 0, d_cbs, d_sizes, stream);
 }
 
 int splitzip_compress_batch_paged(const splitzip_item* items, uint32_t n_items, int dtype, const splitzip_paged* paging,
                                   void* d_workspace, size_t workspace_bytes, splitzip_sizes* d_sizes, void* stream) {
   Words w;
   if (!dtype_ok(dtype) || !paging_geometry(paging, dtype, &w)) return SPLITZIP_ERR_INVALID_ARG;
-  return compress_batch_impl(items, n_items, dtype, w, (uint64_t)paging->n_blocks * paging->block_elems, d_workspace,
+  return compress_batch_impl(items, n_items, dtype, w, (uint64_t)paging->n_blocks * paging->block_elems, nullptr, d_workspace,
                              workspace_bytes, d_sizes, stream);
 }
 
@@ -821,7 +874,7 @@ int splitzip_decompress_batch_paged(const splitzip_ditem* items, uint32_t n_item
                                     splitzip_sizes* d_sizes, void* stream) {
   Words w;
   if (!dtype_ok(dtype) || !paging_geometry(paging, dtype, &w)) return SPLITZIP_ERR_INVALID_ARG;
-  return decompress_batch_impl(items, n_items, dtype, w, (uint64_t)paging->n_blocks * paging->block_elems, d_sizes, stream);
+  return decompress_batch_impl(items, n_items, dtype, w, (uint64_t)paging->n_blocks * paging->block_elems, nullptr, d_sizes, stream);
 }
 
 int splitzip_traffic_probe(const void* d_src, size_t read_bytes, void* d_dst, size_t write_bytes, void* stream) {

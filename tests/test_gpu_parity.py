@@ -428,6 +428,47 @@ def test_codebook_that_never_leaves_the_device(dtype):
     assert sz.read_sizes(st)[2] == 0 and torch.equal(y, xd)
 
 
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_batch_calibrated_on_the_device(dtype):
+    """a codebook per tensor, counted and ranked on the device for the whole batch, then the batch calls under those
+    codebooks: tables, streams and tensors are those of the oracle calibrated on each tensor itself"""
+    sizes = [300 * 1024 + 5, 1, 0, 64 * 1024, 123457, 2048, 700 * 1024, 17]
+    xs_np = []
+    for k, n in enumerate(sizes):
+        x = synth(dtype, (n + 1023) // 1024 + 1, 70 + k, layer=3 * k, kind="KV"[k % 2])[:n].copy()
+        if k == 3:
+            x[:] = x[0]                                    # one exponent only: fifteen unseen ones fill the codebook
+        xs_np.append(x)
+    xs = [words_tensor(x) for x in xs_np]
+    dcbs = sz.DeviceCodebooks(len(xs), dtype)
+    dcbs.hists.fill_(7)                                    # the call zeroes the counts itself
+    sz.CalibrateBatchDevice(xs, dcbs).launch()
+    outs = [torch.full((sz.compress_bound(x.size, dtype) + 512,), POISON, dtype=torch.uint8, device="cuda") for x in xs_np]
+    ws = sz.Workspace(max(sizes), dtype)
+    rec = sz.new_sizes_array(len(xs))
+    sz.CompressBatchDcb(xs, dcbs, outs, capacities=[o.numel() - 512 for o in outs]).launch(ws, rec)
+    torch.cuda.synchronize()
+    got = sz.read_sizes_array(rec)
+    refs = []
+    for k, x in enumerate(xs_np):
+        print(f"case device-calibrated batch dtype={dtype} item {k} n={x.size}", flush=True)
+        cb_or = oracle.calibrate(x, DT[dtype])
+        host = dcbs.to_host(k)
+        assert (host.dec, host.enc, host.member, host.dtype) == (cb_or.dec.tolist(), cb_or.enc.tolist(), cb_or.member.tolist(), dtype), f"item {k}: tables"
+        ref, m = oracle.compress(x, cb_or)
+        refs.append(ref)
+        assert got[k] == (ref.size, m, 0), (k, got[k], ref.size, m)
+        assert np.array_equal(outs[k][: ref.size].cpu().numpy(), ref), f"item {k}: stream differs from the oracle's"
+        assert (outs[k][ref.size: ref.size + 512].cpu().numpy() == POISON).all()
+    ys = [torch.zeros(max(x.size, 1), dtype=t.dtype, device="cuda") for x, t in zip(xs_np, xs)]
+    st = sz.new_sizes()
+    sz.DecompressBatchDcb(outs, [r.size for r in refs], [x.size for x in xs_np], dcbs, ys).launch(st)
+    torch.cuda.synchronize()
+    assert sz.read_sizes(st)[2] == 0
+    for x, y, t in zip(xs_np, ys, xs):
+        assert torch.equal(y[: x.size], t), "round trip differs"
+
+
 def run_env_case(case, **env):
     import os
     import subprocess
