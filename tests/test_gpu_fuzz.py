@@ -131,3 +131,38 @@ def test_variant_calls_on_random_cases(round_):
             sz.variant_decompress(out, ref.size, x.size, v, cb, y, st)
             torch.cuda.synchronize()
             assert sz.read_sizes(st) == (ref.size, m, 0) and torch.equal(y[:x.size], xd)
+
+
+@pytest.mark.parametrize("round_", range(ROUNDS))
+def test_device_calibrated_batches_on_random_cases(round_):
+    rng = np.random.default_rng(20260503 + 1000 * round_)
+    for dt in (sz.BF16, sz.FP8_E5M2):
+        ws = sz.Workspace(400_000, dt)
+        for case in range(6):
+            k = int(rng.integers(1, 9))
+            xs = [random_words(dt, random_size(rng), rng) for _ in range(k)]
+            print(f"case fuzz device calibration dtype={dt} #{case}: sizes={[x.size for x in xs]}", flush=True)
+            xd = [dev(x) for x in xs]
+            dcbs = sz.DeviceCodebooks(k, dt)
+            sz.CalibrateBatchDevice(xd, dcbs).launch()
+            outs = [torch.full((sz.compress_bound(x.size, dt) + 512,), 0xA5, dtype=torch.uint8, device="cuda") for x in xs]
+            rec = sz.new_sizes_array(k)
+            sz.CompressBatchDcb(xd, dcbs, outs, capacities=[o.numel() - 512 for o in outs]).launch(ws, rec)
+            torch.cuda.synchronize()
+            got = sz.read_sizes_array(rec)
+            totals = []
+            for i, x in enumerate(xs):
+                cb_or = oracle.calibrate(x, ODT[dt])
+                assert dcbs.to_host(i).dec == cb_or.dec.tolist(), f"item {i}: codebook"
+                ref, m = oracle.compress(x, cb_or)
+                totals.append(ref.size)
+                assert got[i] == (ref.size, m, 0), (i, got[i], ref.size, m)
+                assert np.array_equal(outs[i][:ref.size].cpu().numpy(), ref), f"stream {i} differs"
+                assert (outs[i][ref.size:ref.size + 512].cpu().numpy() == 0xA5).all()
+            ys = [torch.empty(max(x.size, 1), dtype=t.dtype, device="cuda") for x, t in zip(xs, xd)]
+            st = sz.new_sizes()
+            sz.DecompressBatchDcb(outs, totals, [x.size for x in xs], dcbs, ys).launch(st)
+            torch.cuda.synchronize()
+            assert sz.read_sizes(st)[2] == 0
+            for x, y, t in zip(xs, ys, xd):
+                assert torch.equal(y[:x.size], t), "round trip differs"
