@@ -183,3 +183,36 @@ def test_argument_validation_without_gpu():
     assert L.splitzip_codebook_device(base, 7, base + 512, None) == -1
     assert L.splitzip_workspace_init(None, 1024, None) == -1
     assert L.splitzip_traffic_probe(None, 16, base, 16, None) == -1
+
+
+def test_device_calibrated_batch_calls_reject_bad_arguments_without_gpu():
+    from paper_2605_01708_amd.binding import _CItem, _CDItem, _CCodebook
+    L = sz.lib()
+    buf = (C.c_uint8 * 8192)()
+    base = (C.addressof(buf) + 15) & ~15
+    null_cb = C.POINTER(_CCodebook)()
+    items = (_CItem * 1)(_CItem(base, 64, base + 1024, 1 << 20, null_cb))
+    hists, dcbs, ws, sizes = base + 2048, base + 4096, base + 5120, base + 6144
+    f = L.splitzip_calibrate_batch_device
+    assert f(items, 1, sz.BF16, None, dcbs, None) == -1
+    assert f(items, 1, sz.BF16, hists, None, None) == -1
+    assert f(items, 1, sz.BF16, hists + 4, dcbs, None) == -1       # counts 8-byte aligned
+    assert f(items, 1, sz.BF16, hists, dcbs + 2, None) == -1       # codebooks 4-byte aligned
+    assert f(items, 1, 9, hists, dcbs, None) == -1
+    assert f(None, 0, sz.BF16, None, None, None) == 0              # nothing to do
+    bad = (_CItem * 1)(_CItem(base + 2, 64, None, 0, null_cb))
+    assert f(bad, 1, sz.BF16, hists, dcbs, None) == -1             # misaligned sample
+    g = L.splitzip_compress_batch_dcb
+    assert g(items, 1, sz.BF16, None, ws, 1 << 20, sizes, None) == -1          # no codebooks
+    assert g(items, 1, sz.BF16, dcbs + 2, ws, 1 << 20, sizes, None) == -1
+    assert g(items, 1, sz.BF16, dcbs, ws, 16, sizes, None) == -3               # workspace too small
+    small = (_CItem * 1)(_CItem(base, 64, base + 1024, 8, null_cb))
+    assert g(small, 1, sz.BF16, dcbs, ws, 1 << 20, sizes, None) == -3          # output below the fixed part
+    d = (_CDItem * 1)(_CDItem(base, 1 << 20, 64, base + 1024, null_cb))
+    h = L.splitzip_decompress_batch_dcb
+    assert h(d, 1, sz.BF16, None, None, None) == -1
+    assert h(d, 1, sz.BF16, dcbs + 1, None, None) == -1
+    short = (_CDItem * 1)(_CDItem(base, 8, 64, base + 1024, null_cb))
+    assert h(short, 1, sz.BF16, dcbs, None, None) == -3
+    # and the host-codebook batch calls still insist on a valid codebook per item
+    assert L.splitzip_compress_batch(items, 1, sz.BF16, ws, 1 << 20, sizes, None) == -1
