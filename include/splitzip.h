@@ -241,6 +241,19 @@ int splitzip_compress_batch_dcb(const splitzip_item* items, uint32_t n_items, in
 int splitzip_decompress_batch_dcb(const splitzip_ditem* items, uint32_t n_items, int dtype, const splitzip_codebook* d_cbs,
                                   splitzip_sizes* d_sizes, void* stream);
 
+/* Decompress with the codebook the stream itself carries: its header holds the
+ * 16 decode entries, which is all a decoder needs (section 3.2, decoding
+ * path).  A receiver of streams made under per-tensor or per-call codebooks
+ * needs no side channel for them.  Everything else as splitzip_decompress /
+ * splitzip_decompress_batch (the items' cb fields are not looked at); the
+ * header check then vouches for everything but the entries themselves, and
+ * entries that are no exponents of the dtype give a wrong tensor, never an
+ * access out of bounds. */
+int splitzip_decompress_own(const void* d_comp, size_t comp_bytes, uint64_t n_elems, int dtype, void* d_out,
+                            splitzip_sizes* d_sizes, void* stream);
+int splitzip_decompress_batch_own(const splitzip_ditem* items, uint32_t n_items, int dtype, splitzip_sizes* d_sizes,
+                                  void* stream);
+
 /* Measurement aid: a plain streaming kernel that reads read_bytes from d_src
  * and writes write_bytes (<= read_bytes) to d_dst with 128-bit accesses, i.e.
  * the memory traffic of the codec without its arithmetic.  Both sizes are

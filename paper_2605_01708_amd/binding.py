@@ -119,6 +119,10 @@ def lib():
         L.splitzip_compress_batch_dcb.argtypes = [C.POINTER(_CItem), C.c_uint32, i, vp, vp, sz, vp, vp]
         L.splitzip_decompress_batch_dcb.restype = i
         L.splitzip_decompress_batch_dcb.argtypes = [C.POINTER(_CDItem), C.c_uint32, i, vp, vp, vp]
+        L.splitzip_decompress_own.restype = i
+        L.splitzip_decompress_own.argtypes = [vp, sz, u64, i, vp, vp, vp]
+        L.splitzip_decompress_batch_own.restype = i
+        L.splitzip_decompress_batch_own.argtypes = [C.POINTER(_CDItem), C.c_uint32, i, vp, vp]
         L.splitzip_traffic_probe.restype = i
         L.splitzip_traffic_probe.argtypes = [vp, sz, vp, sz, vp]
         pgp = C.POINTER(_CPaged)
@@ -456,6 +460,36 @@ class DecompressBatchDcb:
         _check(lib().splitzip_decompress_batch_dcb(self.items, self.n, self.dcbs.dtype, self.dcbs.buf.data_ptr(),
                                                    sizes.data_ptr() if sizes is not None else None, _stream_ptr(stream)),
                "splitzip_decompress_batch_dcb")
+
+
+def decompress_own(comp: torch.Tensor, comp_bytes: int, n_elems: int, dtype: int, out: torch.Tensor,
+                   sizes: torch.Tensor | None = None, stream=None) -> None:
+    """splitzip_decompress_own: decompress with the codebook the stream carries in its header."""
+    if out.numel() < n_elems or out.element_size() != _elem_size(dtype) or not out.is_contiguous():
+        raise ValueError("out must be a contiguous tensor of at least n_elems raw words of the dtype")
+    _check(lib().splitzip_decompress_own(comp.data_ptr(), comp_bytes, n_elems, dtype, out.data_ptr(),
+                                         sizes.data_ptr() if sizes is not None else None, _stream_ptr(stream)),
+           "splitzip_decompress_own")
+
+
+class DecompressBatchOwn:
+    """splitzip_decompress_batch_own: every stream under the codebook of its own header."""
+
+    def __init__(self, comps, comp_bytes, n_elems, dtype: int, outs):
+        if not (len(comps) == len(comp_bytes) == len(n_elems) == len(outs)):
+            raise ValueError("all lists must have the same length")
+        self.n, self.dtype = len(comps), dtype
+        self.items = (_CDItem * max(self.n, 1))()
+        self._keep = (list(comps), list(outs))
+        for k, (c, cbytes, n, out) in enumerate(zip(comps, comp_bytes, n_elems, outs)):
+            if out.numel() < n or out.element_size() != _elem_size(dtype) or not out.is_contiguous():
+                raise ValueError("every out must be a contiguous tensor of at least n_elems raw words of the dtype")
+            self.items[k] = _CDItem(c.data_ptr(), cbytes, n, out.data_ptr(), _null_cb())
+
+    def launch(self, sizes: torch.Tensor | None = None, stream=None) -> None:
+        _check(lib().splitzip_decompress_batch_own(self.items, self.n, self.dtype,
+                                                   sizes.data_ptr() if sizes is not None else None, _stream_ptr(stream)),
+               "splitzip_decompress_batch_own")
 
 
 def compress_batch(xs, cbs, outs, workspace: Workspace, sizes: torch.Tensor, stream=None, capacities=None) -> None:

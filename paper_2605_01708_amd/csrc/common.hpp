@@ -10,6 +10,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr uint32_t kChunk = 1024;
 constexpr uint32_t kHalf = 512;
 constexpr uint32_t kHeaderBytes = 64;
+constexpr uint32_t kHeaderDecOffset = 40;                 // the 16 decode entries inside the header
 constexpr int kThreads = 256;                             // decompress / helper kernels
 constexpr int kWaves = kThreads / 64;
 constexpr uint32_t kMaxCpw = 16;                          // decompress: chunks per wave per tile, at most

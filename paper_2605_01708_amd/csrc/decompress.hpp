@@ -374,6 +374,7 @@ struct DecompressBatchArgs {
   Words paging;            // as in CompressBatchArgs
   uint8_t dec[kBatchMax][16];   // every stream's codebook
   const splitzip_codebook* d_cbs;   // nullable: n_items codebooks in device memory, used instead of dec
+  uint32_t own_dec;        // 1: every stream is decoded with the 16 decode entries of its own header
 };
 
 template <typename F>
@@ -397,7 +398,7 @@ __global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const Decomp
   a.cpw = b.cpw;
   a.dtype = b.dtype;
   a.reg_patch_max = b.reg_patch_max;
-  decompress_tile<F>(a, b.d_cbs ? b.d_cbs[blockIdx.y].dec : b.dec[blockIdx.y], blockIdx.x, tbl, lds_chunk);   // a.dec stays unset: the table comes from the kernel arguments
+  decompress_tile<F>(a, b.own_dec ? it.comp + kHeaderDecOffset : b.d_cbs ? b.d_cbs[blockIdx.y].dec : b.dec[blockIdx.y], blockIdx.x, tbl, lds_chunk);   // a.dec stays unset: the table comes from the kernel arguments
 }
 
 #endif  // SPLITZIP_DECOMPRESS_HPP

@@ -15,6 +15,7 @@
 // granule) is owned by one wave; every global access of a wave is one fully coalesced run of 16,
 // 8 or 4 bytes per lane; all plane traffic uses non-temporal loads and stores, nothing is re-used.
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -650,6 +651,15 @@ int splitzip_decompress_dcb(const void* d_comp, size_t comp_bytes, uint64_t n_el
   return decompress_impl(d_comp, comp_bytes, n_elems, dtype, nullptr, d_cb, contiguous_words(d_out), d_sizes, stream);
 }
 
+int splitzip_decompress_own(const void* d_comp, size_t comp_bytes, uint64_t n_elems, int dtype, void* d_out,
+                            splitzip_sizes* d_sizes, void* stream) {
+  if (!d_comp) return SPLITZIP_ERR_INVALID_ARG;
+  // the header's 16 decode entries are where a splitzip_codebook keeps its own: the stream serves as one
+  static_assert(offsetof(splitzip_codebook, dec) == 0, "dec first");
+  const splitzip_codebook* own = reinterpret_cast<const splitzip_codebook*>(static_cast<const uint8_t*>(d_comp) + kHeaderDecOffset);
+  return decompress_impl(d_comp, comp_bytes, n_elems, dtype, nullptr, own, contiguous_words(d_out), d_sizes, stream);
+}
+
 }  // extern "C"
 
 namespace {
@@ -752,12 +762,13 @@ int compress_batch_impl(const splitzip_item* items, uint32_t n_items, int dtype,
 }
 
 int decompress_batch_impl(const splitzip_ditem* items, uint32_t n_items, int dtype, const Words& paging, uint64_t paged_room,
-                          const splitzip_codebook* d_cbs, splitzip_sizes* d_sizes, void* stream) {
+                          const splitzip_codebook* d_cbs, bool own_dec, splitzip_sizes* d_sizes, void* stream) {
   if (!dtype_ok(dtype) || (n_items && !items) || (reinterpret_cast<uintptr_t>(d_sizes) & 7u) || (reinterpret_cast<uintptr_t>(d_cbs) & 3u))
     return SPLITZIP_ERR_INVALID_ARG;
   for (uint32_t i = 0; i < n_items; ++i) {
     const splitzip_ditem& it = items[i];
-    if (!it.d_comp || (it.n_elems && !it.d_out) || !aligned16(it.d_comp) || !aligned16(it.d_out) || (!d_cbs && !codebook_ok(it.cb, dtype)))
+    if (!it.d_comp || (it.n_elems && !it.d_out) || !aligned16(it.d_comp) || !aligned16(it.d_out) ||
+        (!d_cbs && !own_dec && !codebook_ok(it.cb, dtype)))
       return SPLITZIP_ERR_INVALID_ARG;
     if (it.n_elems >> 32) return SPLITZIP_ERR_UNSUPPORTED;
     if (paging.table && it.n_elems > paged_room) return SPLITZIP_ERR_INVALID_ARG;
@@ -773,7 +784,7 @@ int decompress_batch_impl(const splitzip_ditem* items, uint32_t n_items, int dty
     uint64_t chunks_all = 0, chunks_max = 0;
     for (; i + k < n_items && k < kBatchMax; ++k) {
       const splitzip_ditem& it = items[i + k];
-      if (!d_cbs) memcpy(a.dec[k], it.cb->dec, 16);
+      if (!d_cbs && !own_dec) memcpy(a.dec[k], it.cb->dec, 16);
       a.item[k].comp = static_cast<const uint8_t*>(it.d_comp);
       a.item[k].out = static_cast<uint8_t*>(it.d_out);
       a.item[k].n = it.n_elems;
@@ -784,6 +795,7 @@ int decompress_batch_impl(const splitzip_ditem* items, uint32_t n_items, int dty
     }
     a.sizes = d_sizes;
     a.d_cbs = d_cbs ? d_cbs + i : nullptr;
+    a.own_dec = own_dec ? 1u : 0u;
     a.dtype = (uint32_t)dtype;
     a.paging = paging;
     a.cpw = cpw_env ? (uint32_t)cpw_env : pick_decompress_cpw(chunks_all, dtype, tiles_per_cu);
@@ -812,7 +824,7 @@ int splitzip_compress_batch(const splitzip_item* items, uint32_t n_items, int dt
 
 int splitzip_decompress_batch(const splitzip_ditem* items, uint32_t n_items, int dtype, splitzip_sizes* d_sizes,
                               void* stream) {
-  return decompress_batch_impl(items, n_items, dtype, contiguous_words(nullptr), 0, nullptr, d_sizes, stream);
+  return decompress_batch_impl(items, n_items, dtype, contiguous_words(nullptr), 0, nullptr, false, d_sizes, stream);
 }
 
 int splitzip_calibrate_batch_device(const splitzip_item* items, uint32_t n_items, int dtype, uint64_t* d_hists,
@@ -859,7 +871,12 @@ int splitzip_compress_batch_dcb(const splitzip_item* items, uint32_t n_items, in
 int splitzip_decompress_batch_dcb(const splitzip_ditem* items, uint32_t n_items, int dtype, const splitzip_codebook* d_cbs,
                                   splitzip_sizes* d_sizes, void* stream) {
   if (n_items && !d_cbs) return SPLITZIP_ERR_INVALID_ARG;
-  return decompress_batch_impl(items, n_items, dtype, contiguous_words(nullptr), 0, d_cbs, d_sizes, stream);
+  return decompress_batch_impl(items, n_items, dtype, contiguous_words(nullptr), 0, d_cbs, false, d_sizes, stream);
+}
+
+int splitzip_decompress_batch_own(const splitzip_ditem* items, uint32_t n_items, int dtype, splitzip_sizes* d_sizes,
+                                  void* stream) {
+  return decompress_batch_impl(items, n_items, dtype, contiguous_words(nullptr), 0, nullptr, true, d_sizes, stream);
 }
 
 int splitzip_compress_batch_paged(const splitzip_item* items, uint32_t n_items, int dtype, const splitzip_paged* paging,
@@ -874,7 +891,7 @@ int splitzip_decompress_batch_paged(const splitzip_ditem* items, uint32_t n_item
                                     splitzip_sizes* d_sizes, void* stream) {
   Words w;
   if (!dtype_ok(dtype) || !paging_geometry(paging, dtype, &w)) return SPLITZIP_ERR_INVALID_ARG;
-  return decompress_batch_impl(items, n_items, dtype, w, (uint64_t)paging->n_blocks * paging->block_elems, nullptr, d_sizes, stream);
+  return decompress_batch_impl(items, n_items, dtype, w, (uint64_t)paging->n_blocks * paging->block_elems, nullptr, false, d_sizes, stream);
 }
 
 int splitzip_traffic_probe(const void* d_src, size_t read_bytes, void* d_dst, size_t write_bytes, void* stream) {

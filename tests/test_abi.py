@@ -214,5 +214,10 @@ def test_device_calibrated_batch_calls_reject_bad_arguments_without_gpu():
     assert h(d, 1, sz.BF16, dcbs + 1, None, None) == -1
     short = (_CDItem * 1)(_CDItem(base, 8, 64, base + 1024, null_cb))
     assert h(short, 1, sz.BF16, dcbs, None, None) == -3
+    o = L.splitzip_decompress_batch_own
+    assert o(d, 1, 9, None, None) == -1 and o(short, 1, sz.BF16, None, None) == -3 and o(None, 0, sz.BF16, None, None) == 0
+    assert L.splitzip_decompress_own(None, 1 << 20, 64, sz.BF16, base + 1024, None, None) == -1
+    assert L.splitzip_decompress_own(base, 8, 64, sz.BF16, base + 1024, None, None) == -3
+    assert L.splitzip_decompress_own(base + 4, 1 << 20, 64, sz.BF16, base + 1024, None, None) == -1
     # and the host-codebook batch calls still insist on a valid codebook per item
     assert L.splitzip_compress_batch(items, 1, sz.BF16, ws, 1 << 20, sizes, None) == -1

@@ -467,6 +467,20 @@ def test_batch_calibrated_on_the_device(dtype):
     assert sz.read_sizes(st)[2] == 0
     for x, y, t in zip(xs_np, ys, xs):
         assert torch.equal(y[: x.size], t), "round trip differs"
+    # a receiver without the codebooks: every stream decoded under the entries of its own header, batch and single
+    for y in ys:
+        y.fill_(0x55)
+    st2 = sz.new_sizes()
+    sz.DecompressBatchOwn(outs, [r.size for r in refs], [x.size for x in xs_np], dtype, ys).launch(st2)
+    torch.cuda.synchronize()
+    assert sz.read_sizes(st2)[2] == 0
+    for k, (x, y, t) in enumerate(zip(xs_np, ys, xs)):
+        assert torch.equal(y[: x.size], t), f"item {k}: decoded under its own header"
+        y.fill_(0x55)
+        st3 = sz.new_sizes()
+        sz.decompress_own(outs[k], refs[k].size, x.size, dtype, y, st3)
+        torch.cuda.synchronize()
+        assert sz.read_sizes(st3) == (refs[k].size, got[k][1], 0) and torch.equal(y[: x.size], t), f"item {k}: single call"
 
 
 def run_env_case(case, **env):
