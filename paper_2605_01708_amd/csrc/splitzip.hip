@@ -421,7 +421,7 @@ int splitzip_histogram(const void* d_sample, uint64_t n_elems, int dtype, uint64
   if (n_elems == 0) return SPLITZIP_OK;
   const uint64_t nvec = (n_elems * (dtype == SPLITZIP_BF16 ? 2 : 1) + 15) / 16;
   uint64_t grid = (nvec + 4 * 1024 - 1) / (4 * 1024);   // at least four vectors per thread
-  const uint64_t most = (uint64_t)cu_count() * 2;
+  const uint64_t most = (uint64_t)cu_count();   // one workgroup per CU: with two, their 512 final adds per bin cost more than the extra waves bring
   if (grid > most) grid = most;
   if (grid < 1) grid = 1;
   const hipStream_t st = static_cast<hipStream_t>(stream);
