@@ -637,3 +637,39 @@ def test_batch_tensor_larger_than_a_full_group():
         assert got[i] == (ref.size, m, 0), (i, got[i], ref.size, m)
         assert np.array_equal(outs[i][:ref.size].cpu().numpy(), ref), f"item {i}: stream differs from the oracle's"
         assert torch.equal(x, ys[i])
+
+
+def test_more_tensors_than_one_launch_takes():
+    """70 small tensors: the batch calls (host codebooks, device codebooks, own headers) split them over two launches
+    of at most 64; every stream is the oracle's under the tensor's own codebook"""
+    dtype = sz.BF16
+    rng = np.random.default_rng(11)
+    xs_np = [synth(dtype, 3, 200 + k, layer=k, kind="KV"[k % 2])[: int(rng.integers(1, 3000))].copy() for k in range(70)]
+    xs = [words_tensor(x) for x in xs_np]
+    cbs_or = [oracle.calibrate(x, DT[dtype]) for x in xs_np]
+    refs = [oracle.compress(x, c) for x, c in zip(xs_np, cbs_or)]
+    ws = sz.Workspace(4096, dtype)
+    dcbs = sz.DeviceCodebooks(70, dtype)
+    sz.CalibrateBatchDevice(xs, dcbs).launch()
+    for how in ("host codebooks", "device codebooks"):
+        outs = [torch.full((sz.compress_bound(x.size, dtype),), POISON, dtype=torch.uint8, device="cuda") for x in xs_np]
+        rec = sz.new_sizes_array(70)
+        if how == "host codebooks":
+            sz.compress_batch(xs, [gpu_codebook(c) for c in cbs_or], outs, ws, rec)
+        else:
+            sz.CompressBatchDcb(xs, dcbs, outs).launch(ws, rec)
+        torch.cuda.synchronize()
+        got = sz.read_sizes_array(rec)
+        for k, (ref, m) in enumerate(refs):
+            assert got[k] == (ref.size, m, 0), (how, k, got[k], ref.size, m)
+            assert np.array_equal(outs[k][: ref.size].cpu().numpy(), ref), f"{how}: item {k} differs from the oracle's stream"
+        ys = [torch.zeros_like(t) for t in xs]
+        st = sz.new_sizes()
+        if how == "host codebooks":
+            sz.DecompressBatchOwn(outs, [r[0].size for r in refs], [x.size for x in xs_np], dtype, ys).launch(st)
+        else:
+            sz.DecompressBatchDcb(outs, [r[0].size for r in refs], [x.size for x in xs_np], dcbs, ys).launch(st)
+        torch.cuda.synchronize()
+        assert sz.read_sizes(st)[2] == 0
+        for k, (y, t) in enumerate(zip(ys, xs)):
+            assert torch.equal(y, t), f"{how}: item {k} round trip"
