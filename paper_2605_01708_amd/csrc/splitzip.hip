@@ -213,6 +213,20 @@ void variant_tables(const splitzip_variant* v, const splitzip_codebook* cb, VArg
     }                                                                                                              \
   } while (0)
 
+template <int DT, int CB>
+void launch_v_decode(unsigned grid, hipStream_t st, const VArgs& a) {
+  const dim3 g(grid), b(kThreads);
+  if (a.mode == SPLITZIP_ESC_POS) {
+    if (a.chunk_shift == 10) hipLaunchKernelGGL((v_decode_kernel<DT, CB, SPLITZIP_ESC_POS, 10>), g, b, 0, st, a);
+    else hipLaunchKernelGGL((v_decode_kernel<DT, CB, SPLITZIP_ESC_POS, 8>), g, b, 0, st, a);
+  } else if (a.mode == SPLITZIP_ESC_SENTINEL) {
+    if (a.chunk_shift == 10) hipLaunchKernelGGL((v_decode_kernel<DT, CB, SPLITZIP_ESC_SENTINEL, 10>), g, b, 0, st, a);
+    else hipLaunchKernelGGL((v_decode_kernel<DT, CB, SPLITZIP_ESC_SENTINEL, 8>), g, b, 0, st, a);
+  } else {
+    hipLaunchKernelGGL((v_decode_kernel<DT, CB, SPLITZIP_ESC_ABS32, 10>), g, b, 0, st, a);
+  }
+}
+
 }  // namespace
 
 extern "C" {
@@ -341,7 +355,14 @@ int splitzip_variant_decompress(const void* d_comp, size_t comp_bytes, uint64_t 
   const hipStream_t st = static_cast<hipStream_t>(stream);
   const uint64_t blocks = (n_elems + kVBlock - 1) / kVBlock;
   const unsigned grid = blocks ? (unsigned)((blocks + kWaves - 1) / kWaves) : 1u;
-  SPLITZIP_V_DISPATCH2(v_decode_kernel, dim3(grid), dim3(kThreads), st, a);
+  switch ((int)a.dtype * 2 + (a.code_bits == 4 ? 1 : 0)) {
+    case 0: launch_v_decode<SPLITZIP_BF16, 3>(grid, st, a); break;
+    case 1: launch_v_decode<SPLITZIP_BF16, 4>(grid, st, a); break;
+    case 2: launch_v_decode<SPLITZIP_FP8_E5M2, 3>(grid, st, a); break;
+    case 3: launch_v_decode<SPLITZIP_FP8_E5M2, 4>(grid, st, a); break;
+    case 4: launch_v_decode<SPLITZIP_FP8_E4M3, 3>(grid, st, a); break;
+    default: launch_v_decode<SPLITZIP_FP8_E4M3, 4>(grid, st, a); break;
+  }
   if (v->escape_mode == SPLITZIP_ESC_ABS32 && n_elems) {
     // M is known to the device only: a grid that strides over whatever the header says
     const uint64_t most = (comp_bytes - a.off_pos) / 5;

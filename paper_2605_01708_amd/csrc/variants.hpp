@@ -335,9 +335,11 @@ __device__ inline bool v_check_header(const VArgs& a, uint32_t hw, int lane, uin
 // follow as soon as the offsets are known and travel while the planes are decoded into an LDS tile; the records
 // are applied to the tile (in the sentinel mode the exponent of every sentinel is fetched while decoding
 // instead), and the tile is stored.  In the absolute mode the correction is left to v_scatter_kernel.
-template <int DT, int CB>
+template <int DT, int CB, int MODE, int CS>
 __global__ __launch_bounds__(kThreads) void v_decode_kernel(const VArgs a) {
   using F = VFmt<DT>;
+  // escape mode, chunk size and position width are compile-time here: none of the format's choices costs a branch
+  constexpr uint32_t PB = MODE == SPLITZIP_ESC_POS ? (CS == 10 ? 2u : 1u) : MODE == SPLITZIP_ESC_ABS32 ? 4u : 0u;
   __shared__ uint8_t s_dec[16];
   __shared__ __attribute__((aligned(16))) uint8_t s_sm[kWaves][128 * F::SB];
   __shared__ __attribute__((aligned(16))) uint8_t s_code[kWaves][128 * CB];
@@ -346,12 +348,12 @@ __global__ __launch_bounds__(kThreads) void v_decode_kernel(const VArgs a) {
   if (tid < 16) s_dec[tid] = (uint32_t)tid < a.k ? a.dec[tid] : 0;
   const uint64_t blk = (uint64_t)blockIdx.x * kWaves + wave;
   const bool live = blk * kVBlock < a.n;
-  const uint32_t per_blk = kVBlock >> a.chunk_shift, chunk = 1u << a.chunk_shift;
+  const uint32_t per_blk = kVBlock >> CS, chunk = 1u << CS;
   const uint64_t c_first = blk * per_blk;
 
   const uint32_t hw = lane < 16 ? reinterpret_cast<const uint32_t*>(a.in)[lane] : 0u;
   uint32_t my_off = 0;   // lane q holds the offset of chunk c_first + q
-  if (live && a.mode != SPLITZIP_ESC_ABS32 && (uint32_t)lane <= per_blk && c_first + lane <= a.n_chunks)
+  if (live && MODE != SPLITZIP_ESC_ABS32 && (uint32_t)lane <= per_blk && c_first + lane <= a.n_chunks)
     my_off = a.offs[c_first + lane];
   if (live) {
     // the block's slices of both planes (whole dwords; the sections are padded, so nothing past them is read)
@@ -374,26 +376,26 @@ __global__ __launch_bounds__(kThreads) void v_decode_kernel(const VArgs a) {
   }
   __syncthreads();         // s_dec
   if (!ok || !live) return;   // nothing of a stream with a bad header is followed
-  const uint64_t off_val = a.off_pos + a256((uint64_t)a.pos_bytes * M);
+  const uint64_t off_val = a.off_pos + a256((uint64_t)PB * M);
   const uint32_t sentinel = (1u << CB) - 1u;
   // codes the codebook does not have can only occur if it leaves some unused (wave-uniform: no per-element work otherwise)
-  const bool check_codes = a.k + (a.mode == SPLITZIP_ESC_SENTINEL ? 1u : 0u) < (1u << CB);
+  const bool check_codes = a.k + (MODE == SPLITZIP_ESC_SENTINEL ? 1u : 0u) < (1u << CB);
   bool bad = false;
 
   // chunk-relative records: the first 64 of every chunk of the block are fetched now
   uint32_t rec_p[4] = {0, 0, 0, 0}, rec_e[4] = {0, 0, 0, 0}, rec_lo[4], rec_n[4] = {0, 0, 0, 0};
-  if (a.mode == SPLITZIP_ESC_POS) {
+  if (MODE == SPLITZIP_ESC_POS) {
 #pragma unroll
     for (uint32_t q = 0; q < 4; ++q) {
       rec_lo[q] = 0;
       if (q >= per_blk || c_first + q >= a.n_chunks) continue;
       const uint32_t lo = __builtin_amdgcn_readlane(my_off, q), hi = __builtin_amdgcn_readlane(my_off, q + 1);
-      const uint64_t first = (c_first + q) << a.chunk_shift, len = first + chunk <= a.n ? chunk : a.n - first;
+      const uint64_t first = (c_first + q) << CS, len = first + chunk <= a.n ? chunk : a.n - first;
       if (hi < lo || hi - lo > len || hi > M) { bad = true; continue; }
       rec_lo[q] = lo;
       rec_n[q] = hi - lo;
       if ((uint32_t)lane < hi - lo) {
-        rec_p[q] = a.pos_bytes == 2 ? reinterpret_cast<const uint16_t*>(a.in + a.off_pos)[lo + lane] : a.in[a.off_pos + lo + lane];
+        rec_p[q] = PB == 2 ? reinterpret_cast<const uint16_t*>(a.in + a.off_pos)[lo + lane] : a.in[a.off_pos + lo + lane];
         rec_e[q] = a.in[off_val + lo + lane];
       }
     }
@@ -415,14 +417,14 @@ __global__ __launch_bounds__(kThreads) void v_decode_kernel(const VArgs a) {
       if (check_codes) unknown |= (uint32_t)(code >= a.k) << j;
       w[j] = F::combine(av, s_dec[code & 15u]);
     }
-    sent = a.mode == SPLITZIP_ESC_SENTINEL ? sent & vmask : 0u;
+    sent = MODE == SPLITZIP_ESC_SENTINEL ? sent & vmask : 0u;
     if (unknown & vmask & ~sent) bad = true;
-    if (a.mode == SPLITZIP_ESC_SENTINEL) {
+    if (MODE == SPLITZIP_ESC_SENTINEL) {
       // rank of every sentinel inside its chunk, then its exponent from the value array
       const uint32_t cnt = __popc(sent), incl = wave_incl_scan(cnt);
       const uint32_t t31 = __builtin_amdgcn_readlane(incl, 31), t63 = __builtin_amdgcn_readlane(incl, 63);
       uint32_t r, r_end;
-      if (a.chunk_shift == 10) {
+      if (CS == 10) {
         r = __builtin_amdgcn_readlane(my_off, 0) + carry + incl - cnt;
         r_end = __builtin_amdgcn_readlane(my_off, 1);
         carry = t63;
@@ -455,16 +457,16 @@ __global__ __launch_bounds__(kThreads) void v_decode_kernel(const VArgs a) {
   }
 
   v_lds_settle();
-  if (a.mode == SPLITZIP_ESC_POS) {
+  if (MODE == SPLITZIP_ESC_POS) {
     // the records of the block's chunks, one lane each, straight into the tile
 #pragma unroll
     for (uint32_t q = 0; q < 4; ++q) {
       if (q >= per_blk || rec_n[q] == 0) continue;
-      const uint64_t first = (c_first + q) << a.chunk_shift, len = first + chunk <= a.n ? chunk : a.n - first;
+      const uint64_t first = (c_first + q) << CS, len = first + chunk <= a.n ? chunk : a.n - first;
       for (uint32_t i = lane; i < rec_n[q]; i += 64) {
         uint32_t p = rec_p[q], e = rec_e[q];
         if (i >= 64) {   // a chunk with more than 64 escapes: the rest is fetched here
-          p = a.pos_bytes == 2 ? reinterpret_cast<const uint16_t*>(a.in + a.off_pos)[rec_lo[q] + i] : a.in[a.off_pos + rec_lo[q] + i];
+          p = PB == 2 ? reinterpret_cast<const uint16_t*>(a.in + a.off_pos)[rec_lo[q] + i] : a.in[a.off_pos + rec_lo[q] + i];
           e = a.in[off_val + rec_lo[q] + i];
         }
         if (p >= len || e >= (uint32_t)F::EXPS) { bad = true; continue; }
