@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol():
     assert {"splitzip_calibrate", "splitzip_compress", "splitzip_decompress", "splitzip_workspace_init",
             "splitzip_fixed_bytes", "splitzip_total_bytes", "splitzip_compress_bound",
             "splitzip_workspace_bytes", "splitzip_codebook_from_dec", "splitzip_strerror",
-            "splitzip_version", "splitzip_traffic_probe", "splitzip_compress_batch",
+            "splitzip_version", "splitzip_traffic_probe", "splitzip_traffic_probe_shape", "splitzip_compress_batch",
             "splitzip_decompress_batch", "splitzip_histogram", "splitzip_codebook_from_hist",
             "splitzip_codebook_device", "splitzip_compress_dcb", "splitzip_decompress_dcb"} <= set(names)
     L = C.CDLL(sz.lib_path())

@@ -191,7 +191,7 @@ def test_ratio_limit_is_four_thirds():
 def test_printed_ratio_pairs(golden_dir):
     """The payload size function reproduces the (escape rate, ratio) pairs the paper prints."""
     n = 1 << 30
-    rows = 0
+    rows, kinds = 0, {}
     for line in open(os.path.join(golden_dir, "paper_ratio_pairs.txt")):
         line = line.split("#")[0].strip()
         if not line:
@@ -208,10 +208,44 @@ def test_printed_ratio_pairs(golden_dir):
         step = 0.5 * 10 ** (-rdec)
         if kind == "exact":
             assert lo - step <= printed <= hi + step, line
+        elif kind == "all":
+            assert round(ratio(eps), rdec) == printed and lo - step <= printed <= hi + step, line
         else:
+            assert kind == "upper"
             assert printed <= hi + step and printed >= lo - step - 0.01, line
         rows += 1
-    assert rows == 8
+        kinds[kind] = kinds.get(kind, 0) + 1
+    assert rows == 8 and kinds == {"exact": 2, "all": 4, "upper": 2}
+
+
+def test_printed_ratio_pins_reject_a_wrong_record_size():
+    """The pins above bite: a payload function with 2, 4 or 5 bytes per escape instead of 3 (or a code plane of
+    N instead of N/2 bytes) fails at least one of the printed pairs."""
+    rows = []
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "paper_ratio_pairs.txt")):
+        line = line.split("#")[0].strip()
+        if line:
+            dt, eps_pct, eps_dec, printed, rdec, raw_bits, kind = line.split()[:7]
+            rows.append((dt, float(eps_pct) / 100, 0.5 * 10 ** (-int(eps_dec)) / 100, float(printed), int(rdec), int(raw_bits), kind))
+
+    def passes(payload_bits):          # payload_bits(dt, eps) -> bits per element
+        for dt, eps, half, printed, rdec, raw_bits, kind in rows:
+            lo, hi = raw_bits / payload_bits(dt, eps + half), raw_bits / payload_bits(dt, max(eps - half, 0.0))
+            step = 0.5 * 10 ** (-rdec)
+            if kind == "exact" and not (lo - step <= printed <= hi + step):
+                return False
+            if kind == "all" and not (round(raw_bits / payload_bits(dt, eps), rdec) == printed):
+                return False
+            if kind == "upper" and not (printed <= hi + step and printed >= lo - step - 0.01):
+                return False
+        return True
+
+    dense = {"bf16": 12.0, "e5m2": 7.0}
+    assert passes(lambda dt, e: dense[dt] + 24 * e)                    # the paper's B_SZ
+    for wrong in (16, 32, 40):
+        assert not passes(lambda dt, e: dense[dt] + wrong * e), wrong
+    assert not passes(lambda dt, e: dense[dt] + 4 + 24 * e)            # codes not packed two per byte
+    assert not passes(lambda dt, e: dense[dt] - 1 + 24 * e)
 
 
 def test_total_bytes_itemised():
