@@ -125,6 +125,8 @@ def lib():
         L.splitzip_decompress_batch_own.argtypes = [C.POINTER(_CDItem), C.c_uint32, i, vp, vp]
         L.splitzip_traffic_probe.restype = i
         L.splitzip_traffic_probe.argtypes = [vp, sz, vp, sz, vp]
+        L.splitzip_traffic_probe_shape.restype = i
+        L.splitzip_traffic_probe_shape.argtypes = [vp, sz, vp, sz, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, vp]
         pgp = C.POINTER(_CPaged)
         L.splitzip_compress_paged.restype = i
         L.splitzip_compress_paged.argtypes = [pgp, u64, i, cbp, vp, sz, vp, sz, vp, vp]
@@ -505,6 +507,13 @@ def decompress_batch(comps, comp_bytes, n_elems, cbs, outs, sizes: torch.Tensor 
 def traffic_probe(src: torch.Tensor, read_bytes: int, dst: torch.Tensor, write_bytes: int, stream=None) -> None:
     _check(lib().splitzip_traffic_probe(src.data_ptr(), read_bytes, dst.data_ptr(), write_bytes,
                                         _stream_ptr(stream)), "splitzip_traffic_probe")
+
+
+def traffic_probe_shape(src: torch.Tensor, read_bytes: int, dst: torch.Tensor, write_bytes: int, reads_per_step: int,
+                        writes_per_step: int, wgs_per_cu: int, flags: int = 3, stream=None) -> None:
+    _check(lib().splitzip_traffic_probe_shape(src.data_ptr(), read_bytes, dst.data_ptr(), write_bytes, reads_per_step,
+                                              writes_per_step, wgs_per_cu, flags, _stream_ptr(stream)),
+           "splitzip_traffic_probe_shape")
 
 
 # ---- format variants of the ablations -----------------------------------------------------------

@@ -128,4 +128,46 @@ __global__ __launch_bounds__(kThreads) void traffic_probe_kernel(const u32x4* sr
   }
 }
 
+// The same with its shape as arguments, for finding out what the memory system gives a streaming kernel at best:
+// per step a workgroup reads R coalesced 4 KB runs and writes W (either may be 0: write only, read only), with
+// temporal or non-temporal accesses; the steps are dealt to the workgroups round robin (neighbouring workgroups
+// work on neighbouring runs) or in one contiguous block each (the way the codec's kernels own their chunks).
+template <int R, int W, bool NTL, bool NTS>
+__global__ __launch_bounds__(kThreads) void traffic_shape_kernel(const u32x4* src, uint64_t nread, u32x4* dst, uint64_t nwrite,
+                                                                  uint64_t steps, uint32_t blocked) {
+  const uint64_t per = (steps + gridDim.x - 1) / gridDim.x;
+  const uint64_t s0 = blocked ? blockIdx.x * per : blockIdx.x;
+  const uint64_t s_end = blocked ? (s0 + per < steps ? s0 + per : steps) : steps, stride = blocked ? 1 : gridDim.x;
+  // blocked == 2: every workgroup starts somewhere else inside its block and wraps around, so that the workgroups
+  // are not all at the same distance from the start of their blocks at the same time
+  const uint64_t len = s_end > s0 ? s_end - s0 : 0, rot = blocked == 2 && len ? (blockIdx.x * 37ull) % len : 0;
+  u32x4 acc = u32x4{0u, 0u, 0u, 0u};
+  for (uint64_t q = 0; s0 + q * stride < s_end; ++q) {
+    const uint64_t s = blocked == 2 ? s0 + (q + rot) % len : s0 + q * stride;
+    u32x4 v[R > 0 ? R : 1];
+    v[0] = u32x4{(uint32_t)s, threadIdx.x, 0u, 0u};
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+      const uint64_t idx = ((uint64_t)R * s + i) * kThreads + threadIdx.x;
+      v[i] = u32x4{0u, 0u, 0u, 0u};
+      if (idx < nread) v[i] = NTL ? ld_stream(src + idx) : src[idx];
+    }
+    if (W == 0) {
+#pragma unroll
+      for (int i = 0; i < R; ++i) acc ^= v[i];
+    }
+#pragma unroll
+    for (int i = 0; i < W; ++i) {
+      const uint64_t idx = ((uint64_t)W * s + i) * kThreads + threadIdx.x;
+      const u32x4 o = v[R > 0 ? i % R : 0];
+      if (idx < nwrite) {
+        if (NTS) st_stream(dst + idx, o);
+        else dst[idx] = o;
+      }
+    }
+  }
+  // read only: the words must be used; no tensor holds this pattern in every lane
+  if (W == 0 && acc.x == 0x5a17c0deu && acc.y == 0x5a17c0deu && acc.z == 0x5a17c0deu && acc.w == 0x5a17c0deu) dst[0] = acc;
+}
+
 #endif  // SPLITZIP_AUX_KERNELS_HPP

@@ -920,13 +920,50 @@ int splitzip_traffic_probe(const void* d_src, size_t read_bytes, void* d_dst, si
     return SPLITZIP_ERR_INVALID_ARG;
   const uint64_t nread = read_bytes / 16, nwrite = write_bytes / 16;
   if (!nread) return SPLITZIP_OK;
-  static const int wgs_per_cu = env_int("SPLITZIP_PROBE_WGS_PER_CU", 8);
-  uint64_t grid = (uint64_t)cu_count() * wgs_per_cu;
+  uint64_t grid = (uint64_t)cu_count() * 8;
   const uint64_t need = (nread + 4 * kThreads - 1) / (4 * kThreads);
   if (grid > need) grid = need;
   if (grid < 1) grid = 1;
   hipLaunchKernelGGL(traffic_probe_kernel, dim3((unsigned)grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
                      static_cast<const u32x4*>(d_src), nread, static_cast<u32x4*>(d_dst), nwrite);
+  return hipGetLastError() == hipSuccess ? SPLITZIP_OK : SPLITZIP_ERR_HIP;
+}
+
+
+int splitzip_traffic_probe_shape(const void* d_src, size_t read_bytes, void* d_dst, size_t write_bytes, uint32_t reads_per_step,
+                                 uint32_t writes_per_step, uint32_t wgs_per_cu, uint32_t flags, void* stream) {
+  if (!d_src || !d_dst || !aligned16(d_src) || !aligned16(d_dst) || wgs_per_cu > 32 || flags > 15u || (flags & 12u) == 8u)
+    return SPLITZIP_ERR_INVALID_ARG;
+  const uint32_t R = reads_per_step, W = writes_per_step;
+  const uint64_t nread = R ? read_bytes / 16 : 0, nwrite = W ? write_bytes / 16 : 0;
+  const uint64_t rs = R ? (nread + (uint64_t)R * kThreads - 1) / ((uint64_t)R * kThreads) : 0;
+  const uint64_t wsteps = W ? (nwrite + (uint64_t)W * kThreads - 1) / ((uint64_t)W * kThreads) : 0;
+  const uint64_t steps = rs > wsteps ? rs : wsteps;
+  if (!steps) return R || W ? SPLITZIP_OK : SPLITZIP_ERR_INVALID_ARG;
+  uint64_t grid = wgs_per_cu ? (uint64_t)cu_count() * wgs_per_cu : steps;   // 0: one step per workgroup
+  if (grid > steps) grid = steps;
+  if (grid >> 31) return SPLITZIP_ERR_UNSUPPORTED;
+  const hipStream_t st = static_cast<hipStream_t>(stream);
+  const u32x4* src = static_cast<const u32x4*>(d_src);
+  u32x4* dst = static_cast<u32x4*>(d_dst);
+  const uint32_t blocked = (flags & 4u) ? ((flags & 8u) ? 2u : 1u) : 0u;
+  bool found = false;
+#define SPLITZIP_SHAPE(RR, WW)                                                                                              \
+  if (R == RR && W == WW) {                                                                                                 \
+    found = true;                                                                                                           \
+    switch (flags & 3u) {                                                                                                   \
+      case 0: hipLaunchKernelGGL((traffic_shape_kernel<RR, WW, false, false>), dim3((unsigned)grid), dim3(kThreads), 0, st, src, nread, dst, nwrite, steps, blocked); break; \
+      case 1: hipLaunchKernelGGL((traffic_shape_kernel<RR, WW, true, false>), dim3((unsigned)grid), dim3(kThreads), 0, st, src, nread, dst, nwrite, steps, blocked); break;  \
+      case 2: hipLaunchKernelGGL((traffic_shape_kernel<RR, WW, false, true>), dim3((unsigned)grid), dim3(kThreads), 0, st, src, nread, dst, nwrite, steps, blocked); break;  \
+      default: hipLaunchKernelGGL((traffic_shape_kernel<RR, WW, true, true>), dim3((unsigned)grid), dim3(kThreads), 0, st, src, nread, dst, nwrite, steps, blocked); break;  \
+    }                                                                                                                       \
+  }
+  SPLITZIP_SHAPE(1, 0) SPLITZIP_SHAPE(2, 0) SPLITZIP_SHAPE(4, 0) SPLITZIP_SHAPE(8, 0)
+  SPLITZIP_SHAPE(0, 1) SPLITZIP_SHAPE(0, 2) SPLITZIP_SHAPE(0, 4) SPLITZIP_SHAPE(0, 8)
+  SPLITZIP_SHAPE(4, 3) SPLITZIP_SHAPE(8, 6) SPLITZIP_SHAPE(3, 4) SPLITZIP_SHAPE(6, 8)
+  SPLITZIP_SHAPE(1, 1) SPLITZIP_SHAPE(2, 2) SPLITZIP_SHAPE(4, 4)
+#undef SPLITZIP_SHAPE
+  if (!found) return SPLITZIP_ERR_INVALID_ARG;
   return hipGetLastError() == hipSuccess ? SPLITZIP_OK : SPLITZIP_ERR_HIP;
 }
 
