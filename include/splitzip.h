@@ -169,6 +169,24 @@ int splitzip_compress(const void* d_in, uint64_t n_elems, int dtype, const split
                       void* d_out, size_t out_capacity, void* d_workspace, size_t workspace_bytes,
                       splitzip_sizes* d_sizes, void* stream);
 
+/* For callers that cannot allocate device memory -- code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc:
+ * splitzip_compress without a workspace argument.  The words through which
+ * the workgroups exchange their escape counts live in an array of 65 600
+ * bytes inside the library's code object, one copy per GPU, held until the
+ * process ends; the call allocates nothing (no hipMalloc / hipFree, no
+ * allocating library routine) and needs no splitzip_workspace_init.  Same
+ * arguments otherwise, same stream bytes and sizes record as
+ * splitzip_compress.  Limit: n_elems <= splitzip_noalloc_max_elems() (what one
+ * launch takes: 256 x 1024 elements per CU, 64 Mi elements on an MI355X);
+ * beyond it SPLITZIP_ERR_UNSUPPORTED and nothing is enqueued.  All calls on
+ * one GPU share that GPU's array (each leaves it ready for the next): calls
+ * that overlap in time on one GPU -- different streams, no ordering -- race
+ * on it; order them, or use splitzip_compress with a workspace per stream. */
+uint64_t splitzip_noalloc_max_elems(void);
+int splitzip_compress_noalloc(const void* d_in, uint64_t n_elems, int dtype, const splitzip_codebook* cb,
+                              void* d_out, size_t out_capacity, splitzip_sizes* d_sizes, void* stream);
+
 /* Section 3.2, decoding path: nibble unpack, 16-entry table, recombination by
  * eq. (2), then the sparse overwrite of the exponent field at every recorded
  * escape position.

@@ -123,6 +123,10 @@ def lib():
         L.splitzip_decompress_own.argtypes = [vp, sz, u64, i, vp, vp, vp]
         L.splitzip_decompress_batch_own.restype = i
         L.splitzip_decompress_batch_own.argtypes = [C.POINTER(_CDItem), C.c_uint32, i, vp, vp]
+        L.splitzip_noalloc_max_elems.restype = u64
+        L.splitzip_noalloc_max_elems.argtypes = []
+        L.splitzip_compress_noalloc.restype = i
+        L.splitzip_compress_noalloc.argtypes = [vp, u64, i, cbp, vp, sz, vp, vp]
         L.splitzip_traffic_probe.restype = i
         L.splitzip_traffic_probe.argtypes = [vp, sz, vp, sz, vp]
         L.splitzip_traffic_probe_shape.restype = i
@@ -322,6 +326,21 @@ def compress(x: torch.Tensor, cb: Codebook, out: torch.Tensor, workspace: Worksp
     _check(lib().splitzip_compress(x.data_ptr(), n, cb.dtype, C.byref(cb.c), out.data_ptr(), cap,
                                    workspace.buf.data_ptr(), workspace.nbytes, sizes.data_ptr(),
                                    _stream_ptr(stream)), "splitzip_compress")
+
+
+def noalloc_max_elems() -> int:
+    return int(lib().splitzip_noalloc_max_elems())
+
+
+def compress_noalloc(x: torch.Tensor, cb: Codebook, out: torch.Tensor, sizes: torch.Tensor, stream=None,
+                     capacity: int | None = None) -> None:
+    """splitzip_compress_noalloc: splitzip_compress on the library's own per-GPU exchange words."""
+    n = x.numel()
+    if x.element_size() != _elem_size(cb.dtype) or not x.is_contiguous():
+        raise ValueError("x must be a contiguous tensor of raw words of the codebook's dtype")
+    cap = out.numel() * out.element_size() if capacity is None else capacity
+    _check(lib().splitzip_compress_noalloc(x.data_ptr(), n, cb.dtype, C.byref(cb.c), out.data_ptr(), cap,
+                                           sizes.data_ptr(), _stream_ptr(stream)), "splitzip_compress_noalloc")
 
 
 def decompress(comp: torch.Tensor, comp_bytes: int, n_elems: int, cb: Codebook, out: torch.Tensor,

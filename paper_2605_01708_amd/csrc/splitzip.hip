@@ -20,6 +20,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "splitzip.h"
@@ -504,10 +505,31 @@ bool paged_words(const splitzip_paged* pg, uint64_t n_elems, int dtype, Words* w
   return true;
 }
 
+// ---- the exchange words of splitzip_compress_noalloc: one copy per GPU, alive until the process ends ----
+// Word 0 is the epoch and starts at 1, everything else at 0: the state splitzip_workspace_init leaves behind.
+static __device__ __align__(256) uint32_t scratch[(kWsHeaderBytes + kWsTableBytes) / 4] = {1u};
+
+// The array's address on the current device (each GPU holds its own copy at its own address), looked up once per
+// device with that device current; null if the runtime refuses.  `scratch` itself is a host-side stand-in and is
+// never handed to a kernel.
+void* scratch_on_current_device() {
+  static std::mutex lock;
+  static void* ptr[64] = {nullptr};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  std::lock_guard<std::mutex> hold(lock);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+    ptr[dev] = p;
+  }
+  return ptr[dev];
+}
+
 // splitzip_compress with the codebook either on the host (cb) or in device memory (d_cb); the words contiguous or paged
 int compress_impl(const Words& in, uint64_t n_elems, int dtype, const splitzip_codebook* cb, const splitzip_codebook* d_cb,
                   void* d_out, size_t out_capacity, void* d_workspace, size_t workspace_bytes, splitzip_sizes* d_sizes,
-                  void* stream) {
+                  void* stream, bool one_launch = false) {
   const void* d_in = in.base;
   if (!dtype_ok(dtype) || !d_out || !d_workspace || !d_sizes || (n_elems && !d_in)) return SPLITZIP_ERR_INVALID_ARG;
   if (!aligned16(d_in) || !aligned16(d_out) || !aligned16(d_workspace) ||
@@ -516,7 +538,8 @@ int compress_impl(const Words& in, uint64_t n_elems, int dtype, const splitzip_c
   if (d_cb ? (reinterpret_cast<uintptr_t>(d_cb) & 3u) != 0 : !codebook_ok(cb, dtype)) return SPLITZIP_ERR_INVALID_ARG;
   if (n_elems >> 32) return SPLITZIP_ERR_UNSUPPORTED;
   if (out_capacity < splitzip_fixed_bytes(n_elems, dtype)) return SPLITZIP_ERR_CAPACITY;
-  if (workspace_bytes < splitzip_workspace_bytes(n_elems, dtype)) return SPLITZIP_ERR_CAPACITY;
+  // one_launch: the workspace holds the exchange words only (no room to stage the escape values of a call that takes several launches)
+  if (workspace_bytes < (one_launch ? kWsHeaderBytes + kWsTableBytes : splitzip_workspace_bytes(n_elems, dtype))) return SPLITZIP_ERR_CAPACITY;
 
   const Layout L = make_layout(n_elems, dtype);
   CompressArgs a;
@@ -557,6 +580,7 @@ int compress_impl(const Words& in, uint64_t n_elems, int dtype, const splitzip_c
 
   uint64_t done = 0;
   const bool several = L.n_chunks > seg_cap;
+  if (several && one_launch) return SPLITZIP_ERR_UNSUPPORTED;
   do {
     const uint64_t left = L.n_chunks - done;
     const uint32_t seg = (uint32_t)(left < seg_cap ? left : seg_cap);
@@ -628,6 +652,21 @@ int splitzip_compress(const void* d_in, uint64_t n_elems, int dtype, const split
                       void* d_out, size_t out_capacity, void* d_workspace, size_t workspace_bytes,
                       splitzip_sizes* d_sizes, void* stream) {
   return compress_impl(contiguous_words(d_in), n_elems, dtype, cb, nullptr, d_out, out_capacity, d_workspace, workspace_bytes, d_sizes, stream);
+}
+
+uint64_t splitzip_noalloc_max_elems(void) {
+  const uint64_t wgs = (uint64_t)cu_count() < kMaxWorkgroups ? (uint64_t)cu_count() : kMaxWorkgroups;
+  return wgs * kMaxRange * kChunk;   // what one launch takes: no staging of escape values is needed below that
+}
+
+int splitzip_compress_noalloc(const void* d_in, uint64_t n_elems, int dtype, const splitzip_codebook* cb, void* d_out,
+                              size_t out_capacity, splitzip_sizes* d_sizes, void* stream) {
+  if (n_elems > splitzip_noalloc_max_elems()) return SPLITZIP_ERR_UNSUPPORTED;
+  void* ws = scratch_on_current_device();
+  if (!ws) return SPLITZIP_ERR_HIP;
+  // the exchange words are all a call of one launch needs; one that would take several is turned away by the size check
+  return compress_impl(contiguous_words(d_in), n_elems, dtype, cb, nullptr, d_out, out_capacity, ws, sizeof(scratch),
+                       d_sizes, stream, true);
 }
 
 int splitzip_decompress(const void* d_comp, size_t comp_bytes, uint64_t n_elems, int dtype,
