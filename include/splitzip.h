@@ -67,8 +67,8 @@ typedef enum {
 enum {
   SPLITZIP_STATUS_OVERFLOW = 1u,   /* compress: escapes did not fit out_capacity; total_bytes is the size needed */
   SPLITZIP_STATUS_BAD_STREAM = 2u, /* decompress: header / offsets / positions inconsistent; offending records skipped */
-  SPLITZIP_STATUS_INTERNAL = 4u    /* compress: the workgroups' exchange timed out (workspace not initialised, shared by
-                                      overlapping calls, or the launch could not become resident) */
+  SPLITZIP_STATUS_INTERNAL = 4u    /* reserved: no call of this version sets it (earlier versions reported a timed-out
+                                      exchange between workgroups here; the kernels no longer wait for one another) */
 };
 
 /* The three calibration tables of section 3.3.  Plain data, host memory,
@@ -134,22 +134,19 @@ size_t splitzip_fixed_bytes(uint64_t n_elems, int dtype);
 size_t splitzip_total_bytes(uint64_t n_elems, uint64_t n_escapes, int dtype);
 size_t splitzip_compress_bound(uint64_t n_elems, int dtype);
 
-/* Device scratch a compress call of up to n_elems needs: the words through
- * which the workgroups of a launch exchange their escape counts, and staging
- * for the escape values of tensors too large for one launch (about n_elems
- * bytes in all).  A workspace must be prepared once with
- * splitzip_workspace_init and can then serve any number of compress calls of
- * up to that size; each call leaves it ready for the next.  Calls that share
- * a workspace must not overlap in time (same stream, or otherwise ordered).
- * All workgroups of a compress launch wait for one another, so they must be
- * resident together.  One launch never asks for more than the device holds.
- * Launches that run at the same time on different streams of one device share
- * that room: two single-tensor compress calls always fit side by side (each
- * with its own workspace); a batch compress call fills the device alone, so
- * order it against every other compress call (same stream, or events).  A wait
- * that does not end within two seconds gives up with
- * SPLITZIP_STATUS_INTERNAL instead of hanging; re-initialise the workspace
- * after that.  Decompress calls and the variant calls have no such rule. */
+/* Device scratch of a compress call of up to n_elems: a status area of 4 MiB
+ * (the escape count of every 16 KB tile of the tensor) and a staging area of
+ * n_elems bytes and a little more (the tiles' escape records until their rank
+ * in the stream is known).  A compress call is two kernel launches: the first
+ * does the dense work tile by tile, the second ranks and places the escape
+ * records; no workgroup ever waits for another, so the calls run correctly
+ * whatever else the device is doing and however little of a launch fits the
+ * device at a time.  No word of a workspace needs a defined value before a
+ * call: splitzip_workspace_init exists for symmetry (it clears a small
+ * header) and is cheap.  Calls that share a workspace must not overlap in
+ * time (same stream, or otherwise ordered); calls with workspaces of their
+ * own may run side by side on different streams.  Decompress calls and the
+ * variant calls use no workspace of this kind. */
 size_t splitzip_workspace_bytes(uint64_t n_elems, int dtype);
 int splitzip_workspace_init(void* d_workspace, size_t workspace_bytes, void* stream);
 
@@ -163,6 +160,7 @@ int splitzip_workspace_init(void* d_workspace, size_t workspace_bytes, void* str
  * enqueued.  If the fixed part fits but the escapes do not, everything that
  * fits is written, status gets SPLITZIP_STATUS_OVERFLOW and total_bytes is
  * the size a retry needs.  n_elems == 0 is valid (header and one offset).
+ * Two launches on `stream` (three above 32 Mi elements of BF16).
  * The output is a pure function of (input, codebook): independent of
  * scheduling, capacity slack and earlier calls. */
 int splitzip_compress(const void* d_in, uint64_t n_elems, int dtype, const splitzip_codebook* cb,
@@ -171,18 +169,21 @@ int splitzip_compress(const void* d_in, uint64_t n_elems, int dtype, const split
 
 /* For callers that cannot allocate device memory -- code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc:
- * splitzip_compress without a workspace argument.  The words through which
- * the workgroups exchange their escape counts live in an array of 65 600
- * bytes inside the library's code object, one copy per GPU, held until the
+ * splitzip_compress without a workspace argument.  Status and staging areas
+ * live in an array of 1 MiB inside the library's code object (256 KiB of tile
+ * counts, 768 KiB of staged escape records), one copy per GPU, held until the
  * process ends; the call allocates nothing (no hipMalloc / hipFree, no
- * allocating library routine) and needs no splitzip_workspace_init.  Same
- * arguments otherwise, same stream bytes and sizes record as
- * splitzip_compress.  Limit: n_elems <= splitzip_noalloc_max_elems() (what one
- * launch takes: 256 x 1024 elements per CU, 64 Mi elements on an MI355X);
- * beyond it SPLITZIP_ERR_UNSUPPORTED and nothing is enqueued.  All calls on
- * one GPU share that GPU's array (each leaves it ready for the next): calls
- * that overlap in time on one GPU -- different streams, no ordering -- race
- * on it; order them, or use splitzip_compress with a workspace per stream. */
+ * allocating library routine).  Same arguments otherwise, same stream bytes
+ * and sizes record as splitzip_compress.  Limit: n_elems <=
+ * splitzip_noalloc_max_elems() = 2^30; beyond it SPLITZIP_ERR_UNSUPPORTED and
+ * nothing is enqueued.  (Tensors above 64 Mi elements get tiles larger than
+ * 16 KB so that their counts fit, and a tile whose escape records outgrow its
+ * share of the staging area -- a few dozen per tile at 64 MiB of BF16 -- is
+ * encoded a second time by the finishing launch: correct at any escape rate,
+ * slower above a few percent.)  All calls on one GPU share that GPU's array:
+ * calls that overlap in time on one GPU -- different streams, no ordering --
+ * race on it; order them, or use splitzip_compress with a workspace per
+ * stream. */
 uint64_t splitzip_noalloc_max_elems(void);
 int splitzip_compress_noalloc(const void* d_in, uint64_t n_elems, int dtype, const splitzip_codebook* cb,
                               void* d_out, size_t out_capacity, splitzip_sizes* d_sizes, void* stream);
@@ -208,15 +209,15 @@ int splitzip_decompress(const void* d_comp, size_t comp_bytes, uint64_t n_elems,
  * prefill chunk (the pipeline of the appendix "The Potential of Hiding Codec
  * Overhead with Pipeline Overlap" feeds the codec such batches).  Each item is
  * compressed exactly as splitzip_compress would (same stream bytes); what a
- * single call pays per tensor for the exchange between workgroups, the wait
- * for the slowest of them and the launch is paid once per launch of up to 64
- * tensors, because the exchange of one tensor is hidden under the dense pass
- * of the next.  Every item names its own codebook: per-layer codebooks (the
+ * single call pays per tensor for two launches -- the ramps of the dense pass
+ * and the short finishing pass -- is paid once per 64 tensors.  Every item
+ * names its own codebook: per-layer codebooks (the
  * section "Ablation on Layer-Wise Coverage") cost no more than shared ones.
  * `items` is a HOST array, read before the call returns.
  * d_sizes is a device array of n_items records.  Argument errors are found
  * before anything is enqueued.  Same workspace rules as splitzip_compress
- * (size it for the largest item). */
+ * (size it for the largest item; the items of a launch share its staging
+ * area, a larger workspace gives every tile more room for escape records). */
 typedef struct {
   const void* d_in;
   uint64_t n_elems;

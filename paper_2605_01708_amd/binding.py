@@ -127,6 +127,8 @@ def lib():
         L.splitzip_noalloc_max_elems.argtypes = []
         L.splitzip_compress_noalloc.restype = i
         L.splitzip_compress_noalloc.argtypes = [vp, u64, i, cbp, vp, sz, vp, vp]
+        L.splitzip_internal_test_hooks.restype = None
+        L.splitzip_internal_test_hooks.argtypes = [u64, u64]
         L.splitzip_traffic_probe.restype = i
         L.splitzip_traffic_probe.argtypes = [vp, sz, vp, sz, vp]
         L.splitzip_traffic_probe_shape.restype = i
@@ -326,6 +328,12 @@ def compress(x: torch.Tensor, cb: Codebook, out: torch.Tensor, workspace: Worksp
     _check(lib().splitzip_compress(x.data_ptr(), n, cb.dtype, C.byref(cb.c), out.data_ptr(), cap,
                                    workspace.buf.data_ptr(), workspace.nbytes, sizes.data_ptr(),
                                    _stream_ptr(stream)), "splitzip_compress")
+
+
+def internal_test_hooks(stage_bytes: int = 0, status_bytes: int = 0) -> None:
+    """What the tests of the rarely taken paths turn (not part of splitzip.h): a staging area and a status area smaller
+    than the workspace has.  0 = as built."""
+    lib().splitzip_internal_test_hooks(stage_bytes, status_bytes)
 
 
 def noalloc_max_elems() -> int:

@@ -134,7 +134,9 @@ __global__ __launch_bounds__(kThreads) void traffic_probe_kernel(const u32x4* sr
 // work on neighbouring runs) or in one contiguous block each (the way the codec's kernels own their chunks).
 template <int R, int W, bool NTL, bool NTS>
 __global__ __launch_bounds__(kThreads) void traffic_shape_kernel(const u32x4* src, uint64_t nread, u32x4* dst, uint64_t nwrite,
-                                                                  uint64_t steps, uint32_t blocked) {
+                                                                  uint64_t steps, uint32_t blocked_in) {
+  const uint32_t blocked = blocked_in & 3u;
+  const bool blocked_narrow = (blocked_in & 4u) != 0;
   const uint64_t per = (steps + gridDim.x - 1) / gridDim.x;
   const uint64_t s0 = blocked ? blockIdx.x * per : blockIdx.x;
   const uint64_t s_end = blocked ? (s0 + per < steps ? s0 + per : steps) : steps, stride = blocked ? 1 : gridDim.x;
@@ -142,8 +144,23 @@ __global__ __launch_bounds__(kThreads) void traffic_shape_kernel(const u32x4* sr
   // are not all at the same distance from the start of their blocks at the same time
   const uint64_t len = s_end > s0 ? s_end - s0 : 0, rot = blocked == 2 && len ? (blockIdx.x * 37ull) % len : 0;
   u32x4 acc = u32x4{0u, 0u, 0u, 0u};
-  for (uint64_t q = 0; s0 + q * stride < s_end; ++q) {
-    const uint64_t s = blocked == 2 ? s0 + (q + rot) % len : s0 + q * stride;
+  // blocked == 3: the steps are handed out in order through a counter (the word behind the written bytes, zeroed
+  // by the caller): the next step's number is fetched while this step's runs are on their way
+  __shared__ uint32_t s_ticket[2];
+  uint32_t* counter = reinterpret_cast<uint32_t*>(dst + nwrite);
+  uint64_t tk = 0;
+  if (blocked == 3) {
+    if (threadIdx.x == 0) s_ticket[0] = atomicAdd(counter, 1u);
+    __syncthreads();
+    tk = s_ticket[0];
+  }
+  for (uint64_t q = 0; blocked == 3 ? tk < steps : s0 + q * stride < s_end; ++q) {
+    const uint64_t s = blocked == 3 ? tk : blocked == 2 ? s0 + (q + rot) % len : s0 + q * stride;
+    if (blocked == 3) {
+      if (threadIdx.x == 0) s_ticket[(q + 1) & 1] = atomicAdd(counter, 1u);
+      __syncthreads();
+      tk = s_ticket[(q + 1) & 1];
+    }
     u32x4 v[R > 0 ? R : 1];
     v[0] = u32x4{(uint32_t)s, threadIdx.x, 0u, 0u};
 #pragma unroll
@@ -155,6 +172,17 @@ __global__ __launch_bounds__(kThreads) void traffic_shape_kernel(const u32x4* sr
     if (W == 0) {
 #pragma unroll
       for (int i = 0; i < R; ++i) acc ^= v[i];
+    }
+    if (blocked_narrow) {
+      // the codec's store shapes: two thirds of the step's bytes as 8-byte stores, one third as 4-byte stores
+      if (W == 3 && ((uint64_t)W * s + W) * kThreads <= nwrite) {
+        uint8_t* base = reinterpret_cast<uint8_t*>(dst + (uint64_t)W * s * kThreads);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) st_stream(reinterpret_cast<u32x2*>(base) + i * kThreads + threadIdx.x, u32x2{v[i % (R > 0 ? R : 1)].x, v[i % (R > 0 ? R : 1)].y});
+#pragma unroll
+        for (int i = 0; i < 4; ++i) st_stream(reinterpret_cast<uint32_t*>(base + 8192) + i * kThreads + threadIdx.x, v[i % (R > 0 ? R : 1)].z);
+      }
+      continue;
     }
 #pragma unroll
     for (int i = 0; i < W; ++i) {

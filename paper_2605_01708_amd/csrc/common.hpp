@@ -14,12 +14,10 @@ constexpr uint32_t kHeaderDecOffset = 40;                 // the 16 decode entri
 constexpr int kThreads = 256;                             // decompress / helper kernels
 constexpr int kWaves = kThreads / 64;
 constexpr uint32_t kMaxCpw = 16;                          // decompress: chunks per wave per tile, at most
-constexpr uint32_t kMaxRange = 256;                       // compress: chunks per workgroup per launch, at most
-constexpr uint32_t kMaxWorkgroups = 8192;                 // compress: words of exchange state in the workspace
-constexpr uint32_t kWsTableBytes = 8 * kMaxWorkgroups;
-constexpr uint32_t kStageCap = 512;                       // escapes a wave can stage in LDS
-constexpr uint32_t kWsHeaderBytes = 64;                   // epoch, running escape count, error flags
-constexpr uint32_t kSegFirst = 1u, kSegLast = 2u;         // CompressArgs.flags
+constexpr uint32_t kMaxRange = 256;                       // compress: chunks per tile, at most
+constexpr uint32_t kWsHeaderBytes = 512;                  // workspace: epoch, counters, error flags
+constexpr uint32_t kStatusBytes = 4u << 20;               // workspace: the words of the chains of escape counts
+constexpr uint32_t kStageFloor = 64u << 10;               // workspace: staging of escape values, at least
 constexpr uint64_t kSpinTicks = 200000000ull;             // 2 s of the 100 MHz wall clock
 
 __host__ __device__ inline uint64_t a256(uint64_t x) { return (x + 255u) & ~(uint64_t)255u; }

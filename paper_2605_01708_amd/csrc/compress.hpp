@@ -1,4 +1,4 @@
-// SplitZip for MI355X: the compress kernels (dense transform of both formats, escape staging, the exchange between workgroups, single-tensor and batch kernels).
+// SplitZip for MI355X: the compress kernels (dense transform of both formats with escape staging, one tile per workgroup; the finishing pass that ranks and places the escape records; the trailer).
 // Part of the single translation unit splitzip.hip (included inside its anonymous namespace).
 #ifndef SPLITZIP_COMPRESS_HPP
 #define SPLITZIP_COMPRESS_HPP
@@ -30,21 +30,6 @@ __host__ __device__ inline Planes make_planes(const Words& in, void* out, uint64
   return p;
 }
 
-struct CompressArgs {
-  Planes p;
-  uint32_t* ws_hdr;      // [0] epoch of this launch, [1] escapes of the earlier segments, [2] sticky error flags
-  uint64_t* state;       // one word per workgroup: epoch << 32 | escapes in its range
-  uint8_t* val_stage;    // n bytes: escape values of a call of several launches, until M is known
-  splitzip_sizes* sizes;
-  uint64_t spin_ticks;
-  uint32_t seg_chunk0, seg_chunks;   // the chunks this launch covers
-  uint32_t flags;        // kSegFirst | kSegLast
-  uint32_t expect_wgs;   // workgroups whose counts are awaited (= the grid size)
-  const splitzip_codebook* d_cb;   // nullable: a codebook in device memory, used instead of dec / lut below
-  uint8_t dec[16];
-  uint16_t lut[256];     // exponent -> code | (non-member ? 0x100 : 0)   (the "marked" table of appendix A)
-};
-
 // where a chunk's escape records go: LDS staging (first pass) or their final place
 struct LdsSink {
   uint16_t* pos;
@@ -58,7 +43,16 @@ struct LdsSink {
     }
   }
 };
-struct GlobalSink {
+// a tile's slot in the staging area: records in the order of the tile's elements, position | exponent << 16
+struct SlotSink {
+  uint32_t* slot;
+  uint32_t cap;   // records the slot holds
+  __device__ inline void put(uint32_t r, uint32_t p, uint32_t e) const {
+    if (r < cap) slot[r] = p | (e << 16);
+  }
+};
+// the final place of the records of a tensor: positions and, behind them, values
+struct FinalSink {
   uint16_t* pos;
   uint8_t* val;
   uint64_t pos_room, val_room;   // records that fit below the capacity
@@ -66,6 +60,10 @@ struct GlobalSink {
     if (r < pos_room) pos[r] = (uint16_t)p;
     if (r < val_room) val[r] = (uint8_t)e;
   }
+};
+// counting only
+struct NullSink {
+  __device__ inline void put(uint32_t, uint32_t, uint32_t) const {}
 };
 
 // Dense transform of 8 BF16 elements held in four dwords.
@@ -330,11 +328,12 @@ struct Bf16 {
 #pragma unroll
       for (int d = 0; d < 4; ++d) asm volatile("" : "+v"(r.w[h][d]));
   }
-  // batch kernel: two workgroups of 512 per CU, 512 staged escapes per wave.  Against one workgroup of 1024: the
-  // same on 64 MiB tensors, 2 to 4 % faster on 4 to 32 MiB ones; four workgroups of 512 (eight waves per SIMD) are
-  // no faster, eight of 256 are 3 % slower.
-  static constexpr int kBatchThreads = 512, kBatchWgsPerCu = 2, kBatchWavesPerSimd = 4;
-  static constexpr uint32_t kBatchStageCap = kStageCap;
+  // A workgroup of four waves takes a tile of 4 x kCpt chunks (16 KB of words).  Five workgroups per CU serve BF16
+  // best (one launch over 64 tensors of 64 MiB: 1270 us against 1310 us with eight, 1300 with four, 1460 with
+  // three); unused LDS asked for at the launch sets the number.
+  static constexpr uint32_t kCpt = 2;
+  static constexpr int kWavesPerSimd = 8;
+  static constexpr uint32_t kTileLdsPad = 22000;
   static constexpr int kLutShift = 0;       // the LDS encode table holds the entry of exponent e in slot e
   // a chunk goes the fast way if it is complete (then nothing of a pad is its business: N is a multiple of 1024 there)
   __device__ static inline bool full(const Planes& a, uint64_t cbase) { return cbase + kChunk <= a.n; }
@@ -353,13 +352,11 @@ struct E5m2 {
 #pragma unroll
     for (int d = 0; d < 4; ++d) asm volatile("" : "+v"(r.w[d]));
   }
-  // batch kernel: eight workgroups of 256 per CU, eight waves per SIMD at 64 registers.  Many small workgroups
-  // matter more than the wave count: while one of them exchanges counts and writes escape records out, the others
-  // keep the CU's memory pipeline busy (measured on 64 tensors of 32 MiB: 1 x 1024 threads 2.2 TB/s, 4 x 256 and
-  // 4 x 512 2.45, 8 x 256 2.65).  256 staged escapes per wave are plenty: FP8 exponents miss the codebook far less
-  // often than BF16 ones, and a wave that does overflow takes the second pass of write_out.
-  static constexpr int kBatchThreads = 256, kBatchWgsPerCu = 8, kBatchWavesPerSimd = 8;
-  static constexpr uint32_t kBatchStageCap = 256;
+  // a tile of 4 x kCpt chunks is 16 KB of words here too; eight workgroups per CU (730 us for 64 tensors of 32 MiB
+  // against 750 us with six and 790 us with five)
+  static constexpr uint32_t kCpt = 4;
+  static constexpr int kWavesPerSimd = 8;
+  static constexpr uint32_t kTileLdsPad = 0;
   // The LDS encode table holds the entry of exponent e in slots 2 e and 2 e + 1: its byte offset is then
   // the word's byte with the sign and mantissa bits masked off, one instruction per element.
   static constexpr int kLutShift = 1;
@@ -407,284 +404,71 @@ __device__ void compress_write_trailer(const Planes& a, const uint8_t* dec, spli
   }
 }
 
-// ---- building blocks of the compress kernels ----
-// A workgroup owns a contiguous range [r0, r0 + nb) of a tensor's chunks, nb <= kMaxRange, dealt
-// round-robin to its NW waves (chunk k of the range belongs to wave k mod NW).  LDS per range:
-//   stage_pk/val[wave][.]  the wave's escape records, position | (k / NW) << 10 and exponent
-//   s_off[k]               escapes of chunk k, after the scan: escapes of the chunks before it
-//   s_wstart[k]            records its wave had staged before chunk k
-struct RangeLds {
-  uint16_t* stage_pk;    // this wave's `cap` entries
-  uint8_t* stage_val;
-  uint32_t* s_off;       // kMaxRange + 1
-  uint16_t* s_wstart;    // kMaxRange
-  uint32_t cap;          // escape records a wave can stage
-};
+// ---- the two passes of a compress call ----
+// Pass 1, compress_tile_kernel: one workgroup of four waves per tile of 4 x cpt chunks (16 KB of words), started by
+// the hardware in the order of the tiles -- the access pattern the memory system likes best, see
+// traffic_shape_kernel.  A workgroup waits for nobody: planes out; escapes of the tile staged in LDS, then written
+// as (position | exponent << 16) records, in element order, to the tile's slot of the staging area; the tile's
+// entries of the offset table as offsets inside the tile; the tile's escape count to the status area.
+// Pass 2, compress_finish_kernel: one workgroup per group of 16 tiles.  It sums the counts (all of the tensor's:
+// M; those before the group: its first rank), adds what lies before each tile to the tile's table entries and
+// moves the records from the slots to their ranks in the position and value arrays.  A tile with more escapes
+// than its slot (or its LDS staging) holds is encoded once more from the words, straight to the final place.
+// Between the passes lies a kernel boundary: no workgroup ever waits for another, nothing needs to be resident
+// together, and no word of the workspace needs a defined value before a call.
+constexpr uint32_t kTileThreads = 256;
+constexpr uint32_t kGroup = 16;             // tiles per workgroup of the finishing pass
+constexpr uint32_t kSlotAhead = 16;         // records per tile the finishing pass fetches before it knows the counts
+constexpr uint32_t kTileStageCap = 256;     // escapes a wave can stage in LDS
+constexpr uint32_t kSlotCapMost = 1024;     // records per tile slot, at most
+constexpr uint32_t kDirectTiles = 4096;     // up to this many tiles per tensor the finishing pass sums the tile counts itself
+constexpr uint32_t kSumGroup = 64;          // beyond: sums of this many tile counts, by tile_group_sum_kernel
+constexpr uint32_t kBatchMax = 64;          // tensors per launch: their descriptors travel as kernel arguments
+constexpr uint32_t kRedo = 0x80000000u;     // in a tile's count: its records are not in its slot
+static_assert(kGroup * kSlotAhead == kTileThreads, "one record fetched ahead per thread");
 
-// this workgroup's share of `chunks` chunks starting at chunk0: dealt evenly, the first `rem`
-// workgroups get one more
-__device__ inline void my_range(uint32_t chunk0, uint32_t chunks, uint32_t wgs, uint32_t b, uint32_t& r0, uint32_t& nb) {
-  const uint32_t per = chunks / wgs, rem = chunks % wgs;
-  nb = per + (b < rem ? 1u : 0u);
-  r0 = chunk0 + b * per + (b < rem ? b : rem);
-}
-
-struct NoHook {
-  __device__ inline void operator()() const {}
-};
-
-// dense pass of one wave over its chunks of the range; the loads of the next chunk are issued before
-// this chunk is worked on (what a wave has in flight at that point is what keeps the memory system
-// busy: 1 to 2 KB per wave).  `mid` is called once, half way through (not at all by a wave without
-// chunks).  Returns the wave's escape count.
-template <int NW, typename F, typename Hook>
-__device__ inline uint32_t dense_pass(const Planes& P, const uint16_t* lut, uint32_t* park, const RangeLds& L,
-                                      uint32_t r0, uint32_t nb, int wave, int lane, Hook& mid) {
-  uint32_t wave_count = 0;
-  const uint32_t mine = nb > (uint32_t)wave ? (nb - wave + NW - 1) / NW : 0u;   // chunks of this wave
-  const uint32_t mid_it = mine / 2;
-  typename F::Regs w, nx;
-  // paged tensor: the pool pages of all of the wave's chunks at once (lane it <-> its it-th chunk), so that no
-  // table read stands in front of a chunk's loads later
-  uint32_t my_pages = 0;
-  if (P.w.table && (uint32_t)lane < mine) my_pages = page_of_chunk(P.w, r0 + wave + (uint32_t)lane * NW);
-  // the wave's it-th chunk into r (nothing if it has no such chunk)
-  auto fetch = [&](uint32_t it, typename F::Regs& r) {
-    if (it < mine) {
-      const uint64_t cbase = (uint64_t)(r0 + wave + it * NW) * kChunk;
-      const uint8_t* cptr = chunk_at<F::ES>(P.w, cbase, __builtin_amdgcn_readlane(my_pages, it));
-      if (F::full(P, cbase)) F::template load<true>(P, cptr, cbase, lane, r);
-      else F::template load<false>(P, cptr, cbase, lane, r);
-    }
-  };
-  // Only the tensor's last chunk can be ragged, and it is the last of its wave: the loop takes complete chunks
-  // only (no branch between two ways of storing stands between a chunk's loads and the wait for them), the
-  // ragged one comes after it.
-  const bool last_ragged = mine > 0 && !F::full(P, (uint64_t)(r0 + wave + (mine - 1) * NW) * kChunk);
-  const uint32_t fast = mine - (last_ragged ? 1u : 0u);
-  auto chunk = [&](uint32_t it, auto complete) {
-    const uint32_t k = wave + it * NW;
-    const uint64_t cbase = (uint64_t)(r0 + k) * kChunk;
-    if (it == mid_it) mid();
-    const LdsSink lds{L.stage_pk, L.stage_val, it << 10, L.cap};
-    const uint32_t cnt = F::template process<decltype(complete)::value, true>(P, lut, park, cbase, lane, w, wave_count, lds);
-    if (lane == 0) {
-      L.s_off[k] = cnt;
-      L.s_wstart[k] = (uint16_t)(wave_count < 0xffffu ? wave_count : 0xffffu);
-    }
-    wave_count += cnt;
-  };
-  fetch(0, w);
-  // The first chunk has to be there before the loop is entered: a load still pending on entry would put the
-  // compiler's wait into the loop header, where every iteration pays it in full (all loads and stores issued
-  // so far), the next chunk's loads included.
-  F::arrived(w);
-  for (uint32_t it = 0; it < fast; ++it) {
-    fetch(it + 1, nx);
-    chunk(it, std::true_type{});
-    w = nx;
-  }
-  if (last_ragged) chunk(mine - 1, std::false_type{});
-  return wave_count;
-}
-
-// one wave: exclusive offsets of the range's chunks, four per lane, in place; s_off[nb] = total
-__device__ inline void scan_range(uint32_t* s_off, uint32_t nb, int lane) {
-  uint32_t v[4], sum = 0;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const uint32_t q = 4 * lane + j;
-    v[j] = q < nb ? s_off[q] : 0u;
-    sum += v[j];
-  }
-  const uint32_t incl = wave_incl_scan(sum);
-  uint32_t run = incl - sum;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const uint32_t q = 4 * lane + j;
-    if (q < nb) s_off[q] = run;
-    run += v[j];
-  }
-  if (lane == 63) s_off[nb] = incl;
-}
-
-// one wave: wait until the words of all `wgs` workgroups carry `tag`, then sum the counts of the
-// workgroups before b (lower) and of all.  Returns false if the wait was given up: it is bounded
-// by spin_ticks of the 100 MHz wall clock (or not begun at all if `dead`).
-__device__ inline bool exchange(const uint64_t* state, uint32_t tag, uint32_t wgs, uint32_t b, int lane,
-                                uint64_t spin_ticks, bool dead, uint32_t& lower, uint32_t& all) {
-  uint32_t lo = 0, al = 0, spins = 0;
-  bool ok = !dead;
-  const uint64_t t0 = wall_clock64();
-  while (ok) {
-    lo = 0;
-    al = 0;
-    int ready = 1;
-    for (uint32_t i = lane; i < wgs; i += 64) {
-      const uint64_t s = ld_agent(&state[i]);
-      if ((uint32_t)(s >> 32) != tag) ready = 0;
-      al += (uint32_t)s;
-      lo += i < b ? (uint32_t)s : 0u;
-    }
-    if (__ballot(ready) == ~0ull) break;
-    if ((++spins & 15u) == 0 && (uint64_t)(wall_clock64() - t0) > spin_ticks) ok = false;
-    else __builtin_amdgcn_s_sleep(1);
-  }
-  lower = wave_last(wave_incl_scan(lo));
-  all = wave_last(wave_incl_scan(al));
-  return ok;
-}
-
-// all waves: the range's entries of the stream's offset table and this wave's escape records to
-// their final rank.  `prefix` = escapes before the range in the whole tensor.
-template <int NW, typename F>
-__device__ inline void write_out(const Planes& P, const uint16_t* lut, uint32_t* park, const RangeLds& L,
-                                 uint32_t r0, uint32_t nb, uint32_t wave_count, uint32_t prefix,
-                                 const GlobalSink& g, int tid, int wave, int lane) {
-  uint32_t* tab = reinterpret_cast<uint32_t*>(P.out + P.off_tab);
-  if ((uint32_t)tid < nb) tab[r0 + tid] = prefix + L.s_off[tid];
-  if (wave_count <= L.cap) {
-    // staged record i of this wave belongs to chunk k and is the (i - s_wstart[k])-th of it
-    for (uint32_t i = lane; i < wave_count; i += 64) {
-      const uint32_t pk = L.stage_pk[i], k = (pk >> 10) * NW + wave;
-      g.put(prefix + L.s_off[k] + (i - L.s_wstart[k]), pk & 1023u, L.stage_val[i]);
-    }
-  } else {
-    // more escapes than the staging holds: go over this wave's chunks again and write the
-    // records straight to their place
-    typename F::Regs w;
-    for (uint32_t k = wave; k < nb; k += NW) {
-      const uint64_t cbase = (uint64_t)(r0 + k) * kChunk;
-      const uint32_t r = prefix + L.s_off[k];
-      const uint8_t* cptr = chunk_at<F::ES>(P.w, cbase, P.w.table ? page_of_chunk(P.w, r0 + k) : 0u);
-      if (F::full(P, cbase)) {
-        F::template load<true>(P, cptr, cbase, lane, w);
-        F::template process<true, false>(P, lut, park, cbase, lane, w, r, g);
-      } else {
-        F::template load<false>(P, cptr, cbase, lane, w);
-        F::template process<false, false>(P, lut, park, cbase, lane, w, r, g);
-      }
-    }
-  }
-}
-
-// where escape records of a tensor go when M is final: positions and, behind them, values
-__device__ inline GlobalSink final_sink(const Planes& P, uint32_t M) {
-  const uint64_t off_val = P.off_pos + a256(2ull * M);
-  GlobalSink g;
-  g.pos = reinterpret_cast<uint16_t*>(P.out + P.off_pos);
-  g.pos_room = P.capacity > P.off_pos ? (P.capacity - P.off_pos) / 2 : 0;
-  g.val = P.out + off_val;
-  g.val_room = P.capacity > off_val ? P.capacity - off_val : 0;
-  return g;
-}
-
-// One launch covers the chunks [seg_chunk0, seg_chunk0 + seg_chunks) with a grid in which every
-// workgroup is resident at the same time.  After its dense pass a workgroup publishes the escape
-// count of its range in state[b] (tagged with the launch's epoch, so that the words never need
-// clearing) and one wave reads the words of all workgroups: the counts before b give its offset,
-// all of them give M.  The wait ends when the slowest workgroup has published.
-template <int T, typename F>
-__global__ __launch_bounds__(T, (T == 1024 ? 8 : 1)) void compress_kernel(const CompressArgs a) {
-  constexpr int NW = T / 64;
-  static_assert(kMaxRange <= 256 && NW >= 4 && NW <= 16, "one wave scans the range, four chunks per lane");
-  __shared__ uint16_t lut[256];
-  __shared__ uint16_t stage_pk[NW][kStageCap];
-  __shared__ uint8_t stage_val[NW][kStageCap];
-  __shared__ uint32_t s_off[kMaxRange + 1];
-  __shared__ uint16_t s_wstart[kMaxRange];
-  __shared__ u32x4 s_park[T];
-  __shared__ uint32_t s_red[16];
-  __shared__ uint32_t s_misc[4];
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: loops over chunks stay scalar
-  const uint32_t b = blockIdx.x;
-  uint32_t* park = reinterpret_cast<uint32_t*>(&s_park[tid]);
-  const RangeLds L{stage_pk[wave], stage_val[wave], s_off, s_wstart, kStageCap};
-
-  if (tid < 256) {
-    const int e = tid >> F::kLutShift;   // LDS slot tid holds the entry of exponent e
-    lut[tid] = a.d_cb ? (a.d_cb->member[e] ? (uint16_t)a.d_cb->enc[e] : (uint16_t)0x100u) : a.lut[e];
-  }
-  const uint8_t* dec = a.d_cb ? a.d_cb->dec : a.dec;
-  const uint32_t epoch = ld_agent(&a.ws_hdr[0]);
-  const uint32_t base = (a.flags & kSegFirst) ? 0u : ld_agent(&a.ws_hdr[1]);
-  const uint32_t err_before = b == 0 ? ld_agent(&a.ws_hdr[2]) : 0u;   // sticky flags of earlier launches
-  const bool single = (a.flags & (kSegFirst | kSegLast)) == (kSegFirst | kSegLast);
-  __syncthreads();
-
-  uint32_t r0, nb;
-  my_range(a.seg_chunk0, a.seg_chunks, gridDim.x, b, r0, nb);
-  NoHook no_hook;
-  const uint32_t wave_count = dense_pass<NW, F>(a.p, lut, park, L, r0, nb, wave, lane, no_hook);
-  if (lane == 0) s_red[wave] = wave_count;
-  __syncthreads();
-
-  if (wave == 0) {
-    const uint32_t agg = wave_last(wave_incl_scan(lane < NW ? s_red[lane] : 0u));
-    if (lane == 0) st_agent(&a.state[b], ((uint64_t)epoch << 32) | agg);
-    uint32_t lo, al;
-    const bool ok = exchange(a.state, epoch, a.expect_wgs, b, lane, a.spin_ticks, false, lo, al);
-    if (lane == 0) {
-      s_misc[0] = base + lo;
-      s_misc[1] = base + al;
-      s_misc[2] = ok ? 0u : 1u;
-    }
-    // workgroup 0 closes the launch: it has seen every workgroup's word, so all of them have
-    // read the header words
-    if (b == 0) {
-      const uint32_t err = err_before | (ok ? 0u : (uint32_t)SPLITZIP_STATUS_INTERNAL);
-      if (lane == 0) {
-        st_agent(&a.ws_hdr[0], epoch + 1u);
-        st_agent(&a.ws_hdr[1], base + al);
-        st_agent(&a.ws_hdr[2], single ? 0u : err);   // a call of several launches reports in its finishing launch
-      }
-      if (single) compress_write_trailer(a.p, dec, a.sizes, base + al, err, lane);
-    }
-  } else if (wave == 1) {
-    scan_range(s_off, nb, lane);   // meanwhile
-  }
-  __syncthreads();
-  const uint32_t prefix = s_misc[0], M = s_misc[1];
-  const bool timed_out = s_misc[2] != 0;
-
-  if (!timed_out) {
-    // values go behind the positions when M is final, else into the workspace
-    GlobalSink g = final_sink(a.p, M);
-    if (!single) {
-      g.val = a.val_stage;
-      g.val_room = ~0ull;
-    }
-    write_out<NW, F>(a.p, lut, park, L, r0, nb, wave_count, prefix, g, tid, wave, lane);
-  } else if (tid == 0) {
-    __hip_atomic_fetch_or(&a.ws_hdr[2], (uint32_t)SPLITZIP_STATUS_INTERNAL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
-}
-
-// ---- several tensors in one launch ----
-constexpr uint32_t kBatchMax = 64;     // tensors per launch: their descriptors travel as kernel arguments
-constexpr uint32_t kRing = 4;          // exchange slots: a workgroup can be two tensors ahead of the slowest
-constexpr uint32_t kRingWgs = 2048;    // words per slot
-
-struct BatchItem {
+struct TileItem {
   const uint8_t* in;
   uint8_t* out;
   uint64_t n, capacity;
 };
-struct CompressBatchArgs {
-  BatchItem item[kBatchMax];
-  splitzip_sizes* sizes;     // n_items records
-  uint32_t* ws_hdr;          // [0] epoch, [2] sticky error flags, [3] groups that are through
-  uint64_t* state;           // per group kRing slots of group_wgs words: (epoch + item) << 32 | escapes in the range
-  uint64_t spin_ticks;
+struct TileArgs {
+  TileItem item[kBatchMax];
+  splitzip_sizes* sizes;          // n_items records
+  uint8_t* status;                // per tensor: u32 count of every tile, then u32 sum of every kSumGroup tiles
+  uint8_t* stage;                 // per tensor stage_cap bytes: the tiles' slots
+  uint64_t stage_cap;
+  uint32_t status_off[kBatchMax]; // where a tensor's counts start in `status`
   uint32_t n_items, dtype;
-  uint32_t group_wgs;        // workgroups that share one tensor; the grid is n_groups * group_wgs
-  uint32_t await_extra;      // error-path tests: words awaited beyond the group's
-  Words paging;              // table and page geometry shared by all tensors (table null: contiguous tensors); base unused
-  uint8_t dec[kBatchMax][16];   // every tensor's codebook, as its 16 decode entries: the kernel builds the encode table from them
-  const splitzip_codebook* d_cbs;   // nullable: n_items codebooks in device memory, used instead of dec
+  uint32_t cpt;                   // chunks per wave and tile, a power of two
+  uint32_t tile_shift;            // log2 of the chunks per tile (4 cpt)
+  uint32_t slot_cap;              // records per tile slot (the same for all tensors of the launch)
+  uint32_t use_group_sums;        // the finishing pass reads sums of kSumGroup tile counts (tile_group_sum_kernel) instead of all tile counts
+  Words paging;                   // table and page geometry shared by all tensors (table null: contiguous tensors); base unused
+  const splitzip_codebook* d_cbs; // nullable: n_items codebooks in device memory, used instead of dec
+  uint8_t dec[kBatchMax][16];     // every tensor's codebook, as its 16 decode entries: the kernels build the encode table from them
   __device__ inline const uint8_t* dec_of(uint32_t k) const { return d_cbs ? d_cbs[k].dec : dec[k]; }
 };
+
+// what both passes derive from the arguments for one tensor
+struct TileGeom {
+  Planes P;
+  uint32_t tile_chunks, n_tiles;
+  uint32_t* counts;      // n_tiles
+  uint32_t* group_sums;  // ceil(n_tiles / kSumGroup)
+  uint32_t* slots;       // n_tiles x slot_cap records
+};
+__device__ inline TileGeom tile_geom(const TileArgs& a, uint32_t item) {
+  TileGeom g;
+  const TileItem it = a.item[item];
+  g.P = make_planes(item_words(a.paging, it.in), it.out, it.n, it.capacity, (int)a.dtype);
+  g.tile_chunks = 1u << a.tile_shift;
+  g.n_tiles = (g.P.n_chunks + g.tile_chunks - 1) >> a.tile_shift;
+  g.counts = reinterpret_cast<uint32_t*>(a.status + a.status_off[item]);
+  g.group_sums = g.counts + g.n_tiles;
+  g.slots = reinterpret_cast<uint32_t*>(a.stage + (uint64_t)item * a.stage_cap);
+  return g;
+}
 
 // entry of the LDS encode table for exponent e under the codebook dec (wave-uniform): its code, or the escape mark
 __device__ inline uint16_t encode_entry(const uint8_t* dec, uint32_t e) {
@@ -694,220 +478,227 @@ __device__ inline uint16_t encode_entry(const uint8_t* dec, uint32_t e) {
   return (uint16_t)entry;
 }
 
-// Half way through a dense pass: the loads of the previous tensor's exchange words, so that their
-// latency is hidden.  Wave w of the first few waves (one per 256 workgroups a group can have, four at most)
-// fetches the words [256 w, 256 w + 256) of the group, four per lane, reduces them at the end of its pass,
-// and wave 0 puts the parts together.  A larger group goes without: wave 0 reads its words when it needs them.
-struct ExchangePrefetch {
-  const uint64_t* slot;
-  uint32_t first, wgs;
-  int lane;
-  bool enabled, issued;
-  uint64_t v[4];
-  __device__ inline void operator()() {
-    if (!enabled) return;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const uint32_t i = first + lane + 64 * j;
-      v[j] = i < wgs ? ld_agent(&slot[i]) : 0ull;
-    }
-    issued = true;
-  }
-  // the wave's part: true if all of its words carry the tag; lower = counts of the workgroups before b, all = of all
-  __device__ inline bool reduce(uint32_t tag, uint32_t b, uint32_t& lower, uint32_t& all) const {
-    uint32_t lo = 0, al = 0;
-    int ready = 1;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const uint32_t q = first + lane + 64 * j;
-      if (q < wgs) {
-        if ((uint32_t)(v[j] >> 32) != tag) ready = 0;
-        al += (uint32_t)v[j];
-        lo += q < b ? (uint32_t)v[j] : 0u;
-      }
-    }
-    lower = wave_last(wave_incl_scan(lo));
-    all = wave_last(wave_incl_scan(al));
-    return __ballot(ready) == ~0ull;
-  }
-};
+// a barrier for LDS traffic only: global loads that are on their way stay on their way
+__device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-// The same persistent grid works through the tensors one after the other, and the exchange of
-// tensor i is taken out of the critical path: a workgroup publishes its count for tensor i, then
-// completes tensor i - 1 (whose counts every workgroup published a whole dense pass ago; the words
-// are even fetched half way through the dense pass of tensor i, so the read costs nothing) and
-// goes on to tensor i + 1.  Staging in LDS has three sets (tensor i + 1 may be staged while i - 1 is still written out).  What a single launch pays per
-// tensor -- the wait for the slowest workgroup, the exchange, the write-out and the launch itself
-// -- is paid once per batch here.  Small tensors are shared by a group of workgroups only; the
-// groups work on different tensors at the same time (tensor i belongs to group i mod n_groups).
-template <int T, typename F>
-__global__ __launch_bounds__(T, F::kBatchWavesPerSimd) void compress_batch_kernel(const CompressBatchArgs a) {
-  constexpr int NW = T / 64;
-  constexpr uint32_t CAP = F::kBatchStageCap;
-  constexpr int PFW = F::kBatchWgsPerCu < 4 ? F::kBatchWgsPerCu : 4;   // waves that fetch exchange words ahead, 256 each: for groups of up to 256 PFW workgroups
-  static_assert(PFW <= NW && PFW <= 4, "prefetching waves");
-  __shared__ uint32_t s_pf[4][4];          // parts of the waves 1 .. PFW - 1: ready, lower, all
-  // the table of the tensor whose dense pass is running, at an address the compiler knows: its lookups carry
-  // the table's place as an immediate, one address instruction less per element
-  __shared__ uint16_t lut_now[256];
-  // the tables of the two tensors before it (a wave whose staging overflowed encodes its chunks again in write_out)
-  __shared__ uint16_t lut_old[2][256];
-  __shared__ uint16_t stage_pk[3][NW][CAP];   // three sets: a wave may stage tensor i + 1 while another still writes out i - 1
-  __shared__ uint8_t stage_val[3][NW][CAP];
-  __shared__ uint32_t s_off[3][kMaxRange + 1];
-  __shared__ uint16_t s_wstart[3][kMaxRange];
-  __shared__ u32x4 s_park[T];
-  __shared__ uint32_t s_red[16];
-  __shared__ uint32_t s_misc[4];
+// CPT: chunks of a wave whose loads are issued together, before anything else happens in the workgroup.  Wave w of
+// the tile owns the chunks [w cpt, w cpt + cpt) of the tile.
+template <typename F, int CPT>
+__global__ __launch_bounds__(kTileThreads, F::kWavesPerSimd) void compress_tile_kernel(const TileArgs a) {
+  constexpr int NW = kTileThreads / 64;
+  __shared__ uint16_t lut[256];
+  __shared__ uint16_t stage_pk[NW][kTileStageCap];
+  __shared__ uint8_t stage_val[NW][kTileStageCap];
+  __shared__ u32x4 s_park[kTileThreads];
+  __shared__ uint32_t s_cnt[NW];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const uint32_t G = a.group_wgs, n_groups = gridDim.x / G;
-  const uint32_t grp = blockIdx.x / G, b = blockIdx.x % G;
+  const uint32_t item = blockIdx.y;
+  const TileGeom G = tile_geom(a, item);
+  const Planes& P = G.P;
+  const uint32_t t = blockIdx.x;
+  if (t >= G.n_tiles) return;
+  const uint32_t r0 = t << a.tile_shift, nb = P.n_chunks - r0 < G.tile_chunks ? P.n_chunks - r0 : G.tile_chunks;
+  const uint32_t w0 = (uint32_t)wave * a.cpt;                                   // the wave's first chunk inside the tile
+  const uint32_t mine = nb > w0 ? (nb - w0 < a.cpt ? nb - w0 : a.cpt) : 0u;     // and how many it has
   uint32_t* park = reinterpret_cast<uint32_t*>(&s_park[tid]);
 
-  if (grp < a.n_items)
-    for (int i = tid; i < 256; i += T) lut_now[i] = encode_entry(a.dec_of(grp), (uint32_t)i >> F::kLutShift);
-  const uint32_t epoch = ld_agent(&a.ws_hdr[0]);
-  const uint32_t err_before = b == 0 ? ld_agent(&a.ws_hdr[2]) : 0u;
-  if (tid == 0) s_misc[3] = 0;   // set once an exchange was given up: later ones are not waited for
-  __syncthreads();
+  // the wave's chunks [it0, it0 + CPT) into r (nothing for chunks it does not have)
+  auto fetch = [&](uint32_t it0, typename F::Regs (&r)[CPT]) {
+#pragma unroll
+    for (int j = 0; j < CPT; ++j) {
+      const uint32_t it = it0 + j;
+      if (it < mine) {
+        const uint64_t cbase = (uint64_t)(r0 + w0 + it) * kChunk;
+        const uint8_t* cptr = chunk_at<F::ES>(P.w, cbase, P.w.table ? page_of_chunk(P.w, r0 + w0 + it) : 0u);
+        if (F::full(P, cbase)) F::template load<true>(P, cptr, cbase, lane, r[j]);
+        else F::template load<false>(P, cptr, cbase, lane, r[j]);
+      }
+    }
+  };
+  typename F::Regs w[CPT];
+  // the words first: the table is built while they are on their way
+  fetch(0, w);
+  lut[tid] = encode_entry(a.dec_of(item), (uint32_t)tid >> F::kLutShift);
+  lds_barrier();
 
-  uint64_t* const ring = a.state + (uint64_t)grp * kRing * G;   // this group's slots
-  Planes Pprev = make_planes(contiguous_words(nullptr), nullptr, 0, 0, (int)a.dtype);
-  uint32_t prev_count = 0, prev_r0 = 0, prev_nb = 0, prev_item = 0;
-  // this group's tensors: grp, grp + n_groups, ...; seq counts them
-  for (uint32_t seq = 0;; ++seq) {
-    const uint32_t i = grp + seq * n_groups;
-    const bool have = i < a.n_items;
-    if (!have && seq == 0) break;   // a group without tensors
-    const uint32_t set = seq % 3u;
-    const RangeLds L{stage_pk[set][wave], stage_val[set][wave], s_off[set], s_wstart[set], CAP};
-    Planes P = Pprev;
-    uint32_t r0 = 0, nb = 0, wave_count = 0;
-    ExchangePrefetch pf;
-    pf.slot = ring + ((seq + kRing - 1) % kRing) * G;
-    pf.first = 256u * (uint32_t)wave;
-    pf.wgs = G;
-    pf.lane = lane;
-    pf.enabled = wave < PFW && seq > 0 && G <= 256u * PFW && a.await_extra == 0;
-    pf.issued = false;
-    if (have) {
-      P = make_planes(item_words(a.paging, a.item[i].in), a.item[i].out, a.item[i].n, a.item[i].capacity, (int)a.dtype);
-      my_range(0, P.n_chunks, G, b, r0, nb);
-      wave_count = dense_pass<NW, F>(P, lut_now, park, L, r0, nb, wave, lane, pf);
-      if (lane == 0) s_red[wave] = wave_count;
-    }
-    if (PFW > 1 && wave > 0 && wave < PFW) {
-      uint32_t lo = 0, al = 0;
-      // a wave whose words lie beyond the group has nothing to wait for
-      const bool ready = pf.first >= G || (pf.issued && pf.reduce(epoch + prev_item, b, lo, al));
-      if (lane == 0) {
-        s_pf[wave][0] = ready ? 1u : 0u;
-        s_pf[wave][1] = lo;
-        s_pf[wave][2] = al;
-      }
-    }
-    __syncthreads();
-    if (wave == 0) {
-      if (have) {
-        const uint32_t agg = wave_last(wave_incl_scan(lane < NW ? s_red[lane] : 0u));
-        if (lane == 0) st_agent(&ring[(seq % kRing) * G + b], ((uint64_t)(epoch + i) << 32) | agg);
-      }
-      if (seq > 0) {
-        // complete the previous tensor: from the prefetched words if they were all there
-        const uint32_t tag = epoch + prev_item;
-        uint32_t lo = 0, al = 0;
-        bool ok = true, done = false;
-        if (pf.issued) {
-          done = pf.reduce(tag, b, lo, al);
+  // dense pass; the wave's escape records into its LDS staging in element order, the chunks' counts kept in lanes
+  uint32_t wave_count = 0, my_start = 0;   // lane it: escapes of the wave before its it-th chunk
+  for (uint32_t it0 = 0; it0 < mine; it0 += CPT) {
+    if (it0 > 0) fetch(it0, w);   // tiles of more than CPT chunks per wave (very large tensors)
 #pragma unroll
-          for (int w = 1; w < PFW; ++w) {
-            done = done && s_pf[w][0] != 0;
-            lo += s_pf[w][1];
-            al += s_pf[w][2];
-          }
-        }
-        if (!done)
-          ok = exchange(ring + ((seq - 1) % kRing) * G, tag, G + a.await_extra, b, lane, a.spin_ticks, s_misc[3] != 0, lo, al);
-        if (lane == 0) {
-          s_misc[0] = lo;
-          s_misc[1] = al;
-          s_misc[2] = ok ? 0u : 1u;
-          if (!ok) s_misc[3] = 1;
-        }
-        if (b == 0) {
-          const uint32_t err = err_before | (ok ? 0u : (uint32_t)SPLITZIP_STATUS_INTERNAL);
-          compress_write_trailer(Pprev, a.dec_of(prev_item), a.sizes + prev_item, al, err, lane);
-          if (!have && lane == 0) {
-            // this group is through.  The last group to get here closes the launch: by then every
-            // workgroup has read the header words, because each group completed an exchange.
-            const uint32_t through = __hip_atomic_fetch_add(&a.ws_hdr[3], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const uint32_t active = a.n_items < n_groups ? a.n_items : n_groups;
-            if (through + 1 == active) {
-              st_agent(&a.ws_hdr[3], 0u);
-              st_agent(&a.ws_hdr[2], 0u);
-              st_agent(&a.ws_hdr[0], epoch + a.n_items);
-            }
-          }
-        }
-      }
-    } else if (wave == 1 && have) {
-      scan_range(s_off[set], nb, lane);
-    } else if (wave == 2 && have) {
-      // Every dense pass of tensor i is over: its table is kept for its write-out, and the table of this group's
-      // next tensor takes its place -- every entry the escape mark, then the 16 codes by the lanes that own them.
-      // One wave does all of it: its LDS accesses are carried out in program order.
-      const bool more = i + n_groups < a.n_items;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        lut_old[seq & 1u][4 * lane + q] = lut_now[4 * lane + q];
-        if (more) lut_now[4 * lane + q] = 0x100u;
-      }
-      if (more && lane < 16) {
-        const uint32_t e = a.dec_of(i + n_groups)[lane] & ((256u >> F::kLutShift) - 1u);   // whatever a device codebook holds, the table is not left
-#pragma unroll
-        for (int q = 0; q < (1 << F::kLutShift); ++q) lut_now[(e << F::kLutShift) + q] = (uint16_t)lane;
-      }
+    for (int j = 0; j < CPT; ++j) {
+      const uint32_t it = it0 + j;
+      if (it >= mine) break;
+      const uint64_t cbase = (uint64_t)(r0 + w0 + it) * kChunk;
+      const LdsSink lds{stage_pk[wave], stage_val[wave], 0u, kTileStageCap};
+      if ((uint32_t)lane == it) my_start = wave_count;
+      wave_count += F::full(P, cbase) ? F::template process<true, true>(P, lut, park, cbase, lane, w[j], wave_count, lds)
+                                      : F::template process<false, true>(P, lut, park, cbase, lane, w[j], wave_count, lds);
     }
-    __syncthreads();
-    if (seq > 0 && s_misc[2] == 0) {
-      const uint32_t pset = (seq + 2u) % 3u;
-      const RangeLds Lp{stage_pk[pset][wave], stage_val[pset][wave], s_off[pset], s_wstart[pset], CAP};
-      write_out<NW, F>(Pprev, lut_old[(seq + 1u) & 1u], park, Lp, prev_r0, prev_nb, prev_count, s_misc[0],
-                       final_sink(Pprev, s_misc[1]), tid, wave, lane);
-    }
-    if (!have) break;
-    // no barrier here: the next tensor is staged in the third LDS set, and s_misc / s_red are only
-    // rewritten behind the next barrier, which every wave reaches after its write-out
-    Pprev = P;
-    prev_count = wave_count;
-    prev_r0 = r0;
-    prev_nb = nb;
-    prev_item = i;
   }
+  if (lane == 0) s_cnt[wave] = wave_count;
+  lds_barrier();
+  uint32_t before = 0, total = 0;
+  bool redo = false;
+#pragma unroll
+  for (int q = 0; q < NW; ++q) {
+    const uint32_t c = s_cnt[q];
+    before += q < wave ? c : 0u;
+    total += c;
+    redo = redo || c > kTileStageCap;
+  }
+  redo = redo || total > a.slot_cap;
+  // the tile's entries of the offset table, for now as offsets inside the tile
+  uint32_t* tab = reinterpret_cast<uint32_t*>(P.out + P.off_tab);
+  if ((uint32_t)lane < mine) tab[r0 + w0 + lane] = before + my_start;
+  if (!redo) {
+    uint32_t* slot = G.slots + (uint64_t)t * a.slot_cap + before;   // staged record i of this wave is the (before + i)-th of the tile
+    for (uint32_t i = lane; i < wave_count; i += 64) slot[i] = (uint32_t)stage_pk[wave][i] | ((uint32_t)stage_val[wave][i] << 16);
+  }
+  if (tid == 0) G.counts[t] = total | (redo ? kRedo : 0u);
 }
 
-// Last launch of a call that took several: M is known now.  Moves the staged escape values
-// behind the position array and writes the trailer.
-__global__ __launch_bounds__(kThreads) void compress_finish_kernel(const CompressArgs a) {
-  const uint32_t M = ld_agent(&a.ws_hdr[1]);
-  const uint64_t off_val = a.p.off_pos + a256(2ull * M);
-  const uint64_t room = a.p.capacity > off_val ? a.p.capacity - off_val : 0;
-  const uint64_t m = M < room ? M : room;
-  const uint64_t nvec = m / 16;
-  const u32x4* src = reinterpret_cast<const u32x4*>(a.val_stage);
-  u32x4* dst = reinterpret_cast<u32x4*>(a.p.out + off_val);
-  const uint64_t gtid = blockIdx.x * (uint64_t)kThreads + threadIdx.x, gsz = (uint64_t)gridDim.x * kThreads;
-  for (uint64_t i = gtid; i < nvec; i += gsz) dst[i] = src[i];
-  for (uint64_t i = nvec * 16 + gtid; i < m; i += gsz) a.p.out[off_val + i] = a.val_stage[i];
-  if (blockIdx.x == 0 && threadIdx.x < 64) {
-    uint32_t err = 0;
-    if (threadIdx.x == 0) {
-      err = ld_agent(&a.ws_hdr[2]);
-      st_agent(&a.ws_hdr[2], 0u);
+// sums of kSumGroup tile counts each, for tensors of more than kDirectTiles tiles (one wave per sum)
+__global__ __launch_bounds__(64) void tile_group_sum_kernel(const TileArgs a) {
+  const TileGeom G = tile_geom(a, blockIdx.y);
+  const uint32_t g = blockIdx.x, t = g * kSumGroup + threadIdx.x;
+  if (g * kSumGroup >= G.n_tiles) return;
+  const uint32_t sum = wave_last(wave_incl_scan(t < G.n_tiles ? G.counts[t] & ~kRedo : 0u));
+  if (threadIdx.x == 0) G.group_sums[g] = sum;
+}
+
+template <typename F>
+__global__ __launch_bounds__(kTileThreads) void compress_finish_kernel(const TileArgs a) {
+  constexpr int NW = kTileThreads / 64;
+  __shared__ uint16_t lut[256];
+  __shared__ u32x4 s_park[kTileThreads];
+  __shared__ uint32_t s_cnt[kGroup];       // the counts of the group's tiles, redo mark included
+  __shared__ uint32_t s_tp[kGroup + 1];    // escapes of the group's tiles before each tile
+  __shared__ uint32_t s_red[2 * NW];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t item = blockIdx.y, g = blockIdx.x;
+  const TileGeom G = tile_geom(a, item);
+  const Planes& P = G.P;
+  const uint32_t n_groups = (G.n_tiles + kGroup - 1) / kGroup;
+  if (g >= (n_groups ? n_groups : 1u)) return;   // a tensor without elements still gets its header
+  uint32_t* park = reinterpret_cast<uint32_t*>(&s_park[tid]);
+  uint32_t* tab = reinterpret_cast<uint32_t*>(P.out + P.off_tab);
+  const uint32_t t0 = g * kGroup;
+
+  // Everything whose address does not depend on the counts is fetched at once: the counts themselves, the
+  // group's table entries (one per thread or a few) and the first kSlotAhead records of every tile's slot.
+  const uint32_t c0 = t0 << a.tile_shift;
+  const uint32_t entries = P.n_chunks > c0 ? (P.n_chunks - c0 < (kGroup << a.tile_shift) ? P.n_chunks - c0 : (kGroup << a.tile_shift)) : 0u;
+  const uint32_t my_entry = (uint32_t)tid < entries ? tab[c0 + tid] : 0u;
+  const uint32_t sl = (uint32_t)tid / kSlotAhead, sj = (uint32_t)tid % kSlotAhead;   // tile of the group, record of the tile
+  uint32_t rec_ahead = 0;
+  if (t0 + sl < G.n_tiles && sj < a.slot_cap) rec_ahead = G.slots[(uint64_t)(t0 + sl) * a.slot_cap + sj];
+  uint32_t before = 0, all = 0;
+  if (a.use_group_sums) {
+    const uint32_t n_sums = (G.n_tiles + kSumGroup - 1) / kSumGroup, whole = t0 / kSumGroup;   // sums that lie before the group entirely
+    for (uint32_t i = tid; i < n_sums; i += kTileThreads) {
+      const uint32_t c = G.group_sums[i];
+      all += c;
+      before += i < whole ? c : 0u;
     }
-    compress_write_trailer(a.p, a.d_cb ? a.d_cb->dec : a.dec, a.sizes, M, err, threadIdx.x);
+    for (uint32_t i = whole * kSumGroup + tid; i < t0; i += kTileThreads) before += G.counts[i] & ~kRedo;
+  } else {
+    // four counts per load, four loads per thread on their way at a time (the counts start 256-byte aligned and
+    // the sums behind them pad the last vector)
+    const u32x4* cv = reinterpret_cast<const u32x4*>(G.counts);
+    const uint32_t nvec = (G.n_tiles + 3) / 4;
+    for (uint32_t v0 = 0; v0 < nvec; v0 += 4 * kTileThreads) {
+      u32x4 v[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t idx = v0 + q * kTileThreads + tid;
+        v[q] = idx < nvec ? cv[idx] : u32x4{0u, 0u, 0u, 0u};
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t e = 4 * (v0 + q * kTileThreads + tid);
+        const uint32_t c[4] = {v[q].x, v[q].y, v[q].z, v[q].w};
+#pragma unroll
+        for (int z = 0; z < 4; ++z) {
+          const uint32_t cz = e + z < G.n_tiles ? c[z] & ~kRedo : 0u;
+          all += cz;
+          before += e + z < t0 ? cz : 0u;
+        }
+      }
+    }
   }
+  before = wave_last(wave_incl_scan(before));
+  all = wave_last(wave_incl_scan(all));
+  if (lane == 0) {
+    s_red[wave] = before;
+    s_red[NW + wave] = all;
+  }
+  if (wave == 0) {
+    const uint32_t c = (uint32_t)lane < kGroup && t0 + lane < G.n_tiles ? G.counts[t0 + lane] : 0u;
+    const uint32_t incl = wave_incl_scan(c & ~kRedo);
+    if ((uint32_t)lane < kGroup) {
+      s_cnt[lane] = c;
+      s_tp[lane] = incl - (c & ~kRedo);
+    }
+    if (lane == 63) s_tp[kGroup] = incl;
+  }
+  lut[tid] = encode_entry(a.dec_of(item), (uint32_t)tid >> F::kLutShift);
+  __syncthreads();
+  uint32_t first = 0, M = 0;
+#pragma unroll
+  for (int q = 0; q < NW; ++q) {
+    first += s_red[q];
+    M += s_red[NW + q];
+  }
+  const uint64_t off_val = P.off_pos + a256(2ull * M);
+  FinalSink fin;
+  fin.pos = reinterpret_cast<uint16_t*>(P.out + P.off_pos);
+  fin.pos_room = P.capacity > P.off_pos ? (P.capacity - P.off_pos) / 2 : 0;
+  fin.val = P.out + off_val;
+  fin.val_room = P.capacity > off_val ? P.capacity - off_val : 0;
+
+  // tiles whose records are not in their slots: once more from the words, by the offsets inside the tile that the
+  // first pass left in the table
+  bool any_redo = false;
+  for (uint32_t l = 0; l < kGroup; ++l) {
+    if (!(s_cnt[l] & kRedo)) continue;   // uniform: s_cnt is the same for every thread
+    any_redo = true;
+    const uint32_t r0 = (t0 + l) << a.tile_shift;
+    const uint32_t nb = P.n_chunks - r0 < G.tile_chunks ? P.n_chunks - r0 : G.tile_chunks;
+    typename F::Regs w;
+    for (uint32_t k = wave; k < nb; k += NW) {
+      const uint64_t cbase = (uint64_t)(r0 + k) * kChunk;
+      const uint32_t base = first + s_tp[l] + tab[r0 + k];
+      const uint8_t* cptr = chunk_at<F::ES>(P.w, cbase, P.w.table ? page_of_chunk(P.w, r0 + k) : 0u);
+      if (F::full(P, cbase)) {
+        F::template load<true>(P, cptr, cbase, lane, w);
+        F::template process<true, false>(P, lut, park, cbase, lane, w, base, fin);
+      } else {
+        F::template load<false>(P, cptr, cbase, lane, w);
+        F::template process<false, false>(P, lut, park, cbase, lane, w, base, fin);
+      }
+    }
+  }
+  if (any_redo) __syncthreads();   // the table has been read by whoever needed its entries as offsets inside a tile
+  // the table entries: what lies before the tile added to the offsets inside the tile
+  if ((uint32_t)tid < entries) tab[c0 + tid] = my_entry + first + s_tp[(uint32_t)tid >> a.tile_shift];
+  for (uint32_t e = tid + kTileThreads; e < entries; e += kTileThreads) tab[c0 + e] += first + s_tp[e >> a.tile_shift];
+  // the records fetched ahead
+  const uint32_t cl = s_cnt[sl];
+  if (!(cl & kRedo) && sj < cl) fin.put(first + s_tp[sl] + sj, rec_ahead & 0xffffu, rec_ahead >> 16);
+  // the rest of the slots of tiles with more records than that
+  for (uint32_t l = 0; l < kGroup; ++l) {
+    const uint32_t c = s_cnt[l];
+    if ((c & kRedo) || c <= kSlotAhead) continue;
+    const uint32_t* slot = G.slots + (uint64_t)(t0 + l) * a.slot_cap;
+    for (uint32_t j = kSlotAhead + tid; j < c; j += kTileThreads) {
+      const uint32_t rec = slot[j];
+      fin.put(first + s_tp[l] + j, rec & 0xffffu, rec >> 16);
+    }
+  }
+  if (g == 0 && wave == 0) compress_write_trailer(P, a.dec_of(item), a.sizes + item, M, 0u, lane);
 }
 
 #endif  // SPLITZIP_COMPRESS_HPP

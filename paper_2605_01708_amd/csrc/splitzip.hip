@@ -20,6 +20,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <atomic>
 #include <mutex>
 #include <type_traits>
 
@@ -40,13 +41,6 @@ namespace {
 bool dtype_ok(int dtype) { return dtype == SPLITZIP_BF16 || dtype == SPLITZIP_FP8_E5M2; }
 unsigned exp_values(int dtype) { return dtype == SPLITZIP_BF16 ? 256u : 32u; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-
-int env_int(const char* name, int dflt) {
-  const char* s = getenv(name);
-  if (!s || !*s) return dflt;
-  const int v = atoi(s);
-  return v > 0 ? v : dflt;
-}
 
 int cu_count() {
   static int cached[64] = {0};
@@ -71,9 +65,9 @@ uint32_t pick_cpw(uint64_t n_chunks, uint32_t most, uint32_t want_tiles_per_cu) 
 // Chunks per wave of a decompress launch over n_chunks chunks in all.  Measured on 64 MiB BF16 /
 // 32 MiB E5M2 tensors: BF16 wants one chunk per wave for a single tensor (32 768 chunks) and two for
 // a whole cache in one launch; E5M2 wants four and eight.
-uint32_t pick_decompress_cpw(uint64_t n_chunks, int dtype, int tiles_per_cu_env) {
+uint32_t pick_decompress_cpw(uint64_t n_chunks, int dtype) {
   const uint32_t most = dtype == SPLITZIP_BF16 ? 2 : 8;
-  const uint32_t want = tiles_per_cu_env ? (uint32_t)tiles_per_cu_env : (dtype == SPLITZIP_BF16 ? 32u : 8u);
+  const uint32_t want = dtype == SPLITZIP_BF16 ? 32u : 8u;
   return pick_cpw(n_chunks, most, want);
 }
 
@@ -93,43 +87,14 @@ bool codebook_ok(const splitzip_codebook* cb, int dtype) {
   return members == 16;
 }
 
-template <int T>
-void launch_compress(unsigned grid, hipStream_t stream, const CompressArgs& a) {
-  if (a.p.dtype == SPLITZIP_BF16) hipLaunchKernelGGL((compress_kernel<T, Bf16>), dim3(grid), dim3(T), 0, stream, a);
-  else hipLaunchKernelGGL((compress_kernel<T, E5m2>), dim3(grid), dim3(T), 0, stream, a);
-}
-
-// workgroups of T threads that can be resident on the current device at the same time
-template <int T>
-uint32_t resident_workgroups() {
-  static uint32_t cached[64] = {0};
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
-  if (!cached[dev]) {
-    int per_cu = 0;
-    // both formats' kernels use the same LDS; the BF16 one needs more registers
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, compress_kernel<T, Bf16>, T, 0) != hipSuccess || per_cu <= 0)
-      return 0;
-    cached[dev] = (uint32_t)per_cu * (uint32_t)cu_count();
-  }
-  return cached[dev];
-}
-
-// the same for the batch kernel (more LDS)
-uint32_t resident_workgroups_batch(int dtype) {
-  static uint32_t cached[2][64] = {{0}};
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
-  const int f = dtype == SPLITZIP_BF16 ? 0 : 1;
-  if (!cached[f][dev]) {
-    int per_cu = 0;
-    const hipError_t rc = f == 0 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, compress_batch_kernel<Bf16::kBatchThreads, Bf16>, Bf16::kBatchThreads, 0)
-                                 : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, compress_batch_kernel<E5m2::kBatchThreads, E5m2>, E5m2::kBatchThreads, 0);
-    if (rc != hipSuccess || per_cu <= 0) return 0;
-    cached[f][dev] = (uint32_t)per_cu * (uint32_t)cu_count();
-  }
-  return cached[f][dev];
-}
+// What the tests of the rarely taken paths turn: a staging area and a status area smaller than the workspace has
+// (tiles whose records do not fit their slots; batches that take several launches).  Set through
+// splitzip_internal_test_hooks (exported, not declared in splitzip.h); zero in normal use.
+struct TestHooks {
+  std::atomic<uint64_t> stage_bytes{0};
+  std::atomic<uint64_t> status_bytes{0};
+};
+TestHooks g_hooks;
 
 // ---------------------------------------------------------------------------
 // format variants: host side
@@ -464,16 +429,22 @@ size_t splitzip_compress_bound(uint64_t n_elems, int dtype) { return splitzip_to
 
 size_t splitzip_workspace_bytes(uint64_t n_elems, int dtype) {
   if (!dtype_ok(dtype) || n_elems >> 32) return 0;
-  return (size_t)(kWsHeaderBytes + kWsTableBytes + a256(n_elems));
+  return (size_t)(kWsHeaderBytes + kStatusBytes + kStageFloor + a256(n_elems));
 }
 
 int splitzip_workspace_init(void* d_workspace, size_t workspace_bytes, void* stream) {
-  if (!d_workspace || !aligned16(d_workspace) || workspace_bytes < kWsHeaderBytes + kWsTableBytes)
+  if (!d_workspace || !aligned16(d_workspace) || workspace_bytes < kWsHeaderBytes + kStatusBytes + kStageFloor)
     return SPLITZIP_ERR_INVALID_ARG;
-  // header and exchange words; the epoch starts at 1 so that a cleared word never looks published
-  hipLaunchKernelGGL(workspace_init_kernel, dim3(8), dim3(256), 0, static_cast<hipStream_t>(stream),
-                     static_cast<uint32_t*>(d_workspace), (uint32_t)((kWsHeaderBytes + kWsTableBytes) / 4));
+  // No word of a workspace needs a defined value before a call; the header is cleared all the same, so that what
+  // a later version of the library may keep there starts from zero.
+  hipLaunchKernelGGL(workspace_init_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream),
+                     static_cast<uint32_t*>(d_workspace), (uint32_t)(kWsHeaderBytes / 4));
   return hipGetLastError() == hipSuccess ? SPLITZIP_OK : SPLITZIP_ERR_HIP;
+}
+
+void splitzip_internal_test_hooks(uint64_t stage_bytes, uint64_t status_bytes) {
+  g_hooks.stage_bytes = stage_bytes;
+  g_hooks.status_bytes = status_bytes;
 }
 
 }  // extern "C"
@@ -505,9 +476,10 @@ bool paged_words(const splitzip_paged* pg, uint64_t n_elems, int dtype, Words* w
   return true;
 }
 
-// ---- the exchange words of splitzip_compress_noalloc: one copy per GPU, alive until the process ends ----
-// Word 0 is the epoch and starts at 1, everything else at 0: the state splitzip_workspace_init leaves behind.
-static __device__ __align__(256) uint32_t scratch[(kWsHeaderBytes + kWsTableBytes) / 4] = {1u};
+// ---- the workspace of splitzip_compress_noalloc: one copy per GPU, alive until the process ends ----
+// Header, status area and staging area as in a caller's workspace, only smaller.
+constexpr uint64_t kScratchStatusBytes = 256u << 10, kScratchStageBytes = 768u << 10;
+static __device__ __align__(256) uint32_t scratch[(kWsHeaderBytes + kScratchStatusBytes + kScratchStageBytes) / 4];
 
 // The array's address on the current device (each GPU holds its own copy at its own address), looked up once per
 // device with that device current; null if the runtime refuses.  `scratch` itself is a host-side stand-in and is
@@ -526,83 +498,144 @@ void* scratch_on_current_device() {
   return ptr[dev];
 }
 
-// splitzip_compress with the codebook either on the host (cb) or in device memory (d_cb); the words contiguous or paged
-int compress_impl(const Words& in, uint64_t n_elems, int dtype, const splitzip_codebook* cb, const splitzip_codebook* d_cb,
-                  void* d_out, size_t out_capacity, void* d_workspace, size_t workspace_bytes, splitzip_sizes* d_sizes,
-                  void* stream, bool one_launch = false) {
-  const void* d_in = in.base;
-  if (!dtype_ok(dtype) || !d_out || !d_workspace || !d_sizes || (n_elems && !d_in)) return SPLITZIP_ERR_INVALID_ARG;
-  if (!aligned16(d_in) || !aligned16(d_out) || !aligned16(d_workspace) ||
-      (reinterpret_cast<uintptr_t>(d_sizes) & 7u))
-    return SPLITZIP_ERR_INVALID_ARG;
-  if (d_cb ? (reinterpret_cast<uintptr_t>(d_cb) & 3u) != 0 : !codebook_ok(cb, dtype)) return SPLITZIP_ERR_INVALID_ARG;
-  if (n_elems >> 32) return SPLITZIP_ERR_UNSUPPORTED;
-  if (out_capacity < splitzip_fixed_bytes(n_elems, dtype)) return SPLITZIP_ERR_CAPACITY;
-  // one_launch: the workspace holds the exchange words only (no room to stage the escape values of a call that takes several launches)
-  if (workspace_bytes < (one_launch ? kWsHeaderBytes + kWsTableBytes : splitzip_workspace_bytes(n_elems, dtype))) return SPLITZIP_ERR_CAPACITY;
+// a workspace as the compress calls see it: header, then the status words, then the staging of escape values
+struct WsView {
+  uint8_t* base;
+  uint64_t status_bytes, stage_bytes;
+};
 
-  const Layout L = make_layout(n_elems, dtype);
-  CompressArgs a;
-  memset(&a, 0, sizeof a);
-  a.p = make_planes(in, d_out, n_elems, out_capacity, dtype);
-  uint8_t* ws = static_cast<uint8_t*>(d_workspace);
-  a.ws_hdr = reinterpret_cast<uint32_t*>(ws);
-  a.state = reinterpret_cast<uint64_t*>(ws + kWsHeaderBytes);
-  a.val_stage = ws + kWsHeaderBytes + kWsTableBytes;
-  a.sizes = d_sizes;
-  a.d_cb = d_cb;
-  if (!d_cb) {
-    memcpy(a.dec, cb->dec, 16);
-    for (unsigned v = 0; v < 256; ++v) a.lut[v] = cb->member[v] ? cb->enc[v] : 0x100u;   // indexed by the exponent
+// the view of a workspace: a caller's (d_workspace non-null: sized by splitzip_workspace_bytes for its largest tensor,
+// n_max elements) or the library's own array on the current device; an error code if it is too small or not to be had
+int workspace_view(void* d_workspace, size_t workspace_bytes, uint64_t n_max, int dtype, WsView* v) {
+  if (d_workspace) {
+    if (workspace_bytes < splitzip_workspace_bytes(n_max, dtype)) return SPLITZIP_ERR_CAPACITY;
+    v->base = static_cast<uint8_t*>(d_workspace);
+    v->status_bytes = kStatusBytes;
+    v->stage_bytes = (workspace_bytes - kWsHeaderBytes - kStatusBytes) & ~(uint64_t)255u;
+  } else {
+    v->base = static_cast<uint8_t*>(scratch_on_current_device());
+    if (!v->base) return SPLITZIP_ERR_HIP;
+    v->status_bytes = kScratchStatusBytes;
+    v->stage_bytes = kScratchStageBytes;
   }
-  static const int spin_env = env_int("SPLITZIP_SPIN_TICKS", 0);
-  a.spin_ticks = spin_env ? (uint64_t)spin_env : kSpinTicks;
+  // tests of the paths that small areas force
+  const uint64_t hs = g_hooks.status_bytes, hg = g_hooks.stage_bytes;
+  if (hs && hs < v->status_bytes) v->status_bytes = hs;
+  if (hg && hg < v->stage_bytes) v->stage_bytes = hg;
+  return SPLITZIP_OK;
+}
 
-  // the grid: every workgroup resident at once, not more workgroups than tiles
-  // One workgroup per CU; BF16 with 512 threads, E5M2 with 1024 (swept on 64 and 32 MiB tensors: 256, 512 and 1024
-  // threads, one to four workgroups per CU; BF16 does 1.5 % better with eight waves per CU than with sixteen).
-  static const int threads_env = env_int("SPLITZIP_COMPRESS_THREADS", 0);
-  static const int wgs_per_cu_env = env_int("SPLITZIP_COMPRESS_WGS_PER_CU", 0);
-  const int threads = threads_env ? threads_env : (dtype == SPLITZIP_BF16 ? 512 : 1024);
-  const int wgs_per_cu = wgs_per_cu_env > 0 ? wgs_per_cu_env : 1;
-  const int T = threads == 256 || threads == 512 ? threads : 1024;
-  const uint32_t nw = (uint32_t)T / 64;
-  uint32_t resident = T == 256 ? resident_workgroups<256>() : T == 512 ? resident_workgroups<512>() : resident_workgroups<1024>();
-  if (!resident) return SPLITZIP_ERR_HIP;
-  uint32_t w_max = (uint32_t)cu_count() * (uint32_t)wgs_per_cu;
-  if (w_max > resident) w_max = resident;
-  static const int max_wgs = env_int("SPLITZIP_COMPRESS_MAX_WGS", 0);   // small grids, to exercise calls of several launches
-  if (max_wgs && w_max > (uint32_t)max_wgs) w_max = (uint32_t)max_wgs;
-  if (w_max > kMaxWorkgroups) w_max = kMaxWorkgroups;
-  const uint64_t seg_cap = (uint64_t)w_max * kMaxRange;   // chunks one launch can take
+uint64_t chunks_of(uint64_t n) { return (n + kChunk - 1) / kChunk; }
+uint64_t tiles_of(uint64_t chunks, uint32_t cpt) { return (chunks + 4ull * cpt - 1) / (4ull * cpt); }
+// bytes of the status area a tensor of `tiles` tiles takes: a count per tile, a sum per group of tiles
+uint64_t status_need(uint64_t tiles) { return a256(4 * tiles + 4 * ((tiles + kSumGroup - 1) / kSumGroup)); }
+
+// chunks per wave and tile for a tensor of `chunks` chunks: `at_least`, doubled until the tensor's counts fit
+// `status_bytes`; 0 if nothing fits
+uint32_t pick_cpt(uint64_t chunks, uint32_t at_least, uint64_t status_bytes) {
+  for (uint32_t cpt = at_least; cpt <= kMaxRange / 4; cpt *= 2)
+    if (status_need(tiles_of(chunks, cpt)) <= status_bytes) return cpt;
+  return 0;
+}
+
+// The compress calls, all of them: n_items tensors (a host list), each under its own codebook -- the items' own (host)
+// or d_cbs[k] (device memory).  paging: table and page geometry shared by all items, or contiguous tensors (table null).
+// d_workspace: the caller's workspace, or null with own_scratch for the library's own array.
+int compress_launch(const splitzip_item* items, uint32_t n_items, int dtype, const Words& paging, uint64_t paged_room,
+                   const splitzip_codebook* d_cbs, void* d_workspace, size_t workspace_bytes, bool own_scratch,
+                   splitzip_sizes* d_sizes, void* stream) {
+  if (!dtype_ok(dtype) || (n_items && (!items || !d_sizes)) || (own_scratch ? d_workspace != nullptr : !d_workspace) ||
+      !aligned16(d_workspace) || (reinterpret_cast<uintptr_t>(d_sizes) & 7u) || (reinterpret_cast<uintptr_t>(d_cbs) & 3u))
+    return SPLITZIP_ERR_INVALID_ARG;
+  uint64_t n_max = 0;
+  for (uint32_t i = 0; i < n_items; ++i) {
+    const splitzip_item& it = items[i];
+    if (!it.d_out || (it.n_elems && !it.d_in) || !aligned16(it.d_in) || !aligned16(it.d_out) || (!d_cbs && !codebook_ok(it.cb, dtype)))
+      return SPLITZIP_ERR_INVALID_ARG;
+    if (it.n_elems >> 32) return SPLITZIP_ERR_UNSUPPORTED;
+    if (paging.table && it.n_elems > paged_room) return SPLITZIP_ERR_INVALID_ARG;   // the table does not cover the tensor
+    if (it.out_capacity < splitzip_fixed_bytes(it.n_elems, dtype)) return SPLITZIP_ERR_CAPACITY;
+    if (it.n_elems > n_max) n_max = it.n_elems;
+  }
+  WsView ws;
+  const int rc = workspace_view(d_workspace, workspace_bytes, n_max, dtype, &ws);
+  if (rc != SPLITZIP_OK) return rc;
+  if (n_items == 0) return SPLITZIP_OK;
+  if (!pick_cpt(chunks_of(n_max), 1, ws.status_bytes)) return SPLITZIP_ERR_CAPACITY;
+  const uint32_t base_cpt = dtype == SPLITZIP_BF16 ? Bf16::kCpt : E5m2::kCpt;
   const hipStream_t st = static_cast<hipStream_t>(stream);
-  static const int missing = env_int("SPLITZIP_TEST_AWAIT_EXTRA_WGS", 0);   // error-path tests only
 
-  uint64_t done = 0;
-  const bool several = L.n_chunks > seg_cap;
-  if (several && one_launch) return SPLITZIP_ERR_UNSUPPORTED;
-  do {
-    const uint64_t left = L.n_chunks - done;
-    const uint32_t seg = (uint32_t)(left < seg_cap ? left : seg_cap);
-    a.seg_chunk0 = (uint32_t)done;
-    a.seg_chunks = seg;
-    a.flags = (done == 0 ? kSegFirst : 0u) | (done + seg == L.n_chunks ? kSegLast : 0u);
-    uint32_t grid = (seg + nw - 1) / nw;    // at least one chunk per wave where the tensor allows
-    if (grid > w_max) grid = w_max;
-    if (grid < 1) grid = 1;
-    a.expect_wgs = grid + (uint32_t)missing;
-    if (a.expect_wgs > kMaxWorkgroups) return SPLITZIP_ERR_INVALID_ARG;
-    if (T == 256) launch_compress<256>(grid, st, a);
-    else if (T == 512) launch_compress<512>(grid, st, a);
-    else launch_compress<1024>(grid, st, a);
+  uint32_t i = 0;
+  while (i < n_items) {
+    // one pair of launches: as many of the next tensors (kBatchMax at most) as find room for their counts in the
+    // status area; all of them share the tile size of the one that needs the largest
+    uint32_t k = 0, cpt = base_cpt;
+    for (; i + k < n_items && k < kBatchMax; ++k) {
+      const uint32_t need = pick_cpt(chunks_of(items[i + k].n_elems), cpt, ws.status_bytes);
+      uint64_t total = 0;
+      for (uint32_t q = 0; q <= k && need; ++q) total += status_need(tiles_of(chunks_of(items[i + q].n_elems), need));
+      if (!need || total > ws.status_bytes) break;
+      cpt = need;
+    }
+    if (k == 0) return SPLITZIP_ERR_CAPACITY;   // cannot happen: every tensor fits alone
+    TileArgs a;
+    memset(&a, 0, sizeof a);
+    uint64_t off = 0, tiles_max = 0;
+    for (uint32_t q = 0; q < k; ++q) {
+      const splitzip_item& it = items[i + q];
+      if (!d_cbs) memcpy(a.dec[q], it.cb->dec, 16);   // codebook_ok has shown that dec and the encode table describe the same bijection
+      a.item[q].in = static_cast<const uint8_t*>(it.d_in);
+      a.item[q].out = static_cast<uint8_t*>(it.d_out);
+      a.item[q].n = it.n_elems;
+      a.item[q].capacity = it.out_capacity;
+      const uint64_t tiles = tiles_of(chunks_of(it.n_elems), cpt);
+      a.status_off[q] = (uint32_t)off;
+      off += status_need(tiles);
+      if (tiles > tiles_max) tiles_max = tiles;
+    }
+    a.sizes = d_sizes + i;
+    a.d_cbs = d_cbs ? d_cbs + i : nullptr;
+    a.status = ws.base + kWsHeaderBytes;
+    a.stage = ws.base + kWsHeaderBytes + ws.status_bytes;
+    a.stage_cap = (ws.stage_bytes / k) & ~(uint64_t)255u;
+    a.n_items = k;
+    a.dtype = (uint32_t)dtype;
+    a.cpt = cpt;
+    a.tile_shift = 2u + (uint32_t)__builtin_ctz(cpt);
+    {
+      const uint64_t per_tile = tiles_max ? a.stage_cap / 4 / tiles_max : 0;
+      a.slot_cap = (uint32_t)(per_tile < kSlotCapMost ? per_tile : kSlotCapMost);
+    }
+    a.use_group_sums = tiles_max > kDirectTiles ? 1u : 0u;
+    a.paging = paging;
+    const unsigned groups_max = (unsigned)((tiles_max + kGroup - 1) / kGroup), sums_max = (unsigned)((tiles_max + kSumGroup - 1) / kSumGroup);
+    if (tiles_max) {
+      const dim3 grid((unsigned)tiles_max, k);   // one workgroup per tile, started by the hardware in the tiles' order
+      if (dtype == SPLITZIP_BF16) hipLaunchKernelGGL((compress_tile_kernel<Bf16, Bf16::kCpt>), grid, dim3(kTileThreads), Bf16::kTileLdsPad, st, a);
+      else hipLaunchKernelGGL((compress_tile_kernel<E5m2, E5m2::kCpt>), grid, dim3(kTileThreads), E5m2::kTileLdsPad, st, a);
+      if (a.use_group_sums) hipLaunchKernelGGL(tile_group_sum_kernel, dim3(sums_max, k), dim3(64), 0, st, a);
+    }
+    const dim3 fgrid(groups_max ? groups_max : 1u, k);
+    if (dtype == SPLITZIP_BF16) hipLaunchKernelGGL(compress_finish_kernel<Bf16>, fgrid, dim3(kTileThreads), 0, st, a);
+    else hipLaunchKernelGGL(compress_finish_kernel<E5m2>, fgrid, dim3(kTileThreads), 0, st, a);
     if (hipGetLastError() != hipSuccess) return SPLITZIP_ERR_HIP;
-    done += seg;
-  } while (done < L.n_chunks);
-  if (several) {
-    hipLaunchKernelGGL(compress_finish_kernel, dim3(64), dim3(kThreads), 0, st, a);
-    if (hipGetLastError() != hipSuccess) return SPLITZIP_ERR_HIP;
+    i += k;
   }
   return SPLITZIP_OK;
+}
+
+// one tensor through compress_chain: the codebook on the host (cb) or in device memory (d_cb)
+int compress_one(const Words& in, uint64_t n_elems, int dtype, const splitzip_codebook* cb, const splitzip_codebook* d_cb,
+                 void* d_out, size_t out_capacity, void* d_workspace, size_t workspace_bytes, bool own_scratch,
+                 splitzip_sizes* d_sizes, void* stream) {
+  if (!d_sizes || (!cb && !d_cb)) return SPLITZIP_ERR_INVALID_ARG;
+  splitzip_item it;
+  it.d_in = in.base;
+  it.n_elems = n_elems;
+  it.d_out = d_out;
+  it.out_capacity = out_capacity;
+  it.cb = cb;
+  return compress_launch(&it, 1, dtype, in, in.table ? n_elems : 0, d_cb, d_workspace, workspace_bytes, own_scratch, d_sizes, stream);
 }
 
 // splitzip_decompress with the codebook either on the host (cb) or in device memory (d_cb); the words contiguous or paged
@@ -626,12 +659,8 @@ int decompress_impl(const void* d_comp, size_t comp_bytes, uint64_t n_elems, int
   a.sizes = d_sizes;
   a.off_tab = L.off_tab; a.off_sm = L.off_sm; a.off_code = L.off_code; a.off_pos = L.off_pos;
   a.sm_bytes = L.sm_bytes; a.code_bytes = L.code_bytes;
-  static const int cpw_env = env_int("SPLITZIP_DECOMPRESS_CPW", 0);
-  static const int tiles_per_cu = env_int("SPLITZIP_DECOMPRESS_TILES_PER_CU", 0);
-  a.cpw = cpw_env ? (uint32_t)cpw_env : pick_decompress_cpw(L.n_chunks, dtype, tiles_per_cu);
-  if (a.cpw > kMaxCpw) a.cpw = kMaxCpw;
-  static const int reg_patch = env_int("SPLITZIP_DECOMPRESS_REG_PATCH", (int)kRegPatchDefault);
-  a.reg_patch_max = (uint32_t)reg_patch;
+  a.cpw = pick_decompress_cpw(L.n_chunks, dtype);
+  a.reg_patch_max = kRegPatchDefault;
   a.n_chunks = (uint32_t)L.n_chunks;
   a.n_tiles = (uint32_t)((L.n_chunks + (uint64_t)kWaves * a.cpw - 1) / (kWaves * a.cpw));
   a.dtype = (uint32_t)dtype;
@@ -651,22 +680,15 @@ extern "C" {
 int splitzip_compress(const void* d_in, uint64_t n_elems, int dtype, const splitzip_codebook* cb,
                       void* d_out, size_t out_capacity, void* d_workspace, size_t workspace_bytes,
                       splitzip_sizes* d_sizes, void* stream) {
-  return compress_impl(contiguous_words(d_in), n_elems, dtype, cb, nullptr, d_out, out_capacity, d_workspace, workspace_bytes, d_sizes, stream);
+  return compress_one(contiguous_words(d_in), n_elems, dtype, cb, nullptr, d_out, out_capacity, d_workspace, workspace_bytes, false, d_sizes, stream);
 }
 
-uint64_t splitzip_noalloc_max_elems(void) {
-  const uint64_t wgs = (uint64_t)cu_count() < kMaxWorkgroups ? (uint64_t)cu_count() : kMaxWorkgroups;
-  return wgs * kMaxRange * kChunk;   // what one launch takes: no staging of escape values is needed below that
-}
+uint64_t splitzip_noalloc_max_elems(void) { return 1ull << 30; }
 
 int splitzip_compress_noalloc(const void* d_in, uint64_t n_elems, int dtype, const splitzip_codebook* cb, void* d_out,
                               size_t out_capacity, splitzip_sizes* d_sizes, void* stream) {
   if (n_elems > splitzip_noalloc_max_elems()) return SPLITZIP_ERR_UNSUPPORTED;
-  void* ws = scratch_on_current_device();
-  if (!ws) return SPLITZIP_ERR_HIP;
-  // the exchange words are all a call of one launch needs; one that would take several is turned away by the size check
-  return compress_impl(contiguous_words(d_in), n_elems, dtype, cb, nullptr, d_out, out_capacity, ws, sizeof(scratch),
-                       d_sizes, stream, true);
+  return compress_one(contiguous_words(d_in), n_elems, dtype, cb, nullptr, d_out, out_capacity, nullptr, 0, true, d_sizes, stream);
 }
 
 int splitzip_decompress(const void* d_comp, size_t comp_bytes, uint64_t n_elems, int dtype,
@@ -687,7 +709,7 @@ int splitzip_compress_paged(const splitzip_paged* src, uint64_t n_elems, int dty
                             splitzip_sizes* d_sizes, void* stream) {
   Words w;
   if (!dtype_ok(dtype) || !paged_words(src, n_elems, dtype, &w)) return SPLITZIP_ERR_INVALID_ARG;
-  return compress_impl(w, n_elems, dtype, cb, nullptr, d_out, out_capacity, d_workspace, workspace_bytes, d_sizes, stream);
+  return compress_one(w, n_elems, dtype, cb, nullptr, d_out, out_capacity, d_workspace, workspace_bytes, false, d_sizes, stream);
 }
 
 int splitzip_decompress_paged(const void* d_comp, size_t comp_bytes, uint64_t n_elems, int dtype,
@@ -702,7 +724,7 @@ int splitzip_compress_dcb(const void* d_in, uint64_t n_elems, int dtype, const s
                           void* d_out, size_t out_capacity, void* d_workspace, size_t workspace_bytes,
                           splitzip_sizes* d_sizes, void* stream) {
   if (!d_cb) return SPLITZIP_ERR_INVALID_ARG;
-  return compress_impl(contiguous_words(d_in), n_elems, dtype, nullptr, d_cb, d_out, out_capacity, d_workspace, workspace_bytes, d_sizes, stream);
+  return compress_one(contiguous_words(d_in), n_elems, dtype, nullptr, d_cb, d_out, out_capacity, d_workspace, workspace_bytes, false, d_sizes, stream);
 }
 
 int splitzip_decompress_dcb(const void* d_comp, size_t comp_bytes, uint64_t n_elems, int dtype,
@@ -724,103 +746,8 @@ int splitzip_decompress_own(const void* d_comp, size_t comp_bytes, uint64_t n_el
 
 namespace {
 
-// the batch calls; paging: table and page geometry shared by all items, or contiguous tensors (table null)
+// the batch decompress calls; paging: table and page geometry shared by all items, or contiguous tensors (table null)
 // d_cbs (nullable): n_items codebooks in device memory, used instead of the items' own
-int compress_batch_impl(const splitzip_item* items, uint32_t n_items, int dtype, const Words& paging, uint64_t paged_room,
-                        const splitzip_codebook* d_cbs, void* d_workspace, size_t workspace_bytes, splitzip_sizes* d_sizes,
-                        void* stream) {
-  if (!dtype_ok(dtype) || (n_items && (!items || !d_sizes)) || !d_workspace || !aligned16(d_workspace) ||
-      (reinterpret_cast<uintptr_t>(d_sizes) & 7u) || (reinterpret_cast<uintptr_t>(d_cbs) & 3u))
-    return SPLITZIP_ERR_INVALID_ARG;
-  uint64_t n_max = 0;
-  for (uint32_t i = 0; i < n_items; ++i) {
-    const splitzip_item& it = items[i];
-    if (!it.d_out || (it.n_elems && !it.d_in) || !aligned16(it.d_in) || !aligned16(it.d_out) || (!d_cbs && !codebook_ok(it.cb, dtype)))
-      return SPLITZIP_ERR_INVALID_ARG;
-    if (it.n_elems >> 32) return SPLITZIP_ERR_UNSUPPORTED;
-    if (paging.table && it.n_elems > paged_room) return SPLITZIP_ERR_INVALID_ARG;   // the table does not cover the tensor
-    if (it.out_capacity < splitzip_fixed_bytes(it.n_elems, dtype)) return SPLITZIP_ERR_CAPACITY;
-    if (it.n_elems > n_max) n_max = it.n_elems;
-  }
-  if (workspace_bytes < splitzip_workspace_bytes(n_max, dtype)) return SPLITZIP_ERR_CAPACITY;
-  if (n_items == 0) return SPLITZIP_OK;
-
-  static const int wgs_per_cu_env = env_int("SPLITZIP_COMPRESS_WGS_PER_CU", 0);   // 0: what the kernel of the dtype is built for
-  const int wgs_per_cu = wgs_per_cu_env > 0 ? wgs_per_cu_env : (dtype == SPLITZIP_BF16 ? Bf16::kBatchWgsPerCu : E5m2::kBatchWgsPerCu);
-  const uint32_t resident = resident_workgroups_batch(dtype);
-  if (!resident) return SPLITZIP_ERR_HIP;
-  uint32_t W = (uint32_t)cu_count() * (uint32_t)wgs_per_cu;
-  if (W > resident) W = resident;
-  if (W > kRingWgs) W = kRingWgs;
-  static const int max_wgs = env_int("SPLITZIP_COMPRESS_MAX_WGS", 0);
-  if (max_wgs && W > (uint32_t)max_wgs) W = (uint32_t)max_wgs;
-  const uint64_t chunk_cap = (uint64_t)W * kMaxRange;   // chunks of one tensor the batch kernel can take
-  static const int spin_env = env_int("SPLITZIP_SPIN_TICKS", 0);
-  static const int missing = env_int("SPLITZIP_TEST_AWAIT_EXTRA_WGS", 0);   // error-path tests only
-  const hipStream_t st = static_cast<hipStream_t>(stream);
-  uint8_t* ws = static_cast<uint8_t*>(d_workspace);
-
-  uint32_t i = 0;
-  while (i < n_items) {
-    // a tensor beyond the batch kernel's reach goes through the single call, in its place in the order
-    if ((items[i].n_elems + kChunk - 1) / kChunk > chunk_cap) {
-      const int rc = compress_impl(item_words(paging, items[i].d_in), items[i].n_elems, dtype, d_cbs ? nullptr : items[i].cb,
-                                   d_cbs ? d_cbs + i : nullptr, items[i].d_out, items[i].out_capacity, d_workspace,
-                                   workspace_bytes, d_sizes + i, stream);
-      if (rc != SPLITZIP_OK) return rc;
-      ++i;
-      continue;
-    }
-    // one launch: up to kBatchMax tensors, each with a codebook of its own (its 16 decode entries travel as
-    // kernel arguments: codebook_ok has shown that they and the encode table describe the same bijection)
-    CompressBatchArgs a;
-    memset(&a, 0, sizeof a);
-    uint32_t k = 0;
-    for (; i + k < n_items && k < kBatchMax; ++k) {
-      const splitzip_item& it = items[i + k];
-      if ((it.n_elems + kChunk - 1) / kChunk > chunk_cap) break;
-      if (!d_cbs) memcpy(a.dec[k], it.cb->dec, 16);
-      a.item[k].in = static_cast<const uint8_t*>(it.d_in);
-      a.item[k].out = static_cast<uint8_t*>(it.d_out);
-      a.item[k].n = it.n_elems;
-      a.item[k].capacity = it.out_capacity;
-    }
-    a.sizes = d_sizes + i;
-    a.d_cbs = d_cbs ? d_cbs + i : nullptr;
-    a.ws_hdr = reinterpret_cast<uint32_t*>(ws);
-    a.state = reinterpret_cast<uint64_t*>(ws + kWsHeaderBytes);
-    a.spin_ticks = spin_env ? (uint64_t)spin_env : kSpinTicks;
-    a.n_items = k;
-    a.dtype = (uint32_t)dtype;
-    a.paging = paging;
-    // Workgroups per tensor: all of them for large tensors; for small ones a power-of-two share that
-    // leaves each workgroup about 64 chunks, the groups working on different tensors side by side.
-    uint64_t chunks_max = 0;
-    for (uint32_t q = 0; q < k; ++q) {
-      const uint64_t c = (a.item[q].n + kChunk - 1) / kChunk;
-      if (c > chunks_max) chunks_max = c;
-    }
-    uint32_t G = W;
-    while (G > 8 && G % 2 == 0 && (uint64_t)(G / 2) * 64 >= chunks_max && W / (G / 2) <= k) G /= 2;   // never more groups than tensors
-    while ((uint64_t)G * kMaxRange < chunks_max) G *= 2;   // never beyond W: chunks_max <= chunk_cap
-    if (G > W) G = W;
-    // A group larger than the kernel fetches exchange words ahead for would put the exchange back on every
-    // workgroup's critical path (and have each read that many more words): a smaller grid serves such tensors better.
-    const uint32_t kernel_wgs_per_cu = (uint32_t)(dtype == SPLITZIP_BF16 ? Bf16::kBatchWgsPerCu : E5m2::kBatchWgsPerCu);
-    const uint32_t ahead = 256u * (kernel_wgs_per_cu < 4u ? kernel_wgs_per_cu : 4u);
-    uint32_t Wk = W;
-    if (G > ahead && (uint64_t)ahead * kMaxRange >= chunks_max) Wk = G = ahead;
-    a.group_wgs = G;
-    a.await_extra = (uint32_t)missing;
-    const uint32_t grid = (Wk / G) * G;
-    if (dtype == SPLITZIP_BF16) hipLaunchKernelGGL((compress_batch_kernel<Bf16::kBatchThreads, Bf16>), dim3(grid), dim3(Bf16::kBatchThreads), 0, st, a);
-    else hipLaunchKernelGGL((compress_batch_kernel<E5m2::kBatchThreads, E5m2>), dim3(grid), dim3(E5m2::kBatchThreads), 0, st, a);
-    if (hipGetLastError() != hipSuccess) return SPLITZIP_ERR_HIP;
-    i += k;
-  }
-  return SPLITZIP_OK;
-}
-
 int decompress_batch_impl(const splitzip_ditem* items, uint32_t n_items, int dtype, const Words& paging, uint64_t paged_room,
                           const splitzip_codebook* d_cbs, bool own_dec, splitzip_sizes* d_sizes, void* stream) {
   if (!dtype_ok(dtype) || (n_items && !items) || (reinterpret_cast<uintptr_t>(d_sizes) & 7u) || (reinterpret_cast<uintptr_t>(d_cbs) & 3u))
@@ -834,8 +761,6 @@ int decompress_batch_impl(const splitzip_ditem* items, uint32_t n_items, int dty
     if (paging.table && it.n_elems > paged_room) return SPLITZIP_ERR_INVALID_ARG;
     if (it.comp_bytes < splitzip_fixed_bytes(it.n_elems, dtype)) return SPLITZIP_ERR_CAPACITY;
   }
-  static const int cpw_env = env_int("SPLITZIP_DECOMPRESS_CPW", 0);
-  static const int tiles_per_cu = env_int("SPLITZIP_DECOMPRESS_TILES_PER_CU", 0);
   uint32_t i = 0;
   while (i < n_items) {
     DecompressBatchArgs a;
@@ -858,10 +783,8 @@ int decompress_batch_impl(const splitzip_ditem* items, uint32_t n_items, int dty
     a.own_dec = own_dec ? 1u : 0u;
     a.dtype = (uint32_t)dtype;
     a.paging = paging;
-    a.cpw = cpw_env ? (uint32_t)cpw_env : pick_decompress_cpw(chunks_all, dtype, tiles_per_cu);
-    if (a.cpw > kMaxCpw) a.cpw = kMaxCpw;
-    static const int reg_patch = env_int("SPLITZIP_DECOMPRESS_REG_PATCH", (int)kRegPatchDefault);
-    a.reg_patch_max = (uint32_t)reg_patch;
+    a.cpw = pick_decompress_cpw(chunks_all, dtype);
+    a.reg_patch_max = kRegPatchDefault;
     uint64_t gx = (chunks_max + (uint64_t)kWaves * a.cpw - 1) / (kWaves * a.cpw);
     if (gx < 1) gx = 1;
     const dim3 grid((unsigned)gx, k);
@@ -879,7 +802,7 @@ extern "C" {
 
 int splitzip_compress_batch(const splitzip_item* items, uint32_t n_items, int dtype, void* d_workspace,
                             size_t workspace_bytes, splitzip_sizes* d_sizes, void* stream) {
-  return compress_batch_impl(items, n_items, dtype, contiguous_words(nullptr), 0, nullptr, d_workspace, workspace_bytes, d_sizes, stream);
+  return compress_launch(items, n_items, dtype, contiguous_words(nullptr), 0, nullptr, d_workspace, workspace_bytes, false, d_sizes, stream);
 }
 
 int splitzip_decompress_batch(const splitzip_ditem* items, uint32_t n_items, int dtype, splitzip_sizes* d_sizes,
@@ -925,7 +848,7 @@ int splitzip_calibrate_batch_device(const splitzip_item* items, uint32_t n_items
 int splitzip_compress_batch_dcb(const splitzip_item* items, uint32_t n_items, int dtype, const splitzip_codebook* d_cbs,
                                 void* d_workspace, size_t workspace_bytes, splitzip_sizes* d_sizes, void* stream) {
   if (n_items && !d_cbs) return SPLITZIP_ERR_INVALID_ARG;
-  return compress_batch_impl(items, n_items, dtype, contiguous_words(nullptr), 0, d_cbs, d_workspace, workspace_bytes, d_sizes, stream);
+  return compress_launch(items, n_items, dtype, contiguous_words(nullptr), 0, d_cbs, d_workspace, workspace_bytes, false, d_sizes, stream);
 }
 
 int splitzip_decompress_batch_dcb(const splitzip_ditem* items, uint32_t n_items, int dtype, const splitzip_codebook* d_cbs,
@@ -943,8 +866,8 @@ int splitzip_compress_batch_paged(const splitzip_item* items, uint32_t n_items, 
                                   void* d_workspace, size_t workspace_bytes, splitzip_sizes* d_sizes, void* stream) {
   Words w;
   if (!dtype_ok(dtype) || !paging_geometry(paging, dtype, &w)) return SPLITZIP_ERR_INVALID_ARG;
-  return compress_batch_impl(items, n_items, dtype, w, (uint64_t)paging->n_blocks * paging->block_elems, nullptr, d_workspace,
-                             workspace_bytes, d_sizes, stream);
+  return compress_launch(items, n_items, dtype, w, (uint64_t)paging->n_blocks * paging->block_elems, nullptr, d_workspace,
+                        workspace_bytes, false, d_sizes, stream);
 }
 
 int splitzip_decompress_batch_paged(const splitzip_ditem* items, uint32_t n_items, int dtype, const splitzip_paged* paging,
@@ -971,7 +894,7 @@ int splitzip_traffic_probe(const void* d_src, size_t read_bytes, void* d_dst, si
 
 int splitzip_traffic_probe_shape(const void* d_src, size_t read_bytes, void* d_dst, size_t write_bytes, uint32_t reads_per_step,
                                  uint32_t writes_per_step, uint32_t wgs_per_cu, uint32_t flags, void* stream) {
-  if (!d_src || !d_dst || !aligned16(d_src) || !aligned16(d_dst) || wgs_per_cu > 32 || flags > 15u || (flags & 12u) == 8u)
+  if (!d_src || !d_dst || !aligned16(d_src) || !aligned16(d_dst) || wgs_per_cu > 32 || flags > 63u || (flags & 12u) == 8u || ((flags & 16u) && (flags & 12u)))
     return SPLITZIP_ERR_INVALID_ARG;
   const uint32_t R = reads_per_step, W = writes_per_step;
   const uint64_t nread = R ? read_bytes / 16 : 0, nwrite = W ? write_bytes / 16 : 0;
@@ -985,7 +908,7 @@ int splitzip_traffic_probe_shape(const void* d_src, size_t read_bytes, void* d_d
   const hipStream_t st = static_cast<hipStream_t>(stream);
   const u32x4* src = static_cast<const u32x4*>(d_src);
   u32x4* dst = static_cast<u32x4*>(d_dst);
-  const uint32_t blocked = (flags & 4u) ? ((flags & 8u) ? 2u : 1u) : 0u;
+  const uint32_t blocked = ((flags & 16u) ? 3u : (flags & 4u) ? ((flags & 8u) ? 2u : 1u) : 0u) | ((flags & 32u) ? 4u : 0u);
   bool found = false;
 #define SPLITZIP_SHAPE(RR, WW)                                                                                              \
   if (R == RR && W == WW) {                                                                                                 \

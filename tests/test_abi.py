@@ -107,7 +107,7 @@ def test_argument_validation_without_gpu():
     base = (C.addressof(buf) + 15) & ~15
     n = 64
     good = dict(d_in=base, n=n, dtype=sz.BF16, cb=C.byref(cb.c), d_out=base + 1024, cap=1 << 20,
-                ws=base + 2048, wsb=1 << 20, sizes=base + 3072, stream=None)
+                ws=base + 2048, wsb=1 << 24, sizes=base + 3072, stream=None)
 
     def comp(**kw):
         a = dict(good, **kw)
@@ -147,7 +147,7 @@ def test_argument_validation_without_gpu():
     from paper_2605_01708_amd.binding import _CDItem, _CItem
     items = (_CItem * 2)(_CItem(base, n, base + 1024, 1 << 20, C.pointer(cb.c)),
                          _CItem(base, n, base + 1024, 1 << 20, C.pointer(cb.c)))
-    bcomp = lambda its, k, ws=base + 2048, wsb=1 << 20, sizes=base + 3072: L.splitzip_compress_batch(  # noqa: E731
+    bcomp = lambda its, k, ws=base + 2048, wsb=1 << 24, sizes=base + 3072: L.splitzip_compress_batch(  # noqa: E731
         its, k, sz.BF16, ws, wsb, sizes, None)
     assert bcomp(None, 2) == -1
     assert bcomp(items, 2, ws=None) == -1
@@ -176,7 +176,7 @@ def test_argument_validation_without_gpu():
     # device-codebook calls: the codebook pointer is all the host can check
     assert L.splitzip_compress_dcb(base, n, sz.BF16, None, base + 1024, 1 << 20, base + 2048, 1 << 20, base + 3072, None) == -1
     assert L.splitzip_compress_dcb(base, n, sz.BF16, base + 512 + 2, base + 1024, 1 << 20, base + 2048, 1 << 20, base + 3072, None) == -1
-    assert L.splitzip_compress_dcb(base, n, sz.BF16, base + 512, base + 1024, 16, base + 2048, 1 << 20, base + 3072, None) == -3
+    assert L.splitzip_compress_dcb(base, n, sz.BF16, base + 512, base + 1024, 16, base + 2048, 1 << 24, base + 3072, None) == -3
     assert L.splitzip_decompress_dcb(base, 1 << 20, n, sz.BF16, None, base + 1024, None, None) == -1
     assert L.splitzip_decompress_dcb(base, 16, n, sz.BF16, base + 512, base + 1024, None, None) == -3
     assert L.splitzip_codebook_device(None, sz.BF16, base, None) == -1
