@@ -250,6 +250,20 @@ __device__ inline void decompress_tile(const DecompressArgs& a, const uint8_t* d
   // paged tensor: the pool pages of the wave's chunks, lane c <-> its chunk c
   uint32_t my_pages = 0;
   if (a.w.table && (uint32_t)lane < cpw && wave_chunk0 + lane < a.n_chunks) my_pages = page_of_chunk(a.w, wave_chunk0 + lane);
+
+  // The wave's chunks; only the tensor's last chunk can be ragged, and it is the last of its wave.
+  const uint32_t mine = wave_chunk0 < a.n_chunks ? (a.n_chunks - wave_chunk0 < cpw ? a.n_chunks - wave_chunk0 : cpw) : 0u;
+  const bool last_ragged = mine > 0 && !F::full(a, (uint64_t)(wave_chunk0 + mine - 1) * kChunk);
+  const uint32_t fast = mine - (last_ragged ? 1u : 0u);
+  // everything chunk c needs from memory: its planes and the first 64 of its records, one lane each
+  struct Fetched {
+    typename F::In in;
+    uint32_t pos, val;
+  };
+  Fetched cur, nxt;
+  // The planes of the wave's first chunk depend on nothing that is loaded: they are asked for right behind the
+  // table entries, and the decode table is built while both are on their way (the barrier below is for LDS only).
+  if (fast > 0) F::template load<true>(a, (uint64_t)wave_chunk0 * kChunk, lane, cur.in);
   tbl[tid] = F::table(tid, dec);
 
   // escapes are only trusted if their sections lie inside the stream
@@ -262,12 +276,8 @@ __device__ inline void decompress_tile(const DecompressArgs& a, const uint8_t* d
   if (!esc_ok) M = 0;
   const uint16_t* pos_arr = reinterpret_cast<const uint16_t*>(a.comp + a.off_pos);
   const uint8_t* val_arr = a.comp + off_val;
-  __syncthreads();
+  lds_barrier();
 
-  // The wave's chunks; only the tensor's last chunk can be ragged, and it is the last of its wave.
-  const uint32_t mine = wave_chunk0 < a.n_chunks ? (a.n_chunks - wave_chunk0 < cpw ? a.n_chunks - wave_chunk0 : cpw) : 0u;
-  const bool last_ragged = mine > 0 && !F::full(a, (uint64_t)(wave_chunk0 + mine - 1) * kChunk);
-  const uint32_t fast = mine - (last_ragged ? 1u : 0u);
   // escape records of the wave's c-th chunk: first record and count, from the offset table (0 records if the entries are inconsistent)
   auto records = [&](uint32_t c, uint32_t& lo, bool& valid) -> uint32_t {
     const uint64_t cbase = (uint64_t)(wave_chunk0 + c) * kChunk;
@@ -277,12 +287,7 @@ __device__ inline void decompress_tile(const DecompressArgs& a, const uint8_t* d
     valid = hi >= lo && hi - lo <= clen && hi <= M;
     return valid ? hi - lo : 0u;
   };
-  // everything chunk c needs from memory: its planes and the first 64 of its records, one lane each
-  struct Fetched {
-    typename F::In in;
-    uint32_t pos, val;
-  };
-  auto fetch = [&](uint32_t c, Fetched& f, auto complete) {
+  auto fetch_records = [&](uint32_t c, Fetched& f) {
     uint32_t lo;
     bool valid;
     const uint32_t cnt = records(c, lo, valid);
@@ -291,6 +296,9 @@ __device__ inline void decompress_tile(const DecompressArgs& a, const uint8_t* d
       f.pos = pos_arr[lo + lane];
       f.val = val_arr[lo + lane];
     }
+  };
+  auto fetch = [&](uint32_t c, Fetched& f, auto complete) {
+    fetch_records(c, f);
     F::template load<decltype(complete)::value>(a, (uint64_t)(wave_chunk0 + c) * kChunk, lane, f.in);
   };
   // A few escapes, the usual case, are applied to the decoded words in registers, one after the other; more
@@ -307,11 +315,13 @@ __device__ inline void decompress_tile(const DecompressArgs& a, const uint8_t* d
     typename F::Out r;
     F::decode(f.in, tbl, lane, r);
     if (cnt > 0 && cnt <= a.reg_patch_max) {
+      uint32_t floor = 0;   // a chunk's positions ascend: each must lie above the one before it
       for (uint32_t j = 0; j < cnt; ++j) {
         const uint32_t p = __builtin_amdgcn_readlane(f.pos, j), v = __builtin_amdgcn_readlane(f.val, j);
-        if (p >= clen || !F::patch_reg(r, lane, p, v)) {
+        if (p >= clen || p < floor || !F::patch_reg(r, lane, p, v)) {
           if (lane == 0) flag_bad(a);
         }
+        floor = p + 1;
       }
     }
     if (cnt > a.reg_patch_max) {
@@ -324,7 +334,10 @@ __device__ inline void decompress_tile(const DecompressArgs& a, const uint8_t* d
           p = pos_arr[lo + j];
           v = val_arr[lo + j];
         }
-        if (p >= clen || !F::patch_tile(t, p, v)) flag_bad(a);
+        // a chunk's positions ascend: the record before this one (the lane below holds it, or memory does)
+        uint32_t before = (uint32_t)__shfl_up((int)p, 1);
+        if (lane == 0 && j > 0) before = pos_arr[lo + j - 1];
+        if (p >= clen || (j > 0 && p <= before) || !F::patch_tile(t, p, v)) flag_bad(a);
       }
       lds_settle();
       F::from_tile(r, t, lane);
@@ -337,9 +350,8 @@ __device__ inline void decompress_tile(const DecompressArgs& a, const uint8_t* d
   // and the ragged chunk stays out of it altogether, its loads included: the compiler's wait at the bottom of an
   // iteration then covers the next chunk's loads but not the store issued after them, and no wait stands in
   // front of the loads.
-  Fetched cur, nxt;
   if (fast > 0) {
-    fetch(0, cur, std::true_type{});
+    fetch_records(0, cur);
     F::arrived(cur.in);
     asm volatile("" : "+v"(cur.pos), "+v"(cur.val));
   }

@@ -469,7 +469,10 @@ __global__ __launch_bounds__(kThreads) void v_decode_kernel(const VArgs a) {
           p = PB == 2 ? reinterpret_cast<const uint16_t*>(a.in + a.off_pos)[rec_lo[q] + i] : a.in[a.off_pos + rec_lo[q] + i];
           e = a.in[off_val + rec_lo[q] + i];
         }
-        if (p >= len || e >= (uint32_t)F::EXPS) { bad = true; continue; }
+        // a chunk's positions ascend: the record before this one (the lane below holds it, or memory does)
+        uint32_t before = (uint32_t)__shfl_up((int)p, 1);
+        if (lane == 0 && i > 0) before = PB == 2 ? reinterpret_cast<const uint16_t*>(a.in + a.off_pos)[rec_lo[q] + i - 1] : a.in[a.off_pos + rec_lo[q] + i - 1];
+        if (p >= len || (i > 0 && p <= before) || e >= (uint32_t)F::EXPS) { bad = true; continue; }
         const uint32_t at = q * chunk + p;
         if (F::ES == 2) {
           uint16_t* t = reinterpret_cast<uint16_t*>(s_tile[wave]) + at;
@@ -510,7 +513,8 @@ __global__ __launch_bounds__(kThreads) void v_scatter_kernel(const VArgs a) {
   for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < M; i += (uint64_t)gridDim.x * kThreads) {
     const uint64_t p = reinterpret_cast<const uint32_t*>(a.in + a.off_pos)[i];
     const uint32_t e = a.in[off_val + i];
-    if (p >= a.n || e >= (uint32_t)F::EXPS) { bad = true; continue; }
+    // the element indices ascend
+    if (p >= a.n || e >= (uint32_t)F::EXPS || (i > 0 && p <= reinterpret_cast<const uint32_t*>(a.in + a.off_pos)[i - 1])) { bad = true; continue; }
     if (F::ES == 2) {
       uint16_t* t = reinterpret_cast<uint16_t*>(a.out) + p;
       *t = (uint16_t)F::combine(F::signmant(*t), e);

@@ -263,6 +263,39 @@ def test_bad_stream_is_flagged_not_followed():
     y, st = run(set_(64 + 4 * c + 3, 0x7F))  # M in the offset table far beyond the stream
     assert st & sz.STATUS_BAD_STREAM
 
+    # positions inside a chunk must ascend (the oracle's decoder rejects such a stream; the GPU's flags it): a chunk
+    # with two escapes, a chunk with a few (corrected in registers) and one with many (corrected in the LDS tile)
+    x2 = synth(sz.BF16, 16, 3).copy()
+    x2[[7, 300]] = 0                          # chunk 0: two escapes
+    x2[3 * 1024: 3 * 1024 + 200: 2] = 0       # chunk 3: a hundred of them
+    blob2, m2 = oracle.compress(x2, cb_or)
+    off_pos2 = blob2.size - m2 - (2 * m2 + 255) // 256 * 256
+    tab2 = blob2[64:64 + 4 * (c + 1)].view(np.uint32)
+
+    def swap(j):                               # records j and j + 1 change places (positions only)
+        def f(b):
+            p = b[off_pos2:off_pos2 + 2 * m2].view(np.uint16)
+            p[j], p[j + 1] = p[j + 1], p[j]
+        return f
+
+    def dup(j):                                # record j + 1 repeats the position of record j
+        def f(b):
+            p = b[off_pos2:off_pos2 + 2 * m2].view(np.uint16)
+            p[j + 1] = p[j]
+        return f
+
+    def run2(mut):
+        b = blob2.copy()
+        mut(b)
+        with pytest.raises(ValueError):
+            oracle.decompress(b, n, cb_or)
+        y, (_, _, st) = g.decompress(torch.from_numpy(b).cuda(), b.size, n, cb)
+        return st
+
+    assert tab2[1] - tab2[0] >= 2 and tab2[4] - tab2[3] >= 100
+    for mut in (swap(int(tab2[0])), dup(int(tab2[0])), swap(int(tab2[3]) + 10), dup(int(tab2[3]) + 70), swap(int(tab2[3]) + 63)):
+        assert run2(mut) & sz.STATUS_BAD_STREAM
+
 
 @pytest.mark.parametrize("dtype", DTYPES)
 def test_batch_calls_match_the_oracle_item_by_item(dtype):

@@ -195,6 +195,34 @@ def test_variant_overflow_and_bad_streams():
         assert st & sz.STATUS_BAD_STREAM, (off, st)
     _, (_, _, st) = run.decompress(good, ref.size, x.size, cb)
     assert st == 0
+    # positions inside a chunk must ascend: two records of one chunk change places (the oracle's decoder rejects it)
+    n_chunks = (x.size + 255) // 256
+    tab = ref[64:64 + 4 * (n_chunks + 1)].view(np.uint32)
+    ch = int(np.argmax(np.diff(tab) >= 2))
+    assert tab[ch + 1] - tab[ch] >= 2
+    off_pos = sz.variant_total_bytes(x.size, 0, v)              # 8-bit positions start behind the fixed part
+    swapped = ref.copy()
+    j = off_pos + int(tab[ch])
+    swapped[j], swapped[j + 1] = swapped[j + 1], swapped[j]
+    with pytest.raises(ValueError):
+        ov.decompress(swapped, x.size, o, dec)
+    _, (_, _, st) = run.decompress(torch.from_numpy(swapped).cuda(), ref.size, x.size, cb)
+    assert st & sz.STATUS_BAD_STREAM
+    # the same for absolute positions
+    va, oa = sz.variant(sz.BF16, 4, 16, sz.ESC_ABS32, 0), ov.variant(ov.BF16, 4, 16, ov.ESC_ABS32, 0)
+    cba = sz.variant_codebook_from_dec(dec, va)
+    refa, ma = ov.compress(x, oa, dec)
+    posa = sz.variant_total_bytes(x.size, 0, va)
+    swapped = refa.copy()
+    p32 = swapped[posa:posa + 4 * ma].view(np.uint32)
+    p32[5], p32[6] = p32[6], p32[5]
+    with pytest.raises(ValueError):
+        ov.decompress(swapped, x.size, oa, dec)
+    runa = Run(x.size, va)
+    _, (_, _, st) = runa.decompress(torch.from_numpy(swapped).cuda(), refa.size, x.size, cba)
+    assert st & sz.STATUS_BAD_STREAM
+    _, (_, _, st) = runa.decompress(torch.from_numpy(refa.copy()).cuda(), refa.size, x.size, cba)
+    assert st == 0
 
 
 @pytest.mark.gpu
