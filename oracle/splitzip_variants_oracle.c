@@ -22,7 +22,7 @@
  *     with the 4-bit top-16 code is the main format).
  *
  * A variant is (dtype, code bits, codebook entries k, escape mode, chunk
- * elements).  Field split, dense coding, escape order and the decoding rule
+ * elements, bits per escape value).  Field split, dense coding, escape order and the decoding rule
  * are those of the main format; only widths and the escape representation
  * change.  E4M3 byte = s eeee mmm: e = (x >> 3) & 15, a = ((x >> 4) & 8) |
  * (x & 7), by analogy with eq. (1) (the paper prints no FP8 formula).
@@ -41,9 +41,11 @@
  *   esc_pos    positions       u16[M] (chunk > 256) or u8[M] chunk-relative;
  *                              nothing in the sentinel mode; u32[M] absolute
  *                              element indices in the absolute mode
- *   esc_val    M B             u8 raw exponents, element order
+ *   esc_val    ceil(M*vb/8) B  raw exponents, element order: whole bytes (vb = 8)
+ *                              or an LSB-first bit stream of vb = the exponent
+ *                              field's own width (5 for E5M2, 4 for E4M3)
  *
- *   total = A(64 + table) + A(sm) + A(code) + A(positions) + M
+ *   total = A(64 + table) + A(sm) + A(code) + A(positions) + ceil(M*vb/8)
  *
  * With (BF16 or E5M2, 4 bits, k = 16, chunk-relative, 1024) every byte after
  * the header equals the main format's stream; the header differs in the
@@ -54,12 +56,19 @@
  * slots >= k are written as 0 in the header; the sentinel is the all-ones
  * code; the sentinel mode keeps the per-chunk offset table, because without
  * it no decoder can start anywhere but at element 0 (the paper's size figure
- * for this variant, like all its ratios, counts payload only).  The FP8 top-8
- * ratios the paper prints (1.049 and 0.933) correspond to 21 and 20 bits per
- * escape, i.e. exponents stored in their native width; this build keeps
- * whole-byte escape values in every variant, which gives 1.019 and 0.901 at
- * the same escape rates -- those two printed ratios are not reproduced and the
- * FP8 top-8 sizes are pinned by the closed form only.
+ * for this variant, like all its ratios, counts payload only).
+ *
+ * Width of an escape value.  Section 3.2 stores the raw exponent of a BF16
+ * escape "as an 8-bit integer", which is its own width; the FP8 appendix does
+ * not say.  Its table pins both readings: E5M2 top-16 at 0.16 % escapes gives
+ * 1.136 only with 24-bit records (16-bit position + a whole byte: 8 / (7 + 24
+ * x 0.0016) = 1.1366; 21 bits would give 1.1374), while E5M2 top-8 at 7.72 %
+ * and E4M3 top-8 at 7.83 % give 1.049 and 0.933 only with 21 and 20 bits per
+ * escape (8 / (6 + 21 x 0.0772) = 1.0497, 8 / (7 + 20 x 0.0783) = 0.9339;
+ * whole bytes would give 1.019 and 0.901), i.e. the exponent in its own
+ * width.  Both are formats here: vb = 8 (the main format's records) and vb =
+ * the exponent's width.  Every printed ratio is matched by one of them to
+ * within 0.001 (the paper's ratios include some metadata it does not itemise).
  */
 #include <stddef.h>
 #include <stdint.h>
@@ -87,6 +96,7 @@ typedef struct {
   uint32_t k;           /* codebook entries in use */
   uint32_t escape_mode; /* V_ESC_* */
   uint32_t chunk;       /* elements per chunk (power of two, 64..65536); ignored in the absolute mode */
+  uint32_t value_bits;  /* bits per escape value: 0 or 8 = whole bytes, else the exponent field's width (5 / 4 for E5M2 / E4M3) */
 } oracle_variant;
 
 static uint64_t v_a256(uint64_t x) { return (x + 255u) & ~(uint64_t)255u; }
@@ -94,6 +104,8 @@ static uint64_t v_a256(uint64_t x) { return (x + 255u) & ~(uint64_t)255u; }
 static unsigned v_elem_bytes(uint32_t dtype) { return dtype == V_BF16 ? 2u : 1u; }
 static unsigned v_exp_values(uint32_t dtype) { return dtype == V_BF16 ? 256u : dtype == V_E5M2 ? 32u : 16u; }
 static unsigned v_sm_bits(uint32_t dtype) { return dtype == V_BF16 ? 8u : dtype == V_E5M2 ? 3u : 4u; }
+static unsigned v_exp_bits(uint32_t dtype) { return dtype == V_BF16 ? 8u : dtype == V_E5M2 ? 5u : 4u; }
+static unsigned v_value_bits(const void* vv);
 
 int oracle_v_valid(const oracle_variant* v) {
   if (!v || v->dtype > V_E4M3) return 0;
@@ -105,7 +117,12 @@ int oracle_v_valid(const oracle_variant* v) {
   if (v->escape_mode != V_ESC_ABS32) {
     if (v->chunk < 64 || v->chunk > 65536 || (v->chunk & (v->chunk - 1u))) return 0;
   }
+  if (v->value_bits != 0 && v->value_bits != 8 && v->value_bits != v_exp_bits(v->dtype)) return 0;
   return 1;
+}
+static unsigned v_value_bits(const void* vv) {
+  const oracle_variant* v = (const oracle_variant*)vv;
+  return v->value_bits ? v->value_bits : 8u;
 }
 
 /* exponent field and the remaining sign+mantissa bits of one element */
@@ -149,13 +166,14 @@ static uint64_t v_plane_bytes(uint64_t n, unsigned bits) { return (n * bits + 7u
  * two planes and the escape records */
 uint64_t oracle_v_payload_bytes(uint64_t n, uint64_t m, const oracle_variant* v) {
   if (!oracle_v_valid(v)) return 0;
-  return v_plane_bytes(n, v_sm_bits(v->dtype)) + v_plane_bytes(n, v->code_bits) + m * (v_pos_bytes(v) + 1u);
+  return v_plane_bytes(n, v_sm_bits(v->dtype)) + v_plane_bytes(n, v->code_bits) + m * v_pos_bytes(v) +
+         v_plane_bytes(m, v_value_bits(v));
 }
 
 uint64_t oracle_v_total_bytes(uint64_t n, uint64_t m, const oracle_variant* v) {
   if (!oracle_v_valid(v)) return 0;
   return v_a256(V_HEADER + v_table_bytes(n, v)) + v_a256(v_plane_bytes(n, v_sm_bits(v->dtype))) +
-         v_a256(v_plane_bytes(n, v->code_bits)) + v_a256(m * v_pos_bytes(v)) + m;
+         v_a256(v_plane_bytes(n, v->code_bits)) + v_a256(m * v_pos_bytes(v)) + v_plane_bytes(m, v_value_bits(v));
 }
 
 /* ---- calibration (section 3.3, with k entries) ------------------------------ */
@@ -222,7 +240,8 @@ static uint64_t v_get(const uint8_t* p, unsigned bytes) {
 
 /* header, 64 bytes:
  *   0  u32 magic 'S','Z','P','1'   4  u16 version = 2   6  u8 dtype   7  u8 code bits
- *   8  u32 chunk elements (0 in the absolute mode)   12  u8 escape mode   13  u8 k   14  u16 0
+ *   8  u32 chunk elements (0 in the absolute mode)   12  u8 escape mode   13  u8 k
+ *  14  u8 bits per escape value if not 8, else 0   15  u8 0
  *  16  u64 N   24  u64 M   32  u64 total bytes   40  u8 dec[16] (slots >= k are 0)   56  u8 reserved[8] = 0 */
 static void v_write_header(uint8_t* out, uint64_t n, uint64_t m, uint64_t total, const oracle_variant* v,
                            const uint8_t dec[16]) {
@@ -234,6 +253,7 @@ static void v_write_header(uint8_t* out, uint64_t n, uint64_t m, uint64_t total,
   v_put(out + 8, 4, v->escape_mode == V_ESC_ABS32 ? 0u : v->chunk);
   out[12] = (uint8_t)v->escape_mode;
   out[13] = (uint8_t)v->k;
+  out[14] = (uint8_t)(v_value_bits(v) == 8u ? 0u : v_value_bits(v));
   v_put(out + 16, 8, n);
   v_put(out + 24, 8, m);
   v_put(out + 32, 8, total);
@@ -273,7 +293,7 @@ int oracle_v_compress(const void* in, uint64_t n, const oracle_variant* v, const
   if (!out || cap < total) return V_ERR_CAPACITY;
 
   const v_offsets o = v_layout(n, m, v);
-  const unsigned sb = v_sm_bits(v->dtype), cb = v->code_bits, pb = v_pos_bytes(v);
+  const unsigned sb = v_sm_bits(v->dtype), cb = v->code_bits, pb = v_pos_bytes(v), vb = v_value_bits(v);
   const unsigned sentinel = (1u << cb) - 1u;
   memset(out, 0, total);
   v_write_header(out, n, m, total, v, dec);
@@ -290,7 +310,7 @@ int oracle_v_compress(const void* in, uint64_t n, const oracle_variant* v, const
       put_bits(out + o.code, (uint64_t)cb * i, cb, v->escape_mode == V_ESC_SENTINEL ? sentinel : 0u);
       if (v->escape_mode == V_ESC_POS) v_put(out + o.pos + (uint64_t)pb * r, pb, i % v->chunk);
       if (v->escape_mode == V_ESC_ABS32) v_put(out + o.pos + 4u * r, 4, i);
-      out[o.val + r] = (uint8_t)e;
+      put_bits(out + o.val, (uint64_t)vb * r, vb, e);   /* vb = 8: the byte out[o.val + r] */
       ++r;
     }
   }
@@ -316,7 +336,8 @@ int oracle_v_decompress(const uint8_t* blob, uint64_t blob_bytes, uint64_t n, co
   if (blob_bytes < V_HEADER) return V_ERR_FORMAT;
   if (memcmp(blob, "SZP1", 4) != 0 || v_get(blob + 4, 2) != 2 || blob[6] != v->dtype || blob[7] != v->code_bits ||
       v_get(blob + 8, 4) != (v->escape_mode == V_ESC_ABS32 ? 0u : v->chunk) || blob[12] != v->escape_mode ||
-      blob[13] != v->k || v_get(blob + 14, 2) != 0 || v_get(blob + 16, 8) != n)
+      blob[13] != v->k || blob[14] != (v_value_bits(v) == 8u ? 0u : v_value_bits(v)) || blob[15] != 0 ||
+      v_get(blob + 16, 8) != n)
     return V_ERR_FORMAT;
   const uint64_t m = v_get(blob + 24, 8), total = v_get(blob + 32, 8);
   if (m > n || total != oracle_v_total_bytes(n, m, v) || total > blob_bytes) return V_ERR_FORMAT;
@@ -326,12 +347,14 @@ int oracle_v_decompress(const uint8_t* blob, uint64_t blob_bytes, uint64_t n, co
     if (blob[i]) return V_ERR_FORMAT;
 
   const v_offsets o = v_layout(n, m, v);
-  const unsigned sb = v_sm_bits(v->dtype), cb = v->code_bits, pb = v_pos_bytes(v);
+  const unsigned sb = v_sm_bits(v->dtype), cb = v->code_bits, pb = v_pos_bytes(v), vb = v_value_bits(v);
   const unsigned sentinel = (1u << cb) - 1u;
   const uint64_t c = v_chunks(n, v);
 
   for (uint64_t j = 0; j < m; ++j)
-    if (blob[o.val + j] >= v_exp_values(v->dtype)) return V_ERR_FORMAT;
+    if (get_bits(blob + o.val, (uint64_t)vb * j, vb) >= v_exp_values(v->dtype)) return V_ERR_FORMAT;
+  /* the unused bits of the last value byte are zero */
+  if ((m * vb) % 8u && (blob[o.val + (m * vb) / 8u] >> ((m * vb) % 8u))) return V_ERR_FORMAT;
   if (v->escape_mode == V_ESC_ABS32) {
     for (uint64_t j = 0; j < m; ++j) {
       const uint64_t p = v_get(blob + o.pos + 4u * j, 4);
@@ -368,7 +391,7 @@ int oracle_v_decompress(const uint8_t* blob, uint64_t blob_bytes, uint64_t n, co
     const unsigned a = get_bits(blob + o.sm, (uint64_t)sb * i, sb);
     const unsigned code = get_bits(blob + o.code, (uint64_t)cb * i, cb);
     unsigned e;
-    if (v->escape_mode == V_ESC_SENTINEL && code == sentinel) e = blob[o.val + r++];
+    if (v->escape_mode == V_ESC_SENTINEL && code == sentinel) e = get_bits(blob + o.val, (uint64_t)vb * r++, vb);
     else e = dec[code];
     v_store(out, v->dtype, i, v_combine(v->dtype, a, e));
   }
@@ -379,14 +402,14 @@ int oracle_v_decompress(const uint8_t* blob, uint64_t blob_bytes, uint64_t n, co
       for (uint64_t j = lo; j < hi; ++j) {
         const uint64_t i = ch * v->chunk + v_get(blob + o.pos + (uint64_t)pb * j, pb);
         const unsigned a = v_signmant(v->dtype, v_load(out, v->dtype, i));
-        v_store(out, v->dtype, i, v_combine(v->dtype, a, blob[o.val + j]));
+        v_store(out, v->dtype, i, v_combine(v->dtype, a, get_bits(blob + o.val, (uint64_t)vb * j, vb)));
       }
     }
   } else if (v->escape_mode == V_ESC_ABS32) {
     for (uint64_t j = 0; j < m; ++j) {
       const uint64_t i = v_get(blob + o.pos + 4u * j, 4);
       const unsigned a = v_signmant(v->dtype, v_load(out, v->dtype, i));
-      v_store(out, v->dtype, i, v_combine(v->dtype, a, blob[o.val + j]));
+      v_store(out, v->dtype, i, v_combine(v->dtype, a, get_bits(blob + o.val, (uint64_t)vb * j, vb)));
     }
   }
   return V_OK;

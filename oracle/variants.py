@@ -24,15 +24,15 @@ _lib = None
 
 class Variant(C.Structure):
     _fields_ = [("dtype", C.c_uint32), ("code_bits", C.c_uint32), ("k", C.c_uint32),
-                ("escape_mode", C.c_uint32), ("chunk", C.c_uint32)]
+                ("escape_mode", C.c_uint32), ("chunk", C.c_uint32), ("value_bits", C.c_uint32)]
 
     def __repr__(self):
         return (f"Variant(dtype={self.dtype}, code_bits={self.code_bits}, k={self.k}, "
-                f"escape_mode={self.escape_mode}, chunk={self.chunk})")
+                f"escape_mode={self.escape_mode}, chunk={self.chunk}, value_bits={self.value_bits})")
 
 
-def variant(dtype, code_bits=4, k=16, escape_mode=ESC_POS, chunk=1024) -> Variant:
-    return Variant(dtype, code_bits, k, escape_mode, chunk)
+def variant(dtype, code_bits=4, k=16, escape_mode=ESC_POS, chunk=1024, value_bits=0) -> Variant:
+    return Variant(dtype, code_bits, k, escape_mode, chunk, value_bits)
 
 
 def build(force: bool = False) -> str:

@@ -32,11 +32,20 @@ def all_variants():
                 ov.variant(dt, 4, 16, ov.ESC_ABS32, 0)]         # absolute 32-bit positions
     out += [ov.variant(ov.E4M3, 3, 8, ov.ESC_POS, 1024),
             ov.variant(ov.E4M3, 3, 7, ov.ESC_SENTINEL, 256)]
+    # escape values in the exponent's own width (the FP8 table's top-8 columns)
+    out += [ov.variant(ov.E5M2, 3, 8, ov.ESC_POS, 1024, 5),
+            ov.variant(ov.E4M3, 3, 8, ov.ESC_POS, 1024, 4),
+            ov.variant(ov.E5M2, 4, 15, ov.ESC_SENTINEL, 256, 5),
+            ov.variant(ov.E4M3, 3, 8, ov.ESC_ABS32, 0, 4)]
     return out
 
 
+def vb_of(v):
+    return v.value_bits or 8
+
+
 def vid(v):
-    return f"dt{v.dtype}-b{v.code_bits}-k{v.k}-m{v.escape_mode}-c{v.chunk}"
+    return f"dt{v.dtype}-b{v.code_bits}-k{v.k}-m{v.escape_mode}-c{v.chunk}" + (f"-v{v.value_bits}" if v.value_bits else "")
 
 
 def exponent_np(x, dt):
@@ -95,13 +104,14 @@ def py_decode(blob, n, v, dec):
     off_pos = off_code + a256(-(-n * cb // 8))
     pb = 0 if v.escape_mode == ov.ESC_SENTINEL else 4 if absolute else (2 if v.chunk > 256 else 1)
     off_val = off_pos + a256(m * pb)
-    assert off_val + m == field(blob, 32, 8) == len(blob)
-    sm, code = blob[off_sm:], blob[off_code:]
+    vb = vb_of(v)
+    assert off_val + -(-m * vb // 8) == field(blob, 32, 8) == len(blob)
+    sm, code, vals = blob[off_sm:], blob[off_code:], blob[off_val:]
     exps, next_val = [], 0
     for i in range(n):
         cde = bits_at(code, i, cb)
         if v.escape_mode == ov.ESC_SENTINEL and cde == (1 << cb) - 1:
-            exps.append(int(blob[off_val + next_val]))
+            exps.append(bits_at(vals, next_val, vb))
             next_val += 1
         else:
             exps.append(int(dec[cde]))
@@ -109,10 +119,10 @@ def py_decode(blob, n, v, dec):
         for ch in range(c):
             lo, hi = field(blob, tab + 4 * ch, 4), field(blob, tab + 4 * ch + 4, 4)
             for j in range(lo, hi):
-                exps[ch * v.chunk + field(blob, off_pos + pb * j, pb)] = int(blob[off_val + j])
+                exps[ch * v.chunk + field(blob, off_pos + pb * j, pb)] = bits_at(vals, j, vb)
     elif absolute:
         for j in range(m):
-            exps[field(blob, off_pos + 4 * j, 4)] = int(blob[off_val + j])
+            exps[field(blob, off_pos + 4 * j, 4)] = bits_at(vals, j, vb)
     out = []
     for i in range(n):
         a, e = bits_at(sm, i, sb), exps[i]
@@ -129,6 +139,7 @@ def py_decode(blob, n, v, dec):
 
 def read_golden(path):
     var = dec = words = None
+    escapes = 1
     blob, in_blob = [], False
     for line in open(path):
         line = line.split("#")[0].strip()
@@ -136,6 +147,8 @@ def read_golden(path):
             continue
         if line.startswith("variant:"):
             var = [int(t) for t in line[8:].split()]
+        elif line.startswith("escapes:"):
+            escapes = int(line[8:])
         elif line.startswith("dec:"):
             dec = [int(t) for t in line[4:].split()]
         elif line.startswith("words:"):
@@ -148,17 +161,18 @@ def read_golden(path):
             blob += [int(t, 16) for t in line.split()]
     d = np.zeros(16, np.uint8)
     d[:len(dec)] = dec
-    return ov.variant(*var), d, words, np.array(blob, np.uint8)
+    return ov.variant(*var), d, words, np.array(blob, np.uint8), escapes
 
 
 @pytest.mark.parametrize("name", ["hand_stream_variant_bf16_top3_chunk256.txt",
                                   "hand_stream_variant_e4m3_sentinel.txt",
-                                  "hand_stream_variant_bf16_abs32.txt"])
+                                  "hand_stream_variant_bf16_abs32.txt",
+                                  "hand_stream_variant_e5m2_top2_values5.txt"])
 def test_hand_assembled_variant_streams(name):
-    v, dec, words, blob = read_golden(os.path.join(GOLDEN, name))
+    v, dec, words, blob, escapes = read_golden(os.path.join(GOLDEN, name))
     x = np.array(words, WORD[v.dtype])
     got, m = ov.compress(x, v, dec)
-    assert m == 1
+    assert m == escapes
     assert got.size == blob.size and np.array_equal(got, blob), np.flatnonzero(got != blob)[:8]
     assert np.array_equal(ov.decompress(blob, x.size, v, dec), x)
     assert np.array_equal(py_decode(blob, x.size, v, dec), x)
@@ -177,6 +191,30 @@ def test_printed_ratios_of_the_ablated_formats():
         assert abs(ratio - want) < 0.0006, (vid(v), ratio)
 
 
+def test_printed_fp8_ratios_fix_the_width_of_an_escape_value():
+    """Table "FP8 codec throughput and compression ratio": E5M2 top-16 at 0.16 % escapes gives 1.136 -- only with
+    whole-byte escape values; E5M2 top-8 at 7.72 % gives 1.049 and E4M3 top-8 at 7.83 % gives 0.933 -- only with the
+    exponent in its own width (5 and 4 bits).  A printed ratio counts as reproduced if the payload ratio at some
+    escape rate inside the rounding interval of the printed one rounds to it, or lies above it by less than 0.001
+    (the paper's ratios include some metadata it does not itemise: its 1.324 is 1.329 by its own formula)."""
+    n = 1 << 26
+
+    def reproduced(v, eps, want):
+        lo = n / ov.payload_bytes(n, round((eps + 0.00005) * n), v)      # ratio falls as the escape rate grows
+        hi = n / ov.payload_bytes(n, round((eps - 0.00005) * n), v)
+        return lo - 0.0005 - 0.001 <= want <= hi + 0.0005
+
+    rows = ((ov.E5M2, 4, 16, 0.0016, 1.136, 8), (ov.E5M2, 3, 8, 0.0772, 1.049, 5), (ov.E4M3, 3, 8, 0.0783, 0.933, 4))
+    for dt, cb, k, eps, want, vb in rows:
+        assert reproduced(ov.variant(dt, cb, k, ov.ESC_POS, 1024, vb), eps, want), (dt, k, vb)
+    # and the other width of each fails: the table needs both formats
+    assert not reproduced(ov.variant(ov.E5M2, 3, 8, ov.ESC_POS, 1024, 8), 0.0772, 1.049)
+    assert not reproduced(ov.variant(ov.E4M3, 3, 8, ov.ESC_POS, 1024, 8), 0.0783, 0.933)
+    # (E5M2 top-16 with 5-bit values: 1.1374, which the slack for metadata would still let pass; what excludes it is
+    # the main format's own pin, which has no slack: tests/golden/paper_ratio_pairs.txt, kind "exact")
+    assert round(n / ov.payload_bytes(n, round(0.0016 * n), ov.variant(ov.E5M2, 4, 16, ov.ESC_POS, 1024, 5)), 3) == 1.137
+
+
 def test_payload_and_total_closed_forms():
     """payload = ceil(N sb / 8) + ceil(N cb / 8) + M (position bytes + 1): the size formula of section 3.2
     with the widths of each ablation; total adds header, offset table and 256-byte alignment."""
@@ -185,10 +223,10 @@ def test_payload_and_total_closed_forms():
         pb = {ov.ESC_POS: 2 if v.chunk > 256 else 1, ov.ESC_SENTINEL: 0, ov.ESC_ABS32: 4}[v.escape_mode]
         for n, m in ((0, 0), (1, 0), (1, 1), (255, 3), (256, 256), (1023, 7), (1024, 0), (1025, 1025), (4099, 12),
                      (1 << 20, 1234)):
-            assert ov.payload_bytes(n, m, v) == -(-n * sb // 8) + -(-n * cb // 8) + m * (pb + 1)
+            assert ov.payload_bytes(n, m, v) == -(-n * sb // 8) + -(-n * cb // 8) + m * pb + -(-m * vb_of(v) // 8)
             tab = 0 if v.escape_mode == ov.ESC_ABS32 else 4 * (-(-n // v.chunk) + 1)
             assert ov.total_bytes(n, m, v) == (a256(64 + tab) + a256(-(-n * sb // 8)) + a256(-(-n * cb // 8))
-                                               + a256(m * pb) + m)
+                                               + a256(m * pb) + -(-m * vb_of(v) // 8))
 
 
 def test_zero_escapes_give_the_dense_ratio():
