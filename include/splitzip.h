@@ -372,8 +372,9 @@ int splitzip_decompress_batch_paged(const splitzip_ditem* items, uint32_t n_item
  *   code plane ceil(N cb / 8) B; both planes are LSB-first bit streams
  *   esc_pos    u16[M] (chunk > 256) or u8[M]; nothing in the sentinel mode;
  *              u32[M] element indices in the absolute mode
- *   esc_val    u8[M]
- * With (BF16 or E5M2, 4, 16, SPLITZIP_ESC_POS, 1024) every byte behind the
+ *   esc_val    u8[M], or M values of value_bits bits each (header byte 14 holds
+ *              value_bits then, else 0)
+ * With (BF16 or E5M2, 4, 16, SPLITZIP_ESC_POS, 1024, whole-byte values) every byte behind the
  * header equals the main format's stream. */
 typedef enum {
   SPLITZIP_ESC_POS = 0,      /* chunk-relative positions + exponents (the main format's way) */
@@ -387,6 +388,10 @@ typedef struct {
   uint32_t k;           /* codebook entries in use: 1 .. 2^code_bits (one less in the sentinel mode) */
   uint32_t escape_mode; /* splitzip_escape_mode */
   uint32_t chunk_elems; /* 256 or 1024; ignored in the absolute mode */
+  uint32_t value_bits;  /* bits per escape value: 0 or 8 = a whole byte (the main format's record); or the exponent
+                           field's own width, 5 for E5M2 and 4 for E4M3: the value section is then an LSB-first bit
+                           stream of ceil(M value_bits / 8) bytes.  The top-8 columns of the paper's FP8 table (ratios
+                           1.049 and 0.933) count 21 and 20 bits per escape, i.e. this width. */
 } splitzip_variant;
 
 /* 1 if the library can run this variant, else 0 */
@@ -412,8 +417,9 @@ int splitzip_variant_codebook_from_dec(const uint8_t* dec, const splitzip_varian
  * for the main calls) and the error codes are those of splitzip_compress and
  * splitzip_decompress; d_workspace needs splitzip_variant_workspace_bytes and
  * 16-byte alignment.  Four kernel launches per compress call (dense pass,
- * two for the scan of the per-chunk counts, escape pass), one per decompress
- * call (two in the absolute mode), all on `stream`. */
+ * two for the scan of the per-chunk counts, escape pass; a fifth packs values
+ * narrower than a byte), one per decompress call (two in the absolute mode),
+ * all on `stream`. */
 int splitzip_variant_compress(const void* d_in, uint64_t n_elems, const splitzip_variant* v,
                               const splitzip_codebook* cb, void* d_out, size_t out_capacity, void* d_workspace,
                               size_t workspace_bytes, splitzip_sizes* d_sizes, void* stream);

@@ -59,11 +59,11 @@ class _CPaged(C.Structure):
 class Variant(C.Structure):
     """splitzip_variant: one of the formats of the paper's ablations"""
     _fields_ = [("dtype", C.c_uint32), ("code_bits", C.c_uint32), ("k", C.c_uint32), ("escape_mode", C.c_uint32),
-                ("chunk_elems", C.c_uint32)]
+                ("chunk_elems", C.c_uint32), ("value_bits", C.c_uint32)]
 
     def __repr__(self):
         return (f"Variant(dtype={self.dtype}, code_bits={self.code_bits}, k={self.k}, "
-                f"escape_mode={self.escape_mode}, chunk_elems={self.chunk_elems})")
+                f"escape_mode={self.escape_mode}, chunk_elems={self.chunk_elems}, value_bits={self.value_bits})")
 
 
 _lib = None
@@ -545,8 +545,9 @@ def traffic_probe_shape(src: torch.Tensor, read_bytes: int, dst: torch.Tensor, w
 
 # ---- format variants of the ablations -----------------------------------------------------------
 
-def variant(dtype: int, code_bits: int = 4, k: int = 16, escape_mode: int = 0, chunk_elems: int = 1024) -> Variant:
-    return Variant(dtype, code_bits, k, escape_mode, chunk_elems)
+def variant(dtype: int, code_bits: int = 4, k: int = 16, escape_mode: int = 0, chunk_elems: int = 1024,
+            value_bits: int = 0) -> Variant:
+    return Variant(dtype, code_bits, k, escape_mode, chunk_elems, value_bits)
 
 
 def variant_supported(v: Variant) -> bool:

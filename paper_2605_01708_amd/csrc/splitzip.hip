@@ -108,6 +108,7 @@ bool variant_ok(const splitzip_variant* v) {
   const uint32_t kmax = v->escape_mode == SPLITZIP_ESC_SENTINEL ? codes - 1 : codes;
   if (v->k < 1 || v->k > kmax || v->k > v_exp_values(v->dtype)) return false;
   if (v->escape_mode != SPLITZIP_ESC_ABS32 && v->chunk_elems != 256 && v->chunk_elems != 1024) return false;
+  if (v->value_bits != 0 && v->value_bits != 8 && v->value_bits != v_exp_bits(v->dtype)) return false;
   return true;
 }
 
@@ -133,6 +134,7 @@ void variant_layout(uint64_t n, const splitzip_variant* v, VArgs* a) {
   a->dtype = v->dtype; a->code_bits = v->code_bits; a->k = v->k; a->mode = v->escape_mode;
   a->chunk_shift = absolute || v->chunk_elems == 1024 ? 10 : 8;
   a->pos_bytes = v_pos_bytes(v->escape_mode, v->chunk_elems);
+  a->val_bits = v->value_bits ? v->value_bits : 8u;
   a->n_chunks = (n + (1ull << a->chunk_shift) - 1) >> a->chunk_shift;
   a->sm_bytes = (n * v_sm_bits(v->dtype) + 7) / 8;
   a->code_bytes = (n * v->code_bits + 7) / 8;
@@ -151,7 +153,7 @@ void variant_tables(const splitzip_variant* v, const splitzip_codebook* cb, VArg
   a->hdr[0] = 0x31505A53u;   // "SZP1"
   a->hdr[1] = 2u | (a->dtype << 16) | (a->code_bits << 24);
   a->hdr[2] = a->mode == SPLITZIP_ESC_ABS32 ? 0u : 1u << a->chunk_shift;
-  a->hdr[3] = a->mode | (a->k << 8);
+  a->hdr[3] = a->mode | (a->k << 8) | ((a->val_bits == 8 ? 0u : a->val_bits) << 16);
   a->hdr[4] = (uint32_t)a->n;
   a->hdr[5] = (uint32_t)(a->n >> 32);
   for (int i = 0; i < 4; ++i)
@@ -208,7 +210,7 @@ size_t splitzip_variant_total_bytes(uint64_t n_elems, uint64_t n_escapes, const 
   if (!variant_ok(v) || (n_elems >> 32)) return 0;
   VArgs a;
   variant_layout(n_elems, v, &a);
-  return a.off_pos + a256(a.pos_bytes * n_escapes) + n_escapes;
+  return a.off_pos + a256(a.pos_bytes * n_escapes) + v_val_bytes(n_escapes, a.val_bits);
 }
 
 size_t splitzip_variant_compress_bound(uint64_t n_elems, const splitzip_variant* v) {
@@ -219,7 +221,8 @@ size_t splitzip_variant_workspace_bytes(uint64_t n_elems, const splitzip_variant
   if (!variant_ok(v) || (n_elems >> 32)) return 0;
   VArgs a;
   variant_layout(n_elems, v, &a);
-  return a256(4 * a.n_chunks + 4) + a256(4 * (a.n_chunks + 1)) + a256(4 * (uint64_t)a.n_tiles);
+  return a256(4 * a.n_chunks + 4) + a256(4 * (a.n_chunks + 1)) + a256(4 * (uint64_t)a.n_tiles) +
+         (a.val_bits == 8 ? 0 : a256(n_elems));   // values narrower than a byte are packed from whole bytes kept here
 }
 
 int splitzip_variant_codebook_from_dec(const uint8_t* dec, const splitzip_variant* v, splitzip_codebook* out) {
@@ -287,6 +290,7 @@ int splitzip_variant_compress(const void* d_in, uint64_t n_elems, const splitzip
   a.offs = v->escape_mode == SPLITZIP_ESC_ABS32 ? reinterpret_cast<uint32_t*>(ws + a256(4 * a.n_chunks + 4))
                                                 : reinterpret_cast<uint32_t*>(a.out + a.off_tab);
   a.tile_sums = reinterpret_cast<uint32_t*>(ws + a256(4 * a.n_chunks + 4) + a256(4 * (a.n_chunks + 1)));
+  a.val_stage = ws + a256(4 * a.n_chunks + 4) + a256(4 * (a.n_chunks + 1)) + a256(4 * (uint64_t)a.n_tiles);
   variant_tables(v, cb, &a);
   const uint8_t escape = (uint8_t)(0x80u | (v->escape_mode == SPLITZIP_ESC_SENTINEL ? (1u << v->code_bits) - 1u : 0u));
   for (unsigned e = 0; e < 256; ++e) a.lut[e] = cb->member[e] ? cb->enc[e] : escape;
@@ -298,6 +302,13 @@ int splitzip_variant_compress(const void* d_in, uint64_t n_elems, const splitzip
   hipLaunchKernelGGL(v_tile_sum_kernel, dim3(a.n_tiles), dim3(1024), 0, st, a);
   hipLaunchKernelGGL(v_scan_kernel, dim3(a.n_tiles), dim3(1024), 0, st, a);
   if (grid) SPLITZIP_V_DISPATCH1(v_emit_kernel, dim3(grid), dim3(kThreads), st, a);
+  if (grid && a.val_bits != 8) {
+    // M is known to the device only: a grid that strides over however many bytes the section has
+    uint64_t g = (v_val_bytes(n_elems, a.val_bits) + kThreads - 1) / kThreads;
+    const uint64_t cap = (uint64_t)cu_count() * 8;
+    if (g > cap) g = cap;
+    hipLaunchKernelGGL(v_pack_kernel, dim3((unsigned)g), dim3(kThreads), 0, st, a);
+  }
   return hipGetLastError() == hipSuccess ? SPLITZIP_OK : SPLITZIP_ERR_HIP;
 }
 

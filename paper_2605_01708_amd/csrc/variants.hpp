@@ -43,6 +43,9 @@ struct VFmt<SPLITZIP_FP8_E4M3> {
 
 __host__ __device__ inline uint32_t v_sm_bits(uint32_t dtype) { return dtype == SPLITZIP_BF16 ? 8u : dtype == SPLITZIP_FP8_E5M2 ? 3u : 4u; }
 __host__ __device__ inline uint32_t v_exp_values(uint32_t dtype) { return dtype == SPLITZIP_BF16 ? 256u : dtype == SPLITZIP_FP8_E5M2 ? 32u : 16u; }
+__host__ __device__ inline uint32_t v_exp_bits(uint32_t dtype) { return dtype == SPLITZIP_BF16 ? 8u : dtype == SPLITZIP_FP8_E5M2 ? 5u : 4u; }
+// bytes of the value section for m escapes of vb bits each
+__host__ __device__ inline uint64_t v_val_bytes(uint64_t m, uint32_t vb) { return (m * vb + 7) / 8; }
 __host__ __device__ inline uint32_t v_pos_bytes(uint32_t mode, uint32_t chunk) {
   return mode == SPLITZIP_ESC_SENTINEL ? 0u : mode == SPLITZIP_ESC_ABS32 ? 4u : chunk > 256u ? 2u : 1u;
 }
@@ -56,6 +59,8 @@ struct VArgs {
   uint32_t dtype, code_bits, k, mode;
   uint32_t chunk_shift;  // log2 of the chunk the counts are kept for (10 in the absolute mode: the wave's block)
   uint32_t pos_bytes;
+  uint32_t val_bits;     // bits per escape value: 8, or the exponent field's own width
+  uint8_t* val_stage;    // compress, val_bits < 8: workspace for the values as whole bytes, until v_pack_kernel packs them
   uint64_t n_chunks;     // of that chunk size
   uint64_t sm_bytes, code_bytes;
   uint64_t off_tab, off_sm, off_code, off_pos;
@@ -231,7 +236,7 @@ __global__ __launch_bounds__(1024) void v_scan_kernel(const VArgs a) {
   if (b != 0) return;
   if (tid == 0) a.offs[a.n_chunks] = M;
 
-  const uint64_t pos_sec = a256((uint64_t)a.pos_bytes * M), total = a.off_pos + pos_sec + M;
+  const uint64_t pos_sec = a256((uint64_t)a.pos_bytes * M), total = a.off_pos + pos_sec + v_val_bytes(M, a.val_bits);
   // zero padding: behind the table, behind what the dense pass covered of each plane, behind the positions
   const uint64_t tab_end = a.mode == SPLITZIP_ESC_ABS32 ? kHeaderBytes : a.off_tab + 4 * (a.n_chunks + 1);
   for (uint64_t i = tab_end + tid; i < a.off_sm; i += 1024) a.out[i] = 0;
@@ -306,13 +311,41 @@ __global__ __launch_bounds__(kThreads) void v_emit_kernel(const VArgs a) {
         const uint64_t at = a.off_pos + 4ull * r;
         if (at + 4 <= a.capacity) *reinterpret_cast<uint32_t*>(a.out + at) = (uint32_t)i;
       }
-      if (off_val + r < a.capacity) a.out[off_val + r] = (uint8_t)F::exponent(x[j]);
+      if (a.val_bits != 8) a.val_stage[r] = (uint8_t)F::exponent(x[j]);
+      else if (off_val + r < a.capacity) a.out[off_val + r] = (uint8_t)F::exponent(x[j]);
       ++r;
     }
   }
 }
 
+// compress pass 4, for values narrower than a byte: the value section as an LSB-first bit stream of val_bits per
+// value, from the whole-byte values of the workspace.  Every thread makes whole bytes of the section from the
+// values that overlap them, so no two threads write the same byte.
+__global__ __launch_bounds__(kThreads) void v_pack_kernel(const VArgs a) {
+  const uint32_t M = a.offs[a.n_chunks], vb = a.val_bits;
+  const uint64_t off_val = a.off_pos + a256((uint64_t)a.pos_bytes * M), bytes = v_val_bytes(M, vb);
+  for (uint64_t b = (uint64_t)blockIdx.x * kThreads + threadIdx.x; b < bytes; b += (uint64_t)gridDim.x * kThreads) {
+    uint32_t byte = 0;
+    for (uint64_t r = 8 * b / vb; r < M && r * vb < 8 * b + 8; ++r) {
+      const int64_t shift = (int64_t)(r * vb) - (int64_t)(8 * b);   // where value r starts, relative to this byte
+      const uint32_t v = a.val_stage[r];
+      byte |= shift >= 0 ? v << shift : v >> -shift;
+    }
+    if (off_val + b < a.capacity) a.out[off_val + b] = (uint8_t)byte;
+  }
+}
+
 // ---- decompress -----------------------------------------------------------------------------
+
+// escape value idx of a stream whose value section starts at off_val (the section is known to lie inside the stream)
+__device__ inline uint32_t v_value(const VArgs& a, uint64_t off_val, uint64_t idx) {
+  if (a.val_bits == 8) return a.in[off_val + idx];
+  const uint64_t bit = idx * a.val_bits;
+  const uint32_t sh = (uint32_t)(bit & 7u);
+  uint32_t v = a.in[off_val + (bit >> 3)] >> sh;
+  if (sh + a.val_bits > 8) v |= (uint32_t)a.in[off_val + (bit >> 3) + 1] << (8 - sh);
+  return v & ((1u << a.val_bits) - 1u);
+}
 
 // an inconsistent header or record: sticky bit in the caller's sizes record (nullable)
 __device__ inline void v_flag_bad(const VArgs& a) {
@@ -326,8 +359,8 @@ __device__ inline bool v_check_header(const VArgs& a, uint32_t hw, int lane, uin
   const uint64_t M = __builtin_amdgcn_readlane(hw, 6) | ((uint64_t)__builtin_amdgcn_readlane(hw, 7) << 32);
   const uint64_t total = __builtin_amdgcn_readlane(hw, 8) | ((uint64_t)__builtin_amdgcn_readlane(hw, 9) << 32);
   *m_out = (uint32_t)M;
-  return __builtin_amdgcn_ballot_w64(!word_ok) == 0 && M <= a.n && total == a.off_pos + a256(a.pos_bytes * M) + M &&
-         total <= a.capacity;
+  return __builtin_amdgcn_ballot_w64(!word_ok) == 0 && M <= a.n &&
+         total == a.off_pos + a256(a.pos_bytes * M) + v_val_bytes(M, a.val_bits) && total <= a.capacity;
 }
 
 // One block of 1024 elements per wave.  Everything that depends on nothing -- the header, the offsets of the
@@ -396,7 +429,7 @@ __global__ __launch_bounds__(kThreads) void v_decode_kernel(const VArgs a) {
       rec_n[q] = hi - lo;
       if ((uint32_t)lane < hi - lo) {
         rec_p[q] = PB == 2 ? reinterpret_cast<const uint16_t*>(a.in + a.off_pos)[lo + lane] : a.in[a.off_pos + lo + lane];
-        rec_e[q] = a.in[off_val + lo + lane];
+        rec_e[q] = v_value(a, off_val, lo + lane);
       }
     }
   }
@@ -440,7 +473,7 @@ __global__ __launch_bounds__(kThreads) void v_decode_kernel(const VArgs a) {
       for (int j = 0; j < 8; ++j) {
         if (!((sent >> j) & 1u)) continue;
         uint32_t e = 0;
-        if (r < r_end && r < M) e = a.in[off_val + r];
+        if (r < r_end && r < M) e = v_value(a, off_val, r);
         else bad = true;
         if (e >= (uint32_t)F::EXPS) { bad = true; e = 0; }
         const uint32_t av = (uint32_t)(smw >> (F::SB * j)) & ((1u << F::SB) - 1u);
@@ -467,7 +500,7 @@ __global__ __launch_bounds__(kThreads) void v_decode_kernel(const VArgs a) {
         uint32_t p = rec_p[q], e = rec_e[q];
         if (i >= 64) {   // a chunk with more than 64 escapes: the rest is fetched here
           p = PB == 2 ? reinterpret_cast<const uint16_t*>(a.in + a.off_pos)[rec_lo[q] + i] : a.in[a.off_pos + rec_lo[q] + i];
-          e = a.in[off_val + rec_lo[q] + i];
+          e = v_value(a, off_val, rec_lo[q] + i);
         }
         // a chunk's positions ascend: the record before this one (the lane below holds it, or memory does)
         uint32_t before = (uint32_t)__shfl_up((int)p, 1);
@@ -512,7 +545,7 @@ __global__ __launch_bounds__(kThreads) void v_scatter_kernel(const VArgs a) {
   bool bad = false;
   for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < M; i += (uint64_t)gridDim.x * kThreads) {
     const uint64_t p = reinterpret_cast<const uint32_t*>(a.in + a.off_pos)[i];
-    const uint32_t e = a.in[off_val + i];
+    const uint32_t e = v_value(a, off_val, i);
     // the element indices ascend
     if (p >= a.n || e >= (uint32_t)F::EXPS || (i > 0 && p <= reinterpret_cast<const uint32_t*>(a.in + a.off_pos)[i - 1])) { bad = true; continue; }
     if (F::ES == 2) {

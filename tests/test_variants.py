@@ -25,12 +25,17 @@ def variants():
     for cb, k, mode, chunk in ((3, 8, sz.ESC_POS, 1024), (3, 7, sz.ESC_SENTINEL, 1024), (3, 8, sz.ESC_ABS32, 0),
                                (3, 8, sz.ESC_POS, 256)):
         out.append((sz.variant(sz.FP8_E4M3, cb, k, mode, chunk), ov.variant(ov.E4M3, cb, k, mode, chunk)))
+    # escape values in the exponent's own width (the top-8 columns of the paper's FP8 table), in every escape mode
+    for dt, odt, vb in ((sz.FP8_E5M2, ov.E5M2, 5), (sz.FP8_E4M3, ov.E4M3, 4)):
+        for cb, k, mode, chunk in ((3, 8, sz.ESC_POS, 1024), (3, 7, sz.ESC_SENTINEL, 256), (3, 8, sz.ESC_ABS32, 0)):
+            out.append((sz.variant(dt, cb, k, mode, chunk, vb), ov.variant(odt, cb, k, mode, chunk, vb)))
+    out.append((sz.variant(sz.FP8_E5M2, 4, 16, sz.ESC_POS, 1024, 5), ov.variant(ov.E5M2, 4, 16, ov.ESC_POS, 1024, 5)))
     return out
 
 
 def vid(pair):
     v = pair[0]
-    return f"dt{v.dtype}-b{v.code_bits}-k{v.k}-m{v.escape_mode}-c{v.chunk_elems}"
+    return f"dt{v.dtype}-b{v.code_bits}-k{v.k}-m{v.escape_mode}-c{v.chunk_elems}" + (f"-v{v.value_bits}" if v.value_bits else "")
 
 
 def words(dt, tokens, seed, layer=0, kind="K", device="cpu"):
