@@ -688,14 +688,25 @@ __global__ __launch_bounds__(kTileThreads) void compress_finish_kernel(const Til
   // the records fetched ahead
   const uint32_t cl = s_cnt[sl];
   if (!(cl & kRedo) && sj < cl) fin.put(first + s_tp[sl] + sj, rec_ahead & 0xffffu, rec_ahead >> 16);
-  // the rest of the slots of tiles with more records than that
-  for (uint32_t l = 0; l < kGroup; ++l) {
-    const uint32_t c = s_cnt[l];
-    if ((c & kRedo) || c <= kSlotAhead) continue;
-    const uint32_t* slot = G.slots + (uint64_t)(t0 + l) * a.slot_cap;
-    for (uint32_t j = kSlotAhead + tid; j < c; j += kTileThreads) {
-      const uint32_t rec = slot[j];
-      fin.put(first + s_tp[l] + j, rec & 0xffffu, rec >> 16);
+  // The rest of the slots of tiles with more records than that: rank r of the group belongs to the last tile that
+  // starts at or before r.  Two records per thread are on their way at a time.
+  const uint32_t group_total = s_tp[kGroup];
+  if (group_total > kSlotAhead) {   // else no tile can have more than kSlotAhead records
+    auto locate = [&](uint32_t r, uint32_t& l, uint32_t& j) -> bool {
+      l = 0;
+#pragma unroll
+      for (uint32_t step = kGroup / 2; step; step >>= 1)
+        if (s_tp[l + step] <= r) l += step;
+      j = r - s_tp[l];
+      return r < group_total && j >= kSlotAhead && !(s_cnt[l] & kRedo);
+    };
+    for (uint32_t r = tid; r < group_total; r += 2 * kTileThreads) {
+      uint32_t l0, j0, l1, j1, rec0 = 0, rec1 = 0;
+      const bool take0 = locate(r, l0, j0), take1 = locate(r + kTileThreads, l1, j1);
+      if (take0) rec0 = G.slots[(uint64_t)(t0 + l0) * a.slot_cap + j0];
+      if (take1) rec1 = G.slots[(uint64_t)(t0 + l1) * a.slot_cap + j1];
+      if (take0) fin.put(first + r, rec0 & 0xffffu, rec0 >> 16);
+      if (take1) fin.put(first + r + kTileThreads, rec1 & 0xffffu, rec1 >> 16);
     }
   }
   if (g == 0 && wave == 0) compress_write_trailer(P, a.dec_of(item), a.sizes + item, M, 0u, lane);
