@@ -617,7 +617,9 @@ int compress_launch(const splitzip_item* items, uint32_t n_items, int dtype, con
       const uint64_t per_tile = tiles_max ? a.stage_cap / 4 / tiles_max : 0;
       a.slot_cap = (uint32_t)(per_tile < kSlotCapMost ? per_tile : kSlotCapMost);
     }
-    a.use_group_sums = tiles_max > kDirectTiles ? 1u : 0u;
+    // A finishing workgroup that sums all tile counts of its tensor itself reads 4 bytes per tile: fine for one
+    // tensor of up to kDirectTiles tiles (and one launch fewer), too much for the thousands of workgroups of a batch.
+    a.use_group_sums = tiles_max > kDirectTiles || k > 1 ? 1u : 0u;
     a.paging = paging;
     const unsigned groups_max = (unsigned)((tiles_max + kGroup - 1) / kGroup), sums_max = (unsigned)((tiles_max + kSumGroup - 1) / kSumGroup);
     if (tiles_max) {

@@ -523,9 +523,45 @@ def hooks():
     sz.internal_test_hooks()
 
 
+def test_compress_beside_other_work_on_the_device():
+    """The compress calls wait for nothing -- no workgroup for another, no launch for room on the device: with a
+    long run of elementwise kernels keeping the device busy on another stream (what a prefill worker's model does
+    beside the codec), single and batch calls complete and give the streams they give on a quiet device."""
+    dtype = sz.BF16
+    n = 8 * 1024 * 1024
+    cb_or = calibrated(dtype)
+    cb = gpu_codebook(cb_or)
+    xs = [kv_synth.kv_bf16(n // 1024, 0, layer, "K", device="cuda") for layer in range(6)]
+    refs = [oracle.compress(kv_synth.to_numpy_words(x), cb_or) for x in xs[:2]]
+    outs = [torch.empty(sz.compress_bound(n, dtype), dtype=torch.uint8, device="cuda") for _ in xs]
+    quiet = [torch.empty_like(o) for o in outs]
+    ws = sz.Workspace(n, dtype)
+    rec, rec_q, one = sz.new_sizes_array(len(xs)), sz.new_sizes_array(len(xs)), sz.new_sizes()
+    sz.compress_batch(xs, [cb] * len(xs), quiet, ws, rec_q)
+    torch.cuda.synchronize()
+    want = sz.read_sizes_array(rec_q)
+    busy = torch.ones(1 << 29, dtype=torch.float32, device="cuda")          # 2 GiB: each pass over it takes about a millisecond
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        for _ in range(40):
+            busy.mul_(1.0001)
+    for rep in range(10):
+        sz.compress_batch(xs, [cb] * len(xs), outs, ws, rec)
+        sz.compress(xs[0], cb, outs[0], ws, one)
+    done_first = not side.query()                                            # the side stream is still busy: the calls ran beside it
+    torch.cuda.synchronize()
+    assert sz.read_sizes_array(rec) == want and sz.read_sizes(one) == want[0]
+    for k in range(len(xs)):
+        assert torch.equal(outs[k][: want[k][0]], quiet[k][: want[k][0]]), f"tensor {k} differs beside other work"
+    for k, (ref, m) in enumerate(refs):
+        assert want[k] == (ref.size, m, 0) and np.array_equal(outs[k][: ref.size].cpu().numpy(), ref)
+    print("codec calls enqueued while the side stream was still running:", done_first, flush=True)
+
+
 def test_two_compress_calls_on_two_streams_at_once():
-    """two single-tensor compress calls, each with its own workspace, may run side by side: both launches fit the
-    device together, so neither can starve the other of room (streams and results as in the serial case)"""
+    """two single-tensor compress calls, each with its own workspace, may run side by side on two streams (streams and
+    results as in the serial case)"""
     n = 32768 * 1024 // 4
     cb_or = calibrated(sz.BF16)
     cb = gpu_codebook(cb_or)
