@@ -358,8 +358,9 @@ int splitzip_decompress_batch_paged(const splitzip_ditem* items, uint32_t n_item
  * 256-element chunks with 8-bit positions, 32-bit absolute positions without
  * chunks, and E4M3 words.  These calls exist to measure those formats beside
  * the main one on the same device; they run through one generic set of kernels
- * (dense pass with per-chunk counts, scan, escape pass; dense decode with the
- * correction applied in LDS) that is NOT the tuned path of splitzip_compress
+ * (dense pass with per-chunk counts and staged escape records, sums, finishing
+ * pass; dense decode with the correction applied in LDS) that is NOT the tuned
+ * path of splitzip_compress
  * and splitzip_decompress.  The main format is one of the variants, so all of
  * them can be compared through the same kernels.
  *
@@ -400,7 +401,8 @@ int splitzip_variant_supported(const splitzip_variant* v);
 /* Sizes as for the main format (0 for an unsupported variant or n_elems >= 2^32). */
 size_t splitzip_variant_total_bytes(uint64_t n_elems, uint64_t n_escapes, const splitzip_variant* v);
 size_t splitzip_variant_compress_bound(uint64_t n_elems, const splitzip_variant* v);
-/* Device scratch of one compress call: per-chunk counts and their offsets.  No initialisation needed. */
+/* Device scratch of one compress call: per-chunk counts, their sums, and a slot of staged escape records per 1024
+ * elements (about n_elems / 2 bytes).  No initialisation needed. */
 size_t splitzip_variant_workspace_bytes(uint64_t n_elems, const splitzip_variant* v);
 
 /* Section 3.3 with v->k entries: counts the exponents of a HOST sample and
@@ -416,10 +418,10 @@ int splitzip_variant_codebook_from_dec(const uint8_t* dec, const splitzip_varian
  * the sizes record (total_bytes, n_escapes, status; OVERFLOW and BAD_STREAM as
  * for the main calls) and the error codes are those of splitzip_compress and
  * splitzip_decompress; d_workspace needs splitzip_variant_workspace_bytes and
- * 16-byte alignment.  Four kernel launches per compress call (dense pass,
- * two for the scan of the per-chunk counts, escape pass; a fifth packs values
- * narrower than a byte), one per decompress call (two in the absolute mode),
- * all on `stream`. */
+ * 16-byte alignment.  Three kernel launches per compress call (dense pass
+ * that also stages the escape records, sums of the per-chunk counts, finishing
+ * pass; a fourth packs values narrower than a byte), one per decompress call
+ * (two in the absolute mode), all on `stream`. */
 int splitzip_variant_compress(const void* d_in, uint64_t n_elems, const splitzip_variant* v,
                               const splitzip_codebook* cb, void* d_out, size_t out_capacity, void* d_workspace,
                               size_t workspace_bytes, splitzip_sizes* d_sizes, void* stream);

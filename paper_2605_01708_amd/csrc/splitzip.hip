@@ -221,7 +221,9 @@ size_t splitzip_variant_workspace_bytes(uint64_t n_elems, const splitzip_variant
   if (!variant_ok(v) || (n_elems >> 32)) return 0;
   VArgs a;
   variant_layout(n_elems, v, &a);
+  const uint64_t n_blocks = (n_elems + kVBlock - 1) / kVBlock;
   return a256(4 * a.n_chunks + 4) + a256(4 * (a.n_chunks + 1)) + a256(4 * (uint64_t)a.n_tiles) +
+         a256(4ull * kVSlotCap * n_blocks) +         // the blocks' slots of staged escape records
          (a.val_bits == 8 ? 0 : a256(n_elems));   // values narrower than a byte are packed from whole bytes kept here
 }
 
@@ -290,18 +292,19 @@ int splitzip_variant_compress(const void* d_in, uint64_t n_elems, const splitzip
   a.offs = v->escape_mode == SPLITZIP_ESC_ABS32 ? reinterpret_cast<uint32_t*>(ws + a256(4 * a.n_chunks + 4))
                                                 : reinterpret_cast<uint32_t*>(a.out + a.off_tab);
   a.tile_sums = reinterpret_cast<uint32_t*>(ws + a256(4 * a.n_chunks + 4) + a256(4 * (a.n_chunks + 1)));
-  a.val_stage = ws + a256(4 * a.n_chunks + 4) + a256(4 * (a.n_chunks + 1)) + a256(4 * (uint64_t)a.n_tiles);
+  const uint64_t blocks = (n_elems + kVBlock - 1) / kVBlock;
+  a.slots = reinterpret_cast<uint32_t*>(ws + a256(4 * a.n_chunks + 4) + a256(4 * (a.n_chunks + 1)) + a256(4 * (uint64_t)a.n_tiles));
+  a.val_stage = reinterpret_cast<uint8_t*>(a.slots) + a256(4ull * kVSlotCap * blocks);
   variant_tables(v, cb, &a);
   const uint8_t escape = (uint8_t)(0x80u | (v->escape_mode == SPLITZIP_ESC_SENTINEL ? (1u << v->code_bits) - 1u : 0u));
   for (unsigned e = 0; e < 256; ++e) a.lut[e] = cb->member[e] ? cb->enc[e] : escape;
 
   const hipStream_t st = static_cast<hipStream_t>(stream);
-  const uint64_t blocks = (n_elems + kVBlock - 1) / kVBlock;
   const unsigned grid = (unsigned)((blocks + kWaves - 1) / kWaves);
   if (grid) SPLITZIP_V_DISPATCH2(v_dense_kernel, dim3(grid), dim3(kThreads), st, a);
   hipLaunchKernelGGL(v_tile_sum_kernel, dim3(a.n_tiles), dim3(1024), 0, st, a);
-  hipLaunchKernelGGL(v_scan_kernel, dim3(a.n_tiles), dim3(1024), 0, st, a);
-  if (grid) SPLITZIP_V_DISPATCH1(v_emit_kernel, dim3(grid), dim3(kThreads), st, a);
+  const unsigned fgrid = (unsigned)((blocks + kVFinishBlocks - 1) / kVFinishBlocks);
+  SPLITZIP_V_DISPATCH1(v_finish_kernel, dim3(fgrid ? fgrid : 1u), dim3(kThreads), st, a);
   if (grid && a.val_bits != 8) {
     // M is known to the device only: a grid that strides over however many bytes the section has
     uint64_t g = (v_val_bytes(n_elems, a.val_bits) + kThreads - 1) / kThreads;

@@ -3,9 +3,11 @@
 // and "SplitZip on FP8") through one generic set of kernels.  Part of the single translation unit
 // splitzip.hip (included inside its anonymous namespace).
 //
-// These kernels follow the paper's own structure (appendix "Quad64 Vectorized Encoding"): a dense
-// pass that also counts the escapes of every chunk, a scan of the counts, and a second pass over
-// the input that writes the escape records to their final place.  They are deliberately plain --
+// These kernels follow the structure of the tuned path: a dense pass that also counts the escapes of every chunk
+// and stages the escape records of every block of 1024 elements in a slot of the workspace, sums of the counts,
+// and a short finishing pass that ranks the records and moves them to their final place (the paper's own
+// structure, appendix "Quad64 Vectorized Encoding", counts in the dense pass and reads the input a second time
+// to write the records; the first version of these kernels did that).  They are deliberately plain --
 // a block of 1024 elements per wave, eight elements per lane and step, both planes packed as
 // LSB-first bit streams of any width and staged through LDS so that global accesses stay whole
 // dwords -- because their job is to compare the formats with one another on equal terms, the main
@@ -15,6 +17,7 @@
 
 constexpr uint32_t kVBlock = 1024;   // elements a wave handles at a time
 constexpr uint32_t kVStep = 512;     // ... in two steps of 8 elements per lane
+constexpr uint32_t kVSlotCap = 128;  // escape records a block's slot holds (one in eight elements: a block with more is encoded again by the finishing pass)
 
 // per-format field arithmetic: e, a and the inverse (eq. (1) and (2); FP8 by analogy)
 template <int DT>
@@ -68,6 +71,8 @@ struct VArgs {
   uint32_t* offs;        // exclusive offsets, n_chunks + 1: in the stream, or in the workspace in the absolute mode
   uint32_t* tile_sums;   // workspace: escapes per tile of kVScanTile chunks
   uint32_t n_tiles;
+  uint32_t* slots;       // workspace: per block of 1024 elements kVSlotCap records, position in the block | exponent << 16
+
   splitzip_sizes* sizes;
   uint32_t hdr[16];      // the header of a stream of this call, words 6..9 (M, total) left 0
   uint8_t dec[16];
@@ -175,14 +180,25 @@ __global__ __launch_bounds__(kThreads) void v_dense_kernel(const VArgs a) {
     v_lds_settle();   // the staging is written again in the next step
     const uint32_t incl = wave_incl_scan(__popc(esc));
     const uint32_t t31 = __builtin_amdgcn_readlane(incl, 31), t63 = __builtin_amdgcn_readlane(incl, 63);
+    // the block's escape records, in element order, into its slot
+    if (esc) {
+      uint32_t r = (s == 0 ? 0u : carry) + incl - __popc(esc);
+      uint32_t* slot = a.slots + blk * kVSlotCap;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        if (!((esc >> j) & 1u)) continue;
+        if (r < kVSlotCap) slot[r] = (uint32_t)(s * kVStep + lane * 8 + j) | (F::exponent(x[j]) << 16);
+        ++r;
+      }
+    }
     if (a.chunk_shift == 10) {
-      if (s == 0) carry = t63;
-      else if (lane == 0) a.counts[blk] = carry + t63;
+      if (s == 1 && lane == 0) a.counts[blk] = carry + t63;
     } else if (lane == 0) {   // two 256-element chunks per step
       const uint64_t c0 = g >> 8;
       if (c0 < a.n_chunks) a.counts[c0] = t31;
       if (c0 + 1 < a.n_chunks) a.counts[c0 + 1] = t63 - t31;
     }
+    if (s == 0) carry = t63;
   }
 }
 
@@ -214,37 +230,125 @@ __global__ __launch_bounds__(1024) void v_tile_sum_kernel(const VArgs a) {
   if (threadIdx.x == 0) a.tile_sums[blockIdx.x] = all;
 }
 
-// compress pass 2b: exclusive offsets of all chunks; workgroup 0 also writes the header, the sizes record and
-// the zero padding
-__global__ __launch_bounds__(1024) void v_scan_kernel(const VArgs a) {
-  __shared__ uint32_t s_wave[16];
-  const uint32_t tid = threadIdx.x, b = blockIdx.x;
-  // escapes in the tiles before this one, and in all of them
-  uint32_t part = 0, every = 0;
-  for (uint32_t t = tid; t < a.n_tiles; t += 1024) {
-    const uint32_t v = a.tile_sums[t];
-    if (t < b) part += v;
-    every += v;
-  }
-  uint32_t incl, before;
-  const uint32_t base = v_block_sum(part, s_wave, incl, before);
-  const uint32_t M = v_block_sum(every, s_wave, incl, before);
-  const uint64_t c = (uint64_t)b * kVScanTile + tid;
-  const uint32_t mine = c < a.n_chunks ? a.counts[c] : 0u;
-  v_block_sum(mine, s_wave, incl, before);
-  if (c < a.n_chunks) a.offs[c] = base + before + incl - mine;
-  if (b != 0) return;
-  if (tid == 0) a.offs[a.n_chunks] = M;
+constexpr uint32_t kVFinishBlocks = 64;   // blocks of 1024 elements per workgroup of the finishing pass
 
+// where record `rank` of the stream goes: its position in the variant's width (none in the sentinel mode) and its
+// exponent (as a byte of the stream, or of the workspace if values are narrower than a byte: v_pack_kernel)
+__device__ inline void v_put_record(const VArgs& a, uint64_t off_val, uint32_t rank, uint64_t elem, uint32_t e) {
+  if (a.mode == SPLITZIP_ESC_POS) {
+    const uint32_t p = (uint32_t)elem & ((1u << a.chunk_shift) - 1u);
+    const uint64_t at = a.off_pos + (uint64_t)a.pos_bytes * rank;
+    if (at + a.pos_bytes <= a.capacity) {
+      if (a.pos_bytes == 2) *reinterpret_cast<uint16_t*>(a.out + at) = (uint16_t)p;
+      else a.out[at] = (uint8_t)p;
+    }
+  } else if (a.mode == SPLITZIP_ESC_ABS32) {
+    const uint64_t at = a.off_pos + 4ull * rank;
+    if (at + 4 <= a.capacity) *reinterpret_cast<uint32_t*>(a.out + at) = (uint32_t)elem;
+  }
+  if (a.val_bits != 8) a.val_stage[rank] = (uint8_t)e;
+  else if (off_val + rank < a.capacity) a.out[off_val + rank] = (uint8_t)e;
+}
+
+// compress pass 3: one workgroup per kVFinishBlocks blocks.  It sums the counts (the whole tensor's: M; those before
+// its blocks: its first rank), writes its chunks' entries of the offset table, and moves its blocks' records from
+// their slots to their ranks; a block with more records than its slot holds is encoded once more from the words.
+// Workgroup 0 also writes the header, the sizes record and the zero padding.
+template <int DT>
+__global__ __launch_bounds__(kThreads) void v_finish_kernel(const VArgs a) {
+  using F = VFmt<DT>;
+  __shared__ uint8_t lut[256];
+  __shared__ uint32_t s_part[3][kWaves];
+  __shared__ uint32_t s_bp[kVFinishBlocks + 1];   // escapes of the group's blocks before each block
+  const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = blockIdx.x;
+  const uint32_t cpb_shift = 10u - a.chunk_shift;   // log2 of the chunks per block: 0 or 2
+  const uint64_t n_blocks = (a.n + kVBlock - 1) / kVBlock;
+  const uint64_t blk0 = (uint64_t)g * kVFinishBlocks, c0 = blk0 << cpb_shift;
+  lut[tid] = a.lut[tid];
+  // escapes before the group's first chunk and in the whole tensor: whole scan tiles by their sums, the rest by chunk
+  uint32_t before = 0, all = 0;
+  const uint64_t whole = c0 / kVScanTile;
+  for (uint32_t t = tid; t < a.n_tiles; t += kThreads) {
+    const uint32_t v = a.tile_sums[t];
+    all += v;
+    before += t < whole ? v : 0u;
+  }
+  for (uint64_t c = whole * kVScanTile + tid; c < c0 && c < a.n_chunks; c += kThreads) before += a.counts[c];
+  // the group's chunks, one per thread (64 or 256 of them)
+  const uint64_t my_c = c0 + tid;
+  const bool have = tid < (kVFinishBlocks << cpb_shift) && my_c < a.n_chunks;
+  const uint32_t mine = have ? a.counts[my_c] : 0u;
+  const uint32_t incl = wave_incl_scan(mine);
+  before = wave_last(wave_incl_scan(before));
+  all = wave_last(wave_incl_scan(all));
+  if (lane == 63) {
+    s_part[0][wave] = incl;
+    s_part[1][wave] = before;
+    s_part[2][wave] = all;
+  }
+  __syncthreads();
+  uint32_t first = 0, M = 0, waves_before = 0, group_total = 0;
+#pragma unroll
+  for (uint32_t w = 0; w < kWaves; ++w) {
+    waves_before += w < wave ? s_part[0][w] : 0u;
+    group_total += s_part[0][w];
+    first += s_part[1][w];
+    M += s_part[2][w];
+  }
+  const uint32_t excl = waves_before + incl - mine;   // escapes of the group before this thread's chunk
+  if (have && (tid & ((1u << cpb_shift) - 1u)) == 0) s_bp[tid >> cpb_shift] = excl;
+  // blocks behind the tensor's last start where the group ends
+  const uint64_t blocks_here = n_blocks > blk0 ? (n_blocks - blk0 < kVFinishBlocks ? n_blocks - blk0 : kVFinishBlocks) : 0;
+  if (tid >= blocks_here && tid <= kVFinishBlocks) s_bp[tid] = group_total;
+  __syncthreads();
+  if (have && a.mode != SPLITZIP_ESC_ABS32) a.offs[my_c] = first + excl;
+  const uint64_t off_val = a.off_pos + a256((uint64_t)a.pos_bytes * M);
+
+  // records that wait in their blocks' slots: rank r of the group belongs to the last block that starts at or before r
+  for (uint32_t r = tid; r < group_total; r += kThreads) {
+    uint32_t b = 0;
+#pragma unroll
+    for (uint32_t step = kVFinishBlocks / 2; step; step >>= 1)
+      if (s_bp[b + step] <= r) b += step;
+    if (s_bp[b + 1] - s_bp[b] > kVSlotCap) continue;
+    const uint32_t rec = a.slots[(blk0 + b) * kVSlotCap + (r - s_bp[b])];
+    v_put_record(a, off_val, first + r, (blk0 + b) * kVBlock + (rec & 0xffffu), rec >> 16);
+  }
+  // blocks whose records did not fit their slots, a wave each
+  for (uint32_t b = wave; b < blocks_here; b += kWaves) {
+    if (s_bp[b + 1] - s_bp[b] <= kVSlotCap) continue;
+    uint32_t rank = first + s_bp[b];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      const uint64_t g0 = (blk0 + b) * kVBlock + s * kVStep + lane * 8;
+      uint32_t x[8];
+      v_load8<DT>(a, g0, x);
+      uint32_t esc = 0;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) esc |= (uint32_t)(lut[F::exponent(x[j])] >> 7) << j;
+      esc &= (1u << v_nvalid(a, g0)) - 1u;
+      const uint32_t cnt = __popc(esc), sc = wave_incl_scan(cnt);
+      uint32_t r = rank + sc - cnt;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        if (!((esc >> j) & 1u)) continue;
+        v_put_record(a, off_val, r, g0 + j, F::exponent(x[j]));
+        ++r;
+      }
+      rank += __builtin_amdgcn_readlane(sc, 63);
+    }
+  }
+  if (g != 0) return;
+
+  if (tid == 0) a.offs[a.n_chunks] = M;   // the table's last entry; in the absolute mode a word of the workspace, for v_pack_kernel
   const uint64_t pos_sec = a256((uint64_t)a.pos_bytes * M), total = a.off_pos + pos_sec + v_val_bytes(M, a.val_bits);
   // zero padding: behind the table, behind what the dense pass covered of each plane, behind the positions
   const uint64_t tab_end = a.mode == SPLITZIP_ESC_ABS32 ? kHeaderBytes : a.off_tab + 4 * (a.n_chunks + 1);
-  for (uint64_t i = tab_end + tid; i < a.off_sm; i += 1024) a.out[i] = 0;
-  const uint64_t blocks = (a.n + kVBlock - 1) / kVBlock;
-  const uint64_t sm_cov = blocks * (kVBlock / 8) * v_sm_bits(a.dtype), code_cov = blocks * (kVBlock / 8) * a.code_bits;
-  for (uint64_t i = sm_cov + tid; i < a256(a.sm_bytes); i += 1024) a.out[a.off_sm + i] = 0;
-  for (uint64_t i = code_cov + tid; i < a256(a.code_bytes); i += 1024) a.out[a.off_code + i] = 0;
-  for (uint64_t i = (uint64_t)a.pos_bytes * M + tid; i < pos_sec; i += 1024)
+  for (uint64_t i = tab_end + tid; i < a.off_sm; i += kThreads) a.out[i] = 0;
+  const uint64_t sm_cov = n_blocks * (kVBlock / 8) * v_sm_bits(a.dtype), code_cov = n_blocks * (kVBlock / 8) * a.code_bits;
+  for (uint64_t i = sm_cov + tid; i < a256(a.sm_bytes); i += kThreads) a.out[a.off_sm + i] = 0;
+  for (uint64_t i = code_cov + tid; i < a256(a.code_bytes); i += kThreads) a.out[a.off_code + i] = 0;
+  for (uint64_t i = (uint64_t)a.pos_bytes * M + tid; i < pos_sec; i += kThreads)
     if (a.off_pos + i < a.capacity) a.out[a.off_pos + i] = 0;
   if (tid < 16) {
     uint32_t w = a.hdr[tid];
@@ -258,63 +362,6 @@ __global__ __launch_bounds__(1024) void v_scan_kernel(const VArgs a) {
     a.sizes->n_escapes = M;
     a.sizes->status = total > a.capacity ? SPLITZIP_STATUS_OVERFLOW : 0u;
     a.sizes->reserved = 0;
-  }
-}
-
-// compress pass 3: the escape records, each at its final rank (what does not fit the capacity is dropped)
-template <int DT>
-__global__ __launch_bounds__(kThreads) void v_emit_kernel(const VArgs a) {
-  using F = VFmt<DT>;
-  __shared__ uint8_t lut[256];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  lut[tid] = a.lut[tid];
-  __syncthreads();
-  const uint64_t blk = (uint64_t)blockIdx.x * kWaves + wave;
-  if (blk * kVBlock >= a.n) return;
-  const uint32_t per_blk = kVBlock >> a.chunk_shift;   // chunks per block: 1 or 4
-  const uint64_t c_first = blk * per_blk, c_end = c_first + per_blk < a.n_chunks ? c_first + per_blk : a.n_chunks;
-  if (a.offs[c_end] == a.offs[c_first]) return;         // nothing escaped in this block
-  const uint32_t M = a.offs[a.n_chunks];
-  const uint64_t off_val = a.off_pos + a256((uint64_t)a.pos_bytes * M);
-  uint32_t carry = 0;
-#pragma unroll
-  for (int s = 0; s < 2; ++s) {
-    const uint64_t g = blk * kVBlock + s * kVStep, g0 = g + lane * 8;
-    uint32_t x[8];
-    v_load8<DT>(a, g0, x);
-    uint32_t esc = 0;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) esc |= (uint32_t)(lut[F::exponent(x[j])] >> 7) << j;
-    esc &= (1u << v_nvalid(a, g0)) - 1u;
-    const uint32_t cnt = __popc(esc), incl = wave_incl_scan(cnt);
-    const uint32_t t31 = __builtin_amdgcn_readlane(incl, 31), t63 = __builtin_amdgcn_readlane(incl, 63);
-    uint32_t r;
-    if (a.chunk_shift == 10) {
-      r = a.offs[blk] + carry + incl - cnt;
-      carry = t63;
-    } else {
-      const uint64_t c = (g >> 8) + (lane >> 5);
-      r = (c < a.n_chunks ? a.offs[c] : 0u) + incl - cnt - (lane >= 32 ? t31 : 0u);
-    }
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      if (!((esc >> j) & 1u)) continue;
-      const uint64_t i = g0 + j;
-      if (a.mode == SPLITZIP_ESC_POS) {
-        const uint32_t p = (uint32_t)i & ((1u << a.chunk_shift) - 1u);
-        const uint64_t at = a.off_pos + (uint64_t)a.pos_bytes * r;
-        if (at + a.pos_bytes <= a.capacity) {
-          if (a.pos_bytes == 2) *reinterpret_cast<uint16_t*>(a.out + at) = (uint16_t)p;
-          else a.out[at] = (uint8_t)p;
-        }
-      } else if (a.mode == SPLITZIP_ESC_ABS32) {
-        const uint64_t at = a.off_pos + 4ull * r;
-        if (at + 4 <= a.capacity) *reinterpret_cast<uint32_t*>(a.out + at) = (uint32_t)i;
-      }
-      if (a.val_bits != 8) a.val_stage[r] = (uint8_t)F::exponent(x[j]);
-      else if (off_val + r < a.capacity) a.out[off_val + r] = (uint8_t)F::exponent(x[j]);
-      ++r;
-    }
   }
 }
 
@@ -388,15 +435,23 @@ __global__ __launch_bounds__(kThreads) void v_decode_kernel(const VArgs a) {
   uint32_t my_off = 0;   // lane q holds the offset of chunk c_first + q
   if (live && MODE != SPLITZIP_ESC_ABS32 && (uint32_t)lane <= per_blk && c_first + lane <= a.n_chunks)
     my_off = a.offs[c_first + lane];
-  if (live) {
-    // the block's slices of both planes (whole dwords; the sections are padded, so nothing past them is read)
+  // The block's slices of both planes (whole dwords; the sections are padded, so nothing past them is read) are
+  // asked for now and kept in registers: they go to LDS further down, once the escape records -- whose addresses
+  // need the offsets and the header, asked for before the planes -- are on their way too.
+  constexpr uint32_t SMD = (32u * F::SB + 63u) / 64u, CDD = (32u * CB + 63u) / 64u;   // dwords per lane
+  uint32_t psm[SMD], pcd[CDD];
+  {
     const uint64_t sm0 = blk * (kVBlock / 8) * F::SB, code0 = blk * (kVBlock / 8) * CB;
-    for (uint32_t i = lane; i < 32u * F::SB; i += 64)
-      reinterpret_cast<uint32_t*>(s_sm[wave])[i] =
-          sm0 + 4 * i < a256(a.sm_bytes) ? ld_stream(reinterpret_cast<const uint32_t*>(a.in + a.off_sm + sm0) + i) : 0u;
-    for (uint32_t i = lane; i < 32u * CB; i += 64)
-      reinterpret_cast<uint32_t*>(s_code[wave])[i] =
-          code0 + 4 * i < a256(a.code_bytes) ? ld_stream(reinterpret_cast<const uint32_t*>(a.in + a.off_code + code0) + i) : 0u;
+#pragma unroll
+    for (uint32_t q = 0; q < SMD; ++q) {
+      const uint32_t i = lane + 64 * q;
+      psm[q] = live && i < 32u * F::SB && sm0 + 4 * i < a256(a.sm_bytes) ? ld_stream(reinterpret_cast<const uint32_t*>(a.in + a.off_sm + sm0) + i) : 0u;
+    }
+#pragma unroll
+    for (uint32_t q = 0; q < CDD; ++q) {
+      const uint32_t i = lane + 64 * q;
+      pcd[q] = live && i < 32u * CB && code0 + 4 * i < a256(a.code_bytes) ? ld_stream(reinterpret_cast<const uint32_t*>(a.in + a.off_code + code0) + i) : 0u;
+    }
   }
   uint32_t M;
   const bool ok = v_check_header(a, hw, lane, &M);
@@ -407,7 +462,7 @@ __global__ __launch_bounds__(kThreads) void v_decode_kernel(const VArgs a) {
     }
     if (!ok) v_flag_bad(a);
   }
-  __syncthreads();         // s_dec
+  lds_barrier();            // s_dec (an LDS-only barrier: the planes stay on their way)
   if (!ok || !live) return;   // nothing of a stream with a bad header is followed
   const uint64_t off_val = a.off_pos + a256((uint64_t)PB * M);
   const uint32_t sentinel = (1u << CB) - 1u;
@@ -434,6 +489,13 @@ __global__ __launch_bounds__(kThreads) void v_decode_kernel(const VArgs a) {
     }
   }
 
+  // the planes into LDS now (every lane its dwords), so that each lane can pick its elements' bits
+#pragma unroll
+  for (uint32_t q = 0; q < SMD; ++q)
+    if (lane + 64 * q < 32u * F::SB) reinterpret_cast<uint32_t*>(s_sm[wave])[lane + 64 * q] = psm[q];
+#pragma unroll
+  for (uint32_t q = 0; q < CDD; ++q)
+    if (lane + 64 * q < 32u * CB) reinterpret_cast<uint32_t*>(s_code[wave])[lane + 64 * q] = pcd[q];
   v_lds_settle();
   uint32_t carry = 0;
 #pragma unroll
