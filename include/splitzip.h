@@ -285,15 +285,21 @@ int splitzip_traffic_probe(const void* d_src, size_t read_bytes, void* d_dst, si
  * (the ceiling the codec's kernels are compared with).  Per step a workgroup
  * of 256 threads reads reads_per_step and writes writes_per_step coalesced
  * runs of 4 KB; (reads, writes) is one of (1,0) (2,0) (4,0) (8,0) read only,
- * (0,1) (0,2) (0,4) (0,8) write only, (4,3) (8,6) the compress mix,
- * (3,4) (6,8) the decompress mix, (1,1) (2,2) (4,4) a copy; wgs_per_cu is 1 to
- * 32 workgroups per CU that stay for the whole launch, or 0 for one workgroup
- * per step, started by the hardware in order.  flags: bit 0 non-temporal
- * loads, bit 1 non-temporal stores, bit 2 every workgroup owns one contiguous
- * block of steps (otherwise the steps are dealt round robin), bit 3 (with bit
- * 2) every workgroup starts at a different place inside its block.  read_bytes of d_src are read and write_bytes of d_dst
- * written (each rounded down to a multiple of 16; the side with 0 runs per
- * step is not touched, but both pointers must be valid).  Anything else gives
+ * (0,1) (0,2) (0,4) (0,8) write only, (4,3) (8,6) (16,12) the compress mix,
+ * (3,4) (6,8) (12,16) the decompress mix, (1,1) (2,2) (4,4) a copy; wgs_per_cu
+ * is 1 to 32 workgroups per CU that stay for the whole launch, or 0 for one
+ * workgroup per step, started by the hardware in order.  Every load of a step
+ * is issued before the first is waited for, and every store before the next
+ * step's loads.  flags: bit 0 non-temporal loads, bit 1 non-temporal stores,
+ * bit 2 every workgroup owns one contiguous block of steps (otherwise the
+ * steps are dealt round robin), bit 3 (with bit 2) every workgroup starts at
+ * a different place inside its block, bit 4 (without bits 2 and 3) the steps
+ * are handed out through a counter in the 4 bytes behind the written bytes,
+ * which the caller has set to zero, bit 5 (with the shape (4,3)) the stores
+ * have the codec's widths, 8 and 4 bytes per thread.  read_bytes of d_src are
+ * read and write_bytes of d_dst written (each rounded down to a multiple of
+ * 16; the side with 0 runs per step is not touched, but both pointers must be
+ * valid).  Anything else gives
  * SPLITZIP_ERR_INVALID_ARG. */
 int splitzip_traffic_probe_shape(const void* d_src, size_t read_bytes, void* d_dst, size_t write_bytes,
                                  uint32_t reads_per_step, uint32_t writes_per_step, uint32_t wgs_per_cu,

@@ -114,16 +114,31 @@ __global__ __launch_bounds__(kThreads) void traffic_probe_kernel(const u32x4* sr
   const uint64_t steps = (nread + 4 * kThreads - 1) / (4 * kThreads);
   for (uint64_t s = blockIdx.x; s < steps; s += gridDim.x) {
     u32x4 v[4];
+    // a step inside both buffers runs without a condition per access: all its loads are on their way before the
+    // first is waited for, and its stores follow one another without a wait in between
+    const bool whole = (4 * (s + 1)) * kThreads <= nread && (3 * (s + 1)) * kThreads <= nwrite;
+    if (whole) {
+      const u32x4* sp = src + 4 * s * kThreads + threadIdx.x;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const uint64_t idx = (4 * s + i) * kThreads + threadIdx.x;
-      v[i] = idx < nread ? ld_stream(src + idx) : u32x4{0u, 0u, 0u, 0u};
+      for (int i = 0; i < 4; ++i) v[i] = ld_stream(sp + i * kThreads);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint64_t idx = (4 * s + i) * kThreads + threadIdx.x;
+        v[i] = idx < nread ? ld_stream(src + idx) : u32x4{0u, 0u, 0u, 0u};
+      }
     }
     v[0].x ^= v[3].x; v[1].y ^= v[3].y; v[2].z ^= v[3].z; v[0].w ^= v[3].w;
+    if (whole) {
+      u32x4* dp = dst + 3 * s * kThreads + threadIdx.x;
 #pragma unroll
-    for (int i = 0; i < 3; ++i) {
-      const uint64_t idx = (3 * s + i) * kThreads + threadIdx.x;
-      if (idx < nwrite) st_stream(dst + idx, v[i]);
+      for (int i = 0; i < 3; ++i) st_stream(dp + i * kThreads, v[i]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 3; ++i) {
+        const uint64_t idx = (3 * s + i) * kThreads + threadIdx.x;
+        if (idx < nwrite) st_stream(dst + idx, v[i]);
+      }
     }
   }
 }
@@ -163,11 +178,20 @@ __global__ __launch_bounds__(kThreads) void traffic_shape_kernel(const u32x4* sr
     }
     u32x4 v[R > 0 ? R : 1];
     v[0] = u32x4{(uint32_t)s, threadIdx.x, 0u, 0u};
+    // A step that lies inside both buffers entirely (all but the last, as a rule) runs without a condition per
+    // access: every load of the step is on its way before the first is waited for, and so is every store.
+    const bool whole = (R == 0 || ((uint64_t)R * (s + 1)) * kThreads <= nread) && (W == 0 || ((uint64_t)W * (s + 1)) * kThreads <= nwrite);
+    if (whole) {
+      const u32x4* sp = src + (uint64_t)R * s * kThreads + threadIdx.x;
 #pragma unroll
-    for (int i = 0; i < R; ++i) {
-      const uint64_t idx = ((uint64_t)R * s + i) * kThreads + threadIdx.x;
-      v[i] = u32x4{0u, 0u, 0u, 0u};
-      if (idx < nread) v[i] = NTL ? ld_stream(src + idx) : src[idx];
+      for (int i = 0; i < R; ++i) v[i] = NTL ? ld_stream(sp + i * kThreads) : sp[i * kThreads];
+    } else {
+#pragma unroll
+      for (int i = 0; i < R; ++i) {
+        const uint64_t idx = ((uint64_t)R * s + i) * kThreads + threadIdx.x;
+        v[i] = u32x4{0u, 0u, 0u, 0u};
+        if (idx < nread) v[i] = NTL ? ld_stream(src + idx) : src[idx];
+      }
     }
     if (W == 0) {
 #pragma unroll
@@ -175,7 +199,7 @@ __global__ __launch_bounds__(kThreads) void traffic_shape_kernel(const u32x4* sr
     }
     if (blocked_narrow) {
       // the codec's store shapes: two thirds of the step's bytes as 8-byte stores, one third as 4-byte stores
-      if (W == 3 && ((uint64_t)W * s + W) * kThreads <= nwrite) {
+      if (W == 3 && whole) {
         uint8_t* base = reinterpret_cast<uint8_t*>(dst + (uint64_t)W * s * kThreads);
 #pragma unroll
         for (int i = 0; i < 4; ++i) st_stream(reinterpret_cast<u32x2*>(base) + i * kThreads + threadIdx.x, u32x2{v[i % (R > 0 ? R : 1)].x, v[i % (R > 0 ? R : 1)].y});
@@ -184,13 +208,23 @@ __global__ __launch_bounds__(kThreads) void traffic_shape_kernel(const u32x4* sr
       }
       continue;
     }
+    if (whole) {
+      u32x4* dp = dst + (uint64_t)W * s * kThreads + threadIdx.x;
 #pragma unroll
-    for (int i = 0; i < W; ++i) {
-      const uint64_t idx = ((uint64_t)W * s + i) * kThreads + threadIdx.x;
-      const u32x4 o = v[R > 0 ? i % R : 0];
-      if (idx < nwrite) {
-        if (NTS) st_stream(dst + idx, o);
-        else dst[idx] = o;
+      for (int i = 0; i < W; ++i) {
+        const u32x4 o = v[R > 0 ? i % R : 0];
+        if (NTS) st_stream(dp + i * kThreads, o);
+        else dp[i * kThreads] = o;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < W; ++i) {
+        const uint64_t idx = ((uint64_t)W * s + i) * kThreads + threadIdx.x;
+        const u32x4 o = v[R > 0 ? i % R : 0];
+        if (idx < nwrite) {
+          if (NTS) st_stream(dst + idx, o);
+          else dst[idx] = o;
+        }
       }
     }
   }

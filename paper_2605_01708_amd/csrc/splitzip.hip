@@ -938,7 +938,7 @@ int splitzip_traffic_probe_shape(const void* d_src, size_t read_bytes, void* d_d
   }
   SPLITZIP_SHAPE(1, 0) SPLITZIP_SHAPE(2, 0) SPLITZIP_SHAPE(4, 0) SPLITZIP_SHAPE(8, 0)
   SPLITZIP_SHAPE(0, 1) SPLITZIP_SHAPE(0, 2) SPLITZIP_SHAPE(0, 4) SPLITZIP_SHAPE(0, 8)
-  SPLITZIP_SHAPE(4, 3) SPLITZIP_SHAPE(8, 6) SPLITZIP_SHAPE(3, 4) SPLITZIP_SHAPE(6, 8)
+  SPLITZIP_SHAPE(4, 3) SPLITZIP_SHAPE(8, 6) SPLITZIP_SHAPE(16, 12) SPLITZIP_SHAPE(3, 4) SPLITZIP_SHAPE(6, 8) SPLITZIP_SHAPE(12, 16)
   SPLITZIP_SHAPE(1, 1) SPLITZIP_SHAPE(2, 2) SPLITZIP_SHAPE(4, 4)
 #undef SPLITZIP_SHAPE
   if (!found) return SPLITZIP_ERR_INVALID_ARG;

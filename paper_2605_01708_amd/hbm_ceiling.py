@@ -1,6 +1,6 @@
 """What the memory system of this GPU gives a plain streaming kernel at best: a sweep of
 splitzip_traffic_probe_shape over traffic mix (read only, write only, the codec's 4:3 and 3:4 mixes, a copy),
-workgroups per CU, 4 KB runs in flight per workgroup, temporal / non-temporal accesses, round-robin or blocked
+workgroups per CU (or one workgroup per step, handed out by the dispatcher), 4 KB runs in flight per workgroup, temporal / non-temporal accesses, round-robin or blocked
 ownership of the runs, and the alignment of the written buffer against the read one.
 
     python -m paper_2605_01708_amd.hbm_ceiling [--gib 4] [--reps 3] [--quick]
@@ -24,8 +24,8 @@ HBM_PEAK_GBPS = 8000.0
 MIXES = {
     "read_only": [(1, 0), (2, 0), (4, 0), (8, 0)],
     "write_only": [(0, 1), (0, 2), (0, 4), (0, 8)],
-    "compress_4_3": [(4, 3), (8, 6)],
-    "decompress_3_4": [(3, 4), (6, 8)],
+    "compress_4_3": [(4, 3), (8, 6), (16, 12)],
+    "decompress_3_4": [(3, 4), (6, 8), (12, 16)],
     "copy_1_1": [(1, 1), (2, 2), (4, 4)],
 }
 
@@ -45,12 +45,12 @@ def time_shape(src, dst, rbytes, wbytes, r, w, wgs, flags, reps):
 
 def sweep(gib: float = 4.0, reps: int = 3, quick: bool = False, out=sys.stdout):
     """Returns {mix: best setting}; prints every setting to `out` (None: silent)."""
-    unit = int(gib * (1 << 30)) // (24 * 4096) * (24 * 4096)     # whole steps for every (reads, writes) pair
+    unit = int(gib * (1 << 30)) // (48 * 4096) * (48 * 4096)     # whole steps for every (reads, writes) pair
     src = torch.empty(unit + (2 << 20), dtype=torch.uint8, device="cuda")
     dst = torch.empty(unit + (2 << 20), dtype=torch.uint8, device="cuda")
     src.random_(0, 256)
     torch.cuda.synchronize()
-    wgs_list = [2, 8] if quick else [1, 2, 4, 8, 16]
+    wgs_list = [0, 8] if quick else [0, 1, 2, 4, 8, 16]   # 0: one workgroup per step, in dispatch order
     best = {}
     for mix, shapes in MIXES.items():
         for r, w in (shapes[-1:] if quick else shapes):
@@ -59,8 +59,8 @@ def sweep(gib: float = 4.0, reps: int = 3, quick: bool = False, out=sys.stdout):
             wbytes = unit if w >= r else unit // r * w
             for wgs in wgs_list:
                 for flags in ([3, 7] if quick else range(8)):
-                    if (r == 0 and flags & 1) or (w == 0 and flags & 2):
-                        continue                                  # a flag for a side the mix does not have
+                    if (r == 0 and flags & 1) or (w == 0 and flags & 2) or (wgs == 0 and flags & 4):
+                        continue                                  # a flag for a side or an ownership the setting does not have
                     gbps = time_shape(src, dst, rbytes, wbytes, r, w, wgs, flags, reps)
                     rec = {"mix": mix, "reads": r, "writes": w, "wgs_per_cu": wgs, "nt_loads": bool(flags & 1),
                            "nt_stores": bool(flags & 2), "blocked": bool(flags & 4), "GBps": round(gbps, 1),
