@@ -109,6 +109,21 @@ __device__ inline uint32_t wave_incl_scan(uint32_t v) {
 
 __device__ inline uint32_t wave_last(uint32_t v) { return __builtin_amdgcn_readlane(v, 63); }
 
+// Exclusive prefix sum over the lanes of small counts c that are zero in most lanes (escapes per lane), and their
+// total (wave-uniform): one ballot per value a count reaches -- set bits below a lane, summed over k, are the
+// counts below it.  Three vector instructions per round and usually one round, against a dozen for a full scan.
+__device__ inline uint32_t wave_sparse_excl(uint32_t c, uint32_t& excl) {
+  uint32_t total = 0;
+  excl = 0;
+  for (uint32_t k = 1;; ++k) {
+    const uint64_t m = __ballot(c >= k);
+    if (!m) break;
+    excl = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, excl));
+    total += (uint32_t)__popcll(m);
+  }
+  return total;
+}
+
 // agent-scope relaxed accesses: performed at the device-wide coherence point, no fences
 template <typename T>
 __device__ inline void st_agent(T* p, T v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }

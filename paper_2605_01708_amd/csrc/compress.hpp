@@ -168,16 +168,13 @@ __device__ inline uint32_t process_chunk_bf16(const Planes& a, const uint16_t* l
       }
     }
   }
-  // escapes per lane; both halves scanned at once (16 bits each: a half has at most 512)
-  const uint32_t packed = __popc(F[0]) | (__popc(F[1]) << 16);
-  const uint32_t incl = wave_incl_scan(packed);
-  const uint32_t tot = wave_last(incl);
-  const uint32_t excl = incl - packed;
-  const uint32_t tot0 = tot & 0xffffu, total = tot0 + (tot >> 16);
+  // escapes per lane and half, ranked over the wave; element order inside the chunk: half, lane, element
+  uint32_t excl0, excl1;
+  const uint32_t tot0 = wave_sparse_excl(__popc(F[0]), excl0), tot1 = wave_sparse_excl(__popc(F[1]), excl1);
+  const uint32_t total = tot0 + tot1;
   if (total) {
-    // element order inside the chunk: half, lane, element
-    emit_half_bf16(park, w[0], F[0], base + (excl & 0xffffu), lane * 8, sink);
-    emit_half_bf16(park, w[1], F[1], base + tot0 + (excl >> 16), kHalf + lane * 8, sink);
+    emit_half_bf16(park, w[0], F[0], base + excl0, lane * 8, sink);
+    emit_half_bf16(park, w[1], F[1], base + tot0 + excl1, kHalf + lane * 8, sink);
   }
   return total;
 }
@@ -266,18 +263,21 @@ __device__ inline uint32_t process_chunk_e5m2(const Planes& a, const uint16_t* l
   if (STORE) {
     // plane bytes of this lane pair: [12 p, 12 p + 12) of the chunk's 384
     // quad_perm [1,1,3,3]: the odd neighbour's bits
-    const uint32_t lo_up = __builtin_amdgcn_update_dpp(0u, lo, 0xF5, 0xf, 0xf, false);
-    const uint32_t hi_up = __builtin_amdgcn_update_dpp(0u, hi, 0xF5, 0xf, 0xf, false);
-    const uint64_t sm_off = (cbase / 8) * 3 + (uint32_t)(lane >> 1) * 12;
-    uint8_t* sm_dst = a.out + a.off_sm + (cbase / 8) * 3 + (uint32_t)(lane >> 1) * 12;   // uniform pointer + lane offset
+    // (a quad permute reads lanes of its own quad only: every lane gets a value, the old one is never kept)
+    const uint32_t lo_up = __builtin_amdgcn_mov_dpp(lo, 0xF5, 0xf, 0xf, false);
+    const uint32_t hi_up = __builtin_amdgcn_mov_dpp(hi, 0xF5, 0xf, 0xf, false);
+    const uint64_t sm_chunk = (uint64_t)(uint32_t)(cbase >> 10) * 384u;   // the chunk's plane bytes start here: a scalar product
+    const uint64_t sm_off = sm_chunk + (uint32_t)(lane >> 1) * 12;
+    uint8_t* sm_chunk_ptr = a.out + a.off_sm + sm_chunk;
+    uint8_t* sm_dst = sm_chunk_ptr + (uint32_t)(lane >> 1) * 12;
     // the pair's 12 bytes, all in the even lane
     uint32_t d0 = lo, d1 = (hi & 0xffffu) | (lo_up << 16), d2 = (lo_up >> 16) | (hi_up << 16);
     if (FULL) {
       // Both lanes of a pair write the pair's 12 bytes (quad_perm [0,0,2,2]: the even neighbour's bits): one
       // instruction writes the chunk's 384 bytes back to back, and it is issued whatever the lane -- so the
       // compiler can count on it when it works out how long a wave must wait for the loads issued before it.
-      const uint32_t lo_dn = __builtin_amdgcn_update_dpp(0u, lo, 0xA0, 0xf, 0xf, false);
-      const uint32_t hi_dn = __builtin_amdgcn_update_dpp(0u, hi, 0xA0, 0xf, 0xf, false);
+      const uint32_t lo_dn = __builtin_amdgcn_mov_dpp(lo, 0xA0, 0xf, 0xf, false);
+      const uint32_t hi_dn = __builtin_amdgcn_mov_dpp(hi, 0xA0, 0xf, 0xf, false);
       d0 = lo_dn; d1 = (hi_dn & 0xffffu) | (lo_up << 16);
       st_stream(reinterpret_cast<u32x3*>(sm_dst), u32x3{d0, d1, d2});
       st_stream(reinterpret_cast<u32x2*>(a.out + a.off_code + (cbase >> 1)) + (uint32_t)lane, u32x2{code[0], code[1]});
@@ -290,20 +290,20 @@ __device__ inline uint32_t process_chunk_e5m2(const Planes& a, const uint16_t* l
         if (sm_off + 4 < sm_end) *reinterpret_cast<uint32_t*>(sm_dst + 4) = d1;
         if (sm_off + 8 < sm_end) *reinterpret_cast<uint32_t*>(sm_dst + 8) = d2;
       }
-      const uint64_t past = (cbase / 8) * 3 + 384 + 4 * (uint32_t)lane;
+      const uint64_t past = sm_chunk + 384 + 4 * (uint32_t)lane;
       if (lane < 32 && past < sm_end) *reinterpret_cast<uint32_t*>(a.out + a.off_sm + past) = 0;
       if ((g0 >> 1) < a256(a.code_bytes))
         *reinterpret_cast<u32x2*>(a.out + a.off_code + (g0 >> 1)) = u32x2{code[0], code[1]};
     }
   }
   const uint32_t mine = __popc(F[0]) + __popc(F[1]);
-  const uint32_t incl = wave_incl_scan(mine);
-  const uint32_t total = wave_last(incl);
+  uint32_t excl;
+  const uint32_t total = wave_sparse_excl(mine, excl);
   if (total && mine) {
     // element order inside the chunk: lane, element
     *reinterpret_cast<u32x4*>(park) = u32x4{w[0], w[1], w[2], w[3]};
     const uint8_t* x = reinterpret_cast<const uint8_t*>(park);
-    uint32_t rr = base + incl - mine;
+    uint32_t rr = base + excl;
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
       uint32_t m = F[q];
@@ -470,12 +470,21 @@ __device__ inline TileGeom tile_geom(const TileArgs& a, uint32_t item) {
   return g;
 }
 
-// entry of the LDS encode table for exponent e under the codebook dec (wave-uniform): its code, or the escape mark
-__device__ inline uint16_t encode_entry(const uint8_t* dec, uint32_t e) {
-  uint32_t entry = 0x100u;
+// The LDS encode table (exponent e in slots e << shift ... : its code, or the escape mark 0x100) from the 16 decode
+// entries of the codebook, by the first wave of the workgroup alone: escape marks everywhere, then the 16 codes on
+// top (the LDS takes a wave's writes in order); the caller's barrier makes it visible to the others.  Entries that
+// are no exponent of the format (a codebook in device memory is not the host's to check) are left out.
+__device__ inline void build_encode_table(uint16_t* lut, const uint8_t* dec, int tid, int shift) {
+  if (tid < 64) {
+    const uint32_t* d32 = reinterpret_cast<const uint32_t*>(dec);   // 4-byte aligned wherever it comes from
+    const uint32_t d0 = d32[0], d1 = d32[1], d2 = d32[2], d3 = d32[3];
 #pragma unroll
-  for (uint32_t k = 0; k < 16; ++k) entry = dec[k] == e ? k : entry;
-  return (uint16_t)entry;
+    for (int q = 0; q < 4; ++q) lut[q * 64 + tid] = 0x100u;
+    const uint32_t k = (uint32_t)tid >> shift, sub = (uint32_t)tid & ((1u << shift) - 1u);
+    const uint32_t d = k < 8 ? (k < 4 ? d0 : d1) : (k < 12 ? d2 : d3);
+    const uint32_t e = (d >> ((k & 3u) * 8u)) & 0xffu;
+    if (k < 16 && e < (256u >> shift)) lut[(e << shift) + sub] = (uint16_t)k;
+  }
 }
 
 // a barrier for LDS traffic only: global loads that are on their way stay on their way
@@ -503,38 +512,63 @@ __global__ __launch_bounds__(kTileThreads, F::kWavesPerSimd) void compress_tile_
   const uint32_t mine = nb > w0 ? (nb - w0 < a.cpt ? nb - w0 : a.cpt) : 0u;     // and how many it has
   uint32_t* park = reinterpret_cast<uint32_t*>(&s_park[tid]);
 
-  // the wave's chunks [it0, it0 + CPT) into r (nothing for chunks it does not have)
-  auto fetch = [&](uint32_t it0, typename F::Regs (&r)[CPT]) {
+  uint32_t wave_count = 0, my_start = 0;   // lane it: escapes of the wave before its it-th chunk
+  const LdsSink lds{stage_pk[wave], stage_val[wave], 0u, kTileStageCap};
+  typename F::Regs w[CPT];
+  // A tile all of whose chunks are complete (every tile but a tensor's last, as a rule) takes a path without a
+  // condition per chunk: nothing stands between the loads, and the compiler need not merge the registers of two
+  // ways of loading a chunk.
+  const uint32_t r_last = r0 + G.tile_chunks - 1;
+  if (nb == G.tile_chunks && F::full(P, (uint64_t)r_last * kChunk)) {
+    auto fetch = [&](uint32_t it0) {
 #pragma unroll
-    for (int j = 0; j < CPT; ++j) {
-      const uint32_t it = it0 + j;
-      if (it < mine) {
-        const uint64_t cbase = (uint64_t)(r0 + w0 + it) * kChunk;
-        const uint8_t* cptr = chunk_at<F::ES>(P.w, cbase, P.w.table ? page_of_chunk(P.w, r0 + w0 + it) : 0u);
-        if (F::full(P, cbase)) F::template load<true>(P, cptr, cbase, lane, r[j]);
-        else F::template load<false>(P, cptr, cbase, lane, r[j]);
+      for (int j = 0; j < CPT; ++j) {
+        const uint64_t cbase = (uint64_t)(r0 + w0 + it0 + j) * kChunk;
+        const uint8_t* cptr = chunk_at<F::ES>(P.w, cbase, P.w.table ? page_of_chunk(P.w, r0 + w0 + it0 + j) : 0u);
+        F::template load<true>(P, cptr, cbase, lane, w[j]);
+      }
+    };
+    // the words first: the table is built while they are on their way
+    fetch(0);
+    build_encode_table(lut, a.dec_of(item), tid, F::kLutShift);
+    lds_barrier();
+    for (uint32_t it0 = 0; it0 < a.cpt; it0 += CPT) {
+      if (it0 > 0) fetch(it0);   // tiles of more than CPT chunks per wave (very large tensors)
+#pragma unroll
+      for (int j = 0; j < CPT; ++j) {
+        if ((uint32_t)lane == it0 + j) my_start = wave_count;
+        wave_count += F::template process<true, true>(P, lut, park, (uint64_t)(r0 + w0 + it0 + j) * kChunk, lane, w[j], wave_count, lds);
       }
     }
-  };
-  typename F::Regs w[CPT];
-  // the words first: the table is built while they are on their way
-  fetch(0, w);
-  lut[tid] = encode_entry(a.dec_of(item), (uint32_t)tid >> F::kLutShift);
-  lds_barrier();
-
-  // dense pass; the wave's escape records into its LDS staging in element order, the chunks' counts kept in lanes
-  uint32_t wave_count = 0, my_start = 0;   // lane it: escapes of the wave before its it-th chunk
-  for (uint32_t it0 = 0; it0 < mine; it0 += CPT) {
-    if (it0 > 0) fetch(it0, w);   // tiles of more than CPT chunks per wave (very large tensors)
+  } else {
+    // the wave's chunks [it0, it0 + CPT) into w (nothing for chunks it does not have)
+    auto fetch = [&](uint32_t it0) {
 #pragma unroll
-    for (int j = 0; j < CPT; ++j) {
-      const uint32_t it = it0 + j;
-      if (it >= mine) break;
-      const uint64_t cbase = (uint64_t)(r0 + w0 + it) * kChunk;
-      const LdsSink lds{stage_pk[wave], stage_val[wave], 0u, kTileStageCap};
-      if ((uint32_t)lane == it) my_start = wave_count;
-      wave_count += F::full(P, cbase) ? F::template process<true, true>(P, lut, park, cbase, lane, w[j], wave_count, lds)
-                                      : F::template process<false, true>(P, lut, park, cbase, lane, w[j], wave_count, lds);
+      for (int j = 0; j < CPT; ++j) {
+        const uint32_t it = it0 + j;
+        if (it < mine) {
+          const uint64_t cbase = (uint64_t)(r0 + w0 + it) * kChunk;
+          const uint8_t* cptr = chunk_at<F::ES>(P.w, cbase, P.w.table ? page_of_chunk(P.w, r0 + w0 + it) : 0u);
+          if (F::full(P, cbase)) F::template load<true>(P, cptr, cbase, lane, w[j]);
+          else F::template load<false>(P, cptr, cbase, lane, w[j]);
+        }
+      }
+    };
+    fetch(0);
+    build_encode_table(lut, a.dec_of(item), tid, F::kLutShift);
+    lds_barrier();
+    // dense pass; the wave's escape records into its LDS staging in element order, the chunks' counts kept in lanes
+    for (uint32_t it0 = 0; it0 < mine; it0 += CPT) {
+      if (it0 > 0) fetch(it0);
+#pragma unroll
+      for (int j = 0; j < CPT; ++j) {
+        const uint32_t it = it0 + j;
+        if (it >= mine) break;
+        const uint64_t cbase = (uint64_t)(r0 + w0 + it) * kChunk;
+        if ((uint32_t)lane == it) my_start = wave_count;
+        wave_count += F::full(P, cbase) ? F::template process<true, true>(P, lut, park, cbase, lane, w[j], wave_count, lds)
+                                        : F::template process<false, true>(P, lut, park, cbase, lane, w[j], wave_count, lds);
+      }
     }
   }
   if (lane == 0) s_cnt[wave] = wave_count;
@@ -644,7 +678,7 @@ __global__ __launch_bounds__(kTileThreads) void compress_finish_kernel(const Til
     }
     if (lane == 63) s_tp[kGroup] = incl;
   }
-  lut[tid] = encode_entry(a.dec_of(item), (uint32_t)tid >> F::kLutShift);
+  build_encode_table(lut, a.dec_of(item), tid, F::kLutShift);
   __syncthreads();
   uint32_t first = 0, M = 0;
 #pragma unroll
