@@ -63,11 +63,12 @@ uint32_t pick_cpw(uint64_t n_chunks, uint32_t most, uint32_t want_tiles_per_cu) 
 }
 
 // Chunks per wave of a decompress launch over n_chunks chunks in all.  Measured on 64 MiB BF16 /
-// 32 MiB E5M2 tensors: BF16 wants one chunk per wave for a single tensor (32 768 chunks) and two for
-// a whole cache in one launch; E5M2 wants four and eight.
+// 32 MiB E5M2 tensors: BF16 wants two chunks per wave from 32 768 chunks in a launch on (with the planes of both
+// asked for at once: 23.7 us per 64 MiB tensor against 24.1 us with one) and one below; E5M2 wants four for a
+// single tensor and eight for a whole cache in one launch.
 uint32_t pick_decompress_cpw(uint64_t n_chunks, int dtype) {
   const uint32_t most = dtype == SPLITZIP_BF16 ? 2 : 8;
-  const uint32_t want = dtype == SPLITZIP_BF16 ? 32u : 8u;
+  const uint32_t want = dtype == SPLITZIP_BF16 ? 16u : 8u;
   return pick_cpw(n_chunks, most, want);
 }
 
