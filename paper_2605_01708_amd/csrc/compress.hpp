@@ -417,7 +417,8 @@ __device__ void compress_write_trailer(const Planes& a, const uint8_t* dec, spli
 // Between the passes lies a kernel boundary: no workgroup ever waits for another, nothing needs to be resident
 // together, and no word of the workspace needs a defined value before a call.
 constexpr uint32_t kTileThreads = 256;
-constexpr uint32_t kGroup = 16;             // tiles per workgroup of the finishing pass
+constexpr uint32_t kGroup = 16;             // tiles per group of the finishing pass
+constexpr uint32_t kFinishMost = 4;         // groups per workgroup of the finishing pass, at most
 constexpr uint32_t kSlotAhead = 16;         // records per tile the finishing pass fetches before it knows the counts
 constexpr uint32_t kTileStageCap = 256;     // escapes a wave can stage in LDS
 constexpr uint32_t kSlotCapMost = 1024;     // records per tile slot, at most
@@ -443,6 +444,7 @@ struct TileArgs {
   uint32_t cpt;                   // chunks per wave and tile, a power of two
   uint32_t tile_shift;            // log2 of the chunks per tile (4 cpt)
   uint32_t slot_cap;              // records per tile slot (the same for all tensors of the launch)
+  uint32_t finish_groups;         // groups of kGroup tiles per workgroup of the finishing pass, 1 to kFinishMost
   uint32_t use_group_sums;        // the finishing pass reads sums of kSumGroup tile counts (tile_group_sum_kernel) instead of all tile counts
   Words paging;                   // table and page geometry shared by all tensors (table null: contiguous tensors); base unused
   const splitzip_codebook* d_cbs; // nullable: n_items codebooks in device memory, used instead of dec
@@ -605,39 +607,52 @@ __global__ __launch_bounds__(64) void tile_group_sum_kernel(const TileArgs a) {
 template <typename F>
 __global__ __launch_bounds__(kTileThreads) void compress_finish_kernel(const TileArgs a) {
   constexpr int NW = kTileThreads / 64;
+  static_assert(kFinishMost <= NW, "one wave scans the counts of one group");
   __shared__ uint16_t lut[256];
   __shared__ u32x4 s_park[kTileThreads];
-  __shared__ uint32_t s_cnt[kGroup];       // the counts of the group's tiles, redo mark included
-  __shared__ uint32_t s_tp[kGroup + 1];    // escapes of the group's tiles before each tile
+  __shared__ uint32_t s_cnt[kFinishMost][kGroup];       // the counts of the groups' tiles, redo mark included
+  __shared__ uint32_t s_tp[kFinishMost][kGroup + 1];    // escapes of a group's tiles before each tile
   __shared__ uint32_t s_red[2 * NW];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const uint32_t item = blockIdx.y, g = blockIdx.x;
+  const uint32_t item = blockIdx.y;
   const TileGeom G = tile_geom(a, item);
   const Planes& P = G.P;
   const uint32_t n_groups = (G.n_tiles + kGroup - 1) / kGroup;
-  if (g >= (n_groups ? n_groups : 1u)) return;   // a tensor without elements still gets its header
+  // the workgroup's groups: [g0, g0 + ng) -- a.finish_groups of them in a row (1 to kFinishMost: a launch of many
+  // groups gives every workgroup several, so that fewer rounds of workgroups pass through the chip; each round
+  // costs the same few trips to memory whatever it carries)
+  const uint32_t g0 = blockIdx.x * a.finish_groups;
+  if (g0 >= (n_groups ? n_groups : 1u)) return;   // a tensor without elements still gets its header
+  const uint32_t ng = n_groups - g0 < a.finish_groups ? (n_groups > g0 ? n_groups - g0 : 1u) : a.finish_groups;
   uint32_t* park = reinterpret_cast<uint32_t*>(&s_park[tid]);
   uint32_t* tab = reinterpret_cast<uint32_t*>(P.out + P.off_tab);
-  const uint32_t t0 = g * kGroup;
+  const uint32_t group_entries = kGroup << a.tile_shift;
 
   // Everything whose address does not depend on the counts is fetched at once: the counts themselves, the
-  // group's table entries (one per thread or a few) and the first kSlotAhead records of every tile's slot.
-  const uint32_t c0 = t0 << a.tile_shift;
-  const uint32_t entries = P.n_chunks > c0 ? (P.n_chunks - c0 < (kGroup << a.tile_shift) ? P.n_chunks - c0 : (kGroup << a.tile_shift)) : 0u;
-  const uint32_t my_entry = (uint32_t)tid < entries ? tab[c0 + tid] : 0u;
-  const uint32_t sl = (uint32_t)tid / kSlotAhead, sj = (uint32_t)tid % kSlotAhead;   // tile of the group, record of the tile
-  uint32_t rec_ahead = 0;
-  if (t0 + sl < G.n_tiles && sj < a.slot_cap) rec_ahead = G.slots[(uint64_t)(t0 + sl) * a.slot_cap + sj];
+  // groups' table entries (one per thread and group, or a few) and the first kSlotAhead records of every tile's slot.
+  const uint32_t sl = (uint32_t)tid / kSlotAhead, sj = (uint32_t)tid % kSlotAhead;   // tile of a group, record of the tile
+  uint32_t my_entry[kFinishMost], rec_ahead[kFinishMost];
+#pragma unroll
+  for (uint32_t q = 0; q < kFinishMost; ++q) {
+    my_entry[q] = 0;
+    rec_ahead[q] = 0;
+    if (q < ng) {
+      const uint32_t t0 = (g0 + q) * kGroup, c0 = t0 << a.tile_shift;
+      if (c0 + tid < P.n_chunks && (uint32_t)tid < group_entries) my_entry[q] = tab[c0 + tid];
+      if (t0 + sl < G.n_tiles && sj < a.slot_cap) rec_ahead[q] = G.slots[(uint64_t)(t0 + sl) * a.slot_cap + sj];
+    }
+  }
+  const uint32_t t_first = g0 * kGroup;   // the first tile of the workgroup's first group
   uint32_t before = 0, all = 0;
   if (a.use_group_sums) {
-    const uint32_t n_sums = (G.n_tiles + kSumGroup - 1) / kSumGroup, whole = t0 / kSumGroup;   // sums that lie before the group entirely
+    const uint32_t n_sums = (G.n_tiles + kSumGroup - 1) / kSumGroup, whole = t_first / kSumGroup;   // sums that lie before the first group entirely
     for (uint32_t i = tid; i < n_sums; i += kTileThreads) {
       const uint32_t c = G.group_sums[i];
       all += c;
       before += i < whole ? c : 0u;
     }
-    for (uint32_t i = whole * kSumGroup + tid; i < t0; i += kTileThreads) before += G.counts[i] & ~kRedo;
+    for (uint32_t i = whole * kSumGroup + tid; i < t_first; i += kTileThreads) before += G.counts[i] & ~kRedo;
   } else {
     // four counts per load, four loads per thread on their way at a time (the counts start 256-byte aligned and
     // the sums behind them pad the last vector)
@@ -658,7 +673,7 @@ __global__ __launch_bounds__(kTileThreads) void compress_finish_kernel(const Til
         for (int z = 0; z < 4; ++z) {
           const uint32_t cz = e + z < G.n_tiles ? c[z] & ~kRedo : 0u;
           all += cz;
-          before += e + z < t0 ? cz : 0u;
+          before += e + z < t_first ? cz : 0u;
         }
       }
     }
@@ -669,18 +684,20 @@ __global__ __launch_bounds__(kTileThreads) void compress_finish_kernel(const Til
     s_red[wave] = before;
     s_red[NW + wave] = all;
   }
-  if (wave == 0) {
+  if ((uint32_t)wave < ng) {
+    // wave q: the counts of the tiles of group q, and what lies before each inside the group
+    const uint32_t t0 = (g0 + (uint32_t)wave) * kGroup;
     const uint32_t c = (uint32_t)lane < kGroup && t0 + lane < G.n_tiles ? G.counts[t0 + lane] : 0u;
     const uint32_t incl = wave_incl_scan(c & ~kRedo);
     if ((uint32_t)lane < kGroup) {
-      s_cnt[lane] = c;
-      s_tp[lane] = incl - (c & ~kRedo);
+      s_cnt[wave][lane] = c;
+      s_tp[wave][lane] = incl - (c & ~kRedo);
     }
-    if (lane == 63) s_tp[kGroup] = incl;
+    if (lane == 63) s_tp[wave][kGroup] = incl;
   }
   build_encode_table(lut, a.dec_of(item), tid, F::kLutShift);
   __syncthreads();
-  uint32_t first = 0, M = 0;
+  uint32_t first = 0, M = 0;   // the rank of the first record of the group at hand; all records of the tensor
 #pragma unroll
   for (int q = 0; q < NW; ++q) {
     first += s_red[q];
@@ -693,57 +710,66 @@ __global__ __launch_bounds__(kTileThreads) void compress_finish_kernel(const Til
   fin.val = P.out + off_val;
   fin.val_room = P.capacity > off_val ? P.capacity - off_val : 0;
 
-  // tiles whose records are not in their slots: once more from the words, by the offsets inside the tile that the
-  // first pass left in the table
-  bool any_redo = false;
-  for (uint32_t l = 0; l < kGroup; ++l) {
-    if (!(s_cnt[l] & kRedo)) continue;   // uniform: s_cnt is the same for every thread
-    any_redo = true;
-    const uint32_t r0 = (t0 + l) << a.tile_shift;
-    const uint32_t nb = P.n_chunks - r0 < G.tile_chunks ? P.n_chunks - r0 : G.tile_chunks;
-    typename F::Regs w;
-    for (uint32_t k = wave; k < nb; k += NW) {
-      const uint64_t cbase = (uint64_t)(r0 + k) * kChunk;
-      const uint32_t base = first + s_tp[l] + tab[r0 + k];
-      const uint8_t* cptr = chunk_at<F::ES>(P.w, cbase, P.w.table ? page_of_chunk(P.w, r0 + k) : 0u);
-      if (F::full(P, cbase)) {
-        F::template load<true>(P, cptr, cbase, lane, w);
-        F::template process<true, false>(P, lut, park, cbase, lane, w, base, fin);
-      } else {
-        F::template load<false>(P, cptr, cbase, lane, w);
-        F::template process<false, false>(P, lut, park, cbase, lane, w, base, fin);
+#pragma unroll
+  for (uint32_t q = 0; q < kFinishMost; ++q) {
+    if (q >= ng) break;
+    const uint32_t t0 = (g0 + q) * kGroup, c0 = t0 << a.tile_shift;
+    const uint32_t entries = P.n_chunks > c0 ? (P.n_chunks - c0 < group_entries ? P.n_chunks - c0 : group_entries) : 0u;
+    const uint32_t* cnt = s_cnt[q];
+    const uint32_t* tp = s_tp[q];
+    // tiles whose records are not in their slots: once more from the words, by the offsets inside the tile that the
+    // first pass left in the table
+    bool any_redo = false;
+    for (uint32_t l = 0; l < kGroup; ++l) {
+      if (!(cnt[l] & kRedo)) continue;   // uniform: the counts are the same for every thread
+      any_redo = true;
+      const uint32_t r0 = (t0 + l) << a.tile_shift;
+      const uint32_t nb = P.n_chunks - r0 < G.tile_chunks ? P.n_chunks - r0 : G.tile_chunks;
+      typename F::Regs w;
+      for (uint32_t k = wave; k < nb; k += NW) {
+        const uint64_t cbase = (uint64_t)(r0 + k) * kChunk;
+        const uint32_t base = first + tp[l] + tab[r0 + k];
+        const uint8_t* cptr = chunk_at<F::ES>(P.w, cbase, P.w.table ? page_of_chunk(P.w, r0 + k) : 0u);
+        if (F::full(P, cbase)) {
+          F::template load<true>(P, cptr, cbase, lane, w);
+          F::template process<true, false>(P, lut, park, cbase, lane, w, base, fin);
+        } else {
+          F::template load<false>(P, cptr, cbase, lane, w);
+          F::template process<false, false>(P, lut, park, cbase, lane, w, base, fin);
+        }
       }
     }
-  }
-  if (any_redo) __syncthreads();   // the table has been read by whoever needed its entries as offsets inside a tile
-  // the table entries: what lies before the tile added to the offsets inside the tile
-  if ((uint32_t)tid < entries) tab[c0 + tid] = my_entry + first + s_tp[(uint32_t)tid >> a.tile_shift];
-  for (uint32_t e = tid + kTileThreads; e < entries; e += kTileThreads) tab[c0 + e] += first + s_tp[e >> a.tile_shift];
-  // the records fetched ahead
-  const uint32_t cl = s_cnt[sl];
-  if (!(cl & kRedo) && sj < cl) fin.put(first + s_tp[sl] + sj, rec_ahead & 0xffffu, rec_ahead >> 16);
-  // The rest of the slots of tiles with more records than that: rank r of the group belongs to the last tile that
-  // starts at or before r.  Two records per thread are on their way at a time.
-  const uint32_t group_total = s_tp[kGroup];
-  if (group_total > kSlotAhead) {   // else no tile can have more than kSlotAhead records
-    auto locate = [&](uint32_t r, uint32_t& l, uint32_t& j) -> bool {
-      l = 0;
+    if (any_redo) __syncthreads();   // the table has been read by whoever needed its entries as offsets inside a tile
+    // the table entries: what lies before the tile added to the offsets inside the tile
+    if ((uint32_t)tid < entries) tab[c0 + tid] = my_entry[q] + first + tp[(uint32_t)tid >> a.tile_shift];
+    for (uint32_t e = tid + kTileThreads; e < entries; e += kTileThreads) tab[c0 + e] += first + tp[e >> a.tile_shift];
+    // the records fetched ahead
+    const uint32_t cl = cnt[sl];
+    if (!(cl & kRedo) && sj < cl) fin.put(first + tp[sl] + sj, rec_ahead[q] & 0xffffu, rec_ahead[q] >> 16);
+    // The rest of the slots of tiles with more records than that: rank r of the group belongs to the last tile that
+    // starts at or before r.  Two records per thread are on their way at a time.
+    const uint32_t group_total = tp[kGroup];
+    if (group_total > kSlotAhead) {   // else no tile can have more than kSlotAhead records
+      auto locate = [&](uint32_t r, uint32_t& l, uint32_t& j) -> bool {
+        l = 0;
 #pragma unroll
-      for (uint32_t step = kGroup / 2; step; step >>= 1)
-        if (s_tp[l + step] <= r) l += step;
-      j = r - s_tp[l];
-      return r < group_total && j >= kSlotAhead && !(s_cnt[l] & kRedo);
-    };
-    for (uint32_t r = tid; r < group_total; r += 2 * kTileThreads) {
-      uint32_t l0, j0, l1, j1, rec0 = 0, rec1 = 0;
-      const bool take0 = locate(r, l0, j0), take1 = locate(r + kTileThreads, l1, j1);
-      if (take0) rec0 = G.slots[(uint64_t)(t0 + l0) * a.slot_cap + j0];
-      if (take1) rec1 = G.slots[(uint64_t)(t0 + l1) * a.slot_cap + j1];
-      if (take0) fin.put(first + r, rec0 & 0xffffu, rec0 >> 16);
-      if (take1) fin.put(first + r + kTileThreads, rec1 & 0xffffu, rec1 >> 16);
+        for (uint32_t step = kGroup / 2; step; step >>= 1)
+          if (tp[l + step] <= r) l += step;
+        j = r - tp[l];
+        return r < group_total && j >= kSlotAhead && !(cnt[l] & kRedo);
+      };
+      for (uint32_t r = tid; r < group_total; r += 2 * kTileThreads) {
+        uint32_t l0, j0, l1, j1, rec0 = 0, rec1 = 0;
+        const bool take0 = locate(r, l0, j0), take1 = locate(r + kTileThreads, l1, j1);
+        if (take0) rec0 = G.slots[(uint64_t)(t0 + l0) * a.slot_cap + j0];
+        if (take1) rec1 = G.slots[(uint64_t)(t0 + l1) * a.slot_cap + j1];
+        if (take0) fin.put(first + r, rec0 & 0xffffu, rec0 >> 16);
+        if (take1) fin.put(first + r + kTileThreads, rec1 & 0xffffu, rec1 >> 16);
+      }
     }
+    first += group_total;
   }
-  if (g == 0 && wave == 0) compress_write_trailer(P, a.dec_of(item), a.sizes + item, M, 0u, lane);
+  if (g0 == 0 && wave == 0) compress_write_trailer(P, a.dec_of(item), a.sizes + item, M, 0u, lane);
 }
 
 #endif  // SPLITZIP_COMPRESS_HPP

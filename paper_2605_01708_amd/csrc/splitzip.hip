@@ -632,7 +632,11 @@ int compress_launch(const splitzip_item* items, uint32_t n_items, int dtype, con
       else hipLaunchKernelGGL((compress_tile_kernel<E5m2, E5m2::kCpt>), grid, dim3(kTileThreads), E5m2::kTileLdsPad, st, a);
       if (a.use_group_sums) hipLaunchKernelGGL(tile_group_sum_kernel, dim3(sums_max, k), dim3(64), 0, st, a);
     }
-    const dim3 fgrid(groups_max ? groups_max : 1u, k);
+    // many groups in the launch: several per workgroup, as long as the chip still gets a few workgroups per CU
+    a.finish_groups = 1;
+    while (a.finish_groups < kFinishMost && (uint64_t)groups_max * k / (2 * a.finish_groups) >= (uint64_t)cu_count() * 8) a.finish_groups *= 2;
+    const unsigned fgroups = (groups_max + a.finish_groups - 1) / a.finish_groups;
+    const dim3 fgrid(fgroups ? fgroups : 1u, k);
     if (dtype == SPLITZIP_BF16) hipLaunchKernelGGL(compress_finish_kernel<Bf16>, fgrid, dim3(kTileThreads), 0, st, a);
     else hipLaunchKernelGGL(compress_finish_kernel<E5m2>, fgrid, dim3(kTileThreads), 0, st, a);
     if (hipGetLastError() != hipSuccess) return SPLITZIP_ERR_HIP;
