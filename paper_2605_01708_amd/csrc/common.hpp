@@ -109,6 +109,34 @@ __device__ inline uint32_t wave_incl_scan(uint32_t v) {
 
 __device__ inline uint32_t wave_last(uint32_t v) { return __builtin_amdgcn_readlane(v, 63); }
 
+// The 16 decode entries of a codebook as four registers.  Entries that travel in the kernel's arguments are copied
+// out of them (dec16_from: the compiler reads kernel arguments with scalar loads); entries in device memory or in
+// a stream's header are fetched by one scalar load (load_dec16).  Either way the entries are not behind the
+// vector loads in the order of returns, so a table can be built from them while a wave's data loads are still on
+// their way (a vector load of the entries would be waited for behind all of those).
+__device__ inline u32x4 dec16_from(const uint8_t (&dec)[16]) {
+  u32x4 v;
+  __builtin_memcpy(&v, dec, 16);
+  return v;
+}
+// dec: an address in device memory (never that of a kernel argument), wave-uniform, 4-byte aligned; the entries
+// were written before the launch
+__device__ inline u32x4 load_dec16(const uint8_t* dec) {
+  const uint64_t p = reinterpret_cast<uint64_t>(dec);
+  // (the builtin returns a signed int: without the casts the low half would be sign-extended over the high half)
+  const uint32_t p_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)p);
+  const uint32_t p_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(p >> 32));
+  const uint64_t sp = ((uint64_t)p_hi << 32) | (uint64_t)p_lo;
+  u32x4 v;
+  asm volatile("s_load_dwordx4 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(sp) : "memory");
+  return v;
+}
+// entry k (0..15, may differ from lane to lane) of the 16 in v
+__device__ inline uint32_t dec16_at(const u32x4& v, uint32_t k) {
+  const uint32_t d = k < 8 ? (k < 4 ? v.x : v.y) : (k < 12 ? v.z : v.w);
+  return (d >> ((k & 3u) * 8u)) & 0xffu;
+}
+
 // Exclusive prefix sum over the lanes of small counts c that are zero in most lanes (escapes per lane), and their
 // total (wave-uniform): one ballot per value a count reaches -- set bits below a lane, summed over k, are the
 // counts below it.  Three vector instructions per round and usually one round, against a dozen for a full scan.

@@ -450,6 +450,7 @@ struct TileArgs {
   const splitzip_codebook* d_cbs; // nullable: n_items codebooks in device memory, used instead of dec
   uint8_t dec[kBatchMax][16];     // every tensor's codebook, as its 16 decode entries: the kernels build the encode table from them
   __device__ inline const uint8_t* dec_of(uint32_t k) const { return d_cbs ? d_cbs[k].dec : dec[k]; }
+  __device__ inline u32x4 dec16_of(uint32_t k) const { return d_cbs ? load_dec16(d_cbs[k].dec) : dec16_from(dec[k]); }
 };
 
 // what both passes derive from the arguments for one tensor
@@ -476,15 +477,12 @@ __device__ inline TileGeom tile_geom(const TileArgs& a, uint32_t item) {
 // entries of the codebook, by the first wave of the workgroup alone: escape marks everywhere, then the 16 codes on
 // top (the LDS takes a wave's writes in order); the caller's barrier makes it visible to the others.  Entries that
 // are no exponent of the format (a codebook in device memory is not the host's to check) are left out.
-__device__ inline void build_encode_table(uint16_t* lut, const uint8_t* dec, int tid, int shift) {
+__device__ inline void build_encode_table(uint16_t* lut, const u32x4& d, int tid, int shift) {
   if (tid < 64) {
-    const uint32_t* d32 = reinterpret_cast<const uint32_t*>(dec);   // 4-byte aligned wherever it comes from
-    const uint32_t d0 = d32[0], d1 = d32[1], d2 = d32[2], d3 = d32[3];
 #pragma unroll
     for (int q = 0; q < 4; ++q) lut[q * 64 + tid] = 0x100u;
     const uint32_t k = (uint32_t)tid >> shift, sub = (uint32_t)tid & ((1u << shift) - 1u);
-    const uint32_t d = k < 8 ? (k < 4 ? d0 : d1) : (k < 12 ? d2 : d3);
-    const uint32_t e = (d >> ((k & 3u) * 8u)) & 0xffu;
+    const uint32_t e = dec16_at(d, k & 15u);
     if (k < 16 && e < (256u >> shift)) lut[(e << shift) + sub] = (uint16_t)k;
   }
 }
@@ -532,7 +530,7 @@ __global__ __launch_bounds__(kTileThreads, F::kWavesPerSimd) void compress_tile_
     };
     // the words first: the table is built while they are on their way
     fetch(0);
-    build_encode_table(lut, a.dec_of(item), tid, F::kLutShift);
+    build_encode_table(lut, a.dec16_of(item), tid, F::kLutShift);
     lds_barrier();
     for (uint32_t it0 = 0; it0 < a.cpt; it0 += CPT) {
       if (it0 > 0) fetch(it0);   // tiles of more than CPT chunks per wave (very large tensors)
@@ -557,7 +555,7 @@ __global__ __launch_bounds__(kTileThreads, F::kWavesPerSimd) void compress_tile_
       }
     };
     fetch(0);
-    build_encode_table(lut, a.dec_of(item), tid, F::kLutShift);
+    build_encode_table(lut, a.dec16_of(item), tid, F::kLutShift);
     lds_barrier();
     // dense pass; the wave's escape records into its LDS staging in element order, the chunks' counts kept in lanes
     for (uint32_t it0 = 0; it0 < mine; it0 += CPT) {
@@ -695,7 +693,7 @@ __global__ __launch_bounds__(kTileThreads) void compress_finish_kernel(const Til
     }
     if (lane == 63) s_tp[wave][kGroup] = incl;
   }
-  build_encode_table(lut, a.dec_of(item), tid, F::kLutShift);
+  build_encode_table(lut, a.dec16_of(item), tid, F::kLutShift);
   __syncthreads();
   uint32_t first = 0, M = 0;   // the rank of the first record of the group at hand; all records of the tensor
 #pragma unroll
