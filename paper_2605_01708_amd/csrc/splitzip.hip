@@ -89,11 +89,13 @@ bool codebook_ok(const splitzip_codebook* cb, int dtype) {
 }
 
 // What the tests of the rarely taken paths turn: a staging area and a status area smaller than the workspace has
-// (tiles whose records do not fit their slots; batches that take several launches).  Set through
+// (tiles whose records do not fit their slots; batches that take several launches), and the number of groups a
+// workgroup of the finishing pass takes, which small launches would leave at one.  Set through
 // splitzip_internal_test_hooks (exported, not declared in splitzip.h); zero in normal use.
 struct TestHooks {
   std::atomic<uint64_t> stage_bytes{0};
   std::atomic<uint64_t> status_bytes{0};
+  std::atomic<uint32_t> finish_groups{0};
 };
 TestHooks g_hooks;
 
@@ -457,9 +459,10 @@ int splitzip_workspace_init(void* d_workspace, size_t workspace_bytes, void* str
   return hipGetLastError() == hipSuccess ? SPLITZIP_OK : SPLITZIP_ERR_HIP;
 }
 
-void splitzip_internal_test_hooks(uint64_t stage_bytes, uint64_t status_bytes) {
+void splitzip_internal_test_hooks(uint64_t stage_bytes, uint64_t status_bytes, uint32_t finish_groups) {
   g_hooks.stage_bytes = stage_bytes;
   g_hooks.status_bytes = status_bytes;
+  g_hooks.finish_groups = finish_groups == 1 || finish_groups == 2 || finish_groups == 4 ? finish_groups : 0;
 }
 
 }  // extern "C"
@@ -635,6 +638,7 @@ int compress_launch(const splitzip_item* items, uint32_t n_items, int dtype, con
     // many groups in the launch: several per workgroup, as long as the chip still gets a few workgroups per CU
     a.finish_groups = 1;
     while (a.finish_groups < kFinishMost && (uint64_t)groups_max * k / (2 * a.finish_groups) >= (uint64_t)cu_count() * 8) a.finish_groups *= 2;
+    if (const uint32_t forced = g_hooks.finish_groups.load()) a.finish_groups = forced;
     const unsigned fgroups = (groups_max + a.finish_groups - 1) / a.finish_groups;
     const dim3 fgrid(fgroups ? fgroups : 1u, k);
     if (dtype == SPLITZIP_BF16) hipLaunchKernelGGL(compress_finish_kernel<Bf16>, fgrid, dim3(kTileThreads), 0, st, a);

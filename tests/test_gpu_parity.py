@@ -641,9 +641,47 @@ def test_batch_that_takes_several_launches(hooks, dtype):
             assert np.array_equal(outs[k][: r.size].cpu().numpy(), r), f"item {k} differs"
 
 
+@pytest.mark.parametrize("dtype", [sz.BF16, sz.FP8_E5M2])
+@pytest.mark.parametrize("groups,stage", [(2, 0), (4, 0), (4, 8192)])
+def test_finishing_pass_with_several_groups_per_workgroup(hooks, dtype, groups, stage):
+    """Large launches give every workgroup of the finishing pass two or four groups of 16 tiles; forced here on a
+    batch of tensors whose group counts are everything but multiples of four (none, one, a group and a tile, ...),
+    once with a staging area so small that tiles are encoded again by the finishing pass"""
+    hooks(finish_groups=groups, stage_bytes=stage)
+    cb_or = calibrated(dtype)
+    cb = gpu_codebook(cb_or)
+    per_group = 128 if dtype == sz.BF16 else 256     # chunks per group of 16 tiles
+    chunks = [11 * per_group - 60, per_group - 1, per_group, per_group + 1, 1, 0, 4 * per_group + 9, 8 * per_group, 3]
+    xs_np = []
+    for k, c in enumerate(chunks):
+        n = max(c * 1024 - (k * 53 if c else 0), 0)
+        xs_np.append(synth(dtype, max(c, 1), 20 + k)[:n].copy())
+    xs = [words_tensor(x) if x.size else torch.empty(0, dtype=torch.int16 if dtype == sz.BF16 else torch.uint8, device="cuda") for x in xs_np]
+    outs = [torch.empty(sz.compress_bound(x.size, dtype), dtype=torch.uint8, device="cuda") for x in xs_np]
+    ws = sz.Workspace(max(x.size for x in xs_np), dtype)
+    rec = sz.new_sizes_array(len(xs))
+    for rep in range(2):
+        for o in outs:
+            o.fill_(POISON)
+        sz.compress_batch(xs, [cb] * len(xs), outs, ws, rec)
+        torch.cuda.synchronize()
+        got = sz.read_sizes_array(rec)
+        for k, x in enumerate(xs_np):
+            r, mm = oracle.compress(x, cb_or)
+            assert got[k] == (r.size, mm, 0), (k, got[k], r.size, mm)
+            assert np.array_equal(outs[k][: r.size].cpu().numpy(), r), f"item {k} differs"
+    # and a single call, where the groups of one tensor are all there is
+    one = sz.new_sizes()
+    sz.compress(xs[0], cb, outs[0], ws, one)
+    torch.cuda.synchronize()
+    r, mm = oracle.compress(xs_np[0], cb_or)
+    assert sz.read_sizes(one) == (r.size, mm, 0)
+    assert np.array_equal(outs[0][: r.size].cpu().numpy(), r)
+
+
 def test_tensor_of_many_chain_segments():
-    """307 M BF16 elements (586 MiB, ragged): 37 500 tiles, ten segments of the chain of escape counts; the offset
-    table alone is 1.2 MB"""
+    """307 M BF16 elements (586 MiB, ragged): 37 500 tiles, so the finishing pass reads sums of 64 tile counts instead
+    of every count; the offset table alone is 1.2 MB"""
     x_dev = kv_synth.kv_bf16(300007, 5, 9, "V", device="cuda")
     x = kv_synth.to_numpy_words(x_dev)[:-517].copy()
     del x_dev
