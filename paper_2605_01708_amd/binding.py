@@ -342,7 +342,7 @@ def noalloc_max_elems() -> int:
 
 def compress_noalloc(x: torch.Tensor, cb: Codebook, out: torch.Tensor, sizes: torch.Tensor, stream=None,
                      capacity: int | None = None) -> None:
-    """splitzip_compress_noalloc: splitzip_compress on the library's own per-GPU exchange words."""
+    """splitzip_compress_noalloc: splitzip_compress on the library's own per-GPU scratch array instead of a workspace."""
     n = x.numel()
     if x.element_size() != _elem_size(cb.dtype) or not x.is_contiguous():
         raise ValueError("x must be a contiguous tensor of raw words of the codebook's dtype")

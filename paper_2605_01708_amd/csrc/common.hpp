@@ -15,10 +15,9 @@ constexpr int kThreads = 256;                             // decompress / helper
 constexpr int kWaves = kThreads / 64;
 constexpr uint32_t kMaxCpw = 16;                          // decompress: chunks per wave per tile, at most
 constexpr uint32_t kMaxRange = 256;                       // compress: chunks per tile, at most
-constexpr uint32_t kWsHeaderBytes = 512;                  // workspace: epoch, counters, error flags
-constexpr uint32_t kStatusBytes = 4u << 20;               // workspace: the words of the chains of escape counts
-constexpr uint32_t kStageFloor = 64u << 10;               // workspace: staging of escape values, at least
-constexpr uint64_t kSpinTicks = 200000000ull;             // 2 s of the 100 MHz wall clock
+constexpr uint32_t kWsHeaderBytes = 512;                  // workspace: reserved words in front (cleared by splitzip_workspace_init, read by nobody)
+constexpr uint32_t kStatusBytes = 4u << 20;               // workspace: the escape counts of the tiles and their sums
+constexpr uint32_t kStageFloor = 64u << 10;               // workspace: the tiles' slots for escape records, at least
 
 __host__ __device__ inline uint64_t a256(uint64_t x) { return (x + 255u) & ~(uint64_t)255u; }
 

@@ -649,7 +649,7 @@ int compress_launch(const splitzip_item* items, uint32_t n_items, int dtype, con
   return SPLITZIP_OK;
 }
 
-// one tensor through compress_chain: the codebook on the host (cb) or in device memory (d_cb)
+// one tensor through compress_launch: the codebook on the host (cb) or in device memory (d_cb)
 int compress_one(const Words& in, uint64_t n_elems, int dtype, const splitzip_codebook* cb, const splitzip_codebook* d_cb,
                  void* d_out, size_t out_capacity, void* d_workspace, size_t workspace_bytes, bool own_scratch,
                  splitzip_sizes* d_sizes, void* stream) {
