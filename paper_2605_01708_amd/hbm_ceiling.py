@@ -53,14 +53,15 @@ def sweep(gib: float = 4.0, reps: int = 3, quick: bool = False, out=sys.stdout):
     wgs_list = [0, 8] if quick else [0, 1, 2, 4, 8, 16]   # 0: one workgroup per step, in dispatch order
     best = {}
     for mix, shapes in MIXES.items():
-        for r, w in (shapes[-1:] if quick else shapes):
+        for r, w in ((shapes[:1] + shapes[-1:]) if quick else shapes):
             # bytes of each side so that both run the same number of steps
             rbytes = unit if r >= w else unit // w * r
             wbytes = unit if w >= r else unit // r * w
             for wgs in wgs_list:
-                for flags in ([3, 7] if quick else range(8)):
-                    if (r == 0 and flags & 1) or (w == 0 and flags & 2) or (wgs == 0 and flags & 4):
-                        continue                                  # a flag for a side or an ownership the setting does not have
+                # a flag for a side the mix does not have, or for an ownership the setting does not have, is left out
+                absent = (0 if r else 1) | (0 if w else 2) | (4 if wgs == 0 else 0)
+                usable = sorted({f & ~absent for f in (3, 7)}) if quick else [f for f in range(8) if not f & absent]
+                for flags in usable:
                     gbps = time_shape(src, dst, rbytes, wbytes, r, w, wgs, flags, reps)
                     rec = {"mix": mix, "reads": r, "writes": w, "wgs_per_cu": wgs, "nt_loads": bool(flags & 1),
                            "nt_stores": bool(flags & 2), "blocked": bool(flags & 4), "GBps": round(gbps, 1),
