@@ -328,12 +328,12 @@ struct Bf16 {
 #pragma unroll
       for (int d = 0; d < 4; ++d) asm volatile("" : "+v"(r.w[h][d]));
   }
-  // A workgroup of four waves takes a tile of 4 x kCpt chunks (16 KB of words).  Five workgroups per CU serve BF16
-  // best (one launch over 64 tensors of 64 MiB: 1270 us against 1310 us with eight, 1300 with four, 1460 with
-  // three); unused LDS asked for at the launch sets the number.
+  // A workgroup of four waves takes a tile of 4 x kCpt chunks (16 KB of words).  Four workgroups per CU serve BF16
+  // best (one launch pair over 64 tensors of 64 MiB: 1245-1259 us against 1266-1268 us with five, 1298 us with
+  // eight and 1306 us with three); unused LDS asked for at the launch sets the number.
   static constexpr uint32_t kCpt = 2;
   static constexpr int kWavesPerSimd = 8;
-  static constexpr uint32_t kTileLdsPad = 22000;
+  static constexpr uint32_t kTileLdsPad = 28000;
   static constexpr int kLutShift = 0;       // the LDS encode table holds the entry of exponent e in slot e
   // a chunk goes the fast way if it is complete (then nothing of a pad is its business: N is a multiple of 1024 there)
   __device__ static inline bool full(const Planes& a, uint64_t cbase) { return cbase + kChunk <= a.n; }
