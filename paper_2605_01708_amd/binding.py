@@ -128,7 +128,7 @@ def lib():
         L.splitzip_compress_noalloc.restype = i
         L.splitzip_compress_noalloc.argtypes = [vp, u64, i, cbp, vp, sz, vp, vp]
         L.splitzip_internal_test_hooks.restype = None
-        L.splitzip_internal_test_hooks.argtypes = [u64, u64, C.c_uint32]
+        L.splitzip_internal_test_hooks.argtypes = [u64, u64, C.c_uint32, u64]
         L.splitzip_traffic_probe.restype = i
         L.splitzip_traffic_probe.argtypes = [vp, sz, vp, sz, vp]
         L.splitzip_traffic_probe_shape.restype = i
@@ -330,10 +330,11 @@ def compress(x: torch.Tensor, cb: Codebook, out: torch.Tensor, workspace: Worksp
                                    _stream_ptr(stream)), "splitzip_compress")
 
 
-def internal_test_hooks(stage_bytes: int = 0, status_bytes: int = 0, finish_groups: int = 0) -> None:
+def internal_test_hooks(stage_bytes: int = 0, status_bytes: int = 0, finish_groups: int = 0, direct_bytes: int = 0) -> None:
     """What the tests of the rarely taken paths turn (not part of splitzip.h): a staging area and a status area smaller
-    than the workspace has, and the groups of tiles per workgroup of the finishing pass (1, 2 or 4).  0 = as built."""
-    lib().splitzip_internal_test_hooks(stage_bytes, status_bytes, finish_groups)
+    than the workspace has, the groups of tiles per workgroup of the finishing pass (1, 2 or 4), and the bytes of tile
+    counts a launch's finishing pass may read directly (beyond: sums of 64 counts).  0 = as built."""
+    lib().splitzip_internal_test_hooks(stage_bytes, status_bytes, finish_groups, direct_bytes)
 
 
 def noalloc_max_elems() -> int:

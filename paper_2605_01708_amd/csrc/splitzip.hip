@@ -90,12 +90,14 @@ bool codebook_ok(const splitzip_codebook* cb, int dtype) {
 
 // What the tests of the rarely taken paths turn: a staging area and a status area smaller than the workspace has
 // (tiles whose records do not fit their slots; batches that take several launches), and the number of groups a
-// workgroup of the finishing pass takes, which small launches would leave at one.  Set through
+// workgroup of the finishing pass takes, which small launches would leave at one, and the bytes of tile counts the
+// finishing pass may read directly before it is given sums instead.  Set through
 // splitzip_internal_test_hooks (exported, not declared in splitzip.h); zero in normal use.
 struct TestHooks {
   std::atomic<uint64_t> stage_bytes{0};
   std::atomic<uint64_t> status_bytes{0};
   std::atomic<uint32_t> finish_groups{0};
+  std::atomic<uint64_t> direct_bytes{0};
 };
 TestHooks g_hooks;
 
@@ -459,7 +461,8 @@ int splitzip_workspace_init(void* d_workspace, size_t workspace_bytes, void* str
   return hipGetLastError() == hipSuccess ? SPLITZIP_OK : SPLITZIP_ERR_HIP;
 }
 
-void splitzip_internal_test_hooks(uint64_t stage_bytes, uint64_t status_bytes, uint32_t finish_groups) {
+void splitzip_internal_test_hooks(uint64_t stage_bytes, uint64_t status_bytes, uint32_t finish_groups, uint64_t direct_bytes) {
+  g_hooks.direct_bytes = direct_bytes;
   g_hooks.stage_bytes = stage_bytes;
   g_hooks.status_bytes = status_bytes;
   g_hooks.finish_groups = finish_groups == 1 || finish_groups == 2 || finish_groups == 4 ? finish_groups : 0;
@@ -624,22 +627,25 @@ int compress_launch(const splitzip_item* items, uint32_t n_items, int dtype, con
       const uint64_t per_tile = tiles_max ? a.stage_cap / 4 / tiles_max : 0;
       a.slot_cap = (uint32_t)(per_tile < kSlotCapMost ? per_tile : kSlotCapMost);
     }
-    // A finishing workgroup that sums all tile counts of its tensor itself reads 4 bytes per tile: fine for one
-    // tensor of up to kDirectTiles tiles (and one launch fewer), too much for the thousands of workgroups of a batch.
-    a.use_group_sums = tiles_max > kDirectTiles || k > 1 ? 1u : 0u;
     a.paging = paging;
     const unsigned groups_max = (unsigned)((tiles_max + kGroup - 1) / kGroup), sums_max = (unsigned)((tiles_max + kSumGroup - 1) / kSumGroup);
+    // many groups in the launch: several per workgroup, as long as the chip still gets a few workgroups per CU
+    a.finish_groups = 1;
+    while (a.finish_groups < kFinishMost && (uint64_t)groups_max * k / (2 * a.finish_groups) >= (uint64_t)cu_count() * 8) a.finish_groups *= 2;
+    if (const uint32_t forced = g_hooks.finish_groups.load()) a.finish_groups = forced;
+    const unsigned fgroups = (groups_max + a.finish_groups - 1) / a.finish_groups;
+    // A finishing workgroup that sums all tile counts of its tensor itself reads 4 bytes per tile: fine while all
+    // workgroups of the launch together read a few tens of MB that way (and one launch fewer: 6 us of the 90 us of a
+    // batch of eight 32 MiB tensors), too much for the thousands of workgroups of a large batch, which read sums of
+    // kSumGroup counts instead (tile_group_sum_kernel).
+    const uint64_t direct_budget = g_hooks.direct_bytes.load() ? g_hooks.direct_bytes.load() : kDirectBytes;
+    a.use_group_sums = tiles_max > kDirectTiles || (uint64_t)fgroups * k * tiles_max * 4 > direct_budget ? 1u : 0u;
     if (tiles_max) {
       const dim3 grid((unsigned)tiles_max, k);   // one workgroup per tile, started by the hardware in the tiles' order
       if (dtype == SPLITZIP_BF16) hipLaunchKernelGGL((compress_tile_kernel<Bf16, Bf16::kCpt>), grid, dim3(kTileThreads), Bf16::kTileLdsPad, st, a);
       else hipLaunchKernelGGL((compress_tile_kernel<E5m2, E5m2::kCpt>), grid, dim3(kTileThreads), E5m2::kTileLdsPad, st, a);
       if (a.use_group_sums) hipLaunchKernelGGL(tile_group_sum_kernel, dim3(sums_max, k), dim3(64), 0, st, a);
     }
-    // many groups in the launch: several per workgroup, as long as the chip still gets a few workgroups per CU
-    a.finish_groups = 1;
-    while (a.finish_groups < kFinishMost && (uint64_t)groups_max * k / (2 * a.finish_groups) >= (uint64_t)cu_count() * 8) a.finish_groups *= 2;
-    if (const uint32_t forced = g_hooks.finish_groups.load()) a.finish_groups = forced;
-    const unsigned fgroups = (groups_max + a.finish_groups - 1) / a.finish_groups;
     const dim3 fgrid(fgroups ? fgroups : 1u, k);
     if (dtype == SPLITZIP_BF16) hipLaunchKernelGGL(compress_finish_kernel<Bf16>, fgrid, dim3(kTileThreads), 0, st, a);
     else hipLaunchKernelGGL(compress_finish_kernel<E5m2>, fgrid, dim3(kTileThreads), 0, st, a);

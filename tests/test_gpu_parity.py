@@ -642,12 +642,13 @@ def test_batch_that_takes_several_launches(hooks, dtype):
 
 
 @pytest.mark.parametrize("dtype", [sz.BF16, sz.FP8_E5M2])
-@pytest.mark.parametrize("groups,stage", [(2, 0), (4, 0), (4, 8192)])
-def test_finishing_pass_with_several_groups_per_workgroup(hooks, dtype, groups, stage):
+@pytest.mark.parametrize("groups,stage,direct", [(2, 0, 0), (4, 0, 1), (4, 8192, 0), (1, 0, 1), (2, 8192, 1)])
+def test_finishing_pass_with_several_groups_per_workgroup(hooks, dtype, groups, stage, direct):
     """Large launches give every workgroup of the finishing pass two or four groups of 16 tiles; forced here on a
     batch of tensors whose group counts are everything but multiples of four (none, one, a group and a tile, ...),
-    once with a staging area so small that tiles are encoded again by the finishing pass"""
-    hooks(finish_groups=groups, stage_bytes=stage)
+    once with a staging area so small that tiles are encoded again by the finishing pass; direct = 1: the finishing
+    pass is given sums of 64 tile counts (as in large launches) instead of reading the counts itself"""
+    hooks(finish_groups=groups, stage_bytes=stage, direct_bytes=direct)
     cb_or = calibrated(dtype)
     cb = gpu_codebook(cb_or)
     per_group = 128 if dtype == sz.BF16 else 256     # chunks per group of 16 tiles
