@@ -419,7 +419,7 @@ __device__ void compress_write_trailer(const Planes& a, const uint8_t* dec, spli
 constexpr uint32_t kTileThreads = 256;
 constexpr uint32_t kGroup = 16;             // tiles per group of the finishing pass
 constexpr uint32_t kFinishMost = 4;         // groups per workgroup of the finishing pass, at most
-constexpr uint32_t kSlotAhead = 16;         // records per tile the finishing pass fetches before it knows the counts
+constexpr uint32_t kSlotAhead = 16;         // threads per tile that fetch records before the finishing pass knows the counts, two records each
 constexpr uint32_t kTileStageCap = 256;     // escapes a wave can stage in LDS
 constexpr uint32_t kSlotCapMost = 1024;     // records per tile slot, at most
 constexpr uint32_t kDirectTiles = 4096;     // up to this many tiles per tensor the finishing pass sums the tile counts itself ...
@@ -427,7 +427,7 @@ constexpr uint64_t kDirectBytes = 32ull << 20;   // ... if all its workgroups to
 constexpr uint32_t kSumGroup = 64;          // beyond: sums of this many tile counts, by tile_group_sum_kernel
 constexpr uint32_t kBatchMax = 64;          // tensors per launch: their descriptors travel as kernel arguments
 constexpr uint32_t kRedo = 0x80000000u;     // in a tile's count: its records are not in its slot
-static_assert(kGroup * kSlotAhead == kTileThreads, "one record fetched ahead per thread");
+static_assert(kGroup * kSlotAhead == kTileThreads, "every thread fetches records of one tile ahead");
 
 struct TileItem {
   const uint8_t* in;
@@ -612,6 +612,7 @@ __global__ __launch_bounds__(kTileThreads) void compress_finish_kernel(const Til
   __shared__ uint32_t s_cnt[kFinishMost][kGroup];       // the counts of the groups' tiles, redo mark included
   __shared__ uint32_t s_tp[kFinishMost][kGroup + 1];    // escapes of a group's tiles before each tile
   __shared__ uint32_t s_red[2 * NW];
+  __shared__ uint32_t s_more[kFinishMost];              // a group has a tile with more records than were fetched ahead
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const uint32_t item = blockIdx.y;
@@ -629,17 +630,20 @@ __global__ __launch_bounds__(kTileThreads) void compress_finish_kernel(const Til
   const uint32_t group_entries = kGroup << a.tile_shift;
 
   // Everything whose address does not depend on the counts is fetched at once: the counts themselves, the
-  // groups' table entries (one per thread and group, or a few) and the first kSlotAhead records of every tile's slot.
+  // groups' table entries (one per thread and group, or a few) and the first 2 kSlotAhead records of every tile's slot
+  // (two per thread: hardly a tile has more, so hardly a workgroup has to go to memory once more after the barrier).
   const uint32_t sl = (uint32_t)tid / kSlotAhead, sj = (uint32_t)tid % kSlotAhead;   // tile of a group, record of the tile
-  uint32_t my_entry[kFinishMost], rec_ahead[kFinishMost];
+  uint32_t my_entry[kFinishMost], rec_ahead[kFinishMost], rec_ahead2[kFinishMost];
 #pragma unroll
   for (uint32_t q = 0; q < kFinishMost; ++q) {
     my_entry[q] = 0;
     rec_ahead[q] = 0;
+    rec_ahead2[q] = 0;
     if (q < ng) {
       const uint32_t t0 = (g0 + q) * kGroup, c0 = t0 << a.tile_shift;
       if (c0 + tid < P.n_chunks && (uint32_t)tid < group_entries) my_entry[q] = tab[c0 + tid];
       if (t0 + sl < G.n_tiles && sj < a.slot_cap) rec_ahead[q] = G.slots[(uint64_t)(t0 + sl) * a.slot_cap + sj];
+      if (t0 + sl < G.n_tiles && sj + kSlotAhead < a.slot_cap) rec_ahead2[q] = G.slots[(uint64_t)(t0 + sl) * a.slot_cap + sj + kSlotAhead];
     }
   }
   const uint32_t t_first = g0 * kGroup;   // the first tile of the workgroup's first group
@@ -693,6 +697,8 @@ __global__ __launch_bounds__(kTileThreads) void compress_finish_kernel(const Til
       s_tp[wave][lane] = incl - (c & ~kRedo);
     }
     if (lane == 63) s_tp[wave][kGroup] = incl;
+    const uint64_t more = __ballot((c & ~kRedo) > 2 * kSlotAhead && !(c & kRedo));
+    if (lane == 0) s_more[wave] = more != 0;
   }
   build_encode_table(lut, a.dec16_of(item), tid, F::kLutShift);
   __syncthreads();
@@ -745,17 +751,18 @@ __global__ __launch_bounds__(kTileThreads) void compress_finish_kernel(const Til
     // the records fetched ahead
     const uint32_t cl = cnt[sl];
     if (!(cl & kRedo) && sj < cl) fin.put(first + tp[sl] + sj, rec_ahead[q] & 0xffffu, rec_ahead[q] >> 16);
+    if (!(cl & kRedo) && sj + kSlotAhead < cl) fin.put(first + tp[sl] + sj + kSlotAhead, rec_ahead2[q] & 0xffffu, rec_ahead2[q] >> 16);
     // The rest of the slots of tiles with more records than that: rank r of the group belongs to the last tile that
     // starts at or before r.  Two records per thread are on their way at a time.
     const uint32_t group_total = tp[kGroup];
-    if (group_total > kSlotAhead) {   // else no tile can have more than kSlotAhead records
+    if (s_more[q]) {   // a tile of the group has more records than were fetched ahead
       auto locate = [&](uint32_t r, uint32_t& l, uint32_t& j) -> bool {
         l = 0;
 #pragma unroll
         for (uint32_t step = kGroup / 2; step; step >>= 1)
           if (tp[l + step] <= r) l += step;
         j = r - tp[l];
-        return r < group_total && j >= kSlotAhead && !(cnt[l] & kRedo);
+        return r < group_total && j >= 2 * kSlotAhead && !(cnt[l] & kRedo);
       };
       for (uint32_t r = tid; r < group_total; r += 2 * kTileThreads) {
         uint32_t l0, j0, l1, j1, rec0 = 0, rec1 = 0;
