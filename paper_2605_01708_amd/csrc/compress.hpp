@@ -423,7 +423,7 @@ constexpr uint32_t kSlotAhead = 16;         // threads per tile that fetch recor
 constexpr uint32_t kTileStageCap = 256;     // escapes a wave can stage in LDS
 constexpr uint32_t kSlotCapMost = 1024;     // records per tile slot, at most
 constexpr uint32_t kDirectTiles = 4096;     // up to this many tiles per tensor the finishing pass sums the tile counts itself ...
-constexpr uint64_t kDirectBytes = 32ull << 20;   // ... if all its workgroups together read no more than this many bytes of counts
+constexpr uint64_t kDirectBytes = 128ull << 20;   // ... if all its workgroups together read no more than this many bytes of counts
 constexpr uint32_t kSumGroup = 64;          // beyond: sums of this many tile counts, by tile_group_sum_kernel
 constexpr uint32_t kBatchMax = 64;          // tensors per launch: their descriptors travel as kernel arguments
 constexpr uint32_t kRedo = 0x80000000u;     // in a tile's count: its records are not in its slot
